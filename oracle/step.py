@@ -1,0 +1,59 @@
+"""One partition's isolated train step (oracle glue; test infrastructure).
+
+Puts the pieces in the order of the paper's phase-parallel algorithm: (isolated
+sampling) -> forward -> backward -> coverage statistics.  The scaling by the coverage
+factor and the reduction over partitions are in ``coverage.aggregate``.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import coverage, gnn, sampling
+
+
+def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
+               estimator: int = coverage.NONE, gcn_self_loops: bool = True,
+               minibatch: dict | None = None):
+    """Returns (grad[P] float64, stats dict) for one partition.
+
+    full-graph mode (``minibatch is None``): every local node is an input, the loss runs
+    over the local nodes selected by ``train_mask`` (all if None).
+    mini-batch mode: ``minibatch = dict(seeds=int array of local ids, fanouts=(f_0..f_{k-1}),
+    sampler_seed=int, batch_id=int)``; fanouts[l] belongs to layer l, layer 0 being the input
+    side, so the seeds draw fanouts[k-1] neighbours.
+    """
+    n = part["n"]
+    k = len(dims) - 1
+    dl, dg = part["d_local_in"], part["d_global_in"]
+    w_all = coverage.node_weights(dl, dg) if estimator == coverage.NODE_LEVEL else np.ones(n)
+
+    if minibatch is None:
+        blk = gnn.block_from_csr(part["rowptr"], part["col"])
+        if train_mask is None:
+            loss_nodes = np.arange(n, dtype=np.int64)
+        else:
+            loss_nodes = np.flatnonzero(np.asarray(train_mask) != 0).astype(np.int64)
+        loss, grad = gnn.forward_backward(arch, dims, theta, x, [blk] * k, labels, w_all,
+                                          loss_nodes, gcn_self_loops)
+        st = coverage.coverage_stats(dl, dg, loss_nodes, None)
+        st["loss"] = loss
+        st["nnz_used"] = int(part["nnz"])
+        return grad, st
+
+    if arch != "sage":
+        raise ValueError("mini-batch mode is defined for GraphSAGE only")
+    seeds = np.asarray(minibatch["seeds"], dtype=np.int64)
+    blocks, input_nodes = sampling.sample_blocks(part, seeds, minibatch["fanouts"],
+                                                 minibatch["sampler_seed"], minibatch["batch_id"])
+    xin = np.asarray(x, dtype=np.float64)[input_nodes]
+    nseed = seeds.size
+    loss, grad = gnn.forward_backward(arch, dims, theta, xin, blocks, np.asarray(labels)[seeds],
+                                      w_all[seeds], np.arange(nseed, dtype=np.int64),
+                                      gcn_self_loops)
+    last = blocks[-1]
+    sampled = np.bincount(last["edst"], minlength=nseed)
+    st = coverage.coverage_stats(np.asarray(dl)[seeds], np.asarray(dg)[seeds],
+                                 np.arange(nseed, dtype=np.int64), sampled)
+    st["loss"] = loss
+    st["nnz_used"] = int(sum(b["esrc"].size for b in blocks))
+    return grad, st
