@@ -1,0 +1,232 @@
+/*
+ * grappa.h - C ABI of the MI355X (gfx950) hot path of gradient-only GNN training:
+ * the isolated per-partition train step and the coverage-corrected aggregation of
+ * the partition gradients (Grappa, sections "Isolated Training Strategy",
+ * "Coverage-Corrected Aggregation" and "Phase-Parallel Training").
+ *
+ * One iteration of the paper's phase-parallel algorithm with one partition active
+ * at a time is, per partition p = 0..K-1:
+ *     (isolated sampling) -> forward -> backward            grp_train_step
+ *     scale grad by the coverage factor, reduce over p      grp_aggregate
+ * on a local subgraph built once per (graph, K, seed, p) by grp_partition.
+ *
+ * General conventions
+ *   - Pointers marked DEV are device (HBM) addresses, HOST are host addresses.  The
+ *     caller owns every buffer it passes; the library owns only the opaque handles it
+ *     returns and frees them in *_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *     asynchronous on that stream unless stated otherwise and never synchronise it.
+ *   - Every function returns GRP_OK (0) or a negative status; it never throws or aborts.
+ *     grp_last_error() gives a thread-local, library-owned description of the last
+ *     failure on the calling thread.
+ *   - Matrices are dense row-major; `ld*` is the row pitch in elements.
+ *   - Local node ids are int32, edge offsets int64 (a partition may hold 2^32 edges).
+ */
+#ifndef GRAPPA_H_
+#define GRAPPA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t grp_status;
+#define GRP_OK            0
+#define GRP_EINVAL       (-1)   /* null pointer, K < 1, part_id outside [0,K), dims <= 0, ... */
+#define GRP_ERANGE       (-2)   /* node id outside [0,N), local node count >= 2^31            */
+#define GRP_ENOMEM       (-3)   /* a device allocation owned by a handle failed               */
+#define GRP_EWORKSPACE   (-4)   /* caller's workspace is smaller than the queried size        */
+#define GRP_EHIP         (-5)   /* a HIP runtime call failed (message has the HIP error)      */
+#define GRP_EUNSUPPORTED (-6)   /* a combination this build does not implement                */
+
+const char* grp_last_error(void);
+
+/* ------------------------------------------------------------------ partition */
+
+typedef struct grp_partition_s grp_partition_t;
+
+/* Borrowed DEV pointers into a partition handle, valid until grp_partition_destroy.
+ * CSR: row v lists the local sources u of the kept edges u->v, ascending; CSC: row u
+ * lists the destinations, ascending.  Duplicate edges and self-loops are kept.       */
+typedef struct {
+    int64_t        n;            /* local nodes                                  */
+    int64_t        nnz;          /* local edges (both endpoints owned)           */
+    const int64_t* l2g;          /* [n]   global id of local node, ascending     */
+    const int64_t* rowptr;       /* [n+1] CSR by destination                     */
+    const int32_t* col;          /* [nnz] source local ids                       */
+    const int64_t* colptr;       /* [n+1] CSC by source                          */
+    const int32_t* row;          /* [nnz] destination local ids                  */
+    const int32_t* d_local_in;   /* [n]   in-degree inside the partition         */
+    const int32_t* d_local_out;  /* [n]   out-degree inside the partition        */
+    const int64_t* d_global_in;  /* [n]   in-degree in the whole graph           */
+} grp_partition_view_t;
+
+/* Random node assignment and the isolated local subgraph ("Graph Partitioning": nodes
+ * are assigned to partitions at random; "Isolated Training": only local nodes and
+ * edges take part; no halo nodes: an edge with an endpoint in another partition is
+ * dropped).
+ *   owner(v) = SplitMix64_output(seed, v) mod K, where output number v (from 0) of the
+ *   SplitMix64 sequence is mix(seed + (v+1)*0x9E3779B97F4A7C15) in wrapping uint64
+ *   arithmetic, mix(z): z=(z^(z>>30))*0xBF58476D1CE4E5B9; z=(z^(z>>27))*0x94D049BB133111EB;
+ *   z^(z>>31); the modulo is unsigned.
+ * src/dst: DEV int64[E] global ids, edge e means dst[e] aggregates from src[e].
+ * Degrees are in-degrees with multiplicity.  Local ids follow ascending global id.
+ * Synchronous: returns after the handle is complete (it needs n and nnz on the host).
+ * Errors: GRP_EINVAL (null, K<1, part_id, E<0, N<0), GRP_ERANGE (an id outside [0,N), or
+ * n >= 2^31), GRP_ENOMEM, GRP_EHIP.  On error *out is NULL.                            */
+grp_status grp_partition(const int64_t* src, const int64_t* dst, int64_t E, int64_t N,
+                         int32_t K, uint64_t seed, int32_t part_id, void* stream,
+                         grp_partition_t** out);
+
+/* Adopt a partition's share that was generated directly as local edges.
+ * src_local/dst_local: DEV int64[E] ids in [0,n).  d_global_in: DEV int64[n] or NULL
+ * (= local in-degree, i.e. full coverage).  l2g: DEV int64[n] or NULL (= identity).
+ * Builds the same canonical CSR/CSC as grp_partition.  Synchronous.                   */
+grp_status grp_partition_from_local_coo(const int64_t* src_local, const int64_t* dst_local,
+                                        int64_t E, int64_t n, const int64_t* d_global_in,
+                                        const int64_t* l2g, void* stream, grp_partition_t** out);
+
+grp_status grp_partition_view(const grp_partition_t* part, grp_partition_view_t* view /*HOST*/);
+grp_status grp_partition_destroy(grp_partition_t* part);   /* NULL is a no-op */
+
+/* ------------------------------------------------------------------ model */
+
+#define GRP_MAX_LAYERS 16
+
+#define GRP_ARCH_SAGE_MEAN    0  /* z_v = h_v W_self + mean_{u in N_v} h_u W_neigh + b        */
+#define GRP_ARCH_GCN          1  /* z_v = sum_u Ahat[v,u] (h_u W) + b, symmetric normalisation */
+#define GRP_ARCH_GCN_RESIDUAL 2  /* GCN with h^{l+1} = h^l + ReLU(z^l) where widths agree      */
+
+#define GRP_DTYPE_FP32 0
+#define GRP_DTYPE_BF16 1         /* storage of the input features only; accumulate in fp32 */
+
+/* Model description (the paper's "GNN Models": GraphSAGE aggregates the neighbours'
+ * states by averaging, combines with the node's own state and multiplies by a matrix;
+ * GCN applies a linear map and averages neighbours with degree-based weights).
+ * ReLU after every layer but the last; no dropout.  GCN normalisation:
+ * Ahat[v,u] = (A[v,u] + [u==v]) / sqrt((d_in(v)+1)(d_out(u)+1)) on local degrees when
+ * gcn_self_loops != 0, else A[v,u] / sqrt(max(d_in(v),1) max(d_out(u),1)).
+ * Flat parameter layout (weights in, gradients out): layer-major; per layer W_self
+ * (GCN: W) row-major [dims[l] x dims[l+1]], then W_neigh (SAGE only), then b[dims[l+1]]. */
+typedef struct {
+    int32_t arch;
+    int32_t n_layers;
+    int32_t dims[GRP_MAX_LAYERS + 1];
+    int32_t feat_dtype;
+    int32_t gcn_self_loops;
+} grp_model_desc;
+
+/* Number of floats in the flat parameter vector, or -1 for an invalid description. */
+int64_t grp_param_count(const grp_model_desc* model);
+
+/* ------------------------------------------------------------------ train step */
+
+#define GRP_EST_NONE           0  /* c = 1 (the paper's "no correction" ablation)             */
+#define GRP_EST_NODE_LEVEL     1  /* asymptotically unbiased node-level estimator, uniform
+                                     neighbours: node v's loss is weighted d_local/d_global   */
+#define GRP_EST_BATCH_MIN_DIST 2  /* batch-level factor c = mean_v d_local/d_global           */
+#define GRP_EST_SHRINKAGE      3  /* c = 1 / sum_v (d_global/d_local - 1)|S_v|                */
+
+typedef struct {
+    int32_t        estimator;     /* only NODE_LEVEL changes the step (per-node loss weights)  */
+    int32_t        full_graph;    /* 1: whole partition each step; 0: mini-batch               */
+    int32_t        n_seeds;       /* mini-batch: number of seed nodes                          */
+    int32_t        reserved;
+    const int32_t* seeds;         /* DEV int32[n_seeds] distinct local ids (mini-batch)        */
+    int32_t        fanouts[GRP_MAX_LAYERS]; /* fanouts[l] belongs to layer l, 0 = input side   */
+    uint64_t       sampler_seed;
+    uint64_t       batch_id;
+} grp_step_opts;
+
+/* Written to DEV memory by grp_train_step (one record per partition). */
+typedef struct {
+    double  loss;        /* (1/|S|) sum_{v in S} w_v (logsumexp z_v - z_v[y_v]); 0 if S empty */
+    double  sum_ratio;   /* sum_{v in S} d_local(v)/d_global(v)  (1 if d_global = 0)          */
+    double  R;           /* sum_{v in S} (d_global - d_local)|S_v|/d_local; full-graph:
+                            sum (d_global - d_local), the number of dropped in-edges of S     */
+    int64_t S;           /* nodes carrying loss                                               */
+    int64_t nnz_used;    /* edges processed (local edges, or edges of the sampled blocks)     */
+} grp_step_stats;
+
+/* Bytes of caller-provided DEV workspace grp_train_step needs for this partition, model
+ * and options (activations kept for the backward pass, temporaries, partial sums).     */
+grp_status grp_step_workspace_bytes(const grp_partition_t* part, const grp_model_desc* model,
+                                    const grp_step_opts* opts, size_t* bytes /*HOST*/);
+
+/* One isolated train step on one partition (phase-parallel algorithm, the per-worker
+ * body: isolated_sampling, forward_pass, backward_pass): loss and gradient of the mean
+ * weighted softmax cross-entropy of the k-layer model over the loss nodes S, using only
+ * the partition's local edges, plus the coverage statistics of S.
+ *   features   DEV [n x dims[0]] row-major, fp32 or bf16 per model->feat_dtype
+ *   labels     DEV int32[n], values in [0, dims[k])
+ *   train_mask DEV uint8[n] or NULL (= all local nodes); full-graph mode only
+ *   weights    DEV float[P] flat parameters (layout above)
+ *   workspace  DEV, 256-byte aligned, at least the queried size; contents undefined after
+ *   grad_out   DEV float[P], overwritten
+ *   stats_out  DEV grp_step_stats, overwritten
+ * S = train_mask ∩ local nodes (full graph) or the seeds (mini-batch).  Deterministic:
+ * no floating-point atomics; two calls with equal inputs give equal bits.
+ * Errors: GRP_EINVAL, GRP_EWORKSPACE, GRP_EUNSUPPORTED (mini-batch with a GCN arch),
+ * GRP_EHIP.                                                                            */
+grp_status grp_train_step(const grp_partition_t* part, const grp_model_desc* model,
+                          const grp_step_opts* opts, const void* features,
+                          const int32_t* labels, const uint8_t* train_mask,
+                          const float* weights, void* workspace, size_t workspace_bytes,
+                          void* stream, float* grad_out, grp_step_stats* stats_out);
+
+/* ------------------------------------------------------------------ aggregation */
+
+/* Coverage-corrected aggregation ("Coverage-Corrected Aggregation"; the scale-then-
+ * all_reduce lines of the phase-parallel algorithm):  G = (1/K) sum_p c_p g_p  with
+ *   c_p = 1                                  NONE, NODE_LEVEL
+ *   c_p = sum_ratio_p / S_p  (1 if S_p = 0)  BATCH_MIN_DIST   (uniform batch-level factor)
+ *   c_p = 1 / R_p            (1 if R_p = 0)  SHRINKAGE        (shrinkage equation)
+ *   grads   DEV float, partition p's gradient starts at grads + p*ld_grads, P floats
+ *   stats   DEV grp_step_stats[K]
+ *   update  DEV float[P], overwritten;  c_out DEV float[K] or NULL
+ * Sums over p in ascending order with fp32 fused multiply-adds.  Errors: GRP_EINVAL.   */
+grp_status grp_aggregate(const float* grads, int64_t ld_grads, const grp_step_stats* stats,
+                         int32_t K, int64_t P, int32_t variant, void* stream,
+                         float* update, float* c_out);
+
+/* ------------------------------------------------------------------ building blocks */
+
+/* Neighbour aggregation on a partition (the message-passing step of every layer):
+ *   transposed = 0:  Y[v,:] = a_v (sum_{u->v} X[u,:] + self*X[v,:])     rows of the CSR
+ *   transposed = 1:  Y[u,:] = a_u (sum_{u->v} X[v,:] + self*X[u,:])     rows of the CSC
+ * a = 1 (scale GRP_SCALE_NONE), 1/max(deg,1) (MEAN) or 1/sqrt(deg+self) clamped at
+ * deg>=1 (RSQRT), deg = the row's length.  X: DEV [n x F] fp32/bf16, Y: DEV [n x F] fp32. */
+#define GRP_SCALE_NONE  0
+#define GRP_SCALE_MEAN  1
+#define GRP_SCALE_RSQRT 2
+grp_status grp_spmm(const grp_partition_t* part, int32_t transposed, int32_t scale,
+                    int32_t self_term, int32_t F, const void* X, int64_t ldx, int32_t x_dtype,
+                    float* Y, int64_t ldy, void* stream);
+
+/* Dense transforms on the matrix cores (fp32 MFMA, fp32 accumulate):
+ *   grp_gemm_nn:  C[M x N] = A[M x K] B[K x N]            (X W, dY W^T with B given transposed)
+ *   grp_gemm_tn:  C[K x N] = A[M x K]^T B[M x N]          (X^T dY), reduction over M in a
+ *                 fixed order; `workspace` DEV of grp_gemm_tn_workspace_bytes(M,K,N).   */
+grp_status grp_gemm_nn(int64_t M, int32_t N, int32_t K, const void* A, int64_t lda,
+                       int32_t a_dtype, const float* B, int64_t ldb, float* C, int64_t ldc,
+                       void* stream);
+size_t     grp_gemm_tn_workspace_bytes(int64_t M, int32_t K, int32_t N);
+grp_status grp_gemm_tn(int64_t M, int32_t K, int32_t N, const void* A, int64_t lda,
+                       int32_t a_dtype, const float* B, int64_t ldb, float* C, int64_t ldc,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------ profiling */
+
+/* Per-kernel timing with HIP events on the launch stream.  While enabled, every kernel
+ * the library launches is bracketed by two events.  grp_profile_report synchronises the
+ * recorded events, writes one line "name launches total_ms\n" per kernel name into
+ * buf (HOST, NUL-terminated, truncated to cap) and clears the records.                */
+grp_status grp_profile_enable(int32_t on);
+grp_status grp_profile_report(char* buf, size_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRAPPA_H_ */

@@ -1,0 +1,266 @@
+"""ctypes binding with the same names as the C ABI (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgrappa_hip.so")
+
+GRP_MAX_LAYERS = 16
+ARCH_SAGE_MEAN, ARCH_GCN, ARCH_GCN_RESIDUAL = 0, 1, 2
+DTYPE_FP32, DTYPE_BF16 = 0, 1
+EST_NONE, EST_NODE_LEVEL, EST_BATCH_MIN_DIST, EST_SHRINKAGE = 0, 1, 2, 3
+SCALE_NONE, SCALE_MEAN, SCALE_RSQRT = 0, 1, 2
+OK, EINVAL, ERANGE, ENOMEM, EWORKSPACE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+
+
+class GrappaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"grappa status {status}: {message}")
+        self.status = status
+
+
+class PartitionView(C.Structure):
+    _fields_ = [("n", C.c_int64), ("nnz", C.c_int64), ("l2g", C.c_void_p), ("rowptr", C.c_void_p),
+                ("col", C.c_void_p), ("colptr", C.c_void_p), ("row", C.c_void_p),
+                ("d_local_in", C.c_void_p), ("d_local_out", C.c_void_p), ("d_global_in", C.c_void_p)]
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("arch", C.c_int32), ("n_layers", C.c_int32), ("dims", C.c_int32 * (GRP_MAX_LAYERS + 1)),
+                ("feat_dtype", C.c_int32), ("gcn_self_loops", C.c_int32)]
+
+
+class StepOpts(C.Structure):
+    _fields_ = [("estimator", C.c_int32), ("full_graph", C.c_int32), ("n_seeds", C.c_int32),
+                ("reserved", C.c_int32), ("seeds", C.c_void_p), ("fanouts", C.c_int32 * GRP_MAX_LAYERS),
+                ("sampler_seed", C.c_uint64), ("batch_id", C.c_uint64)]
+
+
+STATS_DTYPE = np.dtype([("loss", "<f8"), ("sum_ratio", "<f8"), ("R", "<f8"), ("S", "<i8"), ("nnz_used", "<i8")])
+STATS_BYTES = STATS_DTYPE.itemsize
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load the built library; raises if it is missing (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, u64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_size_t
+    lib.grp_last_error.restype = C.c_char_p
+    lib.grp_last_error.argtypes = []
+    sigs = {
+        "grp_partition": [vp, vp, i64, i64, i32, u64, i32, vp, C.POINTER(vp)],
+        "grp_partition_from_local_coo": [vp, vp, i64, i64, vp, vp, vp, C.POINTER(vp)],
+        "grp_partition_view": [vp, C.POINTER(PartitionView)],
+        "grp_partition_destroy": [vp],
+        "grp_step_workspace_bytes": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), C.POINTER(sz)],
+        "grp_train_step": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), vp, vp, vp, vp, vp, sz, vp, vp, vp],
+        "grp_aggregate": [vp, i64, vp, i32, i64, i32, vp, vp, vp],
+        "grp_spmm": [vp, i32, i32, i32, i32, vp, i64, i32, vp, i64, vp],
+        "grp_gemm_nn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
+        "grp_gemm_tn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp, sz, vp],
+        "grp_profile_enable": [i32],
+        "grp_profile_report": [C.c_char_p, sz],
+    }
+    for name, args in sigs.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = i32
+    lib.grp_param_count.argtypes = [C.POINTER(ModelDesc)]
+    lib.grp_param_count.restype = i64
+    lib.grp_gemm_tn_workspace_bytes.argtypes = [i64, i32, i32]
+    lib.grp_gemm_tn_workspace_bytes.restype = sz
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise GrappaError(status, load().grp_last_error().decode())
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+
+
+def model_desc(arch: int, dims, feat_dtype: int = DTYPE_FP32, gcn_self_loops: bool = True) -> ModelDesc:
+    m = ModelDesc()
+    m.arch = arch
+    m.n_layers = len(dims) - 1
+    for i, d in enumerate(dims[:GRP_MAX_LAYERS + 1]):
+        m.dims[i] = int(d)
+    m.feat_dtype = feat_dtype
+    m.gcn_self_loops = 1 if gcn_self_loops else 0
+    return m
+
+
+def step_opts(estimator: int = EST_NONE, full_graph: bool = True, seeds=None, fanouts=(), sampler_seed: int = 0,
+              batch_id: int = 0) -> StepOpts:
+    o = StepOpts()
+    o.estimator = estimator
+    o.full_graph = 1 if full_graph else 0
+    o.n_seeds = 0 if seeds is None else int(seeds.numel())
+    o.seeds = _ptr(seeds)
+    for i, f in enumerate(fanouts):
+        o.fanouts[i] = int(f)
+    o.sampler_seed = sampler_seed
+    o.batch_id = batch_id
+    o._keep = seeds
+    return o
+
+
+class Partition:
+    """Owns a grp_partition_t handle; arrays are exposed as device tensors copied on request."""
+
+    def __init__(self, handle: int):
+        self.handle = handle
+        v = PartitionView()
+        _check(load().grp_partition_view(handle, C.byref(v)))
+        self.view = v
+        self.n, self.nnz = int(v.n), int(v.nnz)
+
+    def array(self, name: str) -> np.ndarray:
+        """Host copy of one of the handle's arrays (for tests)."""
+        spec = {"l2g": (np.int64, self.n), "rowptr": (np.int64, self.n + 1), "col": (np.int32, self.nnz),
+                "colptr": (np.int64, self.n + 1), "row": (np.int32, self.nnz), "d_local_in": (np.int32, self.n),
+                "d_local_out": (np.int32, self.n), "d_global_in": (np.int64, self.n)}[name]
+        dt, count = spec
+        out = np.empty(count, dtype=dt)
+        if count:
+            torch.cuda.synchronize()
+            _hip_memcpy_d2h(out, getattr(self.view, name))
+        return out
+
+    def destroy(self):
+        if self.handle:
+            _check(load().grp_partition_destroy(self.handle))
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+_hip = None
+
+
+def _hip_memcpy_d2h(dst: np.ndarray, src_ptr: int):
+    global _hip
+    if _hip is None:
+        _hip = C.CDLL("libamdhip64.so")
+        _hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+        _hip.hipMemcpy.restype = C.c_int
+    rc = _hip.hipMemcpy(dst.ctypes.data, src_ptr, dst.nbytes, 2)
+    if rc != 0:
+        raise RuntimeError(f"hipMemcpy D2H failed: {rc}")
+
+
+def grp_partition(src, dst, N: int, K: int, seed: int, part_id: int, stream=None) -> Partition:
+    out = C.c_void_p()
+    E = 0 if src is None else int(src.numel())
+    _check(load().grp_partition(_ptr(src), _ptr(dst), E, N, K, seed, part_id, _stream(stream), C.byref(out)))
+    return Partition(out.value)
+
+
+def grp_partition_from_local_coo(src_local, dst_local, n: int, d_global_in=None, l2g=None, stream=None) -> Partition:
+    out = C.c_void_p()
+    E = 0 if src_local is None else int(src_local.numel())
+    _check(load().grp_partition_from_local_coo(_ptr(src_local), _ptr(dst_local), E, n, _ptr(d_global_in), _ptr(l2g),
+                                               _stream(stream), C.byref(out)))
+    return Partition(out.value)
+
+
+def grp_param_count(model: ModelDesc) -> int:
+    return int(load().grp_param_count(C.byref(model)))
+
+
+def grp_step_workspace_bytes(part: Partition, model: ModelDesc, opts: StepOpts) -> int:
+    b = C.c_size_t()
+    _check(load().grp_step_workspace_bytes(part.handle, C.byref(model), C.byref(opts), C.byref(b)))
+    return int(b.value)
+
+
+def grp_train_step(part: Partition, model: ModelDesc, opts: StepOpts, features, labels, train_mask, weights,
+                   workspace, grad_out, stats_out, stream=None, workspace_bytes=None):
+    wb = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    _check(load().grp_train_step(part.handle, C.byref(model), C.byref(opts), _ptr(features), _ptr(labels),
+                                 _ptr(train_mask), _ptr(weights), _ptr(workspace), wb, _stream(stream),
+                                 _ptr(grad_out), _ptr(stats_out)))
+
+
+def grp_aggregate(grads, ld_grads: int, stats, K: int, P: int, variant: int, update, c_out=None, stream=None):
+    _check(load().grp_aggregate(_ptr(grads), ld_grads, _ptr(stats), K, P, variant, _stream(stream), _ptr(update),
+                                _ptr(c_out)))
+
+
+def grp_spmm(part: Partition, transposed: bool, scale: int, self_term: bool, F: int, X, ldx: int, x_dtype: int, Y,
+             ldy: int, stream=None):
+    _check(load().grp_spmm(part.handle, int(transposed), scale, int(self_term), F, _ptr(X), ldx, x_dtype, _ptr(Y), ldy,
+                           _stream(stream)))
+
+
+def grp_gemm_nn(M, N, K, A, lda, a_dtype, B, ldb, Cm, ldc, stream=None):
+    _check(load().grp_gemm_nn(M, N, K, _ptr(A), lda, a_dtype, _ptr(B), ldb, _ptr(Cm), ldc, _stream(stream)))
+
+
+def grp_gemm_tn_workspace_bytes(M, K, N) -> int:
+    return int(load().grp_gemm_tn_workspace_bytes(M, K, N))
+
+
+def grp_gemm_tn(M, K, N, A, lda, a_dtype, B, ldb, Cm, ldc, workspace, stream=None):
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().grp_gemm_tn(M, K, N, _ptr(A), lda, a_dtype, _ptr(B), ldb, _ptr(Cm), ldc, _ptr(workspace), wb,
+                              _stream(stream)))
+
+
+def grp_profile_enable(on: bool):
+    _check(load().grp_profile_enable(1 if on else 0))
+
+
+def grp_profile_report() -> dict:
+    buf = C.create_string_buffer(1 << 16)
+    _check(load().grp_profile_report(buf, len(buf)))
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, cnt, ms = line.split()
+        out[name] = (int(cnt), float(ms))
+    return out
+
+
+def new_stats(K: int = 1, device="cuda") -> torch.Tensor:
+    """Device buffer for K grp_step_stats records."""
+    return torch.zeros(K * STATS_BYTES, dtype=torch.uint8, device=device)
+
+
+def read_stats(stats: torch.Tensor) -> np.ndarray:
+    """Host view of the records as a structured array (loss, sum_ratio, R, S, nnz_used)."""
+    return np.frombuffer(stats.cpu().numpy().tobytes(), dtype=STATS_DTYPE)
+
+
+def exported_symbols():
+    return ["grp_last_error", "grp_partition", "grp_partition_from_local_coo", "grp_partition_view",
+            "grp_partition_destroy", "grp_param_count", "grp_step_workspace_bytes", "grp_train_step",
+            "grp_aggregate", "grp_spmm", "grp_gemm_nn", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
+            "grp_profile_enable", "grp_profile_report"]

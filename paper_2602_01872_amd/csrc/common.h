@@ -1,0 +1,178 @@
+// Internal helpers shared by the HIP translation units of libgrappa_hip.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <string>
+
+#include "../../include/grappa.h"
+
+namespace grp {
+
+// ---------------------------------------------------------------- errors
+void set_error(const char* fmt, ...);
+grp_status fail(grp_status code, const char* fmt, ...);
+
+#define GRP_HIP(call)                                                                   \
+    do {                                                                                \
+        hipError_t e_ = (call);                                                         \
+        if (e_ != hipSuccess)                                                           \
+            return grp::fail(GRP_EHIP, "%s failed: %s (%s:%d)", #call,                  \
+                             hipGetErrorString(e_), __FILE__, __LINE__);                \
+    } while (0)
+
+#define GRP_TRY(call)                                                                   \
+    do {                                                                                \
+        grp_status s_ = (call);                                                         \
+        if (s_ != GRP_OK) return s_;                                                    \
+    } while (0)
+
+// ---------------------------------------------------------------- profiling
+// Brackets a kernel launch with two events when profiling is enabled.
+void prof_begin(const char* name, hipStream_t st);
+void prof_end(hipStream_t st);
+
+struct ProfScope {
+    hipStream_t st;
+    ProfScope(const char* name, hipStream_t s) : st(s) { prof_begin(name, s); }
+    ~ProfScope() { prof_end(st); }
+};
+
+// Checks the launch itself (bad configuration etc.); kernels run asynchronously.
+#define GRP_LAUNCH_CHECK()                                                              \
+    do {                                                                                \
+        hipError_t e_ = hipGetLastError();                                              \
+        if (e_ != hipSuccess)                                                           \
+            return grp::fail(GRP_EHIP, "kernel launch failed: %s (%s:%d)",              \
+                             hipGetErrorString(e_), __FILE__, __LINE__);                \
+    } while (0)
+
+// ---------------------------------------------------------------- partition handle
+}  // namespace grp
+
+struct grp_partition_s {
+    int64_t n = 0, nnz = 0;
+    int64_t* l2g = nullptr;
+    int64_t* rowptr = nullptr;
+    int32_t* col = nullptr;
+    int64_t* colptr = nullptr;
+    int32_t* row = nullptr;
+    int32_t* d_local_in = nullptr;
+    int32_t* d_local_out = nullptr;
+    int64_t* d_global_in = nullptr;
+    int device = 0;
+};
+
+namespace grp {
+
+static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline int64_t round_up(int64_t a, int64_t b) { return cdiv(a, b) * b; }
+
+// ---------------------------------------------------------------- kernels (host launchers)
+// Neighbour aggregation over a CSR-like structure (ptr/idx), one output row per group of
+// lanes.  Y[i,:] = a_i (sum_e X[idx[e],:] + self*X[i,:]) (+ addend[i,:]) (+ bias) (ReLU).
+struct SpmmArgs {
+    const int64_t* ptr = nullptr;   // [n_rows+1]
+    const int32_t* idx = nullptr;   // [nnz]
+    int64_t n_rows = 0;
+    int32_t F = 0;
+    const void* X = nullptr;
+    int64_t ldx = 0;
+    int32_t x_bf16 = 0;
+    int32_t scale = GRP_SCALE_NONE;
+    int32_t self_term = 0;
+    const float* colscale = nullptr;  // per gathered row multiplier [n_src] or null
+    const float* addend = nullptr;  // [n_rows x F] or null (may alias Y)
+    int64_t ld_add = 0;
+    const float* bias = nullptr;    // [F] or null
+    int32_t relu = 0;
+    float* Y = nullptr;
+    int64_t ldy = 0;
+};
+grp_status launch_spmm(const SpmmArgs& a, hipStream_t st);
+
+// C[M x N] = epilogue(A[M x K] B[K x N] + A2[M x K2] B2[K2 x N])
+// epilogue: (+ bias[N]) (+ addend[M x N]) (* rowscale[M]) (ReLU) (* (mask[M x N] > 0))
+struct GemmNNArgs {
+    int64_t M = 0;
+    int32_t N = 0, K = 0;
+    const void* A = nullptr;
+    int64_t lda = 0;
+    int32_t a_bf16 = 0;
+    const float* B = nullptr;
+    int64_t ldb = 0;
+    int32_t K2 = 0;                 // 0 = no second product
+    const float* A2 = nullptr;
+    int64_t lda2 = 0;
+    const float* B2 = nullptr;
+    int64_t ldb2 = 0;
+    const float* bias = nullptr;
+    const float* addend = nullptr;
+    int64_t ld_add = 0;
+    const float* rowscale = nullptr;
+    int32_t relu = 0;
+    const float* mask = nullptr;
+    int64_t ld_mask = 0;
+    float* C = nullptr;
+    int64_t ldc = 0;
+    int32_t zero_pad_to = 0;        // also write zeros to columns [N, zero_pad_to)
+};
+grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st);
+
+// C[K x N] = A[M x K]^T B[M x N], fixed-order split over M.
+size_t gemm_tn_workspace_bytes(int64_t M, int32_t K, int32_t N);
+struct GemmTNArgs {
+    int64_t M = 0;
+    int32_t K = 0, N = 0;
+    const void* A = nullptr;
+    int64_t lda = 0;
+    int32_t a_bf16 = 0;
+    const float* B = nullptr;
+    int64_t ldb = 0;
+    float* C = nullptr;
+    int64_t ldc = 0;
+    void* workspace = nullptr;
+    size_t workspace_bytes = 0;
+};
+grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st);
+
+// out[N x K] (ld_out) = in[K x N]^T, rows [N, n_pad_rows) zero-filled.
+grp_status launch_transpose(const float* in, int32_t K, int32_t N, float* out, int64_t ld_out,
+                            int32_t n_pad_rows, hipStream_t st);
+
+// out[N] = column sums of A[M x N]; scratch holds the per-block partials.
+size_t colsum_workspace_bytes(int64_t M, int32_t N);
+grp_status launch_colsum(const float* A, int64_t M, int32_t N, int64_t lda, float* out,
+                         void* scratch, hipStream_t st);
+// Same with every row multiplied by rowmul[m] first (rowmul may be null).
+grp_status launch_colsum_scaled(const float* A, int64_t M, int32_t N, int64_t lda, const float* rowmul,
+                                float* out, void* scratch, hipStream_t st);
+// inv_in = 1/max(d_in,1); r = 1/sqrt(max(d_in+sl,1)); s = 1/sqrt(max(d_out+sl,1)); rinv = 1/r.
+grp_status launch_degree_scales(const int32_t* d_in, const int32_t* d_out, int64_t n, int sl,
+                                float* inv_in, float* r, float* s, float* rinv, hipStream_t st);
+// out[rows x ld_out] = in[rows x cols] (dense, pitch cols) with zero pad columns.
+grp_status launch_pad_copy(const float* in, int32_t rows, int32_t cols, float* out, int64_t ld_out,
+                           hipStream_t st);
+
+// Coverage statistics over the loss nodes and the weighted softmax cross-entropy.
+size_t stats_workspace_bytes(int64_t n);
+grp_status launch_stats(int64_t n_loss, const int32_t* loss_nodes /*null = 0..n-1 by mask*/,
+                        const uint8_t* mask, const int32_t* d_local, const int64_t* d_global,
+                        const int32_t* sampled_count /*null = full graph*/, int64_t nnz_used,
+                        void* scratch, grp_step_stats* out, hipStream_t st);
+grp_status launch_softmax_xent(int64_t n_rows, int32_t C, const float* Z, int64_t ldz,
+                               const int32_t* labels, const int32_t* node_of_row /*null = row*/,
+                               const uint8_t* mask, int32_t node_level,
+                               const int32_t* d_local, const int64_t* d_global,
+                               const float* rowscale /*null; multiplies dZ rows*/,
+                               float* dZ, int64_t lddz, void* scratch,
+                               grp_step_stats* stats /*reads S, writes loss*/, hipStream_t st);
+
+grp_status launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+
+}  // namespace grp

@@ -1,0 +1,378 @@
+// Bandwidth-bound kernels of the train step and the aggregation:
+//   weight preparation (aligned copies and transposes of the layer matrices, degree scales),
+//   column sums (bias gradients), coverage statistics over the loss nodes, weighted softmax
+//   cross-entropy with its logit gradient, and the K-way weighted gradient aggregation.
+// All reductions are two-stage with a fixed block count and a fixed tree, so results are
+// bit-reproducible (no floating-point atomics).
+#include "common.h"
+
+namespace grp {
+
+// ------------------------------------------------------------------ small utilities
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p, size_t words) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < words; i += stride) p[i] = 0u;
+}
+
+grp_status launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
+    if (bytes == 0) return GRP_OK;
+    if (bytes % 4 != 0 || (uintptr_t)p % 4 != 0) return fail(GRP_EINVAL, "fill_zero: unaligned");
+    const size_t words = bytes / 4;
+    size_t blocks = (words + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    ProfScope ps("fill_zero", st);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (uint32_t*)p, words);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
+// out[N rows, ld_out] = in[K x N]^T ; rows [N, n_pad_rows) and pad columns are zero.
+__global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict__ in, int K, int N,
+                                                        float* __restrict__ out, int64_t ld_out, int n_pad_rows) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (int64_t)n_pad_rows * ld_out) return;
+    const int r = (int)(e / ld_out), c = (int)(e % ld_out);     // out[r][c] = in[c][r]
+    out[e] = (r < N && c < K) ? in[(int64_t)c * N + r] : 0.f;
+}
+
+grp_status launch_transpose(const float* in, int32_t K, int32_t N, float* out, int64_t ld_out, int32_t n_pad_rows,
+                            hipStream_t st) {
+    ProfScope ps("transpose_w", st);
+    const int64_t blocks = cdiv((int64_t)n_pad_rows * ld_out, 256);
+    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, K, N, out, ld_out, n_pad_rows);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
+__global__ __launch_bounds__(256) void pad_copy_kernel(const float* __restrict__ in, int rows, int cols,
+                                                       float* __restrict__ out, int64_t ld_out) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (int64_t)rows * ld_out) return;
+    const int r = (int)(e / ld_out), c = (int)(e % ld_out);
+    out[e] = c < cols ? in[(int64_t)r * cols + c] : 0.f;
+}
+
+grp_status launch_pad_copy(const float* in, int32_t rows, int32_t cols, float* out, int64_t ld_out, hipStream_t st) {
+    ProfScope ps("pad_copy_w", st);
+    const int64_t blocks = cdiv((int64_t)rows * ld_out, 256);
+    hipLaunchKernelGGL(pad_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, rows, cols, out, ld_out);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
+// ------------------------------------------------------------------ block reductions
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T block_sum(T v, T* sm /*[4]*/) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return sm[0] + sm[1] + sm[2] + sm[3];
+}
+
+// ------------------------------------------------------------------ column sums
+constexpr int COLSUM_ROWS = 1024;    // rows per block
+
+size_t colsum_workspace_bytes(int64_t M, int32_t N) { return (size_t)cdiv(M > 0 ? M : 1, COLSUM_ROWS) * N * sizeof(float); }
+
+// part[b][c] = sum over the block's rows of A[m][c] * (rowmul ? rowmul[m] : 1)
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const float* __restrict__ A, int64_t M, int N, int64_t lda,
+                                                             const float* __restrict__ rowmul,
+                                                             float* __restrict__ part) {
+    const int64_t m0 = (int64_t)blockIdx.x * COLSUM_ROWS;
+    const int64_t m1 = m0 + COLSUM_ROWS < M ? m0 + COLSUM_ROWS : M;
+    for (int c = threadIdx.x; c < N; c += 256) {
+        float s = 0.f;
+        for (int64_t m = m0; m < m1; ++m) s += rowmul ? A[m * lda + c] * rowmul[m] : A[m * lda + c];
+        part[(int64_t)blockIdx.x * N + c] = s;
+    }
+}
+
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, int64_t blocks, int N,
+                                                           float* __restrict__ out) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= N) return;
+    float s = 0.f;
+    for (int64_t b = 0; b < blocks; ++b) s += part[b * N + c];
+    out[c] = s;
+}
+
+grp_status launch_colsum_scaled(const float* A, int64_t M, int32_t N, int64_t lda, const float* rowmul, float* out,
+                                void* scratch, hipStream_t st) {
+    const int64_t blocks = cdiv(M > 0 ? M : 1, COLSUM_ROWS);
+    ProfScope ps("colsum", st);
+    hipLaunchKernelGGL(colsum_partial_kernel, dim3((unsigned)blocks), dim3(256), 0, st, A, M, N, lda, rowmul,
+                       (float*)scratch);
+    GRP_LAUNCH_CHECK();
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, (const float*)scratch,
+                       blocks, N, out);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
+grp_status launch_colsum(const float* A, int64_t M, int32_t N, int64_t lda, float* out, void* scratch, hipStream_t st) {
+    return launch_colsum_scaled(A, M, N, lda, nullptr, out, scratch, st);
+}
+
+// ------------------------------------------------------------------ degree scales
+// inv_in[v] = 1/max(d_in,1); r[v] = 1/sqrt(max(d_in+sl,1)); s[v] = 1/sqrt(max(d_out+sl,1));
+// rinv[v] = sqrt(max(d_in+sl,1)).  Null outputs are skipped.
+__global__ __launch_bounds__(256) void degree_scales_kernel(const int32_t* __restrict__ d_in,
+                                                            const int32_t* __restrict__ d_out, int64_t n, int sl,
+                                                            float* __restrict__ inv_in, float* __restrict__ r,
+                                                            float* __restrict__ s, float* __restrict__ rinv) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v >= n) return;
+    const int di = d_in[v], dout = d_out[v];
+    if (inv_in) inv_in[v] = 1.0f / (float)(di > 1 ? di : 1);
+    const float a = (float)(di + sl > 1 ? di + sl : 1), b = (float)(dout + sl > 1 ? dout + sl : 1);
+    if (r) r[v] = 1.0f / sqrtf(a);
+    if (rinv) rinv[v] = sqrtf(a);
+    if (s) s[v] = 1.0f / sqrtf(b);
+}
+
+grp_status launch_degree_scales(const int32_t* d_in, const int32_t* d_out, int64_t n, int sl, float* inv_in, float* r,
+                                float* s, float* rinv, hipStream_t st) {
+    if (n == 0) return GRP_OK;
+    ProfScope ps("degree_scales", st);
+    hipLaunchKernelGGL(degree_scales_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, d_in, d_out, n, sl, inv_in,
+                       r, s, rinv);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
+// ------------------------------------------------------------------ coverage statistics
+constexpr int STATS_BLOCKS = 512;
+
+struct StatsPartial {
+    double ratio, r_dbl;
+    int64_t s, r_int;
+};
+
+size_t stats_workspace_bytes(int64_t) { return (size_t)STATS_BLOCKS * sizeof(StatsPartial) + STATS_BLOCKS * sizeof(double); }
+
+__device__ __forceinline__ double degree_ratio(int64_t dl, int64_t dg) { return dg > 0 ? (double)dl / (double)dg : 1.0; }
+
+// Rows are loss candidates: node = nodes ? nodes[i] : i; kept if !mask || mask[node].
+__global__ __launch_bounds__(256) void stats_partial_kernel(int64_t n_rows, const int32_t* __restrict__ nodes,
+                                                            const uint8_t* __restrict__ mask,
+                                                            const int32_t* __restrict__ d_local,
+                                                            const int64_t* __restrict__ d_global,
+                                                            const int32_t* __restrict__ sampled,
+                                                            StatsPartial* __restrict__ part) {
+    __shared__ double smd[4];
+    __shared__ int64_t smi[4];
+    double ratio = 0.0, rd = 0.0;
+    int64_t s = 0, ri = 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_rows; i += (int64_t)gridDim.x * 256) {
+        const int64_t v = nodes ? nodes[i] : i;
+        if (mask && !mask[v]) continue;
+        const int64_t dl = d_local[v], dg = d_global[v];
+        s += 1;
+        ratio += degree_ratio(dl, dg);
+        if (sampled) {
+            if (dl > 0) rd += (double)(dg - dl) * (double)sampled[i] / (double)dl;
+        } else {
+            ri += dg - dl;
+        }
+    }
+    ratio = block_sum<double>(ratio, smd);
+    rd = block_sum<double>(rd, smd);
+    s = block_sum<int64_t>(s, smi);
+    ri = block_sum<int64_t>(ri, smi);
+    if (threadIdx.x == 0) part[blockIdx.x] = StatsPartial{ratio, rd, s, ri};
+}
+
+__global__ __launch_bounds__(256) void stats_final_kernel(const StatsPartial* __restrict__ part, int blocks,
+                                                          int full_graph, int64_t nnz_used,
+                                                          grp_step_stats* __restrict__ out) {
+    __shared__ double smd[4];
+    __shared__ int64_t smi[4];
+    double ratio = 0.0, rd = 0.0;
+    int64_t s = 0, ri = 0;
+    for (int b = threadIdx.x; b < blocks; b += 256) {
+        ratio += part[b].ratio; rd += part[b].r_dbl; s += part[b].s; ri += part[b].r_int;
+    }
+    ratio = block_sum<double>(ratio, smd);
+    rd = block_sum<double>(rd, smd);
+    s = block_sum<int64_t>(s, smi);
+    ri = block_sum<int64_t>(ri, smi);
+    if (threadIdx.x == 0) {
+        out->loss = 0.0;
+        out->sum_ratio = ratio;
+        out->R = full_graph ? (double)ri : rd;
+        out->S = s;
+        out->nnz_used = nnz_used;
+    }
+}
+
+grp_status launch_stats(int64_t n_rows, const int32_t* nodes, const uint8_t* mask, const int32_t* d_local,
+                        const int64_t* d_global, const int32_t* sampled_count, int64_t nnz_used, void* scratch,
+                        grp_step_stats* out, hipStream_t st) {
+    ProfScope ps("coverage_stats", st);
+    StatsPartial* part = (StatsPartial*)scratch;
+    hipLaunchKernelGGL(stats_partial_kernel, dim3(STATS_BLOCKS), dim3(256), 0, st, n_rows, nodes, mask, d_local, d_global,
+                       sampled_count, part);
+    GRP_LAUNCH_CHECK();
+    hipLaunchKernelGGL(stats_final_kernel, dim3(1), dim3(256), 0, st, (const StatsPartial*)part, STATS_BLOCKS,
+                       sampled_count ? 0 : 1, nnz_used, out);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
+// ------------------------------------------------------------------ softmax cross-entropy
+// 16 lanes per row; dZ[row,:] = w (softmax(z) - onehot(y)) / |S| for loss rows, 0 otherwise
+// (pad columns up to the pitch's multiple of 4 are written as zeros too).
+__global__ __launch_bounds__(256) void softmax_xent_kernel(int64_t n_rows, int C, const float* __restrict__ Z,
+                                                           int64_t ldz, const int32_t* __restrict__ labels,
+                                                           const int32_t* __restrict__ nodes,
+                                                           const uint8_t* __restrict__ mask, int node_level,
+                                                           const int32_t* __restrict__ d_local,
+                                                           const int64_t* __restrict__ d_global,
+                                                           const float* __restrict__ rowscale,
+                                                           float* __restrict__ dZ, int64_t lddz, int c_store,
+                                                           const grp_step_stats* __restrict__ stats,
+                                                           double* __restrict__ loss_part) {
+    __shared__ double smd[4];
+    const int t = threadIdx.x & 15;
+    const int64_t S = stats->S;
+    const float inv_s = S > 0 ? 1.0f / (float)S : 0.f;
+    double loss = 0.0;
+    for (int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4); row < n_rows; row += (int64_t)gridDim.x * 16) {
+        const int64_t v = nodes ? nodes[row] : row;
+        const bool in_loss = !mask || mask[v];
+        if (!in_loss) {
+            for (int c = t; c < c_store; c += 16) dZ[row * lddz + c] = 0.f;
+            continue;
+        }
+        const float* z = Z + row * ldz;
+        float mx = -INFINITY;
+        for (int c = t; c < C; c += 16) mx = fmaxf(mx, z[c]);
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 16));
+        float sum = 0.f;
+        for (int c = t; c < C; c += 16) sum += expf(z[c] - mx);
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 16);
+        const int y = labels[v];
+        float w = 1.f;
+        if (node_level) w = (float)degree_ratio(d_local[v], d_global[v]);
+        const float k = w * inv_s * (rowscale ? rowscale[v] : 1.f), inv_sum = 1.0f / sum;
+        for (int c = t; c < c_store; c += 16) {
+            float g = 0.f;
+            if (c < C) g = (expf(z[c] - mx) * inv_sum - (c == y ? 1.f : 0.f)) * k;
+            dZ[row * lddz + c] = g;
+        }
+        if (t == 0) loss += (double)w * (double)(logf(sum) + mx - z[y]);
+    }
+    loss = block_sum<double>(loss, smd);
+    if (threadIdx.x == 0) loss_part[blockIdx.x] = loss;
+}
+
+__global__ __launch_bounds__(256) void loss_final_kernel(const double* __restrict__ part, int blocks,
+                                                         grp_step_stats* __restrict__ stats) {
+    __shared__ double smd[4];
+    double s = 0.0;
+    for (int b = threadIdx.x; b < blocks; b += 256) s += part[b];
+    s = block_sum<double>(s, smd);
+    if (threadIdx.x == 0) stats->loss = stats->S > 0 ? s / (double)stats->S : 0.0;
+}
+
+grp_status launch_softmax_xent(int64_t n_rows, int32_t C, const float* Z, int64_t ldz, const int32_t* labels,
+                               const int32_t* node_of_row, const uint8_t* mask, int32_t node_level,
+                               const int32_t* d_local, const int64_t* d_global, const float* rowscale, float* dZ,
+                               int64_t lddz, void* scratch, grp_step_stats* stats, hipStream_t st) {
+    ProfScope ps("softmax_xent", st);
+    double* loss_part = (double*)((char*)scratch + (size_t)STATS_BLOCKS * sizeof(StatsPartial));
+    int c_store = (int)round_up(C, 4);
+    if (c_store > lddz) c_store = (int)lddz;
+    hipLaunchKernelGGL(softmax_xent_kernel, dim3(STATS_BLOCKS), dim3(256), 0, st, n_rows, C, Z, ldz, labels, node_of_row,
+                       mask, node_level, d_local, d_global, rowscale, dZ, lddz, c_store, (const grp_step_stats*)stats, loss_part);
+    GRP_LAUNCH_CHECK();
+    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, st, (const double*)loss_part, STATS_BLOCKS, stats);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
+// ------------------------------------------------------------------ aggregation
+// G[i] = (1/K) sum_p c_p g_p[i], p ascending, fp32 FMAs.  c_p is derived from the statistics
+// record of partition p inside the kernel (no host round trip).
+__device__ __forceinline__ float coverage_factor(const grp_step_stats& s, int variant) {
+    if (variant == GRP_EST_BATCH_MIN_DIST) return s.S > 0 ? (float)(s.sum_ratio / (double)s.S) : 1.f;
+    if (variant == GRP_EST_SHRINKAGE) return s.R > 0.0 ? (float)(1.0 / s.R) : 1.f;
+    return 1.f;
+}
+
+constexpr int AGG_MAX_K_LDS = 1024;
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void aggregate_kernel(const float* __restrict__ grads, int64_t ld,
+                                                        const grp_step_stats* __restrict__ stats, int K, int64_t P,
+                                                        int variant, float* __restrict__ out,
+                                                        float* __restrict__ c_out) {
+    __shared__ float cs[AGG_MAX_K_LDS];
+    for (int p = threadIdx.x; p < K; p += 256) {
+        const float c = coverage_factor(stats[p], variant);
+        cs[p] = c;
+        if (c_out && blockIdx.x == 0) c_out[p] = c;
+    }
+    __syncthreads();
+    const float inv_k = 1.0f / (float)K;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    if constexpr (VEC) {
+        const int64_t P4 = P / 4;
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < P4; i += stride) {
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int p = 0; p < K; ++p) {
+                const float4 g = *reinterpret_cast<const float4*>(grads + (int64_t)p * ld + 4 * i);
+                const float c = cs[p];
+                a.x = fmaf(c, g.x, a.x); a.y = fmaf(c, g.y, a.y); a.z = fmaf(c, g.z, a.z); a.w = fmaf(c, g.w, a.w);
+            }
+            *reinterpret_cast<float4*>(out + 4 * i) = make_float4(a.x * inv_k, a.y * inv_k, a.z * inv_k, a.w * inv_k);
+        }
+        for (int64_t i = 4 * P4 + (int64_t)blockIdx.x * 256 + threadIdx.x; i < P; i += stride) {
+            float a = 0.f;
+            for (int p = 0; p < K; ++p) a = fmaf(cs[p], grads[(int64_t)p * ld + i], a);
+            out[i] = a * inv_k;
+        }
+    } else {
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < P; i += stride) {
+            float a = 0.f;
+            for (int p = 0; p < K; ++p) a = fmaf(cs[p], grads[(int64_t)p * ld + i], a);
+            out[i] = a * inv_k;
+        }
+    }
+}
+
+}  // namespace grp
+
+extern "C" grp_status grp_aggregate(const float* grads, int64_t ld_grads, const grp_step_stats* stats, int32_t K,
+                                    int64_t P, int32_t variant, void* stream, float* update, float* c_out) {
+    using namespace grp;
+    if (!grads || !stats || !update) return fail(GRP_EINVAL, "grp_aggregate: null argument");
+    if (K < 1 || K > AGG_MAX_K_LDS) return fail(GRP_EINVAL, "grp_aggregate: K = %d outside [1, %d]", K, AGG_MAX_K_LDS);
+    if (P < 0 || (K > 1 && ld_grads < P)) return fail(GRP_EINVAL, "grp_aggregate: bad P / pitch");
+    if (variant < GRP_EST_NONE || variant > GRP_EST_SHRINKAGE) return fail(GRP_EINVAL, "grp_aggregate: bad variant");
+    hipStream_t st = (hipStream_t)stream;
+    const bool vec = ld_grads % 4 == 0 && (uintptr_t)grads % 16 == 0 && (uintptr_t)update % 16 == 0;
+    int64_t blocks = cdiv((vec ? P / 4 : P) > 0 ? (vec ? P / 4 : P) : 1, 256);
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    ProfScope ps("aggregate", st);
+    if (vec)
+        hipLaunchKernelGGL((aggregate_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, st, grads, ld_grads, stats, K,
+                           P, variant, update, c_out);
+    else
+        hipLaunchKernelGGL((aggregate_kernel<false>), dim3((unsigned)blocks), dim3(256), 0, st, grads, ld_grads, stats, K,
+                           P, variant, update, c_out);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}

@@ -1,0 +1,364 @@
+// Random node assignment and the isolated local subgraph, built on the GPU.
+//
+// owner(v) = SplitMix64_output(seed, v) mod K.  A partition keeps the edges whose two
+// endpoints it owns, renumbers nodes by ascending global id and stores the edge multiset
+// twice in canonical order: CSR by destination (sources ascending) and CSC by source
+// (destinations ascending).  Canonical order comes from a radix sort of the 64-bit keys
+// (row << 32 | column); equal keys are indistinguishable, so the arrays are unique and can
+// be compared bit for bit.  Everything is integer work: counters use integer atomics only.
+//
+// The device-wide radix sort and prefix sum are rocPRIM's; the hashing, filtering,
+// relabelling and pointer construction are the kernels below.
+#include "common.h"
+
+#include <cstring>
+#include <new>
+
+#include <rocprim/rocprim.hpp>
+
+namespace grp {
+
+__device__ __forceinline__ uint64_t splitmix64_output(uint64_t seed, uint64_t index) {
+    uint64_t z = seed + (index + 1ull) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__global__ __launch_bounds__(256) void owner_flag_kernel(int64_t N, uint32_t K, uint64_t seed, uint32_t part,
+                                                         int32_t* __restrict__ flag) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v < N) flag[v] = (splitmix64_output(seed, (uint64_t)v) % K) == part ? 1 : 0;
+}
+
+__global__ __launch_bounds__(256) void scatter_l2g_kernel(int64_t N, const int32_t* __restrict__ flag,
+                                                          const int64_t* __restrict__ pos, int64_t* __restrict__ l2g) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v < N && flag[v]) l2g[pos[v]] = v;
+}
+
+// Pass 1 over the edges: id range check, global in-degree of owned destinations, count of kept edges.
+__global__ __launch_bounds__(256) void edge_scan_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                        int64_t E, int64_t N, const int32_t* __restrict__ flag,
+                                                        const int64_t* __restrict__ pos,
+                                                        unsigned long long* __restrict__ dg,
+                                                        unsigned long long* __restrict__ counters /*[0]=kept,[1]=bad*/) {
+    unsigned long long kept = 0, bad = 0;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
+        const int64_t u = src[e], v = dst[e];
+        if (u < 0 || v < 0 || u >= N || v >= N) { bad++; continue; }
+        if (flag[v]) {
+            atomicAdd(&dg[pos[v]], 1ull);
+            if (flag[u]) kept++;
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        kept += __shfl_down(kept, o, 64);
+        bad += __shfl_down(bad, o, 64);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        if (kept) atomicAdd(&counters[0], kept);
+        if (bad) atomicAdd(&counters[1], bad);
+    }
+}
+
+// Pass 2: write the key (dst_local << 32 | src_local) of every kept edge.  The slot order is
+// arbitrary (integer atomic cursor); the sort that follows makes the result canonical.
+__global__ __launch_bounds__(256) void edge_keys_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                        int64_t E, const int32_t* __restrict__ flag,
+                                                        const int64_t* __restrict__ pos,
+                                                        unsigned long long* __restrict__ cursor,
+                                                        uint64_t* __restrict__ keys) {
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
+        const int64_t u = src[e], v = dst[e];
+        if (flag[v] && flag[u]) {
+            const unsigned long long slot = atomicAdd(cursor, 1ull);
+            keys[slot] = ((uint64_t)pos[v] << 32) | (uint64_t)pos[u];
+        }
+    }
+}
+
+// Local edge list: range check + keys in place order.
+__global__ __launch_bounds__(256) void local_keys_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                         int64_t E, int64_t n, uint64_t* __restrict__ keys,
+                                                         unsigned long long* __restrict__ bad) {
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
+        const int64_t u = src[e], v = dst[e];
+        if (u < 0 || v < 0 || u >= n || v >= n) {
+            atomicAdd(bad, 1ull);
+            keys[e] = 0;
+        } else {
+            keys[e] = ((uint64_t)v << 32) | (uint64_t)u;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void swap_halves_kernel(const uint64_t* __restrict__ in, int64_t nnz,
+                                                          uint64_t* __restrict__ out) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nnz; i += (int64_t)gridDim.x * 256)
+        out[i] = (in[i] << 32) | (in[i] >> 32);
+}
+
+// From sorted keys: idx[i] = low half; ptr[r] = first position whose high half is >= r.
+__global__ __launch_bounds__(256) void csr_from_keys_kernel(const uint64_t* __restrict__ keys, int64_t nnz, int64_t n,
+                                                            int64_t* __restrict__ ptr, int32_t* __restrict__ idx) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i <= nnz; i += (int64_t)gridDim.x * 256) {
+        const int64_t hi = i < nnz ? (int64_t)(keys[i] >> 32) : n;
+        const int64_t prev = i > 0 ? (int64_t)(keys[i - 1] >> 32) : -1;
+        for (int64_t r = prev + 1; r <= hi; ++r) ptr[r] = i;
+        if (i < nnz) idx[i] = (int32_t)(keys[i] & 0xFFFFFFFFull);
+    }
+}
+
+__global__ __launch_bounds__(256) void degree_from_ptr_kernel(const int64_t* __restrict__ ptr, int64_t n,
+                                                              int32_t* __restrict__ deg) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v < n) deg[v] = (int32_t)(ptr[v + 1] - ptr[v]);
+}
+
+__global__ __launch_bounds__(256) void iota_kernel(int64_t n, int64_t* __restrict__ out) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v < n) out[v] = v;
+}
+
+__global__ __launch_bounds__(256) void widen_kernel(const int32_t* __restrict__ in, int64_t n, int64_t* __restrict__ out) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v < n) out[v] = in[v];
+}
+
+static unsigned grid_for(int64_t work) {
+    int64_t b = cdiv(work > 0 ? work : 1, 256);
+    return (unsigned)(b > 16384 ? 16384 : b);
+}
+
+struct DevBuf {
+    void* p = nullptr;
+    ~DevBuf() { if (p) (void)hipFree(p); }
+    grp_status alloc(size_t bytes) {
+        if (hipMalloc(&p, bytes ? bytes : 4) != hipSuccess) {
+            p = nullptr;
+            (void)hipGetLastError();
+            return fail(GRP_ENOMEM, "device allocation of %zu bytes failed", bytes);
+        }
+        return GRP_OK;
+    }
+    template <typename T> T* as() { return (T*)p; }
+};
+
+static void free_partition(grp_partition_t* h) {
+    if (!h) return;
+    void* ptrs[] = {h->l2g, h->rowptr, h->col, h->colptr, h->row, h->d_local_in, h->d_local_out, h->d_global_in};
+    for (void* q : ptrs)
+        if (q) (void)hipFree(q);
+    delete h;
+}
+
+template <typename T>
+static grp_status halloc(T** out, int64_t count) {
+    void* p = nullptr;
+    const size_t bytes = (size_t)(count > 0 ? count : 1) * sizeof(T);
+    if (hipMalloc(&p, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(GRP_ENOMEM, "device allocation of %zu bytes failed", bytes);
+    }
+    *out = (T*)p;
+    return GRP_OK;
+}
+
+static int bits_for(int64_t n) {
+    int b = 1;
+    while (b < 32 && ((int64_t)1 << b) < n) ++b;
+    return b;
+}
+
+// keys (unsorted, nnz of them; clobbered) -> h->rowptr/col/d_local_in and h->colptr/row/d_local_out.
+static grp_status build_csr_csc(grp_partition_t* h, uint64_t* keys, uint64_t* keys_alt, hipStream_t st) {
+    const int64_t n = h->n, nnz = h->nnz;
+    GRP_TRY(halloc(&h->rowptr, n + 1));
+    GRP_TRY(halloc(&h->colptr, n + 1));
+    GRP_TRY(halloc(&h->col, nnz));
+    GRP_TRY(halloc(&h->row, nnz));
+    GRP_TRY(halloc(&h->d_local_in, n));
+    GRP_TRY(halloc(&h->d_local_out, n));
+    const unsigned end_bit = 32 + bits_for(n > 1 ? n : 2);
+    size_t tmp_bytes = 0;
+    DevBuf tmp;
+    if (nnz > 0) {
+        GRP_HIP(rocprim::radix_sort_keys(nullptr, tmp_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
+        GRP_TRY(tmp.alloc(tmp_bytes));
+        GRP_HIP(rocprim::radix_sort_keys(tmp.p, tmp_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
+    }
+    hipLaunchKernelGGL(csr_from_keys_kernel, dim3(grid_for(nnz + 1)), dim3(256), 0, st, keys_alt, nnz, n, h->rowptr, h->col);
+    GRP_LAUNCH_CHECK();
+    if (nnz > 0) {
+        hipLaunchKernelGGL(swap_halves_kernel, dim3(grid_for(nnz)), dim3(256), 0, st, keys_alt, nnz, keys);
+        GRP_LAUNCH_CHECK();
+        GRP_HIP(rocprim::radix_sort_keys(tmp.p, tmp_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
+    }
+    hipLaunchKernelGGL(csr_from_keys_kernel, dim3(grid_for(nnz + 1)), dim3(256), 0, st, keys_alt, nnz, n, h->colptr, h->row);
+    GRP_LAUNCH_CHECK();
+    if (n > 0) {
+        hipLaunchKernelGGL(degree_from_ptr_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, h->rowptr, n, h->d_local_in);
+        GRP_LAUNCH_CHECK();
+        hipLaunchKernelGGL(degree_from_ptr_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, h->colptr, n, h->d_local_out);
+        GRP_LAUNCH_CHECK();
+    }
+    GRP_HIP(hipStreamSynchronize(st));
+    return GRP_OK;
+}
+
+static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t E, int64_t N, int32_t K, uint64_t seed,
+                                 int32_t part_id, hipStream_t st, grp_partition_t* h) {
+    DevBuf flag, pos, counters, scan_tmp;
+    GRP_TRY(flag.alloc((size_t)N * sizeof(int32_t)));
+    GRP_TRY(pos.alloc((size_t)N * sizeof(int64_t)));
+    GRP_TRY(counters.alloc(3 * sizeof(unsigned long long)));
+    GRP_HIP(hipMemsetAsync(counters.p, 0, 3 * sizeof(unsigned long long), st));
+
+    int64_t n = 0;
+    if (N > 0) {
+        hipLaunchKernelGGL(owner_flag_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, N, (uint32_t)K, seed,
+                           (uint32_t)part_id, flag.as<int32_t>());
+        GRP_LAUNCH_CHECK();
+        size_t bytes = 0;
+        GRP_HIP(rocprim::exclusive_scan(nullptr, bytes, flag.as<int32_t>(), pos.as<int64_t>(), (int64_t)0, (size_t)N,
+                                        rocprim::plus<int64_t>(), st));
+        GRP_TRY(scan_tmp.alloc(bytes));
+        GRP_HIP(rocprim::exclusive_scan(scan_tmp.p, bytes, flag.as<int32_t>(), pos.as<int64_t>(), (int64_t)0, (size_t)N,
+                                        rocprim::plus<int64_t>(), st));
+        int64_t last_pos = 0;
+        int32_t last_flag = 0;
+        GRP_HIP(hipMemcpyAsync(&last_pos, pos.as<int64_t>() + (N - 1), sizeof(int64_t), hipMemcpyDeviceToHost, st));
+        GRP_HIP(hipMemcpyAsync(&last_flag, flag.as<int32_t>() + (N - 1), sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        GRP_HIP(hipStreamSynchronize(st));
+        n = last_pos + last_flag;
+    }
+    if (n >= ((int64_t)1 << 31)) return fail(GRP_ERANGE, "partition has %lld >= 2^31 local nodes", (long long)n);
+    h->n = n;
+    GRP_TRY(halloc(&h->l2g, n));
+    GRP_TRY(halloc(&h->d_global_in, n));
+    GRP_HIP(hipMemsetAsync(h->d_global_in, 0, (size_t)(n > 0 ? n : 1) * sizeof(int64_t), st));
+    if (N > 0) {
+        hipLaunchKernelGGL(scatter_l2g_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, N, flag.as<int32_t>(),
+                           pos.as<int64_t>(), h->l2g);
+        GRP_LAUNCH_CHECK();
+    }
+    unsigned long long host_counters[3] = {0, 0, 0};
+    if (E > 0) {
+        hipLaunchKernelGGL(edge_scan_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, N, flag.as<int32_t>(),
+                           pos.as<int64_t>(), (unsigned long long*)h->d_global_in, counters.as<unsigned long long>());
+        GRP_LAUNCH_CHECK();
+        GRP_HIP(hipMemcpyAsync(host_counters, counters.p, sizeof host_counters, hipMemcpyDeviceToHost, st));
+        GRP_HIP(hipStreamSynchronize(st));
+    }
+    if (host_counters[1] != 0)
+        return fail(GRP_ERANGE, "%llu edges have an endpoint outside [0, %lld)", host_counters[1], (long long)N);
+    const int64_t nnz = (int64_t)host_counters[0];
+    h->nnz = nnz;
+    DevBuf keys, keys_alt;
+    GRP_TRY(keys.alloc((size_t)nnz * sizeof(uint64_t)));
+    GRP_TRY(keys_alt.alloc((size_t)nnz * sizeof(uint64_t)));
+    if (nnz > 0) {
+        hipLaunchKernelGGL(edge_keys_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, flag.as<int32_t>(),
+                           pos.as<int64_t>(), counters.as<unsigned long long>() + 2, keys.as<uint64_t>());
+        GRP_LAUNCH_CHECK();
+    }
+    return build_csr_csc(h, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), st);
+}
+
+}  // namespace grp
+
+extern "C" grp_status grp_partition(const int64_t* src, const int64_t* dst, int64_t E, int64_t N, int32_t K, uint64_t seed,
+                                    int32_t part_id, void* stream, grp_partition_t** out) {
+    using namespace grp;
+    if (!out) return fail(GRP_EINVAL, "grp_partition: out is null");
+    *out = nullptr;
+    if (E < 0 || N < 0) return fail(GRP_EINVAL, "grp_partition: negative size");
+    if (E > 0 && (!src || !dst)) return fail(GRP_EINVAL, "grp_partition: null edge arrays");
+    if (K < 1) return fail(GRP_EINVAL, "grp_partition: K = %d < 1", K);
+    if (part_id < 0 || part_id >= K) return fail(GRP_EINVAL, "grp_partition: part_id %d outside [0, %d)", part_id, K);
+    grp_partition_t* h = new (std::nothrow) grp_partition_t();
+    if (!h) return fail(GRP_ENOMEM, "grp_partition: host allocation failed");
+    (void)hipGetDevice(&h->device);
+    const grp_status s = partition_impl(src, dst, E, N, K, seed, part_id, (hipStream_t)stream, h);
+    if (s != GRP_OK) {
+        free_partition(h);
+        return s;
+    }
+    *out = h;
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_partition_from_local_coo(const int64_t* src_local, const int64_t* dst_local, int64_t E, int64_t n,
+                                                   const int64_t* d_global_in, const int64_t* l2g, void* stream,
+                                                   grp_partition_t** out) {
+    using namespace grp;
+    if (!out) return fail(GRP_EINVAL, "grp_partition_from_local_coo: out is null");
+    *out = nullptr;
+    if (E < 0 || n < 0) return fail(GRP_EINVAL, "grp_partition_from_local_coo: negative size");
+    if (E > 0 && (!src_local || !dst_local)) return fail(GRP_EINVAL, "grp_partition_from_local_coo: null edge arrays");
+    if (n >= ((int64_t)1 << 31)) return fail(GRP_ERANGE, "n = %lld >= 2^31", (long long)n);
+    hipStream_t st = (hipStream_t)stream;
+    grp_partition_t* h = new (std::nothrow) grp_partition_t();
+    if (!h) return fail(GRP_ENOMEM, "host allocation failed");
+    (void)hipGetDevice(&h->device);
+    h->n = n;
+    h->nnz = E;
+    auto body = [&]() -> grp_status {
+        DevBuf keys, keys_alt, bad;
+        GRP_TRY(keys.alloc((size_t)E * sizeof(uint64_t)));
+        GRP_TRY(keys_alt.alloc((size_t)E * sizeof(uint64_t)));
+        GRP_TRY(bad.alloc(sizeof(unsigned long long)));
+        GRP_HIP(hipMemsetAsync(bad.p, 0, sizeof(unsigned long long), st));
+        if (E > 0) {
+            hipLaunchKernelGGL(local_keys_kernel, dim3(grid_for(E)), dim3(256), 0, st, src_local, dst_local, E, n,
+                               keys.as<uint64_t>(), bad.as<unsigned long long>());
+            GRP_LAUNCH_CHECK();
+        }
+        unsigned long long nbad = 0;
+        GRP_HIP(hipMemcpyAsync(&nbad, bad.p, sizeof nbad, hipMemcpyDeviceToHost, st));
+        GRP_HIP(hipStreamSynchronize(st));
+        if (nbad) return fail(GRP_ERANGE, "%llu edges have an endpoint outside [0, %lld)", nbad, (long long)n);
+        GRP_TRY(build_csr_csc(h, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), st));
+        GRP_TRY(halloc(&h->l2g, n));
+        GRP_TRY(halloc(&h->d_global_in, n));
+        if (n > 0) {
+            const unsigned g = (unsigned)cdiv(n, 256);
+            if (l2g) GRP_HIP(hipMemcpyAsync(h->l2g, l2g, (size_t)n * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
+            else hipLaunchKernelGGL(iota_kernel, dim3(g), dim3(256), 0, st, n, h->l2g);
+            if (d_global_in)
+                GRP_HIP(hipMemcpyAsync(h->d_global_in, d_global_in, (size_t)n * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
+            else hipLaunchKernelGGL(widen_kernel, dim3(g), dim3(256), 0, st, h->d_local_in, n, h->d_global_in);
+            GRP_LAUNCH_CHECK();
+        }
+        GRP_HIP(hipStreamSynchronize(st));
+        return GRP_OK;
+    };
+    const grp_status s = body();
+    if (s != GRP_OK) {
+        free_partition(h);
+        return s;
+    }
+    *out = h;
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_partition_view(const grp_partition_t* part, grp_partition_view_t* view) {
+    if (!part || !view) return grp::fail(GRP_EINVAL, "grp_partition_view: null argument");
+    view->n = part->n;
+    view->nnz = part->nnz;
+    view->l2g = part->l2g;
+    view->rowptr = part->rowptr;
+    view->col = part->col;
+    view->colptr = part->colptr;
+    view->row = part->row;
+    view->d_local_in = part->d_local_in;
+    view->d_local_out = part->d_local_out;
+    view->d_global_in = part->d_global_in;
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_partition_destroy(grp_partition_t* part) {
+    grp::free_partition(part);
+    return GRP_OK;
+}

@@ -1,0 +1,99 @@
+// Error reporting and per-kernel event timing for libgrappa_hip.so.
+#include "common.h"
+
+#include <map>
+#include <mutex>
+#include <vector>
+
+namespace grp {
+
+static thread_local std::string g_err;
+
+void set_error(const char* fmt, ...) {
+    char buf[1024];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+}
+
+grp_status fail(grp_status code, const char* fmt, ...) {
+    char buf[1024];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+struct ProfRec {
+    const char* name;
+    hipEvent_t a, b;
+};
+static std::mutex g_prof_mu;
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof;
+static thread_local hipEvent_t g_open_end = nullptr;
+
+void prof_begin(const char* name, hipStream_t st) {
+    if (!g_prof_on) return;
+    ProfRec r{name, nullptr, nullptr};
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+    (void)hipEventRecord(r.a, st);
+    g_open_end = r.b;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof.push_back(r);
+}
+
+void prof_end(hipStream_t st) {
+    if (!g_prof_on || !g_open_end) return;
+    (void)hipEventRecord(g_open_end, st);
+    g_open_end = nullptr;
+}
+
+}  // namespace grp
+
+extern "C" const char* grp_last_error(void) { return grp::g_err.c_str(); }
+
+extern "C" grp_status grp_profile_enable(int32_t on) {
+    std::lock_guard<std::mutex> lk(grp::g_prof_mu);
+    grp::g_prof_on = on != 0;
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_profile_report(char* buf, size_t cap) {
+    if (!buf || cap == 0) return grp::fail(GRP_EINVAL, "grp_profile_report: null buffer");
+    std::vector<grp::ProfRec> recs;
+    {
+        std::lock_guard<std::mutex> lk(grp::g_prof_mu);
+        recs.swap(grp::g_prof);
+    }
+    std::map<std::string, std::pair<long, double>> acc;
+    std::vector<std::string> order;
+    for (auto& r : recs) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+            auto it = acc.find(r.name);
+            if (it == acc.end()) {
+                order.push_back(r.name);
+                acc[r.name] = {1, ms};
+            } else {
+                it->second.first += 1;
+                it->second.second += ms;
+            }
+        }
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    std::string out;
+    char line[256];
+    for (auto& nm : order) {
+        snprintf(line, sizeof line, "%s %ld %.6f\n", nm.c_str(), acc[nm].first, acc[nm].second);
+        out += line;
+    }
+    if (out.size() + 1 > cap) out.resize(cap - 1);
+    memcpy(buf, out.c_str(), out.size() + 1);
+    return GRP_OK;
+}

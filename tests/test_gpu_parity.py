@@ -1,0 +1,370 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded
+inputs.  Integer outputs (partition, local indices, degrees, |S|, the full-graph shrinkage
+sum) must be bit-exact; floating point within the tolerances in tests/_cases.py."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import coverage as ocov
+from oracle import gnn as ognn
+from oracle import graph as ograph
+from oracle import step as ostep
+from tests._cases import TOL_BF16, TOL_FP32, assert_grads_close, make_inputs, rel_err
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+@pytest.fixture(scope="module")
+def g():
+    import paper_2602_01872_amd as lib
+    lib.load()
+    return lib
+
+
+def _note(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+PART_KEYS = ("l2g", "rowptr", "col", "colptr", "row", "d_local_in", "d_local_out", "d_global_in")
+
+
+def _assert_partition_equal(part, want):
+    assert part.n == want["n"] and part.nnz == want["nnz"]
+    for k in PART_KEYS:
+        got = part.array(k)
+        assert got.dtype == want[k].dtype, k
+        assert np.array_equal(got, want[k]), f"{k} differs"
+
+
+# ----------------------------------------------------------------------------- partition
+@pytest.mark.parametrize("kind,N,E,K,seed", [
+    ("uniform", 10000, 100000, 4, 1),
+    ("uniform", 1000, 5000, 1, 0),
+    ("uniform", 50, 400, 64, 3),
+    ("rmat", 1 << 14, 300000, 8, 1),
+    ("rmat", 1 << 12, 200000, 3, 12345678901234567),
+])
+def test_partition_bit_exact(g, kind, N, E, K, seed):
+    _note(f"partition {kind} N={N} E={E} K={K} seed={seed}")
+    if kind == "uniform":
+        s, d = synth.uniform_graph(N, E, seed=2602018721, device=DEV)
+    else:
+        s, d = synth.rmat_graph(N.bit_length() - 1, E, seed=2602018722, device=DEV)
+    sh, dh = s.cpu().numpy(), d.cpu().numpy()
+    parts = sorted(set([0, K - 1, K // 2]))
+    for p in parts:
+        part = g.grp_partition(s, d, N, K, seed, p)
+        _assert_partition_equal(part, ograph.partition(sh, dh, N, K, seed, p))
+        part.destroy()
+
+
+def test_partition_edge_cases_and_errors(g):
+    _note("partition edge cases")
+    part = g.grp_partition(None, None, 10, 3, 0, 1)
+    e = np.zeros(0, dtype=np.int64)
+    _assert_partition_equal(part, ograph.partition(e, e, 10, 3, 0, 1))
+    part = g.grp_partition(None, None, 0, 2, 0, 0)
+    assert part.n == 0 and part.nnz == 0
+    s = torch.tensor([0, 1, 12], dtype=torch.int64, device=DEV)
+    d = torch.tensor([1, 2, 3], dtype=torch.int64, device=DEV)
+    with pytest.raises(g.GrappaError) as ei:
+        g.grp_partition(s, d, 10, 2, 0, 0)
+    assert ei.value.status == g.ERANGE
+    for K, p in ((0, 0), (2, 2), (2, -1)):
+        with pytest.raises(g.GrappaError) as ei:
+            g.grp_partition(s[:2], d[:2], 10, K, 0, p)
+        assert ei.value.status == g.EINVAL
+
+
+def test_partition_from_local_coo(g):
+    _note("partition_from_local_coo")
+    n, E = 3000, 40000
+    s, d = synth.rmat_graph(12, E, seed=5, n_nodes=n, device=DEV)
+    part0 = g.grp_partition_from_local_coo(s, d, n)
+    want = ograph.local_graph_from_edges(s.cpu().numpy(), d.cpu().numpy(), n)
+    _assert_partition_equal(part0, want)
+    dg = synth.stand_in_global_degree(torch.from_numpy(want["d_local_in"]), torch.arange(n), 9, 15).to(DEV)
+    part = g.grp_partition_from_local_coo(s, d, n, d_global_in=dg)
+    assert np.array_equal(part.array("d_global_in"), dg.cpu().numpy())
+    with pytest.raises(g.GrappaError) as ei:
+        g.grp_partition_from_local_coo(s, d, n - 2000)
+    assert ei.value.status == g.ERANGE
+
+
+# ----------------------------------------------------------------------------- SpMM
+def _oracle_spmm(part, transposed, scale, self_term, x):
+    n = part["n"]
+    if transposed:
+        ptr, idx = part["colptr"], part["row"]
+    else:
+        ptr, idx = part["rowptr"], part["col"]
+    blk = ognn.block_from_csr(ptr, idx)
+    y = ognn._scatter_rows(n, blk["edst"], x[blk["esrc"]])
+    deg = np.diff(ptr).astype(np.float64)
+    if self_term:
+        y += x
+    if scale == 1:
+        y *= (1.0 / np.maximum(deg, 1.0))[:, None]
+    elif scale == 2:
+        y *= (1.0 / np.sqrt(np.maximum(deg + (1 if self_term else 0), 1.0)))[:, None]
+    return y
+
+
+@pytest.mark.parametrize("F,ld,bf16", [(8, 8, False), (47, 48, False), (47, 47, False), (64, 64, True), (100, 100, False),
+                                       (128, 128, True), (256, 256, False), (300, 300, False), (5, 8, True)])
+def test_spmm_matches_oracle(g, F, ld, bf16):
+    _note(f"spmm F={F} ld={ld} bf16={bf16}")
+    N, E, K = 1 << 13, 200000, 2
+    s, d = synth.rmat_graph(13, E, seed=77, device=DEV)
+    part = g.grp_partition(s, d, N, K, 5, 1)
+    op = ograph.partition(s.cpu().numpy(), d.cpu().numpy(), N, K, 5, 1)
+    n = part.n
+    assert int(op["d_local_in"].max()) > 300          # a hub row spanning several index tiles
+    assert (op["d_local_in"] == 0).any()
+    xf = synth.normal_matrix(n, ld, 3)
+    xf[:, F:] = 0
+    x = (synth.to_bf16_rne(xf) if bf16 else xf).to(DEV)
+    x64 = x.cpu().double().numpy()[:, :F]
+    tol = TOL_FP32
+    for transposed in (False, True):
+        for scale, self_term in ((g.SCALE_NONE, False), (g.SCALE_MEAN, False), (g.SCALE_RSQRT, True), (g.SCALE_RSQRT, False)):
+            y = torch.full((n, ld), float("nan"), device=DEV)
+            g.grp_spmm(part, transposed, scale, self_term, F, x, ld, g.DTYPE_BF16 if bf16 else g.DTYPE_FP32, y, ld)
+            torch.cuda.synchronize()
+            want = _oracle_spmm(op, transposed, scale, self_term, x64)
+            got = y.cpu().numpy()[:, :F]
+            assert rel_err(got, want) <= tol, (transposed, scale, self_term, rel_err(got, want))
+
+
+# ----------------------------------------------------------------------------- GEMMs
+@pytest.mark.parametrize("M,N,K,bf16", [(1000, 256, 256, False), (777, 47, 100, False), (129, 8, 64, False),
+                                        (5000, 172, 128, True), (333, 130, 33, False), (64, 64, 256, False)])
+def test_gemm_nn_matches_numpy(g, M, N, K, bf16):
+    _note(f"gemm_nn M={M} N={N} K={K} bf16={bf16}")
+    a = synth.normal_matrix(M, K, 1)
+    a = (synth.to_bf16_rne(a) if bf16 else a).to(DEV)
+    b = synth.normal_matrix(K, N, 2).to(DEV)
+    c = torch.full((M, N), float("nan"), device=DEV)
+    g.grp_gemm_nn(M, N, K, a, K, g.DTYPE_BF16 if bf16 else g.DTYPE_FP32, b, N, c, N)
+    torch.cuda.synchronize()
+    want = a.cpu().double().numpy() @ b.cpu().double().numpy()
+    assert rel_err(c.cpu().numpy(), want) <= TOL_FP32
+
+
+@pytest.mark.parametrize("M,K,N,bf16", [(10000, 256, 256, False), (70001, 100, 47, False), (513, 64, 8, False),
+                                        (30000, 128, 172, True), (31, 33, 130, False), (0, 16, 16, False)])
+def test_gemm_tn_matches_numpy(g, M, K, N, bf16):
+    _note(f"gemm_tn M={M} K={K} N={N} bf16={bf16}")
+    a = synth.normal_matrix(max(M, 1), K, 3)[:M]
+    a = (synth.to_bf16_rne(a) if bf16 else a).to(DEV)
+    b = synth.normal_matrix(max(M, 1), N, 4)[:M].to(DEV)
+    c = torch.full((K, N), float("nan"), device=DEV)
+    ws = torch.empty(max(g.grp_gemm_tn_workspace_bytes(M, K, N), 16), dtype=torch.uint8, device=DEV)
+    g.grp_gemm_tn(M, K, N, a, K, g.DTYPE_BF16 if bf16 else g.DTYPE_FP32, b, N, c, N, ws)
+    torch.cuda.synchronize()
+    want = a.cpu().double().numpy().T @ b.cpu().double().numpy()
+    got = c.cpu().numpy()
+    if M == 0:
+        assert (got == 0).all()
+    else:
+        assert rel_err(got, want) <= TOL_FP32
+
+
+# ----------------------------------------------------------------------------- train step + aggregate
+ARCH = {"sage": 0, "gcn": 1, "gcn_res": 2}
+
+
+def _run_step(g, part, arch, dims, x, y, theta, mask=None, est=0, bf16=False, self_loops=True):
+    model = g.model_desc(ARCH[arch], dims, g.DTYPE_BF16 if bf16 else g.DTYPE_FP32, self_loops)
+    opts = g.step_opts(estimator=est, full_graph=True)
+    P = g.grp_param_count(model)
+    ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+    grad = torch.full((P,), float("nan"), device=DEV)
+    stats = g.new_stats(1)
+    g.grp_train_step(part, model, opts, x, y, mask, theta, ws, grad, stats)
+    torch.cuda.synchronize()
+    return grad, stats
+
+
+def _check_stats(st_gpu, st_cpu, tol):
+    assert int(st_gpu["S"]) == st_cpu["S"]
+    assert int(st_gpu["nnz_used"]) == st_cpu["nnz_used"]
+    assert float(st_gpu["R"]) == st_cpu["R"]                          # integer count in full-graph mode
+    assert abs(float(st_gpu["sum_ratio"]) - st_cpu["sum_ratio"]) <= 1e-9 * max(1.0, st_cpu["sum_ratio"])
+    assert abs(float(st_gpu["loss"]) - st_cpu["loss"]) <= tol * max(abs(st_cpu["loss"]), 1e-30)
+
+
+@pytest.mark.parametrize("est", [0, 1])
+def test_config1_gcn2_four_partitions_and_aggregate(g, est):
+    """Workload 1: 2-layer GCN, uniform graph N=10,000 / E=100,000, 4 hash partitions,
+    features 64, hidden 64, 8 classes; one step per partition, then every aggregation variant."""
+    _note(f"config 1 est={est}")
+    N, E, K, dims = 10000, 100000, 4, [64, 64, 8]
+    s, d = synth.uniform_graph(N, E, seed=2602018721, device=DEV)
+    sh, dh = s.cpu().numpy(), d.cpu().numpy()
+    xg = synth.normal_matrix(N, 64, 2602018721)
+    yg = synth.labels(N, 8, 2602018721)
+    theta = synth.model_weights("gcn", dims, 2602018721)
+    P = theta.numel()
+    ldg = ((P + 3) // 4) * 4
+    grads = torch.zeros(K, ldg, device=DEV)
+    stats = g.new_stats(K)
+    o_grads, o_stats = [], []
+    for p in range(K):
+        part = g.grp_partition(s, d, N, K, 1, p)
+        op = ograph.partition(sh, dh, N, K, 1, p)
+        _assert_partition_equal(part, op)
+        x = xg[op["l2g"]].contiguous()
+        y = yg[op["l2g"]].contiguous()
+        model = g.model_desc(g.ARCH_GCN, dims)
+        opts = g.step_opts(estimator=est)
+        ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+        g.grp_train_step(part, model, opts, x.to(DEV), y.to(DEV), None, theta.to(DEV), ws, grads[p],
+                         stats[p * g.STATS_BYTES:(p + 1) * g.STATS_BYTES])
+        torch.cuda.synchronize()
+        og, ost = ostep.train_step(op, "gcn", dims, theta.double().numpy(), x.double().numpy(), y.numpy(), estimator=est)
+        assert_grads_close(grads[p, :P].cpu().numpy(), og, "gcn", dims, TOL_FP32)
+        _check_stats(g.read_stats(stats)[p], ost, TOL_FP32)
+        o_grads.append(og)
+        o_stats.append(ost)
+    for variant in (0, 1, 2, 3):
+        upd = torch.full((P,), float("nan"), device=DEV)
+        c = torch.zeros(K, device=DEV)
+        g.grp_aggregate(grads, ldg, stats, K, P, variant, upd, c)
+        torch.cuda.synchronize()
+        G, oc = ocov.aggregate(o_grads, o_stats, variant)
+        assert rel_err(c.cpu().numpy(), oc) <= TOL_FP32
+        assert_grads_close(upd.cpu().numpy(), G, "gcn", dims, TOL_FP32)
+
+
+@pytest.mark.parametrize("arch,dims,bf16,self_loops,masked", [
+    ("sage", [100, 256, 256, 47], False, True, False),
+    ("sage", [64, 128, 16], True, True, True),
+    ("sage", [128, 256, 256, 172], True, True, False),
+    ("sage", [36, 20, 52, 7], False, True, True),
+    ("gcn", [128, 256, 64], False, False, True),
+    ("gcn", [40, 72, 72, 10], False, True, False),
+])
+def test_train_step_rmat_matches_oracle(g, arch, dims, bf16, self_loops, masked):
+    """R-MAT partition (degree skew, empty rows, multi-edges) at sizes the oracle finishes in
+    seconds: several 128-row tiles plus a ragged tail."""
+    _note(f"train_step {arch} dims={dims} bf16={bf16} sl={self_loops} masked={masked}")
+    scale, E, K = 14, 400000, 3
+    N = 1 << scale
+    s, d = synth.rmat_graph(scale, E, seed=2602018722, device=DEV)
+    part = g.grp_partition(s, d, N, K, 1, 0)
+    op = ograph.partition(s.cpu().numpy(), d.cpu().numpy(), N, K, 1, 0)
+    n = part.n
+    assert n % 128 != 0
+    x, y, theta = make_inputs(n, dims, arch, 11, bf16=bf16)
+    mask = synth.train_mask(n, 0.3, 4) if masked else None
+    tol = TOL_BF16 if bf16 else TOL_FP32
+    for est in (0, 1):
+        grad, stats = _run_step(g, part, arch, dims, x.to(DEV), y.to(DEV), theta.to(DEV),
+                                None if mask is None else mask.to(DEV), est, bf16, self_loops)
+        og, ost = ostep.train_step(op, arch, dims, theta.double().numpy(), x.double().numpy(), y.numpy(),
+                                   train_mask=None if mask is None else mask.numpy(), estimator=est,
+                                   gcn_self_loops=self_loops)
+        assert_grads_close(grad.cpu().numpy(), og, arch, dims, min(tol, TOL_FP32))
+        _check_stats(g.read_stats(stats)[0], ost, TOL_FP32)
+
+
+def test_train_step_is_bit_reproducible(g):
+    _note("determinism")
+    scale, E, K, dims = 13, 150000, 2, [64, 96, 10]
+    s, d = synth.rmat_graph(scale, E, seed=9, device=DEV)
+    part = g.grp_partition(s, d, 1 << scale, K, 1, 1)
+    x, y, theta = make_inputs(part.n, dims, "sage", 5)
+    a, sa = _run_step(g, part, "sage", dims, x.to(DEV), y.to(DEV), theta.to(DEV))
+    b, sb = _run_step(g, part, "sage", dims, x.to(DEV), y.to(DEV), theta.to(DEV))
+    assert torch.equal(a, b) and torch.equal(sa, sb)
+
+
+def test_train_step_degenerate_partitions(g):
+    _note("degenerate partitions")
+    dims = [8, 12, 3]
+    theta = synth.model_weights("sage", dims, 1).to(DEV)
+    # empty partition: zero gradient, S = 0, loss 0
+    part = g.grp_partition(None, None, 0, 1, 0, 0)
+    grad, stats = _run_step(g, part, "sage", dims, torch.zeros(1, 8, device=DEV), torch.zeros(1, dtype=torch.int32, device=DEV), theta)
+    st = g.read_stats(stats)[0]
+    assert (grad == 0).all() and st["S"] == 0 and st["loss"] == 0.0
+    # no edges at all; every node isolated
+    part = g.grp_partition(None, None, 300, 1, 0, 0)
+    x, y, _ = make_inputs(300, dims, "sage", 2)
+    grad, stats = _run_step(g, part, "sage", dims, x.to(DEV), y.to(DEV), theta)
+    op = ograph.partition(np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64), 300, 1, 0, 0)
+    og, ost = ostep.train_step(op, "sage", dims, theta.cpu().double().numpy(), x.double().numpy(), y.numpy())
+    assert_grads_close(grad.cpu().numpy(), og, "sage", dims, TOL_FP32)
+    # empty loss set
+    mask = torch.zeros(300, dtype=torch.uint8, device=DEV)
+    grad, stats = _run_step(g, part, "sage", dims, x.to(DEV), y.to(DEV), theta, mask=mask)
+    assert (grad == 0).all() and g.read_stats(stats)[0]["S"] == 0
+
+
+def test_error_paths(g):
+    _note("error paths")
+    part = g.grp_partition(None, None, 100, 1, 0, 0)
+    dims = [8, 4]
+    model = g.model_desc(g.ARCH_GCN, dims)
+    opts = g.step_opts()
+    need = g.grp_step_workspace_bytes(part, model, opts)
+    x, y, theta = make_inputs(100, dims, "gcn", 1)
+    x, y, theta = x.to(DEV), y.to(DEV), theta.to(DEV)
+    grad = torch.zeros(theta.numel(), device=DEV)
+    stats = g.new_stats(1)
+    small = torch.empty(max(need - 256, 1), dtype=torch.uint8, device=DEV)
+    with pytest.raises(g.GrappaError) as ei:
+        g.grp_train_step(part, model, opts, x, y, None, theta, small, grad, stats)
+    assert ei.value.status == g.EWORKSPACE
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    with pytest.raises(g.GrappaError) as ei:
+        g.grp_train_step(part, model, opts, x, y, None, None, ws, grad, stats)
+    assert ei.value.status == g.EINVAL
+    bad = g.model_desc(g.ARCH_GCN, [8, -1])
+    with pytest.raises(g.GrappaError) as ei:
+        g.grp_step_workspace_bytes(part, bad, opts)
+    assert ei.value.status == g.EINVAL
+    with pytest.raises(g.GrappaError) as ei:
+        g.grp_aggregate(grad, 8, stats, 0, 4, 0, grad)
+    assert ei.value.status == g.EINVAL
+    with pytest.raises(g.GrappaError) as ei:
+        g.grp_aggregate(grad, 8, stats, 1, 4, 9, grad)
+    assert ei.value.status == g.EINVAL
+    assert "variant" in str(ei.value)
+
+
+def test_aggregate_invariants(g):
+    """Full coverage -> plain average for every variant; K = 256 shrinkage against the oracle."""
+    _note("aggregate invariants")
+    K, P = 256, 20624
+    ld = P
+    grads = synth.normal_matrix(K, ld, 8).to(DEV)
+    recs = np.zeros(K, dtype=g.STATS_DTYPE)
+    recs["S"] = 1000
+    recs["sum_ratio"] = 1000.0
+    recs["R"] = 0.0
+    stats = torch.from_numpy(recs.view(np.uint8)).to(DEV)
+    plain = grads.cpu().double().numpy().mean(axis=0)
+    for variant in (0, 1, 2, 3):
+        upd = torch.zeros(P, device=DEV)
+        g.grp_aggregate(grads, ld, stats, K, P, variant, upd)
+        torch.cuda.synchronize()
+        assert rel_err(upd.cpu().numpy(), plain) <= TOL_FP32
+    recs["sum_ratio"] = np.linspace(3.0, 900.0, K)
+    recs["R"] = np.arange(K) * 17.0                                  # R_0 = 0 -> c = 1
+    recs["S"][5] = 0
+    stats = torch.from_numpy(recs.view(np.uint8)).to(DEV)
+    ost = [dict(S=int(r["S"]), sum_ratio=float(r["sum_ratio"]), R=float(r["R"])) for r in recs]
+    og = [grads[p].cpu().double().numpy() for p in range(K)]
+    for variant in (2, 3):
+        upd = torch.zeros(P, device=DEV)
+        c = torch.zeros(K, device=DEV)
+        g.grp_aggregate(grads, ld, stats, K, P, variant, upd, c)
+        torch.cuda.synchronize()
+        G, oc = ocov.aggregate(og, ost, variant)
+        assert rel_err(c.cpu().numpy(), oc) <= TOL_FP32
+        assert rel_err(upd.cpu().numpy(), G) <= TOL_FP32
