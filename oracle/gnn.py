@@ -20,6 +20,12 @@ Readings where the paper is silent:
   * residual GCN: h^{l+1} = h^l + ReLU(z^l) where the two widths agree (never on the
                  last layer); not in the paper, defined by the workload list.
   * dropout is off.
+  * the derivative of ReLU is 1 where the pre-activation z > 0 and 0 elsewhere.  A
+    pre-activation within rounding distance of 0 makes that decision depend on the
+    precision and summation order of whoever computes z, so ``forward_backward`` can list
+    the hidden pre-activations with |z| <= guard (``near_kink``) and can be asked to take
+    the opposite decision for chosen elements (``relu_flip``); a checker uses the two to
+    accept either decision exactly at a kink and nothing else.
   * parameters are one flat vector: layer-major; per layer W_self (GCN: W) row-major
     [Fin x Fout], then W_neigh (SAGE only), then b.
   * loss = (1/|S|) sum_{v in S} w_v (logsumexp(z_v) - z_v[y_v]); S empty -> loss 0 and a
@@ -170,12 +176,15 @@ def _gcn_backward(h, blk, w, saved, dz, need_dh, self_loops):
 
 
 def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
-                     gcn_self_loops=True, return_logits=False):
+                     gcn_self_loops=True, return_logits=False, relu_flip=None, near_kink=None):
     """Loss and flat parameter gradient of a k-layer model.
 
     ``blocks`` has one block per layer (input side first); pass the same block k times for
     full-graph mode.  ``x`` is [n_src of block 0, dims[0]]; ``labels``/``node_w`` are indexed by
     the last block's destination ids, and ``loss_nodes`` lists the destinations in the loss.
+    ``relu_flip``: iterable of (layer, row, col) whose ReLU derivative is inverted.
+    ``near_kink``: a guard g; the call then also returns the list of (layer, row, col) of
+    hidden pre-activations with |z| <= g * rms(z of that layer).
     """
     if arch not in ARCHS:
         raise ValueError("unknown arch")
@@ -214,7 +223,11 @@ def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
         if l == k - 1:
             dzl = dz
         else:
-            dzl = dh_next * (zs[l] > 0.0)
+            mask = zs[l] > 0.0
+            for (fl, fr, fc) in (relu_flip or ()):
+                if fl == l:
+                    mask[fr, fc] = not mask[fr, fc]
+            dzl = dh_next * mask
             if arch == "gcn_res" and dims[l] == dims[l + 1]:
                 skip = dh_next
         need_dh = l > 0
@@ -228,6 +241,14 @@ def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
         grads[l] = g
         dh_next = dh
     flat = pack_grads(grads)
+    out = (loss, flat)
     if return_logits:
-        return loss, flat, logits
-    return loss, flat
+        out = out + (logits,)
+    if near_kink is not None:
+        near = []
+        for l in range(k - 1):
+            rms = float(np.sqrt(np.mean(zs[l] ** 2))) if zs[l].size else 0.0
+            rr, cc = np.nonzero(np.abs(zs[l]) <= near_kink * rms)
+            near += [(l, int(r), int(c)) for r, c in zip(rr, cc)]
+        out = out + (near,)
+    return out

@@ -13,7 +13,7 @@ from . import coverage, gnn, sampling
 
 def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
                estimator: int = coverage.NONE, gcn_self_loops: bool = True,
-               minibatch: dict | None = None):
+               minibatch: dict | None = None, relu_flip=None, near_kink=None):
     """Returns (grad[P] float64, stats dict) for one partition.
 
     full-graph mode (``minibatch is None``): every local node is an input, the loss runs
@@ -21,6 +21,8 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
     mini-batch mode: ``minibatch = dict(seeds=int array of local ids, fanouts=(f_0..f_{k-1}),
     sampler_seed=int, batch_id=int)``; fanouts[l] belongs to layer l, layer 0 being the input
     side, so the seeds draw fanouts[k-1] neighbours.
+    ``relu_flip`` / ``near_kink`` are passed to ``gnn.forward_backward``; with ``near_kink`` the
+    stats dict gains the key "near_kink".
     """
     n = part["n"]
     k = len(dims) - 1
@@ -33,9 +35,12 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
             loss_nodes = np.arange(n, dtype=np.int64)
         else:
             loss_nodes = np.flatnonzero(np.asarray(train_mask) != 0).astype(np.int64)
-        loss, grad = gnn.forward_backward(arch, dims, theta, x, [blk] * k, labels, w_all,
-                                          loss_nodes, gcn_self_loops)
+        res = gnn.forward_backward(arch, dims, theta, x, [blk] * k, labels, w_all, loss_nodes,
+                                   gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink)
+        loss, grad = res[0], res[1]
         st = coverage.coverage_stats(dl, dg, loss_nodes, None)
+        if near_kink is not None:
+            st["near_kink"] = res[2]
         st["loss"] = loss
         st["nnz_used"] = int(part["nnz"])
         return grad, st
@@ -47,13 +52,16 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
                                                  minibatch["sampler_seed"], minibatch["batch_id"])
     xin = np.asarray(x, dtype=np.float64)[input_nodes]
     nseed = seeds.size
-    loss, grad = gnn.forward_backward(arch, dims, theta, xin, blocks, np.asarray(labels)[seeds],
-                                      w_all[seeds], np.arange(nseed, dtype=np.int64),
-                                      gcn_self_loops)
+    res = gnn.forward_backward(arch, dims, theta, xin, blocks, np.asarray(labels)[seeds],
+                               w_all[seeds], np.arange(nseed, dtype=np.int64),
+                               gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink)
+    loss, grad = res[0], res[1]
     last = blocks[-1]
     sampled = np.bincount(last["edst"], minlength=nseed)
     st = coverage.coverage_stats(np.asarray(dl)[seeds], np.asarray(dg)[seeds],
                                  np.arange(nseed, dtype=np.int64), sampled)
     st["loss"] = loss
+    if near_kink is not None:
+        st["near_kink"] = res[2]
     st["nnz_used"] = int(sum(b["esrc"].size for b in blocks))
     return grad, st

@@ -169,7 +169,8 @@ _hip = None
 def _hip_memcpy_d2h(dst: np.ndarray, src_ptr: int):
     global _hip
     if _hip is None:
-        _hip = C.CDLL("libamdhip64.so")
+        # the SONAME resolves to the HIP runtime torch already loaded (never a second copy)
+        _hip = C.CDLL("libamdhip64.so.7")
         _hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
         _hip.hipMemcpy.restype = C.c_int
     rc = _hip.hipMemcpy(dst.ctypes.data, src_ptr, dst.nbytes, 2)

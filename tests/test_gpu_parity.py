@@ -10,7 +10,7 @@ from oracle import coverage as ocov
 from oracle import gnn as ognn
 from oracle import graph as ograph
 from oracle import step as ostep
-from tests._cases import TOL_BF16, TOL_FP32, assert_grads_close, make_inputs, rel_err
+from tests._cases import TOL_BF16, TOL_FP32, assert_grads_close, assert_step_grads_close, make_inputs, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -225,8 +225,10 @@ def test_config1_gcn2_four_partitions_and_aggregate(g, est):
         g.grp_train_step(part, model, opts, x.to(DEV), y.to(DEV), None, theta.to(DEV), ws, grads[p],
                          stats[p * g.STATS_BYTES:(p + 1) * g.STATS_BYTES])
         torch.cuda.synchronize()
-        og, ost = ostep.train_step(op, "gcn", dims, theta.double().numpy(), x.double().numpy(), y.numpy(), estimator=est)
-        assert_grads_close(grads[p, :P].cpu().numpy(), og, "gcn", dims, TOL_FP32)
+        def oracle_fn(relu_flip=None, near_kink=None):
+            return ostep.train_step(op, "gcn", dims, theta.double().numpy(), x.double().numpy(), y.numpy(),
+                                    estimator=est, relu_flip=relu_flip, near_kink=near_kink)
+        og, ost = assert_step_grads_close(grads[p, :P].cpu().numpy(), oracle_fn, "gcn", dims, TOL_FP32)
         _check_stats(g.read_stats(stats)[p], ost, TOL_FP32)
         o_grads.append(og)
         o_stats.append(ost)
@@ -265,10 +267,11 @@ def test_train_step_rmat_matches_oracle(g, arch, dims, bf16, self_loops, masked)
     for est in (0, 1):
         grad, stats = _run_step(g, part, arch, dims, x.to(DEV), y.to(DEV), theta.to(DEV),
                                 None if mask is None else mask.to(DEV), est, bf16, self_loops)
-        og, ost = ostep.train_step(op, arch, dims, theta.double().numpy(), x.double().numpy(), y.numpy(),
-                                   train_mask=None if mask is None else mask.numpy(), estimator=est,
-                                   gcn_self_loops=self_loops)
-        assert_grads_close(grad.cpu().numpy(), og, arch, dims, min(tol, TOL_FP32))
+        def oracle_fn(relu_flip=None, near_kink=None, est=est):
+            return ostep.train_step(op, arch, dims, theta.double().numpy(), x.double().numpy(), y.numpy(),
+                                    train_mask=None if mask is None else mask.numpy(), estimator=est,
+                                    gcn_self_loops=self_loops, relu_flip=relu_flip, near_kink=near_kink)
+        og, ost = assert_step_grads_close(grad.cpu().numpy(), oracle_fn, arch, dims, min(tol, TOL_FP32))
         _check_stats(g.read_stats(stats)[0], ost, TOL_FP32)
 
 

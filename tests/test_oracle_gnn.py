@@ -212,3 +212,30 @@ def test_train_mask_selects_loss_nodes():
     loss, g2 = gnn.forward_backward("gcn", dims, theta, x, [blk], y, np.ones(n), np.array([2, 5, 6]))
     assert st["S"] == 3 and st["loss"] == loss
     np.testing.assert_array_equal(g, g2)
+
+
+def test_relu_kink_options_flip_exactly_one_derivative():
+    """near_kink lists hidden pre-activations close to 0; relu_flip inverts the derivative of
+    one element: the gradient changes by that element's contribution and nothing else."""
+    dims = [4, 5, 3]
+    s, d, n, part, x, y, theta = _setup("sage", dims, seed=3)
+    blk = gnn.block_from_csr(part["rowptr"], part["col"])
+    nodes = np.arange(n)
+    w = np.ones(n)
+    loss, g0, near = gnn.forward_backward("sage", dims, theta, x, [blk] * 2, y, w, nodes, near_kink=0.05)
+    params = gnn.unpack_params(theta, "sage", dims)
+    z0, _ = gnn._sage_forward(x, blk, *params[0])
+    rms = np.sqrt((z0 ** 2).mean())
+    want = sorted((0, int(r), int(c)) for r, c in zip(*np.nonzero(np.abs(z0) <= 0.05 * rms)))
+    assert sorted(near) == want and len(near) > 0
+    e = near[0]
+    loss1, g1 = gnn.forward_backward("sage", dims, theta, x, [blk] * 2, y, w, nodes, relu_flip=[e])
+    assert loss1 == loss and not np.allclose(g1, g0)
+    # flipping twice restores the gradient; flips of one layer add up
+    _, g2 = gnn.forward_backward("sage", dims, theta, x, [blk] * 2, y, w, nodes, relu_flip=[e, e])
+    np.testing.assert_array_equal(g2, g0)
+    if len(near) > 1:
+        f = near[1]
+        _, gf = gnn.forward_backward("sage", dims, theta, x, [blk] * 2, y, w, nodes, relu_flip=[f])
+        _, gef = gnn.forward_backward("sage", dims, theta, x, [blk] * 2, y, w, nodes, relu_flip=[e, f])
+        np.testing.assert_allclose(gef - g0, (g1 - g0) + (gf - g0), rtol=1e-9, atol=1e-15)
