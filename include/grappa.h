@@ -221,8 +221,10 @@ grp_status grp_gemm_tn(int64_t M, int32_t K, int32_t N, const void* A, int64_t l
 
 /* Per-kernel timing with HIP events on the launch stream.  While enabled, every kernel
  * the library launches is bracketed by two events.  grp_profile_report synchronises the
- * recorded events, writes one line "name launches total_ms\n" per kernel name into
- * buf (HOST, NUL-terminated, truncated to cap) and clears the records.                */
+ * recorded events, writes one line "name launches total_ms total_flops total_bytes\n"
+ * per kernel name into buf (HOST, NUL-terminated, truncated to cap) and clears the
+ * records.  flops/bytes are the algorithmic work of the launches (operand and result
+ * sizes, 2*M*N*K), not measured traffic.                                              */
 grp_status grp_profile_enable(int32_t on);
 grp_status grp_profile_report(char* buf, size_t cap);
 

@@ -245,8 +245,8 @@ def grp_profile_report() -> dict:
     _check(load().grp_profile_report(buf, len(buf)))
     out = {}
     for line in buf.value.decode().splitlines():
-        name, cnt, ms = line.split()
-        out[name] = (int(cnt), float(ms))
+        name, cnt, ms, flops, nbytes = line.split()
+        out[name] = dict(launches=int(cnt), ms=float(ms), flops=float(flops), bytes=float(nbytes))
     return out
 
 

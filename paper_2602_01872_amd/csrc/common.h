@@ -34,12 +34,16 @@ grp_status fail(grp_status code, const char* fmt, ...);
 
 // ---------------------------------------------------------------- profiling
 // Brackets a kernel launch with two events when profiling is enabled.
-void prof_begin(const char* name, hipStream_t st);
+// flops / bytes: the algorithmic work of the launch (what the operation must compute and
+// move, not what the kernel happens to touch); summed per kernel name in the report.
+void prof_begin(const char* name, hipStream_t st, double flops, double bytes);
 void prof_end(hipStream_t st);
 
 struct ProfScope {
     hipStream_t st;
-    ProfScope(const char* name, hipStream_t s) : st(s) { prof_begin(name, s); }
+    ProfScope(const char* name, hipStream_t s, double flops = 0.0, double bytes = 0.0) : st(s) {
+        prof_begin(name, s, flops, bytes);
+    }
     ~ProfScope() { prof_end(st); }
 };
 
@@ -79,6 +83,8 @@ static inline int64_t round_up(int64_t a, int64_t b) { return cdiv(a, b) * b; }
 struct SpmmArgs {
     const int64_t* ptr = nullptr;   // [n_rows+1]
     const int32_t* idx = nullptr;   // [nnz]
+    int64_t nnz = 0;                // only used for the profiler's byte count
+    int64_t n_src = 0;              // rows of X (0 = n_rows); profiler only
     int64_t n_rows = 0;
     int32_t F = 0;
     const void* X = nullptr;

@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
 grp_status launch_colsum_scaled(const float* A, int64_t M, int32_t N, int64_t lda, const float* rowmul, float* out,
                                 void* scratch, hipStream_t st) {
     const int64_t blocks = cdiv(M > 0 ? M : 1, COLSUM_ROWS);
-    ProfScope ps("colsum", st);
+    ProfScope ps("colsum", st, 0.0, 4.0 * M * N);
     hipLaunchKernelGGL(colsum_partial_kernel, dim3((unsigned)blocks), dim3(256), 0, st, A, M, N, lda, rowmul,
                        (float*)scratch);
     GRP_LAUNCH_CHECK();
@@ -290,7 +290,7 @@ grp_status launch_softmax_xent(int64_t n_rows, int32_t C, const float* Z, int64_
                                const int32_t* node_of_row, const uint8_t* mask, int32_t node_level,
                                const int32_t* d_local, const int64_t* d_global, const float* rowscale, float* dZ,
                                int64_t lddz, void* scratch, grp_step_stats* stats, hipStream_t st) {
-    ProfScope ps("softmax_xent", st);
+    ProfScope ps("softmax_xent", st, 0.0, 8.0 * n_rows * C);
     double* loss_part = (double*)((char*)scratch + (size_t)STATS_BLOCKS * sizeof(StatsPartial));
     int c_store = (int)round_up(C, 4);
     if (c_store > lddz) c_store = (int)lddz;
@@ -366,7 +366,7 @@ extern "C" grp_status grp_aggregate(const float* grads, int64_t ld_grads, const 
     int64_t blocks = cdiv((vec ? P / 4 : P) > 0 ? (vec ? P / 4 : P) : 1, 256);
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
-    ProfScope ps("aggregate", st);
+    ProfScope ps("aggregate", st, 2.0 * K * P, 4.0 * P * (K + 1.0));
     if (vec)
         hipLaunchKernelGGL((aggregate_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, st, grads, ld_grads, stats, K,
                            P, variant, update, c_out);

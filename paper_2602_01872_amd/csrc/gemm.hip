@@ -211,7 +211,10 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
     const bool veca = a.lda % 4 == 0 && a.lda >= round_up(a.K, 4) && (uintptr_t)a.A % (4 * elem) == 0;
     const bool vecb = a.ldb % 4 == 0 && a.ldb >= round_up(a.N, 4) && (uintptr_t)a.B % 16 == 0 &&
                       (a.K2 == 0 || (a.ldb2 % 4 == 0 && a.ldb2 >= round_up(a.N, 4) && (uintptr_t)a.B2 % 16 == 0));
-    ProfScope ps(a.a_bf16 ? "gemm_nn_bf16a" : "gemm_nn_f32", st);
+    const double nn_flops = 2.0 * a.M * a.N * ((double)a.K + a.K2);
+    const double nn_bytes = (double)a.M * a.K * elem + 4.0 * a.M * a.K2 + 4.0 * a.N * ((double)a.K + a.K2) +
+                            4.0 * a.M * a.N * (1.0 + (a.addend ? 1.0 : 0.0) + (a.mask ? 1.0 : 0.0));
+    ProfScope ps(a.a_bf16 ? "gemm_nn_bf16a" : "gemm_nn_f32", st, nn_flops, nn_bytes);
     if (a.a_bf16) {
         if (veca && vecb) nn_pick<__hip_bfloat16, true, true>(a, st);
         else nn_pick<__hip_bfloat16, false, false>(a, st);
@@ -381,7 +384,8 @@ grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st) {
     const int64_t out_ld = p.splits > 1 ? a.N : a.ldc;
     const int64_t stride = p.splits > 1 ? (int64_t)a.K * a.N : 0;
     {
-        ProfScope ps(a.a_bf16 ? "gemm_tn_bf16a" : "gemm_tn_f32", st);
+        ProfScope ps(a.a_bf16 ? "gemm_tn_bf16a" : "gemm_tn_f32", st, 2.0 * a.M * a.K * a.N,
+                     (double)a.M * a.K * elem + 4.0 * a.M * a.N + 4.0 * a.K * a.N);
         if (a.a_bf16) {
             if (veca && vecb) tn_pick<__hip_bfloat16, true, true>(a, p, out, out_ld, stride, st);
             else tn_pick<__hip_bfloat16, false, false>(a, p, out, out_ld, stride, st);
@@ -392,7 +396,7 @@ grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st) {
         GRP_LAUNCH_CHECK();
     }
     if (p.splits > 1) {
-        ProfScope ps("gemm_tn_reduce", st);
+        ProfScope ps("gemm_tn_reduce", st, 0.0, 4.0 * a.K * a.N * (p.splits + 1.0));
         const int64_t blocks = cdiv((int64_t)a.K * a.N, 256);
         hipLaunchKernelGGL(tn_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const float*)a.workspace,
                            p.splits, a.K, a.N, a.C, a.ldc);

@@ -31,15 +31,16 @@ grp_status fail(grp_status code, const char* fmt, ...) {
 struct ProfRec {
     const char* name;
     hipEvent_t a, b;
+    double flops, bytes;
 };
 static std::mutex g_prof_mu;
 static bool g_prof_on = false;
 static std::vector<ProfRec> g_prof;
 static thread_local hipEvent_t g_open_end = nullptr;
 
-void prof_begin(const char* name, hipStream_t st) {
+void prof_begin(const char* name, hipStream_t st, double flops, double bytes) {
     if (!g_prof_on) return;
-    ProfRec r{name, nullptr, nullptr};
+    ProfRec r{name, nullptr, nullptr, flops, bytes};
     if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
     (void)hipEventRecord(r.a, st);
     g_open_end = r.b;
@@ -70,7 +71,8 @@ extern "C" grp_status grp_profile_report(char* buf, size_t cap) {
         std::lock_guard<std::mutex> lk(grp::g_prof_mu);
         recs.swap(grp::g_prof);
     }
-    std::map<std::string, std::pair<long, double>> acc;
+    struct Acc { long n; double ms, flops, bytes; };
+    std::map<std::string, Acc> acc;
     std::vector<std::string> order;
     for (auto& r : recs) {
         float ms = 0.f;
@@ -78,19 +80,22 @@ extern "C" grp_status grp_profile_report(char* buf, size_t cap) {
             auto it = acc.find(r.name);
             if (it == acc.end()) {
                 order.push_back(r.name);
-                acc[r.name] = {1, ms};
+                acc[r.name] = Acc{1, ms, r.flops, r.bytes};
             } else {
-                it->second.first += 1;
-                it->second.second += ms;
+                it->second.n += 1;
+                it->second.ms += ms;
+                it->second.flops += r.flops;
+                it->second.bytes += r.bytes;
             }
         }
         (void)hipEventDestroy(r.a);
         (void)hipEventDestroy(r.b);
     }
     std::string out;
-    char line[256];
+    char line[320];
     for (auto& nm : order) {
-        snprintf(line, sizeof line, "%s %ld %.6f\n", nm.c_str(), acc[nm].first, acc[nm].second);
+        const Acc& a = acc[nm];
+        snprintf(line, sizeof line, "%s %ld %.6f %.6e %.6e\n", nm.c_str(), a.n, a.ms, a.flops, a.bytes);
         out += line;
     }
     if (out.size() + 1 > cap) out.resize(cap - 1);

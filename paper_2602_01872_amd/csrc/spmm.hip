@@ -196,7 +196,12 @@ grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
                         a.ldx % 4 == 0 && a.ldy % 4 == 0 &&
                         ((uintptr_t)a.X % (4 * elem)) == 0 && ((uintptr_t)a.Y % 16) == 0 &&
                         (!a.addend || (a.ld_add % 4 == 0 && a.ld_add >= fpad && ((uintptr_t)a.addend % 16) == 0));
-    ProfScope ps(a.x_bf16 ? "spmm_rows_bf16" : "spmm_rows_f32", st);
+    // compulsory traffic: the index stream, the row pointers, every source row once, every
+    // output row once (+ addend rows)
+    const int64_t n_src = a.n_src > 0 ? a.n_src : a.n_rows;
+    const double bytes = 4.0 * a.nnz + 8.0 * (a.n_rows + 1) + (double)elem * a.F * n_src +
+                         4.0 * a.F * a.n_rows * (a.addend ? 2.0 : 1.0) + (a.colscale ? 4.0 * n_src : 0.0);
+    ProfScope ps(a.x_bf16 ? "spmm_rows_bf16" : "spmm_rows_f32", st, 2.0 * a.nnz * a.F, bytes);
     if (vec_ok) {
         GRP_TRY(a.x_bf16 ? dispatch<__hip_bfloat16>(a, st) : dispatch<float>(a, st));
     } else {
@@ -227,6 +232,7 @@ extern "C" grp_status grp_spmm(const grp_partition_t* part, int32_t transposed, 
     a.ptr = transposed ? part->colptr : part->rowptr;
     a.idx = transposed ? part->row : part->col;
     a.n_rows = part->n;
+    a.nnz = part->nnz;
     a.F = F;
     a.X = X;
     a.ldx = ldx;

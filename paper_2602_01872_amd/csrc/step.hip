@@ -150,7 +150,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
         const int relu = l < k - 1;
         if (L.agg_first) {
             SpmmArgs s;
-            s.ptr = g->rowptr; s.idx = g->col; s.n_rows = n; s.F = fin; s.X = H; s.ldx = ldh; s.x_bf16 = h_bf16;
+            s.ptr = g->rowptr; s.idx = g->col; s.nnz = g->nnz; s.n_rows = n; s.F = fin; s.X = H; s.ldx = ldh; s.x_bf16 = h_bf16;
             s.scale = GRP_SCALE_MEAN; s.Y = L.M; s.ldy = ldp(fin);
             GRP_TRY(launch_spmm(s, st));
             GemmNNArgs a;
@@ -166,7 +166,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             a.B = L.Wp_s; a.bias = theta + L.off_b; a.C = L.H_out;
             GRP_TRY(launch_gemm_nn(a, st));
             SpmmArgs s;
-            s.ptr = g->rowptr; s.idx = g->col; s.n_rows = n; s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout);
+            s.ptr = g->rowptr; s.idx = g->col; s.nnz = g->nnz; s.n_rows = n; s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout);
             s.scale = GRP_SCALE_MEAN; s.addend = L.H_out; s.ld_add = ldp(fout); s.relu = relu; s.Y = L.H_out; s.ldy = ldp(fout);
             GRP_TRY(launch_spmm(s, st));
         }
@@ -201,7 +201,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
                 a.rowscale = p.inv_in; a.C = p.tmpA; a.ldc = ldp(fin); a.zero_pad_to = (int)ldp(fin);
                 GRP_TRY(launch_gemm_nn(a, st));
                 SpmmArgs s;        // P = A^T dM'
-                s.ptr = g->colptr; s.idx = g->row; s.n_rows = n; s.F = fin; s.X = p.tmpA; s.ldx = ldp(fin);
+                s.ptr = g->colptr; s.idx = g->row; s.nnz = g->nnz; s.n_rows = n; s.F = fin; s.X = p.tmpA; s.ldx = ldp(fin);
                 s.Y = p.tmpB; s.ldy = ldp(fin);
                 GRP_TRY(launch_spmm(s, st));
                 GemmNNArgs c;      // dZ_prev = mask * (dZ Ws^T + P)
@@ -212,7 +212,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             }
         } else {
             SpmmArgs s;            // dT = A^T (dZ / d_in)
-            s.ptr = g->colptr; s.idx = g->row; s.n_rows = n; s.F = fout; s.X = dZ; s.ldx = ldp(fout);
+            s.ptr = g->colptr; s.idx = g->row; s.nnz = g->nnz; s.n_rows = n; s.F = fout; s.X = dZ; s.ldx = ldp(fout);
             s.colscale = p.inv_in; s.Y = p.tmpA; s.ldy = ldp(fout);
             GRP_TRY(launch_spmm(s, st));
             t.B = p.tmpA; t.C = grad + L.off_wn;
@@ -258,7 +258,7 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
         a.rowscale = p.gs; a.C = p.tmpA; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
         GRP_TRY(launch_gemm_nn(a, st));
         SpmmArgs s;
-        s.ptr = g->rowptr; s.idx = g->col; s.n_rows = n; s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout);
+        s.ptr = g->rowptr; s.idx = g->col; s.nnz = g->nnz; s.n_rows = n; s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout);
         s.scale = GRP_SCALE_RSQRT; s.self_term = sl; s.bias = theta + L.off_b; s.relu = l < k - 1;
         s.Y = L.H_out; s.ldy = ldp(fout);
         GRP_TRY(launch_spmm(s, st));
@@ -281,7 +281,7 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
         const int in_bf16 = l == 0 && m->feat_dtype == GRP_DTYPE_BF16;
         GRP_TRY(launch_colsum_scaled(dZ, n, fout, ldp(fout), p.grinv, grad + L.off_b, p.colsum_ws, st));
         SpmmArgs s;
-        s.ptr = g->colptr; s.idx = g->row; s.n_rows = n; s.F = fout; s.X = dZ; s.ldx = ldp(fout);
+        s.ptr = g->colptr; s.idx = g->row; s.nnz = g->nnz; s.n_rows = n; s.F = fout; s.X = dZ; s.ldx = ldp(fout);
         s.scale = GRP_SCALE_RSQRT; s.self_term = sl; s.Y = p.tmpA; s.ldy = ldp(fout);
         GRP_TRY(launch_spmm(s, st));
         GemmTNArgs t;
