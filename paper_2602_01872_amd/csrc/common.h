@@ -59,7 +59,24 @@ struct ProfScope {
 // ---------------------------------------------------------------- partition handle
 }  // namespace grp
 
+namespace grp {
+// Rows longer than SPMM_LONG_ROW edges are cut into chunks of at most SPMM_CHUNK edges
+// (device arrays, built once with the partition; see spmm.hip).
+constexpr int SPMM_LONG_ROW = 512;
+constexpr int SPMM_CHUNK = 2048;
+struct LongRows {
+    int32_t n_long = 0, n_chunks = 0;
+    int32_t* long_row = nullptr;     // [n_long]    row index
+    int32_t* long_first = nullptr;   // [n_long+1]  first chunk of each long row
+    int64_t* chunk_begin = nullptr;  // [n_chunks]  edge range of the chunk
+    int64_t* chunk_end = nullptr;    // [n_chunks]
+};
+}  // namespace grp
+
 struct grp_partition_s {
+    grp::LongRows csr_long, csc_long;
+    float* spmm_scratch = nullptr;   // partial sums of the standalone grp_spmm call
+    size_t spmm_scratch_bytes = 0;
     int64_t n = 0, nnz = 0;
     int64_t* l2g = nullptr;
     int64_t* rowptr = nullptr;
@@ -99,8 +116,11 @@ struct SpmmArgs {
     int32_t relu = 0;
     float* Y = nullptr;
     int64_t ldy = 0;
+    const LongRows* long_rows = nullptr;  // null = no row is split
+    float* partials = nullptr;            // [n_chunks x round_up(F,4)] scratch when rows are split
 };
 grp_status launch_spmm(const SpmmArgs& a, hipStream_t st);
+size_t spmm_partials_bytes(const LongRows* lr, int32_t F);
 
 // C[M x N] = epilogue(A[M x K] B[K x N] + A2[M x K2] B2[K2 x N])
 // epilogue: (+ bias[N]) (+ addend[M x N]) (* rowscale[M]) (ReLU) (* (mask[M x N] > 0))

@@ -79,7 +79,7 @@ __device__ __forceinline__ T block_sum(T v, T* sm /*[4]*/) {
 }
 
 // ------------------------------------------------------------------ column sums
-constexpr int COLSUM_ROWS = 1024;    // rows per block
+constexpr int COLSUM_ROWS = 256;     // rows per block
 
 size_t colsum_workspace_bytes(int64_t M, int32_t N) { return (size_t)cdiv(M > 0 ? M : 1, COLSUM_ROWS) * N * sizeof(float); }
 
@@ -96,23 +96,68 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const float* __rest
     }
 }
 
+// out[c] = sum_b part[b][c]: 32 columns per workgroup, 8 lanes per column take the blocks
+// b = j, j + 8, ... and are added in lane order.
 __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, int64_t blocks, int N,
                                                            float* __restrict__ out) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= N) return;
+    __shared__ float red[8][32];
+    const int cl = threadIdx.x & 31, j = threadIdx.x >> 5;
+    const int c = blockIdx.x * 32 + cl;
     float s = 0.f;
-    for (int64_t b = 0; b < blocks; ++b) s += part[b * N + c];
-    out[c] = s;
+    if (c < N)
+        for (int64_t b = j; b < blocks; b += 8) s += part[b * N + c];
+    red[j][cl] = s;
+    __syncthreads();
+    if (j == 0 && c < N) {
+        float t = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) t += red[q][cl];
+        out[c] = t;
+    }
+}
+
+// Same partial sums with 16-byte loads: thread t owns the float4 column t % C4 and the rows
+// t / C4, t / C4 + R, ... of the block's slab (R = 256 / C4 row lanes); the row lanes are then
+// added through LDS in lane order.  Needs N <= 1024, lda % 4 == 0 and a 16-byte aligned A.
+__global__ __launch_bounds__(256) void colsum_partial_vec_kernel(const float* __restrict__ A, int64_t M, int N,
+                                                                 int64_t lda, const float* __restrict__ rowmul,
+                                                                 float* __restrict__ part) {
+    __shared__ float red[256 * 4];
+    const int C4 = (N + 3) / 4;
+    const int R = 256 / C4;
+    const int c4 = threadIdx.x % C4, r0 = threadIdx.x / C4;
+    const int64_t m0 = (int64_t)blockIdx.x * COLSUM_ROWS;
+    const int64_t m1 = m0 + COLSUM_ROWS < M ? m0 + COLSUM_ROWS : M;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (r0 < R) {
+        for (int64_t m = m0 + r0; m < m1; m += R) {
+            const float4 v = *reinterpret_cast<const float4*>(A + m * lda + 4 * c4);
+            const float w = rowmul ? rowmul[m] : 1.f;
+            s.x = fmaf(v.x, w, s.x); s.y = fmaf(v.y, w, s.y); s.z = fmaf(v.z, w, s.z); s.w = fmaf(v.w, w, s.w);
+        }
+    }
+    *reinterpret_cast<float4*>(&red[threadIdx.x * 4]) = s;
+    __syncthreads();
+    for (int c = threadIdx.x; c < N; c += 256) {
+        float acc = 0.f;
+        for (int r = 0; r < R; ++r) acc += red[(r * C4 + c / 4) * 4 + (c & 3)];
+        part[(int64_t)blockIdx.x * N + c] = acc;
+    }
 }
 
 grp_status launch_colsum_scaled(const float* A, int64_t M, int32_t N, int64_t lda, const float* rowmul, float* out,
                                 void* scratch, hipStream_t st) {
     const int64_t blocks = cdiv(M > 0 ? M : 1, COLSUM_ROWS);
     ProfScope ps("colsum", st, 0.0, 4.0 * M * N);
-    hipLaunchKernelGGL(colsum_partial_kernel, dim3((unsigned)blocks), dim3(256), 0, st, A, M, N, lda, rowmul,
-                       (float*)scratch);
+    const bool vec = N <= 1024 && lda % 4 == 0 && lda >= round_up(N, 4) && (uintptr_t)A % 16 == 0;
+    if (vec)
+        hipLaunchKernelGGL(colsum_partial_vec_kernel, dim3((unsigned)blocks), dim3(256), 0, st, A, M, N, lda, rowmul,
+                           (float*)scratch);
+    else
+        hipLaunchKernelGGL(colsum_partial_kernel, dim3((unsigned)blocks), dim3(256), 0, st, A, M, N, lda, rowmul,
+                           (float*)scratch);
     GRP_LAUNCH_CHECK();
-    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, (const float*)scratch,
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)cdiv(N, 32)), dim3(256), 0, st, (const float*)scratch,
                        blocks, N, out);
     GRP_LAUNCH_CHECK();
     return GRP_OK;

@@ -13,8 +13,11 @@
 // 64-lane wavefront: lane l supplies A[i = l%32][k = l/32] and B[k = l/32][j = l%32]; of
 // the 16 accumulator registers, register r of lane l holds D[8*(r/4) + 4*(l/32) + r%4][l%32].
 // Both operands are staged in LDS k-major (the 32 lanes of a half-wave read 32 consecutive
-// floats: no bank conflicts); the next k-tile is fetched from HBM into registers while the
-// current one is multiplied.
+// floats: no bank conflicts).  The next k-tile is requested from HBM into raw registers
+// before the current one is multiplied and is only touched (converted, masked, written to
+// LDS) after the multiply, so the loads overlap the matrix instructions; addresses are
+// clamped into the operand instead of branching, and out-of-range elements are zeroed when
+// they are written to LDS.
 #include "common.h"
 
 namespace grp {
@@ -22,75 +25,105 @@ namespace grp {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 32;      // k-tile depth
+constexpr int NXCD = 8;     // L2 domains; consecutive workgroup ids go round them
 
 template <typename T> __device__ __forceinline__ float to_f(T v);
 template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f<__hip_bfloat16>(__hip_bfloat16 v) { return __bfloat162float(v); }
 
-// Four consecutive elements row[k..k+3] as floats; elements at k+q >= K read as zero.
-template <typename T, bool VEC>
-__device__ __forceinline__ void load4(const T* __restrict__ row, int k, int K, float o[4]) {
-    o[0] = o[1] = o[2] = o[3] = 0.f;
-    if (k >= K) return;
-    if constexpr (VEC) {
-        if constexpr (sizeof(T) == 4) {
-            const float4 v = *reinterpret_cast<const float4*>(row + k);
-            o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
-        } else {
-            const uint2 r = *reinterpret_cast<const uint2*>(row + k);
-            o[0] = __uint_as_float(r.x << 16);
-            o[1] = __uint_as_float(r.x & 0xFFFF0000u);
-            o[2] = __uint_as_float(r.y << 16);
-            o[3] = __uint_as_float(r.y & 0xFFFF0000u);
-        }
-#pragma unroll
-        for (int q = 1; q < 4; ++q)
-            if (k + q >= K) o[q] = 0.f;
+// Four consecutive elements as raw bits (fp32: 16 bytes, bf16: 8 bytes in .x/.y).
+template <typename T>
+__device__ __forceinline__ uint4 ldg_raw4(const T* __restrict__ p) {
+    if constexpr (sizeof(T) == 4) {
+        return *reinterpret_cast<const uint4*>(p);
     } else {
+        const uint2 r = *reinterpret_cast<const uint2*>(p);
+        return make_uint4(r.x, r.y, 0u, 0u);
+    }
+}
+__device__ __forceinline__ void unpack4(const uint4& r, bool bf16, float o[4]) {
+    if (bf16) {
+        o[0] = __uint_as_float(r.x << 16);
+        o[1] = __uint_as_float(r.x & 0xFFFF0000u);
+        o[2] = __uint_as_float(r.y << 16);
+        o[3] = __uint_as_float(r.y & 0xFFFF0000u);
+    } else {
+        o[0] = __uint_as_float(r.x); o[1] = __uint_as_float(r.y);
+        o[2] = __uint_as_float(r.z); o[3] = __uint_as_float(r.w);
+    }
+}
+
+// Slow, always-safe element loads for operands whose pitch or base is not 16-byte friendly.
+template <typename T>
+__device__ __forceinline__ uint4 ldg_safe4(const T* __restrict__ row, bool row_ok, int k, int K) {
+    float o[4] = {0.f, 0.f, 0.f, 0.f};
+    if (row_ok) {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             if (k + q < K) o[q] = to_f<T>(row[k + q]);
     }
+    return make_uint4(__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3]));
 }
 
-// One BK-deep step of the wavefront's TM x TN block from k-major LDS tiles.
-template <int TM, int TN, int PA, int PB>
+__device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
+__device__ __forceinline__ int64_t lmin(int64_t a, int64_t b) { return a < b ? a : b; }
+
+// One BKT-deep step of the wavefront's TM x TN block from k-major LDS tiles.  The operands of
+// the next k-pair are read from LDS before the matrix instructions of the current one are
+// issued, so the LDS latency hides behind them.
+template <int TM, int TN, int PA, int PB, int BKT>
 __device__ __forceinline__ void mma_step(const float* __restrict__ As, const float* __restrict__ Bs, int a_off,
                                          int b_off, floatx16 (&acc)[TM][TN]) {
     const int lane = threadIdx.x & 63;
     const int li = lane & 31, lk = lane >> 5;
+    const float* ap = As + lk * PA + a_off + li;
+    const float* bp = Bs + lk * PB + b_off + li;
+    float a[2][TM], b[2][TN];
 #pragma unroll
-    for (int k = 0; k < BK; k += 2) {
-        float a[TM], b[TN];
+    for (int i = 0; i < TM; ++i) a[0][i] = ap[32 * i];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) a[i] = As[(k + lk) * PA + a_off + 32 * i + li];
+    for (int j = 0; j < TN; ++j) b[0][j] = bp[32 * j];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = Bs[(k + lk) * PB + b_off + 32 * j + li];
+    for (int k = 0; k < BKT; k += 2) {
+        const int cur = (k >> 1) & 1, nxt = cur ^ 1;
+        if (k + 2 < BKT) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[nxt][i] = ap[(k + 2) * PA + 32 * i];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[nxt][j] = bp[(k + 2) * PB + 32 * j];
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
     }
 }
 
 // ------------------------------------------------------------------------------- NN
-template <typename AT, bool VECA, bool VECB, int WM, int WN, int TM, int TN>
+template <typename AT, bool VEC, int WM, int WN, int TM, int TN, int BK, int NBUF>
 __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    constexpr int PA = BM + 4, PB = BN + 4;
-    constexpr int A_REPS = BM * BK / 4 / 256;        // float4 loads per thread for the A tile
+    constexpr int PA = BM + 2, PB = BN + 4;          // PA = 2 mod 8 spreads the transposing writes
+    constexpr int A_REPS = BM * BK / 4 / 256;        // 4-element loads per thread for the A tile
     constexpr int B_REPS = (BN * BK / 4 + 255) / 256;
-    __shared__ float As[BK * PA];
-    __shared__ float Bs[BK * PB];
+    constexpr bool A_BF16 = sizeof(AT) == 2;
+    static_assert(BM * BK / 4 % 256 == 0, "A tile must fill the workgroup");
+    __shared__ float As_[NBUF][BK * PA];
+    __shared__ __attribute__((aligned(16))) float Bs_[NBUF][BK * PB];
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int wm = wave / WN, wn = wave % WN;
     const int n_store = g.zero_pad_to > g.N ? g.zero_pad_to : g.N;
     const int n_tiles = (n_store + BN - 1) / BN;
-    const int64_t m0 = (int64_t)(blockIdx.x / n_tiles) * BM;
-    const int n0 = (blockIdx.x % n_tiles) * BN;
+    // Workgroup ids go round the NXCD L2 domains; the column tiles of one row slab get ids
+    // that differ by NXCD, so they run on the same domain and the slab's second read hits L2.
+    const int64_t hq = blockIdx.x / NXCD;
+    const int64_t slab = (hq / n_tiles) * NXCD + blockIdx.x % NXCD;
+    const int64_t m0 = slab * BM;
+    const int n0 = (int)(hq % n_tiles) * BN;
+    if (m0 >= g.M) return;
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -103,63 +136,90 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
     const int nk1 = (g.K + BK - 1) / BK;
     const int nk2 = (g.K2 + BK - 1) / BK;
     const int nk = nk1 + nk2;
+    const int npad = (g.N + 3) & ~3;
 
-    float ra[A_REPS][4], rb[B_REPS][4];
+    uint4 ra[A_REPS], rb[B_REPS];
 
     auto fetch = [&](int kt) {
         const bool second = kt >= nk1;
         const int k0 = (second ? kt - nk1 : kt) * BK;
         const int Kc = second ? g.K2 : g.K;
-#pragma unroll
-        for (int r = 0; r < A_REPS; ++r) {
-            const int f = tid + 256 * r;                 // float4 slot in the BM x BK tile
-            const int m = f / (BK / 4), kq = f % (BK / 4);
-            const int64_t gm = m0 + m;
-            if (gm < g.M) {
-                if (second) load4<float, true>(g.A2 + gm * g.lda2, k0 + 4 * kq, Kc, ra[r]);
-                else load4<AT, VECA>((const AT*)g.A + gm * g.lda, k0 + 4 * kq, Kc, ra[r]);
-            } else {
-                ra[r][0] = ra[r][1] = ra[r][2] = ra[r][3] = 0.f;
-            }
-        }
+        const int kpad = (Kc + 3) & ~3;
         const float* Bp = second ? g.B2 : g.B;
         const int64_t ldb = second ? g.ldb2 : g.ldb;
 #pragma unroll
+        for (int r = 0; r < A_REPS; ++r) {
+            const int f = tid + 256 * r;                 // 4-element slot in the BM x BK tile
+            const int m = f / (BK / 4), kq = f % (BK / 4);
+            if constexpr (VEC) {
+                const int64_t gm = lmin(m0 + m, g.M - 1);
+                const int kk = imin(k0 + 4 * kq, kpad - 4);
+                ra[r] = second ? ldg_raw4<float>(g.A2 + gm * g.lda2 + kk) : ldg_raw4<AT>((const AT*)g.A + gm * g.lda + kk);
+            } else {
+                const int64_t gm = m0 + m;
+                const bool ok = gm < g.M;
+                const int64_t gmc = ok ? gm : 0;
+                ra[r] = second ? ldg_safe4<float>(g.A2 + gmc * g.lda2, ok, k0 + 4 * kq, Kc)
+                               : ldg_safe4<AT>((const AT*)g.A + gmc * g.lda, ok, k0 + 4 * kq, Kc);
+            }
+        }
+#pragma unroll
         for (int r = 0; r < B_REPS; ++r) {
             const int f = tid + 256 * r;
             const int k = f / (BN / 4), nq = f % (BN / 4);
-            rb[r][0] = rb[r][1] = rb[r][2] = rb[r][3] = 0.f;
-            if (f < BN * BK / 4 && k0 + k < Kc) load4<float, VECB>(Bp + (int64_t)(k0 + k) * ldb, n0 + 4 * nq, g.N, rb[r]);
+            if (BN * BK / 4 % 256 != 0 && f >= BN * BK / 4) { rb[r] = make_uint4(0u, 0u, 0u, 0u); continue; }
+            if constexpr (VEC) {
+                const int kb = imin(k0 + k, Kc - 1);
+                const int nc = imin(n0 + 4 * nq, npad - 4);
+                rb[r] = ldg_raw4<float>(Bp + (int64_t)kb * ldb + nc);
+            } else {
+                const bool ok = k0 + k < Kc;
+                rb[r] = ldg_safe4<float>(Bp + (int64_t)(ok ? k0 + k : 0) * ldb, ok, n0 + 4 * nq, g.N);
+            }
         }
     };
-    auto stage = [&]() {
+    auto stage = [&](int kt) {
+        const bool second = kt >= nk1;
+        const int k0 = (second ? kt - nk1 : kt) * BK;
+        const int Kc = second ? g.K2 : g.K;
+        float* As = As_[NBUF == 1 ? 0 : (kt & 1)];
+        float* Bs = Bs_[NBUF == 1 ? 0 : (kt & 1)];
 #pragma unroll
         for (int r = 0; r < A_REPS; ++r) {
             const int f = tid + 256 * r;
             const int m = f / (BK / 4), kq = f % (BK / 4);
+            float v[4];
+            unpack4(ra[r], VEC && A_BF16 && !second, v);
+            const bool row_ok = m0 + m < g.M;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) As[(4 * kq + q) * PA + m] = ra[r][q];
+            for (int q = 0; q < 4; ++q)
+                As[(4 * kq + q) * PA + m] = (!VEC || (row_ok && k0 + 4 * kq + q < Kc)) ? v[q] : 0.f;
         }
 #pragma unroll
         for (int r = 0; r < B_REPS; ++r) {
             const int f = tid + 256 * r;
             const int k = f / (BN / 4), nq = f % (BN / 4);
-            if (f < BN * BK / 4)
-                *reinterpret_cast<float4*>(&Bs[k * PB + 4 * nq]) = make_float4(rb[r][0], rb[r][1], rb[r][2], rb[r][3]);
+            if (BN * BK / 4 % 256 != 0 && f >= BN * BK / 4) continue;
+            float v[4];
+            unpack4(rb[r], false, v);
+            const bool k_ok = k0 + k < Kc;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (VEC && !(k_ok && n0 + 4 * nq + q < g.N)) v[q] = 0.f;
+            *reinterpret_cast<float4*>(&Bs[k * PB + 4 * nq]) = make_float4(v[0], v[1], v[2], v[3]);
         }
     };
 
     fetch(0);
-    stage();
+    stage(0);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         if (kt + 1 < nk) fetch(kt + 1);
-        mma_step<TM, TN, PA, PB>(As, Bs, wm * TM * 32, wn * TN * 32, acc);
+        mma_step<TM, TN, PA, PB, BK>(As_[NBUF == 1 ? 0 : (kt & 1)], Bs_[NBUF == 1 ? 0 : (kt & 1)], wm * TM * 32,
+                                     wn * TN * 32, acc);
+        if (NBUF == 1) __syncthreads();
+        if (kt + 1 < nk) stage(kt + 1);
         __syncthreads();
-        if (kt + 1 < nk) {
-            stage();
-            __syncthreads();
-        }
     }
 
     const int li = lane & 31, lk = lane >> 5;
@@ -187,25 +247,29 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
         }
 }
 
-template <typename AT, bool VECA, bool VECB>
+// Tile choice (measured on MI355X at M = 3e5): 128 x 128 output tiles at three workgroups per
+// CU beat 128 x 256 at one; a 32-deep single-buffered k-tile is best for long reductions, a
+// 16-deep double-buffered one wastes less on short or ragged K.
+template <typename AT, bool VEC>
 static void nn_pick(const GemmNNArgs& a, hipStream_t st) {
     const int n_eff = a.zero_pad_to > a.N ? a.zero_pad_to : a.N;
+    const bool short_k = a.K <= 128 || (a.K2 > 0 && a.K2 <= 128);
+    const int64_t slabs = round_up(cdiv(a.M, 128), NXCD);
     if (n_eff > 64) {
-        const int64_t blocks = cdiv(a.M, 128) * cdiv(n_eff, 128);
-        hipLaunchKernelGGL((gemm_nn_kernel<AT, VECA, VECB, 2, 2, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+        const unsigned blocks = (unsigned)(slabs * cdiv(n_eff, 128));
+        if (short_k) hipLaunchKernelGGL((gemm_nn_kernel<AT, VEC, 2, 2, 2, 2, 16, 2>), dim3(blocks), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((gemm_nn_kernel<AT, VEC, 2, 2, 2, 2, 32, 1>), dim3(blocks), dim3(256), 0, st, a);
     } else if (n_eff > 32) {
-        const int64_t blocks = cdiv(a.M, 128) * cdiv(n_eff, 64);
-        hipLaunchKernelGGL((gemm_nn_kernel<AT, VECA, VECB, 4, 1, 1, 2>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+        hipLaunchKernelGGL((gemm_nn_kernel<AT, VEC, 4, 1, 1, 2, 32, 1>), dim3((unsigned)slabs), dim3(256), 0, st, a);
     } else {
-        const int64_t blocks = cdiv(a.M, 128) * cdiv(n_eff, 32);
-        hipLaunchKernelGGL((gemm_nn_kernel<AT, VECA, VECB, 4, 1, 1, 1>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+        hipLaunchKernelGGL((gemm_nn_kernel<AT, VEC, 4, 1, 1, 1, 32, 1>), dim3((unsigned)slabs), dim3(256), 0, st, a);
     }
 }
 
 grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
     if (a.M == 0 || a.N == 0) return GRP_OK;
     if (a.M < 0 || a.N < 0 || a.K <= 0 || !a.A || !a.B || !a.C) return fail(GRP_EINVAL, "gemm_nn: bad arguments");
-    if (a.K2 > 0 && (!a.A2 || !a.B2 || a.lda2 % 4 != 0 || (uintptr_t)a.A2 % 16 != 0))
+    if (a.K2 > 0 && (!a.A2 || !a.B2 || a.lda2 % 4 != 0 || a.lda2 < round_up(a.K2, 4) || (uintptr_t)a.A2 % 16 != 0))
         return fail(GRP_EINVAL, "gemm_nn: second operand must be 16-byte aligned with a pitch multiple of 4");
     const int elem = a.a_bf16 ? 2 : 4;
     const bool veca = a.lda % 4 == 0 && a.lda >= round_up(a.K, 4) && (uintptr_t)a.A % (4 * elem) == 0;
@@ -216,19 +280,20 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
                             4.0 * a.M * a.N * (1.0 + (a.addend ? 1.0 : 0.0) + (a.mask ? 1.0 : 0.0));
     ProfScope ps(a.a_bf16 ? "gemm_nn_bf16a" : "gemm_nn_f32", st, nn_flops, nn_bytes);
     if (a.a_bf16) {
-        if (veca && vecb) nn_pick<__hip_bfloat16, true, true>(a, st);
-        else nn_pick<__hip_bfloat16, false, false>(a, st);
+        if (veca && vecb) nn_pick<__hip_bfloat16, true>(a, st);
+        else nn_pick<__hip_bfloat16, false>(a, st);
     } else {
-        if (veca && vecb) nn_pick<float, true, true>(a, st);
-        else nn_pick<float, false, false>(a, st);
+        if (veca && vecb) nn_pick<float, true>(a, st);
+        else nn_pick<float, false>(a, st);
     }
     GRP_LAUNCH_CHECK();
     return GRP_OK;
 }
 
 // ------------------------------------------------------------------------------- TN
-constexpr int TN_ROWS_PER_SPLIT_MIN = 2048;   // node rows per split (multiple of BK)
+constexpr int TN_ROWS_PER_SPLIT_MIN = 512;    // node rows per split (multiple of BK)
 constexpr int TN_MAX_SPLITS = 256;
+constexpr int TN_TARGET_WGS = 512;            // 256 CUs x 2 resident workgroups: one full round
 
 struct TnPlan {
     int tiles_k, tiles_n, splits;
@@ -242,7 +307,8 @@ static TnPlan tn_plan(int64_t M, int K, int N) {
     p.bn_tile = N > 64 ? 128 : (N > 32 ? 64 : 32);
     p.tiles_k = (int)cdiv(K, p.bk_tile);
     p.tiles_n = (int)cdiv(N, p.bn_tile);
-    int64_t s = cdiv(M, TN_ROWS_PER_SPLIT_MIN);
+    int64_t s = TN_TARGET_WGS / (p.tiles_k * p.tiles_n);
+    if (s > cdiv(M, TN_ROWS_PER_SPLIT_MIN)) s = cdiv(M, TN_ROWS_PER_SPLIT_MIN);
     if (s > TN_MAX_SPLITS) s = TN_MAX_SPLITS;
     if (s < 1) s = 1;
     p.chunk = round_up(cdiv(M, s), BK);
@@ -257,23 +323,33 @@ size_t gemm_tn_workspace_bytes(int64_t M, int32_t K, int32_t N) {
     return p.splits > 1 ? (size_t)p.splits * K * N * sizeof(float) : 0;
 }
 
-template <typename AT, bool VECA, bool VECB, int WM, int WN, int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_n, int64_t chunk, float* __restrict__ out,
-                                                      int64_t out_ld, int64_t out_split_stride) {
+// Grid: x = NXCD * tiles * ceil(splits / NXCD).  Workgroup ids are mapped so that the output
+// tiles of one slice of the node dimension run on the same L2 domain (they read the same rows).
+template <typename AT, bool VEC, int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k, int tiles_n, int splits, int64_t chunk,
+                                                      float* __restrict__ out, int64_t out_ld, int64_t out_split_stride) {
     constexpr int BKA = WM * TM * 32, BN = WN * TN * 32;   // output tile: BKA (rows of C) x BN
     constexpr int PA = BKA + 4, PB = BN + 4;
     constexpr int A_REPS = BKA * BK / 4 / 256;
     constexpr int B_REPS = (BN * BK / 4 + 255) / 256;
-    __shared__ float As[BK * PA];
-    __shared__ float Bs[BK * PB];
+    constexpr bool A_BF16 = sizeof(AT) == 2;
+    __shared__ __attribute__((aligned(16))) float As[BK * PA];
+    __shared__ __attribute__((aligned(16))) float Bs[BK * PB];
+
+    const int tiles = tiles_k * tiles_n;
+    const int hq = blockIdx.x / NXCD;
+    const int tile = hq % tiles;
+    const int split = (hq / tiles) * NXCD + blockIdx.x % NXCD;
+    if (split >= splits) return;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int wm = wave / WN, wn = wave % WN;
-    const int ka0 = (blockIdx.x / tiles_n) * BKA;
-    const int n0 = (blockIdx.x % tiles_n) * BN;
-    const int64_t m_begin = (int64_t)blockIdx.y * chunk;
+    const int ka0 = (tile / tiles_n) * BKA;
+    const int n0 = (tile % tiles_n) * BN;
+    const int64_t m_begin = (int64_t)split * chunk;
     const int64_t m_end = m_begin + chunk < g.M ? m_begin + chunk : g.M;
+    const int kpad = (g.K + 3) & ~3, npad = (g.N + 3) & ~3;
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -283,59 +359,80 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_n,
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    float ra[A_REPS][4], rb[B_REPS][4];
+    uint4 ra[A_REPS], rb[B_REPS];
     auto fetch = [&](int64_t mt) {
 #pragma unroll
         for (int r = 0; r < A_REPS; ++r) {
             const int f = tid + 256 * r;
             const int m = f / (BKA / 4), cq = f % (BKA / 4);
-            const int64_t gm = mt + m;
-            ra[r][0] = ra[r][1] = ra[r][2] = ra[r][3] = 0.f;
-            if (gm < m_end) load4<AT, VECA>((const AT*)g.A + gm * g.lda, ka0 + 4 * cq, g.K, ra[r]);
+            if constexpr (VEC) {
+                const int64_t gm = lmin(mt + m, g.M - 1);
+                ra[r] = ldg_raw4<AT>((const AT*)g.A + gm * g.lda + imin(ka0 + 4 * cq, kpad - 4));
+            } else {
+                const bool ok = mt + m < m_end;
+                ra[r] = ldg_safe4<AT>((const AT*)g.A + (ok ? mt + m : 0) * g.lda, ok, ka0 + 4 * cq, g.K);
+            }
         }
 #pragma unroll
         for (int r = 0; r < B_REPS; ++r) {
             const int f = tid + 256 * r;
             const int m = f / (BN / 4), cq = f % (BN / 4);
-            const int64_t gm = mt + m;
-            rb[r][0] = rb[r][1] = rb[r][2] = rb[r][3] = 0.f;
-            if (f < BN * BK / 4 && gm < m_end) load4<float, VECB>(g.B + gm * g.ldb, n0 + 4 * cq, g.N, rb[r]);
+            if (BN * BK / 4 % 256 != 0 && f >= BN * BK / 4) { rb[r] = make_uint4(0u, 0u, 0u, 0u); continue; }
+            if constexpr (VEC) {
+                const int64_t gm = lmin(mt + m, g.M - 1);
+                rb[r] = ldg_raw4<float>(g.B + gm * g.ldb + imin(n0 + 4 * cq, npad - 4));
+            } else {
+                const bool ok = mt + m < m_end;
+                rb[r] = ldg_safe4<float>(g.B + (ok ? mt + m : 0) * g.ldb, ok, n0 + 4 * cq, g.N);
+            }
         }
     };
-    auto stage = [&]() {
+    auto stage = [&](int64_t mt) {
 #pragma unroll
         for (int r = 0; r < A_REPS; ++r) {
             const int f = tid + 256 * r;
             const int m = f / (BKA / 4), cq = f % (BKA / 4);
-            *reinterpret_cast<float4*>(&As[m * PA + 4 * cq]) = make_float4(ra[r][0], ra[r][1], ra[r][2], ra[r][3]);
+            float v[4];
+            unpack4(ra[r], VEC && A_BF16, v);
+            const bool row_ok = mt + m < m_end;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (VEC && !(row_ok && ka0 + 4 * cq + q < g.K)) v[q] = 0.f;
+            *reinterpret_cast<float4*>(&As[m * PA + 4 * cq]) = make_float4(v[0], v[1], v[2], v[3]);
         }
 #pragma unroll
         for (int r = 0; r < B_REPS; ++r) {
             const int f = tid + 256 * r;
             const int m = f / (BN / 4), cq = f % (BN / 4);
-            if (f < BN * BK / 4)
-                *reinterpret_cast<float4*>(&Bs[m * PB + 4 * cq]) = make_float4(rb[r][0], rb[r][1], rb[r][2], rb[r][3]);
+            if (BN * BK / 4 % 256 != 0 && f >= BN * BK / 4) continue;
+            float v[4];
+            unpack4(rb[r], false, v);
+            const bool row_ok = mt + m < m_end;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (VEC && !(row_ok && n0 + 4 * cq + q < g.N)) v[q] = 0.f;
+            *reinterpret_cast<float4*>(&Bs[m * PB + 4 * cq]) = make_float4(v[0], v[1], v[2], v[3]);
         }
     };
 
     if (m_begin < m_end) {
         fetch(m_begin);
-        stage();
+        stage(m_begin);
         __syncthreads();
         for (int64_t mt = m_begin; mt < m_end; mt += BK) {
             const bool more = mt + BK < m_end;
             if (more) fetch(mt + BK);
-            mma_step<TM, TN, PA, PB>(As, Bs, wm * TM * 32, wn * TN * 32, acc);
+            mma_step<TM, TN, PA, PB, BK>(As, Bs, wm * TM * 32, wn * TN * 32, acc);
             __syncthreads();
             if (more) {
-                stage();
+                stage(mt + BK);
                 __syncthreads();
             }
         }
     }
 
     const int li = lane & 31, lk = lane >> 5;
-    float* o = out + (int64_t)blockIdx.y * out_split_stride;
+    float* o = out + (int64_t)split * out_split_stride;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -359,15 +456,16 @@ __global__ __launch_bounds__(256) void tn_reduce_kernel(const float* __restrict_
     C[(e / N) * ldc + (e % N)] = s;
 }
 
-template <typename AT, bool VECA, bool VECB>
+template <typename AT, bool VEC>
 static void tn_pick(const GemmTNArgs& a, const TnPlan& p, float* out, int64_t out_ld, int64_t stride, hipStream_t st) {
-    dim3 grid((unsigned)(p.tiles_k * p.tiles_n), (unsigned)p.splits);
+    const unsigned blocks = (unsigned)(NXCD * p.tiles_k * p.tiles_n * cdiv(p.splits, NXCD));
+    dim3 grid(blocks);
     if (p.bn_tile == 128)
-        hipLaunchKernelGGL((gemm_tn_kernel<AT, VECA, VECB, 2, 2, 2, 2>), grid, dim3(256), 0, st, a, p.tiles_n, p.chunk, out, out_ld, stride);
+        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, 2, 2, 2, 2>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, p.splits, p.chunk, out, out_ld, stride);
     else if (p.bn_tile == 64)
-        hipLaunchKernelGGL((gemm_tn_kernel<AT, VECA, VECB, 4, 1, 1, 2>), grid, dim3(256), 0, st, a, p.tiles_n, p.chunk, out, out_ld, stride);
+        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, 4, 1, 1, 2>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, p.splits, p.chunk, out, out_ld, stride);
     else
-        hipLaunchKernelGGL((gemm_tn_kernel<AT, VECA, VECB, 4, 1, 1, 1>), grid, dim3(256), 0, st, a, p.tiles_n, p.chunk, out, out_ld, stride);
+        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, 4, 1, 1, 1>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, p.splits, p.chunk, out, out_ld, stride);
 }
 
 grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st) {
@@ -378,8 +476,8 @@ grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st) {
     if (need > a.workspace_bytes || (need && !a.workspace))
         return fail(GRP_EWORKSPACE, "gemm_tn: workspace %zu < %zu bytes", a.workspace_bytes, need);
     const int elem = a.a_bf16 ? 2 : 4;
-    const bool veca = a.lda % 4 == 0 && a.lda >= round_up(a.K, 4) && (uintptr_t)a.A % (4 * elem) == 0;
-    const bool vecb = a.ldb % 4 == 0 && a.ldb >= round_up(a.N, 4) && (uintptr_t)a.B % 16 == 0;
+    const bool veca = a.M > 0 && a.lda % 4 == 0 && a.lda >= round_up(a.K, 4) && (uintptr_t)a.A % (4 * elem) == 0;
+    const bool vecb = a.M > 0 && a.ldb % 4 == 0 && a.ldb >= round_up(a.N, 4) && (uintptr_t)a.B % 16 == 0;
     float* out = p.splits > 1 ? (float*)a.workspace : a.C;
     const int64_t out_ld = p.splits > 1 ? a.N : a.ldc;
     const int64_t stride = p.splits > 1 ? (int64_t)a.K * a.N : 0;
@@ -387,11 +485,11 @@ grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st) {
         ProfScope ps(a.a_bf16 ? "gemm_tn_bf16a" : "gemm_tn_f32", st, 2.0 * a.M * a.K * a.N,
                      (double)a.M * a.K * elem + 4.0 * a.M * a.N + 4.0 * a.K * a.N);
         if (a.a_bf16) {
-            if (veca && vecb) tn_pick<__hip_bfloat16, true, true>(a, p, out, out_ld, stride, st);
-            else tn_pick<__hip_bfloat16, false, false>(a, p, out, out_ld, stride, st);
+            if (veca && vecb) tn_pick<__hip_bfloat16, true>(a, p, out, out_ld, stride, st);
+            else tn_pick<__hip_bfloat16, false>(a, p, out, out_ld, stride, st);
         } else {
-            if (veca && vecb) tn_pick<float, true, true>(a, p, out, out_ld, stride, st);
-            else tn_pick<float, false, false>(a, p, out, out_ld, stride, st);
+            if (veca && vecb) tn_pick<float, true>(a, p, out, out_ld, stride, st);
+            else tn_pick<float, false>(a, p, out, out_ld, stride, st);
         }
         GRP_LAUNCH_CHECK();
     }

@@ -13,6 +13,7 @@
 
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include <rocprim/rocprim.hpp>
 
@@ -147,7 +148,10 @@ struct DevBuf {
 
 static void free_partition(grp_partition_t* h) {
     if (!h) return;
-    void* ptrs[] = {h->l2g, h->rowptr, h->col, h->colptr, h->row, h->d_local_in, h->d_local_out, h->d_global_in};
+    void* ptrs[] = {h->l2g, h->rowptr, h->col, h->colptr, h->row, h->d_local_in, h->d_local_out, h->d_global_in,
+                    h->csr_long.long_row, h->csr_long.long_first, h->csr_long.chunk_begin, h->csr_long.chunk_end,
+                    h->csc_long.long_row, h->csc_long.long_first, h->csc_long.chunk_begin, h->csc_long.chunk_end,
+                    h->spmm_scratch};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
     delete h;
@@ -169,6 +173,41 @@ static int bits_for(int64_t n) {
     int b = 1;
     while (b < 32 && ((int64_t)1 << b) < n) ++b;
     return b;
+}
+
+// Split schedule of the rows longer than SPMM_LONG_ROW edges (a function of the pointer
+// array only).  One-off host pass over a copy of the pointers; the result lives on the device.
+static grp_status build_long_rows(const int64_t* ptr_dev, int64_t n, LongRows* out, hipStream_t st) {
+    std::vector<int64_t> ptr((size_t)n + 1);
+    GRP_HIP(hipMemcpyAsync(ptr.data(), ptr_dev, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    GRP_HIP(hipStreamSynchronize(st));
+    std::vector<int32_t> rows, first;
+    std::vector<int64_t> cb, ce;
+    for (int64_t v = 0; v < n; ++v) {
+        const int64_t b = ptr[v], e = ptr[v + 1];
+        if (e - b <= SPMM_LONG_ROW) continue;
+        if (cb.size() + (size_t)cdiv(e - b, SPMM_CHUNK) >= ((size_t)1 << 31))
+            return fail(GRP_ERANGE, "more than 2^31 row chunks");
+        rows.push_back((int32_t)v);
+        first.push_back((int32_t)cb.size());
+        for (int64_t c = b; c < e; c += SPMM_CHUNK) {
+            cb.push_back(c);
+            ce.push_back(c + SPMM_CHUNK < e ? c + SPMM_CHUNK : e);
+        }
+    }
+    first.push_back((int32_t)cb.size());
+    out->n_long = (int32_t)rows.size();
+    out->n_chunks = (int32_t)cb.size();
+    if (out->n_long == 0) return GRP_OK;
+    GRP_TRY(halloc(&out->long_row, out->n_long));
+    GRP_TRY(halloc(&out->long_first, out->n_long + 1));
+    GRP_TRY(halloc(&out->chunk_begin, out->n_chunks));
+    GRP_TRY(halloc(&out->chunk_end, out->n_chunks));
+    GRP_HIP(hipMemcpy(out->long_row, rows.data(), rows.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    GRP_HIP(hipMemcpy(out->long_first, first.data(), first.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    GRP_HIP(hipMemcpy(out->chunk_begin, cb.data(), cb.size() * sizeof(int64_t), hipMemcpyHostToDevice));
+    GRP_HIP(hipMemcpy(out->chunk_end, ce.data(), ce.size() * sizeof(int64_t), hipMemcpyHostToDevice));
+    return GRP_OK;
 }
 
 // keys (unsorted, nnz of them; clobbered) -> h->rowptr/col/d_local_in and h->colptr/row/d_local_out.
@@ -204,6 +243,8 @@ static grp_status build_csr_csc(grp_partition_t* h, uint64_t* keys, uint64_t* ke
         GRP_LAUNCH_CHECK();
     }
     GRP_HIP(hipStreamSynchronize(st));
+    GRP_TRY(build_long_rows(h->rowptr, n, &h->csr_long, st));
+    GRP_TRY(build_long_rows(h->colptr, n, &h->csc_long, st));
     return GRP_OK;
 }
 

@@ -1,10 +1,10 @@
 // Row-parallel neighbour aggregation (SpMM) for gfx950.
 //
-// Y[i,:] = a_i (sum_{e in row i} X[idx[e],:] + self * X[i,:]) (+ addend[i,:]) (+ bias) (ReLU)
+// Y[i,:] = a_i (sum_{e in row i} c_{idx[e]} X[idx[e],:] + self * X[i,:]) (+ addend[i,:]) (+ bias) (ReLU)
 //
-// The same kernel serves the forward pass (rows of the CSR, i.e. destinations gathering
-// their in-neighbours) and the backward pass (rows of the CSC: the transposed operator),
-// so no floating-point atomics are needed and results are bit-reproducible.
+// The same kernels serve the forward pass (rows of the CSR: destinations gathering their
+// in-neighbours) and the backward pass (rows of the CSC: the transposed operator), so no
+// floating-point atomics are needed and results are bit-reproducible.
 //
 // Mapping: a group of G lanes (G = 1..64, a power of two) owns one output row; lane t of
 // the group owns columns 4*(t + G*j), j < NJ, as one 16-byte vector, so a group's gather of
@@ -12,6 +12,12 @@
 // group's lanes fetch G column indices with one coalesced load and hand them round with
 // wavefront shuffles; four neighbour rows are requested before any is accumulated so that
 // several gathers are in flight per lane.
+//
+// Degree skew: rows longer than SPMM_LONG_ROW edges are cut, when the partition is built,
+// into chunks of at most SPMM_CHUNK edges.  A workgroup owns a chunk (its 256/G groups take
+// contiguous slices and are summed through LDS in a fixed order) and writes one partial row;
+// a third kernel adds a row's partials in chunk order and applies the epilogue.  The split
+// depends only on the graph, so results do not depend on scheduling.
 #include "common.h"
 
 namespace grp {
@@ -41,26 +47,20 @@ __device__ __forceinline__ float row_scale(int mode, int64_t deg, int self_term)
     return 1.0f;
 }
 
+__device__ __forceinline__ void axpy4(float4& acc, float s, const float4& v) {
+    acc.x = fmaf(s, v.x, acc.x); acc.y = fmaf(s, v.y, acc.y);
+    acc.z = fmaf(s, v.z, acc.z); acc.w = fmaf(s, v.w, acc.w);
+}
+__device__ __forceinline__ void add4(float4& acc, const float4& v) {
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+}
+
+// Sum of X rows over the edges [b, e) for the calling group of G lanes (lane t).
 template <typename XT, int G, int NJ>
-__global__ __launch_bounds__(256) void spmm_rows_kernel(
-    const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx, int64_t n_rows, int F,
-    const XT* __restrict__ X, int64_t ldx, int scale, int self_term, const float* __restrict__ colscale,
-    const float* addend, int64_t ld_add, const float* __restrict__ bias, int relu,
-    float* Y, int64_t ldy) {
-    constexpr int ROWS = 256 / G;
-    const int t = threadIdx.x % G;
-    const int64_t i = (int64_t)blockIdx.x * ROWS + threadIdx.x / G;
-    if (i >= n_rows) return;          // whole groups leave together (G divides 64)
-    const int64_t b = ptr[i], e = ptr[i + 1];
-
-    float4 acc[NJ];
-    bool live[NJ];
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        live[j] = 4 * (t + G * j) < F;
-    }
-
+__device__ __forceinline__ void gather_rows(const int32_t* __restrict__ idx, int64_t b, int64_t e,
+                                            const XT* __restrict__ X, int64_t ldx,
+                                            const float* __restrict__ colscale, int t, const bool (&live)[NJ],
+                                            float4 (&acc)[NJ]) {
     for (int64_t base = b; base < e; base += G) {
         const int cnt = (int)((e - base) < (int64_t)G ? (e - base) : (int64_t)G);
         const int mine = (t < cnt) ? idx[base + t] : 0;
@@ -79,19 +79,9 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
                 const float4 v2 = Vec4Load<XT>::ld(X + c2 * ldx + col);
                 const float4 v3 = Vec4Load<XT>::ld(X + c3 * ldx + col);
                 if (colscale) {
-                    acc[j].x = fmaf(s0, v0.x, acc[j].x); acc[j].y = fmaf(s0, v0.y, acc[j].y);
-                    acc[j].z = fmaf(s0, v0.z, acc[j].z); acc[j].w = fmaf(s0, v0.w, acc[j].w);
-                    acc[j].x = fmaf(s1, v1.x, acc[j].x); acc[j].y = fmaf(s1, v1.y, acc[j].y);
-                    acc[j].z = fmaf(s1, v1.z, acc[j].z); acc[j].w = fmaf(s1, v1.w, acc[j].w);
-                    acc[j].x = fmaf(s2, v2.x, acc[j].x); acc[j].y = fmaf(s2, v2.y, acc[j].y);
-                    acc[j].z = fmaf(s2, v2.z, acc[j].z); acc[j].w = fmaf(s2, v2.w, acc[j].w);
-                    acc[j].x = fmaf(s3, v3.x, acc[j].x); acc[j].y = fmaf(s3, v3.y, acc[j].y);
-                    acc[j].z = fmaf(s3, v3.z, acc[j].z); acc[j].w = fmaf(s3, v3.w, acc[j].w);
+                    axpy4(acc[j], s0, v0); axpy4(acc[j], s1, v1); axpy4(acc[j], s2, v2); axpy4(acc[j], s3, v3);
                 } else {
-                    acc[j].x += v0.x; acc[j].y += v0.y; acc[j].z += v0.z; acc[j].w += v0.w;
-                    acc[j].x += v1.x; acc[j].y += v1.y; acc[j].z += v1.z; acc[j].w += v1.w;
-                    acc[j].x += v2.x; acc[j].y += v2.y; acc[j].z += v2.z; acc[j].w += v2.w;
-                    acc[j].x += v3.x; acc[j].y += v3.y; acc[j].z += v3.z; acc[j].w += v3.w;
+                    add4(acc[j], v0); add4(acc[j], v1); add4(acc[j], v2); add4(acc[j], v3);
                 }
             }
         }
@@ -102,42 +92,130 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
             for (int j = 0; j < NJ; ++j) {
                 if (!live[j]) continue;
                 const float4 v0 = Vec4Load<XT>::ld(X + c0 * ldx + 4 * (t + G * j));
-                acc[j].x = fmaf(s0, v0.x, acc[j].x); acc[j].y = fmaf(s0, v0.y, acc[j].y);
-                acc[j].z = fmaf(s0, v0.z, acc[j].z); acc[j].w = fmaf(s0, v0.w, acc[j].w);
+                axpy4(acc[j], s0, v0);
             }
         }
-    }
-
-    const float a = row_scale(scale, e - b, self_term);
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        if (!live[j]) continue;
-        const int col = 4 * (t + G * j);
-        float4 r = acc[j];
-        if (self_term) {
-            const float4 s = Vec4Load<XT>::ld(X + i * ldx + col);
-            r.x += s.x; r.y += s.y; r.z += s.z; r.w += s.w;
-        }
-        r.x *= a; r.y *= a; r.z *= a; r.w *= a;
-        if (addend) {
-            const float4 s = *reinterpret_cast<const float4*>(addend + i * ld_add + col);
-            r.x += s.x; r.y += s.y; r.z += s.z; r.w += s.w;
-        }
-        float o[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (col + q < F) {
-                if (bias) o[q] += bias[col + q];
-                if (relu) o[q] = o[q] > 0.f ? o[q] : 0.f;
-            } else {
-                o[q] = 0.f;           // pad columns stay zero
-            }
-        }
-        *reinterpret_cast<float4*>(Y + i * ldy + col) = make_float4(o[0], o[1], o[2], o[3]);
     }
 }
 
-// Fallback for pitches or pointers that are not 16-byte friendly: one lane per column.
+struct SpmmEpilogue {
+    int scale, self_term, relu, F;
+    const float* addend;      // may alias Y
+    int64_t ld_add;
+    const float* bias;
+    float* Y;
+    int64_t ldy;
+};
+
+template <typename XT>
+__device__ __forceinline__ void finish_row(const SpmmEpilogue& ep, int64_t i, int64_t deg, int col, float4 r,
+                                           const XT* __restrict__ X, int64_t ldx) {
+    const float a = row_scale(ep.scale, deg, ep.self_term);
+    if (ep.self_term) add4(r, Vec4Load<XT>::ld(X + i * ldx + col));
+    r.x *= a; r.y *= a; r.z *= a; r.w *= a;
+    if (ep.addend) add4(r, *reinterpret_cast<const float4*>(ep.addend + i * ep.ld_add + col));
+    float o[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (col + q < ep.F) {
+            if (ep.bias) o[q] += ep.bias[col + q];
+            if (ep.relu) o[q] = o[q] > 0.f ? o[q] : 0.f;
+        } else {
+            o[q] = 0.f;           // pad columns stay zero
+        }
+    }
+    *reinterpret_cast<float4*>(ep.Y + i * ep.ldy + col) = make_float4(o[0], o[1], o[2], o[3]);
+}
+
+// Rows of at most `long_thr` edges: one group per row.
+template <typename XT, int G, int NJ>
+__global__ __launch_bounds__(256) void spmm_rows_kernel(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx,
+                                                        int64_t n_rows, int64_t long_thr, const XT* __restrict__ X,
+                                                        int64_t ldx, const float* __restrict__ colscale,
+                                                        SpmmEpilogue ep) {
+    constexpr int ROWS = 256 / G;
+    const int t = threadIdx.x % G;
+    const int64_t i = (int64_t)blockIdx.x * ROWS + threadIdx.x / G;
+    if (i >= n_rows) return;          // whole groups leave together (G divides 64)
+    const int64_t b = ptr[i], e = ptr[i + 1];
+    if (e - b > long_thr) return;     // handled by the chunk kernels
+    float4 acc[NJ];
+    bool live[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        live[j] = 4 * (t + G * j) < ep.F;
+    }
+    gather_rows<XT, G, NJ>(idx, b, e, X, ldx, colscale, t, live, acc);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+        if (live[j]) finish_row<XT>(ep, i, e - b, 4 * (t + G * j), acc[j], X, ldx);
+}
+
+// One workgroup per chunk of a long row -> one partial row.
+template <typename XT, int G, int NJ>
+__global__ __launch_bounds__(256) void spmm_chunk_kernel(const int64_t* __restrict__ chunk_begin,
+                                                         const int64_t* __restrict__ chunk_end,
+                                                         const int32_t* __restrict__ idx, int F,
+                                                         const XT* __restrict__ X, int64_t ldx,
+                                                         const float* __restrict__ colscale,
+                                                         float* __restrict__ partials, int64_t ld_part) {
+    constexpr int NG = 256 / G;
+    constexpr int W = 4 * G * NJ;                 // padded row width held by a group
+    __shared__ float red[NG * W];
+    const int t = threadIdx.x % G, gi = threadIdx.x / G;
+    const int64_t cb = chunk_begin[blockIdx.x], ce = chunk_end[blockIdx.x];
+    const int64_t per = (ce - cb + NG - 1) / NG;
+    int64_t b = cb + gi * per, e = b + per;
+    if (b > ce) b = ce;
+    if (e > ce) e = ce;
+    float4 acc[NJ];
+    bool live[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        live[j] = 4 * (t + G * j) < F;
+    }
+    gather_rows<XT, G, NJ>(idx, b, e, X, ldx, colscale, t, live, acc);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+        *reinterpret_cast<float4*>(&red[gi * W + 4 * (t + G * j)]) = acc[j];
+    __syncthreads();
+    const int fpad = (F + 3) & ~3;
+    for (int c = threadIdx.x; c < fpad; c += 256) {
+        float s = 0.f;
+#pragma unroll
+        for (int q = 0; q < NG; ++q) s += red[q * W + c];
+        partials[(int64_t)blockIdx.x * ld_part + c] = s;
+    }
+}
+
+// One group per long row: partial rows added in chunk order, then the epilogue.
+template <typename XT, int G, int NJ>
+__global__ __launch_bounds__(256) void spmm_combine_kernel(const int32_t* __restrict__ long_row,
+                                                           const int32_t* __restrict__ long_first, int n_long,
+                                                           const int64_t* __restrict__ ptr,
+                                                           const float* __restrict__ partials, int64_t ld_part,
+                                                           const XT* __restrict__ X, int64_t ldx, SpmmEpilogue ep) {
+    constexpr int ROWS = 256 / G;
+    const int t = threadIdx.x % G;
+    const int j0 = blockIdx.x * ROWS + threadIdx.x / G;
+    if (j0 >= n_long) return;
+    const int64_t i = long_row[j0];
+    const int c0 = long_first[j0], c1 = long_first[j0 + 1];
+    const int64_t deg = ptr[i + 1] - ptr[i];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int col = 4 * (t + G * j);
+        if (col >= ep.F) continue;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int c = c0; c < c1; ++c) add4(acc, *reinterpret_cast<const float4*>(partials + (int64_t)c * ld_part + col));
+        finish_row<XT>(ep, i, deg, col, acc, X, ldx);
+    }
+}
+
+// Fallback for pitches or pointers that are not 16-byte friendly: one wavefront per row,
+// one lane per column (handles rows of any length itself).
 template <typename XT>
 __global__ __launch_bounds__(256) void spmm_rows_scalar_kernel(
     const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx, int64_t n_rows, int F,
@@ -151,7 +229,8 @@ __global__ __launch_bounds__(256) void spmm_rows_scalar_kernel(
     const float a = row_scale(scale, e - b, self_term);
     for (int col = t; col < F; col += 64) {
         float acc = 0.f;
-        for (int64_t k = b; k < e; ++k) acc += (colscale ? colscale[idx[k]] : 1.f) * (float)X[(int64_t)idx[k] * ldx + col];
+        for (int64_t k = b; k < e; ++k)
+            acc = fmaf(colscale ? colscale[idx[k]] : 1.f, (float)X[(int64_t)idx[k] * ldx + col], acc);
         if (self_term) acc += (float)X[i * ldx + col];
         acc *= a;
         if (addend) acc += addend[i * ld_add + col];
@@ -162,28 +241,42 @@ __global__ __launch_bounds__(256) void spmm_rows_scalar_kernel(
 }
 
 template <typename XT, int G, int NJ>
-static void launch_one(const SpmmArgs& a, hipStream_t st) {
+static void launch_one(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_t st) {
     constexpr int ROWS = 256 / G;
-    const int64_t blocks = cdiv(a.n_rows, ROWS);
-    hipLaunchKernelGGL((spmm_rows_kernel<XT, G, NJ>), dim3((unsigned)blocks), dim3(256), 0, st, a.ptr, a.idx,
-                       a.n_rows, a.F, (const XT*)a.X, a.ldx, a.scale, a.self_term, a.colscale, a.addend, a.ld_add,
-                       a.bias, a.relu, a.Y, a.ldy);
+    const LongRows* lr = a.long_rows;
+    const bool split = lr && lr->n_long > 0;
+    const int64_t thr = split ? (int64_t)SPMM_LONG_ROW : INT64_MAX;
+    hipLaunchKernelGGL((spmm_rows_kernel<XT, G, NJ>), dim3((unsigned)cdiv(a.n_rows, ROWS)), dim3(256), 0, st, a.ptr, a.idx,
+                       a.n_rows, thr, (const XT*)a.X, a.ldx, a.colscale, ep);
+    if (split) {
+        const int64_t ld_part = round_up(a.F, 4);
+        hipLaunchKernelGGL((spmm_chunk_kernel<XT, G, NJ>), dim3((unsigned)lr->n_chunks), dim3(256), 0, st, lr->chunk_begin,
+                           lr->chunk_end, a.idx, a.F, (const XT*)a.X, a.ldx, a.colscale, a.partials, ld_part);
+        hipLaunchKernelGGL((spmm_combine_kernel<XT, G, NJ>), dim3((unsigned)cdiv(lr->n_long, ROWS)), dim3(256), 0, st,
+                           lr->long_row, lr->long_first, lr->n_long, a.ptr, (const float*)a.partials, ld_part,
+                           (const XT*)a.X, a.ldx, ep);
+    }
 }
 
 template <typename XT>
-static grp_status dispatch(const SpmmArgs& a, hipStream_t st) {
+static grp_status dispatch(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_t st) {
     const int f4 = (a.F + 3) / 4;
-    if (f4 <= 1) launch_one<XT, 1, 1>(a, st);
-    else if (f4 <= 2) launch_one<XT, 2, 1>(a, st);
-    else if (f4 <= 4) launch_one<XT, 4, 1>(a, st);
-    else if (f4 <= 8) launch_one<XT, 8, 1>(a, st);
-    else if (f4 <= 16) launch_one<XT, 16, 1>(a, st);
-    else if (f4 <= 32) launch_one<XT, 32, 1>(a, st);
-    else if (f4 <= 64) launch_one<XT, 64, 1>(a, st);
-    else if (f4 <= 128) launch_one<XT, 64, 2>(a, st);
-    else if (f4 <= 256) launch_one<XT, 64, 4>(a, st);
+    if (f4 <= 1) launch_one<XT, 1, 1>(a, ep, st);
+    else if (f4 <= 2) launch_one<XT, 2, 1>(a, ep, st);
+    else if (f4 <= 4) launch_one<XT, 4, 1>(a, ep, st);
+    else if (f4 <= 8) launch_one<XT, 8, 1>(a, ep, st);
+    else if (f4 <= 16) launch_one<XT, 16, 1>(a, ep, st);
+    else if (f4 <= 32) launch_one<XT, 32, 1>(a, ep, st);
+    else if (f4 <= 64) launch_one<XT, 64, 1>(a, ep, st);
+    else if (f4 <= 128) launch_one<XT, 64, 2>(a, ep, st);
+    else if (f4 <= 256) launch_one<XT, 64, 4>(a, ep, st);
     else return fail(GRP_EUNSUPPORTED, "spmm: F = %d exceeds 1024", a.F);
     return GRP_OK;
+}
+
+size_t spmm_partials_bytes(const LongRows* lr, int32_t F) {
+    if (!lr || lr->n_long == 0) return 0;
+    return (size_t)lr->n_chunks * round_up(F, 4) * sizeof(float);
 }
 
 grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
@@ -192,8 +285,7 @@ grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
         return fail(GRP_EINVAL, "spmm: bad arguments");
     const int elem = a.x_bf16 ? 2 : 4;
     const int64_t fpad = round_up(a.F, 4);
-    const bool vec_ok = a.ldx >= fpad && a.ldy >= fpad && (a.ldx * elem) % (4 * elem) == 0 &&
-                        a.ldx % 4 == 0 && a.ldy % 4 == 0 &&
+    const bool vec_ok = a.ldx >= fpad && a.ldy >= fpad && a.ldx % 4 == 0 && a.ldy % 4 == 0 &&
                         ((uintptr_t)a.X % (4 * elem)) == 0 && ((uintptr_t)a.Y % 16) == 0 &&
                         (!a.addend || (a.ld_add % 4 == 0 && a.ld_add >= fpad && ((uintptr_t)a.addend % 16) == 0));
     // compulsory traffic: the index stream, the row pointers, every source row once, every
@@ -203,7 +295,10 @@ grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
                          4.0 * a.F * a.n_rows * (a.addend ? 2.0 : 1.0) + (a.colscale ? 4.0 * n_src : 0.0);
     ProfScope ps(a.x_bf16 ? "spmm_rows_bf16" : "spmm_rows_f32", st, 2.0 * a.nnz * a.F, bytes);
     if (vec_ok) {
-        GRP_TRY(a.x_bf16 ? dispatch<__hip_bfloat16>(a, st) : dispatch<float>(a, st));
+        if (a.long_rows && a.long_rows->n_long > 0 && (!a.partials || ((uintptr_t)a.partials % 16) != 0))
+            return fail(GRP_EINVAL, "spmm: partition has long rows but no scratch for their partial sums");
+        SpmmEpilogue ep{a.scale, a.self_term, a.relu, a.F, a.addend, a.ld_add, a.bias, a.Y, a.ldy};
+        GRP_TRY(a.x_bf16 ? dispatch<__hip_bfloat16>(a, ep, st) : dispatch<float>(a, ep, st));
     } else {
         const int64_t blocks = cdiv(a.n_rows, 4);
         if (a.x_bf16)
@@ -225,12 +320,13 @@ extern "C" grp_status grp_spmm(const grp_partition_t* part, int32_t transposed, 
                                int32_t self_term, int32_t F, const void* X, int64_t ldx, int32_t x_dtype,
                                float* Y, int64_t ldy, void* stream) {
     if (!part || !X || !Y) return grp::fail(GRP_EINVAL, "grp_spmm: null argument");
-    if (F <= 0 || ldx < F || ldy < F) return grp::fail(GRP_EINVAL, "grp_spmm: bad F / pitch");
+    if (F <= 0 || F > 1024 || ldx < F || ldy < F) return grp::fail(GRP_EINVAL, "grp_spmm: bad F / pitch");
     if (scale < GRP_SCALE_NONE || scale > GRP_SCALE_RSQRT) return grp::fail(GRP_EINVAL, "grp_spmm: bad scale");
     if (x_dtype != GRP_DTYPE_FP32 && x_dtype != GRP_DTYPE_BF16) return grp::fail(GRP_EINVAL, "grp_spmm: bad dtype");
     grp::SpmmArgs a;
     a.ptr = transposed ? part->colptr : part->rowptr;
     a.idx = transposed ? part->row : part->col;
+    a.long_rows = transposed ? &part->csc_long : &part->csr_long;
     a.n_rows = part->n;
     a.nnz = part->nnz;
     a.F = F;
@@ -241,5 +337,19 @@ extern "C" grp_status grp_spmm(const grp_partition_t* part, int32_t transposed, 
     a.self_term = self_term ? 1 : 0;
     a.Y = Y;
     a.ldy = ldy;
+    // the standalone call keeps its partial-sum scratch in the handle (grown on demand)
+    const size_t need = grp::spmm_partials_bytes(a.long_rows, F);
+    if (need > part->spmm_scratch_bytes) {
+        grp_partition_t* mut = const_cast<grp_partition_t*>(part);
+        if (mut->spmm_scratch) (void)hipFree(mut->spmm_scratch);
+        mut->spmm_scratch = nullptr;
+        mut->spmm_scratch_bytes = 0;
+        if (hipMalloc((void**)&mut->spmm_scratch, need) != hipSuccess) {
+            (void)hipGetLastError();
+            return grp::fail(GRP_ENOMEM, "grp_spmm: scratch allocation of %zu bytes failed", need);
+        }
+        mut->spmm_scratch_bytes = need;
+    }
+    a.partials = part->spmm_scratch;
     return grp::launch_spmm(a, (hipStream_t)stream);
 }

@@ -42,6 +42,7 @@ struct StepPlan {
     float *inv_in = nullptr, *gr = nullptr, *gs = nullptr, *grinv = nullptr;
     float *tmpA = nullptr, *tmpB = nullptr, *dZa = nullptr, *dZb = nullptr;
     void *tn_ws = nullptr, *colsum_ws = nullptr, *stats_ws = nullptr;
+    float* partials = nullptr;   // partial rows of the split long rows (SpMM)
     size_t tn_ws_bytes = 0;
     size_t total = 0;
 };
@@ -64,8 +65,9 @@ static int64_t param_count(const grp_model_desc* m) {
 }
 
 // Carves (or, with a null base, measures) the workspace.
-static StepPlan make_plan(int64_t n, const grp_model_desc* m, void* ws, size_t ws_bytes) {
+static StepPlan make_plan(const grp_partition_t* part, const grp_model_desc* m, void* ws, size_t ws_bytes) {
     StepPlan p;
+    const int64_t n = part->n;
     Bump b(ws, ws_bytes);
     const int k = m->n_layers;
     const bool sage = m->arch == GRP_ARCH_SAGE_MEAN;
@@ -108,6 +110,13 @@ static StepPlan make_plan(int64_t n, const grp_model_desc* m, void* ws, size_t w
     p.tn_ws_bytes = tn_bytes;
     p.colsum_ws = b.take<char>(cs_bytes);
     p.stats_ws = b.take<char>(stats_workspace_bytes(n));
+    {
+        int64_t fsp = 0;
+        for (int l = 0; l <= k; ++l)
+            if (ldp(m->dims[l]) > fsp) fsp = ldp(m->dims[l]);
+        const int64_t chunks = part->csr_long.n_chunks > part->csc_long.n_chunks ? part->csr_long.n_chunks : part->csc_long.n_chunks;
+        p.partials = b.take<float>((size_t)chunks * fsp);
+    }
     p.total = (b.off + 255) & ~(size_t)255;
     return p;
 }
@@ -150,7 +159,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
         const int relu = l < k - 1;
         if (L.agg_first) {
             SpmmArgs s;
-            s.ptr = g->rowptr; s.idx = g->col; s.nnz = g->nnz; s.n_rows = n; s.F = fin; s.X = H; s.ldx = ldh; s.x_bf16 = h_bf16;
+            s.ptr = g->rowptr; s.idx = g->col; s.nnz = g->nnz; s.long_rows = &g->csr_long; s.partials = p.partials; s.n_rows = n; s.F = fin; s.X = H; s.ldx = ldh; s.x_bf16 = h_bf16;
             s.scale = GRP_SCALE_MEAN; s.Y = L.M; s.ldy = ldp(fin);
             GRP_TRY(launch_spmm(s, st));
             GemmNNArgs a;
@@ -166,7 +175,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             a.B = L.Wp_s; a.bias = theta + L.off_b; a.C = L.H_out;
             GRP_TRY(launch_gemm_nn(a, st));
             SpmmArgs s;
-            s.ptr = g->rowptr; s.idx = g->col; s.nnz = g->nnz; s.n_rows = n; s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout);
+            s.ptr = g->rowptr; s.idx = g->col; s.nnz = g->nnz; s.long_rows = &g->csr_long; s.partials = p.partials; s.n_rows = n; s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout);
             s.scale = GRP_SCALE_MEAN; s.addend = L.H_out; s.ld_add = ldp(fout); s.relu = relu; s.Y = L.H_out; s.ldy = ldp(fout);
             GRP_TRY(launch_spmm(s, st));
         }
@@ -201,7 +210,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
                 a.rowscale = p.inv_in; a.C = p.tmpA; a.ldc = ldp(fin); a.zero_pad_to = (int)ldp(fin);
                 GRP_TRY(launch_gemm_nn(a, st));
                 SpmmArgs s;        // P = A^T dM'
-                s.ptr = g->colptr; s.idx = g->row; s.nnz = g->nnz; s.n_rows = n; s.F = fin; s.X = p.tmpA; s.ldx = ldp(fin);
+                s.ptr = g->colptr; s.idx = g->row; s.nnz = g->nnz; s.long_rows = &g->csc_long; s.partials = p.partials; s.n_rows = n; s.F = fin; s.X = p.tmpA; s.ldx = ldp(fin);
                 s.Y = p.tmpB; s.ldy = ldp(fin);
                 GRP_TRY(launch_spmm(s, st));
                 GemmNNArgs c;      // dZ_prev = mask * (dZ Ws^T + P)
@@ -212,7 +221,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             }
         } else {
             SpmmArgs s;            // dT = A^T (dZ / d_in)
-            s.ptr = g->colptr; s.idx = g->row; s.nnz = g->nnz; s.n_rows = n; s.F = fout; s.X = dZ; s.ldx = ldp(fout);
+            s.ptr = g->colptr; s.idx = g->row; s.nnz = g->nnz; s.long_rows = &g->csc_long; s.partials = p.partials; s.n_rows = n; s.F = fout; s.X = dZ; s.ldx = ldp(fout);
             s.colscale = p.inv_in; s.Y = p.tmpA; s.ldy = ldp(fout);
             GRP_TRY(launch_spmm(s, st));
             t.B = p.tmpA; t.C = grad + L.off_wn;
@@ -258,7 +267,7 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
         a.rowscale = p.gs; a.C = p.tmpA; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
         GRP_TRY(launch_gemm_nn(a, st));
         SpmmArgs s;
-        s.ptr = g->rowptr; s.idx = g->col; s.nnz = g->nnz; s.n_rows = n; s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout);
+        s.ptr = g->rowptr; s.idx = g->col; s.nnz = g->nnz; s.long_rows = &g->csr_long; s.partials = p.partials; s.n_rows = n; s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout);
         s.scale = GRP_SCALE_RSQRT; s.self_term = sl; s.bias = theta + L.off_b; s.relu = l < k - 1;
         s.Y = L.H_out; s.ldy = ldp(fout);
         GRP_TRY(launch_spmm(s, st));
@@ -281,7 +290,7 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
         const int in_bf16 = l == 0 && m->feat_dtype == GRP_DTYPE_BF16;
         GRP_TRY(launch_colsum_scaled(dZ, n, fout, ldp(fout), p.grinv, grad + L.off_b, p.colsum_ws, st));
         SpmmArgs s;
-        s.ptr = g->colptr; s.idx = g->row; s.nnz = g->nnz; s.n_rows = n; s.F = fout; s.X = dZ; s.ldx = ldp(fout);
+        s.ptr = g->colptr; s.idx = g->row; s.nnz = g->nnz; s.long_rows = &g->csc_long; s.partials = p.partials; s.n_rows = n; s.F = fout; s.X = dZ; s.ldx = ldp(fout);
         s.scale = GRP_SCALE_RSQRT; s.self_term = sl; s.Y = p.tmpA; s.ldy = ldp(fout);
         GRP_TRY(launch_spmm(s, st));
         GemmTNArgs t;
@@ -313,7 +322,7 @@ extern "C" grp_status grp_step_workspace_bytes(const grp_partition_t* part, cons
     if (!bytes) return fail(GRP_EINVAL, "grp_step_workspace_bytes: null output");
     *bytes = 0;
     GRP_TRY(check_step_args(part, model, opts));
-    *bytes = make_plan(part->n, model, nullptr, 0).total;
+    *bytes = make_plan(part, model, nullptr, 0).total;
     return GRP_OK;
 }
 
@@ -325,11 +334,11 @@ extern "C" grp_status grp_train_step(const grp_partition_t* part, const grp_mode
     GRP_TRY(check_step_args(part, model, opts));
     if (!weights || !grad_out || !stats_out) return fail(GRP_EINVAL, "train_step: null weights / grad_out / stats_out");
     if (part->n > 0 && (!features || !labels)) return fail(GRP_EINVAL, "train_step: null features or labels");
-    StepPlan need = make_plan(part->n, model, nullptr, 0);
+    StepPlan need = make_plan(part, model, nullptr, 0);
     if (!workspace || workspace_bytes < need.total)
         return fail(GRP_EWORKSPACE, "train_step: workspace %zu bytes, need %zu", workspace_bytes, need.total);
     if ((uintptr_t)workspace % 256 != 0) return fail(GRP_EINVAL, "train_step: workspace must be 256-byte aligned");
-    StepPlan p = make_plan(part->n, model, workspace, workspace_bytes);
+    StepPlan p = make_plan(part, model, workspace, workspace_bytes);
     hipStream_t st = (hipStream_t)stream;
     if (model->arch == GRP_ARCH_SAGE_MEAN)
         return sage_step(part, model, opts, features, labels, train_mask, weights, p, st, grad_out, stats_out);
