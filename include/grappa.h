@@ -15,7 +15,8 @@
  *     caller owns every buffer it passes; the library owns only the opaque handles it
  *     returns and frees them in *_destroy.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
- *     asynchronous on that stream unless stated otherwise and never synchronise it.
+ *     asynchronous on that stream and do not synchronise it unless stated otherwise
+ *     (grp_partition*, and grp_train_step in mini-batch mode, do).
  *   - Every function returns GRP_OK (0) or a negative status; it never throws or aborts.
  *     grp_last_error() gives a thread-local, library-owned description of the last
  *     failure on the calling thread.
@@ -168,8 +169,20 @@ grp_status grp_step_workspace_bytes(const grp_partition_t* part, const grp_model
  *   stats_out  DEV grp_step_stats, overwritten
  * S = train_mask ∩ local nodes (full graph) or the seeds (mini-batch).  Deterministic:
  * no floating-point atomics; two calls with equal inputs give equal bits.
- * Errors: GRP_EINVAL, GRP_EWORKSPACE, GRP_EUNSUPPORTED (mini-batch with a GCN arch),
- * GRP_EHIP.                                                                            */
+ *
+ * Mini-batch mode (opts->full_graph = 0, GraphSAGE only): isolated k-hop sampling inside the
+ * partition, then the same layers on the sampled blocks.  Sampling rule (the paper fixes
+ * none): per destination node all local in-edges if there are at most fanouts[l], else the
+ * fanouts[l] in-edges with the smallest key
+ *   key = M(M(M(M(M(sampler_seed) ^ batch_id) ^ l) ^ global_id(v)) ^ j),
+ *   M(x) = SplitMix64 finaliser of x + 0x9E3779B97F4A7C15, j = position in v's CSR row,
+ * ties by j; layers are built from the seeds inwards (the seeds draw fanouts[k-1]); the mean
+ * of a layer divides by the number of sampled neighbours.  Fanouts must lie in [1, 64]; seeds
+ * must be distinct.  This mode synchronises the stream once per layer above the input layer
+ * (the sampled block sizes are needed on the host); the workspace is sized from the seeds and
+ * fanouts alone.
+ * Errors: GRP_EINVAL, GRP_EWORKSPACE, GRP_EUNSUPPORTED (mini-batch with a GCN arch; a
+ * residual first layer on bf16 features), GRP_EHIP.                                    */
 grp_status grp_train_step(const grp_partition_t* part, const grp_model_desc* model,
                           const grp_step_opts* opts, const void* features,
                           const int32_t* labels, const uint8_t* train_mask,

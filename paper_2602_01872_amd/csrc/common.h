@@ -118,6 +118,10 @@ struct SpmmArgs {
     int64_t ldy = 0;
     const LongRows* long_rows = nullptr;  // null = no row is split
     float* partials = nullptr;            // [n_chunks x round_up(F,4)] scratch when rows are split
+    const float* residual = nullptr;      // added after the ReLU: Y = residual + act (residual layers)
+    int64_t ld_res = 0;
+    float* Y2 = nullptr;                  // also receives act (before the residual is added)
+    int64_t ldy2 = 0;
 };
 grp_status launch_spmm(const SpmmArgs& a, hipStream_t st);
 size_t spmm_partials_bytes(const LongRows* lr, int32_t F);
@@ -147,6 +151,10 @@ struct GemmNNArgs {
     float* C = nullptr;
     int64_t ldc = 0;
     int32_t zero_pad_to = 0;        // also write zeros to columns [N, zero_pad_to)
+    const int32_t* a_rows = nullptr; // row i of A is stored at row a_rows[i] (null: i)
+    int64_t a_valid_rows = 0;       // rows >= this of the FIRST product's A read as zero (0: M)
+    float* C_raw = nullptr;         // also receives acc + bias + addend (before scale / ReLU / mask)
+    int64_t ld_raw = 0;
 };
 grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st);
 
@@ -164,6 +172,7 @@ struct GemmTNArgs {
     int64_t ldc = 0;
     void* workspace = nullptr;
     size_t workspace_bytes = 0;
+    const int32_t* a_rows = nullptr; // row i of A is stored at row a_rows[i] (null: i)
 };
 grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st);
 
@@ -187,9 +196,11 @@ grp_status launch_pad_copy(const float* in, int32_t rows, int32_t cols, float* o
 
 // Coverage statistics over the loss nodes and the weighted softmax cross-entropy.
 size_t stats_workspace_bytes(int64_t n);
+// nnz_used = nnz_const + the sum of the n_parts device counters nnz_parts[i][0].
 grp_status launch_stats(int64_t n_loss, const int32_t* loss_nodes /*null = 0..n-1 by mask*/,
                         const uint8_t* mask, const int32_t* d_local, const int64_t* d_global,
-                        const int32_t* sampled_count /*null = full graph*/, int64_t nnz_used,
+                        const int32_t* sampled_count /*null = full graph*/, int64_t nnz_const,
+                        const int64_t* const* nnz_parts /*HOST array of device pointers*/, int n_parts,
                         void* scratch, grp_step_stats* out, hipStream_t st);
 grp_status launch_softmax_xent(int64_t n_rows, int32_t C, const float* Z, int64_t ldz,
                                const int32_t* labels, const int32_t* node_of_row /*null = row*/,
@@ -201,4 +212,71 @@ grp_status launch_softmax_xent(int64_t n_rows, int32_t C, const float* Z, int64_
 
 grp_status launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 
+}  // namespace grp
+
+// ---------------------------------------------------------------- device primitives (partition.hip)
+namespace grp {
+// rocPRIM wrappers with caller-provided temporary storage (sizes from the *_temp_bytes calls).
+size_t sort_keys_temp_bytes(int64_t count);
+grp_status sort_keys_u64(void* temp, size_t temp_bytes, const uint64_t* in, uint64_t* out, int64_t count,
+                         unsigned end_bit, hipStream_t st);
+size_t scan_temp_bytes(int64_t count);
+grp_status exclusive_scan_i64(void* temp, size_t temp_bytes, const int64_t* in, int64_t* out, int64_t count,
+                              hipStream_t st);
+grp_status exclusive_scan_i32(void* temp, size_t temp_bytes, const int32_t* in, int32_t* out, int64_t count,
+                              hipStream_t st);
+// From sorted keys (row << 32 | col): idx[i] = low half, ptr[r] = first position with high half >= r.
+grp_status launch_csr_from_sorted_keys(const uint64_t* keys, int64_t nnz, int64_t n, int64_t* ptr, int32_t* idx,
+                                       hipStream_t st);
+// Host pass over a device pointer array: the split schedule of its long rows, written into
+// caller-provided device arrays (capacities in rows / chunks).  Synchronises the stream.
+grp_status build_long_rows_into(const int64_t* ptr_dev, int64_t n, LongRows* out, int64_t cap_long,
+                                int64_t cap_chunks, hipStream_t st);
+
+// ---------------------------------------------------------------- blocks and sampling (sampler.hip)
+// One bipartite message-passing layer.  Rows of `ptr/idx` are the layer's outputs
+// (destinations); `idx` indexes rows of the layer's input matrix.  The outputs are the first
+// n_dst inputs unless `self_rows` says where output i's own input row is stored.
+struct Block {
+    int64_t n_dst = 0, n_in = 0, nnz = 0;
+    const int64_t* ptr = nullptr;
+    const int32_t* idx = nullptr;
+    const int64_t* ptrT = nullptr;       // transposed structure over the n_in inputs (null if unused)
+    const int32_t* idxT = nullptr;
+    const LongRows* long_fwd = nullptr;
+    const LongRows* long_bwd = nullptr;
+    const int32_t* self_rows = nullptr;  // [n_dst] or null (row i)
+    float* inv_in = nullptr;             // [n_dst] 1 / max(row length, 1)
+};
+
+struct SamplerBounds {                   // upper bounds per layer, from seeds and fanouts alone
+    int64_t dst[GRP_MAX_LAYERS], nnz[GRP_MAX_LAYERS], src[GRP_MAX_LAYERS];
+};
+void sampler_bounds(int64_t n, int64_t n_seeds, const int32_t* fanouts, int k, SamplerBounds* out);
+size_t sampler_workspace_bytes(int64_t n, const SamplerBounds& b, int k);
+// Isolated k-hop sampling inside the partition; fills blocks[0..k) (layer 0 = input side).
+// Layer 0's idx holds partition-local node ids (rows of the feature matrix) and its self_rows
+// the destinations' ids; deeper layers are relabelled to block-local indices.  seeds_out
+// receives the device pointer of the seed list; nnz_parts_dev[k] the per-layer edge counts
+// (device).  Synchronises the stream once per layer above the input layer.
+grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* opts, int k, void* ws, size_t ws_bytes,
+                         Block* blocks, LongRows* long_bwd_store, const int64_t** nnz_parts_dev,
+                         const int32_t** seed_counts_dev, hipStream_t st);
+}  // namespace grp
+
+namespace grp {
+// Bump allocator over a caller-provided workspace (null base: only measures).
+struct Bump {
+    char* base;
+    size_t cap, off = 0;
+    bool measure;
+    Bump(void* b, size_t c) : base((char*)b), cap(c), measure(b == nullptr) {}
+    template <typename T> T* take(size_t count) {
+        off = (off + 255) & ~(size_t)255;
+        T* p = measure ? nullptr : (T*)(base + off);
+        off += count * sizeof(T);
+        return p;
+    }
+    size_t total() const { return (off + 255) & ~(size_t)255; }
+};
 }  // namespace grp

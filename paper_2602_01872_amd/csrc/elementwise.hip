@@ -236,8 +236,13 @@ __global__ __launch_bounds__(256) void stats_partial_kernel(int64_t n_rows, cons
     if (threadIdx.x == 0) part[blockIdx.x] = StatsPartial{ratio, rd, s, ri};
 }
 
+struct NnzParts {
+    const int64_t* p[GRP_MAX_LAYERS];
+    int n;
+};
+
 __global__ __launch_bounds__(256) void stats_final_kernel(const StatsPartial* __restrict__ part, int blocks,
-                                                          int full_graph, int64_t nnz_used,
+                                                          int full_graph, int64_t nnz_const, NnzParts np,
                                                           grp_step_stats* __restrict__ out) {
     __shared__ double smd[4];
     __shared__ int64_t smi[4];
@@ -255,20 +260,25 @@ __global__ __launch_bounds__(256) void stats_final_kernel(const StatsPartial* __
         out->sum_ratio = ratio;
         out->R = full_graph ? (double)ri : rd;
         out->S = s;
+        int64_t nnz_used = nnz_const;
+        for (int i = 0; i < np.n; ++i) nnz_used += np.p[i][0];
         out->nnz_used = nnz_used;
     }
 }
 
 grp_status launch_stats(int64_t n_rows, const int32_t* nodes, const uint8_t* mask, const int32_t* d_local,
-                        const int64_t* d_global, const int32_t* sampled_count, int64_t nnz_used, void* scratch,
-                        grp_step_stats* out, hipStream_t st) {
+                        const int64_t* d_global, const int32_t* sampled_count, int64_t nnz_const,
+                        const int64_t* const* nnz_parts, int n_parts, void* scratch, grp_step_stats* out, hipStream_t st) {
+    NnzParts np;
+    np.n = n_parts;
+    for (int i = 0; i < GRP_MAX_LAYERS; ++i) np.p[i] = i < n_parts ? nnz_parts[i] : nullptr;
     ProfScope ps("coverage_stats", st);
     StatsPartial* part = (StatsPartial*)scratch;
     hipLaunchKernelGGL(stats_partial_kernel, dim3(STATS_BLOCKS), dim3(256), 0, st, n_rows, nodes, mask, d_local, d_global,
                        sampled_count, part);
     GRP_LAUNCH_CHECK();
     hipLaunchKernelGGL(stats_final_kernel, dim3(1), dim3(256), 0, st, (const StatsPartial*)part, STATS_BLOCKS,
-                       sampled_count ? 0 : 1, nnz_used, out);
+                       sampled_count ? 0 : 1, nnz_const, np, out);
     GRP_LAUNCH_CHECK();
     return GRP_OK;
 }

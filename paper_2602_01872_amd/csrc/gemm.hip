@@ -140,6 +140,15 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
 
     uint4 ra[A_REPS], rb[B_REPS];
 
+    // rows of the first product's A: optional indirection and a limit on the valid rows
+    const int64_t a_valid = g.a_valid_rows > 0 ? g.a_valid_rows : g.M;
+    int64_t arow[A_REPS];
+#pragma unroll
+    for (int r = 0; r < A_REPS; ++r) {
+        const int64_t gm = lmin(m0 + (tid + 256 * r) / (BK / 4), a_valid - 1);
+        arow[r] = g.a_rows ? (int64_t)g.a_rows[gm] : gm;
+    }
+
     auto fetch = [&](int kt) {
         const bool second = kt >= nk1;
         const int k0 = (second ? kt - nk1 : kt) * BK;
@@ -154,13 +163,13 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
             if constexpr (VEC) {
                 const int64_t gm = lmin(m0 + m, g.M - 1);
                 const int kk = imin(k0 + 4 * kq, kpad - 4);
-                ra[r] = second ? ldg_raw4<float>(g.A2 + gm * g.lda2 + kk) : ldg_raw4<AT>((const AT*)g.A + gm * g.lda + kk);
+                ra[r] = second ? ldg_raw4<float>(g.A2 + gm * g.lda2 + kk)
+                               : ldg_raw4<AT>((const AT*)g.A + arow[r] * g.lda + kk);
             } else {
                 const int64_t gm = m0 + m;
-                const bool ok = gm < g.M;
-                const int64_t gmc = ok ? gm : 0;
-                ra[r] = second ? ldg_safe4<float>(g.A2 + gmc * g.lda2, ok, k0 + 4 * kq, Kc)
-                               : ldg_safe4<AT>((const AT*)g.A + gmc * g.lda, ok, k0 + 4 * kq, Kc);
+                const bool ok2 = gm < g.M, ok1 = gm < a_valid;
+                ra[r] = second ? ldg_safe4<float>(g.A2 + (ok2 ? gm : 0) * g.lda2, ok2, k0 + 4 * kq, Kc)
+                               : ldg_safe4<AT>((const AT*)g.A + arow[r] * g.lda, ok1, k0 + 4 * kq, Kc);
             }
         }
 #pragma unroll
@@ -190,7 +199,7 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
             const int m = f / (BK / 4), kq = f % (BK / 4);
             float v[4];
             unpack4(ra[r], VEC && A_BF16 && !second, v);
-            const bool row_ok = m0 + m < g.M;
+            const bool row_ok = m0 + m < (second ? g.M : a_valid);
 #pragma unroll
             for (int q = 0; q < 4; ++q)
                 As[(4 * kq + q) * PA + m] = (!VEC || (row_ok && k0 + 4 * kq + q < Kc)) ? v[q] : 0.f;
@@ -238,6 +247,9 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
                 if (col < g.N) {
                     v = acc[i][j][r] + bv;
                     if (g.addend) v += g.addend[m * g.ld_add + col];
+                }
+                if (g.C_raw) g.C_raw[m * g.ld_raw + col] = v;
+                if (col < g.N) {
                     if (g.rowscale) v *= g.rowscale[m];
                     if (g.relu) v = v > 0.f ? v : 0.f;
                     if (g.mask) v = g.mask[m * g.ld_mask + col] > 0.f ? v : 0.f;
@@ -367,10 +379,13 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
             const int m = f / (BKA / 4), cq = f % (BKA / 4);
             if constexpr (VEC) {
                 const int64_t gm = lmin(mt + m, g.M - 1);
-                ra[r] = ldg_raw4<AT>((const AT*)g.A + gm * g.lda + imin(ka0 + 4 * cq, kpad - 4));
+                const int64_t row = g.a_rows ? (int64_t)g.a_rows[gm] : gm;
+                ra[r] = ldg_raw4<AT>((const AT*)g.A + row * g.lda + imin(ka0 + 4 * cq, kpad - 4));
             } else {
                 const bool ok = mt + m < m_end;
-                ra[r] = ldg_safe4<AT>((const AT*)g.A + (ok ? mt + m : 0) * g.lda, ok, ka0 + 4 * cq, g.K);
+                const int64_t gm = ok ? mt + m : 0;
+                const int64_t row = (g.a_rows && ok) ? (int64_t)g.a_rows[gm] : gm;
+                ra[r] = ldg_safe4<AT>((const AT*)g.A + row * g.lda, ok, ka0 + 4 * cq, g.K);
             }
         }
 #pragma unroll

@@ -403,3 +403,90 @@ extern "C" grp_status grp_partition_destroy(grp_partition_t* part) {
     grp::free_partition(part);
     return GRP_OK;
 }
+
+// ------------------------------------------------------------------ shared device primitives
+namespace grp {
+
+size_t sort_keys_temp_bytes(int64_t count) {
+    size_t bytes = 0;
+    (void)rocprim::radix_sort_keys(nullptr, bytes, (const uint64_t*)nullptr, (uint64_t*)nullptr,
+                                   (size_t)(count > 0 ? count : 1), 0u, 64u, (hipStream_t)0);
+    return bytes + 256;
+}
+
+grp_status sort_keys_u64(void* temp, size_t temp_bytes, const uint64_t* in, uint64_t* out, int64_t count,
+                         unsigned end_bit, hipStream_t st) {
+    if (count <= 0) return GRP_OK;
+    size_t need = 0;
+    GRP_HIP(rocprim::radix_sort_keys(nullptr, need, in, out, (size_t)count, 0u, end_bit, st));
+    if (need > temp_bytes) return fail(GRP_EWORKSPACE, "sort temp %zu < %zu", temp_bytes, need);
+    GRP_HIP(rocprim::radix_sort_keys(temp, need, in, out, (size_t)count, 0u, end_bit, st));
+    return GRP_OK;
+}
+
+size_t scan_temp_bytes(int64_t count) {
+    size_t bytes = 0;
+    (void)rocprim::exclusive_scan(nullptr, bytes, (const int64_t*)nullptr, (int64_t*)nullptr, (int64_t)0,
+                                  (size_t)(count > 0 ? count : 1), rocprim::plus<int64_t>(), (hipStream_t)0);
+    return bytes + 256;
+}
+
+grp_status exclusive_scan_i64(void* temp, size_t temp_bytes, const int64_t* in, int64_t* out, int64_t count,
+                              hipStream_t st) {
+    if (count <= 0) return GRP_OK;
+    size_t need = 0;
+    GRP_HIP(rocprim::exclusive_scan(nullptr, need, in, out, (int64_t)0, (size_t)count, rocprim::plus<int64_t>(), st));
+    if (need > temp_bytes) return fail(GRP_EWORKSPACE, "scan temp %zu < %zu", temp_bytes, need);
+    GRP_HIP(rocprim::exclusive_scan(temp, need, in, out, (int64_t)0, (size_t)count, rocprim::plus<int64_t>(), st));
+    return GRP_OK;
+}
+
+grp_status exclusive_scan_i32(void* temp, size_t temp_bytes, const int32_t* in, int32_t* out, int64_t count,
+                              hipStream_t st) {
+    if (count <= 0) return GRP_OK;
+    size_t need = 0;
+    GRP_HIP(rocprim::exclusive_scan(nullptr, need, in, out, (int32_t)0, (size_t)count, rocprim::plus<int32_t>(), st));
+    if (need > temp_bytes) return fail(GRP_EWORKSPACE, "scan temp %zu < %zu", temp_bytes, need);
+    GRP_HIP(rocprim::exclusive_scan(temp, need, in, out, (int32_t)0, (size_t)count, rocprim::plus<int32_t>(), st));
+    return GRP_OK;
+}
+
+grp_status launch_csr_from_sorted_keys(const uint64_t* keys, int64_t nnz, int64_t n, int64_t* ptr, int32_t* idx,
+                                       hipStream_t st) {
+    hipLaunchKernelGGL(csr_from_keys_kernel, dim3(grid_for(nnz + 1)), dim3(256), 0, st, keys, nnz, n, ptr, idx);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
+grp_status build_long_rows_into(const int64_t* ptr_dev, int64_t n, LongRows* out, int64_t cap_long, int64_t cap_chunks,
+                                hipStream_t st) {
+    std::vector<int64_t> ptr((size_t)n + 1);
+    GRP_HIP(hipMemcpyAsync(ptr.data(), ptr_dev, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    GRP_HIP(hipStreamSynchronize(st));
+    std::vector<int32_t> rows, first;
+    std::vector<int64_t> cb, ce;
+    for (int64_t v = 0; v < n; ++v) {
+        const int64_t b = ptr[v], e = ptr[v + 1];
+        if (e - b <= SPMM_LONG_ROW) continue;
+        rows.push_back((int32_t)v);
+        first.push_back((int32_t)cb.size());
+        for (int64_t c = b; c < e; c += SPMM_CHUNK) {
+            cb.push_back(c);
+            ce.push_back(c + SPMM_CHUNK < e ? c + SPMM_CHUNK : e);
+        }
+    }
+    first.push_back((int32_t)cb.size());
+    if ((int64_t)rows.size() > cap_long || (int64_t)cb.size() > cap_chunks)
+        return fail(GRP_EWORKSPACE, "long-row schedule (%zu rows, %zu chunks) exceeds its buffers", rows.size(), cb.size());
+    out->n_long = (int32_t)rows.size();
+    out->n_chunks = (int32_t)cb.size();
+    if (out->n_long == 0) return GRP_OK;
+    GRP_HIP(hipMemcpyAsync(out->long_row, rows.data(), rows.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    GRP_HIP(hipMemcpyAsync(out->long_first, first.data(), first.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    GRP_HIP(hipMemcpyAsync(out->chunk_begin, cb.data(), cb.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    GRP_HIP(hipMemcpyAsync(out->chunk_end, ce.data(), ce.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    GRP_HIP(hipStreamSynchronize(st));     // the host vectors go out of scope
+    return GRP_OK;
+}
+
+}  // namespace grp

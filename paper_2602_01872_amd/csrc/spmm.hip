@@ -105,6 +105,10 @@ struct SpmmEpilogue {
     const float* bias;
     float* Y;
     int64_t ldy;
+    const float* residual;    // added after the ReLU (residual layers); null otherwise
+    int64_t ld_res;
+    float* Y2;                // receives the activation before the residual is added; null otherwise
+    int64_t ldy2;
 };
 
 template <typename XT>
@@ -123,6 +127,14 @@ __device__ __forceinline__ void finish_row(const SpmmEpilogue& ep, int64_t i, in
         } else {
             o[q] = 0.f;           // pad columns stay zero
         }
+    }
+    if (ep.Y2) *reinterpret_cast<float4*>(ep.Y2 + i * ep.ldy2 + col) = make_float4(o[0], o[1], o[2], o[3]);
+    if (ep.residual) {
+        const float4 h = *reinterpret_cast<const float4*>(ep.residual + i * ep.ld_res + col);
+        o[0] += h.x; o[1] += h.y; o[2] += h.z; o[3] += h.w;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (col + q >= ep.F) o[q] = 0.f;
     }
     *reinterpret_cast<float4*>(ep.Y + i * ep.ldy + col) = make_float4(o[0], o[1], o[2], o[3]);
 }
@@ -297,9 +309,15 @@ grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
     if (vec_ok) {
         if (a.long_rows && a.long_rows->n_long > 0 && (!a.partials || ((uintptr_t)a.partials % 16) != 0))
             return fail(GRP_EINVAL, "spmm: partition has long rows but no scratch for their partial sums");
-        SpmmEpilogue ep{a.scale, a.self_term, a.relu, a.F, a.addend, a.ld_add, a.bias, a.Y, a.ldy};
+        if (a.residual && (a.ld_res % 4 != 0 || a.ld_res < fpad || (uintptr_t)a.residual % 16 != 0))
+            return fail(GRP_EINVAL, "spmm: residual operand must be 16-byte aligned with a pitch multiple of 4");
+        if (a.Y2 && (a.ldy2 % 4 != 0 || a.ldy2 < fpad || (uintptr_t)a.Y2 % 16 != 0))
+            return fail(GRP_EINVAL, "spmm: second output must be 16-byte aligned with a pitch multiple of 4");
+        SpmmEpilogue ep{a.scale, a.self_term, a.relu, a.F, a.addend, a.ld_add, a.bias, a.Y, a.ldy,
+                        a.residual, a.ld_res, a.Y2, a.ldy2};
         GRP_TRY(a.x_bf16 ? dispatch<__hip_bfloat16>(a, ep, st) : dispatch<float>(a, ep, st));
     } else {
+        if (a.residual || a.Y2) return fail(GRP_EUNSUPPORTED, "spmm: residual epilogue needs 16-byte friendly operands");
         const int64_t blocks = cdiv(a.n_rows, 4);
         if (a.x_bf16)
             hipLaunchKernelGGL((spmm_rows_scalar_kernel<__hip_bfloat16>), dim3((unsigned)blocks), dim3(256), 0, st,

@@ -1,9 +1,12 @@
-// One isolated train step on one partition: forward, loss, backward, coverage statistics.
-// Host-side orchestration of the kernels in spmm.hip / gemm.hip / elementwise.hip on one
-// stream, with every intermediate carved out of the caller's workspace (no allocation, no
-// host synchronisation).
+// One isolated train step on one partition: (sampling,) forward, loss, backward, coverage
+// statistics.  Host-side orchestration of the kernels in sampler.hip / spmm.hip / gemm.hip /
+// elementwise.hip on one stream, with every intermediate carved out of the caller's
+// workspace (no allocation; full-graph mode never synchronises the stream, mini-batch mode
+// does once per layer above the input layer to learn the sampled block sizes).
 //
-// Per layer the neighbour aggregation runs at the narrower of the two widths (mean and the
+// Every layer is a bipartite block (common.h): in full-graph mode all layers share the
+// partition's CSR/CSC, in mini-batch mode each layer has its sampled block.  Per GraphSAGE
+// layer the neighbour aggregation runs at the narrower of the two widths (mean and the
 // linear map commute): "aggregate first" when Fin <= Fout, "transform first" otherwise.
 #include "common.h"
 
@@ -13,37 +16,26 @@ namespace grp {
 
 static inline int64_t ldp(int64_t f) { return round_up(f, 4); }
 
-struct Bump {
-    char* base;
-    size_t cap, off = 0;
-    bool measure;
-    Bump(void* b, size_t c) : base((char*)b), cap(c), measure(b == nullptr) {}
-    template <typename T> T* take(size_t count) {
-        off = (off + 255) & ~(size_t)255;
-        T* p = measure ? nullptr : (T*)(base + off);
-        off += count * sizeof(T);
-        return p;
-    }
-};
-
 struct LayerBufs {
     float* Wp_s = nullptr;   // [Fin x ld(Fout)] aligned copy of W_self (GCN: W)
     float* Wp_n = nullptr;   // same for W_neigh
     float* Wt_s = nullptr;   // [Fout x ld(Fin)] transpose of W_self
     float* Wt_n = nullptr;
-    float* M = nullptr;      // [n x ld(Fin)] aggregated input (aggregate-first SAGE layers)
-    float* H_out = nullptr;  // [n x ld(Fout)] layer output (post-ReLU; logits for the last layer)
+    float* M = nullptr;      // [rows x ld(Fin)] aggregated input (aggregate-first SAGE layers)
+    float* H_out = nullptr;  // [rows x ld(Fout)] layer output (post-activation; logits for the last layer)
+    float* Act = nullptr;    // [rows x ld(Fout)] ReLU(z) of a residual layer (its derivative mask)
     int64_t off_ws = 0, off_wn = 0, off_b = 0;
     bool agg_first = false;
+    bool skip = false;       // residual GCN: H_out = H_in + ReLU(z)
 };
 
 struct StepPlan {
     std::vector<LayerBufs> L;
     float *inv_in = nullptr, *gr = nullptr, *gs = nullptr, *grinv = nullptr;
-    float *tmpA = nullptr, *tmpB = nullptr, *dZa = nullptr, *dZb = nullptr;
-    void *tn_ws = nullptr, *colsum_ws = nullptr, *stats_ws = nullptr;
+    float *tmpA = nullptr, *tmpB = nullptr, *dZa = nullptr, *dZb = nullptr, *Ga = nullptr, *Gb = nullptr;
+    void *tn_ws = nullptr, *colsum_ws = nullptr, *stats_ws = nullptr, *sampler_ws = nullptr;
     float* partials = nullptr;   // partial rows of the split long rows (SpMM)
-    size_t tn_ws_bytes = 0;
+    size_t tn_ws_bytes = 0, sampler_bytes = 0;
     size_t total = 0;
 };
 
@@ -64,48 +56,73 @@ static int64_t param_count(const grp_model_desc* m) {
     return p;
 }
 
-// Carves (or, with a null base, measures) the workspace.
-static StepPlan make_plan(const grp_partition_t* part, const grp_model_desc* m, void* ws, size_t ws_bytes) {
+// Carves (or, with a null base, measures) the workspace.  Row counts are exact in full-graph
+// mode and upper bounds from the seeds and fanouts in mini-batch mode.
+static StepPlan make_plan(const grp_partition_t* part, const grp_model_desc* m, const grp_step_opts* o, void* ws,
+                          size_t ws_bytes) {
     StepPlan p;
     const int64_t n = part->n;
     Bump b(ws, ws_bytes);
     const int k = m->n_layers;
     const bool sage = m->arch == GRP_ARCH_SAGE_MEAN;
+    const bool mb = !o->full_graph;
+    SamplerBounds bd;
+    int64_t chunks_cap = part->csr_long.n_chunks > part->csc_long.n_chunks ? part->csr_long.n_chunks : part->csc_long.n_chunks;
+    if (mb) {
+        sampler_bounds(n, o->n_seeds, o->fanouts, k, &bd);
+        p.sampler_bytes = sampler_workspace_bytes(n, bd, k);
+        p.sampler_ws = b.take<char>(p.sampler_bytes);
+        chunks_cap = 0;
+        for (int l = 1; l < k; ++l) {
+            const int64_t c = bd.nnz[l] / SPMM_CHUNK + bd.nnz[l] / SPMM_LONG_ROW + 2;
+            if (c > chunks_cap) chunks_cap = c;
+        }
+    }
     p.L.resize(k);
-    int64_t off = 0, fmax = 0;
+    int64_t off = 0, fmax = 0, max_rows = 1;
     size_t tn_bytes = 0, cs_bytes = 0;
     for (int l = 0; l < k; ++l) {
         LayerBufs& L = p.L[l];
         const int fin = m->dims[l], fout = m->dims[l + 1];
+        const int64_t rows = mb ? bd.dst[l] : n;
+        const int64_t rows_in = mb ? (l == 0 ? bd.dst[0] : bd.src[l]) : n;
+        if (rows > max_rows) max_rows = rows;
+        if (rows_in > max_rows) max_rows = rows_in;
         L.off_ws = off; off += (int64_t)fin * fout;
         if (sage) { L.off_wn = off; off += (int64_t)fin * fout; }
         L.off_b = off; off += fout;
-        L.agg_first = sage && fin <= fout;
+        L.agg_first = sage && (fin <= fout || (mb && l == 0));
+        L.skip = m->arch == GRP_ARCH_GCN_RESIDUAL && fin == fout && l < k - 1;
         L.Wp_s = b.take<float>((size_t)fin * ldp(fout));
         L.Wt_s = b.take<float>((size_t)fout * ldp(fin));
         if (sage) {
             L.Wp_n = b.take<float>((size_t)fin * ldp(fout));
             L.Wt_n = b.take<float>((size_t)fout * ldp(fin));
-            if (L.agg_first) L.M = b.take<float>((size_t)n * ldp(fin));
+            if (L.agg_first) L.M = b.take<float>((size_t)rows * ldp(fin));
         }
-        L.H_out = b.take<float>((size_t)n * ldp(fout));
+        L.H_out = b.take<float>((size_t)rows * ldp(fout));
+        if (L.skip) L.Act = b.take<float>((size_t)rows * ldp(fout));
         if (ldp(fout) > fmax) fmax = ldp(fout);
         if (l > 0 && ldp(fin) > fmax) fmax = ldp(fin);
-        const size_t t = gemm_tn_workspace_bytes(n, fin, fout);
+        const size_t t = gemm_tn_workspace_bytes(rows_in > rows ? rows_in : rows, fin, fout);
         if (t > tn_bytes) tn_bytes = t;
-        const size_t c = colsum_workspace_bytes(n, fout);
+        const size_t c = colsum_workspace_bytes(rows, fout);
         if (c > cs_bytes) cs_bytes = c;
     }
-    p.inv_in = b.take<float>((size_t)n);
+    if (!mb) p.inv_in = b.take<float>((size_t)n);
     if (!sage) {
         p.gr = b.take<float>((size_t)n);
         p.gs = b.take<float>((size_t)n);
         p.grinv = b.take<float>((size_t)n);
     }
-    p.tmpA = b.take<float>((size_t)n * fmax);
-    p.tmpB = b.take<float>((size_t)n * fmax);
-    p.dZa = b.take<float>((size_t)n * fmax);
-    p.dZb = b.take<float>((size_t)n * fmax);
+    p.tmpA = b.take<float>((size_t)max_rows * fmax);
+    p.tmpB = b.take<float>((size_t)max_rows * fmax);
+    p.dZa = b.take<float>((size_t)max_rows * fmax);
+    p.dZb = b.take<float>((size_t)max_rows * fmax);
+    if (m->arch == GRP_ARCH_GCN_RESIDUAL) {
+        p.Ga = b.take<float>((size_t)max_rows * fmax);
+        p.Gb = b.take<float>((size_t)max_rows * fmax);
+    }
     p.tn_ws = b.take<char>(tn_bytes);
     p.tn_ws_bytes = tn_bytes;
     p.colsum_ws = b.take<char>(cs_bytes);
@@ -114,10 +131,9 @@ static StepPlan make_plan(const grp_partition_t* part, const grp_model_desc* m, 
         int64_t fsp = 0;
         for (int l = 0; l <= k; ++l)
             if (ldp(m->dims[l]) > fsp) fsp = ldp(m->dims[l]);
-        const int64_t chunks = part->csr_long.n_chunks > part->csc_long.n_chunks ? part->csr_long.n_chunks : part->csc_long.n_chunks;
-        p.partials = b.take<float>((size_t)chunks * fsp);
+        p.partials = b.take<float>((size_t)chunks_cap * fsp);
     }
-    p.total = (b.off + 255) & ~(size_t)255;
+    p.total = b.total();
     return p;
 }
 
@@ -126,28 +142,52 @@ static grp_status check_step_args(const grp_partition_t* part, const grp_model_d
     if (!valid_model(model)) return fail(GRP_EINVAL, "train_step: invalid model description");
     if (opts->estimator < GRP_EST_NONE || opts->estimator > GRP_EST_SHRINKAGE)
         return fail(GRP_EINVAL, "train_step: unknown estimator %d", opts->estimator);
-    if (!opts->full_graph) return fail(GRP_EUNSUPPORTED, "train_step: mini-batch mode is not implemented in this build");
-    if (model->arch == GRP_ARCH_GCN_RESIDUAL) return fail(GRP_EUNSUPPORTED, "train_step: residual GCN is not implemented in this build");
+    if (model->arch == GRP_ARCH_GCN_RESIDUAL && model->feat_dtype == GRP_DTYPE_BF16 && model->n_layers > 1 &&
+        model->dims[0] == model->dims[1])
+        return fail(GRP_EUNSUPPORTED, "train_step: a residual first layer needs fp32 features");
+    if (!opts->full_graph) {
+        if (model->arch != GRP_ARCH_SAGE_MEAN)
+            return fail(GRP_EUNSUPPORTED, "train_step: mini-batch mode is defined for GraphSAGE only");
+        if (opts->n_seeds < 1 || !opts->seeds) return fail(GRP_EINVAL, "train_step: mini-batch mode needs seed nodes");
+        for (int l = 0; l < model->n_layers; ++l)
+            if (opts->fanouts[l] < 1 || opts->fanouts[l] > 64)
+                return fail(GRP_EINVAL, "train_step: fanout %d outside [1, 64]", opts->fanouts[l]);
+    }
     return GRP_OK;
 }
 
-static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, const grp_step_opts* o, const void* X,
-                            const int32_t* labels, const uint8_t* mask, const float* theta, StepPlan& p, hipStream_t st,
-                            float* grad, grp_step_stats* stats) {
-    const int k = m->n_layers;
-    const int64_t n = g->n;
-    GRP_TRY(launch_degree_scales(g->d_local_in, g->d_local_out, n, 0, p.inv_in, nullptr, nullptr, nullptr, st));
-    for (int l = 0; l < k; ++l) {
+static void fill_spmm(SpmmArgs& s, const Block& B, bool transposed, float* partials) {
+    s.ptr = transposed ? B.ptrT : B.ptr;
+    s.idx = transposed ? B.idxT : B.idx;
+    s.nnz = B.nnz;
+    s.n_rows = transposed ? B.n_in : B.n_dst;
+    s.n_src = transposed ? B.n_dst : B.n_in;
+    s.long_rows = transposed ? B.long_bwd : B.long_fwd;
+    s.partials = partials;
+}
+
+static grp_status prep_weights(const grp_model_desc* m, const float* theta, StepPlan& p, hipStream_t st) {
+    const bool sage = m->arch == GRP_ARCH_SAGE_MEAN;
+    for (int l = 0; l < m->n_layers; ++l) {
         const LayerBufs& L = p.L[l];
         const int fin = m->dims[l], fout = m->dims[l + 1];
         GRP_TRY(launch_pad_copy(theta + L.off_ws, fin, fout, L.Wp_s, ldp(fout), st));
-        GRP_TRY(launch_pad_copy(theta + L.off_wn, fin, fout, L.Wp_n, ldp(fout), st));
+        if (sage) GRP_TRY(launch_pad_copy(theta + L.off_wn, fin, fout, L.Wp_n, ldp(fout), st));
         if (l > 0) {
             GRP_TRY(launch_transpose(theta + L.off_ws, fin, fout, L.Wt_s, ldp(fin), fout, st));
-            GRP_TRY(launch_transpose(theta + L.off_wn, fin, fout, L.Wt_n, ldp(fin), fout, st));
+            if (sage) GRP_TRY(launch_transpose(theta + L.off_wn, fin, fout, L.Wt_n, ldp(fin), fout, st));
         }
     }
-    GRP_TRY(launch_stats(n, nullptr, mask, g->d_local_in, g->d_global_in, nullptr, g->nnz, p.stats_ws, stats, st));
+    return GRP_OK;
+}
+
+// GraphSAGE-mean forward + loss + backward over k blocks.  X is the input of block 0
+// (the partition's feature matrix); loss rows are block k-1's destinations.
+static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, const grp_step_opts* o, const Block* blk,
+                            const void* X, const int32_t* labels, const uint8_t* mask, const int32_t* loss_nodes,
+                            const float* theta, StepPlan& p, hipStream_t st, float* grad, grp_step_stats* stats) {
+    const int k = m->n_layers;
+    GRP_TRY(prep_weights(m, theta, p, st));
 
     // ---------------- forward
     const void* H = X;
@@ -155,28 +195,32 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
     int h_bf16 = m->feat_dtype == GRP_DTYPE_BF16;
     for (int l = 0; l < k; ++l) {
         const LayerBufs& L = p.L[l];
+        const Block& B = blk[l];
         const int fin = m->dims[l], fout = m->dims[l + 1];
         const int relu = l < k - 1;
+        if (B.n_dst == 0) { H = L.H_out; ldh = ldp(fout); h_bf16 = 0; continue; }
         if (L.agg_first) {
             SpmmArgs s;
-            s.ptr = g->rowptr; s.idx = g->col; s.nnz = g->nnz; s.long_rows = &g->csr_long; s.partials = p.partials; s.n_rows = n; s.F = fin; s.X = H; s.ldx = ldh; s.x_bf16 = h_bf16;
-            s.scale = GRP_SCALE_MEAN; s.Y = L.M; s.ldy = ldp(fin);
+            fill_spmm(s, B, false, p.partials);
+            s.F = fin; s.X = H; s.ldx = ldh; s.x_bf16 = h_bf16; s.scale = GRP_SCALE_MEAN; s.Y = L.M; s.ldy = ldp(fin);
             GRP_TRY(launch_spmm(s, st));
             GemmNNArgs a;
-            a.M = n; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.B = L.Wp_s; a.ldb = ldp(fout);
+            a.M = B.n_dst; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.a_rows = B.self_rows;
+            a.B = L.Wp_s; a.ldb = ldp(fout);
             a.K2 = fin; a.A2 = L.M; a.lda2 = ldp(fin); a.B2 = L.Wp_n; a.ldb2 = ldp(fout);
             a.bias = theta + L.off_b; a.relu = relu; a.C = L.H_out; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
             GRP_TRY(launch_gemm_nn(a, st));
         } else {
-            GemmNNArgs a;
-            a.M = n; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.B = L.Wp_n; a.ldb = ldp(fout);
+            GemmNNArgs a;      // T = H Wn over every input row, Z0 = H_self Ws + b
+            a.M = B.n_in; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.B = L.Wp_n; a.ldb = ldp(fout);
             a.C = p.tmpA; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
             GRP_TRY(launch_gemm_nn(a, st));
-            a.B = L.Wp_s; a.bias = theta + L.off_b; a.C = L.H_out;
+            a.M = B.n_dst; a.a_rows = B.self_rows; a.B = L.Wp_s; a.bias = theta + L.off_b; a.C = L.H_out;
             GRP_TRY(launch_gemm_nn(a, st));
             SpmmArgs s;
-            s.ptr = g->rowptr; s.idx = g->col; s.nnz = g->nnz; s.long_rows = &g->csr_long; s.partials = p.partials; s.n_rows = n; s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout);
-            s.scale = GRP_SCALE_MEAN; s.addend = L.H_out; s.ld_add = ldp(fout); s.relu = relu; s.Y = L.H_out; s.ldy = ldp(fout);
+            fill_spmm(s, B, false, p.partials);
+            s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout); s.scale = GRP_SCALE_MEAN;
+            s.addend = L.H_out; s.ld_add = ldp(fout); s.relu = relu; s.Y = L.H_out; s.ldy = ldp(fout);
             GRP_TRY(launch_spmm(s, st));
         }
         H = L.H_out; ldh = ldp(fout); h_bf16 = 0;
@@ -184,51 +228,59 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
 
     // ---------------- loss
     const int C = m->dims[k];
+    const int64_t n_loss_rows = blk[k - 1].n_dst;
     float* dZ = p.dZa;
     float* dZ_other = p.dZb;
-    GRP_TRY(launch_softmax_xent(n, C, p.L[k - 1].H_out, ldp(C), labels, nullptr, mask, o->estimator == GRP_EST_NODE_LEVEL,
-                                g->d_local_in, g->d_global_in, nullptr, dZ, ldp(C), p.stats_ws, stats, st));
+    GRP_TRY(launch_softmax_xent(n_loss_rows, C, p.L[k - 1].H_out, ldp(C), labels, loss_nodes, mask,
+                                o->estimator == GRP_EST_NODE_LEVEL, g->d_local_in, g->d_global_in, nullptr, dZ, ldp(C),
+                                p.stats_ws, stats, st));
 
     // ---------------- backward
     for (int l = k - 1; l >= 0; --l) {
         const LayerBufs& L = p.L[l];
+        const Block& B = blk[l];
         const int fin = m->dims[l], fout = m->dims[l + 1];
         const void* Hin = l == 0 ? X : (const void*)p.L[l - 1].H_out;
         const int64_t ldin = l == 0 ? m->dims[0] : ldp(fin);
         const int in_bf16 = l == 0 && m->feat_dtype == GRP_DTYPE_BF16;
-        GRP_TRY(launch_colsum(dZ, n, fout, ldp(fout), grad + L.off_b, p.colsum_ws, st));
-        GemmTNArgs t;
-        t.M = n; t.K = fin; t.N = fout; t.A = Hin; t.lda = ldin; t.a_bf16 = in_bf16; t.B = dZ; t.ldb = ldp(fout);
-        t.C = grad + L.off_ws; t.ldc = fout; t.workspace = p.tn_ws; t.workspace_bytes = p.tn_ws_bytes;
+        GRP_TRY(launch_colsum(dZ, B.n_dst, fout, ldp(fout), grad + L.off_b, p.colsum_ws, st));
+        GemmTNArgs t;      // dW_self = H_self^T dZ
+        t.M = B.n_dst; t.K = fin; t.N = fout; t.A = Hin; t.lda = ldin; t.a_bf16 = in_bf16; t.a_rows = B.self_rows;
+        t.B = dZ; t.ldb = ldp(fout); t.C = grad + L.off_ws; t.ldc = fout; t.workspace = p.tn_ws; t.workspace_bytes = p.tn_ws_bytes;
         GRP_TRY(launch_gemm_tn(t, st));
         if (L.agg_first) {
-            t.A = L.M; t.lda = ldp(fin); t.a_bf16 = 0; t.C = grad + L.off_wn;
+            t.A = L.M; t.lda = ldp(fin); t.a_bf16 = 0; t.a_rows = nullptr; t.C = grad + L.off_wn;
             GRP_TRY(launch_gemm_tn(t, st));
-            if (l > 0) {
-                GemmNNArgs a;      // dM' = (dZ Wn^T) / d_in
-                a.M = n; a.N = fin; a.K = fout; a.A = dZ; a.lda = ldp(fout); a.B = L.Wt_n; a.ldb = ldp(fin);
-                a.rowscale = p.inv_in; a.C = p.tmpA; a.ldc = ldp(fin); a.zero_pad_to = (int)ldp(fin);
-                GRP_TRY(launch_gemm_nn(a, st));
-                SpmmArgs s;        // P = A^T dM'
-                s.ptr = g->colptr; s.idx = g->row; s.nnz = g->nnz; s.long_rows = &g->csc_long; s.partials = p.partials; s.n_rows = n; s.F = fin; s.X = p.tmpA; s.ldx = ldp(fin);
-                s.Y = p.tmpB; s.ldy = ldp(fin);
+            if (l > 0 && B.n_in > 0) {
+                if (B.n_dst > 0) {
+                    GemmNNArgs a;      // dM' = (dZ Wn^T) / |N_v|
+                    a.M = B.n_dst; a.N = fin; a.K = fout; a.A = dZ; a.lda = ldp(fout); a.B = L.Wt_n; a.ldb = ldp(fin);
+                    a.rowscale = B.inv_in; a.C = p.tmpA; a.ldc = ldp(fin); a.zero_pad_to = (int)ldp(fin);
+                    GRP_TRY(launch_gemm_nn(a, st));
+                }
+                SpmmArgs s;        // P = A^T dM'  over the block's inputs
+                fill_spmm(s, B, true, p.partials);
+                s.F = fin; s.X = p.tmpA; s.ldx = ldp(fin); s.Y = p.tmpB; s.ldy = ldp(fin);
                 GRP_TRY(launch_spmm(s, st));
-                GemmNNArgs c;      // dZ_prev = mask * (dZ Ws^T + P)
-                c.M = n; c.N = fin; c.K = fout; c.A = dZ; c.lda = ldp(fout); c.B = L.Wt_s; c.ldb = ldp(fin);
+                GemmNNArgs c;      // dZ_prev = mask * ([dZ Ws^T ; 0] + P)
+                c.M = B.n_in; c.N = fin; c.K = fout; c.A = dZ; c.lda = ldp(fout); c.a_valid_rows = B.n_dst;
+                c.B = L.Wt_s; c.ldb = ldp(fin);
                 c.addend = p.tmpB; c.ld_add = ldp(fin); c.mask = p.L[l - 1].H_out; c.ld_mask = ldp(fin);
                 c.C = dZ_other; c.ldc = ldp(fin); c.zero_pad_to = (int)ldp(fin);
                 GRP_TRY(launch_gemm_nn(c, st));
             }
         } else {
-            SpmmArgs s;            // dT = A^T (dZ / d_in)
-            s.ptr = g->colptr; s.idx = g->row; s.nnz = g->nnz; s.long_rows = &g->csc_long; s.partials = p.partials; s.n_rows = n; s.F = fout; s.X = dZ; s.ldx = ldp(fout);
-            s.colscale = p.inv_in; s.Y = p.tmpA; s.ldy = ldp(fout);
+            SpmmArgs s;            // dT = A^T (dZ / |N_v|)  over the block's inputs
+            fill_spmm(s, B, true, p.partials);
+            s.F = fout; s.X = dZ; s.ldx = ldp(fout); s.colscale = B.inv_in; s.Y = p.tmpA; s.ldy = ldp(fout);
             GRP_TRY(launch_spmm(s, st));
+            t.M = B.n_in; t.A = Hin; t.lda = ldin; t.a_bf16 = in_bf16; t.a_rows = nullptr;
             t.B = p.tmpA; t.C = grad + L.off_wn;
             GRP_TRY(launch_gemm_tn(t, st));
-            if (l > 0) {
-                GemmNNArgs c;      // dZ_prev = mask * (dZ Ws^T + dT Wn^T)
-                c.M = n; c.N = fin; c.K = fout; c.A = dZ; c.lda = ldp(fout); c.B = L.Wt_s; c.ldb = ldp(fin);
+            if (l > 0 && B.n_in > 0) {
+                GemmNNArgs c;      // dZ_prev = mask * ([dZ Ws^T ; 0] + dT Wn^T)
+                c.M = B.n_in; c.N = fin; c.K = fout; c.A = dZ; c.lda = ldp(fout); c.a_valid_rows = B.n_dst;
+                c.B = L.Wt_s; c.ldb = ldp(fin);
                 c.K2 = fout; c.A2 = p.tmpA; c.lda2 = ldp(fout); c.B2 = L.Wt_n; c.ldb2 = ldp(fin);
                 c.mask = p.L[l - 1].H_out; c.ld_mask = ldp(fin);
                 c.C = dZ_other; c.ldc = ldp(fin); c.zero_pad_to = (int)ldp(fin);
@@ -240,6 +292,11 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
     return GRP_OK;
 }
 
+// GCN / residual GCN, full-graph mode.
+//   forward:  T' = diag(s) (H W);  A = ReLU(diag(r) (Adj T' + sl T') + b);  H' = A (+ H on a residual layer)
+//   backward: with G = dL/dH' and dZ' = diag(r) (A > 0) G:
+//             db = 1^T diag(1/r) dZ';  dT = diag(s) (Adj^T dZ' + sl dZ');  dW = H^T dT;
+//             G_in = dT W^T (+ G on a residual layer)
 static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, const grp_step_opts* o, const void* X,
                            const int32_t* labels, const uint8_t* mask, const float* theta, StepPlan& p, hipStream_t st,
                            float* grad, grp_step_stats* stats) {
@@ -247,19 +304,15 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
     const int64_t n = g->n;
     const int sl = m->gcn_self_loops ? 1 : 0;
     GRP_TRY(launch_degree_scales(g->d_local_in, g->d_local_out, n, sl, nullptr, p.gr, p.gs, p.grinv, st));
-    for (int l = 0; l < k; ++l) {
-        const LayerBufs& L = p.L[l];
-        const int fin = m->dims[l], fout = m->dims[l + 1];
-        GRP_TRY(launch_pad_copy(theta + L.off_ws, fin, fout, L.Wp_s, ldp(fout), st));
-        if (l > 0) GRP_TRY(launch_transpose(theta + L.off_ws, fin, fout, L.Wt_s, ldp(fin), fout, st));
-    }
-    GRP_TRY(launch_stats(n, nullptr, mask, g->d_local_in, g->d_global_in, nullptr, g->nnz, p.stats_ws, stats, st));
+    GRP_TRY(prep_weights(m, theta, p, st));
+    Block B;
+    B.n_dst = B.n_in = n; B.nnz = g->nnz; B.ptr = g->rowptr; B.idx = g->col; B.ptrT = g->colptr; B.idxT = g->row;
+    B.long_fwd = &g->csr_long; B.long_bwd = &g->csc_long;
 
-    // forward: T' = diag(s) (H W);  H' = ReLU(diag(r) (A T' + sl T') + b)
     const void* H = X;
     int64_t ldh = m->dims[0];
     int h_bf16 = m->feat_dtype == GRP_DTYPE_BF16;
-    for (int l = 0; l < k; ++l) {
+    for (int l = 0; l < k && n > 0; ++l) {
         const LayerBufs& L = p.L[l];
         const int fin = m->dims[l], fout = m->dims[l + 1];
         GemmNNArgs a;
@@ -267,21 +320,22 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
         a.rowscale = p.gs; a.C = p.tmpA; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
         GRP_TRY(launch_gemm_nn(a, st));
         SpmmArgs s;
-        s.ptr = g->rowptr; s.idx = g->col; s.nnz = g->nnz; s.long_rows = &g->csr_long; s.partials = p.partials; s.n_rows = n; s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout);
-        s.scale = GRP_SCALE_RSQRT; s.self_term = sl; s.bias = theta + L.off_b; s.relu = l < k - 1;
-        s.Y = L.H_out; s.ldy = ldp(fout);
+        fill_spmm(s, B, false, p.partials);
+        s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout); s.scale = GRP_SCALE_RSQRT; s.self_term = sl;
+        s.bias = theta + L.off_b; s.relu = l < k - 1; s.Y = L.H_out; s.ldy = ldp(fout);
+        if (L.skip) { s.residual = (const float*)H; s.ld_res = ldh; s.Y2 = L.Act; s.ldy2 = ldp(fout); }
         GRP_TRY(launch_spmm(s, st));
         H = L.H_out; ldh = ldp(fout); h_bf16 = 0;
     }
 
-    // loss: dZ' = diag(r) dZ
     const int C = m->dims[k];
-    float* dZ = p.dZa;
+    float* dZ = p.dZa;          // dZ' of the current layer
     float* dZ_other = p.dZb;
+    float* G = p.Ga;            // dL/dH' of the current layer (residual models only)
+    float* G_other = p.Gb;
     GRP_TRY(launch_softmax_xent(n, C, p.L[k - 1].H_out, ldp(C), labels, nullptr, mask, o->estimator == GRP_EST_NODE_LEVEL,
                                 g->d_local_in, g->d_global_in, p.gr, dZ, ldp(C), p.stats_ws, stats, st));
 
-    // backward: dT = diag(s) (A^T dZ' + sl dZ');  dW = H^T dT;  db = 1^T dZ;  dZ'_prev = diag(r) mask (dT W^T)
     for (int l = k - 1; l >= 0; --l) {
         const LayerBufs& L = p.L[l];
         const int fin = m->dims[l], fout = m->dims[l + 1];
@@ -290,19 +344,23 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
         const int in_bf16 = l == 0 && m->feat_dtype == GRP_DTYPE_BF16;
         GRP_TRY(launch_colsum_scaled(dZ, n, fout, ldp(fout), p.grinv, grad + L.off_b, p.colsum_ws, st));
         SpmmArgs s;
-        s.ptr = g->colptr; s.idx = g->row; s.nnz = g->nnz; s.long_rows = &g->csc_long; s.partials = p.partials; s.n_rows = n; s.F = fout; s.X = dZ; s.ldx = ldp(fout);
-        s.scale = GRP_SCALE_RSQRT; s.self_term = sl; s.Y = p.tmpA; s.ldy = ldp(fout);
+        fill_spmm(s, B, true, p.partials);
+        s.F = fout; s.X = dZ; s.ldx = ldp(fout); s.scale = GRP_SCALE_RSQRT; s.self_term = sl; s.Y = p.tmpA; s.ldy = ldp(fout);
         GRP_TRY(launch_spmm(s, st));
         GemmTNArgs t;
         t.M = n; t.K = fin; t.N = fout; t.A = Hin; t.lda = ldin; t.a_bf16 = in_bf16; t.B = p.tmpA; t.ldb = ldp(fout);
         t.C = grad + L.off_ws; t.ldc = fout; t.workspace = p.tn_ws; t.workspace_bytes = p.tn_ws_bytes;
         GRP_TRY(launch_gemm_tn(t, st));
-        if (l > 0) {
-            GemmNNArgs c;
+        if (l > 0 && n > 0) {
+            const LayerBufs& Lp = p.L[l - 1];
+            GemmNNArgs c;      // G_in = dT W^T (+ G);  dZ'_prev = diag(r) (A_prev > 0) G_in
             c.M = n; c.N = fin; c.K = fout; c.A = p.tmpA; c.lda = ldp(fout); c.B = L.Wt_s; c.ldb = ldp(fin);
-            c.rowscale = p.gr; c.mask = p.L[l - 1].H_out; c.ld_mask = ldp(fin);
+            if (L.skip) { c.addend = G; c.ld_add = ldp(fout); }
+            if (Lp.skip) { c.C_raw = G_other; c.ld_raw = ldp(fin); }
+            c.rowscale = p.gr; c.mask = Lp.skip ? Lp.Act : Lp.H_out; c.ld_mask = ldp(fin);
             c.C = dZ_other; c.ldc = ldp(fin); c.zero_pad_to = (int)ldp(fin);
             GRP_TRY(launch_gemm_nn(c, st));
+            float* sg = G; G = G_other; G_other = sg;
         }
         float* sw = dZ; dZ = dZ_other; dZ_other = sw;
     }
@@ -322,7 +380,7 @@ extern "C" grp_status grp_step_workspace_bytes(const grp_partition_t* part, cons
     if (!bytes) return fail(GRP_EINVAL, "grp_step_workspace_bytes: null output");
     *bytes = 0;
     GRP_TRY(check_step_args(part, model, opts));
-    *bytes = make_plan(part, model, nullptr, 0).total;
+    *bytes = make_plan(part, model, opts, nullptr, 0).total;
     return GRP_OK;
 }
 
@@ -334,13 +392,42 @@ extern "C" grp_status grp_train_step(const grp_partition_t* part, const grp_mode
     GRP_TRY(check_step_args(part, model, opts));
     if (!weights || !grad_out || !stats_out) return fail(GRP_EINVAL, "train_step: null weights / grad_out / stats_out");
     if (part->n > 0 && (!features || !labels)) return fail(GRP_EINVAL, "train_step: null features or labels");
-    StepPlan need = make_plan(part, model, nullptr, 0);
+    StepPlan need = make_plan(part, model, opts, nullptr, 0);
     if (!workspace || workspace_bytes < need.total)
         return fail(GRP_EWORKSPACE, "train_step: workspace %zu bytes, need %zu", workspace_bytes, need.total);
     if ((uintptr_t)workspace % 256 != 0) return fail(GRP_EINVAL, "train_step: workspace must be 256-byte aligned");
-    StepPlan p = make_plan(part, model, workspace, workspace_bytes);
+    StepPlan p = make_plan(part, model, opts, workspace, workspace_bytes);
     hipStream_t st = (hipStream_t)stream;
-    if (model->arch == GRP_ARCH_SAGE_MEAN)
-        return sage_step(part, model, opts, features, labels, train_mask, weights, p, st, grad_out, stats_out);
-    return gcn_step(part, model, opts, features, labels, train_mask, weights, p, st, grad_out, stats_out);
+    const int k = model->n_layers;
+    const int64_t n = part->n;
+
+    if (model->arch != GRP_ARCH_SAGE_MEAN) {
+        GRP_TRY(launch_stats(n, nullptr, train_mask, part->d_local_in, part->d_global_in, nullptr, part->nnz, nullptr, 0,
+                             p.stats_ws, stats_out, st));
+        return gcn_step(part, model, opts, features, labels, train_mask, weights, p, st, grad_out, stats_out);
+    }
+
+    Block blocks[GRP_MAX_LAYERS];
+    if (opts->full_graph) {
+        GRP_TRY(launch_degree_scales(part->d_local_in, part->d_local_out, n, 0, p.inv_in, nullptr, nullptr, nullptr, st));
+        for (int l = 0; l < k; ++l) {
+            Block& B = blocks[l];
+            B.n_dst = B.n_in = n; B.nnz = part->nnz; B.ptr = part->rowptr; B.idx = part->col;
+            B.ptrT = part->colptr; B.idxT = part->row; B.long_fwd = &part->csr_long; B.long_bwd = &part->csc_long;
+            B.inv_in = p.inv_in;
+        }
+        GRP_TRY(launch_stats(n, nullptr, train_mask, part->d_local_in, part->d_global_in, nullptr, part->nnz, nullptr, 0,
+                             p.stats_ws, stats_out, st));
+        return sage_step(part, model, opts, blocks, features, labels, train_mask, nullptr, weights, p, st, grad_out,
+                         stats_out);
+    }
+
+    // mini-batch: isolated sampling, then the same layers over the sampled blocks
+    LongRows long_bwd[GRP_MAX_LAYERS];
+    const int64_t* nnz_parts[GRP_MAX_LAYERS];
+    const int32_t* seed_counts = nullptr;
+    GRP_TRY(sample_blocks(part, opts, k, p.sampler_ws, p.sampler_bytes, blocks, long_bwd, nnz_parts, &seed_counts, st));
+    GRP_TRY(launch_stats(opts->n_seeds, opts->seeds, nullptr, part->d_local_in, part->d_global_in, seed_counts, 0, nnz_parts,
+                         k, p.stats_ws, stats_out, st));
+    return sage_step(part, model, opts, blocks, features, labels, nullptr, opts->seeds, weights, p, st, grad_out, stats_out);
 }

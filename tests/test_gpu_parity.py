@@ -371,3 +371,92 @@ def test_aggregate_invariants(g):
         G, oc = ocov.aggregate(og, ost, variant)
         assert rel_err(c.cpu().numpy(), oc) <= TOL_FP32
         assert rel_err(upd.cpu().numpy(), G) <= TOL_FP32
+
+
+# ----------------------------------------------------------------------------- mini-batch + residual GCN
+@pytest.mark.parametrize("dims,fanouts,bf16,n_seeds", [
+    ([32, 48, 6], (4, 3), False, 200),
+    ([128, 256, 256, 172], (15, 10, 5), True, 1024),
+    ([40, 24, 24, 5], (6, 5, 64), False, 333),
+])
+def test_minibatch_train_step_matches_oracle(g, dims, fanouts, bf16, n_seeds):
+    """Isolated k-hop sampling + SAGE step on the sampled blocks: the sampled structure is
+    integer work (edge count, |S|, per-seed sampled counts enter R), the gradient fp32."""
+    _note(f"minibatch dims={dims} fanouts={fanouts} bf16={bf16} seeds={n_seeds}")
+    scale, E, K = 14, 600000, 2
+    N = 1 << scale
+    s, d = synth.rmat_graph(scale, E, seed=2602018723, device=DEV)
+    part = g.grp_partition(s, d, N, K, 1, 0)
+    op = ograph.partition(s.cpu().numpy(), d.cpu().numpy(), N, K, 1, 0)
+    n = part.n
+    dl = op["d_local_in"]
+    assert dl.max() > 2000                                     # a hub row: the threshold path of the sampler
+    # seeds: the hub, an isolated node, and a seeded spread of others (distinct)
+    order = np.argsort(synth.stream_bits(5, 77, torch.arange(n)).numpy(), kind="stable")
+    hub, iso = int(dl.argmax()), int(np.flatnonzero(dl == 0)[0])
+    rest = [int(v) for v in order if v not in (hub, iso)][:n_seeds - 2]
+    seeds = np.array([hub, iso] + rest, dtype=np.int32)
+    x, y, theta = make_inputs(n, dims, "sage", 21, bf16=bf16)
+    model = g.model_desc(g.ARCH_SAGE_MEAN, dims, g.DTYPE_BF16 if bf16 else g.DTYPE_FP32)
+    for est, batch in ((0, 0), (1, 3)):
+        seeds_dev = torch.from_numpy(seeds).to(DEV)
+        opts = g.step_opts(estimator=est, full_graph=False, seeds=seeds_dev, fanouts=fanouts, sampler_seed=7, batch_id=batch)
+        P = g.grp_param_count(model)
+        ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+        grad = torch.full((P,), float("nan"), device=DEV)
+        stats = g.new_stats(1)
+        g.grp_train_step(part, model, opts, x.to(DEV), y.to(DEV), None, theta.to(DEV), ws, grad, stats)
+        torch.cuda.synchronize()
+        mb = dict(seeds=seeds, fanouts=fanouts, sampler_seed=7, batch_id=batch)
+
+        def oracle_fn(relu_flip=None, near_kink=None, est=est, mb=mb):
+            return ostep.train_step(op, "sage", dims, theta.double().numpy(), x.double().numpy(), y.numpy(),
+                                    estimator=est, minibatch=mb, relu_flip=relu_flip, near_kink=near_kink)
+        og, ost = assert_step_grads_close(grad.cpu().numpy(), oracle_fn, "sage", dims, TOL_FP32)
+        st = g.read_stats(stats)[0]
+        assert int(st["S"]) == ost["S"] == n_seeds
+        assert int(st["nnz_used"]) == ost["nnz_used"]           # same sampled edge multiset size
+        assert abs(float(st["R"]) - ost["R"]) <= 1e-9 * max(1.0, ost["R"])
+        assert abs(float(st["sum_ratio"]) - ost["sum_ratio"]) <= 1e-9 * max(1.0, ost["sum_ratio"])
+        assert abs(float(st["loss"]) - ost["loss"]) <= TOL_FP32 * abs(ost["loss"])
+
+
+def test_minibatch_is_bit_reproducible_and_batch_dependent(g):
+    _note("minibatch determinism")
+    scale, E = 13, 200000
+    s, d = synth.rmat_graph(scale, E, seed=3, device=DEV)
+    part = g.grp_partition(s, d, 1 << scale, 2, 1, 1)
+    dims = [16, 32, 4]
+    x, y, theta = make_inputs(part.n, dims, "sage", 2)
+    model = g.model_desc(g.ARCH_SAGE_MEAN, dims)
+    seeds = torch.arange(0, 512, dtype=torch.int32, device=DEV)
+    outs = []
+    for batch in (0, 0, 1):
+        opts = g.step_opts(full_graph=False, seeds=seeds, fanouts=(5, 5), sampler_seed=9, batch_id=batch)
+        ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+        grad = torch.zeros(g.grp_param_count(model), device=DEV)
+        stats = g.new_stats(1)
+        g.grp_train_step(part, model, opts, x.to(DEV), y.to(DEV), None, theta.to(DEV), ws, grad, stats)
+        torch.cuda.synchronize()
+        outs.append(grad.clone())
+    assert torch.equal(outs[0], outs[1])
+    assert not torch.equal(outs[0], outs[2])
+
+
+@pytest.mark.parametrize("dims,self_loops", [([24, 40, 40, 40, 6], True), ([32, 32, 32, 5], False),
+                                             ([128, 256, 256, 256, 64], True)])
+def test_residual_gcn_matches_oracle(g, dims, self_loops):
+    _note(f"residual gcn dims={dims} sl={self_loops}")
+    scale, E, K = 13, 250000, 2
+    N = 1 << scale
+    s, d = synth.rmat_graph(scale, E, seed=2602018724, device=DEV)
+    part = g.grp_partition(s, d, N, K, 1, 1)
+    op = ograph.partition(s.cpu().numpy(), d.cpu().numpy(), N, K, 1, 1)
+    x, y, theta = make_inputs(part.n, dims, "gcn_res", 31)
+    grad, stats = _run_step(g, part, "gcn_res", dims, x.to(DEV), y.to(DEV), theta.to(DEV), self_loops=self_loops)
+
+    def oracle_fn(relu_flip=None, near_kink=None):
+        return ostep.train_step(op, "gcn_res", dims, theta.double().numpy(), x.double().numpy(), y.numpy(),
+                                gcn_self_loops=self_loops, relu_flip=relu_flip, near_kink=near_kink)
+    og, ost = assert_step_grads_close(grad.cpu().numpy(), oracle_fn, "gcn_res", dims, TOL_FP32)
+    _check_stats(g.read_stats(stats)[0], ost, TOL_FP32)
