@@ -46,6 +46,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--small", action="store_true", help="scaled-down graph (debugging only; not a valid result)")
+    ap.add_argument("--shapes", action="store_true", help="per-launch-shape kernel table on stderr (debugging)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (partitions are processed in turn); "
@@ -122,7 +123,7 @@ def main():
     log(f"{ms_per_step:.3f} ms/step, {edges_per_s:.3e} edges/s (n={part.n}, nnz={nnz})")
 
     # per-kernel pass: same steps with every launch bracketed by HIP events on the launch stream
-    g.grp_profile_enable(True)
+    g.grp_profile_enable(2 if args.shapes else 1)
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()

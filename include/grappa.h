@@ -238,7 +238,7 @@ grp_status grp_gemm_tn(int64_t M, int32_t K, int32_t N, const void* A, int64_t l
  * per kernel name into buf (HOST, NUL-terminated, truncated to cap) and clears the
  * records.  flops/bytes are the algorithmic work of the launches (operand and result
  * sizes, 2*M*N*K), not measured traffic.                                              */
-grp_status grp_profile_enable(int32_t on);
+grp_status grp_profile_enable(int32_t on);   /* 0 off, 1 per kernel name, 2 names carry the launch shape */
 grp_status grp_profile_report(char* buf, size_t cap);
 
 #ifdef __cplusplus

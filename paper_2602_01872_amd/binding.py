@@ -236,8 +236,8 @@ def grp_gemm_tn(M, K, N, A, lda, a_dtype, B, ldb, Cm, ldc, workspace, stream=Non
                               _stream(stream)))
 
 
-def grp_profile_enable(on: bool):
-    _check(load().grp_profile_enable(1 if on else 0))
+def grp_profile_enable(on):
+    _check(load().grp_profile_enable(int(on)))
 
 
 def grp_profile_report() -> dict:

@@ -38,6 +38,8 @@ grp_status fail(grp_status code, const char* fmt, ...);
 // move, not what the kernel happens to touch); summed per kernel name in the report.
 void prof_begin(const char* name, hipStream_t st, double flops, double bytes);
 void prof_end(hipStream_t st);
+// Optional shape suffix for the next prof_begin on this thread (only with profile mode 2).
+void prof_detail(const char* fmt, ...);
 
 struct ProfScope {
     hipStream_t st;

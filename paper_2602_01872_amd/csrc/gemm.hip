@@ -109,8 +109,14 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
     constexpr int B_REPS = (BN * BK / 4 + 255) / 256;
     constexpr bool A_BF16 = sizeof(AT) == 2;
     static_assert(BM * BK / 4 % 256 == 0, "A tile must fill the workgroup");
-    __shared__ float As_[NBUF][BK * PA];
-    __shared__ __attribute__((aligned(16))) float Bs_[NBUF][BK * PB];
+    constexpr int PC = BN + 4;                        // pitch of the staged output tile
+    constexpr int A_FLOATS = ((BK * PA + 3) / 4) * 4; // keeps the B tiles 16-byte aligned
+    constexpr int MAIN_FLOATS = NBUF * (A_FLOATS + BK * PB);
+    constexpr int EPI_FLOATS = WM * 32 * PC;
+    constexpr int LDS_FLOATS = MAIN_FLOATS > EPI_FLOATS ? MAIN_FLOATS : EPI_FLOATS;
+    __shared__ __attribute__((aligned(16))) float lds[LDS_FLOATS];
+    float* const As0 = lds;
+    float* const Bs0 = lds + NBUF * A_FLOATS;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -191,8 +197,8 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
         const bool second = kt >= nk1;
         const int k0 = (second ? kt - nk1 : kt) * BK;
         const int Kc = second ? g.K2 : g.K;
-        float* As = As_[NBUF == 1 ? 0 : (kt & 1)];
-        float* Bs = Bs_[NBUF == 1 ? 0 : (kt & 1)];
+        float* As = As0 + (NBUF == 1 ? 0 : (kt & 1)) * A_FLOATS;
+        float* Bs = Bs0 + (NBUF == 1 ? 0 : (kt & 1)) * (BK * PB);
 #pragma unroll
         for (int r = 0; r < A_REPS; ++r) {
             const int f = tid + 256 * r;
@@ -224,14 +230,66 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         if (kt + 1 < nk) fetch(kt + 1);
-        mma_step<TM, TN, PA, PB, BK>(As_[NBUF == 1 ? 0 : (kt & 1)], Bs_[NBUF == 1 ? 0 : (kt & 1)], wm * TM * 32,
-                                     wn * TN * 32, acc);
+        mma_step<TM, TN, PA, PB, BK>(As0 + (NBUF == 1 ? 0 : (kt & 1)) * A_FLOATS,
+                                     Bs0 + (NBUF == 1 ? 0 : (kt & 1)) * (BK * PB), wm * TM * 32, wn * TN * 32, acc);
         if (NBUF == 1) __syncthreads();
         if (kt + 1 < nk) stage(kt + 1);
         __syncthreads();
     }
 
     const int li = lane & 31, lk = lane >> 5;
+    // Epilogue.  When every operand allows 16-byte accesses the accumulators go through LDS,
+    // 32 tile rows per wavefront row at a time, so that bias / addend / mask are read and the
+    // results written as whole 16-byte vectors along rows (one 512-byte run per 32 lanes).
+    const bool vec_epi = VEC && (n_store % 4 == 0) && g.ldc % 4 == 0 && ((uintptr_t)g.C % 16) == 0 &&
+                         (!g.addend || (g.ld_add % 4 == 0 && ((uintptr_t)g.addend % 16) == 0)) &&
+                         (!g.mask || (g.ld_mask % 4 == 0 && ((uintptr_t)g.mask % 16) == 0)) &&
+                         (!g.C_raw || (g.ld_raw % 4 == 0 && ((uintptr_t)g.C_raw % 16) == 0));
+    if (vec_epi) {
+        float* Cs = lds;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if (i > 0) __syncthreads();               // the previous pass has been read out
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    Cs[(wm * 32 + 8 * (r / 4) + 4 * lk + (r % 4)) * PC + (wn * TN + j) * 32 + li] = acc[i][j][r];
+            __syncthreads();
+            constexpr int C4 = BN / 4;                // 16-byte columns per tile row
+            for (int f = tid; f < WM * 32 * C4; f += 256) {
+                const int lr = f / C4, c4 = f % C4;
+                const int col = n0 + 4 * c4;
+                const int64_t m = m0 + ((lr >> 5) * TM + i) * 32 + (lr & 31);
+                if (m >= g.M || col >= n_store) continue;
+                const float4 a4 = *reinterpret_cast<const float4*>(&Cs[lr * PC + 4 * c4]);
+                float v[4] = {a4.x, a4.y, a4.z, a4.w};
+                if (g.addend) {
+                    const float4 t = *reinterpret_cast<const float4*>(g.addend + m * g.ld_add + col);
+                    v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (col + q < g.N) { if (g.bias) v[q] += g.bias[col + q]; }
+                    else v[q] = 0.f;
+                }
+                if (g.C_raw) *reinterpret_cast<float4*>(g.C_raw + m * g.ld_raw + col) = make_float4(v[0], v[1], v[2], v[3]);
+                const float rs = g.rowscale ? g.rowscale[m] : 1.f;
+                float4 mk = make_float4(1.f, 1.f, 1.f, 1.f);
+                if (g.mask) mk = *reinterpret_cast<const float4*>(g.mask + m * g.ld_mask + col);
+                const float mv[4] = {mk.x, mk.y, mk.z, mk.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float t = v[q] * rs;
+                    if (g.relu) t = t > 0.f ? t : 0.f;
+                    if (g.mask) t = mv[q] > 0.f ? t : 0.f;
+                    v[q] = col + q < g.N ? t : 0.f;
+                }
+                *reinterpret_cast<float4*>(g.C + m * g.ldc + col) = make_float4(v[0], v[1], v[2], v[3]);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -290,6 +348,8 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
     const double nn_flops = 2.0 * a.M * a.N * ((double)a.K + a.K2);
     const double nn_bytes = (double)a.M * a.K * elem + 4.0 * a.M * a.K2 + 4.0 * a.N * ((double)a.K + a.K2) +
                             4.0 * a.M * a.N * (1.0 + (a.addend ? 1.0 : 0.0) + (a.mask ? 1.0 : 0.0));
+    prof_detail("[M=%lld,N=%d,K=%d+%d%s%s%s]", (long long)a.M, a.N, a.K, a.K2, a.addend ? ",add" : "", a.mask ? ",mask" : "",
+                a.rowscale ? ",rs" : "");
     ProfScope ps(a.a_bf16 ? "gemm_nn_bf16a" : "gemm_nn_f32", st, nn_flops, nn_bytes);
     if (a.a_bf16) {
         if (veca && vecb) nn_pick<__hip_bfloat16, true>(a, st);
@@ -497,6 +557,7 @@ grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st) {
     const int64_t out_ld = p.splits > 1 ? a.N : a.ldc;
     const int64_t stride = p.splits > 1 ? (int64_t)a.K * a.N : 0;
     {
+        prof_detail("[M=%lld,K=%d,N=%d]", (long long)a.M, a.K, a.N);
         ProfScope ps(a.a_bf16 ? "gemm_tn_bf16a" : "gemm_tn_f32", st, 2.0 * a.M * a.K * a.N,
                      (double)a.M * a.K * elem + 4.0 * a.M * a.N + 4.0 * a.K * a.N);
         if (a.a_bf16) {

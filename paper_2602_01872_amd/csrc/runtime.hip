@@ -29,7 +29,7 @@ grp_status fail(grp_status code, const char* fmt, ...) {
 }
 
 struct ProfRec {
-    const char* name;
+    std::string name;
     hipEvent_t a, b;
     double flops, bytes;
 };
@@ -37,10 +37,22 @@ static std::mutex g_prof_mu;
 static bool g_prof_on = false;
 static std::vector<ProfRec> g_prof;
 static thread_local hipEvent_t g_open_end = nullptr;
+static bool g_prof_detail = false;           // enable value 2: kernel names carry the launch shape
+static thread_local char g_detail[96] = {0};
+
+void prof_detail(const char* fmt, ...) {
+    if (!g_prof_on || !g_prof_detail) return;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_detail, sizeof g_detail, fmt, ap);
+    va_end(ap);
+}
 
 void prof_begin(const char* name, hipStream_t st, double flops, double bytes) {
     if (!g_prof_on) return;
     ProfRec r{name, nullptr, nullptr, flops, bytes};
+    if (g_prof_detail && g_detail[0]) { r.name += g_detail; }
+    g_detail[0] = 0;
     if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
     (void)hipEventRecord(r.a, st);
     g_open_end = r.b;
@@ -61,6 +73,7 @@ extern "C" const char* grp_last_error(void) { return grp::g_err.c_str(); }
 extern "C" grp_status grp_profile_enable(int32_t on) {
     std::lock_guard<std::mutex> lk(grp::g_prof_mu);
     grp::g_prof_on = on != 0;
+    grp::g_prof_detail = on == 2;
     return GRP_OK;
 }
 

@@ -305,6 +305,7 @@ grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
     const int64_t n_src = a.n_src > 0 ? a.n_src : a.n_rows;
     const double bytes = 4.0 * a.nnz + 8.0 * (a.n_rows + 1) + (double)elem * a.F * n_src +
                          4.0 * a.F * a.n_rows * (a.addend ? 2.0 : 1.0) + (a.colscale ? 4.0 * n_src : 0.0);
+    prof_detail("[rows=%lld,F=%d,nnz=%lld]", (long long)a.n_rows, a.F, (long long)a.nnz);
     ProfScope ps(a.x_bf16 ? "spmm_rows_bf16" : "spmm_rows_f32", st, 2.0 * a.nnz * a.F, bytes);
     if (vec_ok) {
         if (a.long_rows && a.long_rows->n_long > 0 && (!a.partials || ((uintptr_t)a.partials % 16) != 0))
