@@ -120,6 +120,9 @@ struct SpmmArgs {
     int64_t ldy = 0;
     const LongRows* long_rows = nullptr;  // null = no row is split
     float* partials = nullptr;            // [n_chunks x round_up(F,4)] scratch when rows are split
+    int64_t addend_rows = 0;              // rows >= this have no addend (0: every row has one)
+    const float* mask = nullptr;          // result kept where mask[i,c] > 0, else 0 (after the ReLU)
+    int64_t ld_mask = 0;
     const float* residual = nullptr;      // added after the ReLU: Y = residual + act (residual layers)
     int64_t ld_res = 0;
     float* Y2 = nullptr;                  // also receives act (before the residual is added)
@@ -157,6 +160,9 @@ struct GemmNNArgs {
     int64_t a_valid_rows = 0;       // rows >= this of the FIRST product's A read as zero (0: M)
     float* C_raw = nullptr;         // also receives acc + bias + addend (before scale / ReLU / mask)
     int64_t ld_raw = 0;
+    int32_t rowscale_cols = 0;      // rowscale applies to columns < this only (0: all columns)
+    int32_t bias_col0 = 0;          // bias[c - bias_col0] is added to columns c in [bias_col0, bias_col0 + bias_n)
+    int32_t bias_n = 0;             // (0: N - bias_col0)
 };
 grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st);
 
@@ -178,7 +184,8 @@ struct GemmTNArgs {
 };
 grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st);
 
-// out[N x K] (ld_out) = in[K x N]^T, rows [N, n_pad_rows) zero-filled.
+// out[N x K] (pitch ld_out) = in[K x N]^T; columns [K, round_up(K,4)) and rows [N, n_pad_rows) are
+// zero-filled, columns beyond round_up(K,4) are left alone (two matrices may share a pitch).
 grp_status launch_transpose(const float* in, int32_t K, int32_t N, float* out, int64_t ld_out,
                             int32_t n_pad_rows, hipStream_t st);
 
@@ -192,7 +199,8 @@ grp_status launch_colsum_scaled(const float* A, int64_t M, int32_t N, int64_t ld
 // inv_in = 1/max(d_in,1); r = 1/sqrt(max(d_in+sl,1)); s = 1/sqrt(max(d_out+sl,1)); rinv = 1/r.
 grp_status launch_degree_scales(const int32_t* d_in, const int32_t* d_out, int64_t n, int sl,
                                 float* inv_in, float* r, float* s, float* rinv, hipStream_t st);
-// out[rows x ld_out] = in[rows x cols] (dense, pitch cols) with zero pad columns.
+// out[rows x cols] (pitch ld_out) = in (dense, pitch cols); columns [cols, round_up(cols,4)) are
+// zero-filled, columns beyond are left alone.
 grp_status launch_pad_copy(const float* in, int32_t rows, int32_t cols, float* out, int64_t ld_out,
                            hipStream_t st);
 

@@ -30,16 +30,17 @@ grp_status launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
 // out[N rows, ld_out] = in[K x N]^T ; rows [N, n_pad_rows) and pad columns are zero.
 __global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict__ in, int K, int N,
                                                         float* __restrict__ out, int64_t ld_out, int n_pad_rows) {
+    const int width = (K + 3) & ~3;
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= (int64_t)n_pad_rows * ld_out) return;
-    const int r = (int)(e / ld_out), c = (int)(e % ld_out);     // out[r][c] = in[c][r]
-    out[e] = (r < N && c < K) ? in[(int64_t)c * N + r] : 0.f;
+    if (e >= (int64_t)n_pad_rows * width) return;
+    const int r = (int)(e / width), c = (int)(e % width);       // out[r][c] = in[c][r]
+    out[(int64_t)r * ld_out + c] = (r < N && c < K) ? in[(int64_t)c * N + r] : 0.f;
 }
 
 grp_status launch_transpose(const float* in, int32_t K, int32_t N, float* out, int64_t ld_out, int32_t n_pad_rows,
                             hipStream_t st) {
     ProfScope ps("transpose_w", st);
-    const int64_t blocks = cdiv((int64_t)n_pad_rows * ld_out, 256);
+    const int64_t blocks = cdiv((int64_t)n_pad_rows * round_up(K, 4), 256);
     hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, K, N, out, ld_out, n_pad_rows);
     GRP_LAUNCH_CHECK();
     return GRP_OK;
@@ -47,15 +48,16 @@ grp_status launch_transpose(const float* in, int32_t K, int32_t N, float* out, i
 
 __global__ __launch_bounds__(256) void pad_copy_kernel(const float* __restrict__ in, int rows, int cols,
                                                        float* __restrict__ out, int64_t ld_out) {
+    const int width = (cols + 3) & ~3;
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= (int64_t)rows * ld_out) return;
-    const int r = (int)(e / ld_out), c = (int)(e % ld_out);
-    out[e] = c < cols ? in[(int64_t)r * cols + c] : 0.f;
+    if (e >= (int64_t)rows * width) return;
+    const int r = (int)(e / width), c = (int)(e % width);
+    out[(int64_t)r * ld_out + c] = c < cols ? in[(int64_t)r * cols + c] : 0.f;
 }
 
 grp_status launch_pad_copy(const float* in, int32_t rows, int32_t cols, float* out, int64_t ld_out, hipStream_t st) {
     ProfScope ps("pad_copy_w", st);
-    const int64_t blocks = cdiv((int64_t)rows * ld_out, 256);
+    const int64_t blocks = cdiv((int64_t)rows * round_up(cols, 4), 256);
     hipLaunchKernelGGL(pad_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, rows, cols, out, ld_out);
     GRP_LAUNCH_CHECK();
     return GRP_OK;

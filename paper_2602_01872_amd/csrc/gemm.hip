@@ -245,6 +245,8 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
                          (!g.addend || (g.ld_add % 4 == 0 && ((uintptr_t)g.addend % 16) == 0)) &&
                          (!g.mask || (g.ld_mask % 4 == 0 && ((uintptr_t)g.mask % 16) == 0)) &&
                          (!g.C_raw || (g.ld_raw % 4 == 0 && ((uintptr_t)g.C_raw % 16) == 0));
+    const int bias_n = g.bias_n > 0 ? g.bias_n : g.N - g.bias_col0;
+    const int rs_cols = g.rowscale_cols > 0 ? g.rowscale_cols : g.N;   // a multiple of 4 when set
     if (vec_epi) {
         float* Cs = lds;
 #pragma unroll
@@ -270,11 +272,12 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
                 }
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    if (col + q < g.N) { if (g.bias) v[q] += g.bias[col + q]; }
+                    const int cb = col + q - g.bias_col0;
+                    if (col + q < g.N) { if (g.bias && cb >= 0 && cb < bias_n) v[q] += g.bias[cb]; }
                     else v[q] = 0.f;
                 }
                 if (g.C_raw) *reinterpret_cast<float4*>(g.C_raw + m * g.ld_raw + col) = make_float4(v[0], v[1], v[2], v[3]);
-                const float rs = g.rowscale ? g.rowscale[m] : 1.f;
+                const float rs = (g.rowscale && col < rs_cols) ? g.rowscale[m] : 1.f;
                 float4 mk = make_float4(1.f, 1.f, 1.f, 1.f);
                 if (g.mask) mk = *reinterpret_cast<const float4*>(g.mask + m * g.ld_mask + col);
                 const float mv[4] = {mk.x, mk.y, mk.z, mk.w};
@@ -296,7 +299,8 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
         for (int j = 0; j < TN; ++j) {
             const int col = n0 + (wn * TN + j) * 32 + li;
             if (col >= n_store) continue;
-            const float bv = (g.bias && col < g.N) ? g.bias[col] : 0.f;
+            const int cb = col - g.bias_col0;
+            const float bv = (g.bias && col < g.N && cb >= 0 && cb < bias_n) ? g.bias[cb] : 0.f;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
@@ -308,7 +312,7 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
                 }
                 if (g.C_raw) g.C_raw[m * g.ld_raw + col] = v;
                 if (col < g.N) {
-                    if (g.rowscale) v *= g.rowscale[m];
+                    if (g.rowscale && col < rs_cols) v *= g.rowscale[m];
                     if (g.relu) v = v > 0.f ? v : 0.f;
                     if (g.mask) v = g.mask[m * g.ld_mask + col] > 0.f ? v : 0.f;
                 }
@@ -522,12 +526,22 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
         }
 }
 
+// C[e] = sum_p part[p][e], p ascending.  Four partial tiles are requested before the first is
+// added (the adds stay in split order, so the result is the plain sequential sum).
 __global__ __launch_bounds__(256) void tn_reduce_kernel(const float* __restrict__ part, int splits, int K, int N,
                                                         float* __restrict__ C, int64_t ldc) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= (int64_t)K * N) return;
+    const int64_t kn = (int64_t)K * N;
+    if (e >= kn) return;
+    const float* p0 = part + e;
     float s = 0.f;
-    for (int p = 0; p < splits; ++p) s += part[(int64_t)p * K * N + e];
+    int p = 0;
+    for (; p + 4 <= splits; p += 4) {
+        const float a = p0[(int64_t)p * kn], b = p0[(int64_t)(p + 1) * kn];
+        const float c = p0[(int64_t)(p + 2) * kn], d = p0[(int64_t)(p + 3) * kn];
+        s += a; s += b; s += c; s += d;
+    }
+    for (; p < splits; ++p) s += p0[(int64_t)p * kn];
     C[(e / N) * ldc + (e % N)] = s;
 }
 

@@ -109,6 +109,9 @@ struct SpmmEpilogue {
     int64_t ld_res;
     float* Y2;                // receives the activation before the residual is added; null otherwise
     int64_t ldy2;
+    int64_t addend_rows;      // rows >= this have no addend
+    const float* mask;        // keep where mask > 0 (after the ReLU); null otherwise
+    int64_t ld_mask;
 };
 
 template <typename XT>
@@ -117,7 +120,7 @@ __device__ __forceinline__ void finish_row(const SpmmEpilogue& ep, int64_t i, in
     const float a = row_scale(ep.scale, deg, ep.self_term);
     if (ep.self_term) add4(r, Vec4Load<XT>::ld(X + i * ldx + col));
     r.x *= a; r.y *= a; r.z *= a; r.w *= a;
-    if (ep.addend) add4(r, *reinterpret_cast<const float4*>(ep.addend + i * ep.ld_add + col));
+    if (ep.addend && i < ep.addend_rows) add4(r, *reinterpret_cast<const float4*>(ep.addend + i * ep.ld_add + col));
     float o[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -127,6 +130,11 @@ __device__ __forceinline__ void finish_row(const SpmmEpilogue& ep, int64_t i, in
         } else {
             o[q] = 0.f;           // pad columns stay zero
         }
+    }
+    if (ep.mask) {
+        const float4 mk = *reinterpret_cast<const float4*>(ep.mask + i * ep.ld_mask + col);
+        o[0] = mk.x > 0.f ? o[0] : 0.f; o[1] = mk.y > 0.f ? o[1] : 0.f;
+        o[2] = mk.z > 0.f ? o[2] : 0.f; o[3] = mk.w > 0.f ? o[3] : 0.f;
     }
     if (ep.Y2) *reinterpret_cast<float4*>(ep.Y2 + i * ep.ldy2 + col) = make_float4(o[0], o[1], o[2], o[3]);
     if (ep.residual) {
@@ -304,7 +312,8 @@ grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
     // output row once (+ addend rows)
     const int64_t n_src = a.n_src > 0 ? a.n_src : a.n_rows;
     const double bytes = 4.0 * a.nnz + 8.0 * (a.n_rows + 1) + (double)elem * a.F * n_src +
-                         4.0 * a.F * a.n_rows * (a.addend ? 2.0 : 1.0) + (a.colscale ? 4.0 * n_src : 0.0);
+                         4.0 * a.F * a.n_rows * (1.0 + (a.addend ? 1.0 : 0.0) + (a.mask ? 1.0 : 0.0)) +
+                         (a.colscale ? 4.0 * n_src : 0.0);
     prof_detail("[rows=%lld,F=%d,nnz=%lld]", (long long)a.n_rows, a.F, (long long)a.nnz);
     ProfScope ps(a.x_bf16 ? "spmm_rows_bf16" : "spmm_rows_f32", st, 2.0 * a.nnz * a.F, bytes);
     if (vec_ok) {
@@ -314,11 +323,14 @@ grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
             return fail(GRP_EINVAL, "spmm: residual operand must be 16-byte aligned with a pitch multiple of 4");
         if (a.Y2 && (a.ldy2 % 4 != 0 || a.ldy2 < fpad || (uintptr_t)a.Y2 % 16 != 0))
             return fail(GRP_EINVAL, "spmm: second output must be 16-byte aligned with a pitch multiple of 4");
+        if (a.mask && (a.ld_mask % 4 != 0 || a.ld_mask < fpad || (uintptr_t)a.mask % 16 != 0))
+            return fail(GRP_EINVAL, "spmm: mask must be 16-byte aligned with a pitch multiple of 4");
         SpmmEpilogue ep{a.scale, a.self_term, a.relu, a.F, a.addend, a.ld_add, a.bias, a.Y, a.ldy,
-                        a.residual, a.ld_res, a.Y2, a.ldy2};
+                        a.residual, a.ld_res, a.Y2, a.ldy2, a.addend_rows > 0 ? a.addend_rows : a.n_rows, a.mask, a.ld_mask};
         GRP_TRY(a.x_bf16 ? dispatch<__hip_bfloat16>(a, ep, st) : dispatch<float>(a, ep, st));
     } else {
-        if (a.residual || a.Y2) return fail(GRP_EUNSUPPORTED, "spmm: residual epilogue needs 16-byte friendly operands");
+        if (a.residual || a.Y2 || a.mask || a.addend_rows > 0)
+            return fail(GRP_EUNSUPPORTED, "spmm: this epilogue needs 16-byte friendly operands");
         const int64_t blocks = cdiv(a.n_rows, 4);
         if (a.x_bf16)
             hipLaunchKernelGGL((spmm_rows_scalar_kernel<__hip_bfloat16>), dim3((unsigned)blocks), dim3(256), 0, st,

@@ -15,6 +15,7 @@
 namespace grp {
 
 static inline int64_t ldp(int64_t f) { return round_up(f, 4); }
+static inline bool measure_only(const void* p) { return p == nullptr; }
 
 struct LayerBufs {
     float* Wp_s = nullptr;   // [Fin x ld(Fout)] aligned copy of W_self (GCN: W)
@@ -25,6 +26,7 @@ struct LayerBufs {
     float* H_out = nullptr;  // [rows x ld(Fout)] layer output (post-activation; logits for the last layer)
     float* Act = nullptr;    // [rows x ld(Fout)] ReLU(z) of a residual layer (its derivative mask)
     int64_t off_ws = 0, off_wn = 0, off_b = 0;
+    int64_t ldwp = 0, ldwt = 0;   // pitches of Wp_* / Wt_* (SAGE keeps [W_neigh | W_self] side by side)
     bool agg_first = false;
     bool skip = false;       // residual GCN: H_out = H_in + ReLU(z)
 };
@@ -93,12 +95,19 @@ static StepPlan make_plan(const grp_partition_t* part, const grp_model_desc* m, 
         L.off_b = off; off += fout;
         L.agg_first = sage && (fin <= fout || (mb && l == 0));
         L.skip = m->arch == GRP_ARCH_GCN_RESIDUAL && fin == fout && l < k - 1;
-        L.Wp_s = b.take<float>((size_t)fin * ldp(fout));
-        L.Wt_s = b.take<float>((size_t)fout * ldp(fin));
         if (sage) {
-            L.Wp_n = b.take<float>((size_t)fin * ldp(fout));
-            L.Wt_n = b.take<float>((size_t)fout * ldp(fin));
+            L.ldwp = 2 * ldp(fout);
+            L.ldwt = 2 * ldp(fin);
+            float* wp = b.take<float>((size_t)fin * L.ldwp);
+            float* wt = b.take<float>((size_t)fout * L.ldwt);
+            L.Wp_n = wp; L.Wp_s = measure_only(wp) ? nullptr : wp + ldp(fout);
+            L.Wt_n = wt; L.Wt_s = measure_only(wt) ? nullptr : wt + ldp(fin);
             if (L.agg_first) L.M = b.take<float>((size_t)rows * ldp(fin));
+        } else {
+            L.ldwp = ldp(fout);
+            L.ldwt = ldp(fin);
+            L.Wp_s = b.take<float>((size_t)fin * ldp(fout));
+            L.Wt_s = b.take<float>((size_t)fout * ldp(fin));
         }
         L.H_out = b.take<float>((size_t)rows * ldp(fout));
         if (L.skip) L.Act = b.take<float>((size_t)rows * ldp(fout));
@@ -115,7 +124,7 @@ static StepPlan make_plan(const grp_partition_t* part, const grp_model_desc* m, 
         p.gs = b.take<float>((size_t)n);
         p.grinv = b.take<float>((size_t)n);
     }
-    p.tmpA = b.take<float>((size_t)max_rows * fmax);
+    p.tmpA = b.take<float>((size_t)max_rows * 2 * fmax);   // holds two matrices side by side in the fused layers
     p.tmpB = b.take<float>((size_t)max_rows * fmax);
     p.dZa = b.take<float>((size_t)max_rows * fmax);
     p.dZb = b.take<float>((size_t)max_rows * fmax);
@@ -171,11 +180,11 @@ static grp_status prep_weights(const grp_model_desc* m, const float* theta, Step
     for (int l = 0; l < m->n_layers; ++l) {
         const LayerBufs& L = p.L[l];
         const int fin = m->dims[l], fout = m->dims[l + 1];
-        GRP_TRY(launch_pad_copy(theta + L.off_ws, fin, fout, L.Wp_s, ldp(fout), st));
-        if (sage) GRP_TRY(launch_pad_copy(theta + L.off_wn, fin, fout, L.Wp_n, ldp(fout), st));
+        GRP_TRY(launch_pad_copy(theta + L.off_ws, fin, fout, L.Wp_s, L.ldwp, st));
+        if (sage) GRP_TRY(launch_pad_copy(theta + L.off_wn, fin, fout, L.Wp_n, L.ldwp, st));
         if (l > 0) {
-            GRP_TRY(launch_transpose(theta + L.off_ws, fin, fout, L.Wt_s, ldp(fin), fout, st));
-            if (sage) GRP_TRY(launch_transpose(theta + L.off_wn, fin, fout, L.Wt_n, ldp(fin), fout, st));
+            GRP_TRY(launch_transpose(theta + L.off_ws, fin, fout, L.Wt_s, L.ldwt, fout, st));
+            if (sage) GRP_TRY(launch_transpose(theta + L.off_wn, fin, fout, L.Wt_n, L.ldwt, fout, st));
         }
     }
     return GRP_OK;
@@ -206,16 +215,30 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             GRP_TRY(launch_spmm(s, st));
             GemmNNArgs a;
             a.M = B.n_dst; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.a_rows = B.self_rows;
-            a.B = L.Wp_s; a.ldb = ldp(fout);
-            a.K2 = fin; a.A2 = L.M; a.lda2 = ldp(fin); a.B2 = L.Wp_n; a.ldb2 = ldp(fout);
+            a.B = L.Wp_s; a.ldb = L.ldwp;
+            a.K2 = fin; a.A2 = L.M; a.lda2 = ldp(fin); a.B2 = L.Wp_n; a.ldb2 = L.ldwp;
             a.bias = theta + L.off_b; a.relu = relu; a.C = L.H_out; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
             GRP_TRY(launch_gemm_nn(a, st));
+        } else if (B.n_in == B.n_dst && !B.self_rows) {
+            // [T | Z0] = H [Wn | Ws] (+ b on the second half) in one pass over H, then
+            // H' = ReLU(mean-aggregate(T) + Z0)
+            const int64_t w2 = 2 * ldp(fout);
+            GemmNNArgs a;
+            a.M = B.n_dst; a.N = (int)(ldp(fout) + fout); a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16;
+            a.B = L.Wp_n; a.ldb = L.ldwp; a.bias = theta + L.off_b; a.bias_col0 = (int)ldp(fout); a.bias_n = fout;
+            a.C = p.tmpA; a.ldc = w2; a.zero_pad_to = (int)w2;
+            GRP_TRY(launch_gemm_nn(a, st));
+            SpmmArgs s;
+            fill_spmm(s, B, false, p.partials);
+            s.F = fout; s.X = p.tmpA; s.ldx = w2; s.scale = GRP_SCALE_MEAN;
+            s.addend = p.tmpA + ldp(fout); s.ld_add = w2; s.relu = relu; s.Y = L.H_out; s.ldy = ldp(fout);
+            GRP_TRY(launch_spmm(s, st));
         } else {
             GemmNNArgs a;      // T = H Wn over every input row, Z0 = H_self Ws + b
-            a.M = B.n_in; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.B = L.Wp_n; a.ldb = ldp(fout);
+            a.M = B.n_in; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.B = L.Wp_n; a.ldb = L.ldwp;
             a.C = p.tmpA; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
             GRP_TRY(launch_gemm_nn(a, st));
-            a.M = B.n_dst; a.a_rows = B.self_rows; a.B = L.Wp_s; a.bias = theta + L.off_b; a.C = L.H_out;
+            a.M = B.n_dst; a.a_rows = B.self_rows; a.B = L.Wp_s; a.ldb = L.ldwp; a.bias = theta + L.off_b; a.C = L.H_out;
             GRP_TRY(launch_gemm_nn(a, st));
             SpmmArgs s;
             fill_spmm(s, B, false, p.partials);
@@ -252,22 +275,22 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             t.A = L.M; t.lda = ldp(fin); t.a_bf16 = 0; t.a_rows = nullptr; t.C = grad + L.off_wn;
             GRP_TRY(launch_gemm_tn(t, st));
             if (l > 0 && B.n_in > 0) {
+                // [dM' | dS] = dZ [Wn^T | Ws^T], dM' rows divided by |N_v|, in one pass over dZ;
+                // then dZ_prev = mask * (A^T dM' + [dS ; 0]) in the aggregation's epilogue.
+                const int64_t w2 = 2 * ldp(fin);
                 if (B.n_dst > 0) {
-                    GemmNNArgs a;      // dM' = (dZ Wn^T) / |N_v|
-                    a.M = B.n_dst; a.N = fin; a.K = fout; a.A = dZ; a.lda = ldp(fout); a.B = L.Wt_n; a.ldb = ldp(fin);
-                    a.rowscale = B.inv_in; a.C = p.tmpA; a.ldc = ldp(fin); a.zero_pad_to = (int)ldp(fin);
+                    GemmNNArgs a;
+                    a.M = B.n_dst; a.N = (int)(ldp(fin) + fin); a.K = fout; a.A = dZ; a.lda = ldp(fout);
+                    a.B = L.Wt_n; a.ldb = L.ldwt; a.rowscale = B.inv_in; a.rowscale_cols = (int)ldp(fin);
+                    a.C = p.tmpA; a.ldc = w2; a.zero_pad_to = (int)w2;
                     GRP_TRY(launch_gemm_nn(a, st));
                 }
-                SpmmArgs s;        // P = A^T dM'  over the block's inputs
+                SpmmArgs s;
                 fill_spmm(s, B, true, p.partials);
-                s.F = fin; s.X = p.tmpA; s.ldx = ldp(fin); s.Y = p.tmpB; s.ldy = ldp(fin);
+                s.F = fin; s.X = p.tmpA; s.ldx = w2; s.addend = p.tmpA + ldp(fin); s.ld_add = w2;
+                s.addend_rows = B.n_dst; s.mask = p.L[l - 1].H_out; s.ld_mask = ldp(fin);
+                s.Y = dZ_other; s.ldy = ldp(fin);
                 GRP_TRY(launch_spmm(s, st));
-                GemmNNArgs c;      // dZ_prev = mask * ([dZ Ws^T ; 0] + P)
-                c.M = B.n_in; c.N = fin; c.K = fout; c.A = dZ; c.lda = ldp(fout); c.a_valid_rows = B.n_dst;
-                c.B = L.Wt_s; c.ldb = ldp(fin);
-                c.addend = p.tmpB; c.ld_add = ldp(fin); c.mask = p.L[l - 1].H_out; c.ld_mask = ldp(fin);
-                c.C = dZ_other; c.ldc = ldp(fin); c.zero_pad_to = (int)ldp(fin);
-                GRP_TRY(launch_gemm_nn(c, st));
             }
         } else {
             SpmmArgs s;            // dT = A^T (dZ / |N_v|)  over the block's inputs
@@ -280,8 +303,8 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             if (l > 0 && B.n_in > 0) {
                 GemmNNArgs c;      // dZ_prev = mask * ([dZ Ws^T ; 0] + dT Wn^T)
                 c.M = B.n_in; c.N = fin; c.K = fout; c.A = dZ; c.lda = ldp(fout); c.a_valid_rows = B.n_dst;
-                c.B = L.Wt_s; c.ldb = ldp(fin);
-                c.K2 = fout; c.A2 = p.tmpA; c.lda2 = ldp(fout); c.B2 = L.Wt_n; c.ldb2 = ldp(fin);
+                c.B = L.Wt_s; c.ldb = L.ldwt;
+                c.K2 = fout; c.A2 = p.tmpA; c.lda2 = ldp(fout); c.B2 = L.Wt_n; c.ldb2 = L.ldwt;
                 c.mask = p.L[l - 1].H_out; c.ld_mask = ldp(fin);
                 c.C = dZ_other; c.ldc = ldp(fin); c.zero_pad_to = (int)ldp(fin);
                 GRP_TRY(launch_gemm_nn(c, st));
@@ -316,7 +339,7 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
         const LayerBufs& L = p.L[l];
         const int fin = m->dims[l], fout = m->dims[l + 1];
         GemmNNArgs a;
-        a.M = n; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.B = L.Wp_s; a.ldb = ldp(fout);
+        a.M = n; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.B = L.Wp_s; a.ldb = L.ldwp;
         a.rowscale = p.gs; a.C = p.tmpA; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
         GRP_TRY(launch_gemm_nn(a, st));
         SpmmArgs s;
@@ -354,7 +377,7 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
         if (l > 0 && n > 0) {
             const LayerBufs& Lp = p.L[l - 1];
             GemmNNArgs c;      // G_in = dT W^T (+ G);  dZ'_prev = diag(r) (A_prev > 0) G_in
-            c.M = n; c.N = fin; c.K = fout; c.A = p.tmpA; c.lda = ldp(fout); c.B = L.Wt_s; c.ldb = ldp(fin);
+            c.M = n; c.N = fin; c.K = fout; c.A = p.tmpA; c.lda = ldp(fout); c.B = L.Wt_s; c.ldb = L.ldwt;
             if (L.skip) { c.addend = G; c.ld_add = ldp(fout); }
             if (Lp.skip) { c.C_raw = G_other; c.ld_raw = ldp(fin); }
             c.rowscale = p.gr; c.mask = Lp.skip ? Lp.Act : Lp.H_out; c.ld_mask = ldp(fin);
