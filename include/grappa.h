@@ -225,6 +225,11 @@ grp_status grp_spmm(const grp_partition_t* part, int32_t transposed, int32_t sca
 grp_status grp_gemm_nn(int64_t M, int32_t N, int32_t K, const void* A, int64_t lda,
                        int32_t a_dtype, const float* B, int64_t ldb, float* C, int64_t ldc,
                        void* stream);
+/*   grp_gemm_nt:  C[M x N] = A[M x K] Bt[N x K]^T         (B given transposed, k contiguous: the
+ *                 layout the train step keeps its weights in; fastest path)               */
+grp_status grp_gemm_nt(int64_t M, int32_t N, int32_t K, const void* A, int64_t lda,
+                       int32_t a_dtype, const float* Bt, int64_t ldbt, float* C, int64_t ldc,
+                       void* stream);
 size_t     grp_gemm_tn_workspace_bytes(int64_t M, int32_t K, int32_t N);
 grp_status grp_gemm_tn(int64_t M, int32_t K, int32_t N, const void* A, int64_t lda,
                        int32_t a_dtype, const float* B, int64_t ldb, float* C, int64_t ldc,

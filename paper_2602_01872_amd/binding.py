@@ -68,6 +68,7 @@ def load() -> C.CDLL:
         "grp_aggregate": [vp, i64, vp, i32, i64, i32, vp, vp, vp],
         "grp_spmm": [vp, i32, i32, i32, i32, vp, i64, i32, vp, i64, vp],
         "grp_gemm_nn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
+        "grp_gemm_nt": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
         "grp_gemm_tn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp, sz, vp],
         "grp_profile_enable": [i32],
         "grp_profile_report": [C.c_char_p, sz],
@@ -226,6 +227,10 @@ def grp_gemm_nn(M, N, K, A, lda, a_dtype, B, ldb, Cm, ldc, stream=None):
     _check(load().grp_gemm_nn(M, N, K, _ptr(A), lda, a_dtype, _ptr(B), ldb, _ptr(Cm), ldc, _stream(stream)))
 
 
+def grp_gemm_nt(M, N, K, A, lda, a_dtype, Bt, ldbt, Cm, ldc, stream=None):
+    _check(load().grp_gemm_nt(M, N, K, _ptr(A), lda, a_dtype, _ptr(Bt), ldbt, _ptr(Cm), ldc, _stream(stream)))
+
+
 def grp_gemm_tn_workspace_bytes(M, K, N) -> int:
     return int(load().grp_gemm_tn_workspace_bytes(M, K, N))
 
@@ -263,5 +268,5 @@ def read_stats(stats: torch.Tensor) -> np.ndarray:
 def exported_symbols():
     return ["grp_last_error", "grp_partition", "grp_partition_from_local_coo", "grp_partition_view",
             "grp_partition_destroy", "grp_param_count", "grp_step_workspace_bytes", "grp_train_step",
-            "grp_aggregate", "grp_spmm", "grp_gemm_nn", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
+            "grp_aggregate", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
             "grp_profile_enable", "grp_profile_report"]

@@ -163,6 +163,10 @@ struct GemmNNArgs {
     int32_t rowscale_cols = 0;      // rowscale applies to columns < this only (0: all columns)
     int32_t bias_col0 = 0;          // bias[c - bias_col0] is added to columns c in [bias_col0, bias_col0 + bias_n)
     int32_t bias_n = 0;             // (0: N - bias_col0)
+    const float* Bt = nullptr;      // when set: B given transposed, Bt[N x K] (pitch ldbt), fast path
+    int64_t ldbt = 0;
+    const float* Bt2 = nullptr;     // same for the second product
+    int64_t ldbt2 = 0;
 };
 grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st);
 
@@ -201,8 +205,9 @@ grp_status launch_degree_scales(const int32_t* d_in, const int32_t* d_out, int64
                                 float* inv_in, float* r, float* s, float* rinv, hipStream_t st);
 // out[rows x cols] (pitch ld_out) = in (dense, pitch cols); columns [cols, round_up(cols,4)) are
 // zero-filled, columns beyond are left alone.
-grp_status launch_pad_copy(const float* in, int32_t rows, int32_t cols, float* out, int64_t ld_out,
-                           hipStream_t st);
+// Rows [rows, rows_pad) are zero-filled too.
+grp_status launch_pad_copy(const float* in, int32_t rows, int32_t cols, int32_t rows_pad, float* out,
+                           int64_t ld_out, hipStream_t st);
 
 // Coverage statistics over the loss nodes and the weighted softmax cross-entropy.
 size_t stats_workspace_bytes(int64_t n);

@@ -46,19 +46,21 @@ grp_status launch_transpose(const float* in, int32_t K, int32_t N, float* out, i
     return GRP_OK;
 }
 
-__global__ __launch_bounds__(256) void pad_copy_kernel(const float* __restrict__ in, int rows, int cols,
+__global__ __launch_bounds__(256) void pad_copy_kernel(const float* __restrict__ in, int rows, int cols, int rows_pad,
                                                        float* __restrict__ out, int64_t ld_out) {
     const int width = (cols + 3) & ~3;
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= (int64_t)rows * width) return;
+    if (e >= (int64_t)rows_pad * width) return;
     const int r = (int)(e / width), c = (int)(e % width);
-    out[(int64_t)r * ld_out + c] = c < cols ? in[(int64_t)r * cols + c] : 0.f;
+    out[(int64_t)r * ld_out + c] = (r < rows && c < cols) ? in[(int64_t)r * cols + c] : 0.f;
 }
 
-grp_status launch_pad_copy(const float* in, int32_t rows, int32_t cols, float* out, int64_t ld_out, hipStream_t st) {
+grp_status launch_pad_copy(const float* in, int32_t rows, int32_t cols, int32_t rows_pad, float* out, int64_t ld_out,
+                           hipStream_t st) {
     ProfScope ps("pad_copy_w", st);
-    const int64_t blocks = cdiv((int64_t)rows * round_up(cols, 4), 256);
-    hipLaunchKernelGGL(pad_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, rows, cols, out, ld_out);
+    if (rows_pad < rows) rows_pad = rows;
+    const int64_t blocks = cdiv((int64_t)rows_pad * round_up(cols, 4), 256);
+    hipLaunchKernelGGL(pad_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, rows, cols, rows_pad, out, ld_out);
     GRP_LAUNCH_CHECK();
     return GRP_OK;
 }

@@ -92,12 +92,111 @@ __device__ __forceinline__ void mma_step(const float* __restrict__ As, const flo
 #pragma unroll
             for (int j = 0; j < TN; ++j) b[nxt][j] = bp[(k + 2) * PB + 32 * j];
         }
+        __builtin_amdgcn_sched_barrier(0);    // keep the next operands' LDS reads ahead of these MFMAs
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
     }
+}
+
+// Epilogue shared by the nn kernels: (+ addend) (+ bias) -> C_raw; (* rowscale) (ReLU) (mask) -> C.
+// When every operand allows 16-byte accesses the accumulators go through LDS, 32 tile rows
+// per wavefront row at a time, so that addend / mask are read and the results written as
+// whole 16-byte vectors along rows (one 512-byte run per 32 lanes).  `lds` must hold
+// WM*32*(BN+4) floats and must no longer be read by the main loop.
+template <bool VEC, int WM, int WN, int TM, int TN>
+__device__ __forceinline__ void nn_epilogue(const GemmNNArgs& g, floatx16 (&acc)[TM][TN], float* lds, int64_t m0, int n0,
+                                            int n_store) {
+    constexpr int BN = WN * TN * 32;
+    constexpr int PC = BN + 4;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, lk = lane >> 5;
+    // Epilogue.  When every operand allows 16-byte accesses the accumulators go through LDS,
+    // 32 tile rows per wavefront row at a time, so that bias / addend / mask are read and the
+    // results written as whole 16-byte vectors along rows (one 512-byte run per 32 lanes).
+    const bool vec_epi = VEC && (n_store % 4 == 0) && g.ldc % 4 == 0 && ((uintptr_t)g.C % 16) == 0 &&
+                         (!g.addend || (g.ld_add % 4 == 0 && ((uintptr_t)g.addend % 16) == 0)) &&
+                         (!g.mask || (g.ld_mask % 4 == 0 && ((uintptr_t)g.mask % 16) == 0)) &&
+                         (!g.C_raw || (g.ld_raw % 4 == 0 && ((uintptr_t)g.C_raw % 16) == 0));
+    const int bias_n = g.bias_n > 0 ? g.bias_n : g.N - g.bias_col0;
+    const int rs_cols = g.rowscale_cols > 0 ? g.rowscale_cols : g.N;   // a multiple of 4 when set
+    if (vec_epi) {
+        float* Cs = lds;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if (i > 0) __syncthreads();               // the previous pass has been read out
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    Cs[(wm * 32 + 8 * (r / 4) + 4 * lk + (r % 4)) * PC + (wn * TN + j) * 32 + li] = acc[i][j][r];
+            __syncthreads();
+            constexpr int C4 = BN / 4;                // 16-byte columns per tile row
+            for (int f = tid; f < WM * 32 * C4; f += 256) {
+                const int lr = f / C4, c4 = f % C4;
+                const int col = n0 + 4 * c4;
+                const int64_t m = m0 + ((lr >> 5) * TM + i) * 32 + (lr & 31);
+                if (m >= g.M || col >= n_store) continue;
+                const float4 a4 = *reinterpret_cast<const float4*>(&Cs[lr * PC + 4 * c4]);
+                float v[4] = {a4.x, a4.y, a4.z, a4.w};
+                if (g.addend) {
+                    const float4 t = *reinterpret_cast<const float4*>(g.addend + m * g.ld_add + col);
+                    v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int cb = col + q - g.bias_col0;
+                    if (col + q < g.N) { if (g.bias && cb >= 0 && cb < bias_n) v[q] += g.bias[cb]; }
+                    else v[q] = 0.f;
+                }
+                if (g.C_raw) *reinterpret_cast<float4*>(g.C_raw + m * g.ld_raw + col) = make_float4(v[0], v[1], v[2], v[3]);
+                const float rs = (g.rowscale && col < rs_cols) ? g.rowscale[m] : 1.f;
+                float4 mk = make_float4(1.f, 1.f, 1.f, 1.f);
+                if (g.mask) mk = *reinterpret_cast<const float4*>(g.mask + m * g.ld_mask + col);
+                const float mv[4] = {mk.x, mk.y, mk.z, mk.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float t = v[q] * rs;
+                    if (g.relu) t = t > 0.f ? t : 0.f;
+                    if (g.mask) t = mv[q] > 0.f ? t : 0.f;
+                    v[q] = col + q < g.N ? t : 0.f;
+                }
+                *reinterpret_cast<float4*>(g.C + m * g.ldc + col) = make_float4(v[0], v[1], v[2], v[3]);
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + (wn * TN + j) * 32 + li;
+            if (col >= n_store) continue;
+            const int cb = col - g.bias_col0;
+            const float bv = (g.bias && col < g.N && cb >= 0 && cb < bias_n) ? g.bias[cb] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
+                if (m >= g.M) continue;
+                float v = 0.f;
+                if (col < g.N) {
+                    v = acc[i][j][r] + bv;
+                    if (g.addend) v += g.addend[m * g.ld_add + col];
+                }
+                if (g.C_raw) g.C_raw[m * g.ld_raw + col] = v;
+                if (col < g.N) {
+                    if (g.rowscale && col < rs_cols) v *= g.rowscale[m];
+                    if (g.relu) v = v > 0.f ? v : 0.f;
+                    if (g.mask) v = g.mask[m * g.ld_mask + col] > 0.f ? v : 0.f;
+                }
+                g.C[m * g.ldc + col] = v;
+            }
+        }
 }
 
 // ------------------------------------------------------------------------------- NN
@@ -187,6 +286,16 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
                 const int kb = imin(k0 + k, Kc - 1);
                 const int nc = imin(n0 + 4 * nq, npad - 4);
                 rb[r] = ldg_raw4<float>(Bp + (int64_t)kb * ldb + nc);
+            } else if (g.Bt) {                           // B given transposed: element (k, n) is Bt[n][k]
+                const float* Btp = second ? g.Bt2 : g.Bt;
+                const int64_t ldbt = second ? g.ldbt2 : g.ldbt;
+                float o[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n0 + 4 * nq + q;
+                    o[q] = (k0 + k < Kc && n < g.N) ? Btp[(int64_t)n * ldbt + k0 + k] : 0.f;
+                }
+                rb[r] = make_uint4(__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3]));
             } else {
                 const bool ok = k0 + k < Kc;
                 rb[r] = ldg_safe4<float>(Bp + (int64_t)(ok ? k0 + k : 0) * ldb, ok, n0 + 4 * nq, g.N);
@@ -237,88 +346,176 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
         __syncthreads();
     }
 
+    nn_epilogue<VEC, WM, WN, TM, TN>(g, acc, lds, m0, n0, n_store);
+}
+
+// ------------------------------------------------------------------------------- NT (fast path of nn)
+// Same product as gemm_nn with B supplied transposed (Bt[N x K], k contiguous), which is how
+// the step keeps its weight matrices.  Both operands are then loaded along k as 16-byte
+// vectors and written to LDS unchanged (row-major [row][k], pitch 36 floats: the 16-byte
+// writes and reads of eight consecutive lanes fall in distinct banks).  A lane of the MFMA
+// reads its four consecutive k values with one 16-byte LDS read and uses them in four
+// consecutive MFMAs: within a k-tile, step (s, t) multiplies k = 8s + 4*(lane/32) + t from
+// both operands, a permutation of the tile's 32 k values.  Addressing is hoisted out of the
+// k loop and only the last, ragged k-tile is masked.
+template <typename AT, int WM, int WN, int TM, int TN, bool ROWLIMIT, int BKT, int NBUF>
+__global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNNArgs g) {
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr int PK = BKT + 4;
+    constexpr int KQ = BKT / 4;                       // 16-byte slots per tile row
+    constexpr int RSTEP = 256 / KQ;                   // tile rows covered by one pass of the workgroup
+    constexpr int A_REPS = BM * BKT / 4 / 256, B_REPS = BN * BKT / 4 / 256;
+    constexpr bool A_BF16 = sizeof(AT) == 2;
+    static_assert(BM * BKT / 4 % 256 == 0 && BN * BKT / 4 % 256 == 0 && BKT % 8 == 0, "tiles must fill the workgroup");
+    constexpr int PC = BN + 4;
+    constexpr int MAIN_FLOATS = NBUF * (BM + BN) * PK;
+    constexpr int EPI_FLOATS = WM * 32 * PC;
+    constexpr int LDS_FLOATS = MAIN_FLOATS > EPI_FLOATS ? MAIN_FLOATS : EPI_FLOATS;
+    __shared__ __attribute__((aligned(16))) float lds[LDS_FLOATS];
+    float* const As0 = lds;
+    float* const Bs0 = lds + NBUF * BM * PK;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lk = lane >> 5;
-    // Epilogue.  When every operand allows 16-byte accesses the accumulators go through LDS,
-    // 32 tile rows per wavefront row at a time, so that bias / addend / mask are read and the
-    // results written as whole 16-byte vectors along rows (one 512-byte run per 32 lanes).
-    const bool vec_epi = VEC && (n_store % 4 == 0) && g.ldc % 4 == 0 && ((uintptr_t)g.C % 16) == 0 &&
-                         (!g.addend || (g.ld_add % 4 == 0 && ((uintptr_t)g.addend % 16) == 0)) &&
-                         (!g.mask || (g.ld_mask % 4 == 0 && ((uintptr_t)g.mask % 16) == 0)) &&
-                         (!g.C_raw || (g.ld_raw % 4 == 0 && ((uintptr_t)g.C_raw % 16) == 0));
-    const int bias_n = g.bias_n > 0 ? g.bias_n : g.N - g.bias_col0;
-    const int rs_cols = g.rowscale_cols > 0 ? g.rowscale_cols : g.N;   // a multiple of 4 when set
-    if (vec_epi) {
-        float* Cs = lds;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            if (i > 0) __syncthreads();               // the previous pass has been read out
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    Cs[(wm * 32 + 8 * (r / 4) + 4 * lk + (r % 4)) * PC + (wn * TN + j) * 32 + li] = acc[i][j][r];
-            __syncthreads();
-            constexpr int C4 = BN / 4;                // 16-byte columns per tile row
-            for (int f = tid; f < WM * 32 * C4; f += 256) {
-                const int lr = f / C4, c4 = f % C4;
-                const int col = n0 + 4 * c4;
-                const int64_t m = m0 + ((lr >> 5) * TM + i) * 32 + (lr & 31);
-                if (m >= g.M || col >= n_store) continue;
-                const float4 a4 = *reinterpret_cast<const float4*>(&Cs[lr * PC + 4 * c4]);
-                float v[4] = {a4.x, a4.y, a4.z, a4.w};
-                if (g.addend) {
-                    const float4 t = *reinterpret_cast<const float4*>(g.addend + m * g.ld_add + col);
-                    v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
-                }
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int cb = col + q - g.bias_col0;
-                    if (col + q < g.N) { if (g.bias && cb >= 0 && cb < bias_n) v[q] += g.bias[cb]; }
-                    else v[q] = 0.f;
-                }
-                if (g.C_raw) *reinterpret_cast<float4*>(g.C_raw + m * g.ld_raw + col) = make_float4(v[0], v[1], v[2], v[3]);
-                const float rs = (g.rowscale && col < rs_cols) ? g.rowscale[m] : 1.f;
-                float4 mk = make_float4(1.f, 1.f, 1.f, 1.f);
-                if (g.mask) mk = *reinterpret_cast<const float4*>(g.mask + m * g.ld_mask + col);
-                const float mv[4] = {mk.x, mk.y, mk.z, mk.w};
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float t = v[q] * rs;
-                    if (g.relu) t = t > 0.f ? t : 0.f;
-                    if (g.mask) t = mv[q] > 0.f ? t : 0.f;
-                    v[q] = col + q < g.N ? t : 0.f;
-                }
-                *reinterpret_cast<float4*>(g.C + m * g.ldc + col) = make_float4(v[0], v[1], v[2], v[3]);
-            }
-        }
-        return;
-    }
+    const int n_store = g.zero_pad_to > g.N ? g.zero_pad_to : g.N;
+    const int n_tiles = (n_store + BN - 1) / BN;
+    const int64_t hq = blockIdx.x / NXCD;
+    const int64_t slab = (hq / n_tiles) * NXCD + blockIdx.x % NXCD;
+    const int64_t m0 = slab * BM;
+    const int n0 = (int)(hq % n_tiles) * BN;
+    if (m0 >= g.M) return;
+
+    floatx16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + (wn * TN + j) * 32 + li;
-            if (col >= n_store) continue;
-            const int cb = col - g.bias_col0;
-            const float bv = (g.bias && col < g.N && cb >= 0 && cb < bias_n) ? g.bias[cb] : 0.f;
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
-                if (m >= g.M) continue;
-                float v = 0.f;
-                if (col < g.N) {
-                    v = acc[i][j][r] + bv;
-                    if (g.addend) v += g.addend[m * g.ld_add + col];
-                }
-                if (g.C_raw) g.C_raw[m * g.ld_raw + col] = v;
-                if (col < g.N) {
-                    if (g.rowscale && col < rs_cols) v *= g.rowscale[m];
-                    if (g.relu) v = v > 0.f ? v : 0.f;
-                    if (g.mask) v = g.mask[m * g.ld_mask + col] > 0.f ? v : 0.f;
-                }
-                g.C[m * g.ldc + col] = v;
-            }
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // per-thread element offsets of its 16-byte slots (k offset 4*kq included), both products
+    const int kq4 = 4 * (tid % KQ);
+    const int trow = tid / KQ;
+    const int64_t a_valid = g.a_valid_rows > 0 ? g.a_valid_rows : g.M;
+    int64_t aoff[A_REPS], aoff2[A_REPS], boff[B_REPS], boff2[B_REPS];
+    bool a_zero[A_REPS], b_zero[B_REPS];
+#pragma unroll
+    for (int r = 0; r < A_REPS; ++r) {
+        const int64_t row = m0 + trow + RSTEP * r;
+        const int64_t r1 = lmin(row, a_valid - 1);
+        aoff[r] = (g.a_rows ? (int64_t)g.a_rows[r1] : r1) * g.lda;
+        aoff2[r] = lmin(row, g.M - 1) * g.lda2;
+        a_zero[r] = ROWLIMIT && row >= a_valid;          // rows >= M are never stored: no need to zero them
+    }
+#pragma unroll
+    for (int r = 0; r < B_REPS; ++r) {
+        const int n = n0 + trow + RSTEP * r;
+        const int nc = imin(n, g.N - 1);
+        boff[r] = (int64_t)nc * g.ldbt;
+        boff2[r] = (int64_t)nc * g.ldbt2;
+        b_zero[r] = n >= g.N;
+    }
+
+    const int nk1 = (g.K + BKT - 1) / BKT;
+    const int nk2 = (g.K2 + BKT - 1) / BKT;
+    const int nk = nk1 + nk2;
+    uint4 ra[A_REPS], rb[B_REPS];
+
+    auto fetch = [&](int kt) {
+        const bool second = kt >= nk1;
+        const int k0 = (second ? kt - nk1 : kt) * BKT;
+        const int Kc = second ? g.K2 : g.K;
+        const int kk = imin(k0 + kq4, ((Kc + 3) & ~3) - 4);   // clamped into the operand; masked when staged
+        if (second) {
+#pragma unroll
+            for (int r = 0; r < A_REPS; ++r) ra[r] = ldg_raw4<float>(g.A2 + aoff2[r] + kk);
+#pragma unroll
+            for (int r = 0; r < B_REPS; ++r) rb[r] = ldg_raw4<float>(g.Bt2 + boff2[r] + kk);
+        } else {
+#pragma unroll
+            for (int r = 0; r < A_REPS; ++r) ra[r] = ldg_raw4<AT>((const AT*)g.A + aoff[r] + kk);
+#pragma unroll
+            for (int r = 0; r < B_REPS; ++r) rb[r] = ldg_raw4<float>(g.Bt + boff[r] + kk);
         }
+    };
+    auto stage = [&](int kt) {
+        const bool second = kt >= nk1;
+        const int k0 = (second ? kt - nk1 : kt) * BKT;
+        const int Kc = second ? g.K2 : g.K;
+        const bool ragged = k0 + BKT > Kc;                // uniform: only the last k-tile of a product
+        const int kbase = k0 + kq4;
+        float* As = As0 + (NBUF == 1 ? 0 : (kt & 1)) * BM * PK;
+        float* Bs = Bs0 + (NBUF == 1 ? 0 : (kt & 1)) * BN * PK;
+#pragma unroll
+        for (int r = 0; r < A_REPS; ++r) {
+            float v[4];
+            unpack4(ra[r], A_BF16 && !second, v);
+            if (ragged) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) v[q] = kbase + q < Kc ? v[q] : 0.f;
+            }
+            if (ROWLIMIT && !second && a_zero[r]) { v[0] = v[1] = v[2] = v[3] = 0.f; }
+            *reinterpret_cast<float4*>(&As[(trow + RSTEP * r) * PK + kq4]) = make_float4(v[0], v[1], v[2], v[3]);
+        }
+#pragma unroll
+        for (int r = 0; r < B_REPS; ++r) {
+            float v[4];
+            unpack4(rb[r], false, v);
+            if (ragged) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) v[q] = kbase + q < Kc ? v[q] : 0.f;
+            }
+            if (b_zero[r]) { v[0] = v[1] = v[2] = v[3] = 0.f; }
+            *reinterpret_cast<float4*>(&Bs[(trow + RSTEP * r) * PK + kq4]) = make_float4(v[0], v[1], v[2], v[3]);
+        }
+    };
+
+    auto mma = [&](int kt) {
+        const float* ap = As0 + (NBUF == 1 ? 0 : (kt & 1)) * BM * PK + (wm * TM * 32 + li) * PK + 4 * lk;
+        const float* bp = Bs0 + (NBUF == 1 ? 0 : (kt & 1)) * BN * PK + (wn * TN * 32 + li) * PK + 4 * lk;
+        float4 a4[2][TM], b4[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a4[0][i] = *reinterpret_cast<const float4*>(ap + 32 * i * PK);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b4[0][j] = *reinterpret_cast<const float4*>(bp + 32 * j * PK);
+#pragma unroll
+        for (int s = 0; s < BKT / 8; ++s) {
+            const int cur = s & 1, nxt = cur ^ 1;
+            if (s + 1 < BKT / 8) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) a4[nxt][i] = *reinterpret_cast<const float4*>(ap + 32 * i * PK + 8 * (s + 1));
+#pragma unroll
+                for (int j = 0; j < TN; ++j) b4[nxt][j] = *reinterpret_cast<const float4*>(bp + 32 * j * PK + 8 * (s + 1));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const float av = t == 0 ? a4[cur][i].x : t == 1 ? a4[cur][i].y : t == 2 ? a4[cur][i].z : a4[cur][i].w;
+                        const float bv = t == 0 ? b4[cur][j].x : t == 1 ? b4[cur][j].y : t == 2 ? b4[cur][j].z : b4[cur][j].w;
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                    }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) fetch(kt + 1);
+        mma(kt);
+        if (NBUF == 1) __syncthreads();
+        if (kt + 1 < nk) stage(kt + 1);
+        __syncthreads();
+    }
+    nn_epilogue<true, WM, WN, TM, TN>(g, acc, lds, m0, n0, n_store);
 }
 
 // Tile choice (measured on MI355X at M = 3e5): 128 x 128 output tiles at three workgroups per
@@ -342,12 +539,12 @@ static void nn_pick(const GemmNNArgs& a, hipStream_t st) {
 
 grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
     if (a.M == 0 || a.N == 0) return GRP_OK;
-    if (a.M < 0 || a.N < 0 || a.K <= 0 || !a.A || !a.B || !a.C) return fail(GRP_EINVAL, "gemm_nn: bad arguments");
-    if (a.K2 > 0 && (!a.A2 || !a.B2 || a.lda2 % 4 != 0 || a.lda2 < round_up(a.K2, 4) || (uintptr_t)a.A2 % 16 != 0))
+    if (a.M < 0 || a.N < 0 || a.K <= 0 || !a.A || (!a.B && !a.Bt) || !a.C) return fail(GRP_EINVAL, "gemm_nn: bad arguments");
+    if (a.K2 > 0 && (!a.A2 || (!a.B2 && !a.Bt2) || a.lda2 % 4 != 0 || a.lda2 < round_up(a.K2, 4) || (uintptr_t)a.A2 % 16 != 0))
         return fail(GRP_EINVAL, "gemm_nn: second operand must be 16-byte aligned with a pitch multiple of 4");
     const int elem = a.a_bf16 ? 2 : 4;
     const bool veca = a.lda % 4 == 0 && a.lda >= round_up(a.K, 4) && (uintptr_t)a.A % (4 * elem) == 0;
-    const bool vecb = a.ldb % 4 == 0 && a.ldb >= round_up(a.N, 4) && (uintptr_t)a.B % 16 == 0 &&
+    const bool vecb = a.B && a.ldb % 4 == 0 && a.ldb >= round_up(a.N, 4) && (uintptr_t)a.B % 16 == 0 &&
                       (a.K2 == 0 || (a.ldb2 % 4 == 0 && a.ldb2 >= round_up(a.N, 4) && (uintptr_t)a.B2 % 16 == 0));
     const double nn_flops = 2.0 * a.M * a.N * ((double)a.K + a.K2);
     const double nn_bytes = (double)a.M * a.K * elem + 4.0 * a.M * a.K2 + 4.0 * a.N * ((double)a.K + a.K2) +
@@ -355,6 +552,39 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
     prof_detail("[M=%lld,N=%d,K=%d+%d%s%s%s]", (long long)a.M, a.N, a.K, a.K2, a.addend ? ",add" : "", a.mask ? ",mask" : "",
                 a.rowscale ? ",rs" : "");
     ProfScope ps(a.a_bf16 ? "gemm_nn_bf16a" : "gemm_nn_f32", st, nn_flops, nn_bytes);
+    if (a.Bt) {
+        const bool ok = veca && a.ldbt % 4 == 0 && a.ldbt >= round_up(a.K, 4) && (uintptr_t)a.Bt % 16 == 0 &&
+                        (a.K2 == 0 || (a.Bt2 && a.ldbt2 % 4 == 0 && a.ldbt2 >= round_up(a.K2, 4) && (uintptr_t)a.Bt2 % 16 == 0));
+        if (!ok) {                                       // slow, always-safe kernel
+            if (a.a_bf16) nn_pick<__hip_bfloat16, false>(a, st); else nn_pick<float, false>(a, st);
+            GRP_LAUNCH_CHECK();
+            return GRP_OK;
+        }
+        const int n_eff = a.zero_pad_to > a.N ? a.zero_pad_to : a.N;
+        const int64_t slabs = round_up(cdiv(a.M, 128), NXCD);
+        const bool rowlimit = a.a_valid_rows > 0 && a.a_valid_rows < a.M;
+        const unsigned blocks = (unsigned)(slabs * cdiv(n_eff, n_eff > 64 ? 128 : 64));
+        const bool short_k = a.K <= 128 || (a.K2 > 0 && a.K2 <= 128);
+#define GRP_NT_LAUNCH2(AT, WM_, WN_, TM_, TN_, RL)                                                                        \
+    do {                                                                                                                  \
+        if (short_k) hipLaunchKernelGGL((gemm_nt_kernel<AT, WM_, WN_, TM_, TN_, RL, 16, 2>), dim3(blocks), dim3(256), 0, st, a); \
+        else hipLaunchKernelGGL((gemm_nt_kernel<AT, WM_, WN_, TM_, TN_, RL, 32, 1>), dim3(blocks), dim3(256), 0, st, a);         \
+    } while (0)
+#define GRP_NT_LAUNCH(AT, WM_, WN_, TM_, TN_)                                                                       \
+    do {                                                                                                            \
+        if (rowlimit) GRP_NT_LAUNCH2(AT, WM_, WN_, TM_, TN_, true);                                                 \
+        else GRP_NT_LAUNCH2(AT, WM_, WN_, TM_, TN_, false);                                                         \
+    } while (0)
+        if (n_eff > 64) {
+            if (a.a_bf16) GRP_NT_LAUNCH(__hip_bfloat16, 2, 2, 2, 2); else GRP_NT_LAUNCH(float, 2, 2, 2, 2);
+        } else {
+            if (a.a_bf16) GRP_NT_LAUNCH(__hip_bfloat16, 4, 1, 1, 2); else GRP_NT_LAUNCH(float, 4, 1, 1, 2);
+        }
+#undef GRP_NT_LAUNCH
+#undef GRP_NT_LAUNCH2
+        GRP_LAUNCH_CHECK();
+        return GRP_OK;
+    }
     if (a.a_bf16) {
         if (veca && vecb) nn_pick<__hip_bfloat16, true>(a, st);
         else nn_pick<__hip_bfloat16, false>(a, st);
@@ -602,6 +832,16 @@ extern "C" grp_status grp_gemm_nn(int64_t M, int32_t N, int32_t K, const void* A
     grp::GemmNNArgs a;
     a.M = M; a.N = N; a.K = K; a.A = A; a.lda = lda; a.a_bf16 = a_dtype == GRP_DTYPE_BF16;
     a.B = B; a.ldb = ldb; a.C = C; a.ldc = ldc;
+    return grp::launch_gemm_nn(a, (hipStream_t)stream);
+}
+
+extern "C" grp_status grp_gemm_nt(int64_t M, int32_t N, int32_t K, const void* A, int64_t lda, int32_t a_dtype,
+                                  const float* Bt, int64_t ldbt, float* C, int64_t ldc, void* stream) {
+    if (!A || !Bt || !C) return grp::fail(GRP_EINVAL, "grp_gemm_nt: null argument");
+    if (M < 0 || N <= 0 || K <= 0 || lda < K || ldbt < K || ldc < N) return grp::fail(GRP_EINVAL, "grp_gemm_nt: bad shape");
+    grp::GemmNNArgs a;
+    a.M = M; a.N = N; a.K = K; a.A = A; a.lda = lda; a.a_bf16 = a_dtype == GRP_DTYPE_BF16;
+    a.Bt = Bt; a.ldbt = ldbt; a.C = C; a.ldc = ldc;
     return grp::launch_gemm_nn(a, (hipStream_t)stream);
 }
 

@@ -18,9 +18,9 @@ static inline int64_t ldp(int64_t f) { return round_up(f, 4); }
 static inline bool measure_only(const void* p) { return p == nullptr; }
 
 struct LayerBufs {
-    float* Wp_s = nullptr;   // [Fin x ld(Fout)] aligned copy of W_self (GCN: W)
+    float* Wp_s = nullptr;   // [ld(Fin) x ld(Fout)] aligned, zero-padded copy of W_self (GCN: W)
     float* Wp_n = nullptr;   // same for W_neigh
-    float* Wt_s = nullptr;   // [Fout x ld(Fin)] transpose of W_self
+    float* Wt_s = nullptr;   // [ld(Fout) x ld(Fin)] transpose of W_self
     float* Wt_n = nullptr;
     float* M = nullptr;      // [rows x ld(Fin)] aggregated input (aggregate-first SAGE layers)
     float* H_out = nullptr;  // [rows x ld(Fout)] layer output (post-activation; logits for the last layer)
@@ -96,18 +96,20 @@ static StepPlan make_plan(const grp_partition_t* part, const grp_model_desc* m, 
         L.agg_first = sage && (fin <= fout || (mb && l == 0));
         L.skip = m->arch == GRP_ARCH_GCN_RESIDUAL && fin == fout && l < k - 1;
         if (sage) {
-            L.ldwp = 2 * ldp(fout);
-            L.ldwt = 2 * ldp(fin);
-            float* wp = b.take<float>((size_t)fin * L.ldwp);
-            float* wt = b.take<float>((size_t)fout * L.ldwt);
-            L.Wp_n = wp; L.Wp_s = measure_only(wp) ? nullptr : wp + ldp(fout);
-            L.Wt_n = wt; L.Wt_s = measure_only(wt) ? nullptr : wt + ldp(fin);
+            // W_neigh stacked on top of W_self (row offset rounded up to 4, pad rows zero), so that
+            // one product can span both: [.. | ..] = X [Wn | Ws] reads the stack as one Bt.
+            L.ldwp = ldp(fout);
+            L.ldwt = ldp(fin);
+            float* wp = b.take<float>((size_t)2 * ldp(fin) * L.ldwp);
+            float* wt = b.take<float>((size_t)2 * ldp(fout) * L.ldwt);
+            L.Wp_n = wp; L.Wp_s = measure_only(wp) ? nullptr : wp + ldp(fin) * L.ldwp;
+            L.Wt_n = wt; L.Wt_s = measure_only(wt) ? nullptr : wt + ldp(fout) * L.ldwt;
             if (L.agg_first) L.M = b.take<float>((size_t)rows * ldp(fin));
         } else {
             L.ldwp = ldp(fout);
             L.ldwt = ldp(fin);
-            L.Wp_s = b.take<float>((size_t)fin * ldp(fout));
-            L.Wt_s = b.take<float>((size_t)fout * ldp(fin));
+            L.Wp_s = b.take<float>((size_t)ldp(fin) * ldp(fout));
+            L.Wt_s = b.take<float>((size_t)ldp(fout) * ldp(fin));
         }
         L.H_out = b.take<float>((size_t)rows * ldp(fout));
         if (L.skip) L.Act = b.take<float>((size_t)rows * ldp(fout));
@@ -180,11 +182,13 @@ static grp_status prep_weights(const grp_model_desc* m, const float* theta, Step
     for (int l = 0; l < m->n_layers; ++l) {
         const LayerBufs& L = p.L[l];
         const int fin = m->dims[l], fout = m->dims[l + 1];
-        GRP_TRY(launch_pad_copy(theta + L.off_ws, fin, fout, L.Wp_s, L.ldwp, st));
-        if (sage) GRP_TRY(launch_pad_copy(theta + L.off_wn, fin, fout, L.Wp_n, L.ldwp, st));
+        // the products read their weights transposed: forward uses W^T (rows = outputs), the
+        // backward pass to the layer below uses W itself (rows = inputs)
+        GRP_TRY(launch_transpose(theta + L.off_ws, fin, fout, L.Wt_s, L.ldwt, (int)ldp(fout), st));
+        if (sage) GRP_TRY(launch_transpose(theta + L.off_wn, fin, fout, L.Wt_n, L.ldwt, (int)ldp(fout), st));
         if (l > 0) {
-            GRP_TRY(launch_transpose(theta + L.off_ws, fin, fout, L.Wt_s, L.ldwt, fout, st));
-            if (sage) GRP_TRY(launch_transpose(theta + L.off_wn, fin, fout, L.Wt_n, L.ldwt, fout, st));
+            GRP_TRY(launch_pad_copy(theta + L.off_ws, fin, fout, (int)ldp(fin), L.Wp_s, L.ldwp, st));
+            if (sage) GRP_TRY(launch_pad_copy(theta + L.off_wn, fin, fout, (int)ldp(fin), L.Wp_n, L.ldwp, st));
         }
     }
     return GRP_OK;
@@ -215,8 +219,8 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             GRP_TRY(launch_spmm(s, st));
             GemmNNArgs a;
             a.M = B.n_dst; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.a_rows = B.self_rows;
-            a.B = L.Wp_s; a.ldb = L.ldwp;
-            a.K2 = fin; a.A2 = L.M; a.lda2 = ldp(fin); a.B2 = L.Wp_n; a.ldb2 = L.ldwp;
+            a.Bt = L.Wt_s; a.ldbt = L.ldwt;
+            a.K2 = fin; a.A2 = L.M; a.lda2 = ldp(fin); a.Bt2 = L.Wt_n; a.ldbt2 = L.ldwt;
             a.bias = theta + L.off_b; a.relu = relu; a.C = L.H_out; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
             GRP_TRY(launch_gemm_nn(a, st));
         } else if (B.n_in == B.n_dst && !B.self_rows) {
@@ -225,7 +229,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             const int64_t w2 = 2 * ldp(fout);
             GemmNNArgs a;
             a.M = B.n_dst; a.N = (int)(ldp(fout) + fout); a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16;
-            a.B = L.Wp_n; a.ldb = L.ldwp; a.bias = theta + L.off_b; a.bias_col0 = (int)ldp(fout); a.bias_n = fout;
+            a.Bt = L.Wt_n; a.ldbt = L.ldwt; a.bias = theta + L.off_b; a.bias_col0 = (int)ldp(fout); a.bias_n = fout;
             a.C = p.tmpA; a.ldc = w2; a.zero_pad_to = (int)w2;
             GRP_TRY(launch_gemm_nn(a, st));
             SpmmArgs s;
@@ -235,10 +239,10 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             GRP_TRY(launch_spmm(s, st));
         } else {
             GemmNNArgs a;      // T = H Wn over every input row, Z0 = H_self Ws + b
-            a.M = B.n_in; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.B = L.Wp_n; a.ldb = L.ldwp;
+            a.M = B.n_in; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.Bt = L.Wt_n; a.ldbt = L.ldwt;
             a.C = p.tmpA; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
             GRP_TRY(launch_gemm_nn(a, st));
-            a.M = B.n_dst; a.a_rows = B.self_rows; a.B = L.Wp_s; a.ldb = L.ldwp; a.bias = theta + L.off_b; a.C = L.H_out;
+            a.M = B.n_dst; a.a_rows = B.self_rows; a.Bt = L.Wt_s; a.bias = theta + L.off_b; a.C = L.H_out;
             GRP_TRY(launch_gemm_nn(a, st));
             SpmmArgs s;
             fill_spmm(s, B, false, p.partials);
@@ -281,7 +285,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
                 if (B.n_dst > 0) {
                     GemmNNArgs a;
                     a.M = B.n_dst; a.N = (int)(ldp(fin) + fin); a.K = fout; a.A = dZ; a.lda = ldp(fout);
-                    a.B = L.Wt_n; a.ldb = L.ldwt; a.rowscale = B.inv_in; a.rowscale_cols = (int)ldp(fin);
+                    a.Bt = L.Wp_n; a.ldbt = L.ldwp; a.rowscale = B.inv_in; a.rowscale_cols = (int)ldp(fin);
                     a.C = p.tmpA; a.ldc = w2; a.zero_pad_to = (int)w2;
                     GRP_TRY(launch_gemm_nn(a, st));
                 }
@@ -303,8 +307,8 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             if (l > 0 && B.n_in > 0) {
                 GemmNNArgs c;      // dZ_prev = mask * ([dZ Ws^T ; 0] + dT Wn^T)
                 c.M = B.n_in; c.N = fin; c.K = fout; c.A = dZ; c.lda = ldp(fout); c.a_valid_rows = B.n_dst;
-                c.B = L.Wt_s; c.ldb = L.ldwt;
-                c.K2 = fout; c.A2 = p.tmpA; c.lda2 = ldp(fout); c.B2 = L.Wt_n; c.ldb2 = L.ldwt;
+                c.Bt = L.Wp_s; c.ldbt = L.ldwp;
+                c.K2 = fout; c.A2 = p.tmpA; c.lda2 = ldp(fout); c.Bt2 = L.Wp_n; c.ldbt2 = L.ldwp;
                 c.mask = p.L[l - 1].H_out; c.ld_mask = ldp(fin);
                 c.C = dZ_other; c.ldc = ldp(fin); c.zero_pad_to = (int)ldp(fin);
                 GRP_TRY(launch_gemm_nn(c, st));
@@ -339,7 +343,7 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
         const LayerBufs& L = p.L[l];
         const int fin = m->dims[l], fout = m->dims[l + 1];
         GemmNNArgs a;
-        a.M = n; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.B = L.Wp_s; a.ldb = L.ldwp;
+        a.M = n; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.Bt = L.Wt_s; a.ldbt = L.ldwt;
         a.rowscale = p.gs; a.C = p.tmpA; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
         GRP_TRY(launch_gemm_nn(a, st));
         SpmmArgs s;
@@ -377,7 +381,7 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
         if (l > 0 && n > 0) {
             const LayerBufs& Lp = p.L[l - 1];
             GemmNNArgs c;      // G_in = dT W^T (+ G);  dZ'_prev = diag(r) (A_prev > 0) G_in
-            c.M = n; c.N = fin; c.K = fout; c.A = p.tmpA; c.lda = ldp(fout); c.B = L.Wt_s; c.ldb = L.ldwt;
+            c.M = n; c.N = fin; c.K = fout; c.A = p.tmpA; c.lda = ldp(fout); c.Bt = L.Wp_s; c.ldbt = L.ldwp;
             if (L.skip) { c.addend = G; c.ld_add = ldp(fout); }
             if (Lp.skip) { c.C_raw = G_other; c.ld_raw = ldp(fin); }
             c.rowscale = p.gr; c.mask = Lp.skip ? Lp.Act : Lp.H_out; c.ld_mask = ldp(fin);

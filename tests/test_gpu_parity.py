@@ -460,3 +460,17 @@ def test_residual_gcn_matches_oracle(g, dims, self_loops):
                                 gcn_self_loops=self_loops, relu_flip=relu_flip, near_kink=near_kink)
     og, ost = assert_step_grads_close(grad.cpu().numpy(), oracle_fn, "gcn_res", dims, TOL_FP32)
     _check_stats(g.read_stats(stats)[0], ost, TOL_FP32)
+
+
+@pytest.mark.parametrize("M,N,K,bf16", [(1000, 256, 256, False), (777, 47, 100, False), (4097, 172, 36, True),
+                                        (333, 130, 33, False), (129, 512, 48, False)])
+def test_gemm_nt_matches_numpy(g, M, N, K, bf16):
+    _note(f"gemm_nt M={M} N={N} K={K} bf16={bf16}")
+    a = synth.normal_matrix(M, K, 1)
+    a = (synth.to_bf16_rne(a) if bf16 else a).to(DEV)
+    bt = synth.normal_matrix(N, K, 2).to(DEV)
+    c = torch.full((M, N), float("nan"), device=DEV)
+    g.grp_gemm_nt(M, N, K, a, K, g.DTYPE_BF16 if bf16 else g.DTYPE_FP32, bt, K, c, N)
+    torch.cuda.synchronize()
+    want = a.cpu().double().numpy() @ bt.cpu().double().numpy().T
+    assert rel_err(c.cpu().numpy(), want) <= TOL_FP32
