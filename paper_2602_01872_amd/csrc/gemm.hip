@@ -20,6 +20,8 @@
 // they are written to LDS.
 #include "common.h"
 
+#include <type_traits>
+
 namespace grp {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -350,15 +352,83 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
 }
 
 // ------------------------------------------------------------------------------- NT (fast path of nn)
+// Epilogue of an interior tile (all 128 rows < M, all columns < N, bias and row scale either
+// cover the whole tile or none of it, every pointer and pitch 16-byte friendly).  A waiting
+// wavefront issues an instruction only every few cycles while another one feeds the matrix
+// pipe, so what counts here is the instruction count: uniform bases, 32-bit per-thread
+// offsets, immediate LDS offsets, the options applied without branches (neutral operands),
+// and all loads of a pass issued before its first store.
+template <int WM, int WN, int TM, int TN>
+__device__ __forceinline__ void nn_epilogue_interior(const GemmNNArgs& g, floatx16 (&acc)[TM][TN], float* lds, int64_t m0,
+                                                     int n0, bool use_bias, bool use_rs) {
+    constexpr int BN = WN * TN * 32;
+    constexpr int PC = BN + 4;
+    constexpr int C4 = BN / 4;                        // 16-byte columns per tile row
+    constexpr int RPI = 256 / C4;                     // tile rows covered by one pass of the workgroup
+    constexpr int ITS = WM * 32 / RPI;
+    static_assert(32 % RPI == 0, "a pass must not straddle two 32-row blocks");
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, lk = lane >> 5;
+    const uint32_t c4 = tid % C4, r0 = tid / C4;
+    const float* const rd = lds + r0 * PC + 4 * c4;
+    float* const wr = lds + (wm * 32 + 4 * lk) * PC + wn * TN * 32 + li;
+    float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (use_bias) b4 = *reinterpret_cast<const float4*>(g.bias + (n0 - g.bias_col0) + 4 * c4);
+    const float floor_v = g.relu ? 0.f : -INFINITY;
+    float* const Cb = g.C + m0 * g.ldc + n0;
+    float* const Rb = g.C_raw ? g.C_raw + m0 * g.ld_raw + n0 : nullptr;
+    const float* const Ab = g.addend ? g.addend + m0 * g.ld_add + n0 : nullptr;
+    const float* const Mb = g.mask ? g.mask + m0 * g.ld_mask + n0 : nullptr;
+    const float* const Sb = use_rs ? g.rowscale + m0 : nullptr;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        if (i > 0) __syncthreads();                   // the previous pass has been read out
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) wr[(8 * (r / 4) + (r % 4)) * PC + 32 * j] = acc[i][j][r];
+        __syncthreads();
+        float4 av[ITS], mv[ITS];
+        float rs[ITS];
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            const uint32_t row = ((RPI * it) / 32 * TM + i) * 32 + (RPI * it) % 32 + r0;
+            av[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            mv[it] = make_float4(1.f, 1.f, 1.f, 1.f);
+            rs[it] = 1.f;
+            if (Ab) av[it] = *reinterpret_cast<const float4*>(Ab + (row * (uint32_t)g.ld_add + 4 * c4));
+            if (Mb) mv[it] = *reinterpret_cast<const float4*>(Mb + (row * (uint32_t)g.ld_mask + 4 * c4));
+            if (Sb) rs[it] = Sb[row];
+        }
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            const uint32_t row = ((RPI * it) / 32 * TM + i) * 32 + (RPI * it) % 32 + r0;
+            float4 v = *reinterpret_cast<const float4*>(rd + RPI * it * PC);
+            v.x += av[it].x + b4.x; v.y += av[it].y + b4.y; v.z += av[it].z + b4.z; v.w += av[it].w + b4.w;
+            if (Rb) *reinterpret_cast<float4*>(Rb + (row * (uint32_t)g.ld_raw + 4 * c4)) = v;
+            v.x = fmaxf(v.x * rs[it], floor_v); v.y = fmaxf(v.y * rs[it], floor_v);
+            v.z = fmaxf(v.z * rs[it], floor_v); v.w = fmaxf(v.w * rs[it], floor_v);
+            v.x = mv[it].x > 0.f ? v.x : 0.f; v.y = mv[it].y > 0.f ? v.y : 0.f;
+            v.z = mv[it].z > 0.f ? v.z : 0.f; v.w = mv[it].w > 0.f ? v.w : 0.f;
+            *reinterpret_cast<float4*>(Cb + (row * (uint32_t)g.ldc + 4 * c4)) = v;
+        }
+    }
+}
+
 // Same product as gemm_nn with B supplied transposed (Bt[N x K], k contiguous), which is how
 // the step keeps its weight matrices.  Both operands are then loaded along k as 16-byte
 // vectors and written to LDS unchanged (row-major [row][k], pitch 36 floats: the 16-byte
 // writes and reads of eight consecutive lanes fall in distinct banks).  A lane of the MFMA
 // reads its four consecutive k values with one 16-byte LDS read and uses them in four
 // consecutive MFMAs: within a k-tile, step (s, t) multiplies k = 8s + 4*(lane/32) + t from
-// both operands, a permutation of the tile's 32 k values.  Addressing is hoisted out of the
-// k loop and only the last, ragged k-tile is masked.
-template <typename AT, int WM, int WN, int TM, int TN, bool ROWLIMIT, int BKT, int NBUF>
+// both operands, a permutation of the tile's 32 k values.  Loads use a uniform base that
+// advances along k plus 32-bit per-thread offsets fixed before the loop; rows past the end of
+// an operand are clamped to its last row (their products land in rows or columns the epilogue
+// does not store, or zero-fills); only the last, ragged k-tile of a product is masked.
+// IRREG selects the variant with gathered (a_rows) or limited (a_valid_rows) A rows.
+template <typename AT, int WM, int WN, int TM, int TN, bool IRREG, int BKT, int NBUF>
 __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNNArgs g) {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int PK = BKT + 4;
@@ -395,28 +465,38 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNNArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // per-thread element offsets of its 16-byte slots (k offset 4*kq included), both products
+    // Per-thread offsets of its 16-byte slots (k offset 4*kq included).  Regular variant: 32-bit
+    // offsets from the slab's first row; irregular variant: 64-bit offsets from the operand base.
     const int kq4 = 4 * (tid % KQ);
     const int trow = tid / KQ;
-    const int64_t a_valid = g.a_valid_rows > 0 ? g.a_valid_rows : g.M;
-    int64_t aoff[A_REPS], aoff2[A_REPS], boff[B_REPS], boff2[B_REPS];
-    bool a_zero[A_REPS], b_zero[B_REPS];
+    const int rows_here = (int)lmin((int64_t)BM, g.M - m0);
+    using aoff_t = typename std::conditional<IRREG, int64_t, uint32_t>::type;
+    aoff_t aoff[A_REPS];
+    uint32_t aoff2[A_REPS], boff[B_REPS], boff2[B_REPS];
+    bool a_zero[A_REPS];
+    const AT* a_base = (const AT*)g.A;
+    if (!IRREG) a_base += m0 * g.lda;
 #pragma unroll
     for (int r = 0; r < A_REPS; ++r) {
-        const int64_t row = m0 + trow + RSTEP * r;
-        const int64_t r1 = lmin(row, a_valid - 1);
-        aoff[r] = (g.a_rows ? (int64_t)g.a_rows[r1] : r1) * g.lda;
-        aoff2[r] = lmin(row, g.M - 1) * g.lda2;
-        a_zero[r] = ROWLIMIT && row >= a_valid;          // rows >= M are never stored: no need to zero them
+        const int lr = imin(trow + RSTEP * r, rows_here - 1);
+        if (IRREG) {
+            const int64_t a_valid = g.a_valid_rows > 0 ? g.a_valid_rows : g.M;
+            const int64_t r1 = lmin(m0 + lr, a_valid - 1);
+            aoff[r] = (aoff_t)((g.a_rows ? (int64_t)g.a_rows[r1] : r1) * g.lda + kq4);
+            a_zero[r] = m0 + lr >= a_valid;
+        } else {
+            aoff[r] = (aoff_t)((uint32_t)lr * (uint32_t)g.lda + kq4);
+            a_zero[r] = false;
+        }
+        aoff2[r] = (uint32_t)lr * (uint32_t)g.lda2 + kq4;
     }
 #pragma unroll
     for (int r = 0; r < B_REPS; ++r) {
-        const int n = n0 + trow + RSTEP * r;
-        const int nc = imin(n, g.N - 1);
-        boff[r] = (int64_t)nc * g.ldbt;
-        boff2[r] = (int64_t)nc * g.ldbt2;
-        b_zero[r] = n >= g.N;
+        const uint32_t nc = imin(n0 + trow + RSTEP * r, g.N - 1);
+        boff[r] = nc * (uint32_t)g.ldbt + kq4;
+        boff2[r] = nc * (uint32_t)g.ldbt2 + kq4;
     }
+    const float* const a2_base = g.A2 + m0 * g.lda2;
 
     const int nk1 = (g.K + BKT - 1) / BKT;
     const int nk2 = (g.K2 + BKT - 1) / BKT;
@@ -427,27 +507,42 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNNArgs g) {
         const bool second = kt >= nk1;
         const int k0 = (second ? kt - nk1 : kt) * BKT;
         const int Kc = second ? g.K2 : g.K;
-        const int kk = imin(k0 + kq4, ((Kc + 3) & ~3) - 4);   // clamped into the operand; masked when staged
+        // a ragged last tile reads the operand's last whole 16-byte slot again (masked when staged)
+        const int d = k0 + BKT > Kc ? imin(0, ((Kc + 3) & ~3) - 4 - k0 - kq4) : 0;
         if (second) {
+            const float* pa = a2_base + k0;
+            const float* pb = g.Bt2 + k0;
 #pragma unroll
-            for (int r = 0; r < A_REPS; ++r) ra[r] = ldg_raw4<float>(g.A2 + aoff2[r] + kk);
+            for (int r = 0; r < A_REPS; ++r) ra[r] = ldg_raw4<float>(pa + (aoff2[r] + d));
 #pragma unroll
-            for (int r = 0; r < B_REPS; ++r) rb[r] = ldg_raw4<float>(g.Bt2 + boff2[r] + kk);
+            for (int r = 0; r < B_REPS; ++r) rb[r] = ldg_raw4<float>(pb + (boff2[r] + d));
         } else {
+            const AT* pa = a_base + k0;
+            const float* pb = g.Bt + k0;
 #pragma unroll
-            for (int r = 0; r < A_REPS; ++r) ra[r] = ldg_raw4<AT>((const AT*)g.A + aoff[r] + kk);
+            for (int r = 0; r < A_REPS; ++r) ra[r] = ldg_raw4<AT>(pa + (aoff[r] + d));
 #pragma unroll
-            for (int r = 0; r < B_REPS; ++r) rb[r] = ldg_raw4<float>(g.Bt + boff[r] + kk);
+            for (int r = 0; r < B_REPS; ++r) rb[r] = ldg_raw4<float>(pb + (boff[r] + d));
         }
     };
+    float* const as_w = As0 + trow * PK + kq4;
+    float* const bs_w = Bs0 + trow * PK + kq4;
     auto stage = [&](int kt) {
         const bool second = kt >= nk1;
         const int k0 = (second ? kt - nk1 : kt) * BKT;
         const int Kc = second ? g.K2 : g.K;
         const bool ragged = k0 + BKT > Kc;                // uniform: only the last k-tile of a product
         const int kbase = k0 + kq4;
-        float* As = As0 + (NBUF == 1 ? 0 : (kt & 1)) * BM * PK;
-        float* Bs = Bs0 + (NBUF == 1 ? 0 : (kt & 1)) * BN * PK;
+        const int buf = NBUF == 1 ? 0 : (kt & 1);
+        float* As = as_w + buf * BM * PK;
+        float* Bs = bs_w + buf * BN * PK;
+        if (!ragged && !(A_BF16 && !second) && !IRREG) {  // common case: registers go to LDS as loaded
+#pragma unroll
+            for (int r = 0; r < A_REPS; ++r) *reinterpret_cast<uint4*>(As + RSTEP * r * PK) = ra[r];
+#pragma unroll
+            for (int r = 0; r < B_REPS; ++r) *reinterpret_cast<uint4*>(Bs + RSTEP * r * PK) = rb[r];
+            return;
+        }
 #pragma unroll
         for (int r = 0; r < A_REPS; ++r) {
             float v[4];
@@ -456,8 +551,8 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNNArgs g) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) v[q] = kbase + q < Kc ? v[q] : 0.f;
             }
-            if (ROWLIMIT && !second && a_zero[r]) { v[0] = v[1] = v[2] = v[3] = 0.f; }
-            *reinterpret_cast<float4*>(&As[(trow + RSTEP * r) * PK + kq4]) = make_float4(v[0], v[1], v[2], v[3]);
+            if (IRREG && !second && a_zero[r]) { v[0] = v[1] = v[2] = v[3] = 0.f; }
+            *reinterpret_cast<float4*>(As + RSTEP * r * PK) = make_float4(v[0], v[1], v[2], v[3]);
         }
 #pragma unroll
         for (int r = 0; r < B_REPS; ++r) {
@@ -467,14 +562,15 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNNArgs g) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) v[q] = kbase + q < Kc ? v[q] : 0.f;
             }
-            if (b_zero[r]) { v[0] = v[1] = v[2] = v[3] = 0.f; }
-            *reinterpret_cast<float4*>(&Bs[(trow + RSTEP * r) * PK + kq4]) = make_float4(v[0], v[1], v[2], v[3]);
+            *reinterpret_cast<float4*>(Bs + RSTEP * r * PK) = make_float4(v[0], v[1], v[2], v[3]);
         }
     };
 
+    const float* const ap0 = As0 + (wm * TM * 32 + li) * PK + 4 * lk;
+    const float* const bp0 = Bs0 + (wn * TN * 32 + li) * PK + 4 * lk;
     auto mma = [&](int kt) {
-        const float* ap = As0 + (NBUF == 1 ? 0 : (kt & 1)) * BM * PK + (wm * TM * 32 + li) * PK + 4 * lk;
-        const float* bp = Bs0 + (NBUF == 1 ? 0 : (kt & 1)) * BN * PK + (wn * TN * 32 + li) * PK + 4 * lk;
+        const float* ap = ap0 + (NBUF == 1 ? 0 : (kt & 1)) * BM * PK;
+        const float* bp = bp0 + (NBUF == 1 ? 0 : (kt & 1)) * BN * PK;
         float4 a4[2][TM], b4[2][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i) a4[0][i] = *reinterpret_cast<const float4*>(ap + 32 * i * PK);
@@ -515,7 +611,21 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNNArgs g) {
         if (kt + 1 < nk) stage(kt + 1);
         __syncthreads();
     }
-    nn_epilogue<true, WM, WN, TM, TN>(g, acc, lds, m0, n0, n_store);
+    // interior tiles take the lean epilogue; edge tiles and awkward operands the general one
+    const int bias_n = g.bias_n > 0 ? g.bias_n : g.N - g.bias_col0;
+    const int rs_cols = g.rowscale_cols > 0 ? g.rowscale_cols : g.N;
+    const bool bias_in = g.bias && n0 >= g.bias_col0 && n0 + BN <= g.bias_col0 + bias_n;
+    const bool bias_out = !g.bias || n0 + BN <= g.bias_col0 || n0 >= g.bias_col0 + bias_n;
+    const bool rs_in = g.rowscale && n0 + BN <= rs_cols;
+    const bool rs_out = !g.rowscale || n0 >= rs_cols;
+    const bool interior = m0 + BM <= g.M && n0 + BN <= g.N && (bias_in || bias_out) && (rs_in || rs_out) &&
+                          g.ldc % 4 == 0 && ((uintptr_t)g.C % 16) == 0 &&
+                          (!g.addend || (g.ld_add % 4 == 0 && ((uintptr_t)g.addend % 16) == 0)) &&
+                          (!g.mask || (g.ld_mask % 4 == 0 && ((uintptr_t)g.mask % 16) == 0)) &&
+                          (!g.C_raw || (g.ld_raw % 4 == 0 && ((uintptr_t)g.C_raw % 16) == 0)) &&
+                          (!bias_in || (g.bias_col0 % 4 == 0 && ((uintptr_t)g.bias % 16) == 0));
+    if (interior) nn_epilogue_interior<WM, WN, TM, TN>(g, acc, lds, m0, n0, bias_in, rs_in);
+    else nn_epilogue<true, WM, WN, TM, TN>(g, acc, lds, m0, n0, n_store);
 }
 
 // Tile choice (measured on MI355X at M = 3e5): 128 x 128 output tiles at three workgroups per
@@ -553,7 +663,10 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
                 a.rowscale ? ",rs" : "");
     ProfScope ps(a.a_bf16 ? "gemm_nn_bf16a" : "gemm_nn_f32", st, nn_flops, nn_bytes);
     if (a.Bt) {
-        const bool ok = veca && a.ldbt % 4 == 0 && a.ldbt >= round_up(a.K, 4) && (uintptr_t)a.Bt % 16 == 0 &&
+        // 32-bit element offsets inside a slab and inside Bt
+        const bool small = a.lda < (1 << 23) && a.lda2 < (1 << 23) && (int64_t)a.N * a.ldbt < (1ll << 31) &&
+                           (int64_t)a.N * a.ldbt2 < (1ll << 31);
+        const bool ok = small && veca && a.ldbt % 4 == 0 && a.ldbt >= round_up(a.K, 4) && (uintptr_t)a.Bt % 16 == 0 &&
                         (a.K2 == 0 || (a.Bt2 && a.ldbt2 % 4 == 0 && a.ldbt2 >= round_up(a.K2, 4) && (uintptr_t)a.Bt2 % 16 == 0));
         if (!ok) {                                       // slow, always-safe kernel
             if (a.a_bf16) nn_pick<__hip_bfloat16, false>(a, st); else nn_pick<float, false>(a, st);
@@ -562,7 +675,7 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
         }
         const int n_eff = a.zero_pad_to > a.N ? a.zero_pad_to : a.N;
         const int64_t slabs = round_up(cdiv(a.M, 128), NXCD);
-        const bool rowlimit = a.a_valid_rows > 0 && a.a_valid_rows < a.M;
+        const bool rowlimit = a.a_rows != nullptr || (a.a_valid_rows > 0 && a.a_valid_rows < a.M);
         const unsigned blocks = (unsigned)(slabs * cdiv(n_eff, n_eff > 64 ? 128 : 64));
         const bool short_k = a.K <= 128 || (a.K2 > 0 && a.K2 <= 128);
 #define GRP_NT_LAUNCH2(AT, WM_, WN_, TM_, TN_, RL)                                                                        \
