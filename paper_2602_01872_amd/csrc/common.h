@@ -185,6 +185,8 @@ struct GemmTNArgs {
     void* workspace = nullptr;
     size_t workspace_bytes = 0;
     const int32_t* a_rows = nullptr; // row i of A is stored at row a_rows[i] (null: i)
+    float* colsum_out = nullptr;     // optional [N]: column sums of B (each row times colsum_scale[m] if set)
+    const float* colsum_scale = nullptr;
 };
 grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st);
 

@@ -739,19 +739,27 @@ static TnPlan tn_plan(int64_t M, int K, int N) {
 
 size_t gemm_tn_workspace_bytes(int64_t M, int32_t K, int32_t N) {
     TnPlan p = tn_plan(M, K, N);
-    return p.splits > 1 ? (size_t)p.splits * K * N * sizeof(float) : 0;
+    return p.splits > 1 ? (size_t)p.splits * (K + 1) * N * sizeof(float) : 0;   // + the column-sum row
 }
 
 // Grid: x = NXCD * tiles * ceil(splits / NXCD).  Workgroup ids are mapped so that the output
 // tiles of one slice of the node dimension run on the same L2 domain (they read the same rows).
-template <typename AT, bool VEC, int WM, int WN, int TM, int TN>
+// Whole 32-row steps (all but the last of a slice) load through a uniform base plus 32-bit
+// per-thread offsets and go to LDS as loaded; columns past K or N are read from clamped
+// addresses and never masked, since they only reach output rows / columns that are not stored.
+// GATHER: rows of A are taken through g.a_rows.  cs_out (optional): the workgroups of the
+// first row of output tiles also add up the columns of B they stream (times colsum_scale).
+template <typename AT, bool VEC, bool GATHER, int WM, int WN, int TM, int TN>
 __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k, int tiles_n, int splits, int64_t chunk,
-                                                      float* __restrict__ out, int64_t out_ld, int64_t out_split_stride) {
+                                                      float* __restrict__ out, int64_t out_ld, int64_t out_split_stride,
+                                                      float* __restrict__ cs_out, int64_t cs_split_stride) {
     constexpr int BKA = WM * TM * 32, BN = WN * TN * 32;   // output tile: BKA (rows of C) x BN
     constexpr int PA = BKA + 4, PB = BN + 4;
-    constexpr int A_REPS = BKA * BK / 4 / 256;
-    constexpr int B_REPS = (BN * BK / 4 + 255) / 256;
+    constexpr int QA = BKA / 4, QB = BN / 4;               // 16-byte slots per tile row
+    constexpr int RA = 256 / QA, RB = 256 / QB;            // tile rows per pass of the workgroup
+    constexpr int A_REPS = BK / RA, B_REPS = BK / RB;
     constexpr bool A_BF16 = sizeof(AT) == 2;
+    static_assert(BK % RA == 0 && BK % RB == 0 && B_REPS >= 1, "tiles must fill the workgroup");
     __shared__ __attribute__((aligned(16))) float As[BK * PA];
     __shared__ __attribute__((aligned(16))) float Bs[BK * PB];
 
@@ -769,6 +777,8 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
     const int64_t m_begin = (int64_t)split * chunk;
     const int64_t m_end = m_begin + chunk < g.M ? m_begin + chunk : g.M;
     const int kpad = (g.K + 3) & ~3, npad = (g.N + 3) & ~3;
+    const bool do_cs = cs_out != nullptr && ka0 == 0;
+    const float* const cs_scale = do_cs ? g.colsum_scale : nullptr;
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -778,62 +788,84 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    const int cqa = tid % QA, ma = tid / QA, cqb = tid % QB, mb = tid / QB;
+    const int ca = imin(ka0 + 4 * cqa, kpad - 4), cb = imin(n0 + 4 * cqb, npad - 4);
+    uint32_t aoff[A_REPS], boff[B_REPS];
+#pragma unroll
+    for (int r = 0; r < A_REPS; ++r) aoff[r] = (uint32_t)(ma + RA * r) * (uint32_t)g.lda + ca;
+#pragma unroll
+    for (int r = 0; r < B_REPS; ++r) boff[r] = (uint32_t)(mb + RB * r) * (uint32_t)g.ldb + cb;
+    float* const as_w = As + ma * PA + 4 * cqa;
+    float* const bs_w = Bs + mb * PB + 4 * cqb;
+    float csum[4] = {0.f, 0.f, 0.f, 0.f};
+
     uint4 ra[A_REPS], rb[B_REPS];
+    float rsc[B_REPS];
     auto fetch = [&](int64_t mt) {
+        const bool full = mt + BK <= m_end;
+        if (cs_scale) {
+#pragma unroll
+            for (int r = 0; r < B_REPS; ++r) rsc[r] = cs_scale[lmin(mt + mb + RB * r, g.M - 1)];
+        }
+        if (VEC && !GATHER && full) {
+            const AT* pa = (const AT*)g.A + mt * g.lda;
+            const float* pb = g.B + mt * g.ldb;
+#pragma unroll
+            for (int r = 0; r < A_REPS; ++r) ra[r] = ldg_raw4<AT>(pa + aoff[r]);
+#pragma unroll
+            for (int r = 0; r < B_REPS; ++r) rb[r] = ldg_raw4<float>(pb + boff[r]);
+            return;
+        }
 #pragma unroll
         for (int r = 0; r < A_REPS; ++r) {
-            const int f = tid + 256 * r;
-            const int m = f / (BKA / 4), cq = f % (BKA / 4);
+            const int m = ma + RA * r;
             if constexpr (VEC) {
                 const int64_t gm = lmin(mt + m, g.M - 1);
                 const int64_t row = g.a_rows ? (int64_t)g.a_rows[gm] : gm;
-                ra[r] = ldg_raw4<AT>((const AT*)g.A + row * g.lda + imin(ka0 + 4 * cq, kpad - 4));
+                ra[r] = ldg_raw4<AT>((const AT*)g.A + row * g.lda + ca);
             } else {
                 const bool ok = mt + m < m_end;
                 const int64_t gm = ok ? mt + m : 0;
                 const int64_t row = (g.a_rows && ok) ? (int64_t)g.a_rows[gm] : gm;
-                ra[r] = ldg_safe4<AT>((const AT*)g.A + row * g.lda, ok, ka0 + 4 * cq, g.K);
+                ra[r] = ldg_safe4<AT>((const AT*)g.A + row * g.lda, ok, ka0 + 4 * cqa, g.K);
             }
         }
 #pragma unroll
         for (int r = 0; r < B_REPS; ++r) {
-            const int f = tid + 256 * r;
-            const int m = f / (BN / 4), cq = f % (BN / 4);
-            if (BN * BK / 4 % 256 != 0 && f >= BN * BK / 4) { rb[r] = make_uint4(0u, 0u, 0u, 0u); continue; }
+            const int m = mb + RB * r;
             if constexpr (VEC) {
-                const int64_t gm = lmin(mt + m, g.M - 1);
-                rb[r] = ldg_raw4<float>(g.B + gm * g.ldb + imin(n0 + 4 * cq, npad - 4));
+                rb[r] = ldg_raw4<float>(g.B + lmin(mt + m, g.M - 1) * g.ldb + cb);
             } else {
                 const bool ok = mt + m < m_end;
-                rb[r] = ldg_safe4<float>(g.B + (ok ? mt + m : 0) * g.ldb, ok, n0 + 4 * cq, g.N);
+                rb[r] = ldg_safe4<float>(g.B + (ok ? mt + m : 0) * g.ldb, ok, n0 + 4 * cqb, g.N);
             }
         }
     };
     auto stage = [&](int64_t mt) {
+        const bool full = mt + BK <= m_end;
+        if (VEC && full && !A_BF16) {
 #pragma unroll
-        for (int r = 0; r < A_REPS; ++r) {
-            const int f = tid + 256 * r;
-            const int m = f / (BKA / 4), cq = f % (BKA / 4);
-            float v[4];
-            unpack4(ra[r], VEC && A_BF16, v);
-            const bool row_ok = mt + m < m_end;
+            for (int r = 0; r < A_REPS; ++r) *reinterpret_cast<uint4*>(as_w + RA * r * PA) = ra[r];
+        } else {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (VEC && !(row_ok && ka0 + 4 * cq + q < g.K)) v[q] = 0.f;
-            *reinterpret_cast<float4*>(&As[m * PA + 4 * cq]) = make_float4(v[0], v[1], v[2], v[3]);
+            for (int r = 0; r < A_REPS; ++r) {
+                float v[4];
+                unpack4(ra[r], VEC && A_BF16, v);
+                if (VEC && mt + ma + RA * r >= m_end) { v[0] = v[1] = v[2] = v[3] = 0.f; }
+                *reinterpret_cast<float4*>(as_w + RA * r * PA) = make_float4(v[0], v[1], v[2], v[3]);
+            }
         }
 #pragma unroll
         for (int r = 0; r < B_REPS; ++r) {
-            const int f = tid + 256 * r;
-            const int m = f / (BN / 4), cq = f % (BN / 4);
-            if (BN * BK / 4 % 256 != 0 && f >= BN * BK / 4) continue;
             float v[4];
             unpack4(rb[r], false, v);
-            const bool row_ok = mt + m < m_end;
+            if (VEC && !full && mt + mb + RB * r >= m_end) { v[0] = v[1] = v[2] = v[3] = 0.f; }
+            *reinterpret_cast<float4*>(bs_w + RB * r * PB) = make_float4(v[0], v[1], v[2], v[3]);
+            if (do_cs) {
+                const float sc = cs_scale ? rsc[r] : 1.f;
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (VEC && !(row_ok && n0 + 4 * cq + q < g.N)) v[q] = 0.f;
-            *reinterpret_cast<float4*>(&Bs[m * PB + 4 * cq]) = make_float4(v[0], v[1], v[2], v[3]);
+                for (int q = 0; q < 4; ++q) csum[q] += v[q] * sc;
+            }
         }
     };
 
@@ -867,70 +899,90 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
                 if (ka < g.K) o[(int64_t)ka * out_ld + col] = acc[i][j][r];
             }
         }
+    if (do_cs) {                                      // the main loop ended on a barrier: As is free
+        float* red = As;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) red[mb * BN + 4 * cqb + q] = csum[q];
+        __syncthreads();
+        if (tid < BN) {
+            float t = 0.f;
+            for (int u = 0; u < RB; ++u) t += red[u * BN + tid];
+            if (n0 + tid < g.N) cs_out[(int64_t)split * cs_split_stride + n0 + tid] = t;
+        }
+    }
 }
 
 // C[e] = sum_p part[p][e], p ascending.  Four partial tiles are requested before the first is
 // added (the adds stay in split order, so the result is the plain sequential sum).
 __global__ __launch_bounds__(256) void tn_reduce_kernel(const float* __restrict__ part, int splits, int K, int N,
-                                                        float* __restrict__ C, int64_t ldc) {
+                                                        int64_t part_stride, float* __restrict__ C, int64_t ldc,
+                                                        float* __restrict__ colsum_out) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t kn = (int64_t)K * N;
-    if (e >= kn) return;
+    const int64_t rows = colsum_out ? K + 1 : K;      // the partials carry the column sums as row K
+    if (e >= rows * N) return;
     const float* p0 = part + e;
     float s = 0.f;
     int p = 0;
     for (; p + 4 <= splits; p += 4) {
-        const float a = p0[(int64_t)p * kn], b = p0[(int64_t)(p + 1) * kn];
-        const float c = p0[(int64_t)(p + 2) * kn], d = p0[(int64_t)(p + 3) * kn];
+        const float a = p0[(int64_t)p * part_stride], b = p0[(int64_t)(p + 1) * part_stride];
+        const float c = p0[(int64_t)(p + 2) * part_stride], d = p0[(int64_t)(p + 3) * part_stride];
         s += a; s += b; s += c; s += d;
     }
-    for (; p < splits; ++p) s += p0[(int64_t)p * kn];
-    C[(e / N) * ldc + (e % N)] = s;
+    for (; p < splits; ++p) s += p0[(int64_t)p * part_stride];
+    if (e / N < K) C[(e / N) * ldc + (e % N)] = s;
+    else colsum_out[e % N] = s;
 }
 
-template <typename AT, bool VEC>
-static void tn_pick(const GemmTNArgs& a, const TnPlan& p, float* out, int64_t out_ld, int64_t stride, hipStream_t st) {
+template <typename AT, bool VEC, bool GATHER>
+static void tn_pick(const GemmTNArgs& a, const TnPlan& p, float* out, int64_t out_ld, int64_t stride, float* cs_out,
+                    int64_t cs_stride, hipStream_t st) {
     const unsigned blocks = (unsigned)(NXCD * p.tiles_k * p.tiles_n * cdiv(p.splits, NXCD));
     dim3 grid(blocks);
     if (p.bn_tile == 128)
-        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, 2, 2, 2, 2>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, p.splits, p.chunk, out, out_ld, stride);
+        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, 2, 2, 2, 2>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, p.splits, p.chunk, out, out_ld, stride, cs_out, cs_stride);
     else if (p.bn_tile == 64)
-        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, 4, 1, 1, 2>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, p.splits, p.chunk, out, out_ld, stride);
+        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, 4, 1, 1, 2>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, p.splits, p.chunk, out, out_ld, stride, cs_out, cs_stride);
     else
-        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, 4, 1, 1, 1>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, p.splits, p.chunk, out, out_ld, stride);
+        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, 4, 1, 1, 1>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, p.splits, p.chunk, out, out_ld, stride, cs_out, cs_stride);
 }
 
 grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st) {
     if (a.K <= 0 || a.N <= 0 || a.M < 0 || !a.C) return fail(GRP_EINVAL, "gemm_tn: bad arguments");
     if (a.M > 0 && (!a.A || !a.B)) return fail(GRP_EINVAL, "gemm_tn: null operand");
     const TnPlan p = tn_plan(a.M, a.K, a.N);
-    const size_t need = p.splits > 1 ? (size_t)p.splits * a.K * a.N * sizeof(float) : 0;
+    const size_t need = p.splits > 1 ? (size_t)p.splits * (a.K + 1) * a.N * sizeof(float) : 0;
     if (need > a.workspace_bytes || (need && !a.workspace))
         return fail(GRP_EWORKSPACE, "gemm_tn: workspace %zu < %zu bytes", a.workspace_bytes, need);
     const int elem = a.a_bf16 ? 2 : 4;
-    const bool veca = a.M > 0 && a.lda % 4 == 0 && a.lda >= round_up(a.K, 4) && (uintptr_t)a.A % (4 * elem) == 0;
-    const bool vecb = a.M > 0 && a.ldb % 4 == 0 && a.ldb >= round_up(a.N, 4) && (uintptr_t)a.B % 16 == 0;
+    // vector path: 16-byte friendly operands whose 32-row steps fit 32-bit element offsets
+    const bool veca = a.M > 0 && a.lda % 4 == 0 && a.lda >= round_up(a.K, 4) && (uintptr_t)a.A % (4 * elem) == 0 && a.lda < (1 << 25);
+    const bool vecb = a.M > 0 && a.ldb % 4 == 0 && a.ldb >= round_up(a.N, 4) && (uintptr_t)a.B % 16 == 0 && a.ldb < (1 << 25);
+    const int64_t stride = p.splits > 1 ? (int64_t)(a.K + 1) * a.N : 0;
     float* out = p.splits > 1 ? (float*)a.workspace : a.C;
     const int64_t out_ld = p.splits > 1 ? a.N : a.ldc;
-    const int64_t stride = p.splits > 1 ? (int64_t)a.K * a.N : 0;
+    float* cs_out = !a.colsum_out ? nullptr : (p.splits > 1 ? (float*)a.workspace + (int64_t)a.K * a.N : a.colsum_out);
     {
-        prof_detail("[M=%lld,K=%d,N=%d]", (long long)a.M, a.K, a.N);
+        prof_detail("[M=%lld,K=%d,N=%d%s]", (long long)a.M, a.K, a.N, a.colsum_out ? ",colsum" : "");
         ProfScope ps(a.a_bf16 ? "gemm_tn_bf16a" : "gemm_tn_f32", st, 2.0 * a.M * a.K * a.N,
                      (double)a.M * a.K * elem + 4.0 * a.M * a.N + 4.0 * a.K * a.N);
+        const bool vec = veca && vecb;
         if (a.a_bf16) {
-            if (veca && vecb) tn_pick<__hip_bfloat16, true>(a, p, out, out_ld, stride, st);
-            else tn_pick<__hip_bfloat16, false>(a, p, out, out_ld, stride, st);
+            if (vec && !a.a_rows) tn_pick<__hip_bfloat16, true, false>(a, p, out, out_ld, stride, cs_out, stride, st);
+            else if (vec) tn_pick<__hip_bfloat16, true, true>(a, p, out, out_ld, stride, cs_out, stride, st);
+            else tn_pick<__hip_bfloat16, false, true>(a, p, out, out_ld, stride, cs_out, stride, st);
         } else {
-            if (veca && vecb) tn_pick<float, true>(a, p, out, out_ld, stride, st);
-            else tn_pick<float, false>(a, p, out, out_ld, stride, st);
+            if (vec && !a.a_rows) tn_pick<float, true, false>(a, p, out, out_ld, stride, cs_out, stride, st);
+            else if (vec) tn_pick<float, true, true>(a, p, out, out_ld, stride, cs_out, stride, st);
+            else tn_pick<float, false, true>(a, p, out, out_ld, stride, cs_out, stride, st);
         }
         GRP_LAUNCH_CHECK();
     }
     if (p.splits > 1) {
         ProfScope ps("gemm_tn_reduce", st, 0.0, 4.0 * a.K * a.N * (p.splits + 1.0));
-        const int64_t blocks = cdiv((int64_t)a.K * a.N, 256);
+        const int64_t rows = a.colsum_out ? a.K + 1 : a.K;
+        const int64_t blocks = cdiv(rows * a.N, 256);
         hipLaunchKernelGGL(tn_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const float*)a.workspace,
-                           p.splits, a.K, a.N, a.C, a.ldc);
+                           p.splits, a.K, a.N, stride, a.C, a.ldc, a.colsum_out);
         GRP_LAUNCH_CHECK();
     }
     return GRP_OK;

@@ -270,11 +270,12 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
         const void* Hin = l == 0 ? X : (const void*)p.L[l - 1].H_out;
         const int64_t ldin = l == 0 ? m->dims[0] : ldp(fin);
         const int in_bf16 = l == 0 && m->feat_dtype == GRP_DTYPE_BF16;
-        GRP_TRY(launch_colsum(dZ, B.n_dst, fout, ldp(fout), grad + L.off_b, p.colsum_ws, st));
-        GemmTNArgs t;      // dW_self = H_self^T dZ
+        GemmTNArgs t;      // dW_self = H_self^T dZ, and db = 1^T dZ from the same pass over dZ
         t.M = B.n_dst; t.K = fin; t.N = fout; t.A = Hin; t.lda = ldin; t.a_bf16 = in_bf16; t.a_rows = B.self_rows;
         t.B = dZ; t.ldb = ldp(fout); t.C = grad + L.off_ws; t.ldc = fout; t.workspace = p.tn_ws; t.workspace_bytes = p.tn_ws_bytes;
+        t.colsum_out = grad + L.off_b;
         GRP_TRY(launch_gemm_tn(t, st));
+        t.colsum_out = nullptr;
         if (L.agg_first) {
             t.A = L.M; t.lda = ldp(fin); t.a_bf16 = 0; t.a_rows = nullptr; t.C = grad + L.off_wn;
             GRP_TRY(launch_gemm_tn(t, st));
