@@ -104,6 +104,41 @@ __device__ __forceinline__ void mma_step(const float* __restrict__ As, const flo
     }
 }
 
+// Variant for the tn kernel, whose LDS tiles keep the output dimension contiguous: tile t of
+// a wavefront's TM (or TN) tiles takes the interleaved columns TM*l + t of its 32*TM-wide
+// block, so that one 4*TM-byte LDS read per lane feeds all TM tiles.  Accumulator register r
+// of tile (i, j) then holds row TM*(8*(r/4) + 4*(lane/32) + r%4) + i, column TN*(lane%32) + j
+// of the wavefront's block.
+template <int TM, int TN, int PA, int PB, int BKT>
+__device__ __forceinline__ void mma_step_interleaved(const float* __restrict__ As, const float* __restrict__ Bs, int a_off,
+                                                     int b_off, floatx16 (&acc)[TM][TN]) {
+    static_assert((TM == 1 || TM == 2) && (TN == 1 || TN == 2), "one LDS read of at most 8 bytes per operand");
+    const int lane = threadIdx.x & 63;
+    const int li = lane & 31, lk = lane >> 5;
+    const float* ap = As + lk * PA + a_off + TM * li;
+    const float* bp = Bs + lk * PB + b_off + TN * li;
+    float a[2][TM], b[2][TN];
+    auto rd = [&](int k, int buf) {
+        if constexpr (TM == 2) { const float2 t = *reinterpret_cast<const float2*>(ap + k * PA); a[buf][0] = t.x; a[buf][1] = t.y; }
+        else a[buf][0] = ap[k * PA];
+        if constexpr (TN == 2) { const float2 t = *reinterpret_cast<const float2*>(bp + k * PB); b[buf][0] = t.x; b[buf][1] = t.y; }
+        else b[buf][0] = bp[k * PB];
+    };
+    rd(0, 0);
+#pragma unroll
+    for (int k = 0; k < BKT; k += 2) {
+        const int cur = (k >> 1) & 1, nxt = cur ^ 1;
+        if (k + 2 < BKT) rd(k + 2, nxt);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // Epilogue shared by the nn kernels: (+ addend) (+ bias) -> C_raw; (* rowscale) (ReLU) (mask) -> C.
 // When every operand allows 16-byte accesses the accumulators go through LDS, 32 tile rows
 // per wavefront row at a time, so that addend / mask are read and the results written as
@@ -712,7 +747,7 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
 // ------------------------------------------------------------------------------- TN
 constexpr int TN_ROWS_PER_SPLIT_MIN = 512;    // node rows per split (multiple of BK)
 constexpr int TN_MAX_SPLITS = 256;
-constexpr int TN_TARGET_WGS = 512;            // 256 CUs x 2 resident workgroups: one full round
+constexpr int TN_TARGET_WGS = 768;            // 256 CUs x 3 resident workgroups: one full round
 
 struct TnPlan {
     int tiles_k, tiles_n, splits;
@@ -876,7 +911,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
         for (int64_t mt = m_begin; mt < m_end; mt += BK) {
             const bool more = mt + BK < m_end;
             if (more) fetch(mt + BK);
-            mma_step<TM, TN, PA, PB, BK>(As, Bs, wm * TM * 32, wn * TN * 32, acc);
+            mma_step_interleaved<TM, TN, PA, PB, BK>(As, Bs, wm * TM * 32, wn * TN * 32, acc);
             __syncthreads();
             if (more) {
                 stage(mt + BK);
@@ -887,17 +922,21 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
 
     const int li = lane & 31, lk = lane >> 5;
     float* o = out + (int64_t)split * out_split_stride;
+    const int colb = n0 + wn * TN * 32 + TN * li;     // first of this lane's TN interleaved columns
+    const bool pair = TN == 2 && out_ld % 2 == 0 && ((uintptr_t)o % 8) == 0 && colb + 1 < g.N;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + (wn * TN + j) * 32 + li;
-            if (col >= g.N) continue;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int ka = ka0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
-                if (ka < g.K) o[(int64_t)ka * out_ld + col] = acc[i][j][r];
+        for (int r = 0; r < 16; ++r) {
+            const int ka = ka0 + wm * TM * 32 + TM * (8 * (r / 4) + 4 * lk + (r % 4)) + i;
+            if (ka >= g.K) continue;
+            float* orow = o + (int64_t)ka * out_ld + colb;
+            if constexpr (TN == 2) {
+                if (pair) { *reinterpret_cast<float2*>(orow) = make_float2(acc[i][0][r], acc[i][1][r]); continue; }
             }
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                if (colb + j < g.N) orow[j] = acc[i][j][r];
         }
     if (do_cs) {                                      // the main loop ended on a barrier: As is free
         float* red = As;
@@ -931,6 +970,53 @@ __global__ __launch_bounds__(256) void tn_reduce_kernel(const float* __restrict_
     for (; p < splits; ++p) s += p0[(int64_t)p * part_stride];
     if (e / N < K) C[(e / N) * ldc + (e % N)] = s;
     else colsum_out[e % N] = s;
+}
+
+// The same sum for partials whose stride allows 16-byte loads: a workgroup owns 64 elements,
+// 16 groups of threads each add a contiguous range of splits in ascending order, and the 16
+// group sums are then added in ascending order: a fixed association, so still deterministic.
+__global__ __launch_bounds__(256) void tn_reduce_vec_kernel(const float* __restrict__ part, int splits, int K, int N,
+                                                            int64_t part_stride, float* __restrict__ C, int64_t ldc,
+                                                            float* __restrict__ colsum_out) {
+    __shared__ float4 red[16][16];
+    const int c = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int64_t rows = colsum_out ? K + 1 : K;
+    const int64_t total = rows * N;                    // a multiple of 4
+    const int64_t e = ((int64_t)blockIdx.x * 16 + c) * 4;
+    const int per = (splits + 15) / 16;
+    const int p_begin = grp * per, p_end = p_begin + per < splits ? p_begin + per : splits;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (e < total) {
+        const float* p0 = part + e;
+        int p = p_begin;
+        for (; p + 4 <= p_end; p += 4) {
+            const float4 a = *reinterpret_cast<const float4*>(p0 + (int64_t)p * part_stride);
+            const float4 b = *reinterpret_cast<const float4*>(p0 + (int64_t)(p + 1) * part_stride);
+            const float4 c4 = *reinterpret_cast<const float4*>(p0 + (int64_t)(p + 2) * part_stride);
+            const float4 d = *reinterpret_cast<const float4*>(p0 + (int64_t)(p + 3) * part_stride);
+            s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+            s.x += b.x; s.y += b.y; s.z += b.z; s.w += b.w;
+            s.x += c4.x; s.y += c4.y; s.z += c4.z; s.w += c4.w;
+            s.x += d.x; s.y += d.y; s.z += d.z; s.w += d.w;
+        }
+        for (; p < p_end; ++p) {
+            const float4 a = *reinterpret_cast<const float4*>(p0 + (int64_t)p * part_stride);
+            s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+        }
+    }
+    red[grp][c] = s;
+    __syncthreads();
+    if (grp == 0 && e < total) {
+        float4 t = red[0][c];
+        for (int u = 1; u < 16; ++u) { const float4 v = red[u][c]; t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w; }
+        const float tv[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t eq = e + q;
+            if (eq / N < K) C[(eq / N) * ldc + (eq % N)] = tv[q];
+            else colsum_out[eq % N] = tv[q];
+        }
+    }
 }
 
 template <typename AT, bool VEC, bool GATHER>
@@ -980,9 +1066,13 @@ grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st) {
     if (p.splits > 1) {
         ProfScope ps("gemm_tn_reduce", st, 0.0, 4.0 * a.K * a.N * (p.splits + 1.0));
         const int64_t rows = a.colsum_out ? a.K + 1 : a.K;
-        const int64_t blocks = cdiv(rows * a.N, 256);
-        hipLaunchKernelGGL(tn_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const float*)a.workspace,
-                           p.splits, a.K, a.N, stride, a.C, a.ldc, a.colsum_out);
+        if (stride % 4 == 0 && (rows * a.N) % 4 == 0 && (uintptr_t)a.workspace % 16 == 0 && p.splits >= 16) {
+            hipLaunchKernelGGL(tn_reduce_vec_kernel, dim3((unsigned)cdiv(rows * a.N, 64)), dim3(256), 0, st,
+                               (const float*)a.workspace, p.splits, a.K, a.N, stride, a.C, a.ldc, a.colsum_out);
+        } else {
+            hipLaunchKernelGGL(tn_reduce_kernel, dim3((unsigned)cdiv(rows * a.N, 256)), dim3(256), 0, st,
+                               (const float*)a.workspace, p.splits, a.K, a.N, stride, a.C, a.ldc, a.colsum_out);
+        }
         GRP_LAUNCH_CHECK();
     }
     return GRP_OK;
