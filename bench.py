@@ -29,6 +29,13 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0          # MI355X published HBM3E bandwidth
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
 
+# HBM bytes per launch (average over the kernel's launches in one step of this workload), from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by what the same counters
+# read for a plain 1 GiB copy (see profiles/bench_config2_hbm_traffic.md).  Other kernels: None.
+HBM_TRAFFIC_BYTES_PER_LAUNCH = {
+    "gemm_nt_f32_128x128_k32": 7.76e8,
+}
+
 GRAPH_SEED = 2602018722
 N_NODES, N_EDGES, RMAT_SCALE = 2_400_000, 62_000_000, 22
 K_PARTS, PART_SEED, PART_ID = 8, 1, 0
@@ -47,6 +54,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--small", action="store_true", help="scaled-down graph (debugging only; not a valid result)")
     ap.add_argument("--shapes", action="store_true", help="per-launch-shape kernel table on stderr (debugging)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (partitions are processed in turn); "
@@ -110,6 +119,13 @@ def main():
         g.grp_train_step(part, model, opts, x, y, None, theta, ws, grads[PART_ID], st_slice)
         g.grp_aggregate(grads, ld, stats, K_PARTS, P, g.EST_SHRINKAGE, update)
 
+    if args.copy_calibration:
+        cal_src = torch.ones(1 << 28, device=dev)      # 1 GiB read + 1 GiB written by one elementwise kernel
+        cal_dst = torch.empty_like(cal_src)
+        cal_dst.copy_(cal_src)
+        torch.cuda.synchronize()
+        del cal_src, cal_dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -137,15 +153,17 @@ def main():
                              gflops=r["flops"] / r["ms"] / 1e6 if r["ms"] > 0 else 0.0,
                              gbs=r["bytes"] / r["ms"] / 1e6 if r["ms"] > 0 else 0.0)
     dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    traffic = HBM_TRAFFIC_BYTES_PER_LAUNCH.get(dom) if not args.small else None
     if dom.startswith("gemm") and "reduce" not in dom:
         ach = kernels[dom]["gflops"] / 1e3
         roofline = dict(kernel=dom, bound="mfma", achieved=ach, peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
-                        frac=ach / PEAK_FP32_MFMA_TFLOPS, traffic=None)
+                        frac=ach / PEAK_FP32_MFMA_TFLOPS, traffic=traffic)
     else:
         ach = kernels[dom]["gbs"]
         roofline = dict(kernel=dom, bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=ach / PEAK_HBM_GBS, traffic=None)
+                        frac=ach / PEAK_HBM_GBS, traffic=traffic)
     roofline["avg_launch_us"] = kernels[dom]["avg_us"]
+    roofline["launches_per_step"] = kernels[dom]["launches_per_step"]
     for name in sorted(kernels, key=lambda k: -kernels[k]["ms_per_step"]):
         k = kernels[name]
         log(f"  {name:18s} {k['launches_per_step']:5.1f} launches/step {k['ms_per_step']:8.4f} ms/step "

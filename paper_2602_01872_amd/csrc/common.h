@@ -65,7 +65,7 @@ namespace grp {
 // Rows longer than SPMM_LONG_ROW edges are cut into chunks of at most SPMM_CHUNK edges
 // (device arrays, built once with the partition; see spmm.hip).
 constexpr int SPMM_LONG_ROW = 512;
-constexpr int SPMM_CHUNK = 2048;
+constexpr int SPMM_CHUNK = 512;
 struct LongRows {
     int32_t n_long = 0, n_chunks = 0;
     int32_t* long_row = nullptr;     // [n_long]    row index

@@ -696,23 +696,27 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
                             4.0 * a.M * a.N * (1.0 + (a.addend ? 1.0 : 0.0) + (a.mask ? 1.0 : 0.0));
     prof_detail("[M=%lld,N=%d,K=%d+%d%s%s%s]", (long long)a.M, a.N, a.K, a.K2, a.addend ? ",add" : "", a.mask ? ",mask" : "",
                 a.rowscale ? ",rs" : "");
-    ProfScope ps(a.a_bf16 ? "gemm_nn_bf16a" : "gemm_nn_f32", st, nn_flops, nn_bytes);
     if (a.Bt) {
         // 32-bit element offsets inside a slab and inside Bt
         const bool small = a.lda < (1 << 23) && a.lda2 < (1 << 23) && (int64_t)a.N * a.ldbt < (1ll << 31) &&
                            (int64_t)a.N * a.ldbt2 < (1ll << 31);
         const bool ok = small && veca && a.ldbt % 4 == 0 && a.ldbt >= round_up(a.K, 4) && (uintptr_t)a.Bt % 16 == 0 &&
                         (a.K2 == 0 || (a.Bt2 && a.ldbt2 % 4 == 0 && a.ldbt2 >= round_up(a.K2, 4) && (uintptr_t)a.Bt2 % 16 == 0));
+        const int n_eff = a.zero_pad_to > a.N ? a.zero_pad_to : a.N;
+        const bool short_k = a.K <= 128 || (a.K2 > 0 && a.K2 <= 128);
+        // one profiling name per kernel variant, so that the names line up with a kernel trace
+        char pname[64];
+        snprintf(pname, sizeof pname, "gemm_%s_%s_%s%s", ok ? "nt" : "nn", a.a_bf16 ? "bf16a" : "f32",
+                 n_eff > 64 ? "128x128" : (ok || n_eff > 32 ? "128x64" : "128x32"), short_k ? "_k16" : "_k32");
+        ProfScope ps(pname, st, nn_flops, nn_bytes);
         if (!ok) {                                       // slow, always-safe kernel
             if (a.a_bf16) nn_pick<__hip_bfloat16, false>(a, st); else nn_pick<float, false>(a, st);
             GRP_LAUNCH_CHECK();
             return GRP_OK;
         }
-        const int n_eff = a.zero_pad_to > a.N ? a.zero_pad_to : a.N;
         const int64_t slabs = round_up(cdiv(a.M, 128), NXCD);
         const bool rowlimit = a.a_rows != nullptr || (a.a_valid_rows > 0 && a.a_valid_rows < a.M);
         const unsigned blocks = (unsigned)(slabs * cdiv(n_eff, n_eff > 64 ? 128 : 64));
-        const bool short_k = a.K <= 128 || (a.K2 > 0 && a.K2 <= 128);
 #define GRP_NT_LAUNCH2(AT, WM_, WN_, TM_, TN_, RL)                                                                        \
     do {                                                                                                                  \
         if (short_k) hipLaunchKernelGGL((gemm_nt_kernel<AT, WM_, WN_, TM_, TN_, RL, 16, 2>), dim3(blocks), dim3(256), 0, st, a); \
@@ -733,6 +737,7 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
         GRP_LAUNCH_CHECK();
         return GRP_OK;
     }
+    ProfScope ps(a.a_bf16 ? "gemm_nn_bf16a" : "gemm_nn_f32", st, nn_flops, nn_bytes);
     if (a.a_bf16) {
         if (veca && vecb) nn_pick<__hip_bfloat16, true>(a, st);
         else nn_pick<__hip_bfloat16, false>(a, st);

@@ -147,44 +147,14 @@ __device__ __forceinline__ void finish_row(const SpmmEpilogue& ep, int64_t i, in
     *reinterpret_cast<float4*>(ep.Y + i * ep.ldy + col) = make_float4(o[0], o[1], o[2], o[3]);
 }
 
-// Rows of at most `long_thr` edges: one group per row.
-template <typename XT, int G, int NJ>
-__global__ __launch_bounds__(256) void spmm_rows_kernel(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx,
-                                                        int64_t n_rows, int64_t long_thr, const XT* __restrict__ X,
-                                                        int64_t ldx, const float* __restrict__ colscale,
-                                                        SpmmEpilogue ep) {
-    constexpr int ROWS = 256 / G;
-    const int t = threadIdx.x % G;
-    const int64_t i = (int64_t)blockIdx.x * ROWS + threadIdx.x / G;
-    if (i >= n_rows) return;          // whole groups leave together (G divides 64)
-    const int64_t b = ptr[i], e = ptr[i + 1];
-    if (e - b > long_thr) return;     // handled by the chunk kernels
-    float4 acc[NJ];
-    bool live[NJ];
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        live[j] = 4 * (t + G * j) < ep.F;
-    }
-    gather_rows<XT, G, NJ>(idx, b, e, X, ldx, colscale, t, live, acc);
-#pragma unroll
-    for (int j = 0; j < NJ; ++j)
-        if (live[j]) finish_row<XT>(ep, i, e - b, 4 * (t + G * j), acc[j], X, ldx);
-}
-
 // One workgroup per chunk of a long row -> one partial row.
 template <typename XT, int G, int NJ>
-__global__ __launch_bounds__(256) void spmm_chunk_kernel(const int64_t* __restrict__ chunk_begin,
-                                                         const int64_t* __restrict__ chunk_end,
-                                                         const int32_t* __restrict__ idx, int F,
-                                                         const XT* __restrict__ X, int64_t ldx,
-                                                         const float* __restrict__ colscale,
-                                                         float* __restrict__ partials, int64_t ld_part) {
+__device__ __forceinline__ void chunk_body(int64_t cb, int64_t ce, const int32_t* __restrict__ idx, int F,
+                                           const XT* __restrict__ X, int64_t ldx, const float* __restrict__ colscale,
+                                           float* __restrict__ part_row, float* red) {
     constexpr int NG = 256 / G;
     constexpr int W = 4 * G * NJ;                 // padded row width held by a group
-    __shared__ float red[NG * W];
     const int t = threadIdx.x % G, gi = threadIdx.x / G;
-    const int64_t cb = chunk_begin[blockIdx.x], ce = chunk_end[blockIdx.x];
     const int64_t per = (ce - cb + NG - 1) / NG;
     int64_t b = cb + gi * per, e = b + per;
     if (b > ce) b = ce;
@@ -206,8 +176,45 @@ __global__ __launch_bounds__(256) void spmm_chunk_kernel(const int64_t* __restri
         float s = 0.f;
 #pragma unroll
         for (int q = 0; q < NG; ++q) s += red[q * W + c];
-        partials[(int64_t)blockIdx.x * ld_part + c] = s;
+        part_row[c] = s;
     }
+}
+
+// The first n_chunks workgroups each reduce one chunk of a long row to a partial row (they
+// are the heavy ones, so they start first); the others take the rows of at most `long_thr`
+// edges, one group per row.  One launch instead of two keeps the few chunk workgroups from
+// running on an otherwise idle chip.
+template <typename XT, int G, int NJ>
+__global__ __launch_bounds__(256) void spmm_rows_kernel(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx,
+                                                        int64_t n_rows, int64_t long_thr, const XT* __restrict__ X,
+                                                        int64_t ldx, const float* __restrict__ colscale,
+                                                        SpmmEpilogue ep, int n_chunks,
+                                                        const int64_t* __restrict__ chunk_begin,
+                                                        const int64_t* __restrict__ chunk_end,
+                                                        float* __restrict__ partials, int64_t ld_part) {
+    constexpr int ROWS = 256 / G;
+    __shared__ __attribute__((aligned(16))) float red[ROWS * 4 * G * NJ];
+    if ((int)blockIdx.x < n_chunks) {              // uniform per workgroup
+        chunk_body<XT, G, NJ>(chunk_begin[blockIdx.x], chunk_end[blockIdx.x], idx, ep.F, X, ldx, colscale,
+                              partials + (int64_t)blockIdx.x * ld_part, red);
+        return;
+    }
+    const int t = threadIdx.x % G;
+    const int64_t i = (int64_t)(blockIdx.x - n_chunks) * ROWS + threadIdx.x / G;
+    if (i >= n_rows) return;          // whole groups leave together (G divides 64)
+    const int64_t b = ptr[i], e = ptr[i + 1];
+    if (e - b > long_thr) return;     // its chunks are reduced above, the row is finished by the combine kernel
+    float4 acc[NJ];
+    bool live[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        live[j] = 4 * (t + G * j) < ep.F;
+    }
+    gather_rows<XT, G, NJ>(idx, b, e, X, ldx, colscale, t, live, acc);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+        if (live[j]) finish_row<XT>(ep, i, e - b, 4 * (t + G * j), acc[j], X, ldx);
 }
 
 // One group per long row: partial rows added in chunk order, then the epilogue.
@@ -266,12 +273,12 @@ static void launch_one(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_t st
     const LongRows* lr = a.long_rows;
     const bool split = lr && lr->n_long > 0;
     const int64_t thr = split ? (int64_t)SPMM_LONG_ROW : INT64_MAX;
-    hipLaunchKernelGGL((spmm_rows_kernel<XT, G, NJ>), dim3((unsigned)cdiv(a.n_rows, ROWS)), dim3(256), 0, st, a.ptr, a.idx,
-                       a.n_rows, thr, (const XT*)a.X, a.ldx, a.colscale, ep);
+    const int n_chunks = split ? lr->n_chunks : 0;
+    const int64_t ld_part = round_up(a.F, 4);
+    hipLaunchKernelGGL((spmm_rows_kernel<XT, G, NJ>), dim3((unsigned)(n_chunks + cdiv(a.n_rows, ROWS))), dim3(256), 0, st,
+                       a.ptr, a.idx, a.n_rows, thr, (const XT*)a.X, a.ldx, a.colscale, ep, n_chunks,
+                       split ? lr->chunk_begin : nullptr, split ? lr->chunk_end : nullptr, a.partials, ld_part);
     if (split) {
-        const int64_t ld_part = round_up(a.F, 4);
-        hipLaunchKernelGGL((spmm_chunk_kernel<XT, G, NJ>), dim3((unsigned)lr->n_chunks), dim3(256), 0, st, lr->chunk_begin,
-                           lr->chunk_end, a.idx, a.F, (const XT*)a.X, a.ldx, a.colscale, a.partials, ld_part);
         hipLaunchKernelGGL((spmm_combine_kernel<XT, G, NJ>), dim3((unsigned)cdiv(lr->n_long, ROWS)), dim3(256), 0, st,
                            lr->long_row, lr->long_first, lr->n_long, a.ptr, (const float*)a.partials, ld_part,
                            (const XT*)a.X, a.ldx, ep);
