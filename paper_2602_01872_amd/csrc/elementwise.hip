@@ -336,6 +336,76 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(int64_t n_rows, int C
     if (threadIdx.x == 0) loss_part[blockIdx.x] = loss;
 }
 
+// Same for C <= 16*NV: a lane keeps its NV logits in registers (one pass over Z, one expf per
+// element) and the logits of the group's next row are requested before the current row is
+// reduced, so the load latency overlaps the shuffles and exponentials.
+template <int NV>
+__global__ __launch_bounds__(256) void softmax_xent_reg_kernel(int64_t n_rows, int C, const float* __restrict__ Z,
+                                                               int64_t ldz, const int32_t* __restrict__ labels,
+                                                               const int32_t* __restrict__ nodes,
+                                                               const uint8_t* __restrict__ mask, int node_level,
+                                                               const int32_t* __restrict__ d_local,
+                                                               const int64_t* __restrict__ d_global,
+                                                               const float* __restrict__ rowscale,
+                                                               float* __restrict__ dZ, int64_t lddz, int c_store,
+                                                               const grp_step_stats* __restrict__ stats,
+                                                               double* __restrict__ loss_part) {
+    __shared__ double smd[4];
+    const int t = threadIdx.x & 15;
+    const int64_t S = stats->S;
+    const float inv_s = S > 0 ? 1.0f / (float)S : 0.f;
+    const int64_t stride = (int64_t)gridDim.x * 16;
+    double loss = 0.0;
+    int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    float cur[NV], nxt[NV];
+    auto load = [&](int64_t r, float (&v)[NV]) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) v[q] = (r < n_rows && t + 16 * q < C) ? Z[r * ldz + t + 16 * q] : -INFINITY;
+    };
+    load(row, cur);
+    for (; row < n_rows; row += stride) {
+        load(row + stride, nxt);
+        const int64_t v = nodes ? nodes[row] : row;
+        const bool in_loss = !mask || mask[v];
+        if (in_loss) {
+            float mx = cur[0];
+#pragma unroll
+            for (int q = 1; q < NV; ++q) mx = fmaxf(mx, cur[q]);
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 16));
+            float e[NV], sum = 0.f;
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                e[q] = t + 16 * q < C ? expf(cur[q] - mx) : 0.f;
+                sum += e[q];
+            }
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 16);
+            const int y = labels[v];
+            float w = 1.f;
+            if (node_level) w = (float)degree_ratio(d_local[v], d_global[v]);
+            const float k = w * inv_s * (rowscale ? rowscale[v] : 1.f), inv_sum = 1.0f / sum;
+            float zy = 0.f;                           // the label's logit sits in lane y%16, slot y/16
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                const int c = t + 16 * q;
+                if (c == y) zy = cur[q];
+                if (c < c_store) dZ[row * lddz + c] = c < C ? (e[q] * inv_sum - (c == y ? 1.f : 0.f)) * k : 0.f;
+            }
+            zy = __shfl(zy, y & 15, 16);
+            if (t == 0) loss += (double)w * (double)(logf(sum) + mx - zy);
+        } else {
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+                if (t + 16 * q < c_store) dZ[row * lddz + t + 16 * q] = 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < NV; ++q) cur[q] = nxt[q];
+    }
+    loss = block_sum<double>(loss, smd);
+    if (threadIdx.x == 0) loss_part[blockIdx.x] = loss;
+}
+
 __global__ __launch_bounds__(256) void loss_final_kernel(const double* __restrict__ part, int blocks,
                                                          grp_step_stats* __restrict__ stats) {
     __shared__ double smd[4];
@@ -353,8 +423,18 @@ grp_status launch_softmax_xent(int64_t n_rows, int32_t C, const float* Z, int64_
     double* loss_part = (double*)((char*)scratch + (size_t)STATS_BLOCKS * sizeof(StatsPartial));
     int c_store = (int)round_up(C, 4);
     if (c_store > lddz) c_store = (int)lddz;
-    hipLaunchKernelGGL(softmax_xent_kernel, dim3(STATS_BLOCKS), dim3(256), 0, st, n_rows, C, Z, ldz, labels, node_of_row,
-                       mask, node_level, d_local, d_global, rowscale, dZ, lddz, c_store, (const grp_step_stats*)stats, loss_part);
+#define GRP_SOFTMAX_ARGS                                                                                     \
+    n_rows, C, Z, ldz, labels, node_of_row, mask, node_level, d_local, d_global, rowscale, dZ, lddz, c_store, \
+        (const grp_step_stats*)stats, loss_part
+    if (c_store <= 16)
+        hipLaunchKernelGGL(softmax_xent_reg_kernel<1>, dim3(STATS_BLOCKS), dim3(256), 0, st, GRP_SOFTMAX_ARGS);
+    else if (c_store <= 32)
+        hipLaunchKernelGGL(softmax_xent_reg_kernel<2>, dim3(STATS_BLOCKS), dim3(256), 0, st, GRP_SOFTMAX_ARGS);
+    else if (c_store <= 64)
+        hipLaunchKernelGGL(softmax_xent_reg_kernel<4>, dim3(STATS_BLOCKS), dim3(256), 0, st, GRP_SOFTMAX_ARGS);
+    else
+        hipLaunchKernelGGL(softmax_xent_kernel, dim3(STATS_BLOCKS), dim3(256), 0, st, GRP_SOFTMAX_ARGS);
+#undef GRP_SOFTMAX_ARGS
     GRP_LAUNCH_CHECK();
     hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, st, (const double*)loss_part, STATS_BLOCKS, stats);
     GRP_LAUNCH_CHECK();
