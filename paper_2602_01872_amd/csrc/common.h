@@ -190,11 +190,6 @@ struct GemmTNArgs {
 };
 grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st);
 
-// out[N x K] (pitch ld_out) = in[K x N]^T; columns [K, round_up(K,4)) and rows [N, n_pad_rows) are
-// zero-filled, columns beyond round_up(K,4) are left alone (two matrices may share a pitch).
-grp_status launch_transpose(const float* in, int32_t K, int32_t N, float* out, int64_t ld_out,
-                            int32_t n_pad_rows, hipStream_t st);
-
 // out[N] = column sums of A[M x N]; scratch holds the per-block partials.
 size_t colsum_workspace_bytes(int64_t M, int32_t N);
 grp_status launch_colsum(const float* A, int64_t M, int32_t N, int64_t lda, float* out,
@@ -205,11 +200,24 @@ grp_status launch_colsum_scaled(const float* A, int64_t M, int32_t N, int64_t ld
 // inv_in = 1/max(d_in,1); r = 1/sqrt(max(d_in+sl,1)); s = 1/sqrt(max(d_out+sl,1)); rinv = 1/r.
 grp_status launch_degree_scales(const int32_t* d_in, const int32_t* d_out, int64_t n, int sl,
                                 float* inv_in, float* r, float* s, float* rinv, hipStream_t st);
-// out[rows x cols] (pitch ld_out) = in (dense, pitch cols); columns [cols, round_up(cols,4)) are
-// zero-filled, columns beyond are left alone.
-// Rows [rows, rows_pad) are zero-filled too.
-grp_status launch_pad_copy(const float* in, int32_t rows, int32_t cols, int32_t rows_pad, float* out,
-                           int64_t ld_out, hipStream_t st);
+// Weight re-packing jobs of one step (at most four per layer), run by a single launch.
+struct PackJob {
+    const float* in;
+    float* out;
+    int32_t rows, cols;      // shape of `in` (dense, pitch cols)
+    int32_t transpose;       // 0: out = in;  1: out = in^T
+    int64_t ld_out;
+};
+struct PackJobs {
+    int32_t n = 0;
+    PackJob job[4 * GRP_MAX_LAYERS];
+    int64_t begin[4 * GRP_MAX_LAYERS + 1] = {0};
+};
+// Appends a job: the output is written with its columns zero-padded to a multiple of 4 and its
+// rows zero-padded to out_rows_pad.
+void pack_jobs_add(PackJobs& jobs, const float* in, int32_t rows, int32_t cols, bool transpose, int32_t out_rows_pad,
+                   float* out, int64_t ld_out);
+grp_status launch_pack_weights(const PackJobs& jobs, hipStream_t st);
 
 // Coverage statistics over the loss nodes and the weighted softmax cross-entropy.
 size_t stats_workspace_bytes(int64_t n);

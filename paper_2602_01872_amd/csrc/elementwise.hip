@@ -27,40 +27,41 @@ grp_status launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
     return GRP_OK;
 }
 
-// out[N rows, ld_out] = in[K x N]^T ; rows [N, n_pad_rows) and pad columns are zero.
-__global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict__ in, int K, int N,
-                                                        float* __restrict__ out, int64_t ld_out, int n_pad_rows) {
-    const int width = (K + 3) & ~3;
-    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= (int64_t)n_pad_rows * width) return;
-    const int r = (int)(e / width), c = (int)(e % width);       // out[r][c] = in[c][r]
-    out[(int64_t)r * ld_out + c] = (r < N && c < K) ? in[(int64_t)c * N + r] : 0.f;
+// All weight re-packing jobs of a step in one launch: job j owns the flat element range
+// [begin_j, begin_{j+1}) of the grid and is either a zero-padded copy or a zero-padded transpose.
+__global__ __launch_bounds__(256) void pack_weights_kernel(PackJobs jobs) {
+    const int64_t e0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e0 >= jobs.begin[jobs.n]) return;
+    int j = 0;
+    while (e0 >= jobs.begin[j + 1]) ++j;
+    const PackJob& J = jobs.job[j];
+    const int64_t e = e0 - jobs.begin[j];
+    if (J.transpose) {        // out[cols x rows] = in[rows x cols]^T; pad columns and rows [cols, out_rows_pad) are zero
+        const int width = (J.rows + 3) & ~3;
+        const int r = (int)(e / width), c = (int)(e % width);
+        J.out[(int64_t)r * J.ld_out + c] = (r < J.cols && c < J.rows) ? J.in[(int64_t)c * J.cols + r] : 0.f;
+    } else {                  // out[rows x cols] = in; pad columns and rows [rows, out_rows_pad) are zero
+        const int width = (J.cols + 3) & ~3;
+        const int r = (int)(e / width), c = (int)(e % width);
+        J.out[(int64_t)r * J.ld_out + c] = (r < J.rows && c < J.cols) ? J.in[(int64_t)r * J.cols + c] : 0.f;
+    }
 }
 
-grp_status launch_transpose(const float* in, int32_t K, int32_t N, float* out, int64_t ld_out, int32_t n_pad_rows,
-                            hipStream_t st) {
-    ProfScope ps("transpose_w", st);
-    const int64_t blocks = cdiv((int64_t)n_pad_rows * round_up(K, 4), 256);
-    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, K, N, out, ld_out, n_pad_rows);
-    GRP_LAUNCH_CHECK();
-    return GRP_OK;
+void pack_jobs_add(PackJobs& jobs, const float* in, int32_t rows, int32_t cols, bool transpose, int32_t out_rows_pad,
+                   float* out, int64_t ld_out) {
+    PackJob& J = jobs.job[jobs.n];
+    J.in = in; J.out = out; J.rows = rows; J.cols = cols; J.transpose = transpose ? 1 : 0; J.ld_out = ld_out;
+    const int32_t out_rows = transpose ? cols : rows;
+    if (out_rows_pad < out_rows) out_rows_pad = out_rows;
+    const int64_t width = round_up(transpose ? rows : cols, 4);
+    jobs.begin[jobs.n + 1] = jobs.begin[jobs.n] + (int64_t)out_rows_pad * width;
+    ++jobs.n;
 }
 
-__global__ __launch_bounds__(256) void pad_copy_kernel(const float* __restrict__ in, int rows, int cols, int rows_pad,
-                                                       float* __restrict__ out, int64_t ld_out) {
-    const int width = (cols + 3) & ~3;
-    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= (int64_t)rows_pad * width) return;
-    const int r = (int)(e / width), c = (int)(e % width);
-    out[(int64_t)r * ld_out + c] = (r < rows && c < cols) ? in[(int64_t)r * cols + c] : 0.f;
-}
-
-grp_status launch_pad_copy(const float* in, int32_t rows, int32_t cols, int32_t rows_pad, float* out, int64_t ld_out,
-                           hipStream_t st) {
-    ProfScope ps("pad_copy_w", st);
-    if (rows_pad < rows) rows_pad = rows;
-    const int64_t blocks = cdiv((int64_t)rows_pad * round_up(cols, 4), 256);
-    hipLaunchKernelGGL(pad_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, rows, cols, rows_pad, out, ld_out);
+grp_status launch_pack_weights(const PackJobs& jobs, hipStream_t st) {
+    if (jobs.n == 0 || jobs.begin[jobs.n] == 0) return GRP_OK;
+    ProfScope ps("pack_weights", st);
+    hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)cdiv(jobs.begin[jobs.n], 256)), dim3(256), 0, st, jobs);
     GRP_LAUNCH_CHECK();
     return GRP_OK;
 }

@@ -179,23 +179,22 @@ static void fill_spmm(SpmmArgs& s, const Block& B, bool transposed, float* parti
 
 static grp_status prep_weights(const grp_model_desc* m, const float* theta, StepPlan& p, hipStream_t st) {
     const bool sage = m->arch == GRP_ARCH_SAGE_MEAN;
+    PackJobs jobs;
     for (int l = 0; l < m->n_layers; ++l) {
         const LayerBufs& L = p.L[l];
         const int fin = m->dims[l], fout = m->dims[l + 1];
         // the products read their weights transposed: forward uses W^T (rows = outputs), the
         // backward pass to the layer below uses W itself (rows = inputs)
-        GRP_TRY(launch_transpose(theta + L.off_ws, fin, fout, L.Wt_s, L.ldwt, (int)ldp(fout), st));
-        if (sage) GRP_TRY(launch_transpose(theta + L.off_wn, fin, fout, L.Wt_n, L.ldwt, (int)ldp(fout), st));
+        pack_jobs_add(jobs, theta + L.off_ws, fin, fout, true, (int)ldp(fout), L.Wt_s, L.ldwt);
+        if (sage) pack_jobs_add(jobs, theta + L.off_wn, fin, fout, true, (int)ldp(fout), L.Wt_n, L.ldwt);
         if (l > 0) {
-            GRP_TRY(launch_pad_copy(theta + L.off_ws, fin, fout, (int)ldp(fin), L.Wp_s, L.ldwp, st));
-            if (sage) GRP_TRY(launch_pad_copy(theta + L.off_wn, fin, fout, (int)ldp(fin), L.Wp_n, L.ldwp, st));
+            pack_jobs_add(jobs, theta + L.off_ws, fin, fout, false, (int)ldp(fin), L.Wp_s, L.ldwp);
+            if (sage) pack_jobs_add(jobs, theta + L.off_wn, fin, fout, false, (int)ldp(fin), L.Wp_n, L.ldwp);
         }
     }
-    return GRP_OK;
+    return launch_pack_weights(jobs, st);
 }
 
-// GraphSAGE-mean forward + loss + backward over k blocks.  X is the input of block 0
-// (the partition's feature matrix); loss rows are block k-1's destinations.
 static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, const grp_step_opts* o, const Block* blk,
                             const void* X, const int32_t* labels, const uint8_t* mask, const int32_t* loss_nodes,
                             const float* theta, StepPlan& p, hipStream_t st, float* grad, grp_step_stats* stats) {
