@@ -46,6 +46,171 @@ def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+def _time_steps(torch, fn, warmup, steps):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def _kernel_table(g, torch, fn, steps, detail=False):
+    g.grp_profile_enable(2 if detail else 1)
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    prof = g.grp_profile_report()
+    g.grp_profile_enable(False)
+    kernels = {}
+    for name, r in prof.items():
+        kernels[name] = dict(launches_per_step=r["launches"] / steps, avg_us=r["ms"] / r["launches"] * 1e3,
+                             ms_per_step=r["ms"] / steps,
+                             gflops=r["flops"] / r["ms"] / 1e6 if r["ms"] > 0 else 0.0,
+                             gbs=r["bytes"] / r["ms"] / 1e6 if r["ms"] > 0 else 0.0)
+    for name in sorted(kernels, key=lambda k: -kernels[k]["ms_per_step"]):
+        k = kernels[name]
+        log(f"  {name:28s} {k['launches_per_step']:5.1f} launches/step {k['ms_per_step']:9.4f} ms/step "
+            f"{k['gflops'] / 1e3:8.2f} TFLOP/s {k['gbs']:9.1f} GB/s")
+    return kernels
+
+
+def _roofline(kernels, traffic_table):
+    dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    k = kernels[dom]
+    if dom.startswith("gemm") and "reduce" not in dom:
+        r = dict(kernel=dom, bound="mfma", achieved=k["gflops"] / 1e3, peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
+                 frac=k["gflops"] / 1e3 / PEAK_FP32_MFMA_TFLOPS)
+    else:
+        r = dict(kernel=dom, bound="hbm", achieved=k["gbs"], peak=PEAK_HBM_GBS, unit="GB/s", frac=k["gbs"] / PEAK_HBM_GBS)
+    r["traffic"] = traffic_table.get(dom)
+    if r["traffic"] and r["bound"] == "hbm":     # counter-measured bytes over the live launch time
+        r["achieved_traffic_GBs"] = r["traffic"] / (k["avg_us"] * 1e-6) / 1e9
+        r["traffic_frac_of_peak"] = r["achieved_traffic_GBs"] / PEAK_HBM_GBS
+    r["avg_launch_us"] = k["avg_us"]
+    r["launches_per_step"] = k["launches_per_step"]
+    return r
+
+
+# HBM bytes per launch of the evidence workloads' dominant kernels, keyed by workload (same method as
+# above; see profiles/spmm_aggregate_hbm_traffic.md).  A SpMM launch includes its combine kernel.
+EVIDENCE_TRAFFIC = {
+    "c4-spmm": {"spmm_rows_f32": 9.72e10},
+    "c5-spmm": {"spmm_rows_bf16": 1.236e11},
+    "aggregate-stress": {"aggregate": 1.787e10},
+}
+
+
+def run_evidence_workload(args, g, synth, torch, dev):
+    """Evidence runs for the configurations other than the headline one: real shapes, synthetic data,
+    one JSON line each.  Graphs are generated directly as local subgraphs (one partition's share)."""
+    wl = args.workload
+    if args.copy_calibration:
+        cal_src = torch.ones(1 << 28, device=dev)      # 1 GiB read + 1 GiB written by one plain copy kernel
+        cal_dst = torch.empty_like(cal_src)
+        cal_dst.copy_(cal_src)
+        torch.cuda.synchronize()
+        del cal_src, cal_dst
+    out = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "data": "synthetic"}
+    if wl == "aggregate-stress":
+        K, P = 64, 1 << 26                                  # 17 GB of gradients: shows the kernel's bandwidth
+        grads = torch.empty(K, P, device=dev).normal_()
+        stats = g.new_stats(K, device=dev)
+        upd = torch.empty(P, device=dev)
+        fn = lambda: g.grp_aggregate(grads, P, stats, K, P, g.EST_NONE, upd)
+        dt = _time_steps(torch, fn, args.warmup, args.steps)
+        kernels = _kernel_table(g, torch, fn, args.steps)
+        out.update(metric="aggregated gradient bytes/s (K=64, P=2^26; non-config stress shape)", unit="GB/s",
+                   value=4.0 * P * (K + 1) / dt / 1e9, ms_per_step=dt * 1e3, dtype="f32",
+                   config={"workload": "aggregate-stress: K=64 partition gradients of P=2^26 floats"},
+                   roofline=_roofline(kernels, EVIDENCE_TRAFFIC.get(wl, {})), kernels=kernels)
+        print(json.dumps(out), flush=True)
+        return
+
+    if wl in ("c4-spmm", "c4-step"):
+        scale, n, E, seed, F0, bf16 = 22, 1 << 22, 100_000_000, GRAPH_SEED - 2 + 4, 128, False
+    elif wl == "c5-spmm":
+        # one quarter of configuration 5's edge factor (2^30 instead of 2^32 edges) on the same 2^24 nodes
+        scale, n, E, seed, F0, bf16 = 24, 1 << 24, 1 << 30, GRAPH_SEED - 2 + 5, 64, True
+    else:                                                    # c3-step
+        scale, n, E, seed, F0, bf16 = 23, 7_000_000, 100_000_000, GRAPH_SEED - 2 + 3, 128, True
+    t0 = time.time()
+    src, dst = synth.rmat_graph(scale, E, seed=seed, n_nodes=n, device=dev, chunk=1 << 28,
+                                progress=lambda done, total: log(f"{wl}: generated {done} of {total} edges"))
+    torch.cuda.synchronize()
+    missing = {"c3-step": 15, "c5-spmm": 255}.get(wl, 0)    # the other partitions' shares of each node's in-degree
+    d_global = None
+    if missing:
+        d_local = torch.bincount(dst, minlength=n)
+        d_global = synth.stand_in_global_degree(d_local, torch.arange(n, device=dev), seed, missing)
+    part = g.grp_partition_from_local_coo(src, dst, n, d_global_in=d_global)
+    nnz = part.nnz
+    del src, dst
+    torch.cuda.empty_cache()
+    log(f"{wl}: local graph n={n} nnz={nnz} generated and built in {time.time() - t0:.1f}s")
+
+    if wl.endswith("-spmm"):
+        F = 256 if wl == "c4-spmm" else 64
+        x = synth.normal_matrix(n, F, seed, device=dev)
+        if bf16:
+            x = synth.to_bf16_rne(x)
+        y = torch.empty(n, F, device=dev)
+        dt_code = g.DTYPE_BF16 if bf16 else g.DTYPE_FP32
+
+        def fn():
+            g.grp_spmm(part, False, g.SCALE_MEAN, False, F, x, F, dt_code, y, F)      # forward (CSR)
+            g.grp_spmm(part, True, g.SCALE_MEAN, False, F, x, F, dt_code, y, F)       # transposed (CSC)
+        dt = _time_steps(torch, fn, args.warmup, args.steps)
+        kernels = _kernel_table(g, torch, fn, args.steps)
+        el = 2 if bf16 else 4
+        b_min = 4 * nnz + 8 * (n + 1) + el * F * n + 4 * F * n
+        out.update(metric="SpMM edges/s (one forward + one transposed aggregation)", unit="edges/s",
+                   value=2 * nnz / dt, ms_per_step=dt * 1e3, dtype="bf16-stored, f32 accumulate" if bf16 else "f32",
+                   config={"workload": f"{wl}: mean aggregation, F={F}, R-MAT scale {scale}, n={n}, nnz={nnz}"
+                                       + (" (one quarter of the configuration's 2^32 edges)" if wl == "c5-spmm" else ""),
+                           "algorithmic_bytes_per_call": b_min, "no_reuse_bytes_per_call": nnz * (4 + el * F) + 4 * F * n},
+                   roofline=_roofline(kernels, EVIDENCE_TRAFFIC.get(wl, {})), kernels=kernels)
+        print(json.dumps(out), flush=True)
+        return
+
+    # full train steps
+    if wl == "c4-step":
+        dims = [128] + [256] * 7 + [64]
+        model = g.model_desc(g.ARCH_GCN_RESIDUAL, dims)
+        opts = g.step_opts(estimator=g.EST_NONE, full_graph=True)
+        arch = "gcn"
+        x = synth.normal_matrix(n, dims[0], seed, device=dev)
+    else:
+        dims = [128, 256, 256, 172]
+        model = g.model_desc(g.ARCH_SAGE_MEAN, dims, feat_dtype=g.DTYPE_BF16)
+        train = torch.nonzero(synth.train_mask(n, 0.05, seed, device=dev)).flatten().to(torch.int32)
+        seeds = train[:1024].contiguous()
+        opts = g.step_opts(estimator=g.EST_BATCH_MIN_DIST, full_graph=False, seeds=seeds, fanouts=(15, 10, 5),
+                           sampler_seed=7, batch_id=0)
+        arch = "sage"
+        x = synth.to_bf16_rne(synth.normal_matrix(n, dims[0], seed, device=dev))
+    y = synth.labels(n, dims[-1], seed, device=dev)
+    theta = synth.model_weights(arch, dims, seed, device=dev)
+    P = g.grp_param_count(model)
+    grad = torch.zeros((P + 3) // 4 * 4, device=dev)
+    stats = g.new_stats(1, device=dev)
+    ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=dev)
+    log(f"{wl}: workspace {ws.numel() / 1e9:.2f} GB, P={P}")
+    fn = lambda: g.grp_train_step(part, model, opts, x, y, None, theta, ws, grad, stats)
+    dt = _time_steps(torch, fn, args.warmup, args.steps)
+    kernels = _kernel_table(g, torch, fn, args.steps)
+    used = int(g.read_stats(stats)[0]["nnz_used"])
+    out.update(metric="per-partition train-step edges/s (fwd+bwd)", unit="edges/s", value=used / dt, ms_per_step=dt * 1e3,
+               dtype="bf16-stored features, f32 arithmetic" if wl == "c3-step" else "f32",
+               config={"workload": f"{wl}: dims {dims}, R-MAT scale {scale}, n={n}, nnz={nnz}, edges used per step {used}",
+                       "params": P},
+               roofline=_roofline(kernels, EVIDENCE_TRAFFIC.get(wl, {})), kernels=kernels)
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,6 +219,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--small", action="store_true", help="scaled-down graph (debugging only; not a valid result)")
     ap.add_argument("--shapes", action="store_true", help="per-launch-shape kernel table on stderr (debugging)")
+    ap.add_argument("--workload", default="c2-step",
+                    choices=["c2-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "aggregate-stress"],
+                    help="c2-step (default) is the headline workload; the others are evidence runs for the other "
+                         "configurations (each prints one JSON line of the same form)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for hardware byte counters)")
     args = ap.parse_args()
@@ -71,6 +240,9 @@ def main():
     g.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.workload != "c2-step":
+        run_evidence_workload(args, g, synth, torch, dev)
+        return
     n_nodes, n_edges, scale = N_NODES, N_EDGES, RMAT_SCALE
     if args.small:
         n_nodes, n_edges, scale = 240_000, 6_200_000, 18

@@ -68,13 +68,14 @@ def uniform_graph(n_nodes: int, n_edges: int, seed: int, device="cpu"):
 
 def rmat_graph(scale: int, n_edges: int, seed: int, n_nodes: int | None = None,
                a: float = 0.57, b: float = 0.19, c: float = 0.19, device="cpu",
-               chunk: int = 1 << 26):
+               chunk: int = 1 << 26, progress=None):
     """Graph500-style R-MAT edge list with 2**scale raw ids.
 
     Each of the ``scale`` recursion levels picks a quadrant with probabilities
     (a, b, c, 1-a-b-c) from 16 fresh random bits.  Raw ids are then scrambled by a
     fixed bijection-free mixer and folded ``mod n_nodes`` (default 2**scale) so that
     hubs are not clustered at small ids.  Duplicates and self-loops are kept.
+    Edges are generated ``chunk`` at a time (``progress(done, total)`` is called after each).
     """
     if n_nodes is None:
         n_nodes = 1 << scale
@@ -101,6 +102,8 @@ def rmat_graph(scale: int, n_edges: int, seed: int, n_nodes: int | None = None,
         d = _lsr(_fmix(d ^ scr), 1) % n_nodes
         src_parts.append(s)
         dst_parts.append(d)
+        if progress is not None:
+            progress(hi, n_edges)
     if len(src_parts) == 1:
         return src_parts[0], dst_parts[0]
     return torch.cat(src_parts), torch.cat(dst_parts)
