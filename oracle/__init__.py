@@ -18,6 +18,8 @@ Modules
                "Coverage-Corrected Aggregation"; the phase-parallel algorithm)
     sampling   isolated k-hop neighbour sampling inside the local subgraph
     step       glue: one partition's train step -> flat gradient + coverage statistics
+    optim      optimizer step (Adam / SGD) and the phase-parallel epoch loop          (the
+               phase-parallel algorithm)
 
 Pins (what each part is checked against, other than itself) live in
 ``tests/test_oracle_*.py``; a function with no independent pin says "parity unpinned"

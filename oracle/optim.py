@@ -1,0 +1,77 @@
+"""Optimizer step and the phase-parallel epoch loop (oracle; test infrastructure).
+
+The paper's phase-parallel algorithm ends every iteration with
+``theta <- optimizer_step(theta, grad)`` and carries theta and the optimizer state from one
+phase to the next; it names no optimizer (the experimental setup fixes only the learning
+rate, 0.003).  Reading taken here: Adam as published by Kingma & Ba (2015, their
+Algorithm 1: bias-corrected first and second moments, beta1 = 0.9, beta2 = 0.999,
+eps = 1e-8, no weight decay), with plain SGD (theta <- theta - lr * grad) as the other
+choice.  Everything is float64 numpy.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import coverage, step
+
+SGD, ADAM = 0, 1
+
+
+def sgd_step(theta, grad, lr):
+    """theta - lr * grad."""
+    return np.asarray(theta, dtype=np.float64) - lr * np.asarray(grad, dtype=np.float64)
+
+
+def adam_step(theta, grad, m, v, t, lr=0.003, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One Adam update; ``t`` is the 1-based count of this step.  Returns (theta, m, v).
+
+    m <- beta1 m + (1 - beta1) g;  v <- beta2 v + (1 - beta2) g^2;
+    theta <- theta - lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps).
+    """
+    g = np.asarray(grad, dtype=np.float64)
+    m = beta1 * np.asarray(m, dtype=np.float64) + (1.0 - beta1) * g
+    v = beta2 * np.asarray(v, dtype=np.float64) + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** t)
+    v_hat = v / (1.0 - beta2 ** t)
+    return np.asarray(theta, dtype=np.float64) - lr * m_hat / (np.sqrt(v_hat) + eps), m, v
+
+
+def phase_schedule(n_parts: int, max_active: int):
+    """Partitions of phase i = the i-th run of ``max_active`` consecutive partition ids
+    (ceil(n_parts / max_active) phases; the last one may be shorter)."""
+    return [list(range(lo, min(n_parts, lo + max_active))) for lo in range(0, n_parts, max_active)]
+
+
+def train_epochs(parts, arch, dims, theta0, xs, ys, masks, n_epochs, max_active, estimator,
+                 optimizer=ADAM, lr=0.003, gcn_self_loops=True):
+    """The phase-parallel algorithm in full-graph mode (one iteration per phase and epoch).
+
+    ``parts`` are the partitions of one graph; ``xs[p]``, ``ys[p]``, ``masks[p]`` their
+    features, labels and train masks (mask None = every node).  In every phase the active
+    partitions each take one isolated train step at the current theta, their gradients are
+    scaled by the coverage factor of ``estimator`` and averaged over the active partitions,
+    and one optimizer step follows; theta and the optimizer state carry over to the next
+    phase.  Returns (theta, history) where history lists per optimizer step the mean of the
+    active partitions' losses.
+    """
+    theta = np.asarray(theta0, dtype=np.float64).copy()
+    m = np.zeros_like(theta)
+    v = np.zeros_like(theta)
+    t = 0
+    history = []
+    for _ in range(n_epochs):
+        for active in phase_schedule(len(parts), max_active):
+            grads, stats = [], []
+            for p in active:
+                g, st = step.train_step(parts[p], arch, dims, theta, xs[p], ys[p], masks[p],
+                                        estimator=estimator, gcn_self_loops=gcn_self_loops)
+                grads.append(g)
+                stats.append(st)
+            G, _ = coverage.aggregate(grads, stats, estimator)
+            t += 1
+            if optimizer == ADAM:
+                theta, m, v = adam_step(theta, G, m, v, t, lr)
+            else:
+                theta = sgd_step(theta, G, lr)
+            history.append(float(np.mean([s["loss"] for s in stats])))
+    return theta, history

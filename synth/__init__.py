@@ -125,6 +125,12 @@ def labels(n: int, n_classes: int, seed: int, device="cpu") -> torch.Tensor:
     return (_lsr(stream_bits(seed, 5, i), 1) % n_classes).to(torch.int32)
 
 
+def planted_labels(x: torch.Tensor, n_classes: int, seed: int) -> torch.Tensor:
+    """Learnable int32 labels: the arg-max of a seeded random linear map of the features."""
+    r = normal_matrix(x.shape[1], n_classes, seed, stream=9, device=x.device, dtype=torch.float32)
+    return torch.argmax(x.to(torch.float32) @ r, dim=1).to(torch.int32)
+
+
 def train_mask(n: int, frac: float, seed: int, device="cpu") -> torch.Tensor:
     """uint8 mask selecting about ``frac`` of the nodes."""
     i = torch.arange(n, dtype=torch.int64, device=device)

@@ -1,0 +1,112 @@
+"""Pins for oracle.optim: Adam against torch.optim.Adam (a library routine) and against the
+closed form of its first step, SGD against its definition on a quadratic with a known fixed
+point, the phase schedule by brute force, and the epoch loop against its special cases (one
+partition with full coverage = plain gradient descent on the whole graph; a planted-label
+problem whose loss must fall)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import coverage as cov
+from oracle import graph, optim, step
+
+
+def test_adam_matches_library_adam():
+    rng = np.random.default_rng(5)
+    theta0 = rng.normal(size=37)
+    grads = [rng.normal(size=37) * 10.0 ** rng.integers(-4, 2) for _ in range(6)]
+    p = torch.nn.Parameter(torch.tensor(theta0, dtype=torch.float64))
+    opt = torch.optim.Adam([p], lr=0.003, betas=(0.9, 0.999), eps=1e-8)
+    theta, m, v = theta0.copy(), np.zeros(37), np.zeros(37)
+    for t, g in enumerate(grads, start=1):
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        theta, m, v = optim.adam_step(theta, g, m, v, t, lr=0.003)
+        np.testing.assert_allclose(theta, p.detach().numpy(), rtol=1e-12, atol=1e-14)
+
+
+def test_adam_first_step_closed_form():
+    # t = 1: m_hat = g, v_hat = g^2, so the step is lr * g / (|g| + eps): lr * sign(g) for |g| >> eps, 0 for g = 0
+    g = np.array([3.0, -0.25, 0.0, 1e-3])
+    theta, m, v = optim.adam_step(np.zeros(4), g, np.zeros(4), np.zeros(4), 1, lr=0.01)
+    np.testing.assert_allclose(theta, -0.01 * g / (np.abs(g) + 1e-8), rtol=1e-13)
+    assert theta[2] == 0.0
+    np.testing.assert_allclose(m, 0.1 * g)
+    np.testing.assert_allclose(v, 0.001 * g * g)
+
+
+def test_sgd_converges_to_the_quadratic_minimum():
+    a = np.array([1.0, 4.0, 0.5])
+    target = np.array([2.0, -1.0, 3.0])
+    th = np.zeros(3)
+    for _ in range(400):
+        th = optim.sgd_step(th, a * (th - target), 0.2)       # gradient of 0.5 * a * (th - target)^2
+    np.testing.assert_allclose(th, target, atol=1e-12)
+    np.testing.assert_array_equal(optim.sgd_step([1.0, 2.0], [0.5, -1.0], 0.1), [0.95, 2.1])
+
+
+@pytest.mark.parametrize("P,M", [(1, 1), (4, 1), (4, 2), (5, 2), (8, 3), (3, 8)])
+def test_phase_schedule_covers_every_partition_once(P, M):
+    ph = optim.phase_schedule(P, M)
+    assert len(ph) == -(-P // M)
+    assert all(1 <= len(a) <= M for a in ph)
+    assert sorted(p for a in ph for p in a) == list(range(P))
+
+
+def _problem(N=120, E=900, K=1, seed=3):
+    s, d = synth.uniform_graph(N, E, seed=seed)
+    s, d = s.numpy(), d.numpy()
+    parts = [graph.partition(s, d, N, K, 1, p) for p in range(K)]
+    x = synth.normal_matrix(N, 6, 11)
+    y = synth.planted_labels(x, 3, 12).numpy()
+    x = x.double().numpy()
+    xs = [x[p["l2g"]] for p in parts]
+    ys = [y[p["l2g"]] for p in parts]
+    return parts, xs, ys
+
+
+def test_one_partition_full_coverage_is_plain_gradient_descent():
+    parts, xs, ys = _problem(K=1)
+    dims = [6, 8, 3]
+    theta0 = synth.model_weights("sage", dims, 4).double().numpy()
+    for est in (cov.NONE, cov.BATCH_MIN_DIST, cov.SHRINKAGE):
+        th, hist = optim.train_epochs(parts, "sage", dims, theta0, xs, ys, [None], 3, 1, est,
+                                      optimizer=optim.SGD, lr=0.05)
+        ref = theta0.copy()
+        for _ in range(3):
+            g, _ = step.train_step(parts[0], "sage", dims, ref, xs[0], ys[0])
+            ref = ref - 0.05 * g
+        np.testing.assert_allclose(th, ref, rtol=1e-13, atol=1e-15)
+        assert len(hist) == 3
+
+
+@pytest.mark.parametrize("opt,lr", [(optim.ADAM, 0.01), (optim.SGD, 0.2)])
+@pytest.mark.parametrize("M", [1, 2, 4])
+def test_loss_falls_on_planted_labels(opt, lr, M):
+    parts, xs, ys = _problem(N=400, E=4000, K=4)
+    dims = [6, 16, 3]
+    theta0 = synth.model_weights("sage", dims, 4).double().numpy()
+    th, hist = optim.train_epochs(parts, "sage", dims, theta0, xs, ys, [None] * 4, 30, M, cov.BATCH_MIN_DIST,
+                                  optimizer=opt, lr=lr)
+    steps_per_epoch = -(-4 // M)
+    assert len(hist) == 30 * steps_per_epoch
+    first = np.mean(hist[:steps_per_epoch])
+    last = np.mean(hist[-steps_per_epoch:])
+    assert last < 0.8 * first, (first, last)
+    assert np.isfinite(th).all()
+
+
+def test_phase_order_state_is_carried():
+    # M = K (one phase) and M = 1 (K phases) must differ after one epoch: with M = 1 every
+    # partition sees the theta already updated by the partitions before it
+    parts, xs, ys = _problem(N=300, E=3000, K=3)
+    dims = [6, 5, 3]
+    theta0 = synth.model_weights("sage", dims, 4).double().numpy()
+    a, ha = optim.train_epochs(parts, "sage", dims, theta0, xs, ys, [None] * 3, 1, 3, cov.NONE, optimizer=optim.SGD, lr=0.1)
+    b, hb = optim.train_epochs(parts, "sage", dims, theta0, xs, ys, [None] * 3, 1, 1, cov.NONE, optimizer=optim.SGD, lr=0.1)
+    assert len(ha) == 1 and len(hb) == 3
+    assert np.abs(a - b).max() > 1e-6
+    # M = K: one step with the plain average of the three gradients
+    gs = [step.train_step(parts[p], "sage", dims, theta0, xs[p], ys[p])[0] for p in range(3)]
+    np.testing.assert_allclose(a, theta0 - 0.1 * sum(gs) / 3, rtol=1e-13, atol=1e-15)
