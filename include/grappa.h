@@ -8,6 +8,7 @@
  * at a time is, per partition p = 0..K-1:
  *     (isolated sampling) -> forward -> backward            grp_train_step
  *     scale grad by the coverage factor, reduce over p      grp_aggregate
+ *     theta <- optimizer_step(theta, grad)                   grp_optimizer_step
  * on a local subgraph built once per (graph, K, seed, p) by grp_partition.
  *
  * General conventions
@@ -203,6 +204,35 @@ grp_status grp_train_step(const grp_partition_t* part, const grp_model_desc* mod
 grp_status grp_aggregate(const float* grads, int64_t ld_grads, const grp_step_stats* stats,
                          int32_t K, int64_t P, int32_t variant, void* stream,
                          float* update, float* c_out);
+
+/* ------------------------------------------------------------------ optimizer */
+
+#define GRP_OPT_SGD  0
+#define GRP_OPT_ADAM 1
+
+/* Hyper-parameters of the optimizer step.  The paper fixes only the learning rate (0.003,
+ * experimental setup) and names no optimizer; ADAM is the published algorithm of Kingma &
+ * Ba (bias-corrected moments, no weight decay), SGD is theta - lr * update.              */
+typedef struct grp_optimizer_desc {
+    int32_t kind;            /* GRP_OPT_SGD | GRP_OPT_ADAM                                  */
+    int32_t reserved;
+    float   lr;              /* > 0                                                         */
+    float   beta1, beta2;    /* ADAM: in [0, 1)                                             */
+    float   eps;             /* ADAM: > 0                                                   */
+} grp_optimizer_desc;
+
+/* theta <- optimizer_step(theta, update): the last line of an iteration of the phase-
+ * parallel algorithm; theta and the optimizer state (m, v, the step count) are the
+ * caller's and carry over from phase to phase.
+ *   theta   DEV float[P], updated in place
+ *   update  DEV float[P], the aggregated gradient G (read only)
+ *   m, v    DEV float[P] first / second moment, updated in place (ADAM; ignored for SGD,
+ *           may be NULL then); the caller zero-fills them before step 1
+ *   step    1-based count of this step (ADAM's bias correction)
+ * fp32 arithmetic, one pass over the arrays.  Errors: GRP_EINVAL (null pointer, P < 0,
+ * step < 1, hyper-parameters out of range).                                              */
+grp_status grp_optimizer_step(const grp_optimizer_desc* opt, int64_t P, int64_t step, float* theta,
+                              const float* update, float* m, float* v, void* stream);
 
 /* ------------------------------------------------------------------ building blocks */
 

@@ -6,3 +6,4 @@ marshals arguments: device memory comes from torch tensors (``data_ptr()``), str
 There is no CPU fallback: importing ``binding`` without the built library raises.
 """
 from .binding import *  # noqa: F401,F403
+from .loop import PhaseParallelTrainer  # noqa: F401

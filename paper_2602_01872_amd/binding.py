@@ -14,6 +14,7 @@ GRP_MAX_LAYERS = 16
 ARCH_SAGE_MEAN, ARCH_GCN, ARCH_GCN_RESIDUAL = 0, 1, 2
 DTYPE_FP32, DTYPE_BF16 = 0, 1
 EST_NONE, EST_NODE_LEVEL, EST_BATCH_MIN_DIST, EST_SHRINKAGE = 0, 1, 2, 3
+OPT_SGD, OPT_ADAM = 0, 1
 SCALE_NONE, SCALE_MEAN, SCALE_RSQRT = 0, 1, 2
 OK, EINVAL, ERANGE, ENOMEM, EWORKSPACE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 
@@ -33,6 +34,11 @@ class PartitionView(C.Structure):
 class ModelDesc(C.Structure):
     _fields_ = [("arch", C.c_int32), ("n_layers", C.c_int32), ("dims", C.c_int32 * (GRP_MAX_LAYERS + 1)),
                 ("feat_dtype", C.c_int32), ("gcn_self_loops", C.c_int32)]
+
+
+class OptimizerDesc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("reserved", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float),
+                ("beta2", C.c_float), ("eps", C.c_float)]
 
 
 class StepOpts(C.Structure):
@@ -66,6 +72,7 @@ def load() -> C.CDLL:
         "grp_step_workspace_bytes": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), C.POINTER(sz)],
         "grp_train_step": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), vp, vp, vp, vp, vp, sz, vp, vp, vp],
         "grp_aggregate": [vp, i64, vp, i32, i64, i32, vp, vp, vp],
+        "grp_optimizer_step": [C.POINTER(OptimizerDesc), i64, i64, vp, vp, vp, vp, vp],
         "grp_spmm": [vp, i32, i32, i32, i32, vp, i64, i32, vp, i64, vp],
         "grp_gemm_nn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
         "grp_gemm_nt": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
@@ -217,6 +224,17 @@ def grp_aggregate(grads, ld_grads: int, stats, K: int, P: int, variant: int, upd
                                 _ptr(c_out)))
 
 
+def optimizer_desc(kind: int = OPT_ADAM, lr: float = 0.003, beta1: float = 0.9, beta2: float = 0.999,
+                   eps: float = 1e-8) -> OptimizerDesc:
+    o = OptimizerDesc()
+    o.kind, o.lr, o.beta1, o.beta2, o.eps = kind, lr, beta1, beta2, eps
+    return o
+
+
+def grp_optimizer_step(opt: OptimizerDesc, P: int, step: int, theta, update, m=None, v=None, stream=None):
+    _check(load().grp_optimizer_step(C.byref(opt), P, step, _ptr(theta), _ptr(update), _ptr(m), _ptr(v), _stream(stream)))
+
+
 def grp_spmm(part: Partition, transposed: bool, scale: int, self_term: bool, F: int, X, ldx: int, x_dtype: int, Y,
              ldy: int, stream=None):
     _check(load().grp_spmm(part.handle, int(transposed), scale, int(self_term), F, _ptr(X), ldx, x_dtype, _ptr(Y), ldy,
@@ -268,5 +286,5 @@ def read_stats(stats: torch.Tensor) -> np.ndarray:
 def exported_symbols():
     return ["grp_last_error", "grp_partition", "grp_partition_from_local_coo", "grp_partition_view",
             "grp_partition_destroy", "grp_param_count", "grp_step_workspace_bytes", "grp_train_step",
-            "grp_aggregate", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
+            "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
             "grp_profile_enable", "grp_profile_report"]

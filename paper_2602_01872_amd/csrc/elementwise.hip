@@ -6,6 +6,8 @@
 // bit-reproducible (no floating-point atomics).
 #include "common.h"
 
+#include <cmath>
+
 namespace grp {
 
 // ------------------------------------------------------------------ small utilities
@@ -492,7 +494,87 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const float* __restrict_
     }
 }
 
+// ------------------------------------------------------------------ optimizer step
+// One pass: Adam reads theta, g, m, v and writes theta, m, v (28 bytes per parameter); SGD
+// reads theta, g and writes theta (12 bytes).
+template <bool ADAM, bool VEC>
+__global__ __launch_bounds__(256) void optimizer_kernel(int64_t P, float* __restrict__ theta,
+                                                        const float* __restrict__ g, float* __restrict__ m,
+                                                        float* __restrict__ v, float lr, float b1, float b2,
+                                                        float eps, float inv_c1, float inv_c2) {
+    auto upd = [&](float& th, float gi, float& mi, float& vi) {
+        if (ADAM) {
+            mi = b1 * mi + (1.f - b1) * gi;
+            vi = b2 * vi + (1.f - b2) * gi * gi;
+            th -= lr * (mi * inv_c1) / (sqrtf(vi * inv_c2) + eps);
+        } else {
+            th -= lr * gi;
+        }
+    };
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    const int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if constexpr (VEC) {
+        const int64_t P4 = P / 4;
+        for (int64_t i = i0; i < P4; i += stride) {
+            float4 th = reinterpret_cast<float4*>(theta)[i];
+            const float4 gi = reinterpret_cast<const float4*>(g)[i];
+            float4 mi = make_float4(0.f, 0.f, 0.f, 0.f), vi = mi;
+            if (ADAM) { mi = reinterpret_cast<float4*>(m)[i]; vi = reinterpret_cast<float4*>(v)[i]; }
+            upd(th.x, gi.x, mi.x, vi.x); upd(th.y, gi.y, mi.y, vi.y);
+            upd(th.z, gi.z, mi.z, vi.z); upd(th.w, gi.w, mi.w, vi.w);
+            reinterpret_cast<float4*>(theta)[i] = th;
+            if (ADAM) { reinterpret_cast<float4*>(m)[i] = mi; reinterpret_cast<float4*>(v)[i] = vi; }
+        }
+        for (int64_t i = 4 * P4 + i0; i < P; i += stride) {
+            float mi = 0.f, vi = 0.f;
+            if (ADAM) { mi = m[i]; vi = v[i]; }
+            upd(theta[i], g[i], mi, vi);
+            if (ADAM) { m[i] = mi; v[i] = vi; }
+        }
+    } else {
+        for (int64_t i = i0; i < P; i += stride) {
+            float mi = 0.f, vi = 0.f;
+            if (ADAM) { mi = m[i]; vi = v[i]; }
+            upd(theta[i], g[i], mi, vi);
+            if (ADAM) { m[i] = mi; v[i] = vi; }
+        }
+    }
+}
+
 }  // namespace grp
+
+extern "C" grp_status grp_optimizer_step(const grp_optimizer_desc* opt, int64_t P, int64_t step, float* theta,
+                                         const float* update, float* m, float* v, void* stream) {
+    using namespace grp;
+    if (!opt || !theta || !update) return fail(GRP_EINVAL, "grp_optimizer_step: null argument");
+    if (P < 0 || step < 1) return fail(GRP_EINVAL, "grp_optimizer_step: P = %lld, step = %lld", (long long)P, (long long)step);
+    if (opt->kind != GRP_OPT_SGD && opt->kind != GRP_OPT_ADAM) return fail(GRP_EINVAL, "grp_optimizer_step: bad kind %d", opt->kind);
+    if (!(opt->lr > 0.f)) return fail(GRP_EINVAL, "grp_optimizer_step: lr must be positive");
+    const bool adam = opt->kind == GRP_OPT_ADAM;
+    if (adam) {
+        if (!m || !v) return fail(GRP_EINVAL, "grp_optimizer_step: Adam needs the moment arrays");
+        if (!(opt->beta1 >= 0.f && opt->beta1 < 1.f && opt->beta2 >= 0.f && opt->beta2 < 1.f && opt->eps > 0.f))
+            return fail(GRP_EINVAL, "grp_optimizer_step: Adam hyper-parameters out of range");
+    }
+    if (P == 0) return GRP_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const bool vec = (uintptr_t)theta % 16 == 0 && (uintptr_t)update % 16 == 0 &&
+                     (!adam || ((uintptr_t)m % 16 == 0 && (uintptr_t)v % 16 == 0));
+    int64_t blocks = cdiv(vec ? cdiv(P, 4) : P, 256);
+    if (blocks > 8192) blocks = 8192;
+    // bias corrections 1 - beta^t in double on the host (t can be large)
+    const float inv_c1 = adam ? (float)(1.0 / (1.0 - pow((double)opt->beta1, (double)step))) : 1.f;
+    const float inv_c2 = adam ? (float)(1.0 / (1.0 - pow((double)opt->beta2, (double)step))) : 1.f;
+    ProfScope ps("optimizer_step", st, 0.0, (adam ? 28.0 : 12.0) * P);
+#define GRP_OPT_LAUNCH(A, V)                                                                                         \
+    hipLaunchKernelGGL((optimizer_kernel<A, V>), dim3((unsigned)blocks), dim3(256), 0, st, P, theta, update, m, v, \
+                       opt->lr, opt->beta1, opt->beta2, opt->eps, inv_c1, inv_c2)
+    if (adam) { if (vec) GRP_OPT_LAUNCH(true, true); else GRP_OPT_LAUNCH(true, false); }
+    else { if (vec) GRP_OPT_LAUNCH(false, true); else GRP_OPT_LAUNCH(false, false); }
+#undef GRP_OPT_LAUNCH
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
 
 extern "C" grp_status grp_aggregate(const float* grads, int64_t ld_grads, const grp_step_stats* stats, int32_t K,
                                     int64_t P, int32_t variant, void* stream, float* update, float* c_out) {

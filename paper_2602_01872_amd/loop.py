@@ -1,0 +1,61 @@
+"""Phase-parallel epoch loop over the C ABI (the paper's phase-parallel algorithm, one GPU).
+
+Sequencing only: every partition step, the scale-and-reduce and the optimizer step are
+library calls; partitions of a phase are processed in turn on the one GPU and their
+gradients kept resident for the reduction.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as g
+
+
+class PhaseParallelTrainer:
+    """Holds theta, the optimizer state and the per-partition buffers across phases.
+
+    ``parts``: list of ``Partition``; ``xs`` / ``ys`` / ``masks``: per-partition device
+    tensors (features, int32 labels, uint8 train mask or None).  ``max_active`` = M, the
+    number of partitions per phase.  Full-graph mode (one iteration per phase and epoch).
+    """
+
+    def __init__(self, parts, model, xs, ys, masks, theta0, estimator, max_active, optimizer=None):
+        self.parts, self.model, self.xs, self.ys, self.masks = parts, model, xs, ys, masks
+        self.estimator, self.max_active = estimator, max_active
+        self.opt = optimizer if optimizer is not None else g.optimizer_desc()
+        dev = theta0.device
+        self.P = g.grp_param_count(model)
+        self.ld = (self.P + 3) // 4 * 4
+        self.theta = theta0.detach().clone().to(torch.float32).contiguous()
+        self.m = torch.zeros(self.P, device=dev)
+        self.v = torch.zeros(self.P, device=dev)
+        self.update = torch.zeros(self.P, device=dev)
+        self.opts = g.step_opts(estimator=estimator, full_graph=True)
+        self.grads = torch.zeros(max_active, self.ld, device=dev)
+        self.stats = g.new_stats(max_active, device=dev)
+        ws_bytes = max(g.grp_step_workspace_bytes(p, model, self.opts) for p in parts)
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.step_count = 0
+        self.history = []          # per optimizer step: device tensor views are copied lazily
+
+    def phases(self):
+        K, M = len(self.parts), self.max_active
+        return [list(range(lo, min(K, lo + M))) for lo in range(0, K, M)]
+
+    def run_phase(self, active):
+        for slot, p in enumerate(active):
+            g.grp_train_step(self.parts[p], self.model, self.opts, self.xs[p], self.ys[p], self.masks[p],
+                             self.theta, self.ws, self.grads[slot],
+                             self.stats[slot * g.STATS_BYTES:(slot + 1) * g.STATS_BYTES])
+        g.grp_aggregate(self.grads, self.ld, self.stats, len(active), self.P, self.estimator, self.update)
+        self.step_count += 1
+        g.grp_optimizer_step(self.opt, self.P, self.step_count, self.theta, self.update, self.m, self.v)
+        self.history.append(self.stats[:len(active) * g.STATS_BYTES].clone())
+
+    def run_epoch(self):
+        for active in self.phases():
+            self.run_phase(active)
+
+    def losses(self):
+        """Mean loss of the active partitions for every optimizer step so far (host floats)."""
+        return [float(g.read_stats(h)["loss"].mean()) for h in self.history]

@@ -38,6 +38,7 @@ def test_struct_layouts_match_header():
     assert C.sizeof(g.StepOpts) == 16 + 8 + 4 * 16 + 16
     assert g.STATS_BYTES == 40
     assert C.sizeof(g.PartitionView) == 8 * 10
+    assert C.sizeof(g.OptimizerDesc) == 24
 
 
 def test_param_count_and_invalid_model():

@@ -474,3 +474,94 @@ def test_gemm_nt_matches_numpy(g, M, N, K, bf16):
     torch.cuda.synchronize()
     want = a.cpu().double().numpy() @ bt.cpu().double().numpy().T
     assert rel_err(c.cpu().numpy(), want) <= TOL_FP32
+
+
+# ------------------------------------------------------------------ optimizer step and the phase-parallel loop
+@pytest.mark.gpu
+@pytest.mark.parametrize("P", [1, 7, 4096, 100003])
+@pytest.mark.parametrize("kind", ["adam", "sgd"])
+def test_optimizer_step_matches_oracle(g, P, kind):
+    from oracle import optim as ooptim
+    _note(f"optimizer {kind} P={P}")
+    rng = np.random.default_rng(P)
+    theta = rng.normal(size=P)
+    m = np.zeros(P)
+    v = np.zeros(P)
+    th_d = torch.tensor(theta, dtype=torch.float32, device=DEV)
+    m_d = torch.zeros(P, device=DEV)
+    v_d = torch.zeros(P, device=DEV)
+    theta = th_d.cpu().double().numpy()
+    opt = g.optimizer_desc(g.OPT_ADAM if kind == "adam" else g.OPT_SGD, lr=0.003)
+    # the ABI carries the hyper-parameters as fp32: the oracle gets the same (rounded) values
+    lr, b1, b2, eps = (float(np.float32(h)) for h in (0.003, 0.9, 0.999, 1e-8))
+    for t in range(1, 6):
+        grad = (rng.normal(size=P) * 10.0 ** rng.integers(-3, 2, size=P)).astype(np.float32)
+        grad[::5] = 0.0                                            # exact zeros stay put under Adam
+        g_d = torch.tensor(grad, device=DEV)
+        g.grp_optimizer_step(opt, P, t, th_d, g_d, m_d, v_d)
+        if kind == "adam":
+            theta, m, v = ooptim.adam_step(theta, grad.astype(np.float64), m, v, t, lr, b1, b2, eps)
+            assert rel_err(m_d.cpu().numpy(), m) < 2e-6
+            assert rel_err(v_d.cpu().numpy(), v) < 2e-6
+        else:
+            theta = ooptim.sgd_step(theta, grad.astype(np.float64), lr)
+        # the update is lr * O(1) per step: compare absolutely against lr
+        assert np.abs(th_d.cpu().double().numpy() - theta).max() < 0.003 * 2e-4
+
+
+@pytest.mark.gpu
+def test_optimizer_step_error_paths(g):
+    t = torch.zeros(8, device=DEV)
+    with pytest.raises(g.GrappaError):
+        g.grp_optimizer_step(g.optimizer_desc(g.OPT_ADAM), 8, 1, t, t, None, None)      # Adam without moments
+    with pytest.raises(g.GrappaError):
+        g.grp_optimizer_step(g.optimizer_desc(g.OPT_SGD), 8, 0, t, t)                   # step < 1
+    with pytest.raises(g.GrappaError):
+        g.grp_optimizer_step(g.optimizer_desc(g.OPT_SGD, lr=0.0), 8, 1, t, t)
+    with pytest.raises(g.GrappaError):
+        g.grp_optimizer_step(g.optimizer_desc(7), 8, 1, t, t)
+    g.grp_optimizer_step(g.optimizer_desc(g.OPT_SGD), 0, 1, t, t)                       # P = 0 is a no-op
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("M", [1, 2, 4])
+@pytest.mark.parametrize("kind", ["sgd", "adam"])
+def test_phase_parallel_loop_matches_oracle(g, M, kind):
+    """Algorithm 1 with K = 4 partitions, M per phase, two epochs: theta after every epoch and the
+    loss history against the oracle loop.  SGD is linear in the gradient (tight bound); Adam
+    normalises every coordinate, so coordinates whose gradient is at rounding level move by
+    up to lr per step in either run and the bound is lr-sized."""
+    from oracle import optim as ooptim
+    _note(f"phase-parallel loop M={M} {kind}")
+    N, E, K = 2000, 20000, 4
+    s, d = synth.uniform_graph(N, E, seed=77)
+    dims = [16, 32, 5]
+    x = synth.normal_matrix(N, dims[0], 78)
+    y = synth.planted_labels(x, dims[-1], 79)
+    theta0 = synth.model_weights("sage", dims, 80)
+    oparts = [ograph.partition(s.numpy(), d.numpy(), N, K, 1, p) for p in range(K)]
+    oxs = [x.double().numpy()[p["l2g"]] for p in oparts]
+    oys = [y.numpy()[p["l2g"]] for p in oparts]
+    parts = [g.grp_partition(s.to(DEV), d.to(DEV), N, K, 1, p) for p in range(K)]
+    xs = [x.to(DEV)[torch.from_numpy(p["l2g"]).to(DEV)].contiguous() for p in oparts]
+    ys = [y.to(DEV)[torch.from_numpy(p["l2g"]).to(DEV)].contiguous() for p in oparts]
+    model = g.model_desc(g.ARCH_SAGE_MEAN, dims)
+    lr = 0.05 if kind == "sgd" else 0.003
+    opt = g.optimizer_desc(g.OPT_SGD if kind == "sgd" else g.OPT_ADAM, lr=lr)
+    tr = g.PhaseParallelTrainer(parts, model, xs, ys, [None] * K, theta0.to(DEV), g.EST_BATCH_MIN_DIST, M, opt)
+    n_epochs = 2
+    for _ in range(n_epochs):
+        tr.run_epoch()
+    want, hist = ooptim.train_epochs(oparts, "sage", dims, theta0.double().numpy(), oxs, oys, [None] * K, n_epochs, M,
+                                     ocov.BATCH_MIN_DIST, optimizer=ooptim.SGD if kind == "sgd" else ooptim.ADAM, lr=lr)
+    got = tr.theta.cpu().double().numpy()
+    steps = len(hist)
+    assert tr.step_count == steps == n_epochs * -(-K // M)
+    np.testing.assert_allclose(tr.losses(), hist, rtol=2e-4)
+    if kind == "sgd":
+        assert rel_err(got, want) < TOL_FP32
+    else:
+        assert np.abs(got - want).max() < 0.5 * lr * steps          # no coordinate drifts by more than half its travel
+        assert np.mean(np.abs(got - want) < 1e-3 * lr * steps) > 0.99   # and almost all agree closely
+    for p in parts:
+        p.destroy()
