@@ -1,4 +1,4 @@
-"""Workload 2 at full size, in the launch configuration bench.py times: partition 0 of 8 of the
+"""Full-size cases.  Workload 2, in the launch configuration bench.py times: partition 0 of 8 of the
 2.4 M-node / 62 M-edge R-MAT graph, 3-layer GraphSAGE-mean 100-256-256-47.
 
 The partition arrays must be bit-exact.  The loss, the statistics, the last layer's gradients
@@ -59,3 +59,70 @@ def test_workload2_partition0_full_size():
         assert v <= 5e-3, (k, v)
         if v > TOL_FP32:
             assert len(ost["near_kink"]) > 0
+
+
+def _sampled_rows_and_checksum(g, scale, n, E, seed, F, bf16, n_sample=4096):
+    """Mean aggregation (forward over in-edges, transposed over out-edges) of a directly generated
+    local subgraph at full size.  The oracle cannot run at this size, so (a) a seeded sample of
+    output rows is recomputed exactly (each row needs only its own neighbour list, taken from the
+    edge list itself, not from the library's CSR), and (b) the column sums of the whole output are
+    checked against the identity  1^T (D^-1 A X) = sum_u (sum_{v: u->v} 1/deg(v)) X[u,:], which
+    holds at any size and involves every edge."""
+    from oracle import gnn as ognn
+    src, dst = synth.rmat_graph(scale, E, seed=seed, n_nodes=n, device=DEV, chunk=1 << 28)
+    part = g.grp_partition_from_local_coo(src, dst, n)
+    assert part.n == n and part.nnz == E
+    x = synth.normal_matrix(n, F, seed, device=DEV)
+    if bf16:
+        x = synth.to_bf16_rne(x)
+    y = torch.empty(n, F, device=DEV)
+    pick = (synth.stream_bits(seed, 21, torch.arange(n_sample, dtype=torch.int64)) >> 1) % n
+    pick = torch.unique(pick).to(DEV)
+    for transposed in (False, True):
+        a, b = (dst, src) if transposed else (src, dst)       # row owner = b, neighbour = a
+        y.fill_(float("nan"))
+        g.grp_spmm(part, transposed, g.SCALE_MEAN, False, F, x, F, g.DTYPE_BF16 if bf16 else g.DTYPE_FP32, y, F)
+        torch.cuda.synchronize()
+        # (a) sampled rows, exact
+        sel = torch.isin(b, pick)
+        e_row, e_nb = b[sel], a[sel]
+        nbs, inv = torch.unique(e_nb, return_inverse=True)
+        rows, rinv = torch.unique(torch.cat([pick, e_row]), return_inverse=True)     # = pick, sorted
+        blk = dict(n_dst=int(rows.numel()), n_src=int(nbs.numel()), esrc=inv.cpu().numpy(),
+                   edst=rinv[pick.numel():].cpu().numpy())
+        xn = x[nbs].cpu().double().numpy()
+        deg = np.bincount(blk["edst"], minlength=blk["n_dst"]).astype(np.float64)
+        want = ognn._scatter_rows(blk["n_dst"], blk["edst"], xn[blk["esrc"]]) / np.maximum(deg, 1.0)[:, None]
+        got = y[rows].cpu().double().numpy()
+        scale_ref = max(np.abs(want).max(), 1e-30)
+        err = np.abs(got - want).max() / scale_ref
+        print(f"[case] transposed={transposed} sampled rows {rows.numel()} (max degree {int(deg.max())}, "
+              f"{int((deg == 0).sum())} empty) rel err {err:.2e}", flush=True)
+        assert err <= TOL_FP32
+        # (b) column checksum over every edge, in float64
+        degb = torch.bincount(b, minlength=n).to(torch.float64)
+        w = torch.zeros(n, dtype=torch.float64, device=DEV).index_add_(0, a, 1.0 / degb[b])
+        lhs = y.sum(dim=0, dtype=torch.float64)
+        rhs = torch.zeros(F, dtype=torch.float64, device=DEV)
+        step = 1 << 20
+        for lo in range(0, n, step):                       # chunked: keeps the float64 copy of X small
+            rhs += (w[lo:lo + step, None] * x[lo:lo + step].to(torch.float64)).sum(dim=0)
+        cerr = float((lhs - rhs).abs().max() / rhs.abs().max())
+        print(f"[case] transposed={transposed} checksum rel err {cerr:.2e}", flush=True)
+        assert cerr <= TOL_FP32
+        assert not torch.isnan(y).any()
+    part.destroy()
+
+
+def test_config4_spmm_full_size():
+    import paper_2602_01872_amd as g
+    g.load()
+    print("[case] configuration 4 SpMM full size (n=2^22, 1e8 edges, F=256 fp32)", flush=True)
+    _sampled_rows_and_checksum(g, 22, 1 << 22, 100_000_000, 2602018724, 256, False)
+
+
+def test_config5_spmm_quarter_size():
+    import paper_2602_01872_amd as g
+    g.load()
+    print("[case] configuration 5 SpMM at a quarter of its edges (n=2^24, 2^30 edges, F=64 bf16)", flush=True)
+    _sampled_rows_and_checksum(g, 24, 1 << 24, 1 << 30, 2602018725, 64, True)
