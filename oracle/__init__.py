@@ -18,6 +18,9 @@ Modules
                "Coverage-Corrected Aggregation"; the phase-parallel algorithm)
     sampling   isolated k-hop neighbour sampling inside the local subgraph
     step       glue: one partition's train step -> flat gradient + coverage statistics
+    chunks     chunks, base + swept partitions, the sweep schedule and the switching
+               controller                                                      (paragraph
+               "Chunks and Efficient Partition Construction"; the controller subsection)
     optim      optimizer step (Adam / SGD) and the phase-parallel epoch loop          (the
                phase-parallel algorithm)
 

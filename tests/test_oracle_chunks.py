@@ -1,0 +1,101 @@
+"""Pins for oracle.chunks: brute-force construction on tiny graphs, reduction to the plain
+hash partition (already pinned) when the swept chunk is the base chunk, the whole graph when
+two chunks are combined out of two, the coverage guarantee (every cross-chunk edge co-resides
+in some partition of the cycle), the in-degree accounting identity over a cycle, and the
+controller's schedule."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import chunks, graph
+
+KEYS = ("l2g", "rowptr", "col", "colptr", "row", "d_local_in", "d_local_out", "d_global_in")
+
+
+def _graph(N=300, E=3000, seed=5):
+    s, d = synth.uniform_graph(N, E, seed=seed)
+    return s.numpy(), d.numpy()
+
+
+@pytest.mark.parametrize("c", [1, 2, 3, 5])
+def test_swept_equal_base_is_the_plain_hash_partition(c):
+    s, d = _graph()
+    for b in range(c):
+        a = chunks.partition_from_chunks(s, d, 300, c, 7, b, b)
+        want = graph.partition(s, d, 300, c, 7, b)
+        for k in KEYS:
+            assert np.array_equal(a[k], want[k]), k
+        assert a["base_mask"].all()
+
+
+def test_two_of_two_chunks_is_the_whole_graph():
+    s, d = _graph()
+    a = chunks.partition_from_chunks(s, d, 300, 2, 3, 0, 1)
+    whole = graph.partition(s, d, 300, 1, 0, 0)
+    for k in KEYS:
+        assert np.array_equal(a[k], whole[k]), k
+    assert np.array_equal(a["d_local_in"], a["d_global_in"])
+    assert np.array_equal(a["base_mask"], (chunks.chunk_of(300, 2, 3) == 0).astype(np.uint8))
+
+
+def test_brute_force_tiny():
+    rng = np.random.default_rng(1)
+    N, E, c = 23, 90, 4
+    s, d = rng.integers(0, N, E), rng.integers(0, N, E)
+    ch = chunks.chunk_of(N, c, 11)
+    for base, swept in ((0, 1), (2, 0), (3, 3)):
+        p = chunks.partition_from_chunks(s, d, N, c, 11, base, swept)
+        nodes = [v for v in range(N) if ch[v] in (base, swept)]
+        assert list(p["l2g"]) == nodes
+        loc = {v: i for i, v in enumerate(nodes)}
+        rows = [[] for _ in nodes]
+        for u, v in zip(s, d):
+            if u in loc and v in loc:
+                rows[loc[v]].append(loc[u])
+        col = [x for r in rows for x in sorted(r)]
+        assert list(p["col"]) == col
+        assert list(np.diff(p["rowptr"])) == [len(r) for r in rows]
+        assert list(p["d_global_in"]) == [int((d == v).sum()) for v in nodes]
+        assert list(p["base_mask"]) == [1 if ch[v] == base else 0 for v in nodes]
+
+
+@pytest.mark.parametrize("c", [2, 3, 4, 6])
+def test_coverage_guarantee_and_degree_accounting(c):
+    s, d = _graph(N=240, E=2600, seed=9)
+    N = 240
+    ch = chunks.chunk_of(N, c, 2)
+    sched = chunks.sweep_schedule(c)
+    assert len(sched) == c - 1
+    seen = np.zeros(s.size, dtype=bool)
+    base_only = {b: chunks.partition_from_chunks(s, d, N, c, 2, b, b) for b in range(c)}
+    gained = {b: np.zeros(base_only[b]["n"], dtype=np.int64) for b in range(c)}
+    for pairs in sched:
+        assert sorted(b for b, _ in pairs) == list(range(c))
+        assert sorted(w for _, w in pairs) == list(range(c))           # every chunk is swept exactly once
+        assert all(b != w for b, w in pairs)
+        for b, w in pairs:
+            p = chunks.partition_from_chunks(s, d, N, c, 2, b, w)
+            seen |= np.isin(ch[s], (b, w)) & np.isin(ch[d], (b, w))
+            m = p["base_mask"].astype(bool)
+            # in-neighbours of the base nodes that arrived with the swept chunk
+            gained[b] += p["d_local_in"][m].astype(np.int64) - base_only[b]["d_local_in"]
+    assert seen.all()                                                  # every edge co-resides somewhere
+    for b in range(c):
+        # over a cycle a base node meets each of its in-neighbours exactly once
+        np.testing.assert_array_equal(base_only[b]["d_local_in"] + gained[b], base_only[b]["d_global_in"])
+
+
+def test_controller_schedule():
+    ctl = chunks.Controller(total_epochs=12, n_chunks=4)
+    assert ctl.epochs_per_super_epoch == 4
+    switches = [ctl.end_epoch() for _ in range(12)]
+    assert switches == [False, False, False, True] * 3
+    assert ctl.super_epoch == 3
+    assert ctl.pairs() == chunks.sweep_schedule(4)[0]                  # the cycle repeats
+    # early switch: the deficit stays above the threshold for `patience` steps
+    ctl = chunks.Controller(total_epochs=100, n_chunks=3, threshold=0.4, patience=3)
+    ctl.observe_step([0.5, 0.5]); ctl.observe_step([0.5]); assert not ctl.end_epoch()
+    ctl.observe_step([0.7])                                            # deficit 0.3: streak broken
+    ctl.observe_step([0.5]); ctl.observe_step([0.5]); assert not ctl.end_epoch()
+    ctl.observe_step([0.2]); assert ctl.end_epoch()
+    assert ctl.super_epoch == 1 and ctl.pairs() == chunks.sweep_schedule(3)[1]
