@@ -82,6 +82,35 @@ grp_status grp_partition(const int64_t* src, const int64_t* dst, int64_t E, int6
                          int32_t K, uint64_t seed, int32_t part_id, void* stream,
                          grp_partition_t** out);
 
+/* ------------------------------------------------------------------ chunks and sweeping partitions */
+
+typedef struct grp_chunks_s grp_chunks_t;
+
+/* The graph split once into chunks ("Chunks and Efficient Partition Construction"):
+ *   chunk(v) = owner(v) of grp_partition with K = n_chunks (a random split).
+ * The handle keeps a copy of the edge list grouped by (chunk(dst), chunk(src)) and every
+ * node's global in-degree, so that a partition is later built from its own edges only.
+ * src/dst: DEV int64[E] global ids.  1 <= n_chunks <= 64.  Synchronous.
+ * Errors: GRP_EINVAL, GRP_ERANGE (an id outside [0,N)), GRP_ENOMEM, GRP_EHIP.              */
+grp_status grp_chunks_build(const int64_t* src, const int64_t* dst, int64_t E, int64_t N,
+                            int32_t n_chunks, uint64_t seed, void* stream, grp_chunks_t** out);
+grp_status grp_chunks_destroy(grp_chunks_t* chunks);
+
+/* The training partition of a super-epoch: base chunk + swept chunk (swept == base: the base
+ * chunk alone, which is grp_partition's partition `base` of K = n_chunks).  Nodes = the union
+ * of the two chunks in ascending global id; edges = those with both endpoints in the union;
+ * d_global_in = in-degree in the whole graph.  Same canonical CSR/CSC and the same handle as
+ * grp_partition; only the edges of the four chunk pairs involved are read.  Worker i sweeps
+ * chunk (i + 1 + t) mod n_chunks in super-epoch t (coverage guarantee paragraph: after
+ * n_chunks - 1 super-epochs every pair of chunks has shared a partition).  Synchronous.     */
+grp_status grp_partition_from_chunks(const grp_chunks_t* chunks, int32_t base, int32_t swept,
+                                     void* stream, grp_partition_t** out);
+
+/* DEV uint8[n]: 1 for the nodes of the base chunk (a partition's loss nodes are the training
+ * nodes of its base chunk; the swept chunk only supplies neighbours).  *mask is NULL for
+ * partitions not built from chunks.  Borrowed pointer, valid until the handle is destroyed. */
+grp_status grp_partition_base_mask(const grp_partition_t* part, const uint8_t** mask);
+
 /* Adopt a partition's share that was generated directly as local edges.
  * src_local/dst_local: DEV int64[E] ids in [0,n).  d_global_in: DEV int64[n] or NULL
  * (= local in-degree, i.e. full coverage).  l2g: DEV int64[n] or NULL (= identity).

@@ -68,6 +68,10 @@ def load() -> C.CDLL:
         "grp_partition": [vp, vp, i64, i64, i32, u64, i32, vp, C.POINTER(vp)],
         "grp_partition_from_local_coo": [vp, vp, i64, i64, vp, vp, vp, C.POINTER(vp)],
         "grp_partition_view": [vp, C.POINTER(PartitionView)],
+        "grp_chunks_build": [vp, vp, i64, i64, i32, u64, vp, C.POINTER(vp)],
+        "grp_chunks_destroy": [vp],
+        "grp_partition_from_chunks": [vp, i32, i32, vp, C.POINTER(vp)],
+        "grp_partition_base_mask": [vp, C.POINTER(vp)],
         "grp_partition_destroy": [vp],
         "grp_step_workspace_bytes": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), C.POINTER(sz)],
         "grp_train_step": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), vp, vp, vp, vp, vp, sz, vp, vp, vp],
@@ -159,6 +163,23 @@ class Partition:
             _hip_memcpy_d2h(out, getattr(self.view, name))
         return out
 
+    def base_mask_ptr(self) -> int:
+        """Device address of the uint8[n] base-chunk mask (0 for partitions not built from chunks)."""
+        out = C.c_void_p()
+        _check(load().grp_partition_base_mask(self.handle, C.byref(out)))
+        return out.value or 0
+
+    def base_mask(self) -> np.ndarray:
+        """Host copy of the base-chunk mask (for tests)."""
+        out = np.empty(self.n, dtype=np.uint8)
+        p = self.base_mask_ptr()
+        if not p:
+            raise ValueError("this partition was not built from chunks")
+        if self.n:
+            torch.cuda.synchronize()
+            _hip_memcpy_d2h(out, p)
+        return out
+
     def destroy(self):
         if self.handle:
             _check(load().grp_partition_destroy(self.handle))
@@ -198,6 +219,37 @@ def grp_partition_from_local_coo(src_local, dst_local, n: int, d_global_in=None,
     E = 0 if src_local is None else int(src_local.numel())
     _check(load().grp_partition_from_local_coo(_ptr(src_local), _ptr(dst_local), E, n, _ptr(d_global_in), _ptr(l2g),
                                                _stream(stream), C.byref(out)))
+    return Partition(out.value)
+
+
+class Chunks:
+    """Owns a grp_chunks_t handle (the graph split once into chunks)."""
+
+    def __init__(self, handle: int, n_chunks: int):
+        self.handle, self.n_chunks = handle, n_chunks
+
+    def destroy(self):
+        if self.handle:
+            _check(load().grp_chunks_destroy(self.handle))
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def grp_chunks_build(src, dst, n_nodes: int, n_chunks: int, seed: int, stream=None) -> Chunks:
+    out = C.c_void_p()
+    E = 0 if src is None else int(src.numel())
+    _check(load().grp_chunks_build(_ptr(src), _ptr(dst), E, n_nodes, n_chunks, seed, _stream(stream), C.byref(out)))
+    return Chunks(out.value, n_chunks)
+
+
+def grp_partition_from_chunks(chunks: Chunks, base: int, swept: int, stream=None) -> Partition:
+    out = C.c_void_p()
+    _check(load().grp_partition_from_chunks(chunks.handle, base, swept, _stream(stream), C.byref(out)))
     return Partition(out.value)
 
 
@@ -285,6 +337,7 @@ def read_stats(stats: torch.Tensor) -> np.ndarray:
 
 def exported_symbols():
     return ["grp_last_error", "grp_partition", "grp_partition_from_local_coo", "grp_partition_view",
-            "grp_partition_destroy", "grp_param_count", "grp_step_workspace_bytes", "grp_train_step",
+            "grp_partition_destroy", "grp_chunks_build", "grp_chunks_destroy", "grp_partition_from_chunks",
+            "grp_partition_base_mask", "grp_param_count", "grp_step_workspace_bytes", "grp_train_step",
             "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
             "grp_profile_enable", "grp_profile_report"]

@@ -2,6 +2,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <vector>
 #include <hip/hip_bf16.h>
 
 #include <cstdarg>
@@ -88,6 +90,20 @@ struct grp_partition_s {
     int32_t* d_local_in = nullptr;
     int32_t* d_local_out = nullptr;
     int64_t* d_global_in = nullptr;
+    uint8_t* base_mask = nullptr;    // partitions built from chunks: 1 for the base chunk's nodes
+    int device = 0;
+};
+
+// The graph split once into chunks: edges grouped by (chunk(dst), chunk(src)) so that the
+// partition base + swept reads only its four groups, and the global in-degree of every node.
+struct grp_chunks_s {
+    int32_t n_chunks = 0;
+    uint64_t seed = 0;
+    int64_t N = 0, E = 0;
+    int64_t* src = nullptr;          // [E] global ids, grouped by bucket (order inside a bucket arbitrary)
+    int64_t* dst = nullptr;
+    int64_t* d_global_all = nullptr; // [N]
+    std::vector<int64_t> bucket_ptr; // host, [n_chunks^2 + 1], bucket = chunk(dst) * n_chunks + chunk(src)
     int device = 0;
 };
 

@@ -151,7 +151,7 @@ static void free_partition(grp_partition_t* h) {
     void* ptrs[] = {h->l2g, h->rowptr, h->col, h->colptr, h->row, h->d_local_in, h->d_local_out, h->d_global_in,
                     h->csr_long.long_row, h->csr_long.long_first, h->csr_long.chunk_begin, h->csr_long.chunk_end,
                     h->csc_long.long_row, h->csc_long.long_first, h->csc_long.chunk_begin, h->csc_long.chunk_end,
-                    h->spmm_scratch};
+                    h->spmm_scratch, h->base_mask};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
     delete h;
@@ -307,7 +307,253 @@ static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t
     return build_csr_csc(h, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), st);
 }
 
+// ------------------------------------------------------------------ chunks
+constexpr int MAX_CHUNKS = 64;        // n_chunks^2 bucket counters must fit a workgroup's LDS
+
+__device__ __forceinline__ uint32_t chunk_of(uint64_t seed, int64_t v, uint32_t c) {
+    return (uint32_t)(splitmix64_output(seed, (uint64_t)v) % c);
+}
+
+// Pass 1: range check, global in-degrees, size of every (chunk(dst), chunk(src)) bucket.
+__global__ __launch_bounds__(256) void chunk_count_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                          int64_t E, int64_t N, uint32_t c, uint64_t seed,
+                                                          unsigned long long* __restrict__ dg,
+                                                          unsigned long long* __restrict__ bucket_count,
+                                                          unsigned long long* __restrict__ bad) {
+    extern __shared__ unsigned int hist[];            // c*c counters of this workgroup
+    for (int i = threadIdx.x; i < (int)(c * c); i += 256) hist[i] = 0;
+    __syncthreads();
+    unsigned long long nbad = 0;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
+        const int64_t u = src[e], v = dst[e];
+        if (u < 0 || v < 0 || u >= N || v >= N) { nbad++; continue; }
+        atomicAdd(&dg[v], 1ull);
+        atomicAdd(&hist[chunk_of(seed, v, c) * c + chunk_of(seed, u, c)], 1u);
+    }
+    if (nbad) atomicAdd(bad, nbad);
+    __syncthreads();
+    for (int i = threadIdx.x; i < (int)(c * c); i += 256)
+        if (hist[i]) atomicAdd(&bucket_count[i], (unsigned long long)hist[i]);
+}
+
+// Pass 2: every workgroup reserves a run in each bucket for the edges it holds, then writes
+// them (the order inside a bucket is arbitrary; partitions are sorted when they are built).
+__global__ __launch_bounds__(256) void chunk_scatter_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                            int64_t E, uint32_t c, uint64_t seed,
+                                                            unsigned long long* __restrict__ cursor,
+                                                            int64_t* __restrict__ out_src, int64_t* __restrict__ out_dst) {
+    extern __shared__ unsigned int lds_u32[];         // [0, c*c): counts, then run starts (low / high words)
+    unsigned int* cnt = lds_u32;
+    unsigned long long* start = (unsigned long long*)(lds_u32 + ((c * c + 1) & ~1u));
+    const int64_t per = (E + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = (int64_t)blockIdx.x * per, hi = lo + per < E ? lo + per : E;
+    for (int i = threadIdx.x; i < (int)(c * c); i += 256) cnt[i] = 0;
+    __syncthreads();
+    for (int64_t e = lo + threadIdx.x; e < hi; e += 256)
+        atomicAdd(&cnt[chunk_of(seed, dst[e], c) * c + chunk_of(seed, src[e], c)], 1u);
+    __syncthreads();
+    for (int i = threadIdx.x; i < (int)(c * c); i += 256) {
+        start[i] = cnt[i] ? atomicAdd(&cursor[i], (unsigned long long)cnt[i]) : 0ull;
+        cnt[i] = 0;
+    }
+    __syncthreads();
+    for (int64_t e = lo + threadIdx.x; e < hi; e += 256) {
+        const int64_t u = src[e], v = dst[e];
+        const uint32_t b = chunk_of(seed, v, c) * c + chunk_of(seed, u, c);
+        const unsigned long long slot = start[b] + atomicAdd(&cnt[b], 1u);
+        out_src[slot] = u;
+        out_dst[slot] = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void pair_flag_kernel(int64_t N, uint32_t c, uint64_t seed, uint32_t base, uint32_t swept,
+                                                        int32_t* __restrict__ flag) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v < N) {
+        const uint32_t ch = chunk_of(seed, v, c);
+        flag[v] = (ch == base || ch == swept) ? 1 : 0;
+    }
+}
+
+__global__ __launch_bounds__(256) void pair_nodes_kernel(int64_t N, uint32_t c, uint64_t seed, uint32_t base,
+                                                         const int32_t* __restrict__ flag, const int64_t* __restrict__ pos,
+                                                         const int64_t* __restrict__ dg_all, int64_t* __restrict__ l2g,
+                                                         int64_t* __restrict__ dg, uint8_t* __restrict__ base_mask) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v < N && flag[v]) {
+        const int64_t i = pos[v];
+        l2g[i] = v;
+        dg[i] = dg_all[v];
+        base_mask[i] = chunk_of(seed, v, c) == base ? 1 : 0;
+    }
+}
+
+// Keys of one bucket's edges (both endpoints are members by construction).
+__global__ __launch_bounds__(256) void bucket_keys_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                          int64_t count, const int64_t* __restrict__ pos,
+                                                          uint64_t* __restrict__ keys) {
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (int64_t)gridDim.x * 256)
+        keys[e] = ((uint64_t)pos[dst[e]] << 32) | (uint64_t)pos[src[e]];
+}
+
+static void free_chunks(grp_chunks_t* h) {
+    if (!h) return;
+    for (void* q : {(void*)h->src, (void*)h->dst, (void*)h->d_global_all})
+        if (q) (void)hipFree(q);
+    delete h;
+}
+
+static grp_status chunks_impl(const int64_t* src, const int64_t* dst, int64_t E, int64_t N, int32_t c, uint64_t seed,
+                              hipStream_t st, grp_chunks_t* h) {
+    const int nb = c * c;
+    h->n_chunks = c; h->seed = seed; h->N = N; h->E = E;
+    h->bucket_ptr.assign((size_t)nb + 1, 0);
+    GRP_TRY(halloc(&h->src, E));
+    GRP_TRY(halloc(&h->dst, E));
+    GRP_TRY(halloc(&h->d_global_all, N));
+    GRP_HIP(hipMemsetAsync(h->d_global_all, 0, (size_t)(N > 0 ? N : 1) * sizeof(int64_t), st));
+    DevBuf counters;                                   // [0, nb): counts then cursors; [nb]: bad ids
+    GRP_TRY(counters.alloc((size_t)(nb + 1) * sizeof(unsigned long long)));
+    GRP_HIP(hipMemsetAsync(counters.p, 0, (size_t)(nb + 1) * sizeof(unsigned long long), st));
+    if (E == 0) { GRP_HIP(hipStreamSynchronize(st)); return GRP_OK; }
+    const unsigned grid = grid_for(E) > 2048 ? 2048 : grid_for(E);
+    hipLaunchKernelGGL(chunk_count_kernel, dim3(grid), dim3(256), (size_t)nb * sizeof(unsigned int), st, src, dst, E, N,
+                       (uint32_t)c, seed, (unsigned long long*)h->d_global_all, counters.as<unsigned long long>(),
+                       counters.as<unsigned long long>() + nb);
+    GRP_LAUNCH_CHECK();
+    std::vector<unsigned long long> host((size_t)nb + 1);
+    GRP_HIP(hipMemcpyAsync(host.data(), counters.p, host.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+    GRP_HIP(hipStreamSynchronize(st));
+    if (host[nb] != 0) return fail(GRP_ERANGE, "%llu edges have an endpoint outside [0, %lld)", host[nb], (long long)N);
+    for (int b = 0; b < nb; ++b) h->bucket_ptr[b + 1] = h->bucket_ptr[b] + (int64_t)host[b];
+    std::vector<unsigned long long> cur((size_t)nb);
+    for (int b = 0; b < nb; ++b) cur[b] = (unsigned long long)h->bucket_ptr[b];
+    GRP_HIP(hipMemcpyAsync(counters.p, cur.data(), cur.size() * sizeof(unsigned long long), hipMemcpyHostToDevice, st));
+    const size_t lds = (size_t)((nb + 1) & ~1) * sizeof(unsigned int) + (size_t)nb * sizeof(unsigned long long);
+    hipLaunchKernelGGL(chunk_scatter_kernel, dim3(grid), dim3(256), lds, st, src, dst, E, (uint32_t)c, seed,
+                       counters.as<unsigned long long>(), h->src, h->dst);
+    GRP_LAUNCH_CHECK();
+    GRP_HIP(hipStreamSynchronize(st));
+    return GRP_OK;
+}
+
+static grp_status pair_partition_impl(const grp_chunks_t* ck, int32_t base, int32_t swept, hipStream_t st,
+                                      grp_partition_t* h) {
+    const int64_t N = ck->N;
+    const int c = ck->n_chunks;
+    DevBuf flag, pos, scan_tmp;
+    GRP_TRY(flag.alloc((size_t)N * sizeof(int32_t)));
+    GRP_TRY(pos.alloc((size_t)N * sizeof(int64_t)));
+    int64_t n = 0;
+    if (N > 0) {
+        hipLaunchKernelGGL(pair_flag_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, N, (uint32_t)c, ck->seed,
+                           (uint32_t)base, (uint32_t)swept, flag.as<int32_t>());
+        GRP_LAUNCH_CHECK();
+        size_t bytes = 0;
+        GRP_HIP(rocprim::exclusive_scan(nullptr, bytes, flag.as<int32_t>(), pos.as<int64_t>(), (int64_t)0, (size_t)N,
+                                        rocprim::plus<int64_t>(), st));
+        GRP_TRY(scan_tmp.alloc(bytes));
+        GRP_HIP(rocprim::exclusive_scan(scan_tmp.p, bytes, flag.as<int32_t>(), pos.as<int64_t>(), (int64_t)0, (size_t)N,
+                                        rocprim::plus<int64_t>(), st));
+        int64_t last_pos = 0;
+        int32_t last_flag = 0;
+        GRP_HIP(hipMemcpyAsync(&last_pos, pos.as<int64_t>() + (N - 1), sizeof(int64_t), hipMemcpyDeviceToHost, st));
+        GRP_HIP(hipMemcpyAsync(&last_flag, flag.as<int32_t>() + (N - 1), sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        GRP_HIP(hipStreamSynchronize(st));
+        n = last_pos + last_flag;
+    }
+    if (n >= ((int64_t)1 << 31)) return fail(GRP_ERANGE, "partition has %lld >= 2^31 local nodes", (long long)n);
+    h->n = n;
+    GRP_TRY(halloc(&h->l2g, n));
+    GRP_TRY(halloc(&h->d_global_in, n));
+    GRP_TRY(halloc(&h->base_mask, n));
+    if (N > 0) {
+        hipLaunchKernelGGL(pair_nodes_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, N, (uint32_t)c, ck->seed,
+                           (uint32_t)base, flag.as<int32_t>(), pos.as<int64_t>(), ck->d_global_all, h->l2g, h->d_global_in,
+                           h->base_mask);
+        GRP_LAUNCH_CHECK();
+    }
+    // the partition's edges are exactly the buckets (x, y) with x, y in {base, swept}
+    int chunks2[2] = {base, swept};
+    const int nc = base == swept ? 1 : 2;
+    int64_t nnz = 0;
+    for (int a = 0; a < nc; ++a)
+        for (int b = 0; b < nc; ++b) {
+            const int bk = chunks2[a] * c + chunks2[b];
+            nnz += ck->bucket_ptr[bk + 1] - ck->bucket_ptr[bk];
+        }
+    h->nnz = nnz;
+    DevBuf keys, keys_alt;
+    GRP_TRY(keys.alloc((size_t)nnz * sizeof(uint64_t)));
+    GRP_TRY(keys_alt.alloc((size_t)nnz * sizeof(uint64_t)));
+    int64_t off = 0;
+    for (int a = 0; a < nc; ++a)
+        for (int b = 0; b < nc; ++b) {
+            const int bk = chunks2[a] * c + chunks2[b];
+            const int64_t lo = ck->bucket_ptr[bk], cnt = ck->bucket_ptr[bk + 1] - lo;
+            if (cnt > 0) {
+                hipLaunchKernelGGL(bucket_keys_kernel, dim3(grid_for(cnt)), dim3(256), 0, st, ck->src + lo, ck->dst + lo, cnt,
+                                   pos.as<int64_t>(), keys.as<uint64_t>() + off);
+                GRP_LAUNCH_CHECK();
+            }
+            off += cnt;
+        }
+    return build_csr_csc(h, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), st);
+}
+
 }  // namespace grp
+
+extern "C" grp_status grp_chunks_build(const int64_t* src, const int64_t* dst, int64_t E, int64_t N, int32_t n_chunks,
+                                       uint64_t seed, void* stream, grp_chunks_t** out) {
+    using namespace grp;
+    if (!out) return fail(GRP_EINVAL, "grp_chunks_build: out is null");
+    *out = nullptr;
+    if (E < 0 || N < 0) return fail(GRP_EINVAL, "grp_chunks_build: negative size");
+    if (E > 0 && (!src || !dst)) return fail(GRP_EINVAL, "grp_chunks_build: null edge arrays");
+    if (n_chunks < 1 || n_chunks > MAX_CHUNKS)
+        return fail(GRP_EINVAL, "grp_chunks_build: n_chunks = %d outside [1, %d]", n_chunks, MAX_CHUNKS);
+    grp_chunks_t* h = new (std::nothrow) grp_chunks_t();
+    if (!h) return fail(GRP_ENOMEM, "grp_chunks_build: host allocation failed");
+    (void)hipGetDevice(&h->device);
+    const grp_status s = chunks_impl(src, dst, E, N, n_chunks, seed, (hipStream_t)stream, h);
+    if (s != GRP_OK) {
+        free_chunks(h);
+        return s;
+    }
+    *out = h;
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_chunks_destroy(grp_chunks_t* chunks) {
+    grp::free_chunks(chunks);
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_partition_from_chunks(const grp_chunks_t* chunks, int32_t base, int32_t swept, void* stream,
+                                                grp_partition_t** out) {
+    using namespace grp;
+    if (!out) return fail(GRP_EINVAL, "grp_partition_from_chunks: out is null");
+    *out = nullptr;
+    if (!chunks) return fail(GRP_EINVAL, "grp_partition_from_chunks: chunks is null");
+    if (base < 0 || base >= chunks->n_chunks || swept < 0 || swept >= chunks->n_chunks)
+        return fail(GRP_EINVAL, "grp_partition_from_chunks: chunk ids (%d, %d) outside [0, %d)", base, swept, chunks->n_chunks);
+    grp_partition_t* h = new (std::nothrow) grp_partition_t();
+    if (!h) return fail(GRP_ENOMEM, "grp_partition_from_chunks: host allocation failed");
+    (void)hipGetDevice(&h->device);
+    const grp_status s = pair_partition_impl(chunks, base, swept, (hipStream_t)stream, h);
+    if (s != GRP_OK) {
+        free_partition(h);
+        return s;
+    }
+    *out = h;
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_partition_base_mask(const grp_partition_t* part, const uint8_t** mask) {
+    if (!part || !mask) return grp::fail(GRP_EINVAL, "grp_partition_base_mask: null argument");
+    *mask = part->base_mask;
+    return GRP_OK;
+}
 
 extern "C" grp_status grp_partition(const int64_t* src, const int64_t* dst, int64_t E, int64_t N, int32_t K, uint64_t seed,
                                     int32_t part_id, void* stream, grp_partition_t** out) {

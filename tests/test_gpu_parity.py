@@ -565,3 +565,42 @@ def test_phase_parallel_loop_matches_oracle(g, M, kind):
         assert np.mean(np.abs(got - want) < 1e-3 * lr * steps) > 0.99   # and almost all agree closely
     for p in parts:
         p.destroy()
+
+
+# ------------------------------------------------------------------ chunks and sweeping partitions
+@pytest.mark.gpu
+@pytest.mark.parametrize("kind,N,E,c", [("uniform", 3000, 40000, 4), ("rmat", 1 << 12, 150000, 3), ("uniform", 500, 0, 2),
+                                         ("uniform", 2000, 30000, 1), ("rmat", 1 << 13, 300000, 8)])
+def test_partition_from_chunks_bit_exact(g, kind, N, E, c):
+    from oracle import chunks as ochunks
+    _note(f"chunks {kind} N={N} E={E} c={c}")
+    if E == 0:
+        s = d = torch.zeros(0, dtype=torch.int64)
+    elif kind == "uniform":
+        s, d = synth.uniform_graph(N, E, seed=41)
+    else:
+        s, d = synth.rmat_graph(int(np.log2(N)), E, seed=41)
+    ck = g.grp_chunks_build(s.to(DEV), d.to(DEV), N, c, 13)
+    sched = ochunks.sweep_schedule(c)
+    pairs = [(b, b) for b in range(c)] + [p for t in (0, len(sched) - 1) for p in sched[t]][:2 * c]
+    for base, swept in pairs:
+        part = g.grp_partition_from_chunks(ck, base, swept)
+        want = ochunks.partition_from_chunks(s.numpy(), d.numpy(), N, c, 13, base, swept)
+        _assert_partition_equal(part, want)
+        assert np.array_equal(part.base_mask(), want["base_mask"])
+        part.destroy()
+    # the base chunk alone is the plain hash partition
+    part = g.grp_partition_from_chunks(ck, 0, 0)
+    plain = g.grp_partition(s.to(DEV), d.to(DEV), N, c, 13, 0)
+    for k in PART_KEYS:
+        assert np.array_equal(part.array(k), plain.array(k)), k
+    assert plain.base_mask_ptr() == 0
+    with pytest.raises(g.GrappaError):
+        g.grp_partition_from_chunks(ck, c, 0)
+    with pytest.raises(g.GrappaError):
+        g.grp_chunks_build(s.to(DEV), d.to(DEV), N, 65, 13)
+    if E:
+        bad = s.clone(); bad[0] = N
+        with pytest.raises(g.GrappaError):
+            g.grp_chunks_build(bad.to(DEV), d.to(DEV), N, c, 13)
+    part.destroy(); plain.destroy(); ck.destroy()
