@@ -12,7 +12,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import coverage, step
+from . import chunks, coverage, step
 
 SGD, ADAM = 0, 1
 
@@ -75,3 +75,52 @@ def train_epochs(parts, arch, dims, theta0, xs, ys, masks, n_epochs, max_active,
                 theta = sgd_step(theta, G, lr)
             history.append(float(np.mean([s["loss"] for s in stats])))
     return theta, history
+
+
+def train_sweeping(src, dst, n_nodes, n_chunks, chunk_seed, arch, dims, theta0, x, y, train_mask, total_epochs,
+                   max_active, estimator, optimizer=ADAM, lr=0.003, controller=None, gcn_self_loops=True):
+    """The phase-parallel algorithm over sweeping partitions (chunks + controller).
+
+    The graph (global edge list ``src -> dst``, features ``x[n_nodes, F]``, labels ``y``, optional
+    uint8 ``train_mask``) is split once into ``n_chunks`` chunks; worker i trains the partition
+    base chunk i + the chunk swept in the current super-epoch, with the training nodes of its
+    base chunk as loss nodes.  After every epoch the controller decides whether the next
+    super-epoch starts (partitions are then rebuilt from the chunks).  Returns
+    (theta, history, switches) with history the mean active loss per optimizer step and
+    switches the list of epochs (0-based) after which the partitions were switched.
+    """
+    ctl = controller if controller is not None else chunks.Controller(total_epochs, n_chunks)
+    x = np.asarray(x, dtype=np.float64)
+    y = np.asarray(y)
+    tm = np.ones(n_nodes, dtype=np.uint8) if train_mask is None else np.asarray(train_mask, dtype=np.uint8)
+    theta = np.asarray(theta0, dtype=np.float64).copy()
+    m = np.zeros_like(theta)
+    v = np.zeros_like(theta)
+    t = 0
+    history, switches = [], []
+    parts = None
+    for epoch in range(total_epochs):
+        if parts is None:
+            parts = [chunks.partition_from_chunks(src, dst, n_nodes, n_chunks, chunk_seed, b, w) for b, w in ctl.pairs()]
+            xs = [x[p["l2g"]] for p in parts]
+            ys = [y[p["l2g"]] for p in parts]
+            masks = [p["base_mask"] & tm[p["l2g"]] for p in parts]
+        for active in phase_schedule(len(parts), max_active):
+            grads, stats = [], []
+            for p in active:
+                g, st = step.train_step(parts[p], arch, dims, theta, xs[p], ys[p], masks[p], estimator=estimator,
+                                        gcn_self_loops=gcn_self_loops)
+                grads.append(g)
+                stats.append(st)
+            G, _ = coverage.aggregate(grads, stats, estimator)
+            t += 1
+            if optimizer == ADAM:
+                theta, m, v = adam_step(theta, G, m, v, t, lr)
+            else:
+                theta = sgd_step(theta, G, lr)
+            history.append(float(np.mean([s["loss"] for s in stats])))
+            ctl.observe_step([coverage.factor(s, coverage.BATCH_MIN_DIST) for s in stats])
+        if ctl.end_epoch():
+            switches.append(epoch)
+            parts = None
+    return theta, history, switches

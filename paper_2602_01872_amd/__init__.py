@@ -6,4 +6,5 @@ marshals arguments: device memory comes from torch tensors (``data_ptr()``), str
 There is no CPU fallback: importing ``binding`` without the built library raises.
 """
 from .binding import *  # noqa: F401,F403
-from .loop import PhaseParallelTrainer  # noqa: F401
+from .controller import Controller, sweep_pairs  # noqa: F401
+from .loop import PhaseParallelTrainer, SweepingTrainer  # noqa: F401

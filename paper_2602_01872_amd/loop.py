@@ -9,6 +9,7 @@ from __future__ import annotations
 import torch
 
 from . import binding as g
+from .controller import Controller
 
 
 class PhaseParallelTrainer:
@@ -59,3 +60,65 @@ class PhaseParallelTrainer:
     def losses(self):
         """Mean loss of the active partitions for every optimizer step so far (host floats)."""
         return [float(g.read_stats(h)["loss"].mean()) for h in self.history]
+
+
+class SweepingTrainer:
+    """Phase-parallel training over sweeping partitions: the graph is split once into chunks
+    (``grp_chunks_build``); every super-epoch each worker's partition base + swept chunk is
+    rebuilt on the GPU (``grp_partition_from_chunks``) and its rows of the global feature /
+    label / mask tensors are gathered by ``l2g``; the controller decides after each epoch
+    whether to switch.  theta and the optimizer state persist across super-epochs.
+    """
+
+    def __init__(self, src, dst, n_nodes, n_chunks, chunk_seed, model, x, y, train_mask, theta0, estimator,
+                 max_active, total_epochs, optimizer=None, controller=None):
+        self.chunks = g.grp_chunks_build(src, dst, n_nodes, n_chunks, chunk_seed)
+        self.model, self.x, self.y, self.train_mask = model, x, y, train_mask
+        self.estimator, self.max_active = estimator, max_active
+        self.opt = optimizer if optimizer is not None else g.optimizer_desc()
+        self.ctl = controller if controller is not None else Controller(total_epochs, n_chunks)
+        self.theta = theta0.detach().clone().to(torch.float32).contiguous()
+        P = g.grp_param_count(model)
+        self.m = torch.zeros(P, device=self.theta.device)
+        self.v = torch.zeros(P, device=self.theta.device)
+        self.step_count = 0
+        self.inner = None
+        self.switches = []
+        self.epoch = 0
+        self._losses = []
+
+    def _build(self):
+        parts, xs, ys, masks = [], [], [], []
+        for base, swept in self.ctl.pairs():
+            part = g.grp_partition_from_chunks(self.chunks, base, swept)
+            l2g = torch.from_numpy(part.array("l2g")).to(self.x.device)
+            mask = torch.from_numpy(part.base_mask()).to(self.x.device)
+            if self.train_mask is not None:
+                mask = mask & self.train_mask[l2g]
+            parts.append(part)
+            xs.append(self.x[l2g].contiguous())
+            ys.append(self.y[l2g].contiguous())
+            masks.append(mask.contiguous())
+        tr = PhaseParallelTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active, self.opt)
+        tr.theta, tr.m, tr.v, tr.step_count = self.theta, self.m, self.v, self.step_count   # carried state
+        return tr
+
+    def run_epoch(self):
+        if self.inner is None:
+            self.inner = self._build()
+        first = len(self.inner.history)
+        self.inner.run_epoch()
+        self.step_count = self.inner.step_count
+        for h in self.inner.history[first:]:
+            rec = g.read_stats(h)
+            self._losses.append(float(rec["loss"].mean()))
+            self.ctl.observe_step([float(r["sum_ratio"]) / int(r["S"]) if int(r["S"]) > 0 else 1.0 for r in rec])
+        if self.ctl.end_epoch():
+            self.switches.append(self.epoch)
+            for p in self.inner.parts:
+                p.destroy()
+            self.inner = None
+        self.epoch += 1
+
+    def losses(self):
+        return list(self._losses)

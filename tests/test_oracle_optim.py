@@ -110,3 +110,41 @@ def test_phase_order_state_is_carried():
     # M = K: one step with the plain average of the three gradients
     gs = [step.train_step(parts[p], "sage", dims, theta0, xs[p], ys[p])[0] for p in range(3)]
     np.testing.assert_allclose(a, theta0 - 0.1 * sum(gs) / 3, rtol=1e-13, atol=1e-15)
+
+
+def test_sweeping_with_two_chunks_is_the_whole_graph_with_split_loss_nodes():
+    # c = 2: both partitions are chunk 0 + chunk 1 = the whole graph (full coverage); they differ
+    # only in their loss nodes (their base chunk).  One phase, one epoch, SGD:
+    # theta1 = theta0 - lr * (g(S_0) + g(S_1)) / 2 with g(S) the whole-graph gradient of the mean loss over S.
+    from oracle import chunks
+    N = 150
+    s, d = synth.uniform_graph(N, 1200, seed=8)
+    s, d = s.numpy(), d.numpy()
+    dims = [5, 7, 3]
+    x = synth.normal_matrix(N, 5, 21)
+    y = synth.planted_labels(x, 3, 22).numpy()
+    x = x.double().numpy()
+    theta0 = synth.model_weights("sage", dims, 23).double().numpy()
+    for est in (cov.NONE, cov.BATCH_MIN_DIST, cov.SHRINKAGE):
+        th, hist, sw = optim.train_sweeping(s, d, N, 2, 4, "sage", dims, theta0, x, y, None, 1, 2, est,
+                                            optimizer=optim.SGD, lr=0.1)
+        whole = graph.partition(s, d, N, 1, 0, 0)
+        ch = chunks.chunk_of(N, 2, 4)
+        gs = [step.train_step(whole, "sage", dims, theta0, x, y, (ch == b).astype(np.uint8))[0] for b in (0, 1)]
+        np.testing.assert_allclose(th, theta0 - 0.1 * (gs[0] + gs[1]) / 2, rtol=1e-12, atol=1e-14)
+        assert sw == [0] and len(hist) == 1
+
+
+def test_sweeping_switches_and_learns():
+    N = 400
+    s, d = synth.uniform_graph(N, 4000, seed=8)
+    s, d = s.numpy(), d.numpy()
+    dims = [6, 12, 3]
+    x = synth.normal_matrix(N, 6, 21)
+    y = synth.planted_labels(x, 3, 22).numpy()
+    theta0 = synth.model_weights("sage", dims, 23).double().numpy()
+    th, hist, sw = optim.train_sweeping(s, d, N, 4, 4, "sage", dims, theta0, x.double().numpy(), y, None, 30, 2,
+                                        cov.BATCH_MIN_DIST, optimizer=optim.ADAM, lr=0.01)
+    assert sw == [9, 19, 29]                       # ceil(30 / 3) = 10 epochs per super-epoch
+    assert len(hist) == 30 * 2
+    assert np.mean(hist[-4:]) < 0.8 * np.mean(hist[:4])
