@@ -13,6 +13,8 @@ Modules
     gnn        GraphSAGE-mean / GCN / residual-GCN layers, weighted softmax
                cross-entropy and the hand-derived reverse pass                 (the
                model descriptions in the experimental setup; the true-gradient equation)
+    gat        graph attention layers (one head) and their reverse pass              (the
+               third model of the experimental setup)
     coverage   node-level weights, the minimum-distance factor, the shrinkage factor
                and the scale-then-reduce aggregation                           (section
                "Coverage-Corrected Aggregation"; the phase-parallel algorithm)

@@ -8,7 +8,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import coverage, gnn, sampling
+from . import coverage, gat, gnn, sampling
 
 
 def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
@@ -35,8 +35,12 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
             loss_nodes = np.arange(n, dtype=np.int64)
         else:
             loss_nodes = np.flatnonzero(np.asarray(train_mask) != 0).astype(np.int64)
-        res = gnn.forward_backward(arch, dims, theta, x, [blk] * k, labels, w_all, loss_nodes,
-                                   gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink)
+        if arch == "gat":
+            res = gat.forward_backward(dims, theta, x, blk, labels, w_all, loss_nodes,
+                                       relu_flip=relu_flip, near_kink=near_kink)
+        else:
+            res = gnn.forward_backward(arch, dims, theta, x, [blk] * k, labels, w_all, loss_nodes,
+                                       gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink)
         loss, grad = res[0], res[1]
         st = coverage.coverage_stats(dl, dg, loss_nodes, None)
         if near_kink is not None:

@@ -153,7 +153,10 @@ def stand_in_global_degree(d_local: torch.Tensor, gids: torch.Tensor, seed: int,
 
 
 def layer_dims_param_count(arch: str, dims) -> int:
-    """Number of floats in the flat parameter vector (layout: per layer W_self, W_neigh, b)."""
+    """Number of floats in the flat parameter vector (layout: per layer W_self, W_neigh, b;
+    "gat": per layer W, a_src, a_dst, b)."""
+    if arch == "gat":
+        return sum(dims[l] * dims[l + 1] + 3 * dims[l + 1] for l in range(len(dims) - 1))
     per = 2 if arch == "sage" else 1
     return sum(per * dims[l] * dims[l + 1] + dims[l + 1] for l in range(len(dims) - 1))
 
@@ -167,6 +170,10 @@ def model_weights(arch: str, dims, seed: int, device="cpu") -> torch.Tensor:
         for m in range(per):
             out.append(normal_matrix(fin, fout, seed, stream=100 + 10 * l + m,
                                      std=fin ** -0.5, device=device).reshape(-1))
+        if arch == "gat":            # the two attention vectors ~ N(0, 1/Fout)
+            for m in (5, 6):
+                out.append(normal_matrix(1, fout, seed, stream=100 + 10 * l + m, std=fout ** -0.5,
+                                         device=device).reshape(-1))
         out.append(normal_matrix(1, fout, seed, stream=100 + 10 * l + 9, std=0.1,
                                  device=device).reshape(-1))
     return torch.cat(out).contiguous()
