@@ -129,6 +129,7 @@ grp_status grp_partition_destroy(grp_partition_t* part);   /* NULL is a no-op */
 #define GRP_ARCH_SAGE_MEAN    0  /* z_v = h_v W_self + mean_{u in N_v} h_u W_neigh + b        */
 #define GRP_ARCH_GCN          1  /* z_v = sum_u Ahat[v,u] (h_u W) + b, symmetric normalisation */
 #define GRP_ARCH_GCN_RESIDUAL 2  /* GCN with h^{l+1} = h^l + ReLU(z^l) where widths agree      */
+#define GRP_ARCH_GAT          3  /* z_v = sum_u alpha_vu (h_u W) + b, attention weights alpha      */
 
 #define GRP_DTYPE_FP32 0
 #define GRP_DTYPE_BF16 1         /* storage of the input features only; accumulate in fp32 */
@@ -140,7 +141,12 @@ grp_status grp_partition_destroy(grp_partition_t* part);   /* NULL is a no-op */
  * Ahat[v,u] = (A[v,u] + [u==v]) / sqrt((d_in(v)+1)(d_out(u)+1)) on local degrees when
  * gcn_self_loops != 0, else A[v,u] / sqrt(max(d_in(v),1) max(d_out(u),1)).
  * Flat parameter layout (weights in, gradients out): layer-major; per layer W_self
- * (GCN: W) row-major [dims[l] x dims[l+1]], then W_neigh (SAGE only), then b[dims[l+1]]. */
+ * (GCN: W) row-major [dims[l] x dims[l+1]], then W_neigh (SAGE only), then b[dims[l+1]].
+ * GAT (the third model of "GNN Models": the neighbours' states are combined with learned
+ * attention weights; the published single-head layer): t = h W, score
+ * e_vu = LeakyReLU_0.2(a_src . t_u + a_dst . t_v) over the in-edges u -> v (with
+ * multiplicity) and one self term u = v, alpha = softmax_u(e_vu); full-graph mode only;
+ * per-layer parameters W [dims[l] x dims[l+1]], a_src, a_dst, b (each [dims[l+1]]).        */
 typedef struct {
     int32_t arch;
     int32_t n_layers;

@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgrappa_hip.so")
 
 GRP_MAX_LAYERS = 16
-ARCH_SAGE_MEAN, ARCH_GCN, ARCH_GCN_RESIDUAL = 0, 1, 2
+ARCH_SAGE_MEAN, ARCH_GCN, ARCH_GCN_RESIDUAL, ARCH_GAT = 0, 1, 2, 3
 DTYPE_FP32, DTYPE_BF16 = 0, 1
 EST_NONE, EST_NODE_LEVEL, EST_BATCH_MIN_DIST, EST_SHRINKAGE = 0, 1, 2, 3
 OPT_SGD, OPT_ADAM = 0, 1

@@ -235,6 +235,12 @@ void pack_jobs_add(PackJobs& jobs, const float* in, int32_t rows, int32_t cols, 
                    float* out, int64_t ld_out);
 grp_status launch_pack_weights(const PackJobs& jobs, hipStream_t st);
 
+// Graph attention model (full-graph mode): workspace size and the whole train step.
+size_t gat_step_workspace_bytes(const grp_partition_t* part, const grp_model_desc* m);
+grp_status gat_step(const grp_partition_t* g, const grp_model_desc* m, const grp_step_opts* o, const void* X,
+                    const int32_t* labels, const uint8_t* mask, const float* theta, void* ws, size_t ws_bytes,
+                    hipStream_t st, float* grad, grp_step_stats* stats);
+
 // Coverage statistics over the loss nodes and the weighted softmax cross-entropy.
 size_t stats_workspace_bytes(int64_t n);
 // nnz_used = nnz_const + the sum of the n_parts device counters nnz_parts[i][0].

@@ -43,7 +43,7 @@ struct StepPlan {
 
 static bool valid_model(const grp_model_desc* m) {
     if (!m) return false;
-    if (m->arch < GRP_ARCH_SAGE_MEAN || m->arch > GRP_ARCH_GCN_RESIDUAL) return false;
+    if (m->arch < GRP_ARCH_SAGE_MEAN || m->arch > GRP_ARCH_GAT) return false;
     if (m->n_layers < 1 || m->n_layers > GRP_MAX_LAYERS) return false;
     for (int l = 0; l <= m->n_layers; ++l)
         if (m->dims[l] <= 0 || m->dims[l] > 1024) return false;
@@ -52,6 +52,11 @@ static bool valid_model(const grp_model_desc* m) {
 }
 
 static int64_t param_count(const grp_model_desc* m) {
+    if (m->arch == GRP_ARCH_GAT) {        // per layer W, a_src, a_dst, b
+        int64_t p = 0;
+        for (int l = 0; l < m->n_layers; ++l) p += (int64_t)m->dims[l] * m->dims[l + 1] + 3 * m->dims[l + 1];
+        return p;
+    }
     const int per = m->arch == GRP_ARCH_SAGE_MEAN ? 2 : 1;
     int64_t p = 0;
     for (int l = 0; l < m->n_layers; ++l) p += (int64_t)per * m->dims[l] * m->dims[l + 1] + m->dims[l + 1];
@@ -158,7 +163,7 @@ static grp_status check_step_args(const grp_partition_t* part, const grp_model_d
         return fail(GRP_EUNSUPPORTED, "train_step: a residual first layer needs fp32 features");
     if (!opts->full_graph) {
         if (model->arch != GRP_ARCH_SAGE_MEAN)
-            return fail(GRP_EUNSUPPORTED, "train_step: mini-batch mode is defined for GraphSAGE only");
+            return fail(GRP_EUNSUPPORTED, "train_step: mini-batch mode is implemented for GraphSAGE only");
         if (opts->n_seeds < 1 || !opts->seeds) return fail(GRP_EINVAL, "train_step: mini-batch mode needs seed nodes");
         for (int l = 0; l < model->n_layers; ++l)
             if (opts->fanouts[l] < 1 || opts->fanouts[l] > 64)
@@ -407,7 +412,7 @@ extern "C" grp_status grp_step_workspace_bytes(const grp_partition_t* part, cons
     if (!bytes) return fail(GRP_EINVAL, "grp_step_workspace_bytes: null output");
     *bytes = 0;
     GRP_TRY(check_step_args(part, model, opts));
-    *bytes = make_plan(part, model, opts, nullptr, 0).total;
+    *bytes = model->arch == GRP_ARCH_GAT ? gat_step_workspace_bytes(part, model) : make_plan(part, model, opts, nullptr, 0).total;
     return GRP_OK;
 }
 
@@ -419,6 +424,14 @@ extern "C" grp_status grp_train_step(const grp_partition_t* part, const grp_mode
     GRP_TRY(check_step_args(part, model, opts));
     if (!weights || !grad_out || !stats_out) return fail(GRP_EINVAL, "train_step: null weights / grad_out / stats_out");
     if (part->n > 0 && (!features || !labels)) return fail(GRP_EINVAL, "train_step: null features or labels");
+    if (model->arch == GRP_ARCH_GAT) {
+        const size_t need_gat = gat_step_workspace_bytes(part, model);
+        if (!workspace || workspace_bytes < need_gat)
+            return fail(GRP_EWORKSPACE, "train_step: workspace %zu bytes, need %zu", workspace_bytes, need_gat);
+        if ((uintptr_t)workspace % 256 != 0) return fail(GRP_EINVAL, "train_step: workspace must be 256-byte aligned");
+        return gat_step(part, model, opts, features, labels, train_mask, weights, workspace, workspace_bytes,
+                        (hipStream_t)stream, grad_out, stats_out);
+    }
     StepPlan need = make_plan(part, model, opts, nullptr, 0);
     if (!workspace || workspace_bytes < need.total)
         return fail(GRP_EWORKSPACE, "train_step: workspace %zu bytes, need %zu", workspace_bytes, need.total);

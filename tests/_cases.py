@@ -30,6 +30,9 @@ def split_flat(flat, arch: str, dims):
         out[f"W{l}"] = flat[off:off + fin * fout]; off += fin * fout
         if arch == "sage":
             out[f"Wn{l}"] = flat[off:off + fin * fout]; off += fin * fout
+        if arch == "gat":
+            out[f"as{l}"] = flat[off:off + fout]; off += fout
+            out[f"ad{l}"] = flat[off:off + fout]; off += fout
         out[f"b{l}"] = flat[off:off + fout]; off += fout
     assert off == len(flat)
     return out
