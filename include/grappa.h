@@ -106,9 +106,22 @@ grp_status grp_chunks_destroy(grp_chunks_t* chunks);
 grp_status grp_partition_from_chunks(const grp_chunks_t* chunks, int32_t base, int32_t swept,
                                      void* stream, grp_partition_t** out);
 
+/* Partition part_id extended by `hops` hops of read-only halo nodes ("Graph Partitioning":
+ * an endpoint of a partition's edge that is not part of the partition is incorporated as a
+ * halo node).  Hop 0 = the owned nodes; hop h adds the sources of every edge whose destination
+ * lies in hops 0..h-1; the local edges are those whose destination lies in hops 0..hops-1, so
+ * the outermost halo nodes carry features but no in-edges.  Local ids follow ascending global
+ * id over the whole set; the owned nodes (the only loss nodes) are marked in the mask returned
+ * by grp_partition_base_mask.  With hops >= the number of layers, a GraphSAGE or GAT step over
+ * the owned nodes equals the whole-graph step restricted to them (d_local = d_global, c = 1).
+ * 1 <= hops <= GRP_MAX_LAYERS (hops = 0 is grp_partition).  Same handle, same errors.       */
+grp_status grp_partition_halo(const int64_t* src, const int64_t* dst, int64_t E, int64_t N,
+                              int32_t K, uint64_t seed, int32_t part_id, int32_t hops,
+                              void* stream, grp_partition_t** out);
+
 /* DEV uint8[n]: 1 for the nodes of the base chunk (a partition's loss nodes are the training
- * nodes of its base chunk; the swept chunk only supplies neighbours).  *mask is NULL for
- * partitions not built from chunks.  Borrowed pointer, valid until the handle is destroyed. */
+ * nodes of its base chunk; the swept chunk only supplies neighbours), or for the owned nodes of
+ * a halo partition.  *mask is NULL for partitions built by grp_partition / from a local COO.  Borrowed pointer, valid until the handle is destroyed. */
 grp_status grp_partition_base_mask(const grp_partition_t* part, const uint8_t** mask);
 
 /* Adopt a partition's share that was generated directly as local edges.

@@ -116,3 +116,44 @@ def local_graph_from_edges(src_local, dst_local, n: int, d_global_in=None) -> di
     return dict(n=int(n), nnz=int(ls.size), l2g=np.arange(n, dtype=np.int64), rowptr=rowptr,
                 col=col, colptr=colptr, row=row, d_local_in=d_in.astype(np.int32),
                 d_local_out=d_out.astype(np.int32), d_global_in=dg)
+
+
+def partition_halo(src, dst, n_nodes: int, n_parts: int, seed: int, part_id: int, hops: int = 1) -> dict:
+    """Partition ``part_id`` extended by ``hops`` hops of read-only halo nodes.
+
+    The paper's "Graph Partitioning" paragraph: the edges linked to a partition's nodes are
+    included, and an endpoint that is not part of the partition is incorporated as a halo node.
+    Reading: hop 0 is the owned node set; hop h adds the sources of every edge whose
+    destination is in hops 0..h-1; the local edges are the edges whose destination is in hops
+    0..hops-1 (so the outermost halo nodes have features but no in-edges).  Local ids number
+    the whole set in ascending global id; ``owned_mask`` (uint8) marks the owned nodes, which
+    are the only loss nodes.  With hops = 0 this is ``partition``.  Same arrays otherwise.
+    """
+    src = np.asarray(src, dtype=np.int64)
+    dst = np.asarray(dst, dtype=np.int64)
+    if hops < 0:
+        raise ValueError("hops must be >= 0")
+    if not (0 <= part_id < n_parts):
+        raise ValueError("part_id out of range")
+    if src.size and (src.min() < 0 or dst.min() < 0 or src.max() >= n_nodes or dst.max() >= n_nodes):
+        raise ValueError("node id out of range")
+    owned = owner(n_nodes, n_parts, seed) == part_id
+    inner = owned.copy()                                  # hops 0..h-1: nodes that keep their in-edges
+    member = owned.copy()
+    for _ in range(hops):
+        inner = member.copy()
+        member = member.copy()
+        member[src[inner[dst]]] = True
+    if hops == 0:
+        keep = member[src] & member[dst]
+    else:
+        keep = inner[dst]
+    l2g = np.flatnonzero(member).astype(np.int64)
+    n = int(l2g.size)
+    g2l = np.full(n_nodes, -1, dtype=np.int64)
+    g2l[l2g] = np.arange(n, dtype=np.int64)
+    d_global_all = np.bincount(dst, minlength=n_nodes).astype(np.int64)
+    part = local_graph_from_edges(g2l[src[keep]], g2l[dst[keep]], n, d_global_all[l2g])
+    part["l2g"] = l2g
+    part["owned_mask"] = owned[l2g].astype(np.uint8)
+    return part

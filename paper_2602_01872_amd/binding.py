@@ -67,6 +67,7 @@ def load() -> C.CDLL:
     sigs = {
         "grp_partition": [vp, vp, i64, i64, i32, u64, i32, vp, C.POINTER(vp)],
         "grp_partition_from_local_coo": [vp, vp, i64, i64, vp, vp, vp, C.POINTER(vp)],
+        "grp_partition_halo": [vp, vp, i64, i64, i32, u64, i32, i32, vp, C.POINTER(vp)],
         "grp_partition_view": [vp, C.POINTER(PartitionView)],
         "grp_chunks_build": [vp, vp, i64, i64, i32, u64, vp, C.POINTER(vp)],
         "grp_chunks_destroy": [vp],
@@ -253,6 +254,14 @@ def grp_partition_from_chunks(chunks: Chunks, base: int, swept: int, stream=None
     return Partition(out.value)
 
 
+def grp_partition_halo(src, dst, n_nodes: int, n_parts: int, seed: int, part_id: int, hops: int, stream=None) -> Partition:
+    out = C.c_void_p()
+    E = 0 if src is None else int(src.numel())
+    _check(load().grp_partition_halo(_ptr(src), _ptr(dst), E, n_nodes, n_parts, seed, part_id, hops, _stream(stream),
+                                     C.byref(out)))
+    return Partition(out.value)
+
+
 def grp_param_count(model: ModelDesc) -> int:
     return int(load().grp_param_count(C.byref(model)))
 
@@ -338,6 +347,6 @@ def read_stats(stats: torch.Tensor) -> np.ndarray:
 def exported_symbols():
     return ["grp_last_error", "grp_partition", "grp_partition_from_local_coo", "grp_partition_view",
             "grp_partition_destroy", "grp_chunks_build", "grp_chunks_destroy", "grp_partition_from_chunks",
-            "grp_partition_base_mask", "grp_param_count", "grp_step_workspace_bytes", "grp_train_step",
+            "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_train_step",
             "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
             "grp_profile_enable", "grp_profile_report"]

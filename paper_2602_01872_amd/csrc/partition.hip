@@ -307,6 +307,129 @@ static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t
     return build_csr_csc(h, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), st);
 }
 
+// ------------------------------------------------------------------ halo partitions
+// One hop outwards: the source of every edge whose destination is already inside joins.
+__global__ __launch_bounds__(256) void halo_grow_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                        int64_t E, int64_t N, const int32_t* __restrict__ inner,
+                                                        int32_t* __restrict__ member, unsigned long long* __restrict__ bad) {
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
+        const int64_t u = src[e], v = dst[e];
+        if (u < 0 || v < 0 || u >= N || v >= N) { atomicAdd(bad, 1ull); continue; }
+        if (inner[v]) member[u] = 1;              // every writer stores the same value
+    }
+}
+
+// Global in-degree of the members and the number of kept edges (destination in `inner`).
+__global__ __launch_bounds__(256) void halo_scan_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                        int64_t E, const int32_t* __restrict__ member,
+                                                        const int32_t* __restrict__ inner, const int64_t* __restrict__ pos,
+                                                        unsigned long long* __restrict__ dg,
+                                                        unsigned long long* __restrict__ kept_out) {
+    unsigned long long kept = 0;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
+        const int64_t v = dst[e];
+        if (member[v]) atomicAdd(&dg[pos[v]], 1ull);
+        if (inner[v]) kept++;
+    }
+    for (int o = 32; o > 0; o >>= 1) kept += __shfl_down(kept, o, 64);
+    if ((threadIdx.x & 63) == 0 && kept) atomicAdd(kept_out, kept);
+}
+
+__global__ __launch_bounds__(256) void halo_keys_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                        int64_t E, const int32_t* __restrict__ inner,
+                                                        const int64_t* __restrict__ pos, unsigned long long* __restrict__ cursor,
+                                                        uint64_t* __restrict__ keys) {
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
+        const int64_t u = src[e], v = dst[e];
+        if (inner[v]) {
+            const unsigned long long slot = atomicAdd(cursor, 1ull);
+            keys[slot] = ((uint64_t)pos[v] << 32) | (uint64_t)pos[u];
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void halo_nodes_kernel(int64_t N, const int32_t* __restrict__ member,
+                                                         const int32_t* __restrict__ owned, const int64_t* __restrict__ pos,
+                                                         int64_t* __restrict__ l2g, uint8_t* __restrict__ owned_mask) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v < N && member[v]) {
+        l2g[pos[v]] = v;
+        owned_mask[pos[v]] = owned[v] ? 1 : 0;
+    }
+}
+
+static grp_status halo_partition_impl(const int64_t* src, const int64_t* dst, int64_t E, int64_t N, int32_t K, uint64_t seed,
+                                      int32_t part_id, int32_t hops, hipStream_t st, grp_partition_t* h) {
+    DevBuf owned, member, inner, pos, counters, scan_tmp;
+    GRP_TRY(owned.alloc((size_t)N * sizeof(int32_t)));
+    GRP_TRY(member.alloc((size_t)N * sizeof(int32_t)));
+    GRP_TRY(inner.alloc((size_t)N * sizeof(int32_t)));
+    GRP_TRY(pos.alloc((size_t)N * sizeof(int64_t)));
+    GRP_TRY(counters.alloc(3 * sizeof(unsigned long long)));          // [0] kept, [1] bad ids, [2] key cursor
+    GRP_HIP(hipMemsetAsync(counters.p, 0, 3 * sizeof(unsigned long long), st));
+    int64_t n = 0;
+    if (N > 0) {
+        hipLaunchKernelGGL(owner_flag_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, N, (uint32_t)K, seed,
+                           (uint32_t)part_id, owned.as<int32_t>());
+        GRP_LAUNCH_CHECK();
+        GRP_HIP(hipMemcpyAsync(member.p, owned.p, (size_t)N * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+        for (int hop = 0; hop < hops; ++hop) {
+            GRP_HIP(hipMemcpyAsync(inner.p, member.p, (size_t)N * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+            if (E > 0) {
+                hipLaunchKernelGGL(halo_grow_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, N, inner.as<int32_t>(),
+                                   member.as<int32_t>(), counters.as<unsigned long long>() + 1);
+                GRP_LAUNCH_CHECK();
+            }
+        }
+        size_t bytes = 0;
+        GRP_HIP(rocprim::exclusive_scan(nullptr, bytes, member.as<int32_t>(), pos.as<int64_t>(), (int64_t)0, (size_t)N,
+                                        rocprim::plus<int64_t>(), st));
+        GRP_TRY(scan_tmp.alloc(bytes));
+        GRP_HIP(rocprim::exclusive_scan(scan_tmp.p, bytes, member.as<int32_t>(), pos.as<int64_t>(), (int64_t)0, (size_t)N,
+                                        rocprim::plus<int64_t>(), st));
+        int64_t last_pos = 0;
+        int32_t last_flag = 0;
+        unsigned long long nbad = 0;
+        GRP_HIP(hipMemcpyAsync(&last_pos, pos.as<int64_t>() + (N - 1), sizeof(int64_t), hipMemcpyDeviceToHost, st));
+        GRP_HIP(hipMemcpyAsync(&last_flag, member.as<int32_t>() + (N - 1), sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        GRP_HIP(hipMemcpyAsync(&nbad, counters.as<unsigned long long>() + 1, sizeof nbad, hipMemcpyDeviceToHost, st));
+        GRP_HIP(hipStreamSynchronize(st));
+        if (nbad) return fail(GRP_ERANGE, "edges have an endpoint outside [0, %lld)", (long long)N);
+        n = last_pos + last_flag;
+    }
+    if (n >= ((int64_t)1 << 31)) return fail(GRP_ERANGE, "partition has %lld >= 2^31 local nodes", (long long)n);
+    h->n = n;
+    GRP_TRY(halloc(&h->l2g, n));
+    GRP_TRY(halloc(&h->d_global_in, n));
+    GRP_TRY(halloc(&h->base_mask, n));
+    GRP_HIP(hipMemsetAsync(h->d_global_in, 0, (size_t)(n > 0 ? n : 1) * sizeof(int64_t), st));
+    unsigned long long kept = 0;
+    if (N > 0) {
+        hipLaunchKernelGGL(halo_nodes_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, N, member.as<int32_t>(),
+                           owned.as<int32_t>(), pos.as<int64_t>(), h->l2g, h->base_mask);
+        GRP_LAUNCH_CHECK();
+    }
+    if (E > 0) {
+        hipLaunchKernelGGL(halo_scan_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, member.as<int32_t>(),
+                           inner.as<int32_t>(), pos.as<int64_t>(), (unsigned long long*)h->d_global_in,
+                           counters.as<unsigned long long>());
+        GRP_LAUNCH_CHECK();
+        GRP_HIP(hipMemcpyAsync(&kept, counters.p, sizeof kept, hipMemcpyDeviceToHost, st));
+        GRP_HIP(hipStreamSynchronize(st));
+    }
+    const int64_t nnz = (int64_t)kept;
+    h->nnz = nnz;
+    DevBuf keys, keys_alt;
+    GRP_TRY(keys.alloc((size_t)nnz * sizeof(uint64_t)));
+    GRP_TRY(keys_alt.alloc((size_t)nnz * sizeof(uint64_t)));
+    if (nnz > 0) {
+        hipLaunchKernelGGL(halo_keys_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, inner.as<int32_t>(),
+                           pos.as<int64_t>(), counters.as<unsigned long long>() + 2, keys.as<uint64_t>());
+        GRP_LAUNCH_CHECK();
+    }
+    return build_csr_csc(h, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), st);
+}
+
 // ------------------------------------------------------------------ chunks
 constexpr int MAX_CHUNKS = 64;        // n_chunks^2 bucket counters must fit a workgroup's LDS
 
@@ -541,6 +664,28 @@ extern "C" grp_status grp_partition_from_chunks(const grp_chunks_t* chunks, int3
     if (!h) return fail(GRP_ENOMEM, "grp_partition_from_chunks: host allocation failed");
     (void)hipGetDevice(&h->device);
     const grp_status s = pair_partition_impl(chunks, base, swept, (hipStream_t)stream, h);
+    if (s != GRP_OK) {
+        free_partition(h);
+        return s;
+    }
+    *out = h;
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_partition_halo(const int64_t* src, const int64_t* dst, int64_t E, int64_t N, int32_t K, uint64_t seed,
+                                         int32_t part_id, int32_t hops, void* stream, grp_partition_t** out) {
+    using namespace grp;
+    if (!out) return fail(GRP_EINVAL, "grp_partition_halo: out is null");
+    *out = nullptr;
+    if (E < 0 || N < 0) return fail(GRP_EINVAL, "grp_partition_halo: negative size");
+    if (E > 0 && (!src || !dst)) return fail(GRP_EINVAL, "grp_partition_halo: null edge arrays");
+    if (K < 1) return fail(GRP_EINVAL, "grp_partition_halo: K = %d < 1", K);
+    if (part_id < 0 || part_id >= K) return fail(GRP_EINVAL, "grp_partition_halo: part_id %d outside [0, %d)", part_id, K);
+    if (hops < 1 || hops > GRP_MAX_LAYERS) return fail(GRP_EINVAL, "grp_partition_halo: hops = %d outside [1, %d]", hops, GRP_MAX_LAYERS);
+    grp_partition_t* h = new (std::nothrow) grp_partition_t();
+    if (!h) return fail(GRP_ENOMEM, "grp_partition_halo: host allocation failed");
+    (void)hipGetDevice(&h->device);
+    const grp_status s = halo_partition_impl(src, dst, E, N, K, seed, part_id, hops, (hipStream_t)stream, h);
     if (s != GRP_OK) {
         free_partition(h);
         return s;
