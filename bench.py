@@ -33,7 +33,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by what the same counters
 # read for a plain 1 GiB copy (see profiles/bench_config2_hbm_traffic.md).  Other kernels: None.
 HBM_TRAFFIC_BYTES_PER_LAUNCH = {
-    "gemm_nt_f32_128x128_k32": 7.76e8,
+    "gemm_nt_f32_128x128_k32": 9.51e8,
 }
 
 GRAPH_SEED = 2602018722

@@ -399,10 +399,14 @@ __device__ __forceinline__ void nn_epilogue_interior(const GemmNNArgs& g, floatx
     constexpr int BN = WN * TN * 32;
     constexpr int PC = BN + 4;
     constexpr int C4 = BN / 4;                        // 16-byte columns per tile row
-    constexpr int RPI = 256 / C4;                     // tile rows covered by one pass of the workgroup
+    // tile rows covered by one pass of the workgroup: a power of two (a pass must not straddle
+    // two 32-row blocks); with BN = 96 only 192 of the 256 threads take part
+    constexpr int RPI = 256 / C4 >= 32 ? 32 : 256 / C4 >= 16 ? 16 : 256 / C4 >= 8 ? 8 : 4;
     constexpr int ITS = WM * 32 / RPI;
-    static_assert(32 % RPI == 0, "a pass must not straddle two 32-row blocks");
+    constexpr int ITB = ITS < 8 ? ITS : 8;            // passes whose loads are in flight together
+    static_assert(32 % RPI == 0 && ITS % ITB == 0, "a pass must not straddle two 32-row blocks");
     const int tid = threadIdx.x;
+    const bool active = tid < RPI * C4;
     const int wave = tid >> 6, lane = tid & 63;
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lk = lane >> 5;
@@ -410,7 +414,7 @@ __device__ __forceinline__ void nn_epilogue_interior(const GemmNNArgs& g, floatx
     const float* const rd = lds + r0 * PC + 4 * c4;
     float* const wr = lds + (wm * 32 + 4 * lk) * PC + wn * TN * 32 + li;
     float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (use_bias) b4 = *reinterpret_cast<const float4*>(g.bias + (n0 - g.bias_col0) + 4 * c4);
+    if (use_bias && active) b4 = *reinterpret_cast<const float4*>(g.bias + (n0 - g.bias_col0) + 4 * c4);
     const float floor_v = g.relu ? 0.f : -INFINITY;
     float* const Cb = g.C + m0 * g.ldc + n0;
     float* const Rb = g.C_raw ? g.C_raw + m0 * g.ld_raw + n0 : nullptr;
@@ -425,29 +429,35 @@ __device__ __forceinline__ void nn_epilogue_interior(const GemmNNArgs& g, floatx
 #pragma unroll
             for (int r = 0; r < 16; ++r) wr[(8 * (r / 4) + (r % 4)) * PC + 32 * j] = acc[i][j][r];
         __syncthreads();
-        float4 av[ITS], mv[ITS];
-        float rs[ITS];
+        if (!active) continue;                        // (uniform barriers above: nothing below synchronises)
 #pragma unroll
-        for (int it = 0; it < ITS; ++it) {
-            const uint32_t row = ((RPI * it) / 32 * TM + i) * 32 + (RPI * it) % 32 + r0;
-            av[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-            mv[it] = make_float4(1.f, 1.f, 1.f, 1.f);
-            rs[it] = 1.f;
-            if (Ab) av[it] = *reinterpret_cast<const float4*>(Ab + (row * (uint32_t)g.ld_add + 4 * c4));
-            if (Mb) mv[it] = *reinterpret_cast<const float4*>(Mb + (row * (uint32_t)g.ld_mask + 4 * c4));
-            if (Sb) rs[it] = Sb[row];
-        }
+        for (int it0 = 0; it0 < ITS; it0 += ITB) {
+            float4 av[ITB], mv[ITB];
+            float rs[ITB];
 #pragma unroll
-        for (int it = 0; it < ITS; ++it) {
-            const uint32_t row = ((RPI * it) / 32 * TM + i) * 32 + (RPI * it) % 32 + r0;
-            float4 v = *reinterpret_cast<const float4*>(rd + RPI * it * PC);
-            v.x += av[it].x + b4.x; v.y += av[it].y + b4.y; v.z += av[it].z + b4.z; v.w += av[it].w + b4.w;
-            if (Rb) *reinterpret_cast<float4*>(Rb + (row * (uint32_t)g.ld_raw + 4 * c4)) = v;
-            v.x = fmaxf(v.x * rs[it], floor_v); v.y = fmaxf(v.y * rs[it], floor_v);
-            v.z = fmaxf(v.z * rs[it], floor_v); v.w = fmaxf(v.w * rs[it], floor_v);
-            v.x = mv[it].x > 0.f ? v.x : 0.f; v.y = mv[it].y > 0.f ? v.y : 0.f;
-            v.z = mv[it].z > 0.f ? v.z : 0.f; v.w = mv[it].w > 0.f ? v.w : 0.f;
-            *reinterpret_cast<float4*>(Cb + (row * (uint32_t)g.ldc + 4 * c4)) = v;
+            for (int u = 0; u < ITB; ++u) {
+                const int it = it0 + u;
+                const uint32_t row = ((RPI * it) / 32 * TM + i) * 32 + (RPI * it) % 32 + r0;
+                av[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                mv[u] = make_float4(1.f, 1.f, 1.f, 1.f);
+                rs[u] = 1.f;
+                if (Ab) av[u] = *reinterpret_cast<const float4*>(Ab + (row * (uint32_t)g.ld_add + 4 * c4));
+                if (Mb) mv[u] = *reinterpret_cast<const float4*>(Mb + (row * (uint32_t)g.ld_mask + 4 * c4));
+                if (Sb) rs[u] = Sb[row];
+            }
+#pragma unroll
+            for (int u = 0; u < ITB; ++u) {
+                const int it = it0 + u;
+                const uint32_t row = ((RPI * it) / 32 * TM + i) * 32 + (RPI * it) % 32 + r0;
+                float4 v = *reinterpret_cast<const float4*>(rd + RPI * it * PC);
+                v.x += av[u].x + b4.x; v.y += av[u].y + b4.y; v.z += av[u].z + b4.z; v.w += av[u].w + b4.w;
+                if (Rb) *reinterpret_cast<float4*>(Rb + (row * (uint32_t)g.ld_raw + 4 * c4)) = v;
+                v.x = fmaxf(v.x * rs[u], floor_v); v.y = fmaxf(v.y * rs[u], floor_v);
+                v.z = fmaxf(v.z * rs[u], floor_v); v.w = fmaxf(v.w * rs[u], floor_v);
+                v.x = mv[u].x > 0.f ? v.x : 0.f; v.y = mv[u].y > 0.f ? v.y : 0.f;
+                v.z = mv[u].z > 0.f ? v.z : 0.f; v.w = mv[u].w > 0.f ? v.w : 0.f;
+                *reinterpret_cast<float4*>(Cb + (row * (uint32_t)g.ldc + 4 * c4)) = v;
+            }
         }
     }
 }
@@ -469,9 +479,10 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNNArgs g) {
     constexpr int PK = BKT + 4;
     constexpr int KQ = BKT / 4;                       // 16-byte slots per tile row
     constexpr int RSTEP = 256 / KQ;                   // tile rows covered by one pass of the workgroup
-    constexpr int A_REPS = BM * BKT / 4 / 256, B_REPS = BN * BKT / 4 / 256;
+    constexpr int A_REPS = BM * BKT / 4 / 256, B_REPS = (BN * BKT / 4 + 255) / 256;
+    constexpr bool B_FULL = BN * BKT / 4 % 256 == 0;  // else the last pass over the B tile is partial (BN = 96, BKT = 16)
     constexpr bool A_BF16 = sizeof(AT) == 2;
-    static_assert(BM * BKT / 4 % 256 == 0 && BN * BKT / 4 % 256 == 0 && BKT % 8 == 0, "tiles must fill the workgroup");
+    static_assert(BM * BKT / 4 % 256 == 0 && BKT % 8 == 0, "the A tile must fill the workgroup");
     constexpr int PC = BN + 4;
     constexpr int MAIN_FLOATS = NBUF * (BM + BN) * PK;
     constexpr int EPI_FLOATS = WM * 32 * PC;
@@ -575,7 +586,8 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNNArgs g) {
 #pragma unroll
             for (int r = 0; r < A_REPS; ++r) *reinterpret_cast<uint4*>(As + RSTEP * r * PK) = ra[r];
 #pragma unroll
-            for (int r = 0; r < B_REPS; ++r) *reinterpret_cast<uint4*>(Bs + RSTEP * r * PK) = rb[r];
+            for (int r = 0; r < B_REPS; ++r)
+                if (B_FULL || trow + RSTEP * r < BN) *reinterpret_cast<uint4*>(Bs + RSTEP * r * PK) = rb[r];
             return;
         }
 #pragma unroll
@@ -597,7 +609,8 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNNArgs g) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) v[q] = kbase + q < Kc ? v[q] : 0.f;
             }
-            *reinterpret_cast<float4*>(Bs + RSTEP * r * PK) = make_float4(v[0], v[1], v[2], v[3]);
+            if (B_FULL || trow + RSTEP * r < BN)
+                *reinterpret_cast<float4*>(Bs + RSTEP * r * PK) = make_float4(v[0], v[1], v[2], v[3]);
         }
     };
 
@@ -663,7 +676,8 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNNArgs g) {
     else nn_epilogue<true, WM, WN, TM, TN>(g, acc, lds, m0, n0, n_store);
 }
 
-// Tile choice (measured on MI355X at M = 3e5): 128 x 128 output tiles at three workgroups per
+// Tile choice (measured on MI355X at M = 3e5; the nt path adds a 128 x 96 tile for 64 < N <= 96,
+// e.g. two stacked 47-wide weight blocks): 128 x 128 output tiles at three workgroups per
 // CU beat 128 x 256 at one; a 32-deep single-buffered k-tile is best for long reductions, a
 // 16-deep double-buffered one wastes less on short or ragged K.
 template <typename AT, bool VEC>
@@ -707,7 +721,9 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
         // one profiling name per kernel variant, so that the names line up with a kernel trace
         char pname[64];
         snprintf(pname, sizeof pname, "gemm_%s_%s_%s%s", ok ? "nt" : "nn", a.a_bf16 ? "bf16a" : "f32",
-                 n_eff > 64 ? "128x128" : (ok || n_eff > 32 ? "128x64" : "128x32"), short_k ? "_k16" : "_k32");
+                 ok ? (n_eff > 96 ? "128x128" : n_eff > 64 ? "128x96" : "128x64")
+                    : (n_eff > 64 ? "128x128" : n_eff > 32 ? "128x64" : "128x32"),
+                 short_k ? "_k16" : "_k32");
         ProfScope ps(pname, st, nn_flops, nn_bytes);
         if (!ok) {                                       // slow, always-safe kernel
             if (a.a_bf16) nn_pick<__hip_bfloat16, false>(a, st); else nn_pick<float, false>(a, st);
@@ -716,7 +732,8 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
         }
         const int64_t slabs = round_up(cdiv(a.M, 128), NXCD);
         const bool rowlimit = a.a_rows != nullptr || (a.a_valid_rows > 0 && a.a_valid_rows < a.M);
-        const unsigned blocks = (unsigned)(slabs * cdiv(n_eff, n_eff > 64 ? 128 : 64));
+        const int tile_n = n_eff > 96 ? 128 : n_eff > 64 ? 96 : 64;
+        const unsigned blocks = (unsigned)(slabs * cdiv(n_eff, tile_n));
 #define GRP_NT_LAUNCH2(AT, WM_, WN_, TM_, TN_, RL)                                                                        \
     do {                                                                                                                  \
         if (short_k) hipLaunchKernelGGL((gemm_nt_kernel<AT, WM_, WN_, TM_, TN_, RL, 16, 2>), dim3(blocks), dim3(256), 0, st, a); \
@@ -727,8 +744,10 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
         if (rowlimit) GRP_NT_LAUNCH2(AT, WM_, WN_, TM_, TN_, true);                                                 \
         else GRP_NT_LAUNCH2(AT, WM_, WN_, TM_, TN_, false);                                                         \
     } while (0)
-        if (n_eff > 64) {
+        if (n_eff > 96) {
             if (a.a_bf16) GRP_NT_LAUNCH(__hip_bfloat16, 2, 2, 2, 2); else GRP_NT_LAUNCH(float, 2, 2, 2, 2);
+        } else if (n_eff > 64) {
+            if (a.a_bf16) GRP_NT_LAUNCH(__hip_bfloat16, 4, 1, 1, 3); else GRP_NT_LAUNCH(float, 4, 1, 1, 3);
         } else {
             if (a.a_bf16) GRP_NT_LAUNCH(__hip_bfloat16, 4, 1, 1, 2); else GRP_NT_LAUNCH(float, 4, 1, 1, 2);
         }

@@ -463,7 +463,8 @@ def test_residual_gcn_matches_oracle(g, dims, self_loops):
 
 
 @pytest.mark.parametrize("M,N,K,bf16", [(1000, 256, 256, False), (777, 47, 100, False), (4097, 172, 36, True),
-                                        (333, 130, 33, False), (129, 512, 48, False)])
+                                        (333, 130, 33, False), (129, 512, 48, False), (5000, 95, 256, False),
+                                        (700, 96, 100, False), (1031, 80, 52, True), (256, 72, 16, False)])
 def test_gemm_nt_matches_numpy(g, M, N, K, bf16):
     _note(f"gemm_nt M={M} N={N} K={K} bf16={bf16}")
     a = synth.normal_matrix(M, K, 1)
