@@ -1043,6 +1043,39 @@ __global__ __launch_bounds__(256) void tn_reduce_vec_kernel(const float* __restr
     }
 }
 
+// Scalar variant of the same scheme for strides that rule out 16-byte loads: a workgroup owns
+// 64 elements, 4 groups of threads each add a contiguous quarter of the splits in ascending
+// order, the 4 group sums are added in ascending order.
+__global__ __launch_bounds__(256) void tn_reduce_4way_kernel(const float* __restrict__ part, int splits, int K, int N,
+                                                             int64_t part_stride, float* __restrict__ C, int64_t ldc,
+                                                             float* __restrict__ colsum_out) {
+    __shared__ float red[4][64];
+    const int c = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int64_t rows = colsum_out ? K + 1 : K;
+    const int64_t total = rows * N;
+    const int64_t e = (int64_t)blockIdx.x * 64 + c;
+    const int per = (splits + 3) / 4;
+    const int p_begin = grp * per, p_end = p_begin + per < splits ? p_begin + per : splits;
+    float s = 0.f;
+    if (e < total) {
+        const float* p0 = part + e;
+        int p = p_begin;
+        for (; p + 4 <= p_end; p += 4) {
+            const float a = p0[(int64_t)p * part_stride], b = p0[(int64_t)(p + 1) * part_stride];
+            const float c2 = p0[(int64_t)(p + 2) * part_stride], d = p0[(int64_t)(p + 3) * part_stride];
+            s += a; s += b; s += c2; s += d;
+        }
+        for (; p < p_end; ++p) s += p0[(int64_t)p * part_stride];
+    }
+    red[grp][c] = s;
+    __syncthreads();
+    if (grp == 0 && e < total) {
+        const float t = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
+        if (e / N < K) C[(e / N) * ldc + (e % N)] = t;
+        else colsum_out[e % N] = t;
+    }
+}
+
 template <typename AT, bool VEC, bool GATHER>
 static void tn_pick(const GemmTNArgs& a, const TnPlan& p, float* out, int64_t out_ld, int64_t stride, float* cs_out,
                     int64_t cs_stride, hipStream_t st) {
@@ -1092,6 +1125,9 @@ grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st) {
         const int64_t rows = a.colsum_out ? a.K + 1 : a.K;
         if (stride % 4 == 0 && (rows * a.N) % 4 == 0 && (uintptr_t)a.workspace % 16 == 0 && p.splits >= 16) {
             hipLaunchKernelGGL(tn_reduce_vec_kernel, dim3((unsigned)cdiv(rows * a.N, 64)), dim3(256), 0, st,
+                               (const float*)a.workspace, p.splits, a.K, a.N, stride, a.C, a.ldc, a.colsum_out);
+        } else if (p.splits >= 16) {
+            hipLaunchKernelGGL(tn_reduce_4way_kernel, dim3((unsigned)cdiv(rows * a.N, 64)), dim3(256), 0, st,
                                (const float*)a.workspace, p.splits, a.K, a.N, stride, a.C, a.ldc, a.colsum_out);
         } else {
             hipLaunchKernelGGL(tn_reduce_kernel, dim3((unsigned)cdiv(rows * a.N, 256)), dim3(256), 0, st,
