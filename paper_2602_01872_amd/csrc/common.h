@@ -203,6 +203,12 @@ struct GemmTNArgs {
     const int32_t* a_rows = nullptr; // row i of A is stored at row a_rows[i] (null: i)
     float* colsum_out = nullptr;     // optional [N]: column sums of B (each row times colsum_scale[m] if set)
     const float* colsum_scale = nullptr;
+    // A second product from the same launch (at most one of the two):
+    const float* A2 = nullptr;       // C2[K x N] = A2[M x K]^T B   (fp32, rows not gathered)
+    int64_t lda2 = 0;
+    const float* B2 = nullptr;       // C2[K x N] = A^T B2[M x N]
+    int64_t ldb2 = 0;
+    float* C2 = nullptr;             // pitch ldc
 };
 grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st);
 

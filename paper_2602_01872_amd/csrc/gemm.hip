@@ -20,6 +20,8 @@
 // they are written to LDS.
 #include "common.h"
 
+#include <algorithm>
+
 #include <type_traits>
 
 namespace grp {
@@ -779,13 +781,13 @@ struct TnPlan {
     int bk_tile, bn_tile;
 };
 
-static TnPlan tn_plan(int64_t M, int K, int N) {
+static TnPlan tn_plan(int64_t M, int K, int N, int products = 1) {
     TnPlan p;
     p.bk_tile = 128;
     p.bn_tile = N > 64 ? 128 : (N > 32 ? 64 : 32);
     p.tiles_k = (int)cdiv(K, p.bk_tile);
     p.tiles_n = (int)cdiv(N, p.bn_tile);
-    int64_t s = TN_TARGET_WGS / (p.tiles_k * p.tiles_n);
+    int64_t s = TN_TARGET_WGS / (p.tiles_k * p.tiles_n * products);
     if (s > cdiv(M, TN_ROWS_PER_SPLIT_MIN)) s = cdiv(M, TN_ROWS_PER_SPLIT_MIN);
     if (s > TN_MAX_SPLITS) s = TN_MAX_SPLITS;
     if (s < 1) s = 1;
@@ -797,8 +799,15 @@ static TnPlan tn_plan(int64_t M, int K, int N) {
 }
 
 size_t gemm_tn_workspace_bytes(int64_t M, int32_t K, int32_t N) {
-    TnPlan p = tn_plan(M, K, N);
-    return p.splits > 1 ? (size_t)p.splits * (K + 1) * N * sizeof(float) : 0;   // + the column-sum row
+    // room for one product, or for two from one launch: (2K + 1) rows of N, or (K + 1) rows of 2N
+    size_t need = 0;
+    for (int products = 1; products <= 2; ++products) {
+        const TnPlan p = tn_plan(M, K, N, products);
+        if (p.splits <= 1) continue;
+        const size_t rows_n = products == 1 ? (size_t)(K + 1) * N : std::max((size_t)(2 * (size_t)K + 1) * N, (size_t)(K + 1) * 2 * N);
+        need = std::max(need, (size_t)p.splits * rows_n * sizeof(float));
+    }
+    return need;
 }
 
 // Grid: x = NXCD * tiles * ceil(splits / NXCD).  Workgroup ids are mapped so that the output
@@ -809,9 +818,10 @@ size_t gemm_tn_workspace_bytes(int64_t M, int32_t K, int32_t N) {
 // GATHER: rows of A are taken through g.a_rows.  cs_out (optional): the workgroups of the
 // first row of output tiles also add up the columns of B they stream (times colsum_scale).
 template <typename AT, bool VEC, bool GATHER, int WM, int WN, int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k, int tiles_n, int splits, int64_t chunk,
-                                                      float* __restrict__ out, int64_t out_ld, int64_t out_split_stride,
-                                                      float* __restrict__ cs_out, int64_t cs_split_stride) {
+__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k, int tiles_n, int dual, int splits, int64_t chunk,
+                                                      float* __restrict__ out, float* __restrict__ out2, int64_t out_ld,
+                                                      int64_t out_split_stride, float* __restrict__ cs_out,
+                                                      int64_t cs_split_stride) {
     constexpr int BKA = WM * TM * 32, BN = WN * TN * 32;   // output tile: BKA (rows of C) x BN
     constexpr int PA = BKA + 4, PB = BN + 4;
     constexpr int QA = BKA / 4, QB = BN / 4;               // 16-byte slots per tile row
@@ -822,11 +832,22 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
     __shared__ __attribute__((aligned(16))) float As[BK * PA];
     __shared__ __attribute__((aligned(16))) float Bs[BK * PB];
 
-    const int tiles = tiles_k * tiles_n;
+    // dual = 1: the second half of the tiles multiplies A2 instead of A; dual = 2: B2 instead of B
+    const int tiles1 = tiles_k * tiles_n;
+    const int tiles = tiles1 * (dual ? 2 : 1);
     const int hq = blockIdx.x / NXCD;
-    const int tile = hq % tiles;
+    const int tile_all = hq % tiles;
+    const bool op2 = tile_all >= tiles1;
+    const int tile = tile_all % tiles1;
     const int split = (hq / tiles) * NXCD + blockIdx.x % NXCD;
     if (split >= splits) return;
+    const bool a2 = op2 && dual == 1, b2 = op2 && dual == 2;
+    const void* const Aop = a2 ? (const void*)g.A2 : g.A;
+    const int64_t lda = a2 ? g.lda2 : g.lda;
+    const int32_t* const a_rows = a2 ? nullptr : g.a_rows;
+    const float* const Bop = b2 ? g.B2 : g.B;
+    const int64_t ldb = b2 ? g.ldb2 : g.ldb;
+    const bool a_is_bf16 = sizeof(AT) == 2 && !a2;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -836,7 +857,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
     const int64_t m_begin = (int64_t)split * chunk;
     const int64_t m_end = m_begin + chunk < g.M ? m_begin + chunk : g.M;
     const int kpad = (g.K + 3) & ~3, npad = (g.N + 3) & ~3;
-    const bool do_cs = cs_out != nullptr && ka0 == 0;
+    const bool do_cs = cs_out != nullptr && ka0 == 0 && !op2;
     const float* const cs_scale = do_cs ? g.colsum_scale : nullptr;
 
     floatx16 acc[TM][TN];
@@ -851,9 +872,9 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
     const int ca = imin(ka0 + 4 * cqa, kpad - 4), cb = imin(n0 + 4 * cqb, npad - 4);
     uint32_t aoff[A_REPS], boff[B_REPS];
 #pragma unroll
-    for (int r = 0; r < A_REPS; ++r) aoff[r] = (uint32_t)(ma + RA * r) * (uint32_t)g.lda + ca;
+    for (int r = 0; r < A_REPS; ++r) aoff[r] = (uint32_t)(ma + RA * r) * (uint32_t)lda + ca;
 #pragma unroll
-    for (int r = 0; r < B_REPS; ++r) boff[r] = (uint32_t)(mb + RB * r) * (uint32_t)g.ldb + cb;
+    for (int r = 0; r < B_REPS; ++r) boff[r] = (uint32_t)(mb + RB * r) * (uint32_t)ldb + cb;
     float* const as_w = As + ma * PA + 4 * cqa;
     float* const bs_w = Bs + mb * PB + 4 * cqb;
     float csum[4] = {0.f, 0.f, 0.f, 0.f};
@@ -866,11 +887,17 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
 #pragma unroll
             for (int r = 0; r < B_REPS; ++r) rsc[r] = cs_scale[lmin(mt + mb + RB * r, g.M - 1)];
         }
-        if (VEC && !GATHER && full) {
-            const AT* pa = (const AT*)g.A + mt * g.lda;
-            const float* pb = g.B + mt * g.ldb;
+        if (VEC && (!GATHER || !a_rows) && full) {
+            const float* pb = Bop + mt * ldb;
+            if (A_BF16 && !a_is_bf16) {               // the second operand of a bf16 launch is fp32
+                const float* pa = (const float*)Aop + mt * lda;
 #pragma unroll
-            for (int r = 0; r < A_REPS; ++r) ra[r] = ldg_raw4<AT>(pa + aoff[r]);
+                for (int r = 0; r < A_REPS; ++r) ra[r] = ldg_raw4<float>(pa + aoff[r]);
+            } else {
+                const AT* pa = (const AT*)Aop + mt * lda;
+#pragma unroll
+                for (int r = 0; r < A_REPS; ++r) ra[r] = ldg_raw4<AT>(pa + aoff[r]);
+            }
 #pragma unroll
             for (int r = 0; r < B_REPS; ++r) rb[r] = ldg_raw4<float>(pb + boff[r]);
             return;
@@ -880,36 +907,38 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
             const int m = ma + RA * r;
             if constexpr (VEC) {
                 const int64_t gm = lmin(mt + m, g.M - 1);
-                const int64_t row = g.a_rows ? (int64_t)g.a_rows[gm] : gm;
-                ra[r] = ldg_raw4<AT>((const AT*)g.A + row * g.lda + ca);
+                const int64_t row = a_rows ? (int64_t)a_rows[gm] : gm;
+                if (A_BF16 && !a_is_bf16) ra[r] = ldg_raw4<float>((const float*)Aop + row * lda + ca);
+                else ra[r] = ldg_raw4<AT>((const AT*)Aop + row * lda + ca);
             } else {
                 const bool ok = mt + m < m_end;
                 const int64_t gm = ok ? mt + m : 0;
-                const int64_t row = (g.a_rows && ok) ? (int64_t)g.a_rows[gm] : gm;
-                ra[r] = ldg_safe4<AT>((const AT*)g.A + row * g.lda, ok, ka0 + 4 * cqa, g.K);
+                const int64_t row = (a_rows && ok) ? (int64_t)a_rows[gm] : gm;
+                if (A_BF16 && !a_is_bf16) ra[r] = ldg_safe4<float>((const float*)Aop + row * lda, ok, ka0 + 4 * cqa, g.K);
+                else ra[r] = ldg_safe4<AT>((const AT*)Aop + row * lda, ok, ka0 + 4 * cqa, g.K);
             }
         }
 #pragma unroll
         for (int r = 0; r < B_REPS; ++r) {
             const int m = mb + RB * r;
             if constexpr (VEC) {
-                rb[r] = ldg_raw4<float>(g.B + lmin(mt + m, g.M - 1) * g.ldb + cb);
+                rb[r] = ldg_raw4<float>(Bop + lmin(mt + m, g.M - 1) * ldb + cb);
             } else {
                 const bool ok = mt + m < m_end;
-                rb[r] = ldg_safe4<float>(g.B + (ok ? mt + m : 0) * g.ldb, ok, n0 + 4 * cqb, g.N);
+                rb[r] = ldg_safe4<float>(Bop + (ok ? mt + m : 0) * ldb, ok, n0 + 4 * cqb, g.N);
             }
         }
     };
     auto stage = [&](int64_t mt) {
         const bool full = mt + BK <= m_end;
-        if (VEC && full && !A_BF16) {
+        if (VEC && full && !a_is_bf16) {
 #pragma unroll
             for (int r = 0; r < A_REPS; ++r) *reinterpret_cast<uint4*>(as_w + RA * r * PA) = ra[r];
         } else {
 #pragma unroll
             for (int r = 0; r < A_REPS; ++r) {
                 float v[4];
-                unpack4(ra[r], VEC && A_BF16, v);
+                unpack4(ra[r], VEC && a_is_bf16, v);
                 if (VEC && mt + ma + RA * r >= m_end) { v[0] = v[1] = v[2] = v[3] = 0.f; }
                 *reinterpret_cast<float4*>(as_w + RA * r * PA) = make_float4(v[0], v[1], v[2], v[3]);
             }
@@ -945,7 +974,10 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
     }
 
     const int li = lane & 31, lk = lane >> 5;
-    float* o = out + (int64_t)split * out_split_stride;
+    // Partial tiles (out2 null): the second product's rows follow the first's K rows (dual = 1) or its
+    // columns follow the first's N columns (dual = 2).  Direct output: out2 is the second matrix.
+    float* o = (op2 && out2 ? out2 : out) + (int64_t)split * out_split_stride;
+    if (op2 && !out2) o += a2 ? (int64_t)g.K * out_ld : (int64_t)g.N;
     const int colb = n0 + wn * TN * 32 + TN * li;     // first of this lane's TN interleaved columns
     const bool pair = TN == 2 && out_ld % 2 == 0 && ((uintptr_t)o % 8) == 0 && colb + 1 < g.N;
 #pragma unroll
@@ -975,14 +1007,34 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
     }
 }
 
+// Where element (row, col) of the reduced partials goes: rows [0, K) x cols [0, N) -> C; with two
+// products the second one's rows [K, 2K) (dual = 1) or columns [N, 2N) (dual = 2) -> C2; the last row
+// holds the column sums of B (its first N columns).
+__device__ __forceinline__ void tn_store(int64_t e, float val, int K, int N, int dual, float* __restrict__ C,
+                                         float* __restrict__ C2, int64_t ldc, float* __restrict__ colsum_out) {
+    const int width = dual == 2 ? 2 * N : N;
+    const int64_t row = e / width;
+    const int col = (int)(e % width);
+    const int krows = dual == 1 ? 2 * K : K;
+    if (row >= krows) {
+        if (colsum_out && col < N) colsum_out[col] = val;
+    } else if (dual == 1 && row >= K) {
+        C2[(row - K) * ldc + col] = val;
+    } else if (dual == 2 && col >= N) {
+        C2[row * ldc + (col - N)] = val;
+    } else {
+        C[row * ldc + col] = val;
+    }
+}
+
 // C[e] = sum_p part[p][e], p ascending.  Four partial tiles are requested before the first is
 // added (the adds stay in split order, so the result is the plain sequential sum).
 __global__ __launch_bounds__(256) void tn_reduce_kernel(const float* __restrict__ part, int splits, int K, int N,
                                                         int64_t part_stride, float* __restrict__ C, int64_t ldc,
-                                                        float* __restrict__ colsum_out) {
+                                                        float* __restrict__ colsum_out, int dual, float* __restrict__ C2,
+                                                        int64_t total) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t rows = colsum_out ? K + 1 : K;      // the partials carry the column sums as row K
-    if (e >= rows * N) return;
+    if (e >= total) return;                           // total = (rows of products + the column-sum row) x width
     const float* p0 = part + e;
     float s = 0.f;
     int p = 0;
@@ -992,8 +1044,7 @@ __global__ __launch_bounds__(256) void tn_reduce_kernel(const float* __restrict_
         s += a; s += b; s += c; s += d;
     }
     for (; p < splits; ++p) s += p0[(int64_t)p * part_stride];
-    if (e / N < K) C[(e / N) * ldc + (e % N)] = s;
-    else colsum_out[e % N] = s;
+    tn_store(e, s, K, N, dual, C, C2, ldc, colsum_out);
 }
 
 // The same sum for partials whose stride allows 16-byte loads: a workgroup owns 64 elements,
@@ -1001,11 +1052,10 @@ __global__ __launch_bounds__(256) void tn_reduce_kernel(const float* __restrict_
 // group sums are then added in ascending order: a fixed association, so still deterministic.
 __global__ __launch_bounds__(256) void tn_reduce_vec_kernel(const float* __restrict__ part, int splits, int K, int N,
                                                             int64_t part_stride, float* __restrict__ C, int64_t ldc,
-                                                            float* __restrict__ colsum_out) {
+                                                            float* __restrict__ colsum_out, int dual, float* __restrict__ C2,
+                                                            int64_t total) {           // total: a multiple of 4
     __shared__ float4 red[16][16];
     const int c = threadIdx.x & 15, grp = threadIdx.x >> 4;
-    const int64_t rows = colsum_out ? K + 1 : K;
-    const int64_t total = rows * N;                    // a multiple of 4
     const int64_t e = ((int64_t)blockIdx.x * 16 + c) * 4;
     const int per = (splits + 15) / 16;
     const int p_begin = grp * per, p_end = p_begin + per < splits ? p_begin + per : splits;
@@ -1035,11 +1085,7 @@ __global__ __launch_bounds__(256) void tn_reduce_vec_kernel(const float* __restr
         for (int u = 1; u < 16; ++u) { const float4 v = red[u][c]; t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w; }
         const float tv[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int64_t eq = e + q;
-            if (eq / N < K) C[(eq / N) * ldc + (eq % N)] = tv[q];
-            else colsum_out[eq % N] = tv[q];
-        }
+        for (int q = 0; q < 4; ++q) tn_store(e + q, tv[q], K, N, dual, C, C2, ldc, colsum_out);
     }
 }
 
@@ -1048,11 +1094,10 @@ __global__ __launch_bounds__(256) void tn_reduce_vec_kernel(const float* __restr
 // order, the 4 group sums are added in ascending order.
 __global__ __launch_bounds__(256) void tn_reduce_4way_kernel(const float* __restrict__ part, int splits, int K, int N,
                                                              int64_t part_stride, float* __restrict__ C, int64_t ldc,
-                                                             float* __restrict__ colsum_out) {
+                                                             float* __restrict__ colsum_out, int dual, float* __restrict__ C2,
+                                                             int64_t total) {
     __shared__ float red[4][64];
     const int c = threadIdx.x & 63, grp = threadIdx.x >> 6;
-    const int64_t rows = colsum_out ? K + 1 : K;
-    const int64_t total = rows * N;
     const int64_t e = (int64_t)blockIdx.x * 64 + c;
     const int per = (splits + 3) / 4;
     const int p_begin = grp * per, p_end = p_begin + per < splits ? p_begin + per : splits;
@@ -1071,67 +1116,81 @@ __global__ __launch_bounds__(256) void tn_reduce_4way_kernel(const float* __rest
     __syncthreads();
     if (grp == 0 && e < total) {
         const float t = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
-        if (e / N < K) C[(e / N) * ldc + (e % N)] = t;
-        else colsum_out[e % N] = t;
+        tn_store(e, t, K, N, dual, C, C2, ldc, colsum_out);
     }
 }
 
 template <typename AT, bool VEC, bool GATHER>
-static void tn_pick(const GemmTNArgs& a, const TnPlan& p, float* out, int64_t out_ld, int64_t stride, float* cs_out,
-                    int64_t cs_stride, hipStream_t st) {
-    const unsigned blocks = (unsigned)(NXCD * p.tiles_k * p.tiles_n * cdiv(p.splits, NXCD));
+static void tn_pick(const GemmTNArgs& a, const TnPlan& p, int dual, float* out, float* out2, int64_t out_ld, int64_t stride,
+                    float* cs_out, hipStream_t st) {
+    const unsigned blocks = (unsigned)(NXCD * p.tiles_k * p.tiles_n * (dual ? 2 : 1) * cdiv(p.splits, NXCD));
     dim3 grid(blocks);
     if (p.bn_tile == 128)
-        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, 2, 2, 2, 2>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, p.splits, p.chunk, out, out_ld, stride, cs_out, cs_stride);
+        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, 2, 2, 2, 2>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, dual, p.splits, p.chunk, out, out2, out_ld, stride, cs_out, stride);
     else if (p.bn_tile == 64)
-        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, 4, 1, 1, 2>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, p.splits, p.chunk, out, out_ld, stride, cs_out, cs_stride);
+        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, 4, 1, 1, 2>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, dual, p.splits, p.chunk, out, out2, out_ld, stride, cs_out, stride);
     else
-        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, 4, 1, 1, 1>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, p.splits, p.chunk, out, out_ld, stride, cs_out, cs_stride);
+        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, 4, 1, 1, 1>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, dual, p.splits, p.chunk, out, out2, out_ld, stride, cs_out, stride);
 }
 
+// One launch computes C = A^T B and, when a second operand is given, C2 = A2^T B (a.A2) or
+// C2 = A^T B2 (a.B2); C2 has C's shape and leading dimension.  A2 is fp32 and never gathered.
 grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st) {
     if (a.K <= 0 || a.N <= 0 || a.M < 0 || !a.C) return fail(GRP_EINVAL, "gemm_tn: bad arguments");
     if (a.M > 0 && (!a.A || !a.B)) return fail(GRP_EINVAL, "gemm_tn: null operand");
-    const TnPlan p = tn_plan(a.M, a.K, a.N);
-    const size_t need = p.splits > 1 ? (size_t)p.splits * (a.K + 1) * a.N * sizeof(float) : 0;
+    if (a.A2 && a.B2) return fail(GRP_EINVAL, "gemm_tn: at most one second operand");
+    const int dual = a.A2 ? 1 : (a.B2 ? 2 : 0);
+    if (dual && !a.C2) return fail(GRP_EINVAL, "gemm_tn: second product without an output");
+    const TnPlan p = tn_plan(a.M, a.K, a.N, dual ? 2 : 1);
+    // partial tiles of one slice: the products' rows (dual = 1: 2K) by their columns (dual = 2: 2N), then
+    // one more row for the column sums of B
+    const int64_t krows = dual == 1 ? 2 * (int64_t)a.K : a.K;
+    const int64_t width = dual == 2 ? 2 * (int64_t)a.N : a.N;
+    const int64_t stride = p.splits > 1 ? (krows + 1) * width : 0;
+    const size_t need = (size_t)p.splits * stride * sizeof(float);
     if (need > a.workspace_bytes || (need && !a.workspace))
         return fail(GRP_EWORKSPACE, "gemm_tn: workspace %zu < %zu bytes", a.workspace_bytes, need);
     const int elem = a.a_bf16 ? 2 : 4;
     // vector path: 16-byte friendly operands whose 32-row steps fit 32-bit element offsets
     const bool veca = a.M > 0 && a.lda % 4 == 0 && a.lda >= round_up(a.K, 4) && (uintptr_t)a.A % (4 * elem) == 0 && a.lda < (1 << 25);
     const bool vecb = a.M > 0 && a.ldb % 4 == 0 && a.ldb >= round_up(a.N, 4) && (uintptr_t)a.B % 16 == 0 && a.ldb < (1 << 25);
-    const int64_t stride = p.splits > 1 ? (int64_t)(a.K + 1) * a.N : 0;
+    const bool veca2 = !a.A2 || (a.lda2 % 4 == 0 && a.lda2 >= round_up(a.K, 4) && (uintptr_t)a.A2 % 16 == 0 && a.lda2 < (1 << 25));
+    const bool vecb2 = !a.B2 || (a.ldb2 % 4 == 0 && a.ldb2 >= round_up(a.N, 4) && (uintptr_t)a.B2 % 16 == 0 && a.ldb2 < (1 << 25));
     float* out = p.splits > 1 ? (float*)a.workspace : a.C;
-    const int64_t out_ld = p.splits > 1 ? a.N : a.ldc;
-    float* cs_out = !a.colsum_out ? nullptr : (p.splits > 1 ? (float*)a.workspace + (int64_t)a.K * a.N : a.colsum_out);
+    float* out2 = p.splits > 1 ? nullptr : a.C2;
+    const int64_t out_ld = p.splits > 1 ? width : a.ldc;
+    float* cs_out = !a.colsum_out ? nullptr : (p.splits > 1 ? (float*)a.workspace + krows * width : a.colsum_out);
     {
-        prof_detail("[M=%lld,K=%d,N=%d%s]", (long long)a.M, a.K, a.N, a.colsum_out ? ",colsum" : "");
-        ProfScope ps(a.a_bf16 ? "gemm_tn_bf16a" : "gemm_tn_f32", st, 2.0 * a.M * a.K * a.N,
-                     (double)a.M * a.K * elem + 4.0 * a.M * a.N + 4.0 * a.K * a.N);
-        const bool vec = veca && vecb;
+        prof_detail("[M=%lld,K=%d,N=%d%s%s]", (long long)a.M, a.K, a.N, a.colsum_out ? ",colsum" : "",
+                    dual == 1 ? ",A2" : (dual == 2 ? ",B2" : ""));
+        const double prods = dual ? 2.0 : 1.0;
+        ProfScope ps(a.a_bf16 ? "gemm_tn_bf16a" : "gemm_tn_f32", st, 2.0 * prods * a.M * a.K * a.N,
+                     (double)a.M * a.K * (elem + (dual == 1 ? 4 : 0)) + 4.0 * a.M * a.N * (dual == 2 ? 2 : 1) + 4.0 * prods * a.K * a.N);
+        const bool vec = veca && vecb && veca2 && vecb2;
         if (a.a_bf16) {
-            if (vec && !a.a_rows) tn_pick<__hip_bfloat16, true, false>(a, p, out, out_ld, stride, cs_out, stride, st);
-            else if (vec) tn_pick<__hip_bfloat16, true, true>(a, p, out, out_ld, stride, cs_out, stride, st);
-            else tn_pick<__hip_bfloat16, false, true>(a, p, out, out_ld, stride, cs_out, stride, st);
+            if (vec && !a.a_rows) tn_pick<__hip_bfloat16, true, false>(a, p, dual, out, out2, out_ld, stride, cs_out, st);
+            else if (vec) tn_pick<__hip_bfloat16, true, true>(a, p, dual, out, out2, out_ld, stride, cs_out, st);
+            else tn_pick<__hip_bfloat16, false, true>(a, p, dual, out, out2, out_ld, stride, cs_out, st);
         } else {
-            if (vec && !a.a_rows) tn_pick<float, true, false>(a, p, out, out_ld, stride, cs_out, stride, st);
-            else if (vec) tn_pick<float, true, true>(a, p, out, out_ld, stride, cs_out, stride, st);
-            else tn_pick<float, false, true>(a, p, out, out_ld, stride, cs_out, stride, st);
+            if (vec && !a.a_rows) tn_pick<float, true, false>(a, p, dual, out, out2, out_ld, stride, cs_out, st);
+            else if (vec) tn_pick<float, true, true>(a, p, dual, out, out2, out_ld, stride, cs_out, st);
+            else tn_pick<float, false, true>(a, p, dual, out, out2, out_ld, stride, cs_out, st);
         }
         GRP_LAUNCH_CHECK();
     }
     if (p.splits > 1) {
-        ProfScope ps("gemm_tn_reduce", st, 0.0, 4.0 * a.K * a.N * (p.splits + 1.0));
-        const int64_t rows = a.colsum_out ? a.K + 1 : a.K;
-        if (stride % 4 == 0 && (rows * a.N) % 4 == 0 && (uintptr_t)a.workspace % 16 == 0 && p.splits >= 16) {
-            hipLaunchKernelGGL(tn_reduce_vec_kernel, dim3((unsigned)cdiv(rows * a.N, 64)), dim3(256), 0, st,
-                               (const float*)a.workspace, p.splits, a.K, a.N, stride, a.C, a.ldc, a.colsum_out);
+        const int64_t total = krows * width + (a.colsum_out ? a.N : 0);
+        ProfScope ps("gemm_tn_reduce", st, 0.0, 4.0 * total * (p.splits + 1.0));
+        const float* part = (const float*)a.workspace;
+        if (stride % 4 == 0 && total % 4 == 0 && (uintptr_t)a.workspace % 16 == 0 && p.splits >= 16) {
+            hipLaunchKernelGGL(tn_reduce_vec_kernel, dim3((unsigned)cdiv(total, 64)), dim3(256), 0, st, part, p.splits, a.K,
+                               a.N, stride, a.C, a.ldc, a.colsum_out, dual, a.C2, total);
         } else if (p.splits >= 16) {
-            hipLaunchKernelGGL(tn_reduce_4way_kernel, dim3((unsigned)cdiv(rows * a.N, 64)), dim3(256), 0, st,
-                               (const float*)a.workspace, p.splits, a.K, a.N, stride, a.C, a.ldc, a.colsum_out);
+            hipLaunchKernelGGL(tn_reduce_4way_kernel, dim3((unsigned)cdiv(total, 64)), dim3(256), 0, st, part, p.splits, a.K,
+                               a.N, stride, a.C, a.ldc, a.colsum_out, dual, a.C2, total);
         } else {
-            hipLaunchKernelGGL(tn_reduce_kernel, dim3((unsigned)cdiv(rows * a.N, 256)), dim3(256), 0, st,
-                               (const float*)a.workspace, p.splits, a.K, a.N, stride, a.C, a.ldc, a.colsum_out);
+            hipLaunchKernelGGL(tn_reduce_kernel, dim3((unsigned)cdiv(total, 256)), dim3(256), 0, st, part, p.splits, a.K,
+                               a.N, stride, a.C, a.ldc, a.colsum_out, dual, a.C2, total);
         }
         GRP_LAUNCH_CHECK();
     }

@@ -278,11 +278,15 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
         t.M = B.n_dst; t.K = fin; t.N = fout; t.A = Hin; t.lda = ldin; t.a_bf16 = in_bf16; t.a_rows = B.self_rows;
         t.B = dZ; t.ldb = ldp(fout); t.C = grad + L.off_ws; t.ldc = fout; t.workspace = p.tn_ws; t.workspace_bytes = p.tn_ws_bytes;
         t.colsum_out = grad + L.off_b;
-        GRP_TRY(launch_gemm_tn(t, st));
-        t.colsum_out = nullptr;
+        // the same rows of the input feed both weight gradients of a transform-first layer
+        const bool shared_rows = !L.agg_first && B.n_in == B.n_dst && !B.self_rows;
         if (L.agg_first) {
-            t.A = L.M; t.lda = ldp(fin); t.a_bf16 = 0; t.a_rows = nullptr; t.C = grad + L.off_wn;
+            t.A2 = L.M; t.lda2 = ldp(fin); t.C2 = grad + L.off_wn;       // dW_neigh = M^T dZ in the same launch
             GRP_TRY(launch_gemm_tn(t, st));
+        } else if (!shared_rows) {
+            GRP_TRY(launch_gemm_tn(t, st));
+        }
+        if (L.agg_first) {
             if (l > 0 && B.n_in > 0) {
                 // [dM' | dS] = dZ [Wn^T | Ws^T], dM' rows divided by |N_v|, in one pass over dZ;
                 // then dZ_prev = mask * (A^T dM' + [dS ; 0]) in the aggregation's epilogue.
@@ -306,8 +310,12 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             fill_spmm(s, B, true, p.partials);
             s.F = fout; s.X = dZ; s.ldx = ldp(fout); s.colscale = B.inv_in; s.Y = p.tmpA; s.ldy = ldp(fout);
             GRP_TRY(launch_spmm(s, st));
-            t.M = B.n_in; t.A = Hin; t.lda = ldin; t.a_bf16 = in_bf16; t.a_rows = nullptr;
-            t.B = p.tmpA; t.C = grad + L.off_wn;
+            if (shared_rows) {     // [dW_self | dW_neigh] = H^T [dZ | dT] in one launch
+                t.B2 = p.tmpA; t.ldb2 = ldp(fout); t.C2 = grad + L.off_wn;
+            } else {
+                t.colsum_out = nullptr;
+                t.M = B.n_in; t.a_rows = nullptr; t.B = p.tmpA; t.C = grad + L.off_wn;
+            }
             GRP_TRY(launch_gemm_tn(t, st));
             if (l > 0 && B.n_in > 0) {
                 GemmNNArgs c;      // dZ_prev = mask * ([dZ Ws^T ; 0] + dT Wn^T)
