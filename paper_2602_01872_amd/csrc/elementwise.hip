@@ -103,22 +103,22 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const float* __rest
     }
 }
 
-// out[c] = sum_b part[b][c]: 32 columns per workgroup, 8 lanes per column take the blocks
-// b = j, j + 8, ... and are added in lane order.
+// out[c] = sum_b part[b][c]: 8 columns per workgroup, 32 lanes per column take the blocks
+// b = j, j + 32, ... and are added in lane order.
 __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, int64_t blocks, int N,
                                                            float* __restrict__ out) {
-    __shared__ float red[8][32];
-    const int cl = threadIdx.x & 31, j = threadIdx.x >> 5;
-    const int c = blockIdx.x * 32 + cl;
+    __shared__ float red[32][8];
+    const int cl = threadIdx.x & 7, j = threadIdx.x >> 3;
+    const int c = blockIdx.x * 8 + cl;
     float s = 0.f;
     if (c < N)
-        for (int64_t b = j; b < blocks; b += 8) s += part[b * N + c];
+        for (int64_t b = j; b < blocks; b += 32) s += part[b * N + c];
     red[j][cl] = s;
     __syncthreads();
     if (j == 0 && c < N) {
         float t = 0.f;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) t += red[q][cl];
+        for (int q = 0; q < 32; ++q) t += red[q][cl];
         out[c] = t;
     }
 }
@@ -164,7 +164,7 @@ grp_status launch_colsum_scaled(const float* A, int64_t M, int32_t N, int64_t ld
         hipLaunchKernelGGL(colsum_partial_kernel, dim3((unsigned)blocks), dim3(256), 0, st, A, M, N, lda, rowmul,
                            (float*)scratch);
     GRP_LAUNCH_CHECK();
-    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)cdiv(N, 32)), dim3(256), 0, st, (const float*)scratch,
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)cdiv(N, 8)), dim3(256), 0, st, (const float*)scratch,
                        blocks, N, out);
     GRP_LAUNCH_CHECK();
     return GRP_OK;

@@ -52,18 +52,51 @@ __global__ __launch_bounds__(256) void gat_extract_pq_kernel(const float* __rest
 }
 
 // Row statistics of the attention softmax: rowstat[v] = (m_v, Z_v) = (max_u e_uv, sum_u exp(e_uv - m_v)),
-// self term included.  Scalars only (p and q sit in L2), so rows of any length are cheap here.
+// self term included.  Scalars only (p and q sit in L2).  The first n_long workgroups each take one
+// row longer than long_thr edges with all 256 threads (partial results combined through LDS in a
+// fixed order); the others give 16 lanes to a row and skip the long ones.
 __global__ __launch_bounds__(256) void gat_stats_kernel(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx,
                                                         int64_t n, const float2* __restrict__ pq,
-                                                        float2* __restrict__ rowstat) {
+                                                        float2* __restrict__ rowstat, const int32_t* __restrict__ long_row,
+                                                        int n_long, int64_t long_thr) {
     constexpr int G = 16;
+    if ((int)blockIdx.x < n_long) {
+        __shared__ float red[4];
+        const int64_t v = long_row[blockIdx.x];
+        const int64_t b = ptr[v], e = ptr[v + 1];
+        const float2 pqv = pq[v];
+        const float es = leaky(pqv.x + pqv.y);
+        const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+        auto score = [&](int64_t k) { return k < e ? leaky(pq[idx[k]].x + pqv.y) : -INFINITY; };
+        float mx = es;
+        for (int64_t k = b + tid; k < e; k += 4 * 256) {
+            const float s0 = score(k), s1 = score(k + 256), s2 = score(k + 512), s3 = score(k + 768);
+            mx = fmaxf(fmaxf(mx, fmaxf(s0, s1)), fmaxf(s2, s3));
+        }
+        mx = group_max<64>(mx);
+        if (lane == 0) red[wave] = mx;
+        __syncthreads();
+        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        __syncthreads();
+        float sum = 0.f;
+        for (int64_t k = b + tid; k < e; k += 4 * 256) {
+            const float s0 = score(k), s1 = score(k + 256), s2 = score(k + 512), s3 = score(k + 768);
+            sum += __expf(s0 - mx); sum += __expf(s1 - mx); sum += __expf(s2 - mx); sum += __expf(s3 - mx);
+        }
+        sum = group_sum<64>(sum);
+        if (lane == 0) red[wave] = sum;
+        __syncthreads();
+        if (tid == 0) rowstat[v] = make_float2(mx, ((red[0] + red[1]) + (red[2] + red[3])) + __expf(es - mx));
+        return;
+    }
     const int t = threadIdx.x % G;
-    const int64_t v = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
+    const int64_t v = ((int64_t)blockIdx.x - n_long) * (256 / G) + threadIdx.x / G;
     if (v >= n) return;               // whole groups leave together
     const int64_t b = ptr[v], e = ptr[v + 1];
+    if (e - b > long_thr) return;     // done by one of the first workgroups
     const float2 pqv = pq[v];
     const float es = leaky(pqv.x + pqv.y);
-    // four independent index -> score gathers per lane and trip keep long rows from serialising
+    // four independent index -> score gathers per lane and trip
     auto score = [&](int64_t k) { return k < e ? leaky(pq[idx[k]].x + pqv.y) : -INFINITY; };
     float mx = es;
     for (int64_t k = b + t; k < e; k += 4 * G) {
@@ -540,8 +573,9 @@ grp_status gat_step(const grp_partition_t* g, const grp_model_desc* m, const grp
         {
             ProfScope ps("gat_forward", st, 2.0 * g->nnz * L.fout, 4.0 * g->nnz + 8.0 * L.fout * n);
             hipLaunchKernelGGL(gat_extract_pq_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, L.Tx, L.ldx, (int)L.ldh, n, L.pq);
-            hipLaunchKernelGGL(gat_stats_kernel, dim3((unsigned)cdiv(n, 16)), dim3(256), 0, st, g->rowptr, g->col, n,
-                               (const float2*)L.pq, L.rowstat);
+            hipLaunchKernelGGL(gat_stats_kernel, dim3((unsigned)(cdiv(n, 16) + g->csr_long.n_long)), dim3(256), 0, st,
+                               g->rowptr, g->col, n, (const float2*)L.pq, L.rowstat, g->csr_long.long_row,
+                               g->csr_long.n_long, (int64_t)SPMM_LONG_ROW);
             GRP_LAUNCH_CHECK();
             GatWalk A{};
             A.ptr = g->rowptr; A.idx = g->col; A.n = n; A.F = L.fout; A.Tx = L.Tx; A.ldx = L.ldx; A.pq = L.pq;
