@@ -15,6 +15,8 @@ Modules
                model descriptions in the experimental setup; the true-gradient equation)
     gat        graph attention layers (one head) and their reverse pass              (the
                third model of the experimental setup)
+    dropout    counter-based keep masks of the hidden layers                         (the
+               hyper-parameters of the experimental setup)
     coverage   node-level weights, the minimum-distance factor, the shrinkage factor
                and the scale-then-reduce aggregation                           (section
                "Coverage-Corrected Aggregation"; the phase-parallel algorithm)

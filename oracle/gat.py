@@ -87,10 +87,11 @@ def _layer_backward(h, esrc, edst, n, w, a_s, a_d, saved, dout, need_dh):
 
 
 def forward_backward(dims, theta, x, blk, labels, node_w, loss_nodes, return_logits=False,
-                     relu_flip=None, near_kink=None):
+                     relu_flip=None, near_kink=None, drop=None):
     """Loss and flat gradient of a k-layer GAT on the full local graph ``blk`` (n_src = n_dst).
 
-    ``relu_flip`` / ``near_kink`` as in ``gnn.forward_backward``.
+    ``relu_flip`` / ``near_kink`` / ``drop`` as in ``gnn.forward_backward`` (dropout acts on the
+    layer outputs only; the attention coefficients are not dropped).
     """
     if blk["n_src"] != blk["n_dst"]:
         raise ValueError("GAT layers are defined on the full local graph only")
@@ -106,6 +107,8 @@ def forward_backward(dims, theta, x, blk, labels, node_w, loss_nodes, return_log
         saved.append(sv)
         zs.append(z)
         h = z if l == k - 1 else np.maximum(z, 0.0)
+        if drop and l < k - 1:
+            h = h * drop[l]
     logits = h
     loss, dz = softmax_xent(logits, labels, node_w, loss_nodes)
     grads = [None] * k
@@ -120,6 +123,8 @@ def forward_backward(dims, theta, x, blk, labels, node_w, loss_nodes, return_log
                 if fl == l:
                     mask[fr, fc] = not mask[fr, fc]
             dzl = dh_next * mask
+            if drop:
+                dzl = dzl * drop[l]
         g, dh = _layer_backward(hs[l], esrc, edst, n, w, a_s, a_d, saved[l], dzl, l > 0)
         grads[l] = g
         dh_next = dh

@@ -19,7 +19,9 @@ Readings where the paper is silent:
                  degrees are clamped to at least 1.
   * residual GCN: h^{l+1} = h^l + ReLU(z^l) where the two widths agree (never on the
                  last layer); not in the paper, defined by the workload list.
-  * dropout is off.
+  * dropout (off unless factors are passed in): the activation of hidden layer l is multiplied
+    elementwise by ``drop[l]`` = keep / (1 - rate) before a residual skip is added; see
+    ``dropout.py`` for how keep is drawn.
   * the derivative of ReLU is 1 where the pre-activation z > 0 and 0 elsewhere.  A
     pre-activation within rounding distance of 0 makes that decision depend on the
     precision and summation order of whoever computes z, so ``forward_backward`` can list
@@ -176,7 +178,7 @@ def _gcn_backward(h, blk, w, saved, dz, need_dh, self_loops):
 
 
 def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
-                     gcn_self_loops=True, return_logits=False, relu_flip=None, near_kink=None):
+                     gcn_self_loops=True, return_logits=False, relu_flip=None, near_kink=None, drop=None):
     """Loss and flat parameter gradient of a k-layer model.
 
     ``blocks`` has one block per layer (input side first); pass the same block k times for
@@ -185,6 +187,7 @@ def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
     ``relu_flip``: iterable of (layer, row, col) whose ReLU derivative is inverted.
     ``near_kink``: a guard g; the call then also returns the list of (layer, row, col) of
     hidden pre-activations with |z| <= g * rms(z of that layer).
+    ``drop``: per hidden layer the factor array keep / (1 - rate) of its output ([] or None: no dropout).
     """
     if arch not in ARCHS:
         raise ValueError("unknown arch")
@@ -208,6 +211,8 @@ def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
             h = z
         else:
             a = np.maximum(z, 0.0)
+            if drop:
+                a = a * drop[l]
             if arch == "gcn_res" and dims[l] == dims[l + 1]:
                 a = h[:blk["n_dst"]] + a
             h = a
@@ -228,6 +233,8 @@ def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
                 if fl == l:
                     mask[fr, fc] = not mask[fr, fc]
             dzl = dh_next * mask
+            if drop:
+                dzl = dzl * drop[l]
             if arch == "gcn_res" and dims[l] == dims[l + 1]:
                 skip = dh_next
         need_dh = l > 0

@@ -8,12 +8,13 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import coverage, gat, gnn, sampling
+from . import coverage, dropout as dropout_mod, gat, gnn, sampling
 
 
 def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
                estimator: int = coverage.NONE, gcn_self_loops: bool = True,
-               minibatch: dict | None = None, relu_flip=None, near_kink=None):
+               minibatch: dict | None = None, relu_flip=None, near_kink=None,
+               dropout: dict | None = None):
     """Returns (grad[P] float64, stats dict) for one partition.
 
     full-graph mode (``minibatch is None``): every local node is an input, the loss runs
@@ -23,12 +24,20 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
     side, so the seeds draw fanouts[k-1] neighbours.
     ``relu_flip`` / ``near_kink`` are passed to ``gnn.forward_backward``; with ``near_kink`` the
     stats dict gains the key "near_kink".
+    ``dropout = dict(rate=, seed=, batch_id=)`` (full-graph mode only) drops hidden activations as
+    ``dropout.py`` describes, keyed on the nodes' global ids ``part["l2g"]``.
     """
     n = part["n"]
     k = len(dims) - 1
     dl, dg = part["d_local_in"], part["d_global_in"]
     w_all = coverage.node_weights(dl, dg) if estimator == coverage.NODE_LEVEL else np.ones(n)
 
+    drop = None
+    if dropout is not None and float(dropout["rate"]) != 0.0:
+        if minibatch is not None:
+            raise ValueError("dropout is defined for full-graph steps only")
+        drop = dropout_mod.layer_factors(dropout["seed"], dropout.get("batch_id", 0), part["l2g"], dims,
+                                         dropout["rate"])
     if minibatch is None:
         blk = gnn.block_from_csr(part["rowptr"], part["col"])
         if train_mask is None:
@@ -37,10 +46,10 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
             loss_nodes = np.flatnonzero(np.asarray(train_mask) != 0).astype(np.int64)
         if arch == "gat":
             res = gat.forward_backward(dims, theta, x, blk, labels, w_all, loss_nodes,
-                                       relu_flip=relu_flip, near_kink=near_kink)
+                                       relu_flip=relu_flip, near_kink=near_kink, drop=drop)
         else:
             res = gnn.forward_backward(arch, dims, theta, x, [blk] * k, labels, w_all, loss_nodes,
-                                       gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink)
+                                       gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink, drop=drop)
         loss, grad = res[0], res[1]
         st = coverage.coverage_stats(dl, dg, loss_nodes, None)
         if near_kink is not None:
