@@ -130,18 +130,20 @@ def run_evidence_workload(args, g, synth, torch, dev):
         print(json.dumps(out), flush=True)
         return
 
-    if wl == "c2-gat-step":
-        # the headline workload's partition with the attention model in place of GraphSAGE
+    if wl in ("c2-gat-step", "c2-dropout-step"):
+        # the headline workload's partition with the attention model in place of GraphSAGE, or with
+        # GraphSAGE and dropout 0.5 on the hidden layers
         src, dst = synth.rmat_graph(RMAT_SCALE, N_EDGES, seed=GRAPH_SEED, n_nodes=N_NODES, device=dev)
         part = g.grp_partition(src, dst, N_NODES, K_PARTS, PART_SEED, PART_ID)
         del src, dst
         l2g = torch.from_numpy(part.array("l2g")).to(dev)
         dims = [100, 256, 256, 47]
-        model = g.model_desc(g.ARCH_GAT, dims)
-        opts = g.step_opts(estimator=g.EST_SHRINKAGE, full_graph=True)
+        gat = wl == "c2-gat-step"
+        model = g.model_desc(g.ARCH_GAT if gat else g.ARCH_SAGE_MEAN, dims)
+        opts = g.step_opts(estimator=g.EST_SHRINKAGE, full_graph=True, dropout_rate=0.0 if gat else 0.5, dropout_seed=1)
         x = synth.normal_matrix(N_NODES, dims[0], GRAPH_SEED, device=dev)[l2g].contiguous()
         y = synth.labels(N_NODES, dims[-1], GRAPH_SEED, device=dev)[l2g].contiguous()
-        theta = synth.model_weights("gat", dims, GRAPH_SEED, device=dev)
+        theta = synth.model_weights("gat" if gat else "sage", dims, GRAPH_SEED, device=dev)
         P = g.grp_param_count(model)
         grad = torch.zeros((P + 3) // 4 * 4, device=dev)
         stats = g.new_stats(1, device=dev)
@@ -151,8 +153,10 @@ def run_evidence_workload(args, g, synth, torch, dev):
         kernels = _kernel_table(g, torch, fn, args.steps)
         out.update(metric="per-partition train-step edges/s (fwd+bwd)", unit="edges/s", value=part.nnz / dt,
                    ms_per_step=dt * 1e3, dtype="f32",
-                   config={"workload": f"c2-gat-step: GAT-3 (one head) {dims}, partition 0 of 8 of the R-MAT 2.4M-node / "
-                                       f"62M-edge graph, n={part.n}, nnz={part.nnz}", "params": P},
+                   config={"workload": (f"c2-gat-step: GAT-3 (one head) {dims}" if gat else
+                                        f"c2-dropout-step: SAGE-mean-3 {dims} with dropout 0.5") +
+                                       f", partition 0 of 8 of the R-MAT 2.4M-node / 62M-edge graph, n={part.n}, nnz={part.nnz}",
+                           "params": P},
                    roofline=_roofline(kernels, {}), kernels=kernels)
         print(json.dumps(out), flush=True)
         return
@@ -247,7 +251,7 @@ def main():
     ap.add_argument("--small", action="store_true", help="scaled-down graph (debugging only; not a valid result)")
     ap.add_argument("--shapes", action="store_true", help="per-launch-shape kernel table on stderr (debugging)")
     ap.add_argument("--workload", default="c2-step",
-                    choices=["c2-step", "c2-gat-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "aggregate-stress"],
+                    choices=["c2-step", "c2-gat-step", "c2-dropout-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "aggregate-stress"],
                     help="c2-step (default) is the headline workload; the others are evidence runs for the other "
                          "configurations (each prints one JSON line of the same form)")
     ap.add_argument("--copy-calibration", action="store_true",

@@ -188,6 +188,9 @@ typedef struct {
     int32_t        fanouts[GRP_MAX_LAYERS]; /* fanouts[l] belongs to layer l, 0 = input side   */
     uint64_t       sampler_seed;
     uint64_t       batch_id;
+    float          dropout_rate;  /* in [0, 1); 0 = off.  Full-graph mode only (see below)     */
+    int32_t        reserved2;
+    uint64_t       dropout_seed;
 } grp_step_opts;
 
 /* Written to DEV memory by grp_train_step (one record per partition). */
@@ -218,6 +221,16 @@ grp_status grp_step_workspace_bytes(const grp_partition_t* part, const grp_model
  *   stats_out  DEV grp_step_stats, overwritten
  * S = train_mask ∩ local nodes (full graph) or the seeds (mini-batch).  Deterministic:
  * no floating-point atomics; two calls with equal inputs give equal bits.
+ *
+ * Dropout (the experimental setup trains with dropout 0.5; the paper fixes nothing else about it):
+ * inverted dropout on the output of every layer but the last, after the ReLU (a residual layer
+ * drops the activation before the skip is added): a' = keep ? a / (1 - rate) : 0, with
+ *   key_l = mix(dropout_seed + (batch_id * GRP_MAX_LAYERS + l + 1) * 0x9E3779B97F4A7C15)
+ *   keep(v, f) = (mix(key_l + (l2g[v] * dims[l+1] + f + 1) * 0x9E3779B97F4A7C15) >> 40)
+ *                >= floor(dropout_rate * 2^24)
+ * in wrapping uint64 arithmetic (mix as in grp_partition), so a node's mask depends on its global
+ * id, not on the partition that holds it; 1 / (1 - rate) is taken in fp32.  The attention
+ * coefficients of GRP_ARCH_GAT are not dropped.  GRP_EUNSUPPORTED in mini-batch mode.
  *
  * Mini-batch mode (opts->full_graph = 0, GraphSAGE only): isolated k-hop sampling inside the
  * partition, then the same layers on the sampled blocks.  Sampling rule (the paper fixes

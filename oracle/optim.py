@@ -43,8 +43,11 @@ def phase_schedule(n_parts: int, max_active: int):
 
 
 def train_epochs(parts, arch, dims, theta0, xs, ys, masks, n_epochs, max_active, estimator,
-                 optimizer=ADAM, lr=0.003, gcn_self_loops=True):
+                 optimizer=ADAM, lr=0.003, gcn_self_loops=True, dropout=None):
     """The phase-parallel algorithm in full-graph mode (one iteration per phase and epoch).
+
+    ``dropout = dict(rate=, seed=)``: hidden-layer dropout; every partition of a phase draws its
+    masks with batch_id = the number of optimizer steps taken so far.
 
     ``parts`` are the partitions of one graph; ``xs[p]``, ``ys[p]``, ``masks[p]`` their
     features, labels and train masks (mask None = every node).  In every phase the active
@@ -64,7 +67,8 @@ def train_epochs(parts, arch, dims, theta0, xs, ys, masks, n_epochs, max_active,
             grads, stats = [], []
             for p in active:
                 g, st = step.train_step(parts[p], arch, dims, theta, xs[p], ys[p], masks[p],
-                                        estimator=estimator, gcn_self_loops=gcn_self_loops)
+                                        estimator=estimator, gcn_self_loops=gcn_self_loops,
+                                        dropout=None if dropout is None else dict(dropout, batch_id=t))
                 grads.append(g)
                 stats.append(st)
             G, _ = coverage.aggregate(grads, stats, estimator)

@@ -229,6 +229,7 @@ struct PackJob {
     int32_t rows, cols;      // shape of `in` (dense, pitch cols)
     int32_t transpose;       // 0: out = in;  1: out = in^T
     int64_t ld_out;
+    float scale;             // every element is multiplied by this
 };
 struct PackJobs {
     int32_t n = 0;
@@ -238,7 +239,24 @@ struct PackJobs {
 // Appends a job: the output is written with its columns zero-padded to a multiple of 4 and its
 // rows zero-padded to out_rows_pad.
 void pack_jobs_add(PackJobs& jobs, const float* in, int32_t rows, int32_t cols, bool transpose, int32_t out_rows_pad,
-                   float* out, int64_t ld_out);
+                   float* out, int64_t ld_out, float scale = 1.f);
+
+// Inverted dropout of a layer's output (rows = local nodes, F columns), in place:
+//   keep(v, f) = (mix(key + (l2g[v] * F + f + 1) * GAMMA) >> 40) >= thresh;  a' = keep ? a * scale : 0.
+// Plain layer: H holds the activation.  Residual layer (act != null): act holds the activation and
+// is overwritten with a'; H = a' + res.
+struct DropoutPlan {
+    bool on = false;
+    uint32_t thresh = 0;
+    float scale = 1.f;
+    uint64_t seed = 0, batch_id = 0;
+};
+DropoutPlan dropout_plan(const grp_step_opts* o);
+uint64_t dropout_layer_key(const DropoutPlan& d, int layer);
+grp_status launch_dropout(const DropoutPlan& d, int layer, const int64_t* l2g, int64_t n, int32_t F, float* H, int64_t ldh,
+                          float* act, int64_t ld_act, const float* res, int64_t ld_res, hipStream_t st);
+// out[i] = in[i] * s
+grp_status launch_scale_copy(const float* in, float s, float* out, int64_t n, hipStream_t st);
 grp_status launch_pack_weights(const PackJobs& jobs, hipStream_t st);
 
 // Graph attention model (full-graph mode): workspace size and the whole train step.

@@ -41,18 +41,19 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(PackJobs jobs) {
     if (J.transpose) {        // out[cols x rows] = in[rows x cols]^T; pad columns and rows [cols, out_rows_pad) are zero
         const int width = (J.rows + 3) & ~3;
         const int r = (int)(e / width), c = (int)(e % width);
-        J.out[(int64_t)r * J.ld_out + c] = (r < J.cols && c < J.rows) ? J.in[(int64_t)c * J.cols + r] : 0.f;
+        J.out[(int64_t)r * J.ld_out + c] = (r < J.cols && c < J.rows) ? J.in[(int64_t)c * J.cols + r] * J.scale : 0.f;
     } else {                  // out[rows x cols] = in; pad columns and rows [rows, out_rows_pad) are zero
         const int width = (J.cols + 3) & ~3;
         const int r = (int)(e / width), c = (int)(e % width);
-        J.out[(int64_t)r * J.ld_out + c] = (r < J.rows && c < J.cols) ? J.in[(int64_t)r * J.cols + c] : 0.f;
+        J.out[(int64_t)r * J.ld_out + c] = (r < J.rows && c < J.cols) ? J.in[(int64_t)r * J.cols + c] * J.scale : 0.f;
     }
 }
 
 void pack_jobs_add(PackJobs& jobs, const float* in, int32_t rows, int32_t cols, bool transpose, int32_t out_rows_pad,
-                   float* out, int64_t ld_out) {
+                   float* out, int64_t ld_out, float scale) {
     PackJob& J = jobs.job[jobs.n];
     J.in = in; J.out = out; J.rows = rows; J.cols = cols; J.transpose = transpose ? 1 : 0; J.ld_out = ld_out;
+    J.scale = scale;
     const int32_t out_rows = transpose ? cols : rows;
     if (out_rows_pad < out_rows) out_rows_pad = out_rows;
     const int64_t width = round_up(transpose ? rows : cols, 4);
@@ -64,6 +65,102 @@ grp_status launch_pack_weights(const PackJobs& jobs, hipStream_t st) {
     if (jobs.n == 0 || jobs.begin[jobs.n] == 0) return GRP_OK;
     ProfScope ps("pack_weights", st);
     hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)cdiv(jobs.begin[jobs.n], 256)), dim3(256), 0, st, jobs);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
+// ------------------------------------------------------------------ dropout
+// Output function and increment of SplitMix64 (Steele, Lea, Flood 2014).
+constexpr uint64_t SM64_GAMMA = 0x9E3779B97F4A7C15ull;
+__host__ __device__ static inline uint64_t sm64_mix(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+DropoutPlan dropout_plan(const grp_step_opts* o) {
+    DropoutPlan d;
+    if (o->dropout_rate > 0.f && o->dropout_rate < 1.f) {
+        d.on = true;
+        d.thresh = (uint32_t)(o->dropout_rate * 16777216.0f);      // exact: a power-of-two scaling, then truncation
+        d.scale = 1.0f / (1.0f - o->dropout_rate);
+        d.seed = o->dropout_seed;
+        d.batch_id = o->batch_id;
+    }
+    return d;
+}
+
+uint64_t dropout_layer_key(const DropoutPlan& d, int layer) {
+    return sm64_mix(d.seed + (d.batch_id * (uint64_t)GRP_MAX_LAYERS + (uint64_t)layer + 1ull) * SM64_GAMMA);
+}
+
+// One thread per 4 columns of a row.  VEC: every pitch is a multiple of 4 and every base 16-byte
+// aligned, so the 4 columns (pad columns included, which stay zero) move as one float4.
+template <bool VEC>
+__global__ __launch_bounds__(256) void dropout_kernel(const int64_t* __restrict__ l2g, int64_t n, int F, uint64_t key,
+                                                      uint32_t thresh, float scale, float* __restrict__ H, int64_t ldh,
+                                                      float* __restrict__ act, int64_t ld_act,
+                                                      const float* __restrict__ res, int64_t ld_res) {
+    const int C4 = (F + 3) / 4;
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n * C4) return;
+    const int64_t v = e / C4;
+    const int f0 = 4 * (int)(e % C4);
+    const uint64_t base = (uint64_t)l2g[v] * (uint64_t)F + (uint64_t)f0 + 1ull;
+    float m[4];                       // keep ? scale : 0
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        m[q] = (f0 + q < F && (uint32_t)(sm64_mix(key + (base + (uint64_t)q) * SM64_GAMMA) >> 40) >= thresh) ? scale : 0.f;
+    float* const src = act ? act + v * ld_act + f0 : H + v * ldh + f0;
+    if (VEC) {
+        float4 a = *reinterpret_cast<const float4*>(src);
+        a.x *= m[0]; a.y *= m[1]; a.z *= m[2]; a.w *= m[3];
+        if (act) {
+            *reinterpret_cast<float4*>(src) = a;
+            const float4 r = *reinterpret_cast<const float4*>(res + v * ld_res + f0);
+            a.x += r.x; a.y += r.y; a.z += r.z; a.w += r.w;
+        }
+        *reinterpret_cast<float4*>(H + v * ldh + f0) = a;
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (f0 + q >= F) break;
+            float a = src[q] * m[q];
+            if (act) { src[q] = a; a += res[v * ld_res + f0 + q]; }
+            H[v * ldh + f0 + q] = a;
+        }
+    }
+}
+
+grp_status launch_dropout(const DropoutPlan& d, int layer, const int64_t* l2g, int64_t n, int32_t F, float* H, int64_t ldh,
+                          float* act, int64_t ld_act, const float* res, int64_t ld_res, hipStream_t st) {
+    if (!d.on || n <= 0) return GRP_OK;
+    if (!l2g || !H || (act && !res)) return fail(GRP_EINVAL, "dropout: null argument");
+    ProfScope ps("dropout", st, 0.0, 8.0 * n * F * (act ? 2 : 1));
+    const int64_t work = n * ((F + 3) / 4);
+    const bool vec = ldh % 4 == 0 && ldh >= round_up(F, 4) && (uintptr_t)H % 16 == 0 &&
+                     (!act || (ld_act % 4 == 0 && ld_act >= round_up(F, 4) && (uintptr_t)act % 16 == 0 && ld_res % 4 == 0 &&
+                               ld_res >= round_up(F, 4) && (uintptr_t)res % 16 == 0));
+    const uint64_t key = dropout_layer_key(d, layer);
+    if (vec)
+        hipLaunchKernelGGL(dropout_kernel<true>, dim3((unsigned)cdiv(work, 256)), dim3(256), 0, st, l2g, n, (int)F, key,
+                           d.thresh, d.scale, H, ldh, act, ld_act, res, ld_res);
+    else
+        hipLaunchKernelGGL(dropout_kernel<false>, dim3((unsigned)cdiv(work, 256)), dim3(256), 0, st, l2g, n, (int)F, key,
+                           d.thresh, d.scale, H, ldh, act, ld_act, res, ld_res);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
+__global__ __launch_bounds__(256) void scale_copy_kernel(const float* __restrict__ in, float s, float* __restrict__ out,
+                                                         int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) out[i] = in[i] * s;
+}
+
+grp_status launch_scale_copy(const float* in, float s, float* out, int64_t n, hipStream_t st) {
+    if (n <= 0) return GRP_OK;
+    hipLaunchKernelGGL(scale_copy_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, in, s, out, n);
     GRP_LAUNCH_CHECK();
     return GRP_OK;
 }

@@ -135,6 +135,7 @@ struct GatWalk {
     const float* bias;
     int relu;
     float* Hout;      int64_t ldh;       // FWD: output; DST: the layer's stored output
+    float hout_scale;                    // DST: out_v = hout_scale * Hout[v,:] where dOut is non-zero (undoes dropout)
     const float* dOut; int64_t ldd;
     float* cvec;                         // DST: written; SRC: read
     float2* dqs;                         // DST: written (dq, self-term score gradient); SRC: read
@@ -175,7 +176,9 @@ __device__ __forceinline__ void gat_row_setup(const GatWalk& A, int64_t r, int t
             float bb[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) bb[q] = col + q < A.F ? A.bias[col + q] : 0.f;
-            cpart += R.vec[j].x * (h.x - bb[0]) + R.vec[j].y * (h.y - bb[1]) + R.vec[j].z * (h.z - bb[2]) + R.vec[j].w * (h.w - bb[3]);
+            const float hs = A.hout_scale;
+            cpart += R.vec[j].x * (h.x * hs - bb[0]) + R.vec[j].y * (h.y * hs - bb[1]) + R.vec[j].z * (h.z * hs - bb[2]) +
+                     R.vec[j].w * (h.w * hs - bb[3]);
             spart += dot4(R.vec[j], ld4(A.Tx + r * A.ldx + col));
         }
         R.c = group_sum<G>(cpart);        // c_v = dOut_v . (out_v - b) = sum_u alpha_uv (dOut_v . t_u)
@@ -386,11 +389,12 @@ __global__ __launch_bounds__(256) void gat_combine_kernel(GatWalk A, const int32
     gat_row_finish<PASS, G, NJ>(A, R, r, t, live, acc, scal, dself);
 }
 
-// Packed weights of one layer: Wp[Fin x ldx] = [W | 0 | W a_src | W a_dst | 0 0] (rows of the
-// product dT_ext -> dH) and its transpose Wt[ldx x ld(Fin)] (rows of the product H -> T_ext).
+// Packed weights of one layer: Wp[Fin x ldx] = wp_scale [W | 0 | W a_src | W a_dst | 0 0] (rows of the
+// product dT_ext -> dH; wp_scale = 1 / (1 - rate) when the layer's input went through dropout) and the
+// unscaled transpose Wt[ldx x ld(Fin)] (rows of the product H -> T_ext).
 __global__ __launch_bounds__(256) void gat_pack_kernel(const float* __restrict__ W, const float* __restrict__ a_s,
                                                        const float* __restrict__ a_d, int fin, int fout, int fin_pad, int ldx,
-                                                       float* __restrict__ Wp, float* __restrict__ Wt) {
+                                                       float wp_scale, float* __restrict__ Wp, float* __restrict__ Wt) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= (int64_t)fin_pad * ldx) return;
     const int i = (int)(e / ldx), c = (int)(e % ldx);
@@ -403,7 +407,7 @@ __global__ __launch_bounds__(256) void gat_pack_kernel(const float* __restrict__
             const float* a = c == cp ? a_s : a_d;
             for (int j = 0; j < fout; ++j) val = fmaf(W[(int64_t)i * fout + j], a[j], val);
         }
-        Wp[(int64_t)i * ldx + c] = val;
+        Wp[(int64_t)i * ldx + c] = val * wp_scale;
     }
     Wt[(int64_t)c * fin_pad + i] = val;
 }
@@ -551,13 +555,14 @@ grp_status gat_step(const grp_partition_t* g, const grp_model_desc* m, const grp
         return launch_softmax_xent(0, m->dims[k], nullptr, 4, labels, nullptr, mask, o->estimator == GRP_EST_NODE_LEVEL,
                                    g->d_local_in, g->d_global_in, nullptr, p.dZa, 4, p.stats_ws, stats, st);
     }
+    const DropoutPlan drop = dropout_plan(o);
     // ---------------- packed weights
     for (int l = 0; l < k; ++l) {
         const GatLayer& L = p.L[l];
         ProfScope ps("gat_pack_weights", st);
         hipLaunchKernelGGL(gat_pack_kernel, dim3((unsigned)cdiv((int64_t)L.ldin_pad * L.ldx, 256)), dim3(256), 0, st,
                            theta + L.off_w, theta + L.off_as, theta + L.off_ad, L.fin, L.fout, (int)L.ldin_pad, (int)L.ldx,
-                           L.Wp, L.Wt);
+                           l > 0 ? drop.scale : 1.f, L.Wp, L.Wt);
         GRP_LAUNCH_CHECK();
     }
     // ---------------- forward
@@ -582,6 +587,7 @@ grp_status gat_step(const grp_partition_t* g, const grp_model_desc* m, const grp
             A.rowstat = L.rowstat; A.bias = theta + L.off_b; A.relu = l < k - 1 ? 1 : 0; A.Hout = L.Hout; A.ldh = L.ldh;
             GRP_TRY(launch_gat_walk<GAT_FWD>(A, &g->csr_long, p.partials, st));
         }
+        if (l < k - 1) GRP_TRY(launch_dropout(drop, l, g->l2g, n, L.fout, L.Hout, L.ldh, nullptr, 0, nullptr, 0, st));
         H = L.Hout; ldh = L.ldh; h_bf16 = 0;
     }
     // ---------------- loss
@@ -603,6 +609,7 @@ grp_status gat_step(const grp_partition_t* g, const grp_model_desc* m, const grp
             A.ptr = g->rowptr; A.idx = g->col; A.n = n; A.F = L.fout; A.Tx = L.Tx; A.ldx = L.ldx; A.pq = L.pq;
             A.rowstat = L.rowstat; A.bias = theta + L.off_b; A.Hout = L.Hout; A.ldh = L.ldh; A.dOut = dZ; A.ldd = L.ldh;
             A.cvec = p.cvec; A.dqs = p.dqs; A.dTx = p.dTx;
+            A.hout_scale = (drop.on && l < k - 1) ? 1.0f - o->dropout_rate : 1.f;
             GRP_TRY(launch_gat_walk<GAT_DST>(A, &g->csr_long, p.partials, st));
             A.ptr = g->colptr; A.idx = g->row;
             GRP_TRY(launch_gat_walk<GAT_SRC>(A, &g->csc_long, p.partials, st));

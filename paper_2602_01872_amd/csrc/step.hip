@@ -34,6 +34,7 @@ struct LayerBufs {
 struct StepPlan {
     std::vector<LayerBufs> L;
     float *inv_in = nullptr, *gr = nullptr, *gs = nullptr, *grinv = nullptr;
+    float* gr_drop = nullptr;    // gr / (1 - dropout rate): the row scale of the backward pass through a dropped layer
     float *tmpA = nullptr, *tmpB = nullptr, *dZa = nullptr, *dZb = nullptr, *Ga = nullptr, *Gb = nullptr;
     void *tn_ws = nullptr, *colsum_ws = nullptr, *stats_ws = nullptr, *sampler_ws = nullptr;
     float* partials = nullptr;   // partial rows of the split long rows (SpMM)
@@ -130,6 +131,7 @@ static StepPlan make_plan(const grp_partition_t* part, const grp_model_desc* m, 
         p.gr = b.take<float>((size_t)n);
         p.gs = b.take<float>((size_t)n);
         p.grinv = b.take<float>((size_t)n);
+        if (o->dropout_rate > 0.f) p.gr_drop = b.take<float>((size_t)n);
     }
     p.tmpA = b.take<float>((size_t)max_rows * 2 * fmax);   // holds two matrices side by side in the fused layers
     p.tmpB = b.take<float>((size_t)max_rows * fmax);
@@ -161,6 +163,10 @@ static grp_status check_step_args(const grp_partition_t* part, const grp_model_d
     if (model->arch == GRP_ARCH_GCN_RESIDUAL && model->feat_dtype == GRP_DTYPE_BF16 && model->n_layers > 1 &&
         model->dims[0] == model->dims[1])
         return fail(GRP_EUNSUPPORTED, "train_step: a residual first layer needs fp32 features");
+    if (!(opts->dropout_rate >= 0.f && opts->dropout_rate < 1.f))
+        return fail(GRP_EINVAL, "train_step: dropout rate outside [0, 1)");
+    if (opts->dropout_rate > 0.f && !opts->full_graph)
+        return fail(GRP_EUNSUPPORTED, "train_step: dropout is implemented for full-graph steps only");
     if (!opts->full_graph) {
         if (model->arch != GRP_ARCH_SAGE_MEAN)
             return fail(GRP_EUNSUPPORTED, "train_step: mini-batch mode is implemented for GraphSAGE only");
@@ -182,7 +188,9 @@ static void fill_spmm(SpmmArgs& s, const Block& B, bool transposed, float* parti
     s.partials = partials;
 }
 
-static grp_status prep_weights(const grp_model_desc* m, const float* theta, StepPlan& p, hipStream_t st) {
+// bwd_scale multiplies the weights of the products that carry a gradient back through a layer
+// output: 1 / (1 - rate) with dropout (the kept elements were scaled by it), else 1.
+static grp_status prep_weights(const grp_model_desc* m, const float* theta, StepPlan& p, float bwd_scale, hipStream_t st) {
     const bool sage = m->arch == GRP_ARCH_SAGE_MEAN;
     PackJobs jobs;
     for (int l = 0; l < m->n_layers; ++l) {
@@ -193,8 +201,8 @@ static grp_status prep_weights(const grp_model_desc* m, const float* theta, Step
         pack_jobs_add(jobs, theta + L.off_ws, fin, fout, true, (int)ldp(fout), L.Wt_s, L.ldwt);
         if (sage) pack_jobs_add(jobs, theta + L.off_wn, fin, fout, true, (int)ldp(fout), L.Wt_n, L.ldwt);
         if (l > 0) {
-            pack_jobs_add(jobs, theta + L.off_ws, fin, fout, false, (int)ldp(fin), L.Wp_s, L.ldwp);
-            if (sage) pack_jobs_add(jobs, theta + L.off_wn, fin, fout, false, (int)ldp(fin), L.Wp_n, L.ldwp);
+            pack_jobs_add(jobs, theta + L.off_ws, fin, fout, false, (int)ldp(fin), L.Wp_s, L.ldwp, bwd_scale);
+            if (sage) pack_jobs_add(jobs, theta + L.off_wn, fin, fout, false, (int)ldp(fin), L.Wp_n, L.ldwp, bwd_scale);
         }
     }
     return launch_pack_weights(jobs, st);
@@ -204,7 +212,8 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
                             const void* X, const int32_t* labels, const uint8_t* mask, const int32_t* loss_nodes,
                             const float* theta, StepPlan& p, hipStream_t st, float* grad, grp_step_stats* stats) {
     const int k = m->n_layers;
-    GRP_TRY(prep_weights(m, theta, p, st));
+    const DropoutPlan drop = dropout_plan(o);
+    GRP_TRY(prep_weights(m, theta, p, drop.scale, st));
 
     // ---------------- forward
     const void* H = X;
@@ -254,6 +263,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             s.addend = L.H_out; s.ld_add = ldp(fout); s.relu = relu; s.Y = L.H_out; s.ldy = ldp(fout);
             GRP_TRY(launch_spmm(s, st));
         }
+        if (relu) GRP_TRY(launch_dropout(drop, l, g->l2g, B.n_dst, fout, L.H_out, ldp(fout), nullptr, 0, nullptr, 0, st));
         H = L.H_out; ldh = ldp(fout); h_bf16 = 0;
     }
 
@@ -344,7 +354,12 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
     const int64_t n = g->n;
     const int sl = m->gcn_self_loops ? 1 : 0;
     GRP_TRY(launch_degree_scales(g->d_local_in, g->d_local_out, n, sl, nullptr, p.gr, p.gs, p.grinv, st));
-    GRP_TRY(prep_weights(m, theta, p, st));
+    GRP_TRY(prep_weights(m, theta, p, 1.f, st));
+    // With dropout the gradient that reaches a hidden activation is also multiplied by 1 / (1 - rate);
+    // the residual path bypasses it, so the factor rides on the row scale of the masked output.
+    const DropoutPlan drop = dropout_plan(o);
+    if (drop.on) GRP_TRY(launch_scale_copy(p.gr, drop.scale, p.gr_drop, n, st));
+    const float* gr_bwd = drop.on ? p.gr_drop : p.gr;
     Block B;
     B.n_dst = B.n_in = n; B.nnz = g->nnz; B.ptr = g->rowptr; B.idx = g->col; B.ptrT = g->colptr; B.idxT = g->row;
     B.long_fwd = &g->csr_long; B.long_bwd = &g->csc_long;
@@ -365,6 +380,9 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
         s.bias = theta + L.off_b; s.relu = l < k - 1; s.Y = L.H_out; s.ldy = ldp(fout);
         if (L.skip) { s.residual = (const float*)H; s.ld_res = ldh; s.Y2 = L.Act; s.ldy2 = ldp(fout); }
         GRP_TRY(launch_spmm(s, st));
+        if (l < k - 1)
+            GRP_TRY(launch_dropout(drop, l, g->l2g, n, fout, L.H_out, ldp(fout), L.skip ? L.Act : nullptr, ldp(fout),
+                                   L.skip ? (const float*)H : nullptr, ldh, st));
         H = L.H_out; ldh = ldp(fout); h_bf16 = 0;
     }
 
@@ -397,7 +415,7 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
             c.M = n; c.N = fin; c.K = fout; c.A = p.tmpA; c.lda = ldp(fout); c.Bt = L.Wp_s; c.ldbt = L.ldwp;
             if (L.skip) { c.addend = G; c.ld_add = ldp(fout); }
             if (Lp.skip) { c.C_raw = G_other; c.ld_raw = ldp(fin); }
-            c.rowscale = p.gr; c.mask = Lp.skip ? Lp.Act : Lp.H_out; c.ld_mask = ldp(fin);
+            c.rowscale = gr_bwd; c.mask = Lp.skip ? Lp.Act : Lp.H_out; c.ld_mask = ldp(fin);
             c.C = dZ_other; c.ldc = ldp(fin); c.zero_pad_to = (int)ldp(fin);
             GRP_TRY(launch_gemm_nn(c, st));
             float* sg = G; G = G_other; G_other = sg;

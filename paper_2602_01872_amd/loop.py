@@ -18,9 +18,12 @@ class PhaseParallelTrainer:
     ``parts``: list of ``Partition``; ``xs`` / ``ys`` / ``masks``: per-partition device
     tensors (features, int32 labels, uint8 train mask or None).  ``max_active`` = M, the
     number of partitions per phase.  Full-graph mode (one iteration per phase and epoch).
+    ``dropout_rate`` / ``dropout_seed``: hidden-layer dropout; the masks of a phase are drawn with
+    batch_id = the number of optimizer steps taken so far.
     """
 
-    def __init__(self, parts, model, xs, ys, masks, theta0, estimator, max_active, optimizer=None):
+    def __init__(self, parts, model, xs, ys, masks, theta0, estimator, max_active, optimizer=None,
+                 dropout_rate=0.0, dropout_seed=0):
         self.parts, self.model, self.xs, self.ys, self.masks = parts, model, xs, ys, masks
         self.estimator, self.max_active = estimator, max_active
         self.opt = optimizer if optimizer is not None else g.optimizer_desc()
@@ -31,7 +34,8 @@ class PhaseParallelTrainer:
         self.m = torch.zeros(self.P, device=dev)
         self.v = torch.zeros(self.P, device=dev)
         self.update = torch.zeros(self.P, device=dev)
-        self.opts = g.step_opts(estimator=estimator, full_graph=True)
+        self.opts = g.step_opts(estimator=estimator, full_graph=True, dropout_rate=dropout_rate,
+                                dropout_seed=dropout_seed)
         self.grads = torch.zeros(max_active, self.ld, device=dev)
         self.stats = g.new_stats(max_active, device=dev)
         ws_bytes = max(g.grp_step_workspace_bytes(p, model, self.opts) for p in parts)
@@ -44,6 +48,7 @@ class PhaseParallelTrainer:
         return [list(range(lo, min(K, lo + M))) for lo in range(0, K, M)]
 
     def run_phase(self, active):
+        self.opts.batch_id = self.step_count
         for slot, p in enumerate(active):
             g.grp_train_step(self.parts[p], self.model, self.opts, self.xs[p], self.ys[p], self.masks[p],
                              self.theta, self.ws, self.grads[slot],

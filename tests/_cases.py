@@ -88,5 +88,5 @@ def make_inputs(n, dims, arch, seed, bf16=False, n_classes=None):
     if bf16:
         x = synth.to_bf16_rne(x)
     y = synth.labels(n, dims[-1], seed)
-    theta = synth.model_weights("sage" if arch == "sage" else "gcn", dims, seed)
+    theta = synth.model_weights(arch if arch in ("sage", "gat") else "gcn", dims, seed)
     return x, y, theta

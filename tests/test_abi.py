@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_header():
     import paper_2602_01872_amd as g
     assert C.sizeof(g.ModelDesc) == 4 * (2 + 17 + 2)
-    assert C.sizeof(g.StepOpts) == 16 + 8 + 4 * 16 + 16
+    assert C.sizeof(g.StepOpts) == 16 + 8 + 4 * 16 + 16 + 16
     assert g.STATS_BYTES == 40
     assert C.sizeof(g.PartitionView) == 8 * 10
     assert C.sizeof(g.OptimizerDesc) == 24
