@@ -17,6 +17,15 @@ weight (p_v(u) = 1/d_global, q_v(u) = 1/d_local):
                            its own factor and only then reduced, as the phase-parallel
                            algorithm orders it.
 
+General (non-uniform) neighbour weights: with edge weights w(u->v) the target distribution
+is p_v(u) = w(u->v)/W_global(v) and the local one q_v(u) = p_v(u)/sum_{i local} p_v(i) (the
+choice the paper names for the general case), so p_v(u)/q_v(u) = W_local(v)/W_global(v) for every
+local neighbour: the weight masses W take the place of the degrees in the node-level weight and in
+the minimum-distance factor.  The shrinkage factor is only given for degrees; its term becomes
+(W_global - W_local) d_local / W_local (the missing mass counted in units of the node's mean local
+edge weight), and d_global for a node without local in-edges, which is d_global - d_local again
+when every weight is 1.
+
 Readings where the paper is silent (boundary conventions):
   * S = the nodes that carry loss (seeds in mini-batch mode), degrees are the partition's
     in-degrees with multiplicity;
@@ -59,6 +68,19 @@ def coverage_stats(d_local, d_global, loss_nodes, sampled_count=None) -> dict:
         sc = np.asarray(sampled_count, dtype=np.float64)[s]
         ok = dl > 0
         r = float(((dg[ok] - dl[ok]).astype(np.float64) * sc[ok] / dl[ok]).sum())
+    return dict(S=int(s.size), sum_ratio=sum_ratio, R=r)
+
+
+def coverage_stats_weighted(w_local, w_global, d_local, d_global, loss_nodes) -> dict:
+    """Full-graph coverage statistics for weighted neighbour distributions (see the module header)."""
+    s = np.asarray(loss_nodes, dtype=np.int64)
+    wl = np.asarray(w_local, dtype=np.float64)[s]
+    wg = np.asarray(w_global, dtype=np.float64)[s]
+    dl = np.asarray(d_local, dtype=np.int64)[s]
+    dg = np.asarray(d_global, dtype=np.int64)[s]
+    sum_ratio = float(node_weights(wl, wg).sum())
+    ok = dl > 0
+    r = float(((wg[ok] - wl[ok]) * dl[ok] / wl[ok]).sum() + dg[~ok].sum())
     return dict(S=int(s.size), sum_ratio=sum_ratio, R=r)
 
 

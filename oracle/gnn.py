@@ -12,7 +12,9 @@ Readings where the paper is silent:
                  z_v = h_v W_self + m_v W_neigh + b,  h'_v = ReLU(z_v); the last layer
                  outputs z_v (logits).  N_v is the multiset of in-neighbours present in
                  the block (all local in-edges in full-graph mode, the sampled ones in
-                 mini-batch mode).
+                 mini-batch mode).  With edge weights (block key "ew", the general
+                 non-uniform neighbour distribution) the mean is the weighted mean
+                 m_v = sum_u w_uv h_u / sum_u w_uv over the same multiset.
   * GCN:         z_v = sum_u Ahat[v,u] (h_u W) + b with the symmetric normalisation
                  Ahat[v,u] = (A[v,u] + [u==v]) / sqrt((d_in(v)+1) (d_out(u)+1)) over
                  local degrees; with ``self_loops=False`` the identity is not added and
@@ -76,12 +78,15 @@ def pack_grads(grads) -> np.ndarray:
     return np.concatenate(parts)
 
 
-def block_from_csr(rowptr, col, n_src=None) -> dict:
+def block_from_csr(rowptr, col, n_src=None, ew=None) -> dict:
     rowptr = np.asarray(rowptr, dtype=np.int64)
     n_dst = rowptr.size - 1
     edst = np.repeat(np.arange(n_dst, dtype=np.int64), np.diff(rowptr))
-    return dict(n_dst=n_dst, n_src=n_dst if n_src is None else int(n_src),
-                esrc=np.asarray(col, dtype=np.int64), edst=edst)
+    blk = dict(n_dst=n_dst, n_src=n_dst if n_src is None else int(n_src),
+               esrc=np.asarray(col, dtype=np.int64), edst=edst)
+    if ew is not None:
+        blk["ew"] = np.asarray(ew, dtype=np.float64)
+    return blk
 
 
 def _scatter_rows(n_out: int, index, rows) -> np.ndarray:
@@ -120,6 +125,12 @@ def softmax_xent(logits, labels, node_w, loss_nodes):
 # --------------------------------------------------------------------------- layers
 
 def _sage_forward(h, blk, ws, wn, b):
+    if "ew" in blk:
+        mass = np.bincount(blk["edst"], weights=blk["ew"], minlength=blk["n_dst"])
+        inv = np.where(mass > 0, 1.0 / np.where(mass > 0, mass, 1.0), 0.0)
+        m = _scatter_rows(blk["n_dst"], blk["edst"], h[blk["esrc"]] * blk["ew"][:, None]) * inv[:, None]
+        z = h[:blk["n_dst"]] @ ws + m @ wn + b
+        return z, (m, inv)
     deg = np.bincount(blk["edst"], minlength=blk["n_dst"]).astype(np.float64)
     inv = 1.0 / np.maximum(deg, 1.0)
     m = _scatter_rows(blk["n_dst"], blk["edst"], h[blk["esrc"]]) * inv[:, None]
@@ -137,11 +148,16 @@ def _sage_backward(h, blk, ws, wn, saved, dz, need_dh):
         dh = np.zeros_like(h)
         dh[:blk["n_dst"]] += dz @ ws.T
         dm = (dz @ wn.T) * inv[:, None]
-        dh += _scatter_rows(blk["n_src"], blk["esrc"], dm[blk["edst"]])
+        per_edge = dm[blk["edst"]]
+        if "ew" in blk:
+            per_edge = per_edge * blk["ew"][:, None]
+        dh += _scatter_rows(blk["n_src"], blk["esrc"], per_edge)
     return (gws, gwn, gb), dh
 
 
 def _gcn_coeffs(blk, self_loops):
+    if "ew" in blk:
+        raise ValueError("edge weights are defined for the GraphSAGE mean aggregator only")
     if blk["n_src"] != blk["n_dst"]:
         raise ValueError("GCN layers are defined on the full local graph only")
     n = blk["n_dst"]

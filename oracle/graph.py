@@ -45,7 +45,7 @@ def owner(n_nodes: int, n_parts: int, seed: int) -> np.ndarray:
     return (h % np.uint64(n_parts)).astype(np.int32)
 
 
-def partition(src, dst, n_nodes: int, n_parts: int, seed: int, part_id: int) -> dict:
+def partition(src, dst, n_nodes: int, n_parts: int, seed: int, part_id: int, weights=None) -> dict:
     """Local subgraph of partition ``part_id`` with cut edges removed.
 
     ``src[e] -> dst[e]`` are global ids; node ``dst`` aggregates from ``src``.
@@ -53,6 +53,12 @@ def partition(src, dst, n_nodes: int, n_parts: int, seed: int, part_id: int) -> 
       n, nnz, l2g[int64 n], rowptr[int64 n+1], col[int32 nnz] (CSR by destination),
       colptr[int64 n+1], row[int32 nnz] (CSC by source),
       d_local_in[int32 n], d_local_out[int32 n], d_global_in[int64 n].
+    ``weights[e] > 0`` (optional, fp32 values): the neighbour distribution of node v is
+    p_v(u) = w(u->v) / sum of the weights of all in-edges of v (the general, non-uniform case of
+    the coverage-corrected estimators).  The dict then also holds csr_w[float32 nnz] and
+    csc_w[float32 nnz] (the kept edges' weights in CSR / CSC order; equal (dst, src) pairs keep
+    their order in the edge list), w_local_in[float64 n] (sum of the local in-edge weights, added
+    in CSR order) and w_global_in[float64 n] (sum over all in-edges, added in edge-list order).
     """
     src = np.asarray(src, dtype=np.int64)
     dst = np.asarray(dst, dtype=np.int64)
@@ -89,9 +95,23 @@ def partition(src, dst, n_nodes: int, n_parts: int, seed: int, part_id: int) -> 
     colptr = np.zeros(n + 1, dtype=np.int64)
     np.cumsum(d_out, out=colptr[1:])
 
-    return dict(n=n, nnz=nnz, l2g=l2g, rowptr=rowptr, col=col, colptr=colptr, row=row,
-                d_local_in=d_in.astype(np.int32), d_local_out=d_out.astype(np.int32),
-                d_global_in=d_global_all[l2g])
+    out = dict(n=n, nnz=nnz, l2g=l2g, rowptr=rowptr, col=col, colptr=colptr, row=row,
+               d_local_in=d_in.astype(np.int32), d_local_out=d_out.astype(np.int32),
+               d_global_in=d_global_all[l2g])
+    if weights is not None:
+        w = np.asarray(weights, dtype=np.float32)
+        if w.shape != src.shape or not np.all(w > 0) or not np.all(np.isfinite(w)):
+            raise ValueError("edge weights must be positive, finite and one per edge")
+        wk = w[keep]
+        out["csr_w"] = wk[order]
+        out["csc_w"] = wk[order_t]
+        w_local = np.zeros(n, dtype=np.float64)
+        np.add.at(w_local, ld[order], wk[order].astype(np.float64))           # CSR order
+        w_global_all = np.zeros(n_nodes, dtype=np.float64)
+        np.add.at(w_global_all, dst, w.astype(np.float64))                    # edge-list order
+        out["w_local_in"] = w_local
+        out["w_global_in"] = w_global_all[l2g]
+    return out
 
 
 def local_graph_from_edges(src_local, dst_local, n: int, d_global_in=None) -> dict:

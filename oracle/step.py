@@ -24,13 +24,22 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
     side, so the seeds draw fanouts[k-1] neighbours.
     ``relu_flip`` / ``near_kink`` are passed to ``gnn.forward_backward``; with ``near_kink`` the
     stats dict gains the key "near_kink".
+    A partition built with edge weights (``graph.partition(..., weights=)``) trains the weighted-mean
+    GraphSAGE aggregator and reports the coverage statistics of the weight masses (full-graph mode).
     ``dropout = dict(rate=, seed=, batch_id=)`` (full-graph mode only) drops hidden activations as
     ``dropout.py`` describes, keyed on the nodes' global ids ``part["l2g"]``.
     """
     n = part["n"]
     k = len(dims) - 1
     dl, dg = part["d_local_in"], part["d_global_in"]
-    w_all = coverage.node_weights(dl, dg) if estimator == coverage.NODE_LEVEL else np.ones(n)
+    weighted = part.get("csr_w") is not None
+    if weighted and (arch != "sage" or minibatch is not None):
+        raise ValueError("edge weights are defined for full-graph GraphSAGE steps only")
+    if weighted:
+        ratio = coverage.node_weights(part["w_local_in"], part["w_global_in"])
+    else:
+        ratio = coverage.node_weights(dl, dg)
+    w_all = ratio if estimator == coverage.NODE_LEVEL else np.ones(n)
 
     drop = None
     if dropout is not None and float(dropout["rate"]) != 0.0:
@@ -39,7 +48,7 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
         drop = dropout_mod.layer_factors(dropout["seed"], dropout.get("batch_id", 0), part["l2g"], dims,
                                          dropout["rate"])
     if minibatch is None:
-        blk = gnn.block_from_csr(part["rowptr"], part["col"])
+        blk = gnn.block_from_csr(part["rowptr"], part["col"], ew=part["csr_w"] if weighted else None)
         if train_mask is None:
             loss_nodes = np.arange(n, dtype=np.int64)
         else:
@@ -51,7 +60,10 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
             res = gnn.forward_backward(arch, dims, theta, x, [blk] * k, labels, w_all, loss_nodes,
                                        gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink, drop=drop)
         loss, grad = res[0], res[1]
-        st = coverage.coverage_stats(dl, dg, loss_nodes, None)
+        if weighted:
+            st = coverage.coverage_stats_weighted(part["w_local_in"], part["w_global_in"], dl, dg, loss_nodes)
+        else:
+            st = coverage.coverage_stats(dl, dg, loss_nodes, None)
         if near_kink is not None:
             st["near_kink"] = res[2]
         st["loss"] = loss
