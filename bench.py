@@ -130,17 +130,27 @@ def run_evidence_workload(args, g, synth, torch, dev):
         print(json.dumps(out), flush=True)
         return
 
-    if wl in ("c2-gat-step", "c2-dropout-step"):
-        # the headline workload's partition with the attention model in place of GraphSAGE, or with
-        # GraphSAGE and dropout 0.5 on the hidden layers
+    if wl in ("c2-gat-step", "c2-dropout-step", "c2-weighted-step"):
+        # the headline workload's partition with the attention model in place of GraphSAGE, with
+        # GraphSAGE and dropout 0.5 on the hidden layers, or with weighted edges (weighted-mean GraphSAGE)
         src, dst = synth.rmat_graph(RMAT_SCALE, N_EDGES, seed=GRAPH_SEED, n_nodes=N_NODES, device=dev)
-        part = g.grp_partition(src, dst, N_NODES, K_PARTS, PART_SEED, PART_ID)
+        if wl == "c2-weighted-step":
+            ew = synth.edge_weights(N_EDGES, GRAPH_SEED, device=dev)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            part = g.grp_partition_weighted(src, dst, ew, N_NODES, K_PARTS, PART_SEED, PART_ID)
+            torch.cuda.synchronize()
+            print(f"[bench] weighted partition built in {(time.perf_counter() - t0) * 1e3:.1f} ms", file=sys.stderr, flush=True)
+            del ew
+        else:
+            part = g.grp_partition(src, dst, N_NODES, K_PARTS, PART_SEED, PART_ID)
         del src, dst
         l2g = torch.from_numpy(part.array("l2g")).to(dev)
         dims = [100, 256, 256, 47]
         gat = wl == "c2-gat-step"
         model = g.model_desc(g.ARCH_GAT if gat else g.ARCH_SAGE_MEAN, dims)
-        opts = g.step_opts(estimator=g.EST_SHRINKAGE, full_graph=True, dropout_rate=0.0 if gat else 0.5, dropout_seed=1)
+        opts = g.step_opts(estimator=g.EST_SHRINKAGE, full_graph=True, dropout_rate=0.5 if wl == "c2-dropout-step" else 0.0,
+                           dropout_seed=1)
         x = synth.normal_matrix(N_NODES, dims[0], GRAPH_SEED, device=dev)[l2g].contiguous()
         y = synth.labels(N_NODES, dims[-1], GRAPH_SEED, device=dev)[l2g].contiguous()
         theta = synth.model_weights("gat" if gat else "sage", dims, GRAPH_SEED, device=dev)
@@ -154,7 +164,8 @@ def run_evidence_workload(args, g, synth, torch, dev):
         out.update(metric="per-partition train-step edges/s (fwd+bwd)", unit="edges/s", value=part.nnz / dt,
                    ms_per_step=dt * 1e3, dtype="f32",
                    config={"workload": (f"c2-gat-step: GAT-3 (one head) {dims}" if gat else
-                                        f"c2-dropout-step: SAGE-mean-3 {dims} with dropout 0.5") +
+                                        f"c2-dropout-step: SAGE-mean-3 {dims} with dropout 0.5" if wl == "c2-dropout-step" else
+                                        f"c2-weighted-step: SAGE-mean-3 {dims} on weighted edges (weighted mean)") +
                                        f", partition 0 of 8 of the R-MAT 2.4M-node / 62M-edge graph, n={part.n}, nnz={part.nnz}",
                            "params": P},
                    roofline=_roofline(kernels, {}), kernels=kernels)
@@ -251,7 +262,7 @@ def main():
     ap.add_argument("--small", action="store_true", help="scaled-down graph (debugging only; not a valid result)")
     ap.add_argument("--shapes", action="store_true", help="per-launch-shape kernel table on stderr (debugging)")
     ap.add_argument("--workload", default="c2-step",
-                    choices=["c2-step", "c2-gat-step", "c2-dropout-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "aggregate-stress"],
+                    choices=["c2-step", "c2-gat-step", "c2-dropout-step", "c2-weighted-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "aggregate-stress"],
                     help="c2-step (default) is the headline workload; the others are evidence runs for the other "
                          "configurations (each prints one JSON line of the same form)")
     ap.add_argument("--copy-calibration", action="store_true",

@@ -82,6 +82,35 @@ grp_status grp_partition(const int64_t* src, const int64_t* dst, int64_t E, int6
                          int32_t K, uint64_t seed, int32_t part_id, void* stream,
                          grp_partition_t** out);
 
+/* The same partition for neighbours of unequal weight (the general form of the coverage-corrected
+ * estimators: a target distribution p_v(u) over the in-neighbours of v and a local one
+ * q_v(u) = p_v(u) / sum of p_v over the local neighbours).  w: DEV float[E], w[e] > 0 finite, the
+ * weight of edge e; p_v(u) = w(u->v) / (sum of the weights of all in-edges of v).  The handle then
+ * also holds, readable through grp_partition_weights:
+ *   csr_w / csc_w   DEV float[nnz]  the kept edges' weights in CSR / CSC order; equal (dst, src)
+ *                                   pairs keep their order in the edge list
+ *   w_local_in      DEV double[n]   sum of a node's local in-edge weights, added in CSR order
+ *   w_global_in     DEV double[n]   sum over all its in-edges, added in edge-list order
+ * (both sums are sequential fp64 additions in the stated order, so they are reproducible bit
+ * for bit).  grp_train_step on such a handle (GraphSAGE, full-graph mode; GRP_EUNSUPPORTED
+ * otherwise) aggregates with the weighted mean m_v = sum_u w_uv h_u / w_local_in(v), and its
+ * statistics use the weight masses: ratio = w_local_in / w_global_in (1 if w_global_in = 0),
+ * R = sum_{v in S} (w_global_in - w_local_in) d_local / w_local_in (d_global for d_local = 0).
+ * Errors as grp_partition, plus GRP_EINVAL for a weight that is not a positive finite number. */
+grp_status grp_partition_weighted(const int64_t* src, const int64_t* dst, const float* w, int64_t E,
+                                  int64_t N, int32_t K, uint64_t seed, int32_t part_id, void* stream,
+                                  grp_partition_t** out);
+
+typedef struct {
+    const float*  csr_w;
+    const float*  csc_w;
+    const double* w_local_in;
+    const double* w_global_in;
+} grp_partition_weights_t;
+
+/* Borrowed DEV pointers (all NULL for a partition built without weights). */
+grp_status grp_partition_weights(const grp_partition_t* part, grp_partition_weights_t* view);
+
 /* ------------------------------------------------------------------ chunks and sweeping partitions */
 
 typedef struct grp_chunks_s grp_chunks_t;

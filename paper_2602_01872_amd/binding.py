@@ -41,6 +41,10 @@ class OptimizerDesc(C.Structure):
                 ("beta2", C.c_float), ("eps", C.c_float)]
 
 
+class PartitionWeights(C.Structure):
+    _fields_ = [("csr_w", C.c_void_p), ("csc_w", C.c_void_p), ("w_local_in", C.c_void_p), ("w_global_in", C.c_void_p)]
+
+
 class StepOpts(C.Structure):
     _fields_ = [("estimator", C.c_int32), ("full_graph", C.c_int32), ("n_seeds", C.c_int32),
                 ("reserved", C.c_int32), ("seeds", C.c_void_p), ("fanouts", C.c_int32 * GRP_MAX_LAYERS),
@@ -67,6 +71,8 @@ def load() -> C.CDLL:
     lib.grp_last_error.argtypes = []
     sigs = {
         "grp_partition": [vp, vp, i64, i64, i32, u64, i32, vp, C.POINTER(vp)],
+        "grp_partition_weighted": [vp, vp, vp, i64, i64, i32, u64, i32, vp, C.POINTER(vp)],
+        "grp_partition_weights": [vp, C.POINTER(PartitionWeights)],
         "grp_partition_from_local_coo": [vp, vp, i64, i64, vp, vp, vp, C.POINTER(vp)],
         "grp_partition_halo": [vp, vp, i64, i64, i32, u64, i32, i32, vp, C.POINTER(vp)],
         "grp_partition_view": [vp, C.POINTER(PartitionView)],
@@ -167,6 +173,22 @@ class Partition:
             _hip_memcpy_d2h(out, getattr(self.view, name))
         return out
 
+    def weights(self):
+        """Host copies of a weighted partition's arrays as a dict (None for an unweighted one)."""
+        w = PartitionWeights()
+        _check(load().grp_partition_weights(self.handle, C.byref(w)))
+        if not w.csr_w and not w.w_local_in:
+            return None
+        out = {}
+        torch.cuda.synchronize()
+        for name, dt, count in (("csr_w", np.float32, self.nnz), ("csc_w", np.float32, self.nnz),
+                                ("w_local_in", np.float64, self.n), ("w_global_in", np.float64, self.n)):
+            a = np.empty(count, dtype=dt)
+            if count:
+                _hip_memcpy_d2h(a, getattr(w, name))
+            out[name] = a
+        return out
+
     def base_mask_ptr(self) -> int:
         """Device address of the uint8[n] base-chunk mask (0 for partitions not built from chunks)."""
         out = C.c_void_p()
@@ -215,6 +237,15 @@ def grp_partition(src, dst, N: int, K: int, seed: int, part_id: int, stream=None
     out = C.c_void_p()
     E = 0 if src is None else int(src.numel())
     _check(load().grp_partition(_ptr(src), _ptr(dst), E, N, K, seed, part_id, _stream(stream), C.byref(out)))
+    return Partition(out.value)
+
+
+def grp_partition_weighted(src, dst, w, N: int, K: int, seed: int, part_id: int, stream=None) -> Partition:
+    """``w``: float32 device tensor, one positive weight per edge."""
+    out = C.c_void_p()
+    E = 0 if src is None else int(src.numel())
+    _check(load().grp_partition_weighted(_ptr(src), _ptr(dst), _ptr(w), E, N, K, seed, part_id, _stream(stream),
+                                         C.byref(out)))
     return Partition(out.value)
 
 
@@ -348,7 +379,7 @@ def read_stats(stats: torch.Tensor) -> np.ndarray:
 
 
 def exported_symbols():
-    return ["grp_last_error", "grp_partition", "grp_partition_from_local_coo", "grp_partition_view",
+    return ["grp_last_error", "grp_partition", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_view",
             "grp_partition_destroy", "grp_chunks_build", "grp_chunks_destroy", "grp_partition_from_chunks",
             "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_train_step",
             "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",

@@ -90,6 +90,12 @@ struct grp_partition_s {
     int32_t* d_local_in = nullptr;
     int32_t* d_local_out = nullptr;
     int64_t* d_global_in = nullptr;
+    // weighted partitions only (null otherwise): edge weights in CSR / CSC order and the weight
+    // masses of every node's local / global in-edges
+    float* csr_w = nullptr;
+    float* csc_w = nullptr;
+    double* w_local_in = nullptr;
+    double* w_global_in = nullptr;
     uint8_t* base_mask = nullptr;    // partitions built from chunks: 1 for the base chunk's nodes
     int device = 0;
 };
@@ -143,6 +149,8 @@ struct SpmmArgs {
     int64_t ld_res = 0;
     float* Y2 = nullptr;                  // also receives act (before the residual is added)
     int64_t ldy2 = 0;
+    const float* val = nullptr;           // [nnz] per-edge multiplier of the gathered row, or null
+    const float* rowscale = nullptr;      // [n_rows] a_i given explicitly (replaces `scale`), or null
 };
 grp_status launch_spmm(const SpmmArgs& a, hipStream_t st);
 size_t spmm_partials_bytes(const LongRows* lr, int32_t F);
@@ -272,14 +280,18 @@ grp_status launch_stats(int64_t n_loss, const int32_t* loss_nodes /*null = 0..n-
                         const uint8_t* mask, const int32_t* d_local, const int64_t* d_global,
                         const int32_t* sampled_count /*null = full graph*/, int64_t nnz_const,
                         const int64_t* const* nnz_parts /*HOST array of device pointers*/, int n_parts,
-                        void* scratch, grp_step_stats* out, hipStream_t st);
+                        void* scratch, grp_step_stats* out, hipStream_t st,
+                        const double* w_local = nullptr, const double* w_global = nullptr /*weight masses: full graph*/);
 grp_status launch_softmax_xent(int64_t n_rows, int32_t C, const float* Z, int64_t ldz,
                                const int32_t* labels, const int32_t* node_of_row /*null = row*/,
                                const uint8_t* mask, int32_t node_level,
                                const int32_t* d_local, const int64_t* d_global,
                                const float* rowscale /*null; multiplies dZ rows*/,
                                float* dZ, int64_t lddz, void* scratch,
-                               grp_step_stats* stats /*reads S, writes loss*/, hipStream_t st);
+                               grp_step_stats* stats /*reads S, writes loss*/, hipStream_t st,
+                               const double* w_local = nullptr, const double* w_global = nullptr);
+// inv[v] = mass[v] > 0 ? 1 / mass[v] : 0
+grp_status launch_inverse_mass(const double* mass, int64_t n, float* inv, hipStream_t st);
 
 grp_status launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 
@@ -317,7 +329,9 @@ struct Block {
     const LongRows* long_fwd = nullptr;
     const LongRows* long_bwd = nullptr;
     const int32_t* self_rows = nullptr;  // [n_dst] or null (row i)
-    float* inv_in = nullptr;             // [n_dst] 1 / max(row length, 1)
+    float* inv_in = nullptr;             // [n_dst] 1 / max(row length, 1); weighted: 1 / local weight mass (0 if none)
+    const float* val = nullptr;          // weighted partitions: edge weights in ptr/idx order
+    const float* valT = nullptr;         //                      and in ptrT/idxT order
 };
 
 struct SamplerBounds {                   // upper bounds per layer, from seeds and fanouts alone

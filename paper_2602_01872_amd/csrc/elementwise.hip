@@ -310,11 +310,22 @@ size_t stats_workspace_bytes(int64_t) { return (size_t)STATS_BLOCKS * sizeof(Sta
 
 __device__ __forceinline__ double degree_ratio(int64_t dl, int64_t dg) { return dg > 0 ? (double)dl / (double)dg : 1.0; }
 
+// What a node's coverage ratio is computed from: in-degrees, or (weighted partitions) the weight
+// masses of its local and global in-edges.
+struct CoverageIn {
+    const int32_t* d_local;
+    const int64_t* d_global;
+    const double* w_local;
+    const double* w_global;
+};
+__device__ __forceinline__ double coverage_ratio(const CoverageIn& c, int64_t v) {
+    if (c.w_local) { const double wg = c.w_global[v]; return wg > 0.0 ? c.w_local[v] / wg : 1.0; }
+    return degree_ratio(c.d_local[v], c.d_global[v]);
+}
+
 // Rows are loss candidates: node = nodes ? nodes[i] : i; kept if !mask || mask[node].
 __global__ __launch_bounds__(256) void stats_partial_kernel(int64_t n_rows, const int32_t* __restrict__ nodes,
-                                                            const uint8_t* __restrict__ mask,
-                                                            const int32_t* __restrict__ d_local,
-                                                            const int64_t* __restrict__ d_global,
+                                                            const uint8_t* __restrict__ mask, CoverageIn cv,
                                                             const int32_t* __restrict__ sampled,
                                                             StatsPartial* __restrict__ part) {
     __shared__ double smd[4];
@@ -324,10 +335,13 @@ __global__ __launch_bounds__(256) void stats_partial_kernel(int64_t n_rows, cons
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_rows; i += (int64_t)gridDim.x * 256) {
         const int64_t v = nodes ? nodes[i] : i;
         if (mask && !mask[v]) continue;
-        const int64_t dl = d_local[v], dg = d_global[v];
+        const int64_t dl = cv.d_local[v], dg = cv.d_global[v];
         s += 1;
-        ratio += degree_ratio(dl, dg);
-        if (sampled) {
+        ratio += coverage_ratio(cv, v);
+        if (cv.w_local) {         // full graph, weight masses: missing mass in units of the mean local edge weight
+            const double wl = cv.w_local[v];
+            rd += dl > 0 ? (cv.w_global[v] - wl) * (double)dl / wl : (double)dg;
+        } else if (sampled) {
             if (dl > 0) rd += (double)(dg - dl) * (double)sampled[i] / (double)dl;
         } else {
             ri += dg - dl;
@@ -372,17 +386,20 @@ __global__ __launch_bounds__(256) void stats_final_kernel(const StatsPartial* __
 
 grp_status launch_stats(int64_t n_rows, const int32_t* nodes, const uint8_t* mask, const int32_t* d_local,
                         const int64_t* d_global, const int32_t* sampled_count, int64_t nnz_const,
-                        const int64_t* const* nnz_parts, int n_parts, void* scratch, grp_step_stats* out, hipStream_t st) {
+                        const int64_t* const* nnz_parts, int n_parts, void* scratch, grp_step_stats* out, hipStream_t st,
+                        const double* w_local, const double* w_global) {
     NnzParts np;
     np.n = n_parts;
     for (int i = 0; i < GRP_MAX_LAYERS; ++i) np.p[i] = i < n_parts ? nnz_parts[i] : nullptr;
     ProfScope ps("coverage_stats", st);
     StatsPartial* part = (StatsPartial*)scratch;
-    hipLaunchKernelGGL(stats_partial_kernel, dim3(STATS_BLOCKS), dim3(256), 0, st, n_rows, nodes, mask, d_local, d_global,
-                       sampled_count, part);
+    if (w_local && sampled_count) return fail(GRP_EUNSUPPORTED, "coverage statistics: weight masses in mini-batch mode");
+    const CoverageIn cv{d_local, d_global, w_local, w_global};
+    hipLaunchKernelGGL(stats_partial_kernel, dim3(STATS_BLOCKS), dim3(256), 0, st, n_rows, nodes, mask, cv, sampled_count,
+                       part);
     GRP_LAUNCH_CHECK();
     hipLaunchKernelGGL(stats_final_kernel, dim3(1), dim3(256), 0, st, (const StatsPartial*)part, STATS_BLOCKS,
-                       sampled_count ? 0 : 1, nnz_const, np, out);
+                       (sampled_count || w_local) ? 0 : 1, nnz_const, np, out);
     GRP_LAUNCH_CHECK();
     return GRP_OK;
 }
@@ -394,8 +411,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(int64_t n_rows, int C
                                                            int64_t ldz, const int32_t* __restrict__ labels,
                                                            const int32_t* __restrict__ nodes,
                                                            const uint8_t* __restrict__ mask, int node_level,
-                                                           const int32_t* __restrict__ d_local,
-                                                           const int64_t* __restrict__ d_global,
+                                                           CoverageIn cv,
                                                            const float* __restrict__ rowscale,
                                                            float* __restrict__ dZ, int64_t lddz, int c_store,
                                                            const grp_step_stats* __restrict__ stats,
@@ -423,7 +439,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(int64_t n_rows, int C
         for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 16);
         const int y = labels[v];
         float w = 1.f;
-        if (node_level) w = (float)degree_ratio(d_local[v], d_global[v]);
+        if (node_level) w = (float)coverage_ratio(cv, v);
         const float k = w * inv_s * (rowscale ? rowscale[v] : 1.f), inv_sum = 1.0f / sum;
         for (int c = t; c < c_store; c += 16) {
             float g = 0.f;
@@ -444,8 +460,7 @@ __global__ __launch_bounds__(256) void softmax_xent_reg_kernel(int64_t n_rows, i
                                                                int64_t ldz, const int32_t* __restrict__ labels,
                                                                const int32_t* __restrict__ nodes,
                                                                const uint8_t* __restrict__ mask, int node_level,
-                                                               const int32_t* __restrict__ d_local,
-                                                               const int64_t* __restrict__ d_global,
+                                                               CoverageIn cv,
                                                                const float* __restrict__ rowscale,
                                                                float* __restrict__ dZ, int64_t lddz, int c_store,
                                                                const grp_step_stats* __restrict__ stats,
@@ -483,7 +498,7 @@ __global__ __launch_bounds__(256) void softmax_xent_reg_kernel(int64_t n_rows, i
             for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 16);
             const int y = labels[v];
             float w = 1.f;
-            if (node_level) w = (float)degree_ratio(d_local[v], d_global[v]);
+            if (node_level) w = (float)coverage_ratio(cv, v);
             const float k = w * inv_s * (rowscale ? rowscale[v] : 1.f), inv_sum = 1.0f / sum;
             float zy = 0.f;                           // the label's logit sits in lane y%16, slot y/16
 #pragma unroll
@@ -518,13 +533,15 @@ __global__ __launch_bounds__(256) void loss_final_kernel(const double* __restric
 grp_status launch_softmax_xent(int64_t n_rows, int32_t C, const float* Z, int64_t ldz, const int32_t* labels,
                                const int32_t* node_of_row, const uint8_t* mask, int32_t node_level,
                                const int32_t* d_local, const int64_t* d_global, const float* rowscale, float* dZ,
-                               int64_t lddz, void* scratch, grp_step_stats* stats, hipStream_t st) {
+                               int64_t lddz, void* scratch, grp_step_stats* stats, hipStream_t st,
+                               const double* w_local, const double* w_global) {
     ProfScope ps("softmax_xent", st, 0.0, 8.0 * n_rows * C);
+    const CoverageIn cv{d_local, d_global, w_local, w_global};
     double* loss_part = (double*)((char*)scratch + (size_t)STATS_BLOCKS * sizeof(StatsPartial));
     int c_store = (int)round_up(C, 4);
     if (c_store > lddz) c_store = (int)lddz;
 #define GRP_SOFTMAX_ARGS                                                                                     \
-    n_rows, C, Z, ldz, labels, node_of_row, mask, node_level, d_local, d_global, rowscale, dZ, lddz, c_store, \
+    n_rows, C, Z, ldz, labels, node_of_row, mask, node_level, cv, rowscale, dZ, lddz, c_store,               \
         (const grp_step_stats*)stats, loss_part
     if (c_store <= 16)
         hipLaunchKernelGGL(softmax_xent_reg_kernel<1>, dim3(STATS_BLOCKS), dim3(256), 0, st, GRP_SOFTMAX_ARGS);
@@ -537,6 +554,19 @@ grp_status launch_softmax_xent(int64_t n_rows, int32_t C, const float* Z, int64_
 #undef GRP_SOFTMAX_ARGS
     GRP_LAUNCH_CHECK();
     hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, st, (const double*)loss_part, STATS_BLOCKS, stats);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
+__global__ __launch_bounds__(256) void inverse_mass_kernel(const double* __restrict__ mass, int64_t n,
+                                                           float* __restrict__ inv) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v < n) inv[v] = mass[v] > 0.0 ? (float)(1.0 / mass[v]) : 0.f;
+}
+
+grp_status launch_inverse_mass(const double* mass, int64_t n, float* inv, hipStream_t st) {
+    if (n <= 0) return GRP_OK;
+    hipLaunchKernelGGL(inverse_mass_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, mass, n, inv);
     GRP_LAUNCH_CHECK();
     return GRP_OK;
 }

@@ -127,6 +127,50 @@ __global__ __launch_bounds__(256) void widen_kernel(const int32_t* __restrict__ 
     if (v < n) out[v] = in[v];
 }
 
+// ---- weighted partitions: deterministic slots (a scan over per-edge flags) so that equal
+// (dst, src) pairs keep their order in the edge list through the stable sorts.
+// which = 0: edges with both endpoints owned; which = 1: edges whose destination is owned.
+__global__ __launch_bounds__(256) void edge_select_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                          int64_t E, const int32_t* __restrict__ flag, int which,
+                                                          int32_t* __restrict__ sel) {
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256)
+        sel[e] = (flag[dst[e]] && (which == 1 || flag[src[e]])) ? 1 : 0;
+}
+
+__global__ __launch_bounds__(256) void edge_emit_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                        const float* __restrict__ w, int64_t E,
+                                                        const int32_t* __restrict__ sel, const int64_t* __restrict__ slot,
+                                                        const int64_t* __restrict__ pos, int which,
+                                                        uint64_t* __restrict__ keys, uint32_t* __restrict__ keys32,
+                                                        float* __restrict__ vals) {
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
+        if (!sel[e]) continue;
+        const int64_t s = slot[e];
+        if (which == 0) keys[s] = ((uint64_t)pos[dst[e]] << 32) | (uint64_t)pos[src[e]];
+        else keys32[s] = (uint32_t)pos[dst[e]];
+        vals[s] = w[e];
+    }
+}
+
+__global__ __launch_bounds__(256) void weight_check_kernel(const float* __restrict__ w, int64_t E,
+                                                           unsigned long long* __restrict__ bad) {
+    unsigned long long b = 0;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256)
+        if (!(w[e] > 0.f) || !(w[e] <= 3.402823466e+38f)) b++;
+    if (b) atomicAdd(bad, b);
+}
+
+// mass[r] = sum of vals over [ptr[r], ptr[r+1]) in stored order, fp64 (one thread per row: the order
+// of the additions is part of the result).
+__global__ __launch_bounds__(256) void row_mass_kernel(const int64_t* __restrict__ ptr, const float* __restrict__ vals,
+                                                       int64_t n, double* __restrict__ mass) {
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r >= n) return;
+    double s = 0.0;
+    for (int64_t k = ptr[r]; k < ptr[r + 1]; ++k) s += (double)vals[k];
+    mass[r] = s;
+}
+
 static unsigned grid_for(int64_t work) {
     int64_t b = cdiv(work > 0 ? work : 1, 256);
     return (unsigned)(b > 16384 ? 16384 : b);
@@ -151,7 +195,7 @@ static void free_partition(grp_partition_t* h) {
     void* ptrs[] = {h->l2g, h->rowptr, h->col, h->colptr, h->row, h->d_local_in, h->d_local_out, h->d_global_in,
                     h->csr_long.long_row, h->csr_long.long_first, h->csr_long.chunk_begin, h->csr_long.chunk_end,
                     h->csc_long.long_row, h->csc_long.long_first, h->csc_long.chunk_begin, h->csc_long.chunk_end,
-                    h->spmm_scratch, h->base_mask};
+                    h->spmm_scratch, h->base_mask, h->csr_w, h->csc_w, h->w_local_in, h->w_global_in};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
     delete h;
@@ -211,8 +255,15 @@ static grp_status build_long_rows(const int64_t* ptr_dev, int64_t n, LongRows* o
 }
 
 // keys (unsorted, nnz of them; clobbered) -> h->rowptr/col/d_local_in and h->colptr/row/d_local_out.
-static grp_status build_csr_csc(grp_partition_t* h, uint64_t* keys, uint64_t* keys_alt, hipStream_t st) {
+// vals / vals_alt (optional, nnz floats each; clobbered): a value per key that travels through the
+// (stable) sorts into h->csr_w and h->csc_w.
+static grp_status build_csr_csc(grp_partition_t* h, uint64_t* keys, uint64_t* keys_alt, hipStream_t st,
+                                float* vals = nullptr, float* vals_alt = nullptr) {
     const int64_t n = h->n, nnz = h->nnz;
+    if (vals) {
+        GRP_TRY(halloc(&h->csr_w, nnz));
+        GRP_TRY(halloc(&h->csc_w, nnz));
+    }
     GRP_TRY(halloc(&h->rowptr, n + 1));
     GRP_TRY(halloc(&h->colptr, n + 1));
     GRP_TRY(halloc(&h->col, nnz));
@@ -222,17 +273,27 @@ static grp_status build_csr_csc(grp_partition_t* h, uint64_t* keys, uint64_t* ke
     const unsigned end_bit = 32 + bits_for(n > 1 ? n : 2);
     size_t tmp_bytes = 0;
     DevBuf tmp;
-    if (nnz > 0) {
+    if (nnz > 0 && !vals) {
         GRP_HIP(rocprim::radix_sort_keys(nullptr, tmp_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
         GRP_TRY(tmp.alloc(tmp_bytes));
         GRP_HIP(rocprim::radix_sort_keys(tmp.p, tmp_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
+    } else if (nnz > 0) {
+        GRP_HIP(rocprim::radix_sort_pairs(nullptr, tmp_bytes, keys, keys_alt, vals, vals_alt, (size_t)nnz, 0u, end_bit, st));
+        GRP_TRY(tmp.alloc(tmp_bytes));
+        GRP_HIP(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, keys, keys_alt, vals, vals_alt, (size_t)nnz, 0u, end_bit, st));
+        GRP_HIP(hipMemcpyAsync(h->csr_w, vals_alt, (size_t)nnz * sizeof(float), hipMemcpyDeviceToDevice, st));
     }
     hipLaunchKernelGGL(csr_from_keys_kernel, dim3(grid_for(nnz + 1)), dim3(256), 0, st, keys_alt, nnz, n, h->rowptr, h->col);
     GRP_LAUNCH_CHECK();
     if (nnz > 0) {
         hipLaunchKernelGGL(swap_halves_kernel, dim3(grid_for(nnz)), dim3(256), 0, st, keys_alt, nnz, keys);
         GRP_LAUNCH_CHECK();
-        GRP_HIP(rocprim::radix_sort_keys(tmp.p, tmp_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
+        if (!vals) {
+            GRP_HIP(rocprim::radix_sort_keys(tmp.p, tmp_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
+        } else {      // from CSR order (vals_alt) to CSC order (vals)
+            GRP_HIP(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, keys, keys_alt, vals_alt, vals, (size_t)nnz, 0u, end_bit, st));
+            GRP_HIP(hipMemcpyAsync(h->csc_w, vals, (size_t)nnz * sizeof(float), hipMemcpyDeviceToDevice, st));
+        }
     }
     hipLaunchKernelGGL(csr_from_keys_kernel, dim3(grid_for(nnz + 1)), dim3(256), 0, st, keys_alt, nnz, n, h->colptr, h->row);
     GRP_LAUNCH_CHECK();
@@ -248,8 +309,12 @@ static grp_status build_csr_csc(grp_partition_t* h, uint64_t* keys, uint64_t* ke
     return GRP_OK;
 }
 
+static grp_status weighted_build(const int64_t* src, const int64_t* dst, const float* w, int64_t E, const int32_t* flag,
+                                 const int64_t* pos, hipStream_t st, grp_partition_t* h);
+
 static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t E, int64_t N, int32_t K, uint64_t seed,
-                                 int32_t part_id, hipStream_t st, grp_partition_t* h) {
+                                 int32_t part_id, hipStream_t st, grp_partition_t* h, const float* w = nullptr,
+                                 bool weighted = false) {
     DevBuf flag, pos, counters, scan_tmp;
     GRP_TRY(flag.alloc((size_t)N * sizeof(int32_t)));
     GRP_TRY(pos.alloc((size_t)N * sizeof(int64_t)));
@@ -296,6 +361,7 @@ static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t
         return fail(GRP_ERANGE, "%llu edges have an endpoint outside [0, %lld)", host_counters[1], (long long)N);
     const int64_t nnz = (int64_t)host_counters[0];
     h->nnz = nnz;
+    if (weighted) return weighted_build(src, dst, w, E, flag.as<int32_t>(), pos.as<int64_t>(), st, h);
     DevBuf keys, keys_alt;
     GRP_TRY(keys.alloc((size_t)nnz * sizeof(uint64_t)));
     GRP_TRY(keys_alt.alloc((size_t)nnz * sizeof(uint64_t)));
@@ -309,6 +375,99 @@ static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t
 
 // ------------------------------------------------------------------ halo partitions
 // One hop outwards: the source of every edge whose destination is already inside joins.
+// The rest of a weighted partition build (h->n, h->nnz, h->l2g, h->d_global_in are set; the ids are
+// range-checked): CSR/CSC with the edge weights carried along, then the weight masses.
+static grp_status weighted_build(const int64_t* src, const int64_t* dst, const float* w, int64_t E, const int32_t* flag,
+                                 const int64_t* pos, hipStream_t st, grp_partition_t* h) {
+    const int64_t n = h->n, nnz = h->nnz;
+    DevBuf bad, sel, slot, scan_tmp;
+    GRP_TRY(bad.alloc(sizeof(unsigned long long)));
+    GRP_HIP(hipMemsetAsync(bad.p, 0, sizeof(unsigned long long), st));
+    unsigned long long host_bad = 0;
+    if (E > 0) {
+        hipLaunchKernelGGL(weight_check_kernel, dim3(grid_for(E)), dim3(256), 0, st, w, E, bad.as<unsigned long long>());
+        GRP_LAUNCH_CHECK();
+        GRP_HIP(hipMemcpyAsync(&host_bad, bad.p, sizeof host_bad, hipMemcpyDeviceToHost, st));
+        GRP_HIP(hipStreamSynchronize(st));
+    }
+    if (host_bad) return fail(GRP_EINVAL, "%llu edge weights are not positive finite numbers", host_bad);
+    GRP_TRY(sel.alloc((size_t)E * sizeof(int32_t)));
+    GRP_TRY(slot.alloc((size_t)E * sizeof(int64_t)));
+    size_t scan_bytes = 0;
+    if (E > 0) {
+        GRP_HIP(rocprim::exclusive_scan(nullptr, scan_bytes, sel.as<int32_t>(), slot.as<int64_t>(), (int64_t)0, (size_t)E,
+                                        rocprim::plus<int64_t>(), st));
+        GRP_TRY(scan_tmp.alloc(scan_bytes));
+    }
+    auto select = [&](int which) -> grp_status {
+        if (E <= 0) return GRP_OK;
+        hipLaunchKernelGGL(edge_select_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, flag, which, sel.as<int32_t>());
+        GRP_LAUNCH_CHECK();
+        GRP_HIP(rocprim::exclusive_scan(scan_tmp.p, scan_bytes, sel.as<int32_t>(), slot.as<int64_t>(), (int64_t)0, (size_t)E,
+                                        rocprim::plus<int64_t>(), st));
+        return GRP_OK;
+    };
+    // ---- local edges with their weights
+    DevBuf keys, keys_alt, vals, vals_alt;
+    GRP_TRY(keys.alloc((size_t)nnz * sizeof(uint64_t)));
+    GRP_TRY(keys_alt.alloc((size_t)nnz * sizeof(uint64_t)));
+    GRP_TRY(vals.alloc((size_t)nnz * sizeof(float)));
+    GRP_TRY(vals_alt.alloc((size_t)nnz * sizeof(float)));
+    GRP_TRY(select(0));
+    if (nnz > 0) {
+        hipLaunchKernelGGL(edge_emit_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, w, E, sel.as<int32_t>(),
+                           slot.as<int64_t>(), pos, 0, keys.as<uint64_t>(), (uint32_t*)nullptr, vals.as<float>());
+        GRP_LAUNCH_CHECK();
+    }
+    GRP_TRY(build_csr_csc(h, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), st, vals.as<float>(), vals_alt.as<float>()));
+    GRP_TRY(halloc(&h->w_local_in, n));
+    GRP_TRY(halloc(&h->w_global_in, n));
+    if (n == 0) return GRP_OK;
+    hipLaunchKernelGGL(row_mass_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, h->rowptr, h->csr_w, n, h->w_local_in);
+    GRP_LAUNCH_CHECK();
+    // ---- every in-edge of an owned node, grouped by destination in edge-list order
+    DevBuf cnt, off;
+    GRP_TRY(cnt.alloc((size_t)(n + 1) * sizeof(int64_t)));
+    GRP_TRY(off.alloc((size_t)(n + 1) * sizeof(int64_t)));
+    GRP_HIP(hipMemsetAsync(cnt.p, 0, (size_t)(n + 1) * sizeof(int64_t), st));
+    GRP_HIP(hipMemcpyAsync(cnt.p, h->d_global_in, (size_t)n * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
+    {
+        size_t bytes = 0;
+        DevBuf tmp;
+        GRP_HIP(rocprim::exclusive_scan(nullptr, bytes, cnt.as<int64_t>(), off.as<int64_t>(), (int64_t)0, (size_t)(n + 1),
+                                        rocprim::plus<int64_t>(), st));
+        GRP_TRY(tmp.alloc(bytes));
+        GRP_HIP(rocprim::exclusive_scan(tmp.p, bytes, cnt.as<int64_t>(), off.as<int64_t>(), (int64_t)0, (size_t)(n + 1),
+                                        rocprim::plus<int64_t>(), st));
+        GRP_HIP(hipStreamSynchronize(st));        // tmp is released at the end of this scope
+    }
+    int64_t total = 0;
+    GRP_HIP(hipMemcpy(&total, off.as<int64_t>() + n, sizeof(int64_t), hipMemcpyDeviceToHost));
+    DevBuf k32, k32_alt, vin, vin_alt, sort_tmp;
+    GRP_TRY(k32.alloc((size_t)total * sizeof(uint32_t)));
+    GRP_TRY(k32_alt.alloc((size_t)total * sizeof(uint32_t)));
+    GRP_TRY(vin.alloc((size_t)total * sizeof(float)));
+    GRP_TRY(vin_alt.alloc((size_t)total * sizeof(float)));
+    if (total > 0) {
+        GRP_TRY(select(1));
+        hipLaunchKernelGGL(edge_emit_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, w, E, sel.as<int32_t>(),
+                           slot.as<int64_t>(), pos, 1, (uint64_t*)nullptr, k32.as<uint32_t>(), vin.as<float>());
+        GRP_LAUNCH_CHECK();
+        const unsigned end_bit = (unsigned)bits_for(n > 1 ? n : 2);
+        size_t bytes = 0;
+        GRP_HIP(rocprim::radix_sort_pairs(nullptr, bytes, k32.as<uint32_t>(), k32_alt.as<uint32_t>(), vin.as<float>(),
+                                          vin_alt.as<float>(), (size_t)total, 0u, end_bit, st));
+        GRP_TRY(sort_tmp.alloc(bytes));
+        GRP_HIP(rocprim::radix_sort_pairs(sort_tmp.p, bytes, k32.as<uint32_t>(), k32_alt.as<uint32_t>(), vin.as<float>(),
+                                          vin_alt.as<float>(), (size_t)total, 0u, end_bit, st));
+    }
+    hipLaunchKernelGGL(row_mass_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, off.as<int64_t>(),
+                       vin_alt.as<float>(), n, h->w_global_in);
+    GRP_LAUNCH_CHECK();
+    GRP_HIP(hipStreamSynchronize(st));
+    return GRP_OK;
+}
+
 __global__ __launch_bounds__(256) void halo_grow_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
                                                         int64_t E, int64_t N, const int32_t* __restrict__ inner,
                                                         int32_t* __restrict__ member, unsigned long long* __restrict__ bad) {
@@ -718,6 +877,39 @@ extern "C" grp_status grp_partition(const int64_t* src, const int64_t* dst, int6
         return s;
     }
     *out = h;
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_partition_weighted(const int64_t* src, const int64_t* dst, const float* w, int64_t E, int64_t N,
+                                             int32_t K, uint64_t seed, int32_t part_id, void* stream,
+                                             grp_partition_t** out) {
+    using namespace grp;
+    if (!out) return fail(GRP_EINVAL, "grp_partition_weighted: out is null");
+    *out = nullptr;
+    if (E < 0 || N < 0) return fail(GRP_EINVAL, "grp_partition_weighted: negative size");
+    if (E > 0 && (!src || !dst)) return fail(GRP_EINVAL, "grp_partition_weighted: null edge arrays");
+    if (E > 0 && !w) return fail(GRP_EINVAL, "grp_partition_weighted: null weights");
+    if (K < 1) return fail(GRP_EINVAL, "grp_partition_weighted: K = %d < 1", K);
+    if (part_id < 0 || part_id >= K)
+        return fail(GRP_EINVAL, "grp_partition_weighted: part_id %d outside [0, %d)", part_id, K);
+    grp_partition_t* h = new (std::nothrow) grp_partition_t();
+    if (!h) return fail(GRP_ENOMEM, "grp_partition_weighted: host allocation failed");
+    (void)hipGetDevice(&h->device);
+    const grp_status s = partition_impl(src, dst, E, N, K, seed, part_id, (hipStream_t)stream, h, w, true);
+    if (s != GRP_OK) {
+        free_partition(h);
+        return s;
+    }
+    *out = h;
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_partition_weights(const grp_partition_t* part, grp_partition_weights_t* view) {
+    if (!part || !view) return grp::fail(GRP_EINVAL, "grp_partition_weights: null argument");
+    view->csr_w = part->csr_w;
+    view->csc_w = part->csc_w;
+    view->w_local_in = part->w_local_in;
+    view->w_global_in = part->w_global_in;
     return GRP_OK;
 }
 

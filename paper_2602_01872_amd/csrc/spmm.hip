@@ -1,6 +1,7 @@
 // Row-parallel neighbour aggregation (SpMM) for gfx950.
 //
-// Y[i,:] = a_i (sum_{e in row i} c_{idx[e]} X[idx[e],:] + self * X[i,:]) (+ addend[i,:]) (+ bias) (ReLU)
+// Y[i,:] = a_i (sum_{e in row i} w_e c_{idx[e]} X[idx[e],:] + self * X[i,:]) (+ addend[i,:]) (+ bias) (ReLU)
+// (w_e: optional per-edge values, the weighted-mean aggregator of weighted partitions)
 //
 // The same kernels serve the forward pass (rows of the CSR: destinations gathering their
 // in-neighbours) and the backward pass (rows of the CSC: the transposed operator), so no
@@ -56,20 +57,27 @@ __device__ __forceinline__ void add4(float4& acc, const float4& v) {
 }
 
 // Sum of X rows over the edges [b, e) for the calling group of G lanes (lane t).
-template <typename XT, int G, int NJ>
-__device__ __forceinline__ void gather_rows(const int32_t* __restrict__ idx, int64_t b, int64_t e,
-                                            const XT* __restrict__ X, int64_t ldx,
+// EV: every edge carries a value val[e] that multiplies its gathered row.
+template <typename XT, int G, int NJ, bool EV>
+__device__ __forceinline__ void gather_rows(const int32_t* __restrict__ idx, const float* __restrict__ val, int64_t b,
+                                            int64_t e, const XT* __restrict__ X, int64_t ldx,
                                             const float* __restrict__ colscale, int t, const bool (&live)[NJ],
                                             float4 (&acc)[NJ]) {
     for (int64_t base = b; base < e; base += G) {
         const int cnt = (int)((e - base) < (int64_t)G ? (e - base) : (int64_t)G);
         const int mine = (t < cnt) ? idx[base + t] : 0;
+        float minew = 1.f;
+        if (EV) minew = (t < cnt) ? val[base + t] : 0.f;
         int k = 0;
         for (; k + 4 <= cnt; k += 4) {
             const int64_t c0 = __shfl(mine, k, G), c1 = __shfl(mine, k + 1, G);
             const int64_t c2 = __shfl(mine, k + 2, G), c3 = __shfl(mine, k + 3, G);
             float s0 = 1.f, s1 = 1.f, s2 = 1.f, s3 = 1.f;
             if (colscale) { s0 = colscale[c0]; s1 = colscale[c1]; s2 = colscale[c2]; s3 = colscale[c3]; }
+            if (EV) {
+                s0 *= __shfl(minew, k, G); s1 *= __shfl(minew, k + 1, G);
+                s2 *= __shfl(minew, k + 2, G); s3 *= __shfl(minew, k + 3, G);
+            }
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
                 if (!live[j]) continue;
@@ -78,7 +86,7 @@ __device__ __forceinline__ void gather_rows(const int32_t* __restrict__ idx, int
                 const float4 v1 = Vec4Load<XT>::ld(X + c1 * ldx + col);
                 const float4 v2 = Vec4Load<XT>::ld(X + c2 * ldx + col);
                 const float4 v3 = Vec4Load<XT>::ld(X + c3 * ldx + col);
-                if (colscale) {
+                if (EV || colscale) {
                     axpy4(acc[j], s0, v0); axpy4(acc[j], s1, v1); axpy4(acc[j], s2, v2); axpy4(acc[j], s3, v3);
                 } else {
                     add4(acc[j], v0); add4(acc[j], v1); add4(acc[j], v2); add4(acc[j], v3);
@@ -87,7 +95,8 @@ __device__ __forceinline__ void gather_rows(const int32_t* __restrict__ idx, int
         }
         for (; k < cnt; ++k) {
             const int64_t c0 = __shfl(mine, k, G);
-            const float s0 = colscale ? colscale[c0] : 1.f;
+            float s0 = colscale ? colscale[c0] : 1.f;
+            if (EV) s0 *= __shfl(minew, k, G);
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
                 if (!live[j]) continue;
@@ -112,12 +121,13 @@ struct SpmmEpilogue {
     int64_t addend_rows;      // rows >= this have no addend
     const float* mask;        // keep where mask > 0 (after the ReLU); null otherwise
     int64_t ld_mask;
+    const float* rowscale;    // a_i given explicitly; null: from `scale` and the row length
 };
 
 template <typename XT>
 __device__ __forceinline__ void finish_row(const SpmmEpilogue& ep, int64_t i, int64_t deg, int col, float4 r,
                                            const XT* __restrict__ X, int64_t ldx) {
-    const float a = row_scale(ep.scale, deg, ep.self_term);
+    const float a = ep.rowscale ? ep.rowscale[i] : row_scale(ep.scale, deg, ep.self_term);
     if (ep.self_term) add4(r, Vec4Load<XT>::ld(X + i * ldx + col));
     r.x *= a; r.y *= a; r.z *= a; r.w *= a;
     if (ep.addend && i < ep.addend_rows) add4(r, *reinterpret_cast<const float4*>(ep.addend + i * ep.ld_add + col));
@@ -148,8 +158,9 @@ __device__ __forceinline__ void finish_row(const SpmmEpilogue& ep, int64_t i, in
 }
 
 // One workgroup per chunk of a long row -> one partial row.
-template <typename XT, int G, int NJ>
-__device__ __forceinline__ void chunk_body(int64_t cb, int64_t ce, const int32_t* __restrict__ idx, int F,
+template <typename XT, int G, int NJ, bool EV>
+__device__ __forceinline__ void chunk_body(int64_t cb, int64_t ce, const int32_t* __restrict__ idx,
+                                           const float* __restrict__ val, int F,
                                            const XT* __restrict__ X, int64_t ldx, const float* __restrict__ colscale,
                                            float* __restrict__ part_row, float* red) {
     constexpr int NG = 256 / G;
@@ -166,7 +177,7 @@ __device__ __forceinline__ void chunk_body(int64_t cb, int64_t ce, const int32_t
         acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
         live[j] = 4 * (t + G * j) < F;
     }
-    gather_rows<XT, G, NJ>(idx, b, e, X, ldx, colscale, t, live, acc);
+    gather_rows<XT, G, NJ, EV>(idx, val, b, e, X, ldx, colscale, t, live, acc);
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
         *reinterpret_cast<float4*>(&red[gi * W + 4 * (t + G * j)]) = acc[j];
@@ -184,9 +195,10 @@ __device__ __forceinline__ void chunk_body(int64_t cb, int64_t ce, const int32_t
 // are the heavy ones, so they start first); the others take the rows of at most `long_thr`
 // edges, one group per row.  One launch instead of two keeps the few chunk workgroups from
 // running on an otherwise idle chip.
-template <typename XT, int G, int NJ>
+template <typename XT, int G, int NJ, bool EV>
 __global__ __launch_bounds__(256) void spmm_rows_kernel(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx,
-                                                        int64_t n_rows, int64_t long_thr, const XT* __restrict__ X,
+                                                        const float* __restrict__ val, int64_t n_rows, int64_t long_thr,
+                                                        const XT* __restrict__ X,
                                                         int64_t ldx, const float* __restrict__ colscale,
                                                         SpmmEpilogue ep, int n_chunks,
                                                         const int64_t* __restrict__ chunk_begin,
@@ -195,7 +207,7 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(const int64_t* __restric
     constexpr int ROWS = 256 / G;
     __shared__ __attribute__((aligned(16))) float red[ROWS * 4 * G * NJ];
     if ((int)blockIdx.x < n_chunks) {              // uniform per workgroup
-        chunk_body<XT, G, NJ>(chunk_begin[blockIdx.x], chunk_end[blockIdx.x], idx, ep.F, X, ldx, colscale,
+        chunk_body<XT, G, NJ, EV>(chunk_begin[blockIdx.x], chunk_end[blockIdx.x], idx, val, ep.F, X, ldx, colscale,
                               partials + (int64_t)blockIdx.x * ld_part, red);
         return;
     }
@@ -211,7 +223,7 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(const int64_t* __restric
         acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
         live[j] = 4 * (t + G * j) < ep.F;
     }
-    gather_rows<XT, G, NJ>(idx, b, e, X, ldx, colscale, t, live, acc);
+    gather_rows<XT, G, NJ, EV>(idx, val, b, e, X, ldx, colscale, t, live, acc);
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
         if (live[j]) finish_row<XT>(ep, i, e - b, 4 * (t + G * j), acc[j], X, ldx);
@@ -248,16 +260,16 @@ __global__ __launch_bounds__(256) void spmm_rows_scalar_kernel(
     const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx, int64_t n_rows, int F,
     const XT* __restrict__ X, int64_t ldx, int scale, int self_term, const float* __restrict__ colscale,
     const float* addend, int64_t ld_add, const float* __restrict__ bias, int relu,
-    float* Y, int64_t ldy) {
+    float* Y, int64_t ldy, const float* __restrict__ val, const float* __restrict__ rowscale) {
     const int64_t i = (int64_t)blockIdx.x * 4 + threadIdx.x / 64;
     if (i >= n_rows) return;
     const int t = threadIdx.x % 64;
     const int64_t b = ptr[i], e = ptr[i + 1];
-    const float a = row_scale(scale, e - b, self_term);
+    const float a = rowscale ? rowscale[i] : row_scale(scale, e - b, self_term);
     for (int col = t; col < F; col += 64) {
         float acc = 0.f;
         for (int64_t k = b; k < e; ++k)
-            acc = fmaf(colscale ? colscale[idx[k]] : 1.f, (float)X[(int64_t)idx[k] * ldx + col], acc);
+            acc = fmaf((colscale ? colscale[idx[k]] : 1.f) * (val ? val[k] : 1.f), (float)X[(int64_t)idx[k] * ldx + col], acc);
         if (self_term) acc += (float)X[i * ldx + col];
         acc *= a;
         if (addend) acc += addend[i * ld_add + col];
@@ -275,9 +287,15 @@ static void launch_one(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_t st
     const int64_t thr = split ? (int64_t)SPMM_LONG_ROW : INT64_MAX;
     const int n_chunks = split ? lr->n_chunks : 0;
     const int64_t ld_part = round_up(a.F, 4);
-    hipLaunchKernelGGL((spmm_rows_kernel<XT, G, NJ>), dim3((unsigned)(n_chunks + cdiv(a.n_rows, ROWS))), dim3(256), 0, st,
-                       a.ptr, a.idx, a.n_rows, thr, (const XT*)a.X, a.ldx, a.colscale, ep, n_chunks,
-                       split ? lr->chunk_begin : nullptr, split ? lr->chunk_end : nullptr, a.partials, ld_part);
+    const dim3 grid((unsigned)(n_chunks + cdiv(a.n_rows, ROWS)));
+    if (a.val)
+        hipLaunchKernelGGL((spmm_rows_kernel<XT, G, NJ, true>), grid, dim3(256), 0, st, a.ptr, a.idx, a.val, a.n_rows, thr,
+                           (const XT*)a.X, a.ldx, a.colscale, ep, n_chunks, split ? lr->chunk_begin : nullptr,
+                           split ? lr->chunk_end : nullptr, a.partials, ld_part);
+    else
+        hipLaunchKernelGGL((spmm_rows_kernel<XT, G, NJ, false>), grid, dim3(256), 0, st, a.ptr, a.idx, a.val, a.n_rows, thr,
+                           (const XT*)a.X, a.ldx, a.colscale, ep, n_chunks, split ? lr->chunk_begin : nullptr,
+                           split ? lr->chunk_end : nullptr, a.partials, ld_part);
     if (split) {
         hipLaunchKernelGGL((spmm_combine_kernel<XT, G, NJ>), dim3((unsigned)cdiv(lr->n_long, ROWS)), dim3(256), 0, st,
                            lr->long_row, lr->long_first, lr->n_long, a.ptr, (const float*)a.partials, ld_part,
@@ -320,7 +338,7 @@ grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
     const int64_t n_src = a.n_src > 0 ? a.n_src : a.n_rows;
     const double bytes = 4.0 * a.nnz + 8.0 * (a.n_rows + 1) + (double)elem * a.F * n_src +
                          4.0 * a.F * a.n_rows * (1.0 + (a.addend ? 1.0 : 0.0) + (a.mask ? 1.0 : 0.0)) +
-                         (a.colscale ? 4.0 * n_src : 0.0);
+                         (a.colscale ? 4.0 * n_src : 0.0) + (a.val ? 4.0 * a.nnz : 0.0);
     prof_detail("[rows=%lld,F=%d,nnz=%lld]", (long long)a.n_rows, a.F, (long long)a.nnz);
     ProfScope ps(a.x_bf16 ? "spmm_rows_bf16" : "spmm_rows_f32", st, 2.0 * a.nnz * a.F, bytes);
     if (vec_ok) {
@@ -333,7 +351,8 @@ grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
         if (a.mask && (a.ld_mask % 4 != 0 || a.ld_mask < fpad || (uintptr_t)a.mask % 16 != 0))
             return fail(GRP_EINVAL, "spmm: mask must be 16-byte aligned with a pitch multiple of 4");
         SpmmEpilogue ep{a.scale, a.self_term, a.relu, a.F, a.addend, a.ld_add, a.bias, a.Y, a.ldy,
-                        a.residual, a.ld_res, a.Y2, a.ldy2, a.addend_rows > 0 ? a.addend_rows : a.n_rows, a.mask, a.ld_mask};
+                        a.residual, a.ld_res, a.Y2, a.ldy2, a.addend_rows > 0 ? a.addend_rows : a.n_rows, a.mask, a.ld_mask,
+                        a.rowscale};
         GRP_TRY(a.x_bf16 ? dispatch<__hip_bfloat16>(a, ep, st) : dispatch<float>(a, ep, st));
     } else {
         if (a.residual || a.Y2 || a.mask || a.addend_rows > 0)
@@ -342,11 +361,11 @@ grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
         if (a.x_bf16)
             hipLaunchKernelGGL((spmm_rows_scalar_kernel<__hip_bfloat16>), dim3((unsigned)blocks), dim3(256), 0, st,
                                a.ptr, a.idx, a.n_rows, a.F, (const __hip_bfloat16*)a.X, a.ldx, a.scale,
-                               a.self_term, a.colscale, a.addend, a.ld_add, a.bias, a.relu, a.Y, a.ldy);
+                               a.self_term, a.colscale, a.addend, a.ld_add, a.bias, a.relu, a.Y, a.ldy, a.val, a.rowscale);
         else
             hipLaunchKernelGGL((spmm_rows_scalar_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, st, a.ptr,
                                a.idx, a.n_rows, a.F, (const float*)a.X, a.ldx, a.scale, a.self_term, a.colscale, a.addend,
-                               a.ld_add, a.bias, a.relu, a.Y, a.ldy);
+                               a.ld_add, a.bias, a.relu, a.Y, a.ldy, a.val, a.rowscale);
     }
     GRP_LAUNCH_CHECK();
     return GRP_OK;

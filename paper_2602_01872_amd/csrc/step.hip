@@ -163,6 +163,8 @@ static grp_status check_step_args(const grp_partition_t* part, const grp_model_d
     if (model->arch == GRP_ARCH_GCN_RESIDUAL && model->feat_dtype == GRP_DTYPE_BF16 && model->n_layers > 1 &&
         model->dims[0] == model->dims[1])
         return fail(GRP_EUNSUPPORTED, "train_step: a residual first layer needs fp32 features");
+    if (part->csr_w && (model->arch != GRP_ARCH_SAGE_MEAN || !opts->full_graph))
+        return fail(GRP_EUNSUPPORTED, "train_step: a weighted partition trains GraphSAGE in full-graph mode only");
     if (!(opts->dropout_rate >= 0.f && opts->dropout_rate < 1.f))
         return fail(GRP_EINVAL, "train_step: dropout rate outside [0, 1)");
     if (opts->dropout_rate > 0.f && !opts->full_graph)
@@ -186,6 +188,14 @@ static void fill_spmm(SpmmArgs& s, const Block& B, bool transposed, float* parti
     s.n_src = transposed ? B.n_dst : B.n_in;
     s.long_rows = transposed ? B.long_bwd : B.long_fwd;
     s.partials = partials;
+    s.val = transposed ? B.valT : B.val;
+}
+
+// The mean aggregator of a block: 1 / row length, or on a weighted partition the explicit
+// 1 / (local weight mass) beside the per-edge weights fill_spmm has set.
+static void set_mean(SpmmArgs& s, const Block& B) {
+    if (B.val) s.rowscale = B.inv_in;
+    else s.scale = GRP_SCALE_MEAN;
 }
 
 // bwd_scale multiplies the weights of the products that carry a gradient back through a layer
@@ -228,7 +238,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
         if (L.agg_first) {
             SpmmArgs s;
             fill_spmm(s, B, false, p.partials);
-            s.F = fin; s.X = H; s.ldx = ldh; s.x_bf16 = h_bf16; s.scale = GRP_SCALE_MEAN; s.Y = L.M; s.ldy = ldp(fin);
+            s.F = fin; s.X = H; s.ldx = ldh; s.x_bf16 = h_bf16; set_mean(s, B); s.Y = L.M; s.ldy = ldp(fin);
             GRP_TRY(launch_spmm(s, st));
             GemmNNArgs a;
             a.M = B.n_dst; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.a_rows = B.self_rows;
@@ -247,7 +257,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             GRP_TRY(launch_gemm_nn(a, st));
             SpmmArgs s;
             fill_spmm(s, B, false, p.partials);
-            s.F = fout; s.X = p.tmpA; s.ldx = w2; s.scale = GRP_SCALE_MEAN;
+            s.F = fout; s.X = p.tmpA; s.ldx = w2; set_mean(s, B);
             s.addend = p.tmpA + ldp(fout); s.ld_add = w2; s.relu = relu; s.Y = L.H_out; s.ldy = ldp(fout);
             GRP_TRY(launch_spmm(s, st));
         } else {
@@ -259,7 +269,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             GRP_TRY(launch_gemm_nn(a, st));
             SpmmArgs s;
             fill_spmm(s, B, false, p.partials);
-            s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout); s.scale = GRP_SCALE_MEAN;
+            s.F = fout; s.X = p.tmpA; s.ldx = ldp(fout); set_mean(s, B);
             s.addend = L.H_out; s.ld_add = ldp(fout); s.relu = relu; s.Y = L.H_out; s.ldy = ldp(fout);
             GRP_TRY(launch_spmm(s, st));
         }
@@ -274,7 +284,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
     float* dZ_other = p.dZb;
     GRP_TRY(launch_softmax_xent(n_loss_rows, C, p.L[k - 1].H_out, ldp(C), labels, loss_nodes, mask,
                                 o->estimator == GRP_EST_NODE_LEVEL, g->d_local_in, g->d_global_in, nullptr, dZ, ldp(C),
-                                p.stats_ws, stats, st));
+                                p.stats_ws, stats, st, g->w_local_in, g->w_global_in));
 
     // ---------------- backward
     for (int l = k - 1; l >= 0; --l) {
@@ -475,15 +485,16 @@ extern "C" grp_status grp_train_step(const grp_partition_t* part, const grp_mode
 
     Block blocks[GRP_MAX_LAYERS];
     if (opts->full_graph) {
-        GRP_TRY(launch_degree_scales(part->d_local_in, part->d_local_out, n, 0, p.inv_in, nullptr, nullptr, nullptr, st));
+        if (part->csr_w) GRP_TRY(launch_inverse_mass(part->w_local_in, n, p.inv_in, st));
+        else GRP_TRY(launch_degree_scales(part->d_local_in, part->d_local_out, n, 0, p.inv_in, nullptr, nullptr, nullptr, st));
         for (int l = 0; l < k; ++l) {
             Block& B = blocks[l];
             B.n_dst = B.n_in = n; B.nnz = part->nnz; B.ptr = part->rowptr; B.idx = part->col;
             B.ptrT = part->colptr; B.idxT = part->row; B.long_fwd = &part->csr_long; B.long_bwd = &part->csc_long;
-            B.inv_in = p.inv_in;
+            B.inv_in = p.inv_in; B.val = part->csr_w; B.valT = part->csc_w;
         }
         GRP_TRY(launch_stats(n, nullptr, train_mask, part->d_local_in, part->d_global_in, nullptr, part->nnz, nullptr, 0,
-                             p.stats_ws, stats_out, st));
+                             p.stats_ws, stats_out, st, part->w_local_in, part->w_global_in));
         return sage_step(part, model, opts, blocks, features, labels, train_mask, nullptr, weights, p, st, grad_out,
                          stats_out);
     }

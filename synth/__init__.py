@@ -137,6 +137,16 @@ def train_mask(n: int, frac: float, seed: int, device="cpu") -> torch.Tensor:
     return (_unit(stream_bits(seed, 6, i)) < frac).to(torch.uint8)
 
 
+def edge_weights(n_edges: int, seed: int, lo: float = 0.25, hi: float = 4.0, device="cpu", chunk: int = 1 << 26) -> torch.Tensor:
+    """float32 edge weights, log-uniform in [lo, hi) (a stand-in for similarity / frequency weights)."""
+    out = torch.empty(n_edges, dtype=torch.float32, device=device)
+    for b in range(0, n_edges, chunk):
+        e = torch.arange(b, min(n_edges, b + chunk), dtype=torch.int64, device=device)
+        u = _unit(stream_bits(seed, 9, e))
+        out[b:b + e.numel()] = (lo * (hi / lo) ** u).to(torch.float32)
+    return out
+
+
 def stand_in_global_degree(d_local: torch.Tensor, gids: torch.Tensor, seed: int,
                            mean_missing_shares: int) -> torch.Tensor:
     """Global in-degree for a directly generated local subgraph.
