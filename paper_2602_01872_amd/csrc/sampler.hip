@@ -7,7 +7,7 @@
 // The keys depend only on (seed, batch, layer, node, position), so the selection is
 // independent of scheduling and bit-reproducible.
 //
-// Selection for a row of d > fanout edges (one wavefront per row): keys are uniform, so the
+// Selection for a row of d > fanout edges (one wavefront per row, four for very long rows): keys are uniform, so the
 // fanout-th smallest is near fanout/d * 2^64; edges with key <= T (T = 4x that) are compacted
 // into an LDS candidate list, T is doubled / halved until the list holds between fanout and
 // SAMPLE_CAND entries (it does at the first try with overwhelming probability), and the
@@ -66,22 +66,33 @@ __global__ __launch_bounds__(256) void sample_count_kernel(const int64_t* __rest
     if (cnt32) cnt32[i] = (int32_t)c;
 }
 
-// One wavefront (= one workgroup of 64 threads) per destination row.
-__global__ __launch_bounds__(64) void sample_select_kernel(const int64_t* __restrict__ rowptr,
-                                                           const int32_t* __restrict__ col,
-                                                           const int64_t* __restrict__ l2g,
-                                                           const int32_t* __restrict__ dst_nodes, int fanout,
-                                                           uint64_t h2, const int64_t* __restrict__ out_ptr,
-                                                           int32_t* __restrict__ out_idx) {
+// One workgroup of SAMPLE_WAVES wavefronts per destination row.  Rows of at most SAMPLE_MULTI edges
+// are handled by the first wavefront alone (the others leave at once); longer rows (the hubs of a
+// skewed graph, 10^5 edges and more) are scanned by the whole workgroup, which appends its
+// candidates to the LDS list through an LDS counter.  The list's order then depends on timing,
+// the selection does not: it is the `fanout` smallest (key, position) pairs.
+constexpr int SAMPLE_WAVES = 4;
+constexpr int SAMPLE_MULTI = 2048;
+
+__global__ __launch_bounds__(64 * SAMPLE_WAVES) void sample_select_kernel(const int64_t* __restrict__ rowptr,
+                                                                          const int32_t* __restrict__ col,
+                                                                          const int64_t* __restrict__ l2g,
+                                                                          const int32_t* __restrict__ dst_nodes,
+                                                                          int fanout, uint64_t h2,
+                                                                          const int64_t* __restrict__ out_ptr,
+                                                                          int32_t* __restrict__ out_idx) {
     __shared__ uint64_t ckey[SAMPLE_CAND];
     __shared__ int32_t cj[SAMPLE_CAND];
     __shared__ int32_t sel[SAMPLE_MAX_FANOUT];
-    const int lane = threadIdx.x;
+    __shared__ int cand_count;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t v = dst_nodes[blockIdx.x];
     const int64_t b = rowptr[v];
     const int64_t d = rowptr[v + 1] - b;
     const int64_t o = out_ptr[blockIdx.x];
-    if (d <= fanout) {                                   // uniform over the wavefront
+    const bool multi = d > SAMPLE_MULTI;                 // uniform over the workgroup
+    if (!multi && wave > 0) return;
+    if (d <= fanout) {
         for (int64_t j = lane; j < d; j += 64) out_idx[o + j] = col[b + j];
         return;
     }
@@ -92,22 +103,41 @@ __global__ __launch_bounds__(64) void sample_select_kernel(const int64_t* __rest
     int count = 0;
     bool have = false;
     for (int iter = 0; iter < 96 && !have; ++iter) {
-        count = 0;
-        for (int64_t base = 0; base < d; base += 64) {
-            const int64_t j = base + lane;
-            const bool valid = j < d;
-            const uint64_t key = valid ? mixM(h3 ^ (uint64_t)j) : ~0ull;
-            const bool take = valid && key <= T;
-            const unsigned long long m = __ballot(take);
-            const int pos = count + __popcll(m & ((1ull << lane) - 1ull));
-            if (take && pos < SAMPLE_CAND) { ckey[pos] = key; cj[pos] = (int32_t)j; }
-            count += __popcll(m);
+        if (multi) {
+            if (tid == 0) cand_count = 0;
+            __syncthreads();
+            for (int64_t j = tid; j < d; j += 64 * SAMPLE_WAVES) {
+                const uint64_t key = mixM(h3 ^ (uint64_t)j);
+                if (key <= T) {
+                    const int pos = atomicAdd(&cand_count, 1);
+                    if (pos < SAMPLE_CAND) { ckey[pos] = key; cj[pos] = (int32_t)j; }
+                }
+            }
+            __syncthreads();
+            count = cand_count;
+            __syncthreads();                             // everyone has read it before the next reset
+        } else {
+            count = 0;
+            for (int64_t base = 0; base < d; base += 64) {
+                const int64_t j = base + lane;
+                const bool valid = j < d;
+                const uint64_t key = valid ? mixM(h3 ^ (uint64_t)j) : ~0ull;
+                const bool take = valid && key <= T;
+                const unsigned long long m = __ballot(take);
+                const int pos = count + __popcll(m & ((1ull << lane) - 1ull));
+                if (take && pos < SAMPLE_CAND) { ckey[pos] = key; cj[pos] = (int32_t)j; }
+                count += __popcll(m);
+            }
         }
         if (count < fanout) T = T > (~0ull >> 1) ? ~0ull : (T << 1) | 1ull;
         else if (count > SAMPLE_CAND) T >>= 1;
         else have = true;
     }
-    __syncthreads();
+    // The first wavefront finishes the row.  No workgroup barrier from here on (the others have
+    // left); the candidates were published by the scan's last barrier, and a single wavefront's
+    // LDS accesses complete in program order.
+    if (wave > 0) return;
+    __builtin_amdgcn_wave_barrier();
 
     uint64_t last_k = 0;
     int32_t last_j = -1;
@@ -131,7 +161,7 @@ __global__ __launch_bounds__(64) void sample_select_kernel(const int64_t* __rest
         last_j = bj;
         if (lane == 0) sel[r] = bj;
     }
-    __syncthreads();
+    __builtin_amdgcn_wave_barrier();
     if (lane < fanout) {                                 // positions are distinct: rank = output slot
         const int32_t myj = sel[lane];
         int rank = 0;
@@ -315,7 +345,7 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
         GRP_TRY(exclusive_scan_i64(s.scan_tmp, s.scan_bytes, L.cnt, L.ptr, n_dst + 1, st));
         {
             ProfScope ps("sample_select", st);
-            hipLaunchKernelGGL(sample_select_kernel, dim3((unsigned)n_dst), dim3(64), 0, st, part->rowptr, part->col, part->l2g,
+            hipLaunchKernelGGL(sample_select_kernel, dim3((unsigned)n_dst), dim3(64 * SAMPLE_WAVES), 0, st, part->rowptr, part->col, part->l2g,
                                dst_nodes, f, mixM(h1 ^ (uint64_t)l), (const int64_t*)L.ptr, L.idx_local);
             GRP_LAUNCH_CHECK();
         }

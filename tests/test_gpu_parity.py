@@ -390,7 +390,7 @@ def test_minibatch_train_step_matches_oracle(g, dims, fanouts, bf16, n_seeds):
     op = ograph.partition(s.cpu().numpy(), d.cpu().numpy(), N, K, 1, 0)
     n = part.n
     dl = op["d_local_in"]
-    assert dl.max() > 2000                                     # a hub row: the threshold path of the sampler
+    assert dl.max() > 4096                                     # a hub row: the threshold path of the sampler, scanned by a whole workgroup
     # seeds: the hub, an isolated node, and a seeded spread of others (distinct)
     order = np.argsort(synth.stream_bits(5, 77, torch.arange(n)).numpy(), kind="stable")
     hub, iso = int(dl.argmax()), int(np.flatnonzero(dl == 0)[0])
