@@ -77,6 +77,23 @@ def _kernel_table(g, torch, fn, steps, detail=False):
     return kernels
 
 
+def _device_copy_gbs(torch, dev):
+    """Measured read+write rate of a plain 1 GiB device-to-device copy (the practical HBM ceiling that
+    the published 8 TB/s peak is quoted beside)."""
+    src = torch.ones(1 << 28, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    reps = 10
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    del src, dst
+    return 2.0 * (1 << 30) / dt / 1e9
+
+
 def _roofline(kernels, traffic_table):
     dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     k = kernels[dom]
@@ -114,7 +131,7 @@ def run_evidence_workload(args, g, synth, torch, dev):
         torch.cuda.synchronize()
         del cal_src, cal_dst
     out = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
-           "vs_baseline": None, "data": "synthetic"}
+           "vs_baseline": None, "data": "synthetic", "device_copy_GBs": _device_copy_gbs(torch, dev)}
     if wl == "aggregate-stress":
         K, P = 64, 1 << 26                                  # 17 GB of gradients: shows the kernel's bandwidth
         grads = torch.empty(K, P, device=dev).normal_()
@@ -392,6 +409,9 @@ def main():
                    "n_local": part.n, "nnz_local": nnz, "params": P, "small": bool(args.small)},
         "roofline": roofline,
         "kernels": kernels,
+        # every layer aggregates forward and all but the first also over the transposed graph
+        "edge_traversals_per_s": edges_per_s * (2 * 3 - 1),
+        "device_copy_GBs": _device_copy_gbs(torch, dev),
     }
 
     if not args.no_cpu_baseline:

@@ -64,18 +64,55 @@ __global__ __launch_bounds__(256) void edge_scan_kernel(const int64_t* __restric
 }
 
 // Pass 2: write the key (dst_local << 32 | src_local) of every kept edge.  The slot order is
-// arbitrary (integer atomic cursor); the sort that follows makes the result canonical.
+// arbitrary; the sort that follows makes the result canonical.  A workgroup takes tiles of
+// 256 x 8 edges, counts its kept edges through LDS and reserves their slots with one atomic
+// per tile (one atomic per kept edge on a single address would serialise the whole pass).
 __global__ __launch_bounds__(256) void edge_keys_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
                                                         int64_t E, const int32_t* __restrict__ flag,
                                                         const int64_t* __restrict__ pos,
                                                         unsigned long long* __restrict__ cursor,
-                                                        uint64_t* __restrict__ keys) {
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
-        const int64_t u = src[e], v = dst[e];
-        if (flag[v] && flag[u]) {
-            const unsigned long long slot = atomicAdd(cursor, 1ull);
-            keys[slot] = ((uint64_t)pos[v] << 32) | (uint64_t)pos[u];
+                                                        uint64_t* __restrict__ keys, int dst_only) {
+    // dst_only: keep every edge whose destination is flagged (halo partitions), whatever its source
+    constexpr int PER = 8;
+    __shared__ int wave_count[4];
+    __shared__ unsigned long long tile_base;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t n_tiles = (E + 256 * PER - 1) / (256 * PER);
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t e0 = tile * (256 * PER);
+        uint64_t key[PER];
+        int mine = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int64_t e = e0 + (int64_t)i * 256 + tid;
+            key[i] = ~0ull;
+            if (e < E) {
+                const int64_t u = src[e], v = dst[e];
+                if (flag[v] && (dst_only || flag[u])) { key[i] = ((uint64_t)pos[v] << 32) | (uint64_t)pos[u]; ++mine; }
+            }
         }
+        // exclusive prefix of `mine` over the workgroup: inside the wavefront by shuffles, across the four by LDS
+        int incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) wave_count[wave] = incl;
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) before += wave_count[w];
+            total += wave_count[w];
+        }
+        if (tid == 0) tile_base = total ? atomicAdd(cursor, (unsigned long long)total) : 0ull;
+        __syncthreads();
+        unsigned long long slot = tile_base + (unsigned long long)(before + incl - mine);
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (key[i] != ~0ull) keys[slot++] = key[i];
+        __syncthreads();                                 // wave_count / tile_base are reused by the next tile
     }
 }
 
@@ -367,7 +404,7 @@ static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t
     GRP_TRY(keys_alt.alloc((size_t)nnz * sizeof(uint64_t)));
     if (nnz > 0) {
         hipLaunchKernelGGL(edge_keys_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, flag.as<int32_t>(),
-                           pos.as<int64_t>(), counters.as<unsigned long long>() + 2, keys.as<uint64_t>());
+                           pos.as<int64_t>(), counters.as<unsigned long long>() + 2, keys.as<uint64_t>(), 0);
         GRP_LAUNCH_CHECK();
     }
     return build_csr_csc(h, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), st);
@@ -494,19 +531,6 @@ __global__ __launch_bounds__(256) void halo_scan_kernel(const int64_t* __restric
     if ((threadIdx.x & 63) == 0 && kept) atomicAdd(kept_out, kept);
 }
 
-__global__ __launch_bounds__(256) void halo_keys_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
-                                                        int64_t E, const int32_t* __restrict__ inner,
-                                                        const int64_t* __restrict__ pos, unsigned long long* __restrict__ cursor,
-                                                        uint64_t* __restrict__ keys) {
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
-        const int64_t u = src[e], v = dst[e];
-        if (inner[v]) {
-            const unsigned long long slot = atomicAdd(cursor, 1ull);
-            keys[slot] = ((uint64_t)pos[v] << 32) | (uint64_t)pos[u];
-        }
-    }
-}
-
 __global__ __launch_bounds__(256) void halo_nodes_kernel(int64_t N, const int32_t* __restrict__ member,
                                                          const int32_t* __restrict__ owned, const int64_t* __restrict__ pos,
                                                          int64_t* __restrict__ l2g, uint8_t* __restrict__ owned_mask) {
@@ -582,8 +606,8 @@ static grp_status halo_partition_impl(const int64_t* src, const int64_t* dst, in
     GRP_TRY(keys.alloc((size_t)nnz * sizeof(uint64_t)));
     GRP_TRY(keys_alt.alloc((size_t)nnz * sizeof(uint64_t)));
     if (nnz > 0) {
-        hipLaunchKernelGGL(halo_keys_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, inner.as<int32_t>(),
-                           pos.as<int64_t>(), counters.as<unsigned long long>() + 2, keys.as<uint64_t>());
+        hipLaunchKernelGGL(edge_keys_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, inner.as<int32_t>(),
+                           pos.as<int64_t>(), counters.as<unsigned long long>() + 2, keys.as<uint64_t>(), 1);
         GRP_LAUNCH_CHECK();
     }
     return build_csr_csc(h, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), st);
