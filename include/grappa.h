@@ -82,6 +82,12 @@ grp_status grp_partition(const int64_t* src, const int64_t* dst, int64_t E, int6
                          int32_t K, uint64_t seed, int32_t part_id, void* stream,
                          grp_partition_t** out);
 
+/* The node assignment alone: owner_out[v] = owner(v) for v in [0, N) (DEV int32[N]) and, if
+ * count_out is not NULL, the number of nodes of every partition (DEV int64[K], overwritten).
+ * Asynchronous on the stream.  Errors: GRP_EINVAL (N < 0, K < 1, null output), GRP_EHIP.      */
+grp_status grp_node_owners(int64_t N, int32_t K, uint64_t seed, int32_t* owner_out,
+                           int64_t* count_out, void* stream);
+
 /* The same partition for neighbours of unequal weight (the general form of the coverage-corrected
  * estimators: a target distribution p_v(u) over the in-neighbours of v and a local one
  * q_v(u) = p_v(u) / sum of p_v over the local neighbours).  w: DEV float[E], w[e] > 0 finite, the

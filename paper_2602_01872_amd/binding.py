@@ -71,6 +71,7 @@ def load() -> C.CDLL:
     lib.grp_last_error.argtypes = []
     sigs = {
         "grp_partition": [vp, vp, i64, i64, i32, u64, i32, vp, C.POINTER(vp)],
+        "grp_node_owners": [i64, i32, u64, vp, vp, vp],
         "grp_partition_weighted": [vp, vp, vp, i64, i64, i32, u64, i32, vp, C.POINTER(vp)],
         "grp_partition_weights": [vp, C.POINTER(PartitionWeights)],
         "grp_partition_from_local_coo": [vp, vp, i64, i64, vp, vp, vp, C.POINTER(vp)],
@@ -240,6 +241,11 @@ def grp_partition(src, dst, N: int, K: int, seed: int, part_id: int, stream=None
     return Partition(out.value)
 
 
+def grp_node_owners(N: int, K: int, seed: int, owner_out, count_out=None, stream=None):
+    """owner_out: int32 device tensor [N]; count_out: optional int64 device tensor [K]."""
+    _check(load().grp_node_owners(N, K, seed, _ptr(owner_out), _ptr(count_out), _stream(stream)))
+
+
 def grp_partition_weighted(src, dst, w, N: int, K: int, seed: int, part_id: int, stream=None) -> Partition:
     """``w``: float32 device tensor, one positive weight per edge."""
     out = C.c_void_p()
@@ -379,7 +385,7 @@ def read_stats(stats: torch.Tensor) -> np.ndarray:
 
 
 def exported_symbols():
-    return ["grp_last_error", "grp_partition", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_view",
+    return ["grp_last_error", "grp_partition", "grp_node_owners", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_view",
             "grp_partition_destroy", "grp_chunks_build", "grp_chunks_destroy", "grp_partition_from_chunks",
             "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_train_step",
             "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",

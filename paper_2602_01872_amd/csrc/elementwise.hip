@@ -234,7 +234,23 @@ __global__ __launch_bounds__(256) void colsum_partial_vec_kernel(const float* __
     const int64_t m1 = m0 + COLSUM_ROWS < M ? m0 + COLSUM_ROWS : M;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     if (r0 < R) {
-        for (int64_t m = m0 + r0; m < m1; m += R) {
+        // four rows per trip, all requested before the first is added (in row order)
+        int64_t m = m0 + r0;
+        for (; m + 3 * R < m1; m += 4 * R) {
+            float4 v[4];
+            float w[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                v[q] = *reinterpret_cast<const float4*>(A + (m + q * R) * lda + 4 * c4);
+                w[q] = rowmul ? rowmul[m + q * R] : 1.f;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                s.x = fmaf(v[q].x, w[q], s.x); s.y = fmaf(v[q].y, w[q], s.y);
+                s.z = fmaf(v[q].z, w[q], s.z); s.w = fmaf(v[q].w, w[q], s.w);
+            }
+        }
+        for (; m < m1; m += R) {
             const float4 v = *reinterpret_cast<const float4*>(A + m * lda + 4 * c4);
             const float w = rowmul ? rowmul[m] : 1.f;
             s.x = fmaf(v.x, w, s.x); s.y = fmaf(v.y, w, s.y); s.z = fmaf(v.z, w, s.z); s.w = fmaf(v.w, w, s.w);

@@ -32,6 +32,29 @@ __global__ __launch_bounds__(256) void owner_flag_kernel(int64_t N, uint32_t K, 
     if (v < N) flag[v] = (splitmix64_output(seed, (uint64_t)v) % K) == part ? 1 : 0;
 }
 
+// owner[v] for every node and (optionally) the number of nodes per partition.
+__global__ __launch_bounds__(256) void node_owners_kernel(int64_t N, uint32_t K, uint64_t seed, int32_t* __restrict__ owner,
+                                                          unsigned long long* __restrict__ hist) {
+    constexpr int LDS_BINS = 1024;
+    __shared__ unsigned int bins[LDS_BINS];
+    const bool local = hist && K <= LDS_BINS;
+    if (local) {
+        for (int i = threadIdx.x; i < (int)K; i += 256) bins[i] = 0u;
+        __syncthreads();
+    }
+    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < N; v += (int64_t)gridDim.x * 256) {
+        const uint32_t o = (uint32_t)(splitmix64_output(seed, (uint64_t)v) % K);
+        owner[v] = (int32_t)o;
+        if (local) atomicAdd(&bins[o], 1u);
+        else if (hist) atomicAdd(&hist[o], 1ull);
+    }
+    if (local) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < (int)K; i += 256)
+            if (bins[i]) atomicAdd(&hist[i], (unsigned long long)bins[i]);
+    }
+}
+
 __global__ __launch_bounds__(256) void scatter_l2g_kernel(int64_t N, const int32_t* __restrict__ flag,
                                                           const int64_t* __restrict__ pos, int64_t* __restrict__ l2g) {
     const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -901,6 +924,22 @@ extern "C" grp_status grp_partition(const int64_t* src, const int64_t* dst, int6
         return s;
     }
     *out = h;
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_node_owners(int64_t N, int32_t K, uint64_t seed, int32_t* owner_out, int64_t* count_out,
+                                      void* stream) {
+    using namespace grp;
+    if (N < 0 || K < 1) return fail(GRP_EINVAL, "grp_node_owners: N = %lld, K = %d", (long long)N, K);
+    if (N > 0 && !owner_out) return fail(GRP_EINVAL, "grp_node_owners: null output");
+    hipStream_t st = (hipStream_t)stream;
+    if (count_out) GRP_HIP(hipMemsetAsync(count_out, 0, (size_t)K * sizeof(int64_t), st));
+    if (N == 0) return GRP_OK;
+    int64_t blocks = cdiv(N, 256 * 8);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(node_owners_kernel, dim3((unsigned)blocks), dim3(256), 0, st, N, (uint32_t)K, seed, owner_out,
+                       (unsigned long long*)count_out);
+    GRP_LAUNCH_CHECK();
     return GRP_OK;
 }
 

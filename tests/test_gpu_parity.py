@@ -61,6 +61,21 @@ def test_partition_bit_exact(g, kind, N, E, K, seed):
         part.destroy()
 
 
+@pytest.mark.parametrize("N,K,seed", [(100003, 8, 1), (5000, 1, 9), (70000, 3000, 2**63 + 5), (1, 4, 0)])
+def test_node_owners_bit_exact(g, N, K, seed):
+    _note(f"node owners N={N} K={K}")
+    owner = torch.full((N,), -1, dtype=torch.int32, device=DEV)
+    count = torch.full((K,), -7, dtype=torch.int64, device=DEV)
+    g.grp_node_owners(N, K, seed, owner, count)
+    torch.cuda.synchronize()
+    want = ograph.owner(N, K, seed)
+    assert np.array_equal(owner.cpu().numpy(), want)
+    assert np.array_equal(count.cpu().numpy(), np.bincount(want, minlength=K))
+    g.grp_node_owners(N, K, seed, owner, None)            # the histogram is optional
+    with pytest.raises(g.GrappaError):
+        g.grp_node_owners(N, 0, seed, owner, count)
+
+
 def test_partition_edge_cases_and_errors(g):
     _note("partition edge cases")
     part = g.grp_partition(None, None, 10, 3, 0, 1)
