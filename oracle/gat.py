@@ -87,7 +87,7 @@ def _layer_backward(h, esrc, edst, n, w, a_s, a_d, saved, dout, need_dh):
 
 
 def forward_backward(dims, theta, x, blk, labels, node_w, loss_nodes, return_logits=False,
-                     relu_flip=None, near_kink=None, drop=None):
+                     relu_flip=None, near_kink=None, drop=None, relu_set=None):
     """Loss and flat gradient of a k-layer GAT on the full local graph ``blk`` (n_src = n_dst).
 
     ``relu_flip`` / ``near_kink`` / ``drop`` as in ``gnn.forward_backward`` (dropout acts on the
@@ -122,6 +122,9 @@ def forward_backward(dims, theta, x, blk, labels, node_w, loss_nodes, return_log
             for (fl, fr, fc) in (relu_flip or ()):
                 if fl == l:
                     mask[fr, fc] = not mask[fr, fc]
+            for (fl, fr, fc), decision in (relu_set or {}).items():
+                if fl == l:
+                    mask[fr, fc] = bool(decision)
             dzl = dh_next * mask
             if drop:
                 dzl = dzl * drop[l]

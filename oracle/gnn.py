@@ -28,8 +28,8 @@ Readings where the paper is silent:
     pre-activation within rounding distance of 0 makes that decision depend on the
     precision and summation order of whoever computes z, so ``forward_backward`` can list
     the hidden pre-activations with |z| <= guard (``near_kink``) and can be asked to take
-    the opposite decision for chosen elements (``relu_flip``); a checker uses the two to
-    accept either decision exactly at a kink and nothing else.
+    the opposite decision for chosen elements (``relu_flip``) or a given decision (``relu_set``); a
+    checker uses them to accept either decision exactly at a kink and nothing else.
   * parameters are one flat vector: layer-major; per layer W_self (GCN: W) row-major
     [Fin x Fout], then W_neigh (SAGE only), then b.
   * loss = (1/|S|) sum_{v in S} w_v (logsumexp(z_v) - z_v[y_v]); S empty -> loss 0 and a
@@ -194,7 +194,7 @@ def _gcn_backward(h, blk, w, saved, dz, need_dh, self_loops):
 
 
 def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
-                     gcn_self_loops=True, return_logits=False, relu_flip=None, near_kink=None, drop=None):
+                     gcn_self_loops=True, return_logits=False, relu_flip=None, near_kink=None, drop=None, relu_set=None):
     """Loss and flat parameter gradient of a k-layer model.
 
     ``blocks`` has one block per layer (input side first); pass the same block k times for
@@ -203,6 +203,8 @@ def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
     ``relu_flip``: iterable of (layer, row, col) whose ReLU derivative is inverted.
     ``near_kink``: a guard g; the call then also returns the list of (layer, row, col) of
     hidden pre-activations with |z| <= g * rms(z of that layer).
+    ``relu_set``: {(layer, row, col): bool} fixes the ReLU derivative decision of the listed elements
+    (a checker passes the decisions another implementation took for the ``near_kink`` elements).
     ``drop``: per hidden layer the factor array keep / (1 - rate) of its output ([] or None: no dropout).
     """
     if arch not in ARCHS:
@@ -248,6 +250,9 @@ def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
             for (fl, fr, fc) in (relu_flip or ()):
                 if fl == l:
                     mask[fr, fc] = not mask[fr, fc]
+            for (fl, fr, fc), decision in (relu_set or {}).items():
+                if fl == l:
+                    mask[fr, fc] = bool(decision)
             dzl = dh_next * mask
             if drop:
                 dzl = dzl * drop[l]

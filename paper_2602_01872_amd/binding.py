@@ -83,6 +83,7 @@ def load() -> C.CDLL:
         "grp_partition_base_mask": [vp, C.POINTER(vp)],
         "grp_partition_destroy": [vp],
         "grp_step_workspace_bytes": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), C.POINTER(sz)],
+        "grp_step_activation": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), vp, sz, i32, C.POINTER(vp), C.POINTER(i64)],
         "grp_train_step": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), vp, vp, vp, vp, vp, sz, vp, vp, vp],
         "grp_aggregate": [vp, i64, vp, i32, i64, i32, vp, vp, vp],
         "grp_optimizer_step": [C.POINTER(OptimizerDesc), i64, i64, vp, vp, vp, vp, vp],
@@ -312,6 +313,24 @@ def grp_step_workspace_bytes(part: Partition, model: ModelDesc, opts: StepOpts) 
     return int(b.value)
 
 
+def grp_step_activation(part: Partition, model: ModelDesc, opts: StepOpts, workspace, layer: int):
+    """(device pointer, pitch in floats) of layer ``layer``'s stored activation inside ``workspace``."""
+    ptr, ld = C.c_void_p(), C.c_int64()
+    _check(load().grp_step_activation(part.handle, C.byref(model), C.byref(opts), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), layer, C.byref(ptr), C.byref(ld)))
+    return ptr.value, int(ld.value)
+
+
+def read_activation(part: Partition, model: ModelDesc, opts: StepOpts, workspace, layer: int, rows, cols):
+    """Host values of the stored activation at the (row, col) pairs given as equal-length int arrays."""
+    ptr, ld = grp_step_activation(part, model, opts, workspace, layer)
+    base = (ptr - workspace.data_ptr()) // 4
+    flat = workspace.view(torch.float32)
+    idx = torch.as_tensor(np.asarray(rows, dtype=np.int64) * ld + np.asarray(cols, dtype=np.int64), device=workspace.device) + base
+    torch.cuda.synchronize()
+    return flat[idx].cpu().numpy()
+
+
 def grp_train_step(part: Partition, model: ModelDesc, opts: StepOpts, features, labels, train_mask, weights,
                    workspace, grad_out, stats_out, stream=None, workspace_bytes=None):
     wb = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
@@ -387,6 +406,6 @@ def read_stats(stats: torch.Tensor) -> np.ndarray:
 def exported_symbols():
     return ["grp_last_error", "grp_partition", "grp_node_owners", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_view",
             "grp_partition_destroy", "grp_chunks_build", "grp_chunks_destroy", "grp_partition_from_chunks",
-            "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_train_step",
+            "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_step_activation", "grp_train_step",
             "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
             "grp_profile_enable", "grp_profile_report"]

@@ -269,6 +269,9 @@ grp_status launch_pack_weights(const PackJobs& jobs, hipStream_t st);
 
 // Graph attention model (full-graph mode): workspace size and the whole train step.
 size_t gat_step_workspace_bytes(const grp_partition_t* part, const grp_model_desc* m);
+// Where layer `layer`'s stored output lives inside a workspace laid out for this partition and model.
+void gat_step_activation(const grp_partition_t* part, const grp_model_desc* m, void* ws, size_t ws_bytes, int layer,
+                         const float** out, int64_t* ld);
 grp_status gat_step(const grp_partition_t* g, const grp_model_desc* m, const grp_step_opts* o, const void* X,
                     const int32_t* labels, const uint8_t* mask, const float* theta, void* ws, size_t ws_bytes,
                     hipStream_t st, float* grad, grp_step_stats* stats);

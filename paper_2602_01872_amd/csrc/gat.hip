@@ -509,6 +509,13 @@ size_t gat_step_workspace_bytes(const grp_partition_t* part, const grp_model_des
     return gat_plan(part, m, nullptr, 0).total;
 }
 
+void gat_step_activation(const grp_partition_t* part, const grp_model_desc* m, void* ws, size_t ws_bytes, int layer,
+                         const float** out, int64_t* ld) {
+    const GatPlan p = gat_plan(part, m, ws, ws_bytes);
+    *out = p.L[layer].Hout;
+    *ld = p.L[layer].ldh;
+}
+
 template <int PASS, int G, int NJ>
 static void gat_walk_one(const GatWalk& A, const LongRows* lr, hipStream_t st) {
     constexpr int ROWS = 256 / G;

@@ -452,6 +452,31 @@ extern "C" grp_status grp_step_workspace_bytes(const grp_partition_t* part, cons
     return GRP_OK;
 }
 
+extern "C" grp_status grp_step_activation(const grp_partition_t* part, const grp_model_desc* model, const grp_step_opts* opts,
+                                          void* workspace, size_t workspace_bytes, int32_t layer, const float** act_out,
+                                          int64_t* ld_out) {
+    using namespace grp;
+    if (!act_out || !ld_out) return fail(GRP_EINVAL, "grp_step_activation: null output");
+    *act_out = nullptr;
+    *ld_out = 0;
+    GRP_TRY(check_step_args(part, model, opts));
+    if (!opts->full_graph) return fail(GRP_EUNSUPPORTED, "grp_step_activation: full-graph steps only");
+    if (layer < 0 || layer >= model->n_layers) return fail(GRP_EINVAL, "grp_step_activation: layer %d", layer);
+    if (!workspace || (uintptr_t)workspace % 256 != 0) return fail(GRP_EINVAL, "grp_step_activation: bad workspace");
+    if (model->arch == GRP_ARCH_GAT) {
+        if (workspace_bytes < gat_step_workspace_bytes(part, model))
+            return fail(GRP_EWORKSPACE, "grp_step_activation: workspace too small");
+        gat_step_activation(part, model, workspace, workspace_bytes, layer, act_out, ld_out);
+        return GRP_OK;
+    }
+    const StepPlan p = make_plan(part, model, opts, workspace, workspace_bytes);
+    if (workspace_bytes < p.total) return fail(GRP_EWORKSPACE, "grp_step_activation: workspace too small");
+    const LayerBufs& L = p.L[layer];
+    *act_out = L.skip ? L.Act : L.H_out;
+    *ld_out = ldp(model->dims[layer + 1]);
+    return GRP_OK;
+}
+
 extern "C" grp_status grp_train_step(const grp_partition_t* part, const grp_model_desc* model, const grp_step_opts* opts,
                                      const void* features, const int32_t* labels, const uint8_t* train_mask,
                                      const float* weights, void* workspace, size_t workspace_bytes, void* stream,

@@ -52,13 +52,27 @@ def test_workload2_partition0_full_size():
     assert abs(float(st["sum_ratio"]) - ost["sum_ratio"]) <= 1e-9 * ost["sum_ratio"]
     assert abs(float(st["loss"]) - ost["loss"]) <= TOL_FP32 * abs(ost["loss"])
     errs = grad_errors(grad.cpu().numpy(), og, "sage", dims)
-    print("[case] per-tensor errors", {k: f"{v:.2e}" for k, v in errs.items()}, "near-kink", len(ost["near_kink"]), flush=True)
-    for k in ("W2", "Wn2", "b2"):
+    near = ost["near_kink"]
+    print("[case] per-tensor errors before the kink decisions are matched", {k: f"{v:.2e}" for k, v in errs.items()},
+          "near-kink", len(near), flush=True)
+    for k in ("W2", "Wn2", "b2"):                       # the last layer's gradients involve no ReLU decision
         assert errs[k] <= TOL_FP32, (k, errs[k])
-    for k, v in errs.items():
-        assert v <= 5e-3, (k, v)
-        if v > TOL_FP32:
-            assert len(ost["near_kink"]) > 0
+    # Hidden pre-activations within rounding distance of 0 (the oracle lists them) may take either
+    # ReLU-derivative decision; the oracle is rerun with the decisions the library took there (read
+    # from its stored activations) and with its own decisions everywhere else.
+    assert len(near) < 5000
+    decisions = {}
+    for l in range(len(dims) - 2):
+        el = [e for e in near if e[0] == l]
+        if el:
+            vals = g.read_activation(part, model, opts, ws, l, [e[1] for e in el], [e[2] for e in el])
+            decisions.update({e: bool(v > 0) for e, v in zip(el, vals)})
+    og2, _ = ostep.train_step(op, "sage", dims, theta.cpu().double().numpy(), x.cpu().double().numpy(),
+                              y.cpu().numpy(), relu_set=decisions)
+    errs2 = grad_errors(grad.cpu().numpy(), og2, "sage", dims)
+    print("[case] per-tensor errors with matched decisions", {k: f"{v:.2e}" for k, v in errs2.items()}, flush=True)
+    for k, v in errs2.items():
+        assert v <= TOL_FP32, (k, v)
 
 
 def _sampled_rows_and_checksum(g, scale, n, E, seed, F, bf16, n_sample=4096):

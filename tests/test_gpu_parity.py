@@ -620,3 +620,51 @@ def test_partition_from_chunks_bit_exact(g, kind, N, E, c):
         with pytest.raises(g.GrappaError):
             g.grp_chunks_build(bad.to(DEV), d.to(DEV), N, c, 13)
     part.destroy(); plain.destroy(); ck.destroy()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("arch,dims", [("sage", [24, 40, 12]), ("gcn", [16, 32, 32, 6]), ("gcn_res", [16, 32, 32, 32, 6])])
+def test_step_activation_view_matches_oracle_logits(g, arch, dims):
+    """grp_step_activation: the last layer's stored output is the logits matrix, the first hidden
+    layer's is ReLU of the oracle's pre-activations; error paths."""
+    from oracle import gnn as ognn
+    _note(f"activation view {arch}")
+    N, E = 3000, 30000
+    s, d = synth.uniform_graph(N, E, seed=31)
+    part = g.grp_partition(s.to(DEV), d.to(DEV), N, 2, 4, 1)
+    op = ograph.partition(s.numpy(), d.numpy(), N, 2, 4, 1)
+    n, k = part.n, len(dims) - 1
+    x, y, theta = make_inputs(n, dims, arch, 3)
+    model = g.model_desc(ARCH[arch], dims, g.DTYPE_FP32, True)
+    opts = g.step_opts(full_graph=True)
+    ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+    grad = torch.zeros(g.grp_param_count(model), device=DEV)
+    stats = g.new_stats(1)
+    g.grp_train_step(part, model, opts, x.to(DEV), y.to(DEV), None, theta.to(DEV), ws, grad, stats)
+    torch.cuda.synchronize()
+    blk = ognn.block_from_csr(op["rowptr"], op["col"])
+    _, _, logits = ognn.forward_backward(arch, dims, theta.double().numpy(), x.double().numpy(), [blk] * k, y.numpy(),
+                                         np.ones(n), np.arange(n), True, return_logits=True)
+    rows = np.repeat(np.arange(n), dims[-1])
+    cols = np.tile(np.arange(dims[-1]), n)
+    got = g.read_activation(part, model, opts, ws, k - 1, rows, cols).reshape(n, dims[-1])
+    assert rel_err(got, logits) <= TOL_FP32
+    # the first hidden layer against the oracle's layer function
+    params = ognn.unpack_params(theta.double().numpy(), arch, dims)
+    if arch == "sage":
+        z0, _ = ognn._sage_forward(x.double().numpy(), blk, *params[0])
+    else:
+        z0, _ = ognn._gcn_forward(x.double().numpy(), blk, params[0][0], params[0][2], True)
+    rows = np.repeat(np.arange(n), dims[1])
+    cols = np.tile(np.arange(dims[1]), n)
+    hid = g.read_activation(part, model, opts, ws, 0, rows, cols).reshape(n, dims[1])
+    assert rel_err(hid, np.maximum(z0, 0.0)) <= TOL_FP32
+    with pytest.raises(g.GrappaError):
+        g.grp_step_activation(part, model, opts, ws, k)
+    with pytest.raises(g.GrappaError):
+        g.grp_step_activation(part, model, opts, ws[:256], 0)
+    seeds = torch.arange(8, dtype=torch.int32, device=DEV)
+    if arch == "sage":
+        with pytest.raises(g.GrappaError):
+            g.grp_step_activation(part, model, g.step_opts(full_graph=False, seeds=seeds, fanouts=(2, 2)), ws, 0)
+    part.destroy()

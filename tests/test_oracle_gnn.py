@@ -239,3 +239,10 @@ def test_relu_kink_options_flip_exactly_one_derivative():
         _, gf = gnn.forward_backward("sage", dims, theta, x, [blk] * 2, y, w, nodes, relu_flip=[f])
         _, gef = gnn.forward_backward("sage", dims, theta, x, [blk] * 2, y, w, nodes, relu_flip=[e, f])
         np.testing.assert_allclose(gef - g0, (g1 - g0) + (gf - g0), rtol=1e-9, atol=1e-15)
+    # relu_set fixes a decision instead of inverting it: the element's own decision changes nothing,
+    # the opposite one is the flip
+    own = bool(z0[e[1], e[2]] > 0)
+    _, gs = gnn.forward_backward("sage", dims, theta, x, [blk] * 2, y, w, nodes, relu_set={e: own})
+    np.testing.assert_array_equal(gs, g0)
+    _, gs = gnn.forward_backward("sage", dims, theta, x, [blk] * 2, y, w, nodes, relu_set={e: not own})
+    np.testing.assert_array_equal(gs, g1)
