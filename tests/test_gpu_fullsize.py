@@ -1,17 +1,18 @@
 """Full-size cases.  Workload 2, in the launch configuration bench.py times: partition 0 of 8 of the
-2.4 M-node / 62 M-edge R-MAT graph, 3-layer GraphSAGE-mean 100-256-256-47.
+2.4 M-node / 62 M-edge R-MAT graph, 3-layer 100-256-256-47 models (GraphSAGE-mean, the headline; the
+attention model; GraphSAGE on weighted edges with dropout), and the SpMM of workloads 4 and 5.
 
-The partition arrays must be bit-exact.  The loss, the statistics, the last layer's gradients
-and the aggregated update of those tensors do not pass through any ReLU derivative and must
-hold 1e-4.  The lower layers contain ~1.5e8 hidden pre-activations, of which a few dozen lie
-within fp32 rounding of 0; their derivative decisions cannot be enumerated at this size (see
-tests/_cases.py for the exact treatment at small sizes), so those tensors are bounded at 5e-3
-and the oracle must report that such elements exist whenever 1e-4 is exceeded."""
+The partition arrays must be bit-exact; the loss, the statistics and every gradient tensor must hold
+1e-4.  The lower layers contain ~1.5e8 hidden pre-activations, of which a few hundred lie within fp32
+rounding of 0, where the ReLU derivative can be decided either way: the oracle lists those elements,
+the decisions the library took there are read from its stored activations, and the oracle is rerun with
+them (and with its own decisions everywhere else)."""
 import numpy as np
 import pytest
 import torch
 
 import synth
+from oracle import dropout as odropout
 from oracle import graph as ograph
 from oracle import step as ostep
 from tests._cases import KINK_GUARD, TOL_FP32, grad_errors
@@ -73,6 +74,116 @@ def test_workload2_partition0_full_size():
     print("[case] per-tensor errors with matched decisions", {k: f"{v:.2e}" for k, v in errs2.items()}, flush=True)
     for k, v in errs2.items():
         assert v <= TOL_FP32, (k, v)
+
+
+def test_workload2_partition0_full_size_gat():
+    """The attention model on the headline workload's partition at full size (the configuration
+    `bench.py --workload c2-gat-step` times), gradients against the oracle with the library's
+    ReLU decisions at the near-kink elements."""
+    import paper_2602_01872_amd as g
+    g.load()
+    print("[case] workload 2 full size, GAT", flush=True)
+    N, E, K, dims = 2_400_000, 62_000_000, 8, [100, 256, 256, 47]
+    seed = 2602018722
+    s, d = synth.rmat_graph(22, E, seed=seed, n_nodes=N, device=DEV)
+    part = g.grp_partition(s, d, N, K, 1, 0)
+    op = {k: part.array(k) for k in ("l2g", "rowptr", "col", "colptr", "row", "d_local_in", "d_local_out", "d_global_in")}
+    op.update(n=part.n, nnz=part.nnz)          # bit-exactness of these arrays is the previous test's subject
+    del s, d
+    l2g = torch.from_numpy(op["l2g"]).to(DEV)
+    x = synth.normal_matrix(N, dims[0], seed, device=DEV)[l2g].contiguous()
+    y = synth.labels(N, dims[-1], seed, device=DEV)[l2g].contiguous()
+    theta = synth.model_weights("gat", dims, seed, device=DEV)
+    model = g.model_desc(g.ARCH_GAT, dims)
+    opts = g.step_opts(estimator=g.EST_SHRINKAGE)
+    P = g.grp_param_count(model)
+    ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+    grad = torch.full((P,), float("nan"), device=DEV)
+    stats = g.new_stats(1)
+    g.grp_train_step(part, model, opts, x, y, None, theta, ws, grad, stats)
+    torch.cuda.synchronize()
+    th, xh, yh = theta.cpu().double().numpy(), x.cpu().double().numpy(), y.cpu().numpy()
+    print("[case] oracle pass 1 (lists the near-kink elements)", flush=True)
+    og, ost = ostep.train_step(op, "gat", dims, th, xh, yh, near_kink=KINK_GUARD)
+    st = g.read_stats(stats)[0]
+    assert int(st["S"]) == ost["S"] and float(st["R"]) == ost["R"]
+    assert abs(float(st["loss"]) - ost["loss"]) <= TOL_FP32 * abs(ost["loss"])
+    near = ost["near_kink"]
+    errs = grad_errors(grad.cpu().numpy(), og, "gat", dims)
+    print("[case] per-tensor errors before the kink decisions are matched", {k: f"{v:.2e}" for k, v in errs.items()},
+          "near-kink", len(near), flush=True)
+    assert len(near) < 5000
+    decisions = {}
+    for l in range(len(dims) - 2):
+        el = [e for e in near if e[0] == l]
+        if el:
+            vals = g.read_activation(part, model, opts, ws, l, [e[1] for e in el], [e[2] for e in el])
+            decisions.update({e: bool(v > 0) for e, v in zip(el, vals)})
+    print("[case] oracle pass 2 (the library's decisions at those elements)", flush=True)
+    og2, _ = ostep.train_step(op, "gat", dims, th, xh, yh, relu_set=decisions)
+    errs2 = grad_errors(grad.cpu().numpy(), og2, "gat", dims)
+    print("[case] per-tensor errors with matched decisions", {k: f"{v:.2e}" for k, v in errs2.items()}, flush=True)
+    for k, v in errs2.items():
+        assert v <= TOL_FP32, (k, v)
+    part.destroy()
+
+
+def test_workload2_partition0_full_size_weighted_with_dropout():
+    """Weighted edges and hidden-layer dropout together on the headline workload's partition at full
+    size: the weighted partition arrays bit for bit, then the GraphSAGE step against the oracle."""
+    import paper_2602_01872_amd as g
+    g.load()
+    print("[case] workload 2 full size, weighted edges + dropout", flush=True)
+    N, E, K, dims = 2_400_000, 62_000_000, 8, [100, 256, 256, 47]
+    seed = 2602018722
+    s, d = synth.rmat_graph(22, E, seed=seed, n_nodes=N, device=DEV)
+    w = synth.edge_weights(E, seed, device=DEV)
+    part = g.grp_partition_weighted(s, d, w, N, K, 1, 0)
+    print("[case] oracle partition", flush=True)
+    op = ograph.partition(s.cpu().numpy(), d.cpu().numpy(), N, K, 1, 0, weights=w.cpu().numpy())
+    del s, d, w
+    for key in ("l2g", "rowptr", "col", "colptr", "row", "d_local_in", "d_global_in"):
+        assert np.array_equal(part.array(key), op[key]), key
+    got = part.weights()
+    for key in ("csr_w", "csc_w", "w_local_in", "w_global_in"):
+        assert np.array_equal(got[key], op[key]), key
+    l2g = torch.from_numpy(op["l2g"]).to(DEV)
+    x = synth.normal_matrix(N, dims[0], seed, device=DEV)[l2g].contiguous()
+    y = synth.labels(N, dims[-1], seed, device=DEV)[l2g].contiguous()
+    theta = synth.model_weights("sage", dims, seed, device=DEV)
+    model = g.model_desc(g.ARCH_SAGE_MEAN, dims)
+    opts = g.step_opts(estimator=g.EST_NODE_LEVEL, batch_id=5, dropout_rate=0.5, dropout_seed=99)
+    P = g.grp_param_count(model)
+    ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+    grad = torch.full((P,), float("nan"), device=DEV)
+    stats = g.new_stats(1)
+    g.grp_train_step(part, model, opts, x, y, None, theta, ws, grad, stats)
+    torch.cuda.synchronize()
+    th, xh, yh = theta.cpu().double().numpy(), x.cpu().double().numpy(), y.cpu().numpy()
+    dr = dict(rate=0.5, seed=99, batch_id=5)
+    print("[case] oracle pass 1 (lists the near-kink elements)", flush=True)
+    og, ost = ostep.train_step(op, "sage", dims, th, xh, yh, estimator=1, near_kink=KINK_GUARD, dropout=dr)
+    st = g.read_stats(stats)[0]
+    assert int(st["S"]) == ost["S"]
+    assert abs(float(st["R"]) - ost["R"]) <= 1e-9 * ost["R"]
+    assert abs(float(st["sum_ratio"]) - ost["sum_ratio"]) <= 1e-9 * ost["sum_ratio"]
+    assert abs(float(st["loss"]) - ost["loss"]) <= TOL_FP32 * abs(ost["loss"])
+    # a dropped element is stored as 0 by the library and needs no decision; the others are matched
+    near = ost["near_kink"]
+    decisions = {}
+    for l in range(len(dims) - 2):
+        el = [e for e in near if e[0] == l]
+        if el:
+            vals = g.read_activation(part, model, opts, ws, l, [e[1] for e in el], [e[2] for e in el])
+            keep = odropout.keep_mask(99, 5, l, op["l2g"][[e[1] for e in el]], dims[l + 1], 0.5)[np.arange(len(el)), [e[2] for e in el]]
+            decisions.update({e: bool(v > 0) for e, v, kp in zip(el, vals, keep) if kp})
+    print(f"[case] near-kink {len(near)}, kept by dropout {len(decisions)}; oracle pass 2", flush=True)
+    og2, _ = ostep.train_step(op, "sage", dims, th, xh, yh, estimator=1, relu_set=decisions, dropout=dr)
+    errs2 = grad_errors(grad.cpu().numpy(), og2, "sage", dims)
+    print("[case] per-tensor errors with matched decisions", {k: f"{v:.2e}" for k, v in errs2.items()}, flush=True)
+    for k, v in errs2.items():
+        assert v <= TOL_FP32, (k, v)
+    part.destroy()
 
 
 def _sampled_rows_and_checksum(g, scale, n, E, seed, F, bf16, n_sample=4096):
