@@ -287,13 +287,15 @@ grp_status grp_train_step(const grp_partition_t* part, const grp_model_desc* mod
                           void* stream, float* grad_out, grp_step_stats* stats_out);
 
 /* Inspection: where grp_train_step left the activation of layer `layer` inside the workspace it was
- * given (same partition, model and options; full-graph mode).  *act_out is a borrowed DEV pointer
- * into the workspace to a [n x *ld_out] row-major matrix whose first dims[layer+1] columns hold
+ * given (same partition, model and options).  *act_out is a borrowed DEV pointer into the workspace
+ * to a [rows x *ld_out] row-major matrix (rows = n in full-graph mode; in mini-batch mode the layer's
+ * destination nodes in block order: the seeds first, then each deeper layer's new nodes in ascending
+ * local id) whose first dims[layer+1] columns hold
  * a_l = ReLU(z_l) of a hidden layer (after dropout if enabled, before a residual skip is added) or
  * the logits of the last layer; valid until the workspace is reused.  For callers that need the
  * ReLU decisions the step took (a checker comparing gradients with another implementation has to
  * take the same decision where a pre-activation is within rounding distance of zero).
- * Errors: GRP_EINVAL, GRP_EUNSUPPORTED (mini-batch mode), GRP_EWORKSPACE.                        */
+ * Errors: GRP_EINVAL, GRP_EWORKSPACE.                                                            */
 grp_status grp_step_activation(const grp_partition_t* part, const grp_model_desc* model,
                                const grp_step_opts* opts, void* workspace, size_t workspace_bytes,
                                int32_t layer, const float** act_out /*HOST*/, int64_t* ld_out /*HOST*/);

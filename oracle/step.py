@@ -22,7 +22,7 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
     mini-batch mode: ``minibatch = dict(seeds=int array of local ids, fanouts=(f_0..f_{k-1}),
     sampler_seed=int, batch_id=int)``; fanouts[l] belongs to layer l, layer 0 being the input
     side, so the seeds draw fanouts[k-1] neighbours.
-    ``relu_flip`` / ``near_kink`` / ``relu_set`` (full-graph mode) are passed to ``gnn.forward_backward``; with ``near_kink`` the
+    ``relu_flip`` / ``near_kink`` / ``relu_set`` are passed to ``gnn.forward_backward``; with ``near_kink`` the
     stats dict gains the key "near_kink".
     A partition built with edge weights (``graph.partition(..., weights=)``) trains the weighted-mean
     GraphSAGE aggregator and reports the coverage statistics of the weight masses (full-graph mode).
@@ -75,11 +75,11 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
     seeds = np.asarray(minibatch["seeds"], dtype=np.int64)
     blocks, input_nodes = sampling.sample_blocks(part, seeds, minibatch["fanouts"],
                                                  minibatch["sampler_seed"], minibatch["batch_id"])
-    xin = np.asarray(x, dtype=np.float64)[input_nodes]
+    xin = np.asarray(x)[input_nodes].astype(np.float64)      # gather, then widen (same values)
     nseed = seeds.size
     res = gnn.forward_backward(arch, dims, theta, xin, blocks, np.asarray(labels)[seeds],
                                w_all[seeds], np.arange(nseed, dtype=np.int64),
-                               gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink)
+                               gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink, relu_set=relu_set)
     loss, grad = res[0], res[1]
     last = blocks[-1]
     sampled = np.bincount(last["edst"], minlength=nseed)

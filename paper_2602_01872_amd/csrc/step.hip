@@ -460,7 +460,6 @@ extern "C" grp_status grp_step_activation(const grp_partition_t* part, const grp
     *act_out = nullptr;
     *ld_out = 0;
     GRP_TRY(check_step_args(part, model, opts));
-    if (!opts->full_graph) return fail(GRP_EUNSUPPORTED, "grp_step_activation: full-graph steps only");
     if (layer < 0 || layer >= model->n_layers) return fail(GRP_EINVAL, "grp_step_activation: layer %d", layer);
     if (!workspace || (uintptr_t)workspace % 256 != 0) return fail(GRP_EINVAL, "grp_step_activation: bad workspace");
     if (model->arch == GRP_ARCH_GAT) {

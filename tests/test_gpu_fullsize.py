@@ -186,6 +186,75 @@ def test_workload2_partition0_full_size_weighted_with_dropout():
     part.destroy()
 
 
+def test_workload3_minibatch_full_size():
+    """Workload 3 at full size (`bench.py --workload c3-step`): a 7 M-node / 100 M-edge store with hub
+    rows of 10^5 in-edges, isolated 3-hop sampling with fanouts (15, 10, 5) from 1024 seeds, bf16
+    features.  The store's CSR comes from the library (checked here against the edge list by its
+    degrees and a sample of rows); the oracle samples and trains on it."""
+    import paper_2602_01872_amd as g
+    g.load()
+    print("[case] workload 3 full size, mini-batch", flush=True)
+    scale, n, E, seed, dims, fanouts = 23, 7_000_000, 100_000_000, 2602018720 + 3, [128, 256, 256, 172], (15, 10, 5)
+    src, dst = synth.rmat_graph(scale, E, seed=seed, n_nodes=n, device=DEV, chunk=1 << 28)
+    d_local = torch.bincount(dst, minlength=n)
+    d_global = synth.stand_in_global_degree(d_local, torch.arange(n, device=DEV), seed, 15)
+    part = g.grp_partition_from_local_coo(src, dst, n, d_global_in=d_global)
+    assert part.n == n and part.nnz == E
+    rowptr = torch.from_numpy(part.array("rowptr")).to(DEV)
+    col = torch.from_numpy(part.array("col")).to(DEV)
+    assert torch.equal(rowptr[1:] - rowptr[:-1], d_local) and int(rowptr[-1]) == E
+    assert int(d_local.max()) > 50_000                        # hub rows: the sampler's whole-workgroup scan
+    pick = torch.unique((synth.stream_bits(seed, 21, torch.arange(2000, dtype=torch.int64)) >> 1) % n).to(DEV)
+    pick = torch.cat([pick, d_local.argmax().reshape(1)])
+    for v in pick.tolist()[-40:]:                             # rows against the edge list, as sorted multisets
+        want = torch.sort(src[dst == v]).values
+        got = col[int(rowptr[v]):int(rowptr[v + 1])].to(torch.int64)
+        assert torch.equal(got, want), v
+    del src, dst
+    op = dict(n=n, nnz=E, l2g=np.arange(n, dtype=np.int64), rowptr=rowptr.cpu().numpy(), col=col.cpu().numpy(),
+              d_local_in=d_local.cpu().numpy().astype(np.int32), d_global_in=d_global.cpu().numpy())
+    del rowptr, col
+    x = synth.to_bf16_rne(synth.normal_matrix(n, dims[0], seed, device=DEV))
+    y = synth.labels(n, dims[-1], seed, device=DEV)
+    theta = synth.model_weights("sage", dims, seed, device=DEV)
+    train = torch.nonzero(synth.train_mask(n, 0.05, seed, device=DEV)).flatten().to(torch.int32)
+    seeds = train[:1024].contiguous()
+    model = g.model_desc(g.ARCH_SAGE_MEAN, dims, feat_dtype=g.DTYPE_BF16)
+    opts = g.step_opts(estimator=g.EST_BATCH_MIN_DIST, full_graph=False, seeds=seeds, fanouts=fanouts, sampler_seed=7,
+                       batch_id=0)
+    P = g.grp_param_count(model)
+    ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+    grad = torch.full((P,), float("nan"), device=DEV)
+    stats = g.new_stats(1)
+    g.grp_train_step(part, model, opts, x, y, None, theta, ws, grad, stats)
+    torch.cuda.synchronize()
+    th, yh = theta.cpu().double().numpy(), y.cpu().numpy()
+    xh = x.cpu().to(torch.float32).numpy()                    # the oracle widens the rows it gathers
+    mb = dict(seeds=seeds.cpu().numpy(), fanouts=fanouts, sampler_seed=7, batch_id=0)
+    print("[case] oracle pass 1 (sampling, lists the near-kink elements)", flush=True)
+    og, ost = ostep.train_step(op, "sage", dims, th, xh, yh, estimator=2, minibatch=mb, near_kink=KINK_GUARD)
+    st = g.read_stats(stats)[0]
+    assert int(st["S"]) == ost["S"] == 1024
+    assert int(st["nnz_used"]) == ost["nnz_used"]             # the sampled edge multiset has the same size
+    assert abs(float(st["R"]) - ost["R"]) <= 1e-9 * max(1.0, ost["R"])
+    assert abs(float(st["sum_ratio"]) - ost["sum_ratio"]) <= 1e-9 * ost["sum_ratio"]
+    assert abs(float(st["loss"]) - ost["loss"]) <= TOL_FP32 * abs(ost["loss"])
+    near = ost["near_kink"]
+    decisions = {}
+    for l in range(len(dims) - 2):
+        el = [e for e in near if e[0] == l]
+        if el:
+            vals = g.read_activation(part, model, opts, ws, l, [e[1] for e in el], [e[2] for e in el])
+            decisions.update({e: bool(v > 0) for e, v in zip(el, vals)})
+    print(f"[case] edges used {ost['nnz_used']}, near-kink {len(near)}; oracle pass 2", flush=True)
+    og2, _ = ostep.train_step(op, "sage", dims, th, xh, yh, estimator=2, minibatch=mb, relu_set=decisions)
+    errs2 = grad_errors(grad.cpu().numpy(), og2, "sage", dims)
+    print("[case] per-tensor errors with matched decisions", {k: f"{v:.2e}" for k, v in errs2.items()}, flush=True)
+    for k, v in errs2.items():
+        assert v <= TOL_FP32, (k, v)
+    part.destroy()
+
+
 def _sampled_rows_and_checksum(g, scale, n, E, seed, F, bf16, n_sample=4096):
     """Mean aggregation (forward over in-edges, transposed over out-edges) of a directly generated
     local subgraph at full size.  The oracle cannot run at this size, so (a) a seeded sample of
