@@ -191,7 +191,7 @@ def run_evidence_workload(args, g, synth, torch, dev):
 
     if wl in ("c4-spmm", "c4-step"):
         scale, n, E, seed, F0, bf16 = 22, 1 << 22, 100_000_000, GRAPH_SEED - 2 + 4, 128, False
-    elif wl == "c5-spmm":
+    elif wl in ("c5-spmm", "c5-step"):
         # one quarter of configuration 5's edge factor (2^30 instead of 2^32 edges) on the same 2^24 nodes
         scale, n, E, seed, F0, bf16 = 24, 1 << 24, 1 << 30, GRAPH_SEED - 2 + 5, 64, True
     else:                                                    # c3-step
@@ -200,7 +200,7 @@ def run_evidence_workload(args, g, synth, torch, dev):
     src, dst = synth.rmat_graph(scale, E, seed=seed, n_nodes=n, device=dev, chunk=1 << 28,
                                 progress=lambda done, total: log(f"{wl}: generated {done} of {total} edges"))
     torch.cuda.synchronize()
-    missing = {"c3-step": 15, "c5-spmm": 255}.get(wl, 0)    # the other partitions' shares of each node's in-degree
+    missing = {"c3-step": 15, "c5-spmm": 255, "c5-step": 255}.get(wl, 0)    # the other partitions' shares of each node's in-degree
     d_global = None
     if missing:
         d_local = torch.bincount(dst, minlength=n)
@@ -242,6 +242,12 @@ def run_evidence_workload(args, g, synth, torch, dev):
         opts = g.step_opts(estimator=g.EST_NONE, full_graph=True)
         arch = "gcn"
         x = synth.normal_matrix(n, dims[0], seed, device=dev)
+    elif wl == "c5-step":
+        dims = [64, 128, 16]
+        model = g.model_desc(g.ARCH_SAGE_MEAN, dims, feat_dtype=g.DTYPE_BF16)
+        opts = g.step_opts(estimator=g.EST_SHRINKAGE, full_graph=True)
+        arch = "sage"
+        x = synth.to_bf16_rne(synth.normal_matrix(n, dims[0], seed, device=dev))
     else:
         dims = [128, 256, 256, 172]
         model = g.model_desc(g.ARCH_SAGE_MEAN, dims, feat_dtype=g.DTYPE_BF16)
@@ -263,8 +269,9 @@ def run_evidence_workload(args, g, synth, torch, dev):
     kernels = _kernel_table(g, torch, fn, args.steps)
     used = int(g.read_stats(stats)[0]["nnz_used"])
     out.update(metric="per-partition train-step edges/s (fwd+bwd)", unit="edges/s", value=used / dt, ms_per_step=dt * 1e3,
-               dtype="bf16-stored features, f32 arithmetic" if wl == "c3-step" else "f32",
-               config={"workload": f"{wl}: dims {dims}, R-MAT scale {scale}, n={n}, nnz={nnz}, edges used per step {used}",
+               dtype="bf16-stored features, f32 arithmetic" if wl in ("c3-step", "c5-step") else "f32",
+               config={"workload": f"{wl}: dims {dims}, R-MAT scale {scale}, n={n}, nnz={nnz}, edges used per step {used}"
+                                   + (" (one quarter of the configuration's 2^32 edges)" if wl == "c5-step" else ""),
                        "params": P},
                roofline=_roofline(kernels, EVIDENCE_TRAFFIC.get(wl, {})), kernels=kernels)
     print(json.dumps(out), flush=True)
@@ -279,7 +286,7 @@ def main():
     ap.add_argument("--small", action="store_true", help="scaled-down graph (debugging only; not a valid result)")
     ap.add_argument("--shapes", action="store_true", help="per-launch-shape kernel table on stderr (debugging)")
     ap.add_argument("--workload", default="c2-step",
-                    choices=["c2-step", "c2-gat-step", "c2-dropout-step", "c2-weighted-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "aggregate-stress"],
+                    choices=["c2-step", "c2-gat-step", "c2-dropout-step", "c2-weighted-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "c5-step", "aggregate-stress"],
                     help="c2-step (default) is the headline workload; the others are evidence runs for the other "
                          "configurations (each prints one JSON line of the same form)")
     ap.add_argument("--copy-calibration", action="store_true",

@@ -263,6 +263,9 @@ DropoutPlan dropout_plan(const grp_step_opts* o);
 uint64_t dropout_layer_key(const DropoutPlan& d, int layer);
 grp_status launch_dropout(const DropoutPlan& d, int layer, const int64_t* l2g, int64_t n, int32_t F, float* H, int64_t ldh,
                           float* act, int64_t ld_act, const float* res, int64_t ld_res, hipStream_t st);
+// Y[i, :F] = rowscale[i] * X[i, :F] (whole 16-byte column groups)
+grp_status launch_scale_rows(const float* X, int64_t ldx, const float* rowscale, int64_t n, int32_t F, float* Y, int64_t ldy,
+                             hipStream_t st);
 // out[i] = in[i] * s
 grp_status launch_scale_copy(const float* in, float s, float* out, int64_t n, hipStream_t st);
 grp_status launch_pack_weights(const PackJobs& jobs, hipStream_t st);

@@ -158,6 +158,32 @@ __global__ __launch_bounds__(256) void scale_copy_kernel(const float* __restrict
     if (i < n) out[i] = in[i] * s;
 }
 
+// Y[i, :] = rowscale[i] * X[i, :] over c4 float4 columns (pitches multiples of 4, 16-byte aligned bases).
+__global__ __launch_bounds__(256) void scale_rows_kernel(const float* __restrict__ X, int64_t ldx,
+                                                         const float* __restrict__ rowscale, int64_t n, int c4,
+                                                         float* __restrict__ Y, int64_t ldy) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n * c4) return;
+    const int64_t i = e / c4;
+    const int c = 4 * (int)(e % c4);
+    float4 v = *reinterpret_cast<const float4*>(X + i * ldx + c);
+    const float a = rowscale[i];
+    v.x *= a; v.y *= a; v.z *= a; v.w *= a;
+    *reinterpret_cast<float4*>(Y + i * ldy + c) = v;
+}
+
+grp_status launch_scale_rows(const float* X, int64_t ldx, const float* rowscale, int64_t n, int32_t F, float* Y, int64_t ldy,
+                             hipStream_t st) {
+    if (n <= 0) return GRP_OK;
+    const int c4 = (F + 3) / 4;
+    if (ldx % 4 || ldy % 4 || ldx < 4 * c4 || ldy < 4 * c4 || (uintptr_t)X % 16 || (uintptr_t)Y % 16)
+        return fail(GRP_EINVAL, "scale_rows: operands must be 16-byte friendly");
+    ProfScope ps("scale_rows", st, 0.0, 8.0 * n * F);
+    hipLaunchKernelGGL(scale_rows_kernel, dim3((unsigned)cdiv(n * c4, 256)), dim3(256), 0, st, X, ldx, rowscale, n, c4, Y, ldy);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
 grp_status launch_scale_copy(const float* in, float s, float* out, int64_t n, hipStream_t st) {
     if (n <= 0) return GRP_OK;
     hipLaunchKernelGGL(scale_copy_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, in, s, out, n);
@@ -315,7 +341,7 @@ grp_status launch_degree_scales(const int32_t* d_in, const int32_t* d_out, int64
 }
 
 // ------------------------------------------------------------------ coverage statistics
-constexpr int STATS_BLOCKS = 512;
+constexpr int STATS_BLOCKS = 2048;
 
 struct StatsPartial {
     double ratio, r_dbl;

@@ -783,8 +783,8 @@ struct TnPlan {
 
 static TnPlan tn_plan(int64_t M, int K, int N, int products = 1) {
     TnPlan p;
-    p.bk_tile = 128;
     p.bn_tile = N > 64 ? 128 : (N > 32 ? 64 : 32);
+    p.bk_tile = (K <= 64 && p.bn_tile >= 64) ? 64 : 128;      // a short K fills a 64-row tile
     p.tiles_k = (int)cdiv(K, p.bk_tile);
     p.tiles_n = (int)cdiv(N, p.bn_tile);
     int64_t s = TN_TARGET_WGS / (p.tiles_k * p.tiles_n * products);
@@ -1125,12 +1125,15 @@ static void tn_pick(const GemmTNArgs& a, const TnPlan& p, int dual, float* out, 
                     float* cs_out, hipStream_t st) {
     const unsigned blocks = (unsigned)(NXCD * p.tiles_k * p.tiles_n * (dual ? 2 : 1) * cdiv(p.splits, NXCD));
     dim3 grid(blocks);
-    if (p.bn_tile == 128)
-        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, 2, 2, 2, 2>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, dual, p.splits, p.chunk, out, out2, out_ld, stride, cs_out, stride);
-    else if (p.bn_tile == 64)
-        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, 4, 1, 1, 2>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, dual, p.splits, p.chunk, out, out2, out_ld, stride, cs_out, stride);
-    else
-        hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, 4, 1, 1, 1>), grid, dim3(256), 0, st, a, p.tiles_k, p.tiles_n, dual, p.splits, p.chunk, out, out2, out_ld, stride, cs_out, stride);
+#define GRP_TN_LAUNCH(WM_, WN_, TM_, TN_)                                                                              \
+    hipLaunchKernelGGL((gemm_tn_kernel<AT, VEC, GATHER, WM_, WN_, TM_, TN_>), grid, dim3(256), 0, st, a, p.tiles_k,     \
+                       p.tiles_n, dual, p.splits, p.chunk, out, out2, out_ld, stride, cs_out, stride)
+    if (p.bk_tile == 64 && p.bn_tile == 128) GRP_TN_LAUNCH(2, 2, 1, 2);
+    else if (p.bk_tile == 64) GRP_TN_LAUNCH(2, 2, 1, 1);
+    else if (p.bn_tile == 128) GRP_TN_LAUNCH(2, 2, 2, 2);
+    else if (p.bn_tile == 64) GRP_TN_LAUNCH(4, 1, 1, 2);
+    else GRP_TN_LAUNCH(4, 1, 1, 1);
+#undef GRP_TN_LAUNCH
 }
 
 // One launch computes C = A^T B and, when a second operand is given, C2 = A2^T B (a.A2) or

@@ -329,6 +329,13 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             SpmmArgs s;            // dT = A^T (dZ / |N_v|)  over the block's inputs
             fill_spmm(s, B, true, p.partials);
             s.F = fout; s.X = dZ; s.ldx = ldp(fout); s.colscale = B.inv_in; s.Y = p.tmpA; s.ldy = ldp(fout);
+            // The per-edge gather of 1/|N_v| costs a cache line per edge once that array outgrows the L2:
+            // where a row has more edges than an eighth of its width it is cheaper to scale dZ's rows once.
+            if (B.nnz > (int64_t)B.n_dst * fout / 8) {
+                GRP_TRY(launch_scale_rows(dZ, ldp(fout), B.inv_in, B.n_dst, fout, p.tmpB, ldp(fout), st));
+                s.X = p.tmpB;
+                s.colscale = nullptr;
+            }
             GRP_TRY(launch_spmm(s, st));
             if (shared_rows) {     // [dW_self | dW_neigh] = H^T [dZ | dT] in one launch
                 t.B2 = p.tmpA; t.ldb2 = ldp(fout); t.C2 = grad + L.off_wn;

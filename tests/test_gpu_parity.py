@@ -170,7 +170,8 @@ def test_gemm_nn_matches_numpy(g, M, N, K, bf16):
 
 
 @pytest.mark.parametrize("M,K,N,bf16", [(10000, 256, 256, False), (70001, 100, 47, False), (513, 64, 8, False),
-                                        (30000, 128, 172, True), (31, 33, 130, False), (0, 16, 16, False)])
+                                        (30000, 128, 172, True), (31, 33, 130, False), (0, 16, 16, False),
+                                        (20000, 64, 128, True), (9001, 48, 47, False), (40000, 17, 64, False)])
 def test_gemm_tn_matches_numpy(g, M, K, N, bf16):
     _note(f"gemm_tn M={M} K={K} N={N} bf16={bf16}")
     a = synth.normal_matrix(max(M, 1), K, 3)[:M]
