@@ -39,6 +39,8 @@ template <> struct Vec4Load<__hip_bfloat16> {
     }
 };
 
+constexpr int SPMM_DEEP_G = 16;      // groups of this many lanes (rows of 33..64 elements) keep 8 gathers in flight
+
 __device__ __forceinline__ float row_scale(int mode, int64_t deg, int self_term) {
     if (mode == GRP_SCALE_MEAN) return 1.0f / (float)(deg > 1 ? deg : 1);
     if (mode == GRP_SCALE_RSQRT) {
@@ -58,38 +60,42 @@ __device__ __forceinline__ void add4(float4& acc, const float4& v) {
 
 // Sum of X rows over the edges [b, e) for the calling group of G lanes (lane t).
 // EV: every edge carries a value val[e] that multiplies its gathered row.
+// U neighbour rows are requested before any is accumulated: 4, or 8 for groups of 16 lanes (measured:
+// +4 % at F = 47; no gain for wider rows, and narrower groups fetch fewer than 8 indices per batch).
 template <typename XT, int G, int NJ, bool EV>
 __device__ __forceinline__ void gather_rows(const int32_t* __restrict__ idx, const float* __restrict__ val, int64_t b,
                                             int64_t e, const XT* __restrict__ X, int64_t ldx,
                                             const float* __restrict__ colscale, int t, const bool (&live)[NJ],
                                             float4 (&acc)[NJ]) {
+    constexpr int U = (G == SPMM_DEEP_G && NJ == 1) ? 8 : 4;       // a batch holds G indices, so U <= G
     for (int64_t base = b; base < e; base += G) {
         const int cnt = (int)((e - base) < (int64_t)G ? (e - base) : (int64_t)G);
         const int mine = (t < cnt) ? idx[base + t] : 0;
         float minew = 1.f;
         if (EV) minew = (t < cnt) ? val[base + t] : 0.f;
         int k = 0;
-        for (; k + 4 <= cnt; k += 4) {
-            const int64_t c0 = __shfl(mine, k, G), c1 = __shfl(mine, k + 1, G);
-            const int64_t c2 = __shfl(mine, k + 2, G), c3 = __shfl(mine, k + 3, G);
-            float s0 = 1.f, s1 = 1.f, s2 = 1.f, s3 = 1.f;
-            if (colscale) { s0 = colscale[c0]; s1 = colscale[c1]; s2 = colscale[c2]; s3 = colscale[c3]; }
-            if (EV) {
-                s0 *= __shfl(minew, k, G); s1 *= __shfl(minew, k + 1, G);
-                s2 *= __shfl(minew, k + 2, G); s3 *= __shfl(minew, k + 3, G);
+        for (; k + U <= cnt; k += U) {
+            int64_t c[U];
+            float sc[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                c[u] = __shfl(mine, k + u, G);
+                sc[u] = colscale ? colscale[c[u]] : 1.f;
+                if (EV) sc[u] *= __shfl(minew, k + u, G);
             }
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
                 if (!live[j]) continue;
                 const int col = 4 * (t + G * j);
-                const float4 v0 = Vec4Load<XT>::ld(X + c0 * ldx + col);
-                const float4 v1 = Vec4Load<XT>::ld(X + c1 * ldx + col);
-                const float4 v2 = Vec4Load<XT>::ld(X + c2 * ldx + col);
-                const float4 v3 = Vec4Load<XT>::ld(X + c3 * ldx + col);
+                float4 v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[u] = Vec4Load<XT>::ld(X + c[u] * ldx + col);
                 if (EV || colscale) {
-                    axpy4(acc[j], s0, v0); axpy4(acc[j], s1, v1); axpy4(acc[j], s2, v2); axpy4(acc[j], s3, v3);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) axpy4(acc[j], sc[u], v[u]);
                 } else {
-                    add4(acc[j], v0); add4(acc[j], v1); add4(acc[j], v2); add4(acc[j], v3);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) add4(acc[j], v[u]);
                 }
             }
         }
