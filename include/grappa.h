@@ -156,7 +156,8 @@ grp_status grp_partition_halo(const int64_t* src, const int64_t* dst, int64_t E,
 
 /* DEV uint8[n]: 1 for the nodes of the base chunk (a partition's loss nodes are the training
  * nodes of its base chunk; the swept chunk only supplies neighbours), or for the owned nodes of
- * a halo partition.  *mask is NULL for partitions built by grp_partition / from a local COO.  Borrowed pointer, valid until the handle is destroyed. */
+ * a halo partition.  *mask is NULL for partitions built by grp_partition / from a local COO.
+ * Borrowed pointer, valid until the handle is destroyed.                                      */
 grp_status grp_partition_base_mask(const grp_partition_t* part, const uint8_t** mask);
 
 /* Adopt a partition's share that was generated directly as local edges.
@@ -185,7 +186,7 @@ grp_status grp_partition_destroy(grp_partition_t* part);   /* NULL is a no-op */
 /* Model description (the paper's "GNN Models": GraphSAGE aggregates the neighbours'
  * states by averaging, combines with the node's own state and multiplies by a matrix;
  * GCN applies a linear map and averages neighbours with degree-based weights).
- * ReLU after every layer but the last; no dropout.  GCN normalisation:
+ * ReLU after every layer but the last; dropout is a step option (grp_step_opts).  GCN normalisation:
  * Ahat[v,u] = (A[v,u] + [u==v]) / sqrt((d_in(v)+1)(d_out(u)+1)) on local degrees when
  * gcn_self_loops != 0, else A[v,u] / sqrt(max(d_in(v),1) max(d_out(u),1)).
  * Flat parameter layout (weights in, gradients out): layer-major; per layer W_self
