@@ -266,6 +266,8 @@ grp_status launch_dropout(const DropoutPlan& d, int layer, const int64_t* l2g, i
 // Y[i, :F] = rowscale[i] * X[i, :F] (whole 16-byte column groups)
 grp_status launch_scale_rows(const float* X, int64_t ldx, const float* rowscale, int64_t n, int32_t F, float* Y, int64_t ldy,
                              hipStream_t st);
+// Y[i, :] = [X[i, :F] | 0 ...] up to the pitch ldy
+grp_status launch_pad_rows(const float* X, int64_t ldx, int64_t n, int32_t F, float* Y, int64_t ldy, hipStream_t st);
 // out[i] = in[i] * s
 grp_status launch_scale_copy(const float* in, float s, float* out, int64_t n, hipStream_t st);
 grp_status launch_pack_weights(const PackJobs& jobs, hipStream_t st);

@@ -184,6 +184,23 @@ grp_status launch_scale_rows(const float* X, int64_t ldx, const float* rowscale,
     return GRP_OK;
 }
 
+// Y[i, :] = [X[i, :F] | 0 ...] up to the pitch ldy (a zero-padded, 16-byte friendly copy)
+__global__ __launch_bounds__(256) void pad_rows_kernel(const float* __restrict__ X, int64_t ldx, int64_t n, int F,
+                                                       float* __restrict__ Y, int64_t ldy) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n * ldy) return;
+    const int64_t i = e / ldy;
+    const int c = (int)(e % ldy);
+    Y[e] = c < F ? X[i * ldx + c] : 0.f;
+}
+
+grp_status launch_pad_rows(const float* X, int64_t ldx, int64_t n, int32_t F, float* Y, int64_t ldy, hipStream_t st) {
+    if (n <= 0) return GRP_OK;
+    hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)cdiv(n * ldy, 256)), dim3(256), 0, st, X, ldx, n, (int)F, Y, ldy);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
 grp_status launch_scale_copy(const float* in, float s, float* out, int64_t n, hipStream_t st) {
     if (n <= 0) return GRP_OK;
     hipLaunchKernelGGL(scale_copy_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, in, s, out, n);

@@ -34,6 +34,7 @@ struct LayerBufs {
 struct StepPlan {
     std::vector<LayerBufs> L;
     float *inv_in = nullptr, *gr = nullptr, *gs = nullptr, *grinv = nullptr;
+    float* Xpad = nullptr;       // residual first layer: zero-padded copy of features whose rows are not 16-byte friendly
     float* gr_drop = nullptr;    // gr / (1 - dropout rate): the row scale of the backward pass through a dropped layer
     float *tmpA = nullptr, *tmpB = nullptr, *dZa = nullptr, *dZb = nullptr, *Ga = nullptr, *Gb = nullptr;
     void *tn_ws = nullptr, *colsum_ws = nullptr, *stats_ws = nullptr, *sampler_ws = nullptr;
@@ -132,6 +133,7 @@ static StepPlan make_plan(const grp_partition_t* part, const grp_model_desc* m, 
         p.gs = b.take<float>((size_t)n);
         p.grinv = b.take<float>((size_t)n);
         if (o->dropout_rate > 0.f) p.gr_drop = b.take<float>((size_t)n);
+        if (p.L[0].skip) p.Xpad = b.take<float>((size_t)n * ldp(m->dims[0]));
     }
     p.tmpA = b.take<float>((size_t)max_rows * 2 * fmax);   // holds two matrices side by side in the fused layers
     p.tmpB = b.take<float>((size_t)max_rows * fmax);
@@ -387,6 +389,12 @@ static grp_status gcn_step(const grp_partition_t* g, const grp_model_desc* m, co
     for (int l = 0; l < k && n > 0; ++l) {
         const LayerBufs& L = p.L[l];
         const int fin = m->dims[l], fout = m->dims[l + 1];
+        if (l == 0 && L.skip && (ldh % 4 != 0 || (uintptr_t)H % 16 != 0)) {
+            // the skip is added from 16-byte vectors: give the layer an aligned copy of the features
+            GRP_TRY(launch_pad_rows((const float*)X, ldh, n, fin, p.Xpad, ldp(fin), st));
+            H = p.Xpad;
+            ldh = ldp(fin);
+        }
         GemmNNArgs a;
         a.M = n; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.Bt = L.Wt_s; a.ldbt = L.ldwt;
         a.rowscale = p.gs; a.C = p.tmpA; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);

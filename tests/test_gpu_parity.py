@@ -460,7 +460,8 @@ def test_minibatch_is_bit_reproducible_and_batch_dependent(g):
 
 
 @pytest.mark.parametrize("dims,self_loops", [([24, 40, 40, 40, 6], True), ([32, 32, 32, 5], False),
-                                             ([128, 256, 256, 256, 64], True)])
+                                             ([128, 256, 256, 256, 64], True),
+                                             ([13, 13, 13, 13, 6], True)])   # a residual first layer on 52-byte feature rows
 def test_residual_gcn_matches_oracle(g, dims, self_loops):
     _note(f"residual gcn dims={dims} sl={self_loops}")
     scale, E, K = 13, 250000, 2
