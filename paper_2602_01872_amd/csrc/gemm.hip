@@ -1204,8 +1204,9 @@ grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st) {
 
 extern "C" grp_status grp_gemm_nn(int64_t M, int32_t N, int32_t K, const void* A, int64_t lda, int32_t a_dtype,
                                   const float* B, int64_t ldb, float* C, int64_t ldc, void* stream) {
-    if (!A || !B || !C) return grp::fail(GRP_EINVAL, "grp_gemm_nn: null argument");
     if (M < 0 || N <= 0 || K <= 0 || lda < K || ldb < N || ldc < N) return grp::fail(GRP_EINVAL, "grp_gemm_nn: bad shape");
+    if (!B || (M > 0 && (!A || !C))) return grp::fail(GRP_EINVAL, "grp_gemm_nn: null argument");
+    if (M == 0) return GRP_OK;                          // no rows: nothing to compute
     grp::GemmNNArgs a;
     a.M = M; a.N = N; a.K = K; a.A = A; a.lda = lda; a.a_bf16 = a_dtype == GRP_DTYPE_BF16;
     a.B = B; a.ldb = ldb; a.C = C; a.ldc = ldc;
@@ -1214,8 +1215,9 @@ extern "C" grp_status grp_gemm_nn(int64_t M, int32_t N, int32_t K, const void* A
 
 extern "C" grp_status grp_gemm_nt(int64_t M, int32_t N, int32_t K, const void* A, int64_t lda, int32_t a_dtype,
                                   const float* Bt, int64_t ldbt, float* C, int64_t ldc, void* stream) {
-    if (!A || !Bt || !C) return grp::fail(GRP_EINVAL, "grp_gemm_nt: null argument");
+    if (!Bt || (M > 0 && (!A || !C))) return grp::fail(GRP_EINVAL, "grp_gemm_nt: null argument");
     if (M < 0 || N <= 0 || K <= 0 || lda < K || ldbt < K || ldc < N) return grp::fail(GRP_EINVAL, "grp_gemm_nt: bad shape");
+    if (M == 0) return GRP_OK;                          // no rows: nothing to compute
     grp::GemmNNArgs a;
     a.M = M; a.N = N; a.K = K; a.A = A; a.lda = lda; a.a_bf16 = a_dtype == GRP_DTYPE_BF16;
     a.Bt = Bt; a.ldbt = ldbt; a.C = C; a.ldc = ldc;
