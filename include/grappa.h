@@ -224,7 +224,7 @@ typedef struct {
     int32_t        fanouts[GRP_MAX_LAYERS]; /* fanouts[l] belongs to layer l, 0 = input side   */
     uint64_t       sampler_seed;
     uint64_t       batch_id;
-    float          dropout_rate;  /* in [0, 1); 0 = off.  Full-graph mode only (see below)     */
+    float          dropout_rate;  /* in [0, 1); 0 = off (see below)                            */
     int32_t        reserved2;
     uint64_t       dropout_seed;
 } grp_step_opts;
@@ -266,7 +266,8 @@ grp_status grp_step_workspace_bytes(const grp_partition_t* part, const grp_model
  *                >= floor(dropout_rate * 2^24)
  * in wrapping uint64 arithmetic (mix as in grp_partition), so a node's mask depends on its global
  * id, not on the partition that holds it; 1 / (1 - rate) is taken in fp32.  The attention
- * coefficients of GRP_ARCH_GAT are not dropped.  GRP_EUNSUPPORTED in mini-batch mode.
+ * coefficients of GRP_ARCH_GAT are not dropped.  In mini-batch mode v is the node a block row stands
+ * for, and batch_id is the one the sampler uses.
  *
  * Mini-batch mode (opts->full_graph = 0, GraphSAGE only): isolated k-hop sampling inside the
  * partition, then the same layers on the sampled blocks.  Sampling rule (the paper fixes

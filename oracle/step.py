@@ -26,8 +26,9 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
     stats dict gains the key "near_kink".
     A partition built with edge weights (``graph.partition(..., weights=)``) trains the weighted-mean
     GraphSAGE aggregator and reports the coverage statistics of the weight masses (full-graph mode).
-    ``dropout = dict(rate=, seed=, batch_id=)`` (full-graph mode only) drops hidden activations as
-    ``dropout.py`` describes, keyed on the nodes' global ids ``part["l2g"]``.
+    ``dropout = dict(rate=, seed=, batch_id=)`` drops hidden activations as ``dropout.py`` describes,
+    keyed on the nodes' global ids ``part["l2g"]`` (in mini-batch mode a block row is the node it stands
+    for, and batch_id defaults to the sampler's).
     """
     n = part["n"]
     k = len(dims) - 1
@@ -42,9 +43,7 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
     w_all = ratio if estimator == coverage.NODE_LEVEL else np.ones(n)
 
     drop = None
-    if dropout is not None and float(dropout["rate"]) != 0.0:
-        if minibatch is not None:
-            raise ValueError("dropout is defined for full-graph steps only")
+    if dropout is not None and float(dropout["rate"]) != 0.0 and minibatch is None:
         drop = dropout_mod.layer_factors(dropout["seed"], dropout.get("batch_id", 0), part["l2g"], dims,
                                          dropout["rate"])
     if minibatch is None:
@@ -77,9 +76,19 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
                                                  minibatch["sampler_seed"], minibatch["batch_id"])
     xin = np.asarray(x)[input_nodes].astype(np.float64)      # gather, then widen (same values)
     nseed = seeds.size
+    if dropout is not None and float(dropout["rate"]) != 0.0:
+        # a block row is dropped as the node it stands for: layer l's rows are the first n_dst entries of
+        # its source list (partition-local ids), keyed by their global ids
+        sc = dropout_mod.scale(dropout["rate"])
+        drop = []
+        for l in range(k - 1):
+            nodes_l = blocks[l]["src_nodes"][:blocks[l]["n_dst"]]
+            keep = dropout_mod.keep_mask(dropout["seed"], dropout.get("batch_id", minibatch["batch_id"]), l,
+                                         np.asarray(part["l2g"])[nodes_l], dims[l + 1], dropout["rate"])
+            drop.append(keep.astype(np.float64) * sc)
     res = gnn.forward_backward(arch, dims, theta, xin, blocks, np.asarray(labels)[seeds],
                                w_all[seeds], np.arange(nseed, dtype=np.int64),
-                               gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink, relu_set=relu_set)
+                               gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink, relu_set=relu_set, drop=drop)
     loss, grad = res[0], res[1]
     last = blocks[-1]
     sampled = np.bincount(last["edst"], minlength=nseed)

@@ -250,7 +250,7 @@ void pack_jobs_add(PackJobs& jobs, const float* in, int32_t rows, int32_t cols, 
                    float* out, int64_t ld_out, float scale = 1.f);
 
 // Inverted dropout of a layer's output (rows = local nodes, F columns), in place:
-//   keep(v, f) = (mix(key + (l2g[v] * F + f + 1) * GAMMA) >> 40) >= thresh;  a' = keep ? a * scale : 0.
+//   keep(v, f) = (mix(key + (l2g[node(v)] * F + f + 1) * GAMMA) >> 40) >= thresh;  a' = keep ? a * scale : 0.
 // Plain layer: H holds the activation.  Residual layer (act != null): act holds the activation and
 // is overwritten with a'; H = a' + res.
 struct DropoutPlan {
@@ -262,7 +262,8 @@ struct DropoutPlan {
 DropoutPlan dropout_plan(const grp_step_opts* o);
 uint64_t dropout_layer_key(const DropoutPlan& d, int layer);
 grp_status launch_dropout(const DropoutPlan& d, int layer, const int64_t* l2g, int64_t n, int32_t F, float* H, int64_t ldh,
-                          float* act, int64_t ld_act, const float* res, int64_t ld_res, hipStream_t st);
+                          float* act, int64_t ld_act, const float* res, int64_t ld_res, hipStream_t st,
+                          const int32_t* node_of_row = nullptr /*row i is local node node_of_row[i] (null: i)*/);
 // Y[i, :F] = rowscale[i] * X[i, :F] (whole 16-byte column groups)
 grp_status launch_scale_rows(const float* X, int64_t ldx, const float* rowscale, int64_t n, int32_t F, float* Y, int64_t ldy,
                              hipStream_t st);
@@ -338,6 +339,7 @@ struct Block {
     const LongRows* long_bwd = nullptr;
     const int32_t* self_rows = nullptr;  // [n_dst] or null (row i)
     float* inv_in = nullptr;             // [n_dst] 1 / max(row length, 1); weighted: 1 / local weight mass (0 if none)
+    const int32_t* dst_nodes = nullptr;  // mini-batch: partition-local id of every destination row (null: row i is node i)
     const float* val = nullptr;          // weighted partitions: edge weights in ptr/idx order
     const float* valT = nullptr;         //                      and in ptrT/idxT order
 };

@@ -100,13 +100,15 @@ template <bool VEC>
 __global__ __launch_bounds__(256) void dropout_kernel(const int64_t* __restrict__ l2g, int64_t n, int F, uint64_t key,
                                                       uint32_t thresh, float scale, float* __restrict__ H, int64_t ldh,
                                                       float* __restrict__ act, int64_t ld_act,
-                                                      const float* __restrict__ res, int64_t ld_res) {
+                                                      const float* __restrict__ res, int64_t ld_res,
+                                                      const int32_t* __restrict__ node_of_row) {
     const int C4 = (F + 3) / 4;
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= n * C4) return;
     const int64_t v = e / C4;
     const int f0 = 4 * (int)(e % C4);
-    const uint64_t base = (uint64_t)l2g[v] * (uint64_t)F + (uint64_t)f0 + 1ull;
+    const int64_t node = node_of_row ? (int64_t)node_of_row[v] : v;
+    const uint64_t base = (uint64_t)l2g[node] * (uint64_t)F + (uint64_t)f0 + 1ull;
     float m[4];                       // keep ? scale : 0
 #pragma unroll
     for (int q = 0; q < 4; ++q)
@@ -133,7 +135,8 @@ __global__ __launch_bounds__(256) void dropout_kernel(const int64_t* __restrict_
 }
 
 grp_status launch_dropout(const DropoutPlan& d, int layer, const int64_t* l2g, int64_t n, int32_t F, float* H, int64_t ldh,
-                          float* act, int64_t ld_act, const float* res, int64_t ld_res, hipStream_t st) {
+                          float* act, int64_t ld_act, const float* res, int64_t ld_res, hipStream_t st,
+                          const int32_t* node_of_row) {
     if (!d.on || n <= 0) return GRP_OK;
     if (!l2g || !H || (act && !res)) return fail(GRP_EINVAL, "dropout: null argument");
     ProfScope ps("dropout", st, 0.0, 8.0 * n * F * (act ? 2 : 1));
@@ -144,10 +147,10 @@ grp_status launch_dropout(const DropoutPlan& d, int layer, const int64_t* l2g, i
     const uint64_t key = dropout_layer_key(d, layer);
     if (vec)
         hipLaunchKernelGGL(dropout_kernel<true>, dim3((unsigned)cdiv(work, 256)), dim3(256), 0, st, l2g, n, (int)F, key,
-                           d.thresh, d.scale, H, ldh, act, ld_act, res, ld_res);
+                           d.thresh, d.scale, H, ldh, act, ld_act, res, ld_res, node_of_row);
     else
         hipLaunchKernelGGL(dropout_kernel<false>, dim3((unsigned)cdiv(work, 256)), dim3(256), 0, st, l2g, n, (int)F, key,
-                           d.thresh, d.scale, H, ldh, act, ld_act, res, ld_res);
+                           d.thresh, d.scale, H, ldh, act, ld_act, res, ld_res, node_of_row);
     GRP_LAUNCH_CHECK();
     return GRP_OK;
 }

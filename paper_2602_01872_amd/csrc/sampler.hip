@@ -354,6 +354,7 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
 
         Block& B = blocks[l];
         B.n_dst = n_dst;
+        B.dst_nodes = dst_nodes;
         B.ptr = L.ptr;
         B.inv_in = L.inv_in;
         B.long_fwd = nullptr;                            // rows hold at most `fanout` edges

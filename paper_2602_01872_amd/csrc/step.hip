@@ -169,8 +169,6 @@ static grp_status check_step_args(const grp_partition_t* part, const grp_model_d
         return fail(GRP_EUNSUPPORTED, "train_step: a weighted partition trains GraphSAGE in full-graph mode only");
     if (!(opts->dropout_rate >= 0.f && opts->dropout_rate < 1.f))
         return fail(GRP_EINVAL, "train_step: dropout rate outside [0, 1)");
-    if (opts->dropout_rate > 0.f && !opts->full_graph)
-        return fail(GRP_EUNSUPPORTED, "train_step: dropout is implemented for full-graph steps only");
     if (!opts->full_graph) {
         if (model->arch != GRP_ARCH_SAGE_MEAN)
             return fail(GRP_EUNSUPPORTED, "train_step: mini-batch mode is implemented for GraphSAGE only");
@@ -275,7 +273,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             s.addend = L.H_out; s.ld_add = ldp(fout); s.relu = relu; s.Y = L.H_out; s.ldy = ldp(fout);
             GRP_TRY(launch_spmm(s, st));
         }
-        if (relu) GRP_TRY(launch_dropout(drop, l, g->l2g, B.n_dst, fout, L.H_out, ldp(fout), nullptr, 0, nullptr, 0, st));
+        if (relu) GRP_TRY(launch_dropout(drop, l, g->l2g, B.n_dst, fout, L.H_out, ldp(fout), nullptr, 0, nullptr, 0, st, B.dst_nodes));
         H = L.H_out; ldh = ldp(fout); h_bf16 = 0;
     }
 

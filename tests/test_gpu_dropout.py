@@ -85,10 +85,6 @@ def test_dropout_is_reproducible_and_rejects_bad_options(g):
     for bad in (1.0, -0.25, float("nan")):
         with pytest.raises(g.GrappaError):
             g.grp_step_workspace_bytes(part, model, g.step_opts(full_graph=True, dropout_rate=bad))
-    seeds = torch.arange(16, dtype=torch.int32, device=DEV)
-    with pytest.raises(g.GrappaError):
-        g.grp_step_workspace_bytes(part, model, g.step_opts(full_graph=False, seeds=seeds, fanouts=(3, 3),
-                                                            dropout_rate=0.5))
 
 
 @pytest.mark.parametrize("arch", ["sage", "gat"])
@@ -144,3 +140,40 @@ def test_phase_parallel_loop_with_dropout_matches_oracle(g):
     assert np.abs(plain - want).max() > 1e-3 * np.abs(want).max()
     for p in parts:
         p.destroy()
+
+
+@pytest.mark.parametrize("dims,fanouts,bf16", [([32, 48, 40, 6], (5, 4, 3), False), ([64, 128, 16], (10, 64), True)])
+def test_minibatch_dropout_matches_oracle(g, dims, fanouts, bf16):
+    """Mini-batch steps with dropout: a block row is dropped as the node it stands for."""
+    print(f"[case] mini-batch dropout dims={dims} fanouts={fanouts} bf16={bf16}", flush=True)
+    scale, E, K = 13, 250000, 2
+    N = 1 << scale
+    s, d = synth.rmat_graph(scale, E, seed=2602018733)
+    part = g.grp_partition(s.to(DEV), d.to(DEV), N, K, 1, 0)
+    op = ograph.partition(s.numpy(), d.numpy(), N, K, 1, 0)
+    n = part.n
+    x, y, theta = make_inputs(n, dims, "sage", 23, bf16=bf16)
+    seeds = np.sort(np.random.default_rng(3).choice(n, 300, replace=False)).astype(np.int32)
+    model = g.model_desc(0, dims, g.DTYPE_BF16 if bf16 else g.DTYPE_FP32, True)
+    for batch in (0, 9):
+        seeds_dev = torch.from_numpy(seeds).to(DEV)
+        opts = g.step_opts(estimator=1, full_graph=False, seeds=seeds_dev, fanouts=fanouts, sampler_seed=5, batch_id=batch,
+                           dropout_rate=0.5, dropout_seed=808)
+        P = g.grp_param_count(model)
+        ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+        grad = torch.full((P,), float("nan"), device=DEV)
+        stats = g.new_stats(1)
+        g.grp_train_step(part, model, opts, x.to(DEV), y.to(DEV), None, theta.to(DEV), ws, grad, stats)
+        torch.cuda.synchronize()
+        mb = dict(seeds=seeds, fanouts=fanouts, sampler_seed=5, batch_id=batch)
+
+        def oracle_fn(relu_flip=None, near_kink=None, mb=mb, batch=batch):
+            return ostep.train_step(op, "sage", dims, theta.double().numpy(), x.double().numpy(), y.numpy(), estimator=1,
+                                    minibatch=mb, relu_flip=relu_flip, near_kink=near_kink,
+                                    dropout=dict(rate=0.5, seed=808, batch_id=batch))
+        og, ost = assert_step_grads_close(grad.cpu().numpy(), oracle_fn, "sage", dims, TOL_FP32)
+        st = g.read_stats(stats)[0]
+        assert int(st["nnz_used"]) == ost["nnz_used"]
+        assert abs(float(st["loss"]) - ost["loss"]) <= TOL_FP32 * abs(ost["loss"])
+    plain = ostep.train_step(op, "sage", dims, theta.double().numpy(), x.double().numpy(), y.numpy(), estimator=1, minibatch=mb)[0]
+    assert np.abs(plain - og).max() > 1e-3 * np.abs(og).max()

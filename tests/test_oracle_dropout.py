@@ -123,15 +123,38 @@ def test_gradient_with_fixed_masks_matches_finite_differences(arch, dims):
     assert np.abs(g - g0).max() > 1e-3
 
 
-def test_rate_zero_is_no_dropout_and_minibatch_refuses():
+def test_rate_zero_is_no_dropout():
     dims = [4, 6, 3]
     s, d, n, part, x, y, theta = _setup("sage", dims)
     g0, st0 = step.train_step(part, "sage", dims, theta, x, y)
     g1, st1 = step.train_step(part, "sage", dims, theta, x, y, dropout=dict(rate=0.0, seed=9))
     assert np.array_equal(g0, g1) and st0["loss"] == st1["loss"]
-    with pytest.raises(ValueError):
-        step.train_step(part, "sage", dims, theta, x, y, dropout=dict(rate=0.5, seed=9),
-                        minibatch=dict(seeds=np.arange(4), fanouts=(2, 2), sampler_seed=1, batch_id=0))
+
+
+def test_minibatch_with_full_fanout_and_dropout_is_the_full_graph_step_on_the_seeds():
+    # fanouts above every degree keep all local in-edges, so the sampled blocks span the seeds' whole
+    # k-hop neighbourhood; the masks are keyed on global ids, so the mini-batch step with dropout is the
+    # full-graph step with dropout whose loss nodes are the seeds
+    dims = [5, 7, 6, 3]
+    N, E = 120, 500
+    s, d = synth.uniform_graph(N, E, seed=14)
+    part = graph.partition(s.numpy(), d.numpy(), N, 2, 3, 1)
+    n = part["n"]
+    x = synth.normal_matrix(n, dims[0], 4).double().numpy()
+    y = synth.labels(n, dims[-1], 4).numpy()
+    theta = synth.model_weights("sage", dims, 4).double().numpy()
+    seeds = np.array([1, 5, 8, 13, 21, 34], dtype=np.int64)
+    assert int(part["d_local_in"].max()) < 64
+    mask = np.zeros(n, dtype=np.uint8)
+    mask[seeds] = 1
+    dr = dict(rate=0.5, seed=21, batch_id=6)
+    gm, sm = step.train_step(part, "sage", dims, theta, x, y, dropout=dr,
+                             minibatch=dict(seeds=seeds, fanouts=(64, 64, 64), sampler_seed=1, batch_id=6))
+    gf, sf = step.train_step(part, "sage", dims, theta, x, y, train_mask=mask, dropout=dr)
+    np.testing.assert_allclose(gm, gf, rtol=1e-10, atol=1e-13)
+    assert abs(sm["loss"] - sf["loss"]) < 1e-12
+    g0, _ = step.train_step(part, "sage", dims, theta, x, y, minibatch=dict(seeds=seeds, fanouts=(64, 64, 64), sampler_seed=1, batch_id=6))
+    assert np.abs(g0 - gm).max() > 1e-3 * np.abs(g0).max()
 
 
 @pytest.mark.parametrize("arch", ["sage", "gat"])
