@@ -82,7 +82,7 @@ def train_epochs(parts, arch, dims, theta0, xs, ys, masks, n_epochs, max_active,
 
 
 def train_sweeping(src, dst, n_nodes, n_chunks, chunk_seed, arch, dims, theta0, x, y, train_mask, total_epochs,
-                   max_active, estimator, optimizer=ADAM, lr=0.003, controller=None, gcn_self_loops=True):
+                   max_active, estimator, optimizer=ADAM, lr=0.003, controller=None, gcn_self_loops=True, dropout=None):
     """The phase-parallel algorithm over sweeping partitions (chunks + controller).
 
     The graph (global edge list ``src -> dst``, features ``x[n_nodes, F]``, labels ``y``, optional
@@ -92,6 +92,7 @@ def train_sweeping(src, dst, n_nodes, n_chunks, chunk_seed, arch, dims, theta0, 
     super-epoch starts (partitions are then rebuilt from the chunks).  Returns
     (theta, history, switches) with history the mean active loss per optimizer step and
     switches the list of epochs (0-based) after which the partitions were switched.
+    ``dropout`` as in ``train_epochs`` (batch_id = optimizer steps taken so far, across super-epochs).
     """
     ctl = controller if controller is not None else chunks.Controller(total_epochs, n_chunks)
     x = np.asarray(x, dtype=np.float64)
@@ -113,7 +114,8 @@ def train_sweeping(src, dst, n_nodes, n_chunks, chunk_seed, arch, dims, theta0, 
             grads, stats = [], []
             for p in active:
                 g, st = step.train_step(parts[p], arch, dims, theta, xs[p], ys[p], masks[p], estimator=estimator,
-                                        gcn_self_loops=gcn_self_loops)
+                                        gcn_self_loops=gcn_self_loops,
+                                        dropout=None if dropout is None else dict(dropout, batch_id=t))
                 grads.append(g)
                 stats.append(st)
             G, _ = coverage.aggregate(grads, stats, estimator)

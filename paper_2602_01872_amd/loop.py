@@ -76,8 +76,9 @@ class SweepingTrainer:
     """
 
     def __init__(self, src, dst, n_nodes, n_chunks, chunk_seed, model, x, y, train_mask, theta0, estimator,
-                 max_active, total_epochs, optimizer=None, controller=None):
+                 max_active, total_epochs, optimizer=None, controller=None, dropout_rate=0.0, dropout_seed=0):
         self.chunks = g.grp_chunks_build(src, dst, n_nodes, n_chunks, chunk_seed)
+        self.dropout_rate, self.dropout_seed = dropout_rate, dropout_seed
         self.model, self.x, self.y, self.train_mask = model, x, y, train_mask
         self.estimator, self.max_active = estimator, max_active
         self.opt = optimizer if optimizer is not None else g.optimizer_desc()
@@ -104,7 +105,8 @@ class SweepingTrainer:
             xs.append(self.x[l2g].contiguous())
             ys.append(self.y[l2g].contiguous())
             masks.append(mask.contiguous())
-        tr = PhaseParallelTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active, self.opt)
+        tr = PhaseParallelTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active, self.opt,
+                                  dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed)
         tr.theta, tr.m, tr.v, tr.step_count = self.theta, self.m, self.v, self.step_count   # carried state
         return tr
 

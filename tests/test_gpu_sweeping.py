@@ -12,11 +12,11 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-@pytest.mark.parametrize("c,M,masked", [(3, 2, False), (4, 4, True), (2, 1, False)])
-def test_sweeping_loop_matches_oracle(c, M, masked):
+@pytest.mark.parametrize("c,M,masked,drop", [(3, 2, False, 0.0), (4, 4, True, 0.0), (2, 1, False, 0.0), (3, 3, True, 0.5)])
+def test_sweeping_loop_matches_oracle(c, M, masked, drop):
     import paper_2602_01872_amd as g
     g.load()
-    print(f"[case] sweeping loop c={c} M={M} masked={masked}", flush=True)
+    print(f"[case] sweeping loop c={c} M={M} masked={masked} dropout={drop}", flush=True)
     N, E = 2400, 26000
     s, d = synth.uniform_graph(N, E, seed=91)
     dims = [12, 24, 4]
@@ -28,12 +28,13 @@ def test_sweeping_loop_matches_oracle(c, M, masked):
     lr = 0.05
     tr = g.SweepingTrainer(s.to(DEV), d.to(DEV), N, c, 17, g.model_desc(g.ARCH_SAGE_MEAN, dims), x.to(DEV), y.to(DEV),
                            None if tm is None else tm.to(DEV), theta0.to(DEV), g.EST_BATCH_MIN_DIST, M, total_epochs,
-                           g.optimizer_desc(g.OPT_SGD, lr=lr))
+                           g.optimizer_desc(g.OPT_SGD, lr=lr), dropout_rate=drop, dropout_seed=41)
     for _ in range(total_epochs):
         tr.run_epoch()
     want, hist, switches = ooptim.train_sweeping(s.numpy(), d.numpy(), N, c, 17, "sage", dims, theta0.double().numpy(),
                                                  x.double().numpy(), y.numpy(), None if tm is None else tm.numpy(),
-                                                 total_epochs, M, ocov.BATCH_MIN_DIST, optimizer=ooptim.SGD, lr=lr)
+                                                 total_epochs, M, ocov.BATCH_MIN_DIST, optimizer=ooptim.SGD, lr=lr,
+                                                 dropout=dict(rate=drop, seed=41) if drop > 0 else None)
     assert tr.switches == switches
     assert tr.step_count == len(hist)
     np.testing.assert_allclose(tr.losses(), hist, rtol=2e-4)
