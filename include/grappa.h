@@ -129,6 +129,14 @@ typedef struct grp_chunks_s grp_chunks_t;
  * Errors: GRP_EINVAL, GRP_ERANGE (an id outside [0,N)), GRP_ENOMEM, GRP_EHIP.              */
 grp_status grp_chunks_build(const int64_t* src, const int64_t* dst, int64_t E, int64_t N,
                             int32_t n_chunks, uint64_t seed, void* stream, grp_chunks_t** out);
+/* The same with the chunk of every node given by the caller instead of the random split, e.g. the
+ * output of METIS or any other partitioner run beforehand ("Chunks and Efficient Partition
+ * Construction": chunks come from unmodified partitioning strategies such as random or METIS).
+ * chunk_of_node: DEV int32[N], values in [0, n_chunks); the handle keeps a copy.
+ * Errors as grp_chunks_build, plus GRP_ERANGE for an assignment outside [0, n_chunks).          */
+grp_status grp_chunks_build_assigned(const int64_t* src, const int64_t* dst, int64_t E, int64_t N,
+                                     int32_t n_chunks, const int32_t* chunk_of_node, void* stream,
+                                     grp_chunks_t** out);
 grp_status grp_chunks_destroy(grp_chunks_t* chunks);
 
 /* The training partition of a super-epoch: base chunk + swept chunk (swept == base: the base

@@ -43,17 +43,25 @@ def sweep_schedule(n_chunks: int):
     return [[(i, (i + 1 + t) % n_chunks) for i in range(n_chunks)] for t in range(n_chunks - 1)]
 
 
-def partition_from_chunks(src, dst, n_nodes: int, n_chunks: int, seed: int, base: int, swept: int) -> dict:
+def partition_from_chunks(src, dst, n_nodes: int, n_chunks: int, seed: int, base: int, swept: int,
+                          assignment=None) -> dict:
     """Local subgraph of the partition base-chunk + swept-chunk (``swept == base``: the base
     chunk alone).  Same dict as ``graph.partition`` plus ``base_mask`` (uint8 per local node:
-    1 for the base chunk's nodes)."""
+    1 for the base chunk's nodes).  ``assignment`` (optional int array [n_nodes], values in
+    [0, n_chunks)) replaces the random split by any partitioner's output (the paper's chunks come
+    from strategies "such as random or METIS"); ``seed`` is then unused."""
     src = np.asarray(src, dtype=np.int64)
     dst = np.asarray(dst, dtype=np.int64)
     if not (0 <= base < n_chunks and 0 <= swept < n_chunks):
         raise ValueError("chunk id out of range")
     if src.size and (src.min() < 0 or dst.min() < 0 or src.max() >= n_nodes or dst.max() >= n_nodes):
         raise ValueError("node id out of range")
-    ch = chunk_of(n_nodes, n_chunks, seed)
+    if assignment is None:
+        ch = chunk_of(n_nodes, n_chunks, seed)
+    else:
+        ch = np.asarray(assignment, dtype=np.int32)
+        if ch.shape != (n_nodes,) or (ch.size and (ch.min() < 0 or ch.max() >= n_chunks)):
+            raise ValueError("assignment must give every node a chunk in [0, n_chunks)")
     member = (ch == base) | (ch == swept)
     l2g = np.flatnonzero(member).astype(np.int64)
     n = int(l2g.size)

@@ -78,6 +78,7 @@ def load() -> C.CDLL:
         "grp_partition_halo": [vp, vp, i64, i64, i32, u64, i32, i32, vp, C.POINTER(vp)],
         "grp_partition_view": [vp, C.POINTER(PartitionView)],
         "grp_chunks_build": [vp, vp, i64, i64, i32, u64, vp, C.POINTER(vp)],
+        "grp_chunks_build_assigned": [vp, vp, i64, i64, i32, vp, vp, C.POINTER(vp)],
         "grp_chunks_destroy": [vp],
         "grp_partition_from_chunks": [vp, i32, i32, vp, C.POINTER(vp)],
         "grp_partition_base_mask": [vp, C.POINTER(vp)],
@@ -289,6 +290,15 @@ def grp_chunks_build(src, dst, n_nodes: int, n_chunks: int, seed: int, stream=No
     return Chunks(out.value, n_chunks)
 
 
+def grp_chunks_build_assigned(src, dst, n_nodes: int, n_chunks: int, chunk_of_node, stream=None) -> Chunks:
+    """``chunk_of_node``: int32 device tensor [n_nodes] with values in [0, n_chunks)."""
+    out = C.c_void_p()
+    E = 0 if src is None else int(src.numel())
+    _check(load().grp_chunks_build_assigned(_ptr(src), _ptr(dst), E, n_nodes, n_chunks, _ptr(chunk_of_node),
+                                            _stream(stream), C.byref(out)))
+    return Chunks(out.value, n_chunks)
+
+
 def grp_partition_from_chunks(chunks: Chunks, base: int, swept: int, stream=None) -> Partition:
     out = C.c_void_p()
     _check(load().grp_partition_from_chunks(chunks.handle, base, swept, _stream(stream), C.byref(out)))
@@ -405,7 +415,7 @@ def read_stats(stats: torch.Tensor) -> np.ndarray:
 
 def exported_symbols():
     return ["grp_last_error", "grp_partition", "grp_node_owners", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_view",
-            "grp_partition_destroy", "grp_chunks_build", "grp_chunks_destroy", "grp_partition_from_chunks",
+            "grp_partition_destroy", "grp_chunks_build", "grp_chunks_build_assigned", "grp_chunks_destroy", "grp_partition_from_chunks",
             "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_step_activation", "grp_train_step",
             "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
             "grp_profile_enable", "grp_profile_report"]

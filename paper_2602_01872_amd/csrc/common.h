@@ -109,6 +109,7 @@ struct grp_chunks_s {
     int64_t* src = nullptr;          // [E] global ids, grouped by bucket (order inside a bucket arbitrary)
     int64_t* dst = nullptr;
     int64_t* d_global_all = nullptr; // [N]
+    int32_t* assign = nullptr;       // [N] caller-supplied chunk of every node (null: the random split by seed)
     std::vector<int64_t> bucket_ptr; // host, [n_chunks^2 + 1], bucket = chunk(dst) * n_chunks + chunk(src)
     int device = 0;
 };

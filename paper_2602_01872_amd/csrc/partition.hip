@@ -639,17 +639,32 @@ static grp_status halo_partition_impl(const int64_t* src, const int64_t* dst, in
 // ------------------------------------------------------------------ chunks
 constexpr int MAX_CHUNKS = 64;        // n_chunks^2 bucket counters must fit a workgroup's LDS
 
-__device__ __forceinline__ uint32_t chunk_of(uint64_t seed, int64_t v, uint32_t c) {
-    return (uint32_t)(splitmix64_output(seed, (uint64_t)v) % c);
+// Node -> chunk: the random split, or a caller-supplied assignment (any partitioner's output).
+struct ChunkMap {
+    uint64_t seed;
+    uint32_t c;
+    const int32_t* assign;            // [N] chunk ids in [0, c), or null
+};
+__device__ __forceinline__ uint32_t chunk_of(const ChunkMap& m, int64_t v) {
+    return m.assign ? (uint32_t)m.assign[v] : (uint32_t)(splitmix64_output(m.seed, (uint64_t)v) % m.c);
+}
+
+__global__ __launch_bounds__(256) void assignment_check_kernel(const int32_t* __restrict__ assign, int64_t N, int32_t c,
+                                                               unsigned long long* __restrict__ bad) {
+    unsigned long long b = 0;
+    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < N; v += (int64_t)gridDim.x * 256)
+        if (assign[v] < 0 || assign[v] >= c) b++;
+    if (b) atomicAdd(bad, b);
 }
 
 // Pass 1: range check, global in-degrees, size of every (chunk(dst), chunk(src)) bucket.
 __global__ __launch_bounds__(256) void chunk_count_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
-                                                          int64_t E, int64_t N, uint32_t c, uint64_t seed,
+                                                          int64_t E, int64_t N, ChunkMap cm,
                                                           unsigned long long* __restrict__ dg,
                                                           unsigned long long* __restrict__ bucket_count,
                                                           unsigned long long* __restrict__ bad) {
     extern __shared__ unsigned int hist[];            // c*c counters of this workgroup
+    const uint32_t c = cm.c;
     for (int i = threadIdx.x; i < (int)(c * c); i += 256) hist[i] = 0;
     __syncthreads();
     unsigned long long nbad = 0;
@@ -657,7 +672,7 @@ __global__ __launch_bounds__(256) void chunk_count_kernel(const int64_t* __restr
         const int64_t u = src[e], v = dst[e];
         if (u < 0 || v < 0 || u >= N || v >= N) { nbad++; continue; }
         atomicAdd(&dg[v], 1ull);
-        atomicAdd(&hist[chunk_of(seed, v, c) * c + chunk_of(seed, u, c)], 1u);
+        atomicAdd(&hist[chunk_of(cm, v) * c + chunk_of(cm, u)], 1u);
     }
     if (nbad) atomicAdd(bad, nbad);
     __syncthreads();
@@ -668,10 +683,11 @@ __global__ __launch_bounds__(256) void chunk_count_kernel(const int64_t* __restr
 // Pass 2: every workgroup reserves a run in each bucket for the edges it holds, then writes
 // them (the order inside a bucket is arbitrary; partitions are sorted when they are built).
 __global__ __launch_bounds__(256) void chunk_scatter_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
-                                                            int64_t E, uint32_t c, uint64_t seed,
+                                                            int64_t E, ChunkMap cm,
                                                             unsigned long long* __restrict__ cursor,
                                                             int64_t* __restrict__ out_src, int64_t* __restrict__ out_dst) {
     extern __shared__ unsigned int lds_u32[];         // [0, c*c): counts, then run starts (low / high words)
+    const uint32_t c = cm.c;
     unsigned int* cnt = lds_u32;
     unsigned long long* start = (unsigned long long*)(lds_u32 + ((c * c + 1) & ~1u));
     const int64_t per = (E + gridDim.x - 1) / gridDim.x;
@@ -679,7 +695,7 @@ __global__ __launch_bounds__(256) void chunk_scatter_kernel(const int64_t* __res
     for (int i = threadIdx.x; i < (int)(c * c); i += 256) cnt[i] = 0;
     __syncthreads();
     for (int64_t e = lo + threadIdx.x; e < hi; e += 256)
-        atomicAdd(&cnt[chunk_of(seed, dst[e], c) * c + chunk_of(seed, src[e], c)], 1u);
+        atomicAdd(&cnt[chunk_of(cm, dst[e]) * c + chunk_of(cm, src[e])], 1u);
     __syncthreads();
     for (int i = threadIdx.x; i < (int)(c * c); i += 256) {
         start[i] = cnt[i] ? atomicAdd(&cursor[i], (unsigned long long)cnt[i]) : 0ull;
@@ -688,23 +704,23 @@ __global__ __launch_bounds__(256) void chunk_scatter_kernel(const int64_t* __res
     __syncthreads();
     for (int64_t e = lo + threadIdx.x; e < hi; e += 256) {
         const int64_t u = src[e], v = dst[e];
-        const uint32_t b = chunk_of(seed, v, c) * c + chunk_of(seed, u, c);
+        const uint32_t b = chunk_of(cm, v) * c + chunk_of(cm, u);
         const unsigned long long slot = start[b] + atomicAdd(&cnt[b], 1u);
         out_src[slot] = u;
         out_dst[slot] = v;
     }
 }
 
-__global__ __launch_bounds__(256) void pair_flag_kernel(int64_t N, uint32_t c, uint64_t seed, uint32_t base, uint32_t swept,
+__global__ __launch_bounds__(256) void pair_flag_kernel(int64_t N, ChunkMap cm, uint32_t base, uint32_t swept,
                                                         int32_t* __restrict__ flag) {
     const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (v < N) {
-        const uint32_t ch = chunk_of(seed, v, c);
+        const uint32_t ch = chunk_of(cm, v);
         flag[v] = (ch == base || ch == swept) ? 1 : 0;
     }
 }
 
-__global__ __launch_bounds__(256) void pair_nodes_kernel(int64_t N, uint32_t c, uint64_t seed, uint32_t base,
+__global__ __launch_bounds__(256) void pair_nodes_kernel(int64_t N, ChunkMap cm, uint32_t base,
                                                          const int32_t* __restrict__ flag, const int64_t* __restrict__ pos,
                                                          const int64_t* __restrict__ dg_all, int64_t* __restrict__ l2g,
                                                          int64_t* __restrict__ dg, uint8_t* __restrict__ base_mask) {
@@ -713,7 +729,7 @@ __global__ __launch_bounds__(256) void pair_nodes_kernel(int64_t N, uint32_t c, 
         const int64_t i = pos[v];
         l2g[i] = v;
         dg[i] = dg_all[v];
-        base_mask[i] = chunk_of(seed, v, c) == base ? 1 : 0;
+        base_mask[i] = chunk_of(cm, v) == base ? 1 : 0;
     }
 }
 
@@ -727,16 +743,33 @@ __global__ __launch_bounds__(256) void bucket_keys_kernel(const int64_t* __restr
 
 static void free_chunks(grp_chunks_t* h) {
     if (!h) return;
-    for (void* q : {(void*)h->src, (void*)h->dst, (void*)h->d_global_all})
+    for (void* q : {(void*)h->src, (void*)h->dst, (void*)h->d_global_all, (void*)h->assign})
         if (q) (void)hipFree(q);
     delete h;
 }
 
 static grp_status chunks_impl(const int64_t* src, const int64_t* dst, int64_t E, int64_t N, int32_t c, uint64_t seed,
-                              hipStream_t st, grp_chunks_t* h) {
+                              const int32_t* assignment, hipStream_t st, grp_chunks_t* h) {
     const int nb = c * c;
     h->n_chunks = c; h->seed = seed; h->N = N; h->E = E;
     h->bucket_ptr.assign((size_t)nb + 1, 0);
+    if (assignment) {                                  // keep a checked copy: partitions are built from it later
+        GRP_TRY(halloc(&h->assign, N));
+        GRP_HIP(hipMemcpyAsync(h->assign, assignment, (size_t)N * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+        DevBuf bad;
+        GRP_TRY(bad.alloc(sizeof(unsigned long long)));
+        GRP_HIP(hipMemsetAsync(bad.p, 0, sizeof(unsigned long long), st));
+        unsigned long long host_bad = 0;
+        if (N > 0) {
+            hipLaunchKernelGGL(assignment_check_kernel, dim3(grid_for(N)), dim3(256), 0, st, (const int32_t*)h->assign, N, c,
+                               bad.as<unsigned long long>());
+            GRP_LAUNCH_CHECK();
+        }
+        GRP_HIP(hipMemcpyAsync(&host_bad, bad.p, sizeof host_bad, hipMemcpyDeviceToHost, st));
+        GRP_HIP(hipStreamSynchronize(st));
+        if (host_bad) return fail(GRP_ERANGE, "%llu nodes are assigned to a chunk outside [0, %d)", host_bad, c);
+    }
+    const ChunkMap cm{seed, (uint32_t)c, h->assign};
     GRP_TRY(halloc(&h->src, E));
     GRP_TRY(halloc(&h->dst, E));
     GRP_TRY(halloc(&h->d_global_all, N));
@@ -747,7 +780,7 @@ static grp_status chunks_impl(const int64_t* src, const int64_t* dst, int64_t E,
     if (E == 0) { GRP_HIP(hipStreamSynchronize(st)); return GRP_OK; }
     const unsigned grid = grid_for(E) > 2048 ? 2048 : grid_for(E);
     hipLaunchKernelGGL(chunk_count_kernel, dim3(grid), dim3(256), (size_t)nb * sizeof(unsigned int), st, src, dst, E, N,
-                       (uint32_t)c, seed, (unsigned long long*)h->d_global_all, counters.as<unsigned long long>(),
+                       cm, (unsigned long long*)h->d_global_all, counters.as<unsigned long long>(),
                        counters.as<unsigned long long>() + nb);
     GRP_LAUNCH_CHECK();
     std::vector<unsigned long long> host((size_t)nb + 1);
@@ -759,7 +792,7 @@ static grp_status chunks_impl(const int64_t* src, const int64_t* dst, int64_t E,
     for (int b = 0; b < nb; ++b) cur[b] = (unsigned long long)h->bucket_ptr[b];
     GRP_HIP(hipMemcpyAsync(counters.p, cur.data(), cur.size() * sizeof(unsigned long long), hipMemcpyHostToDevice, st));
     const size_t lds = (size_t)((nb + 1) & ~1) * sizeof(unsigned int) + (size_t)nb * sizeof(unsigned long long);
-    hipLaunchKernelGGL(chunk_scatter_kernel, dim3(grid), dim3(256), lds, st, src, dst, E, (uint32_t)c, seed,
+    hipLaunchKernelGGL(chunk_scatter_kernel, dim3(grid), dim3(256), lds, st, src, dst, E, cm,
                        counters.as<unsigned long long>(), h->src, h->dst);
     GRP_LAUNCH_CHECK();
     GRP_HIP(hipStreamSynchronize(st));
@@ -775,7 +808,7 @@ static grp_status pair_partition_impl(const grp_chunks_t* ck, int32_t base, int3
     GRP_TRY(pos.alloc((size_t)N * sizeof(int64_t)));
     int64_t n = 0;
     if (N > 0) {
-        hipLaunchKernelGGL(pair_flag_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, N, (uint32_t)c, ck->seed,
+        hipLaunchKernelGGL(pair_flag_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, N, ChunkMap{ck->seed, (uint32_t)c, ck->assign},
                            (uint32_t)base, (uint32_t)swept, flag.as<int32_t>());
         GRP_LAUNCH_CHECK();
         size_t bytes = 0;
@@ -797,7 +830,7 @@ static grp_status pair_partition_impl(const grp_chunks_t* ck, int32_t base, int3
     GRP_TRY(halloc(&h->d_global_in, n));
     GRP_TRY(halloc(&h->base_mask, n));
     if (N > 0) {
-        hipLaunchKernelGGL(pair_nodes_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, N, (uint32_t)c, ck->seed,
+        hipLaunchKernelGGL(pair_nodes_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, N, ChunkMap{ck->seed, (uint32_t)c, ck->assign},
                            (uint32_t)base, flag.as<int32_t>(), pos.as<int64_t>(), ck->d_global_all, h->l2g, h->d_global_in,
                            h->base_mask);
         GRP_LAUNCH_CHECK();
@@ -844,7 +877,30 @@ extern "C" grp_status grp_chunks_build(const int64_t* src, const int64_t* dst, i
     grp_chunks_t* h = new (std::nothrow) grp_chunks_t();
     if (!h) return fail(GRP_ENOMEM, "grp_chunks_build: host allocation failed");
     (void)hipGetDevice(&h->device);
-    const grp_status s = chunks_impl(src, dst, E, N, n_chunks, seed, (hipStream_t)stream, h);
+    const grp_status s = chunks_impl(src, dst, E, N, n_chunks, seed, nullptr, (hipStream_t)stream, h);
+    if (s != GRP_OK) {
+        free_chunks(h);
+        return s;
+    }
+    *out = h;
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_chunks_build_assigned(const int64_t* src, const int64_t* dst, int64_t E, int64_t N,
+                                                int32_t n_chunks, const int32_t* chunk_of_node, void* stream,
+                                                grp_chunks_t** out) {
+    using namespace grp;
+    if (!out) return fail(GRP_EINVAL, "grp_chunks_build_assigned: out is null");
+    *out = nullptr;
+    if (E < 0 || N < 0) return fail(GRP_EINVAL, "grp_chunks_build_assigned: negative size");
+    if (E > 0 && (!src || !dst)) return fail(GRP_EINVAL, "grp_chunks_build_assigned: null edge arrays");
+    if (N > 0 && !chunk_of_node) return fail(GRP_EINVAL, "grp_chunks_build_assigned: null assignment");
+    if (n_chunks < 1 || n_chunks > MAX_CHUNKS)
+        return fail(GRP_EINVAL, "grp_chunks_build_assigned: n_chunks = %d outside [1, %d]", n_chunks, MAX_CHUNKS);
+    grp_chunks_t* h = new (std::nothrow) grp_chunks_t();
+    if (!h) return fail(GRP_ENOMEM, "grp_chunks_build_assigned: host allocation failed");
+    (void)hipGetDevice(&h->device);
+    const grp_status s = chunks_impl(src, dst, E, N, n_chunks, 0, chunk_of_node, (hipStream_t)stream, h);
     if (s != GRP_OK) {
         free_chunks(h);
         return s;

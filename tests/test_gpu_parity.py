@@ -666,3 +666,38 @@ def test_step_activation_view_matches_oracle_logits(g, arch, dims):
     with pytest.raises(g.GrappaError):
         g.grp_step_activation(part, model, opts, ws[:256], 0)
     part.destroy()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("kind", ["ranges", "skewed", "hash"])
+def test_partition_from_assigned_chunks_bit_exact(g, kind):
+    """Chunks given by the caller (the output of any partitioner): contiguous id ranges, a skewed
+    assignment with an empty chunk, and the library's own random split handed back in."""
+    from oracle import chunks as ochunks
+    _note(f"assigned chunks {kind}")
+    N, E, c = 5000, 90000, 5
+    s, d = synth.rmat_graph(13, E, seed=61, n_nodes=N)
+    if kind == "ranges":
+        assign = (np.arange(N) * c // N).astype(np.int32)
+    elif kind == "skewed":
+        assign = np.minimum(np.arange(N) % 7, 3).astype(np.int32)          # chunk 4 is empty, chunk 3 is large
+    else:
+        assign = ochunks.chunk_of(N, c, 13).astype(np.int32)
+    ck = g.grp_chunks_build_assigned(s.to(DEV), d.to(DEV), N, c, torch.from_numpy(assign).to(DEV))
+    for base, swept in [(0, 1), (3, 3), (4, 2), (2, 4), (1, 3)]:
+        part = g.grp_partition_from_chunks(ck, base, swept)
+        want = ochunks.partition_from_chunks(s.numpy(), d.numpy(), N, c, 0, base, swept, assignment=assign)
+        _assert_partition_equal(part, want)
+        assert np.array_equal(part.base_mask(), want["base_mask"])
+        part.destroy()
+    if kind == "hash":                                    # the same handle as the random split's
+        ck2 = g.grp_chunks_build(s.to(DEV), d.to(DEV), N, c, 13)
+        a, b = g.grp_partition_from_chunks(ck, 1, 2), g.grp_partition_from_chunks(ck2, 1, 2)
+        for k in PART_KEYS:
+            assert np.array_equal(a.array(k), b.array(k)), k
+        a.destroy(); b.destroy(); ck2.destroy()
+    bad = assign.copy()
+    bad[17] = c
+    with pytest.raises(g.GrappaError):
+        g.grp_chunks_build_assigned(s.to(DEV), d.to(DEV), N, c, torch.from_numpy(bad).to(DEV))
+    ck.destroy()

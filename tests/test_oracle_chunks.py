@@ -99,3 +99,31 @@ def test_controller_schedule():
     ctl.observe_step([0.5]); ctl.observe_step([0.5]); assert not ctl.end_epoch()
     ctl.observe_step([0.2]); assert ctl.end_epoch()
     assert ctl.super_epoch == 1 and ctl.pairs() == chunks.sweep_schedule(3)[1]
+
+
+def test_assigned_chunks_generalise_the_random_split():
+    """A caller-supplied assignment equal to the random split gives the same partitions; a contiguous
+    range assignment (what a locality-preserving partitioner returns) is checked by brute force."""
+    rng = np.random.default_rng(4)
+    N, E, c = 90, 400, 3
+    s, d = rng.integers(0, N, E), rng.integers(0, N, E)
+    same = chunks.chunk_of(N, c, 11)
+    for b in range(c):
+        for w in range(c):
+            a = chunks.partition_from_chunks(s, d, N, c, 11, b, w)
+            z = chunks.partition_from_chunks(s, d, N, c, 0, b, w, assignment=same)
+            for k in a:
+                assert np.array_equal(a[k], z[k]), k
+    ranges = (np.arange(N) * c // N).astype(np.int32)
+    part = chunks.partition_from_chunks(s, d, N, c, 0, 2, 0, assignment=ranges)
+    members = [v for v in range(N) if ranges[v] in (0, 2)]
+    assert list(part["l2g"]) == members
+    loc = {v: i for i, v in enumerate(members)}
+    rows = [[] for _ in members]
+    for u, v in zip(s.tolist(), d.tolist()):
+        if u in loc and v in loc:
+            rows[loc[v]].append(loc[u])
+    assert list(part["col"]) == [x for r in rows for x in sorted(r)]
+    assert list(part["base_mask"]) == [1 if ranges[v] == 2 else 0 for v in members]
+    with pytest.raises(ValueError):
+        chunks.partition_from_chunks(s, d, N, c, 0, 0, 1, assignment=np.full(N, 3))
