@@ -50,3 +50,45 @@ def test_param_count_and_invalid_model():
     assert g.grp_param_count(g.model_desc(g.ARCH_SAGE_MEAN, [64, 128, 16])) == 20624
     assert g.grp_param_count(g.model_desc(g.ARCH_GCN, [64, 0, 8])) == -1
     assert g.grp_param_count(g.model_desc(7, [64, 8])) == -1
+
+
+def test_header_is_plain_c_and_its_struct_layouts_are_the_bindings(tmp_path):
+    """grappa.h compiles as C99 on its own, and a C program's view of every struct (size and member
+    offsets) equals the ctypes declarations the Python binding marshals through."""
+    import shutil
+    import subprocess
+    import paper_2602_01872_amd as g
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "layout.c"
+    fields = {
+        "grp_partition_view_t": (g.PartitionView, ["n", "nnz", "l2g", "rowptr", "col", "colptr", "row", "d_local_in",
+                                                   "d_local_out", "d_global_in"]),
+        "grp_partition_weights_t": (g.PartitionWeights, ["csr_w", "csc_w", "w_local_in", "w_global_in"]),
+        "grp_model_desc": (g.ModelDesc, ["arch", "n_layers", "dims", "feat_dtype", "gcn_self_loops"]),
+        "grp_step_opts": (g.StepOpts, ["estimator", "full_graph", "n_seeds", "seeds", "fanouts", "sampler_seed", "batch_id",
+                                       "dropout_rate", "dropout_seed"]),
+        "grp_step_stats": (None, ["loss", "sum_ratio", "R", "S", "nnz_used"]),
+        "grp_optimizer_desc": (g.OptimizerDesc, ["kind", "lr", "beta1", "beta2", "eps"]),
+    }
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "grappa.h"', 'int main(void) {']
+    for name, (_, members) in fields.items():
+        lines.append(f'  printf("{name} %zu", sizeof({name}));')
+        for m in members:
+            lines.append(f'  printf(" %zu", offsetof({name}, {m}));')
+        lines.append('  printf("\\n");')
+    lines += ['  return 0;', '}']
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(root, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.strip().splitlines()
+    seen = {ln.split()[0]: [int(x) for x in ln.split()[1:]] for ln in out}
+    for name, (ctype, members) in fields.items():
+        size, offs = seen[name][0], seen[name][1:]
+        if ctype is None:
+            assert size == g.STATS_BYTES and offs == [0, 8, 16, 24, 32]
+            continue
+        assert size == C.sizeof(ctype), name
+        assert offs == [getattr(ctype, m).offset for m in members], name
