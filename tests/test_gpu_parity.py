@@ -701,3 +701,45 @@ def test_partition_from_assigned_chunks_bit_exact(g, kind):
     with pytest.raises(g.GrappaError):
         g.grp_chunks_build_assigned(s.to(DEV), d.to(DEV), N, c, torch.from_numpy(bad).to(DEV))
     ck.destroy()
+
+
+@pytest.mark.gpu
+def test_calls_run_on_the_stream_they_are_given(g):
+    """Partition build, train step (full-graph and mini-batch), aggregation and optimizer step on a
+    second stream (default priority) give the bits of the default stream."""
+    _note("explicit stream")
+    N, E, dims = 6000, 80000, [32, 48, 8]
+    s, d = synth.uniform_graph(N, E, seed=71)
+    sd, dd = s.to(DEV), d.to(DEV)
+    x, y, theta = make_inputs(N, dims, "sage", 9)
+    xd, yd, td = x.to(DEV), y.to(DEV), theta.to(DEV)
+    model = g.model_desc(g.ARCH_SAGE_MEAN, dims)
+    seeds = torch.arange(0, 256, dtype=torch.int32, device=DEV)
+    torch.cuda.synchronize()
+
+    def run():
+        part = g.grp_partition(sd, dd, N, 1, 3, 0)
+        outs = []
+        for opts in (g.step_opts(estimator=1, full_graph=True),
+                     g.step_opts(full_graph=False, seeds=seeds, fanouts=(4, 4), sampler_seed=2, batch_id=1)):
+            P = g.grp_param_count(model)
+            ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+            grads = torch.zeros(1, (P + 3) // 4 * 4, device=DEV)
+            stats = g.new_stats(1)
+            g.grp_train_step(part, model, opts, xd[:part.n], yd[:part.n], None, td, ws, grads[0], stats)
+            upd = torch.zeros(P, device=DEV)
+            g.grp_aggregate(grads, grads.shape[1], stats, 1, P, g.EST_BATCH_MIN_DIST, upd)
+            th = td.clone()
+            g.grp_optimizer_step(g.optimizer_desc(g.OPT_SGD, lr=0.1), P, 1, th, upd)
+            outs += [grads.clone(), upd, th]
+        torch.cuda.current_stream().synchronize()
+        part.destroy()
+        return outs
+
+    base = run()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        other = run()
+    torch.cuda.synchronize()
+    for a, b in zip(base, other):
+        assert torch.equal(a, b)
