@@ -147,6 +147,56 @@ def run_evidence_workload(args, g, synth, torch, dev):
         print(json.dumps(out), flush=True)
         return
 
+    if wl == "c1-step":
+        # configuration 1 (the correctness configuration): 10,000 nodes, 100,000 uniform edges, K = 4, GCN-2 hidden 64.
+        # ~6 k edges per partition: launch-bound, so one iteration (4 steps + aggregate + optimizer step) is
+        # also timed as a captured HIP graph.
+        N, E, K, dims = 10_000, 100_000, 4, [64, 64, 8]
+        src, dst = synth.uniform_graph(N, E, seed=GRAPH_SEED - 2 + 1, device=dev)
+        parts = [g.grp_partition(src, dst, N, K, PART_SEED, p) for p in range(K)]
+        model = g.model_desc(g.ARCH_GCN, dims)
+        opts = g.step_opts(estimator=g.EST_SHRINKAGE, full_graph=True)
+        xg = synth.normal_matrix(N, dims[0], GRAPH_SEED, device=dev)
+        yg = synth.labels(N, dims[-1], GRAPH_SEED, device=dev)
+        l2gs = [torch.from_numpy(p.array("l2g")).to(dev) for p in parts]
+        xs = [xg[i].contiguous() for i in l2gs]
+        ys = [yg[i].contiguous() for i in l2gs]
+        theta = synth.model_weights("gcn", dims, GRAPH_SEED, device=dev)
+        P = g.grp_param_count(model)
+        ld = (P + 3) // 4 * 4
+        grads = torch.zeros(K, ld, device=dev)
+        stats = g.new_stats(K, device=dev)
+        upd = torch.zeros(P, device=dev)
+        wss = [torch.empty(g.grp_step_workspace_bytes(p, model, opts), dtype=torch.uint8, device=dev) for p in parts]
+        opt = g.optimizer_desc(g.OPT_SGD, lr=1e-6)           # a tiny rate: every iteration does essentially the same work
+
+        def fn():
+            for p in range(K):
+                g.grp_train_step(parts[p], model, opts, xs[p], ys[p], None, theta, wss[p], grads[p],
+                                 stats[p * g.STATS_BYTES:(p + 1) * g.STATS_BYTES])
+            g.grp_aggregate(grads, ld, stats, K, P, g.EST_SHRINKAGE, upd)
+            g.grp_optimizer_step(opt, P, 1, theta, upd)
+        dt = _time_steps(torch, fn, args.warmup, args.steps)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fn()
+        dt_graph = _time_steps(torch, graph.replay, args.warmup, args.steps)
+        kernels = _kernel_table(g, torch, fn, args.steps)
+        nnz = sum(p.nnz for p in parts)
+        out.update(metric="train-step edges/s over the 4 partitions (fwd+bwd), one iteration = 4 steps + aggregate + optimizer",
+                   unit="edges/s", value=nnz / dt_graph, ms_per_step=dt_graph * 1e3, dtype="f32",
+                   config={"workload": f"c1-step: GCN-2 {dims}, {N} nodes / {E} uniform edges, K={K}, local edges {nnz}",
+                           "ms_per_iteration_eager": dt * 1e3, "ms_per_iteration_hip_graph": dt_graph * 1e3, "params": P},
+                   roofline=_roofline(kernels, {}), kernels=kernels)
+        print(json.dumps(out), flush=True)
+        return
+
     if wl in ("c2-gat-step", "c2-dropout-step", "c2-weighted-step"):
         # the headline workload's partition with the attention model in place of GraphSAGE, with
         # GraphSAGE and dropout 0.5 on the hidden layers, or with weighted edges (weighted-mean GraphSAGE)
@@ -286,7 +336,7 @@ def main():
     ap.add_argument("--small", action="store_true", help="scaled-down graph (debugging only; not a valid result)")
     ap.add_argument("--shapes", action="store_true", help="per-launch-shape kernel table on stderr (debugging)")
     ap.add_argument("--workload", default="c2-step",
-                    choices=["c2-step", "c2-gat-step", "c2-dropout-step", "c2-weighted-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "c5-step", "aggregate-stress"],
+                    choices=["c2-step", "c1-step", "c2-gat-step", "c2-dropout-step", "c2-weighted-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "c5-step", "aggregate-stress"],
                     help="c2-step (default) is the headline workload; the others are evidence runs for the other "
                          "configurations (each prints one JSON line of the same form)")
     ap.add_argument("--copy-calibration", action="store_true",

@@ -558,7 +558,7 @@ grp_status gat_step(const grp_partition_t* g, const grp_model_desc* m, const grp
     if (n == 0) {                                       // nothing to train on: zero gradient
         int64_t P = 0;
         for (int l = 0; l < k; ++l) P += (int64_t)m->dims[l] * m->dims[l + 1] + 3 * m->dims[l + 1];
-        GRP_HIP(hipMemsetAsync(grad, 0, (size_t)P * sizeof(float), st));
+        GRP_TRY(launch_fill_zero(grad, (size_t)P * sizeof(float), st));      // a kernel, so the step can be captured in a graph
         return launch_softmax_xent(0, m->dims[k], nullptr, 4, labels, nullptr, mask, o->estimator == GRP_EST_NODE_LEVEL,
                                    g->d_local_in, g->d_global_in, nullptr, p.dZa, 4, p.stats_ws, stats, st);
     }
