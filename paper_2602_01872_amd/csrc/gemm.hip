@@ -723,7 +723,8 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
         // one profiling name per kernel variant, so that the names line up with a kernel trace
         char pname[64];
         snprintf(pname, sizeof pname, "gemm_%s_%s_%s%s", ok ? "nt" : "nn", a.a_bf16 ? "bf16a" : "f32",
-                 ok ? (n_eff > 96 ? "128x128" : n_eff > 64 ? "128x96" : "128x64")
+                 ok ? (a.M > 0 && n_eff > 32 && cdiv(a.M, 128) * cdiv(n_eff, n_eff > 96 ? 128 : n_eff > 64 ? 96 : 64) < 384
+                           ? "64x64" : n_eff > 96 ? "128x128" : n_eff > 64 ? "128x96" : "128x64")
                     : (n_eff > 64 ? "128x128" : n_eff > 32 ? "128x64" : "128x32"),
                  short_k ? "_k16" : "_k32");
         ProfScope ps(pname, st, nn_flops, nn_bytes);
@@ -732,9 +733,13 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
             GRP_LAUNCH_CHECK();
             return GRP_OK;
         }
-        const int64_t slabs = round_up(cdiv(a.M, 128), NXCD);
         const bool rowlimit = a.a_rows != nullptr || (a.a_valid_rows > 0 && a.a_valid_rows < a.M);
-        const int tile_n = n_eff > 96 ? 128 : n_eff > 64 ? 96 : 64;
+        int tile_n = n_eff > 96 ? 128 : n_eff > 64 ? 96 : 64;
+        // A product whose 128-row tiles would leave half the chip idle (mini-batch blocks) is cut into
+        // 64 x 64 tiles instead: four times the workgroups, each a quarter of the work.
+        const bool small_tiles = n_eff > 32 && cdiv(a.M, 128) * cdiv(n_eff, tile_n) < 384;
+        if (small_tiles) tile_n = 64;
+        const int64_t slabs = round_up(cdiv(a.M, small_tiles ? 64 : 128), NXCD);
         const unsigned blocks = (unsigned)(slabs * cdiv(n_eff, tile_n));
 #define GRP_NT_LAUNCH2(AT, WM_, WN_, TM_, TN_, RL)                                                                        \
     do {                                                                                                                  \
@@ -746,7 +751,9 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
         if (rowlimit) GRP_NT_LAUNCH2(AT, WM_, WN_, TM_, TN_, true);                                                 \
         else GRP_NT_LAUNCH2(AT, WM_, WN_, TM_, TN_, false);                                                         \
     } while (0)
-        if (n_eff > 96) {
+        if (small_tiles) {
+            if (a.a_bf16) GRP_NT_LAUNCH(__hip_bfloat16, 2, 2, 1, 1); else GRP_NT_LAUNCH(float, 2, 2, 1, 1);
+        } else if (n_eff > 96) {
             if (a.a_bf16) GRP_NT_LAUNCH(__hip_bfloat16, 2, 2, 2, 2); else GRP_NT_LAUNCH(float, 2, 2, 2, 2);
         } else if (n_eff > 64) {
             if (a.a_bf16) GRP_NT_LAUNCH(__hip_bfloat16, 4, 1, 1, 3); else GRP_NT_LAUNCH(float, 4, 1, 1, 3);
@@ -771,7 +778,7 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------------------- TN
-constexpr int TN_ROWS_PER_SPLIT_MIN = 512;    // node rows per split (multiple of BK)
+constexpr int TN_ROWS_PER_SPLIT_MIN = 128;    // node rows per split (multiple of BK): a lone workgroup spends ~3 us per 32 rows
 constexpr int TN_MAX_SPLITS = 256;
 constexpr int TN_TARGET_WGS = 768;            // 256 CUs x 3 resident workgroups: one full round
 
