@@ -279,11 +279,14 @@ grp_status grp_step_workspace_bytes(const grp_partition_t* part, const grp_model
  *
  * Mini-batch mode (opts->full_graph = 0, GraphSAGE only): isolated k-hop sampling inside the
  * partition, then the same layers on the sampled blocks.  Sampling rule (the paper fixes
- * none): per destination node all local in-edges if there are at most fanouts[l], else the
- * fanouts[l] in-edges with the smallest key
- *   key = M(M(M(M(M(sampler_seed) ^ batch_id) ^ l) ^ global_id(v)) ^ j),
- *   M(x) = SplitMix64 finaliser of x + 0x9E3779B97F4A7C15, j = position in v's CSR row,
- * ties by j; layers are built from the seeds inwards (the seeds draw fanouts[k-1]); the mean
+ * none): per destination node v with d local in-edges all of them if d <= f = fanouts[l], else a
+ * uniformly random f-subset of the positions 0..d-1 of v's CSR row, grown one element at a time:
+ *   for t = 0..f-1:  top = d - f + t,  r = floor(u_t * (top + 1) / 2^64); the subset gains r if
+ *   it does not hold r yet and top otherwise;
+ *   u_t = M(M(M(M(M(sampler_seed) ^ batch_id) ^ l) ^ global_id(v)) ^ t),
+ *   M(x) = SplitMix64 finaliser of x + 0x9E3779B97F4A7C15;
+ * the chosen edges keep their row order; layers are built from the seeds inwards (the seeds draw
+ * fanouts[k-1]); the mean
  * of a layer divides by the number of sampled neighbours.  Fanouts must lie in [1, 64]; seeds
  * must be distinct.  This mode synchronises the stream once per layer above the input layer
  * (the sampled block sizes are needed on the host); the workspace is sized from the seeds and

@@ -5,19 +5,22 @@ Training" paragraph and the first step of each worker in the phase-parallel algo
 but fixes neither the sampler nor its random numbers.  Reading taken here:
 
   * uniform sampling without replacement per destination node: a node with at most ``f``
-    local in-edges keeps them all; otherwise it keeps the ``f`` in-edges with the smallest
-    64-bit key, ties broken by position;
-  * key(e) = M(M(M(M(M(sampler_seed) ^ batch_id) ^ layer) ^ global_id(v)) ^ j) where ``j``
-    is the edge's position inside v's canonical CSR row and M(x) is the SplitMix64
-    finaliser applied to ``x + GAMMA`` (wrapping 64-bit);
+    local in-edges keeps them all; otherwise it keeps a uniformly random ``f``-subset of the
+    ``d`` positions of its canonical CSR row, drawn by the classical subset-growing scheme
+    (Floyd): for t = 0..f-1 let top = d - f + t and draw r uniformly from [0, top]; the
+    subset gains r if it does not hold r yet and top otherwise.  Every f-subset comes out
+    with the same probability, and the work per node is O(f) whatever its degree;
+  * the t-th draw of node v is r = floor(u * (top + 1) / 2^64) with the 64-bit integer
+    u = M(M(M(M(M(sampler_seed) ^ batch_id) ^ layer) ^ global_id(v)) ^ t), where M(x) is the
+    SplitMix64 finaliser applied to ``x + GAMMA`` (wrapping 64-bit);
   * layers are built from the seed side inwards; ``fanouts[l]`` belongs to layer ``l``
     (layer 0 = input side), so the seeds draw ``fanouts[k-1]`` neighbours;
   * a block's source list is its destination list (same order) followed by the newly
     reached nodes in ascending local id; a block's edges are ordered by destination and,
-    inside a destination, by ascending ``j``.
+    inside a destination, by ascending position.
 
-Because keys depend only on (seed, batch, layer, node, position) the result is
-independent of evaluation order.
+Because the draws depend only on (seed, batch, layer, node, t) the result is independent of
+evaluation order.
 """
 from __future__ import annotations
 
@@ -36,12 +39,40 @@ def _M(x: np.ndarray) -> np.ndarray:
     return z
 
 
-def edge_keys(sampler_seed: int, batch_id: int, layer: int, gid, j) -> np.ndarray:
+def draw_bits(sampler_seed: int, batch_id: int, layer: int, gid, t) -> np.ndarray:
+    """The 64 random bits behind draw ``t`` of the node with global id ``gid``."""
     h = _M(np.uint64(sampler_seed & 0xFFFFFFFFFFFFFFFF))
     h = _M(h ^ np.uint64(batch_id))
     h = _M(h ^ np.uint64(layer))
     h = _M(h ^ np.asarray(gid, dtype=np.uint64))
-    return _M(h ^ np.asarray(j, dtype=np.uint64))
+    return _M(h ^ np.asarray(t, dtype=np.uint64))
+
+
+def scale_draw(u, span) -> np.ndarray:
+    """floor(u * span / 2^64) for 64-bit u and span: the uniform draw from [0, span)."""
+    u = np.asarray(u, dtype=np.uint64)
+    span = np.asarray(span, dtype=np.uint64)
+    lo32 = np.uint64(0xFFFFFFFF)
+    s32 = np.uint64(32)
+    with np.errstate(over="ignore"):
+        u0, u1 = u & lo32, u >> s32
+        v0, v1 = span & lo32, span >> s32
+        mid = (u0 * v0 >> s32) + (u1 * v0 & lo32) + (u0 * v1 & lo32)
+        return u1 * v1 + (u1 * v0 >> s32) + (u0 * v1 >> s32) + (mid >> s32)
+
+
+def grow_subset(d: int, draws) -> list:
+    """The subset-growing scheme for one row: ``draws[t]`` is the value drawn from
+    [0, d - f + t]; returns the f = len(draws) chosen positions in ascending order."""
+    f = len(draws)
+    chosen = []
+    for t in range(f):
+        top = d - f + t
+        r = int(draws[t])
+        if not 0 <= r <= top:
+            raise ValueError("draw outside its range")
+        chosen.append(top if r in chosen else r)
+    return sorted(chosen)
 
 
 def sample_layer(part: dict, dst_nodes, fanout: int, sampler_seed: int, batch_id: int, layer: int):
@@ -49,26 +80,21 @@ def sample_layer(part: dict, dst_nodes, fanout: int, sampler_seed: int, batch_id
     ``edst_pos[e]`` indexes ``dst_nodes``; edges ordered by destination then position."""
     rowptr, col, l2g = part["rowptr"], part["col"], part["l2g"]
     dst_nodes = np.asarray(dst_nodes, dtype=np.int64)
-    beg = rowptr[dst_nodes]
-    deg = rowptr[dst_nodes + 1] - beg
-    tot = int(deg.sum())
-    owner_pos = np.repeat(np.arange(dst_nodes.size, dtype=np.int64), deg)
-    first = np.repeat(np.cumsum(deg) - deg, deg)
-    j = np.arange(tot, dtype=np.int64) - first                 # position inside the row
-    epos = np.repeat(beg, deg) + j
-    big = np.repeat(deg > fanout, deg)
-    keep = ~big
-    if big.any():
-        bi = np.flatnonzero(big)
-        keys = edge_keys(sampler_seed, batch_id, layer, l2g[dst_nodes[owner_pos[bi]]], j[bi])
-        order = np.lexsort((j[bi], keys, owner_pos[bi]))       # by row, then key, then position
-        sorted_rows = owner_pos[bi][order]
-        start = np.r_[0, np.flatnonzero(np.diff(sorted_rows)) + 1]
-        run_start = np.repeat(start, np.diff(np.r_[start, sorted_rows.size]))
-        rank = np.arange(sorted_rows.size) - run_start
-        keep[bi[order[rank < fanout]]] = True
-    sel = np.flatnonzero(keep)                                  # already (row, position) ordered
-    return owner_pos[sel], col[epos[sel]].astype(np.int64)
+    edst, epos = [], []
+    steps = np.arange(fanout, dtype=np.int64)
+    for i, v in enumerate(dst_nodes.tolist()):
+        b = int(rowptr[v])
+        d = int(rowptr[v + 1]) - b
+        if d <= fanout:
+            pos = range(d)
+        else:
+            bits = draw_bits(sampler_seed, batch_id, layer, l2g[v], steps)
+            pos = grow_subset(d, scale_draw(bits, d - fanout + steps + 1))
+        edst.extend([i] * len(pos))
+        epos.extend(b + j for j in pos)
+    edst = np.asarray(edst, dtype=np.int64)
+    epos = np.asarray(epos, dtype=np.int64)
+    return edst, col[epos].astype(np.int64)
 
 
 def sample_blocks(part: dict, seeds, fanouts, sampler_seed: int, batch_id: int):

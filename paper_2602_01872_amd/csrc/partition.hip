@@ -1153,9 +1153,27 @@ grp_status exclusive_scan_i32(void* temp, size_t temp_bytes, const int32_t* in, 
     return GRP_OK;
 }
 
+// Same result as csr_from_keys_kernel for matrices with many empty rows (a sampled block has more
+// rows than most of them have entries): every row pointer is found by binary search instead of by
+// the thread at the end of the previous row walking over the gap.
+__global__ __launch_bounds__(256) void csr_from_keys_search_kernel(const uint64_t* __restrict__ keys, int64_t nnz, int64_t n,
+                                                                   int64_t* __restrict__ ptr, int32_t* __restrict__ idx) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < nnz) idx[i] = (int32_t)(keys[i] & 0xFFFFFFFFull);
+    if (i <= n) {
+        int64_t lo = 0, hi = nnz;                        // first position whose row is >= i
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            if ((int64_t)(keys[mid] >> 32) < i) lo = mid + 1; else hi = mid;
+        }
+        ptr[i] = lo;
+    }
+}
+
 grp_status launch_csr_from_sorted_keys(const uint64_t* keys, int64_t nnz, int64_t n, int64_t* ptr, int32_t* idx,
                                        hipStream_t st) {
-    hipLaunchKernelGGL(csr_from_keys_kernel, dim3(grid_for(nnz + 1)), dim3(256), 0, st, keys, nnz, n, ptr, idx);
+    const int64_t work = nnz > n + 1 ? nnz : n + 1;
+    hipLaunchKernelGGL(csr_from_keys_search_kernel, dim3((unsigned)cdiv(work, 256)), dim3(256), 0, st, keys, nnz, n, ptr, idx);
     GRP_LAUNCH_CHECK();
     return GRP_OK;
 }

@@ -394,6 +394,7 @@ def test_aggregate_invariants(g):
     ([32, 48, 6], (4, 3), False, 200),
     ([128, 256, 256, 172], (15, 10, 5), True, 1024),
     ([40, 24, 24, 5], (6, 5, 64), False, 333),
+    ([24, 32, 32, 4], (7, 64, 1), False, 97),          # run on the graph with star hubs (below); fanouts 64 and 1 are the limits
 ])
 def test_minibatch_train_step_matches_oracle(g, dims, fanouts, bf16, n_seeds):
     """Isolated k-hop sampling + SAGE step on the sampled blocks: the sampled structure is
@@ -402,16 +403,24 @@ def test_minibatch_train_step_matches_oracle(g, dims, fanouts, bf16, n_seeds):
     scale, E, K = 14, 600000, 2
     N = 1 << scale
     s, d = synth.rmat_graph(scale, E, seed=2602018723, device=DEV)
+    stars = n_seeds == 97
+    if stars:       # eight nodes with 50 000 extra in-edges each: rows far longer than anything R-MAT gives at this size
+        es, _ = synth.uniform_graph(N, 400000, seed=41, device=DEV)
+        ed = 100 + torch.arange(400000, device=DEV) % 8
+        s, d = torch.cat([s, es]), torch.cat([d, ed])
     part = g.grp_partition(s, d, N, K, 1, 0)
     op = ograph.partition(s.cpu().numpy(), d.cpu().numpy(), N, K, 1, 0)
     n = part.n
     dl = op["d_local_in"]
-    assert dl.max() > 4096                                     # a hub row: the threshold path of the sampler, scanned by a whole workgroup
+    assert dl.max() > 4096                                     # a hub row among the seeds
+    if stars:
+        assert np.count_nonzero(dl > 20000) >= 2
     # seeds: the hub, an isolated node, and a seeded spread of others (distinct)
     order = np.argsort(synth.stream_bits(5, 77, torch.arange(n)).numpy(), kind="stable")
-    hub, iso = int(dl.argmax()), int(np.flatnonzero(dl == 0)[0])
-    rest = [int(v) for v in order if v not in (hub, iso)][:n_seeds - 2]
-    seeds = np.array([hub, iso] + rest, dtype=np.int32)
+    hubs = [int(v) for v in np.flatnonzero(dl > 20000)] if stars else [int(dl.argmax())]
+    iso = int(np.flatnonzero(dl == 0)[0])
+    rest = [int(v) for v in order if v not in hubs and v != iso][:n_seeds - 1 - len(hubs)]
+    seeds = np.array(hubs + [iso] + rest, dtype=np.int32)
     x, y, theta = make_inputs(n, dims, "sage", 21, bf16=bf16)
     model = g.model_desc(g.ARCH_SAGE_MEAN, dims, g.DTYPE_BF16 if bf16 else g.DTYPE_FP32)
     for est, batch in ((0, 0), (1, 3)):

@@ -1,7 +1,13 @@
-"""Pins for oracle.sampling: structural invariants of the sampled blocks, a brute-force
-per-row selection written with Python loops, reproducibility, near-uniform selection
-frequencies, and the reduction to the full-graph step when the fanout covers every row."""
+"""Pins for oracle.sampling: the subset-growing scheme enumerated over every possible sequence of
+draws (each subset equally often: exact uniformity), a hand-worked example, the draw scaling against
+exact integer arithmetic, a per-row selection redone with Python integers, structural invariants of
+the sampled blocks, reproducibility, selection frequencies of single edges and of pairs, and the
+reduction to the full-graph step when the fanout covers every row."""
+import itertools
+import math
+
 import numpy as np
+import pytest
 
 import synth
 from oracle import coverage as cov
@@ -17,7 +23,48 @@ def _part(N=300, E=6000, K=2, scale=None):
     return graph.partition(s.numpy(), d.numpy(), N, K, 4, 0)
 
 
-def test_layer_sample_matches_brute_force_selection():
+@pytest.mark.parametrize("d,f", [(5, 2), (6, 3), (7, 1), (4, 3), (6, 5), (8, 4)])
+def test_subset_growing_is_exactly_uniform_by_enumeration(d, f):
+    # all (d-f+1)(d-f+2)...d sequences of draws are equally likely; they must hit each of the
+    # C(d, f) subsets equally often
+    ranges = [range(d - f + t + 1) for t in range(f)]
+    seen = {}
+    for draws in itertools.product(*ranges):
+        sub = tuple(sampling.grow_subset(d, draws))
+        assert len(set(sub)) == f and all(0 <= j < d for j in sub) and list(sub) == sorted(sub)
+        seen[sub] = seen.get(sub, 0) + 1
+    assert len(seen) == math.comb(d, f)
+    assert set(seen.values()) == {math.prod(len(r) for r in ranges) // math.comb(d, f)}
+
+
+def test_subset_growing_worked_example():
+    # d = 10, f = 3: tops 7, 8, 9.  Draw 2 -> {2}; draw 2 again -> taken, so 8; draw 9 -> 9.
+    assert sampling.grow_subset(10, [2, 2, 9]) == [2, 8, 9]
+    assert sampling.grow_subset(10, [7, 8, 9]) == [7, 8, 9]
+    assert sampling.grow_subset(3, [0, 0]) == [0, 2]
+    with pytest.raises(ValueError):
+        sampling.grow_subset(10, [8, 0, 0])                   # first draw must lie in [0, 7]
+
+
+def test_scale_draw_is_the_exact_integer_quotient():
+    rng = np.random.default_rng(5)
+    u = rng.integers(0, 2 ** 64, 4000, dtype=np.uint64)
+    span = rng.integers(1, 2 ** 64, 4000, dtype=np.uint64)
+    span[:2000] = rng.integers(1, 2 ** 31, 2000)
+    u[:4] = [0, 2 ** 64 - 1, 2 ** 63, 1]
+    got = sampling.scale_draw(u, span)
+    for g, a, b in zip(got.tolist(), u.tolist(), span.tolist()):
+        assert g == (a * b) >> 64 and 0 <= g < b
+
+
+def _mix_int(x):
+    z = (x + 0x9E3779B97F4A7C15) & (2 ** 64 - 1)
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & (2 ** 64 - 1)
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & (2 ** 64 - 1)
+    return z ^ (z >> 31)
+
+
+def test_layer_sample_matches_selection_redone_with_python_integers():
     part = _part(scale=8, E=5000)
     dst = np.array([5, 0, 17, 3, 40, 41])
     f = 4
@@ -25,17 +72,25 @@ def test_layer_sample_matches_brute_force_selection():
     got = [[] for _ in dst]
     for e, u in zip(edst.tolist(), esrc.tolist()):
         got[e].append(u)
+    some_sampled = False
     for i, v in enumerate(dst.tolist()):
         b, e = int(part["rowptr"][v]), int(part["rowptr"][v + 1])
         row = part["col"][b:e].tolist()
-        if len(row) <= f:
+        d = len(row)
+        if d <= f:
             want = row
         else:
-            keys = [int(sampling.edge_keys(7, 2, 1, part["l2g"][v], j)) for j in range(len(row))]
-            pick = sorted(sorted(range(len(row)), key=lambda j: (keys[j], j))[:f])
-            want = [row[j] for j in pick]
+            some_sampled = True
+            h = _mix_int(_mix_int(_mix_int(_mix_int(7) ^ 2) ^ 1) ^ int(part["l2g"][v]))
+            chosen = set()
+            for t in range(f):
+                top = d - f + t
+                r = (_mix_int(h ^ t) * (top + 1)) >> 64
+                chosen.add(top if r in chosen else r)
+            want = [row[j] for j in sorted(chosen)]
         assert got[i] == want
-        assert len(got[i]) == min(f, len(row))
+        assert len(got[i]) == min(f, d)
+    assert some_sampled
 
 
 def test_blocks_are_well_formed_and_reproducible():
@@ -70,19 +125,25 @@ def test_blocks_are_well_formed_and_reproducible():
 
 
 def test_selection_is_close_to_uniform():
-    # one hub row with 40 distinct in-edges, fanout 10: each edge kept ~ 1/4 of the batches
+    # one hub row with 40 distinct in-edges, fanout 10: each edge kept ~ 1/4 of the batches and each
+    # pair of edges together ~ (10 * 9) / (40 * 39) of them
     src = np.arange(1, 41)
     dst = np.zeros(40, dtype=np.int64)
     part = graph.local_graph_from_edges(src, dst, 41)
     counts = np.zeros(41)
-    B = 2000
+    pairs = np.zeros((41, 41))
+    B = 4000
     for b in range(B):
         _, esrc = sampling.sample_layer(part, np.array([0]), 10, 3, b, 0)
         assert esrc.size == 10 and len(set(esrc.tolist())) == 10
         counts[esrc] += 1
+        pairs[np.ix_(esrc, esrc)] += 1
     freq = counts[1:] / B
     sigma = (0.25 * 0.75 / B) ** 0.5
     assert np.abs(freq - 0.25).max() < 5 * sigma
+    pp = 90.0 / 1560.0
+    pf = pairs[1:, 1:][np.triu_indices(40, 1)] / B
+    assert np.abs(pf - pp).max() < 5 * (pp * (1 - pp) / B) ** 0.5
 
 
 def test_full_fanout_minibatch_equals_full_graph_loss_on_seeds():
