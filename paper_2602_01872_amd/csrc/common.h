@@ -321,10 +321,17 @@ grp_status exclusive_scan_i32(void* temp, size_t temp_bytes, const int32_t* in, 
 // From sorted keys (row << 32 | col): idx[i] = low half, ptr[r] = first position with high half >= r.
 grp_status launch_csr_from_sorted_keys(const uint64_t* keys, int64_t nnz, int64_t n, int64_t* ptr, int32_t* idx,
                                        hipStream_t st);
-// Host pass over a device pointer array: the split schedule of its long rows, written into
-// caller-provided device arrays (capacities in rows / chunks).  Synchronises the stream.
-grp_status build_long_rows_into(const int64_t* ptr_dev, int64_t n, LongRows* out, int64_t cap_long,
-                                int64_t cap_chunks, hipStream_t st);
+// The split schedule of the long rows of a device pointer array, written into caller-provided device
+// arrays without a host pass: out->n_long / n_chunks are set to the capacities (the launches cover
+// them) and the slots beyond the real counts are filled so that they do nothing (row -1, empty
+// chunks).  Capacities must cover every possible schedule: cap_long >= nnz / SPMM_LONG_ROW,
+// cap_chunks >= nnz / SPMM_CHUNK + cap_long.  pack / scanned: [n + 1] int64 scratch.
+grp_status build_long_rows_device(const int64_t* ptr_dev, int64_t n, LongRows* out, int64_t cap_long, int64_t cap_chunks,
+                                  int64_t* pack, int64_t* scanned, void* scan_tmp, size_t scan_bytes, hipStream_t st);
+
+// 64 bytes of pinned host memory the device can write, one per host thread, kept until the process
+// ends (sizes a kernel reports to the host; read after synchronising the stream).  Null on failure.
+int64_t* host_mailbox();
 
 // ---------------------------------------------------------------- blocks and sampling (sampler.hip)
 // One bipartite message-passing layer.  Rows of `ptr/idx` are the layer's outputs

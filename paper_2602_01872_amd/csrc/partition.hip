@@ -1178,34 +1178,67 @@ grp_status launch_csr_from_sorted_keys(const uint64_t* keys, int64_t nnz, int64_
     return GRP_OK;
 }
 
-grp_status build_long_rows_into(const int64_t* ptr_dev, int64_t n, LongRows* out, int64_t cap_long, int64_t cap_chunks,
-                                hipStream_t st) {
-    std::vector<int64_t> ptr((size_t)n + 1);
-    GRP_HIP(hipMemcpyAsync(ptr.data(), ptr_dev, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
-    GRP_HIP(hipStreamSynchronize(st));
-    std::vector<int32_t> rows, first;
-    std::vector<int64_t> cb, ce;
-    for (int64_t v = 0; v < n; ++v) {
-        const int64_t b = ptr[v], e = ptr[v + 1];
-        if (e - b <= SPMM_LONG_ROW) continue;
-        rows.push_back((int32_t)v);
-        first.push_back((int32_t)cb.size());
-        for (int64_t c = b; c < e; c += SPMM_CHUNK) {
-            cb.push_back(c);
-            ce.push_back(c + SPMM_CHUNK < e ? c + SPMM_CHUNK : e);
+// ---- split schedule of the long rows, built on the device (no host pass, no synchronisation).
+// pack[r] = (1 << 32 | chunks of row r) for a long row, 0 otherwise; its exclusive prefix sum gives every
+// long row its slot (high half) and first chunk (low half), in ascending row order.
+__global__ __launch_bounds__(256) void long_rows_pack_kernel(const int64_t* __restrict__ ptr, int64_t n,
+                                                             int64_t* __restrict__ pack /*[n+1]*/) {
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r > n) return;
+    int64_t v = 0;
+    if (r < n) {
+        const int64_t len = ptr[r + 1] - ptr[r];
+        if (len > SPMM_LONG_ROW) v = ((int64_t)1 << 32) | ((len + SPMM_CHUNK - 1) / SPMM_CHUNK);
+    }
+    pack[r] = v;
+}
+
+// Slots past the real counts are made harmless: row -1 (skipped by the combine pass), empty chunks.
+__global__ __launch_bounds__(256) void long_rows_emit_kernel(const int64_t* __restrict__ ptr, int64_t n,
+                                                             const int64_t* __restrict__ scanned /*[n+1]*/,
+                                                             int64_t cap_long, int64_t cap_chunks,
+                                                             int32_t* __restrict__ long_row, int32_t* __restrict__ long_first,
+                                                             int64_t* __restrict__ chunk_begin, int64_t* __restrict__ chunk_end) {
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t total = scanned[n];
+    const int64_t n_long = total >> 32, n_chunks = total & 0xFFFFFFFFll;
+    if (r < n) {
+        const int64_t b = ptr[r], e = ptr[r + 1];
+        if (e - b > SPMM_LONG_ROW) {
+            const int64_t slot = scanned[r] >> 32;
+            int64_t c = scanned[r] & 0xFFFFFFFFll;
+            if (slot < cap_long) {
+                long_row[slot] = (int32_t)r;
+                long_first[slot] = (int32_t)c;
+            }
+            for (int64_t at = b; at < e; at += SPMM_CHUNK, ++c) {
+                if (c >= cap_chunks) break;
+                chunk_begin[c] = at;
+                chunk_end[c] = at + SPMM_CHUNK < e ? at + SPMM_CHUNK : e;
+            }
         }
     }
-    first.push_back((int32_t)cb.size());
-    if ((int64_t)rows.size() > cap_long || (int64_t)cb.size() > cap_chunks)
-        return fail(GRP_EWORKSPACE, "long-row schedule (%zu rows, %zu chunks) exceeds its buffers", rows.size(), cb.size());
-    out->n_long = (int32_t)rows.size();
-    out->n_chunks = (int32_t)cb.size();
-    if (out->n_long == 0) return GRP_OK;
-    GRP_HIP(hipMemcpyAsync(out->long_row, rows.data(), rows.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    GRP_HIP(hipMemcpyAsync(out->long_first, first.data(), first.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    GRP_HIP(hipMemcpyAsync(out->chunk_begin, cb.data(), cb.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
-    GRP_HIP(hipMemcpyAsync(out->chunk_end, ce.data(), ce.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
-    GRP_HIP(hipStreamSynchronize(st));     // the host vectors go out of scope
+    if (r >= n_long && r <= cap_long) {
+        if (r < cap_long) long_row[r] = -1;
+        long_first[r] = (int32_t)(n_chunks < cap_chunks ? n_chunks : cap_chunks);
+    }
+    if (r >= n_chunks && r < cap_chunks) { chunk_begin[r] = 0; chunk_end[r] = 0; }
+}
+
+grp_status build_long_rows_device(const int64_t* ptr_dev, int64_t n, LongRows* out, int64_t cap_long, int64_t cap_chunks,
+                                  int64_t* pack, int64_t* scanned, void* scan_tmp, size_t scan_bytes, hipStream_t st) {
+    hipLaunchKernelGGL(long_rows_pack_kernel, dim3((unsigned)cdiv(n + 1, 256)), dim3(256), 0, st, ptr_dev, n, pack);
+    GRP_LAUNCH_CHECK();
+    GRP_TRY(exclusive_scan_i64(scan_tmp, scan_bytes, pack, scanned, n + 1, st));
+    int64_t work = n;
+    if (cap_long + 1 > work) work = cap_long + 1;
+    if (cap_chunks > work) work = cap_chunks;
+    hipLaunchKernelGGL(long_rows_emit_kernel, dim3((unsigned)cdiv(work, 256)), dim3(256), 0, st, ptr_dev, n,
+                       (const int64_t*)scanned, cap_long, cap_chunks, out->long_row, out->long_first, out->chunk_begin,
+                       out->chunk_end);
+    GRP_LAUNCH_CHECK();
+    out->n_long = (int32_t)cap_long;          // upper bounds: the launches cover them, the device arrays say which are real
+    out->n_chunks = (int32_t)cap_chunks;
     return GRP_OK;
 }
 

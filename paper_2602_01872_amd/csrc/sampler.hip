@@ -133,7 +133,12 @@ __global__ __launch_bounds__(256) void assign_new_kernel(int64_t n_words, uint32
 __global__ __launch_bounds__(256) void relabel_kernel(const int64_t* __restrict__ ptr, int64_t n_dst,
                                                       const int32_t* __restrict__ idx_local,
                                                       const int32_t* __restrict__ mark, int32_t* __restrict__ idx_blk,
-                                                      uint64_t* __restrict__ keyT) {
+                                                      uint64_t* __restrict__ keyT, const int32_t* __restrict__ n_new,
+                                                      int64_t* __restrict__ mailbox /*pinned host memory*/) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {           // the block's sizes, for the host
+        mailbox[0] = ptr[n_dst];
+        mailbox[1] = *n_new;
+    }
     const int64_t i = (int64_t)blockIdx.x * 4 + threadIdx.x / 64;
     if (i >= n_dst) return;
     const int lane = threadIdx.x & 63;
@@ -184,6 +189,7 @@ struct SamplerLayerBufs {
     float* inv_in;       // [dst]
     int32_t *lr_row, *lr_first;    // long rows of the transposed block
     int64_t *lr_cb, *lr_ce;
+    int64_t *lr_pack, *lr_scan;    // [src+1] scratch of the schedule's construction
     int64_t lr_cap_long, lr_cap_chunks;
 };
 
@@ -223,10 +229,13 @@ static SamplerBufs carve_sampler(int64_t n, const SamplerBounds& b, int k, void*
             L.lr_first = bump.take<int32_t>((size_t)L.lr_cap_long + 1);
             L.lr_cb = bump.take<int64_t>((size_t)L.lr_cap_chunks);
             L.lr_ce = bump.take<int64_t>((size_t)L.lr_cap_chunks);
+            L.lr_pack = bump.take<int64_t>((size_t)b.src[l] + 1);
+            L.lr_scan = bump.take<int64_t>((size_t)b.src[l] + 1);
             if (b.nnz[l] > max_nnz) max_nnz = b.nnz[l];
         } else {
             L.idx_blk = nullptr; L.src_nodes = nullptr; L.keys = L.keys_sorted = nullptr;
             L.ptrT = nullptr; L.idxT = nullptr; L.lr_row = L.lr_first = nullptr; L.lr_cb = L.lr_ce = nullptr;
+            L.lr_pack = L.lr_scan = nullptr;
             L.lr_cap_long = L.lr_cap_chunks = 0;
         }
     }
@@ -265,6 +274,8 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
         GRP_TRY(launch_fill_zero(s.mark, (size_t)n * sizeof(int32_t), st));
         GRP_TRY(launch_fill_zero(s.bits, (size_t)s.n_words * sizeof(uint32_t), st));
     }
+    int64_t* const mailbox = k > 1 ? host_mailbox() : nullptr;
+    if (k > 1 && !mailbox) return fail(GRP_EHIP, "mini-batch: no pinned host memory for the block sizes");
     const uint64_t h1 = mixM(mixM(o->sampler_seed) ^ o->batch_id);
     const int32_t* dst_nodes = o->seeds;
     int64_t n_dst = o->n_seeds;
@@ -314,15 +325,16 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
         hipLaunchKernelGGL(assign_new_kernel, dim3(blocks_for(s.n_words)), dim3(256), 0, st, s.n_words, s.bits,
                            (const int32_t*)s.wpos, n_dst, s.mark, L.src_nodes);
         GRP_LAUNCH_CHECK();
+        mailbox[0] = mailbox[1] = -1;
         hipLaunchKernelGGL(relabel_kernel, dim3((unsigned)cdiv(n_dst, 4)), dim3(256), 0, st, (const int64_t*)L.ptr, n_dst,
-                           (const int32_t*)L.idx_local, (const int32_t*)s.mark, L.idx_blk, L.keys);
+                           (const int32_t*)L.idx_local, (const int32_t*)s.mark, L.idx_blk, L.keys,
+                           (const int32_t*)(s.wpos + s.n_words), mailbox);
         GRP_LAUNCH_CHECK();
-        int64_t host_nnz = 0;
-        int32_t host_new = 0;
-        GRP_HIP(hipMemcpyAsync(&host_nnz, L.ptr + n_dst, sizeof(int64_t), hipMemcpyDeviceToHost, st));
-        GRP_HIP(hipMemcpyAsync(&host_new, s.wpos + s.n_words, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-        GRP_HIP(hipStreamSynchronize(st));
+        GRP_HIP(hipStreamSynchronize(st));               // the one host round trip of the layer
+        const int64_t host_nnz = mailbox[0];
+        const int64_t host_new = mailbox[1];
         const int64_t n_src = n_dst + host_new;
+        if (host_nnz < 0 || host_new < 0) return fail(GRP_EHIP, "mini-batch: the block sizes did not reach the host");
         if (host_nnz > bd.nnz[l] || n_src > bd.src[l]) return fail(GRP_EHIP, "mini-batch: sampled block exceeds its bounds");
         hipLaunchKernelGGL(clear_marks_kernel, dim3(blocks_for(n_src)), dim3(256), 0, st, (const int32_t*)L.src_nodes, n_src,
                            s.mark);
@@ -333,7 +345,9 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
         GRP_TRY(launch_csr_from_sorted_keys(L.keys_sorted, host_nnz, n_src, L.ptrT, L.idxT, st));
         LongRows& lr = long_bwd_store[l];
         lr.long_row = L.lr_row; lr.long_first = L.lr_first; lr.chunk_begin = L.lr_cb; lr.chunk_end = L.lr_ce;
-        GRP_TRY(build_long_rows_into(L.ptrT, n_src, &lr, L.lr_cap_long, L.lr_cap_chunks, st));
+        const int64_t cap_long = host_nnz / SPMM_LONG_ROW + 1;
+        const int64_t cap_chunks = host_nnz / SPMM_CHUNK + cap_long + 1;      // within L.lr_cap_*: host_nnz <= bd.nnz[l]
+        GRP_TRY(build_long_rows_device(L.ptrT, n_src, &lr, cap_long, cap_chunks, L.lr_pack, L.lr_scan, s.scan_tmp, s.scan_bytes, st));
         B.idx = L.idx_blk;
         B.n_in = n_src;
         B.nnz = host_nnz;

@@ -247,6 +247,7 @@ __global__ __launch_bounds__(256) void spmm_combine_kernel(const int32_t* __rest
     const int j0 = blockIdx.x * ROWS + threadIdx.x / G;
     if (j0 >= n_long) return;
     const int64_t i = long_row[j0];
+    if (i < 0) return;                // an unused slot of a schedule built to its capacity
     const int c0 = long_first[j0], c1 = long_first[j0 + 1];
     const int64_t deg = ptr[i + 1] - ptr[i];
 #pragma unroll

@@ -9,6 +9,7 @@ import synth
 from oracle import coverage as ocov
 from oracle import gnn as ognn
 from oracle import graph as ograph
+from oracle import sampling as osampling
 from oracle import step as ostep
 from tests._cases import TOL_BF16, TOL_FP32, assert_grads_close, assert_step_grads_close, make_inputs, rel_err
 
@@ -444,6 +445,48 @@ def test_minibatch_train_step_matches_oracle(g, dims, fanouts, bf16, n_seeds):
         assert abs(float(st["R"]) - ost["R"]) <= 1e-9 * max(1.0, ost["R"])
         assert abs(float(st["sum_ratio"]) - ost["sum_ratio"]) <= 1e-9 * max(1.0, ost["sum_ratio"])
         assert abs(float(st["loss"]) - ost["loss"]) <= TOL_FP32 * abs(ost["loss"])
+
+
+def test_minibatch_block_with_a_source_shared_by_thousands_of_seeds(g):
+    """One node feeds 1500 seeds: its row of the transposed block is far beyond the length at which the
+    backward aggregation splits a row into chunks (the split schedule is built on the device)."""
+    _note("minibatch transposed long row")
+    scale, E, K = 13, 100000, 2
+    N = 1 << scale
+    s, d = synth.rmat_graph(scale, E, seed=2602018731, device=DEV)
+    op0 = ograph.partition(s.cpu().numpy(), d.cpu().numpy(), N, K, 1, 0)
+    quiet = np.flatnonzero(op0["d_local_in"] <= 20)[:1500]
+    assert quiet.size == 1500
+    feeder = int(op0["l2g"][int(np.flatnonzero(op0["d_local_in"] > 20)[0])])
+    es = torch.full((1500,), feeder, dtype=torch.int64, device=DEV)
+    ed = torch.from_numpy(op0["l2g"][quiet].astype(np.int64)).to(DEV)
+    s, d = torch.cat([s, es]), torch.cat([d, ed])
+    part = g.grp_partition(s, d, N, K, 1, 0)
+    op = ograph.partition(s.cpu().numpy(), d.cpu().numpy(), N, K, 1, 0)
+    assert np.array_equal(op["l2g"], op0["l2g"])              # same nodes, same local ids
+    seeds = quiet.astype(np.int32)
+    dims, fanouts = [16, 24, 24, 5], (5, 6, 64)
+    oblocks, _ = osampling.sample_blocks(op, seeds, fanouts, 11, 2)
+    assert np.bincount(oblocks[2]["esrc"]).max() >= 1500       # the feeder, kept by every seed
+    assert np.bincount(oblocks[1]["esrc"]).max() > 512         # and again one hop further in
+    x, y, theta = make_inputs(part.n, dims, "sage", 23)
+    model = g.model_desc(g.ARCH_SAGE_MEAN, dims)
+    opts = g.step_opts(estimator=3, full_graph=False, seeds=torch.from_numpy(seeds).to(DEV), fanouts=fanouts,
+                       sampler_seed=11, batch_id=2)
+    ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+    grad = torch.full((g.grp_param_count(model),), float("nan"), device=DEV)
+    stats = g.new_stats(1)
+    g.grp_train_step(part, model, opts, x.to(DEV), y.to(DEV), None, theta.to(DEV), ws, grad, stats)
+    torch.cuda.synchronize()
+    mb = dict(seeds=seeds, fanouts=fanouts, sampler_seed=11, batch_id=2)
+
+    def oracle_fn(relu_flip=None, near_kink=None):
+        return ostep.train_step(op, "sage", dims, theta.double().numpy(), x.double().numpy(), y.numpy(),
+                                estimator=3, minibatch=mb, relu_flip=relu_flip, near_kink=near_kink)
+    og, ost = assert_step_grads_close(grad.cpu().numpy(), oracle_fn, "sage", dims, TOL_FP32)
+    st = g.read_stats(stats)[0]
+    assert int(st["nnz_used"]) == ost["nnz_used"]
+    assert abs(float(st["R"]) - ost["R"]) <= 1e-9 * max(1.0, ost["R"])
 
 
 def test_minibatch_is_bit_reproducible_and_batch_dependent(g):
