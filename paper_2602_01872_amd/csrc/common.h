@@ -318,6 +318,9 @@ grp_status exclusive_scan_i64(void* temp, size_t temp_bytes, const int64_t* in, 
                               hipStream_t st);
 grp_status exclusive_scan_i32(void* temp, size_t temp_bytes, const int32_t* in, int32_t* out, int64_t count,
                               hipStream_t st);
+// out[i] = number of set bits in words[0 .. i), i in [0, count): reads `count` words
+grp_status exclusive_scan_popcount(void* temp, size_t temp_bytes, const uint32_t* words, int32_t* out, int64_t count,
+                                   hipStream_t st);
 // From sorted keys (row << 32 | col): idx[i] = low half, ptr[r] = first position with high half >= r.
 grp_status launch_csr_from_sorted_keys(const uint64_t* keys, int64_t nnz, int64_t n, int64_t* ptr, int32_t* idx,
                                        hipStream_t st);
@@ -325,9 +328,9 @@ grp_status launch_csr_from_sorted_keys(const uint64_t* keys, int64_t nnz, int64_
 // arrays without a host pass: out->n_long / n_chunks are set to the capacities (the launches cover
 // them) and the slots beyond the real counts are filled so that they do nothing (row -1, empty
 // chunks).  Capacities must cover every possible schedule: cap_long >= nnz / SPMM_LONG_ROW,
-// cap_chunks >= nnz / SPMM_CHUNK + cap_long.  pack / scanned: [n + 1] int64 scratch.
+// cap_chunks >= nnz / SPMM_CHUNK + cap_long.  scanned: [n + 1] int64 scratch.
 grp_status build_long_rows_device(const int64_t* ptr_dev, int64_t n, LongRows* out, int64_t cap_long, int64_t cap_chunks,
-                                  int64_t* pack, int64_t* scanned, void* scan_tmp, size_t scan_bytes, hipStream_t st);
+                                  int64_t* scanned, void* scan_tmp, size_t scan_bytes, hipStream_t st);
 
 // 64 bytes of pinned host memory the device can write, one per host thread, kept until the process
 // ends (sizes a kernel reports to the host; read after synchronising the stream).  Null on failure.

@@ -1153,6 +1153,28 @@ grp_status exclusive_scan_i32(void* temp, size_t temp_bytes, const int32_t* in, 
     return GRP_OK;
 }
 
+struct PopcountOf {
+    __host__ __device__ int32_t operator()(uint32_t w) const {
+#if defined(__HIP_DEVICE_COMPILE__)
+        return __popc(w);
+#else
+        return __builtin_popcount(w);
+#endif
+    }
+};
+
+// out[i] = number of set bits in words[0 .. i), for i in [0, count)
+grp_status exclusive_scan_popcount(void* temp, size_t temp_bytes, const uint32_t* words, int32_t* out, int64_t count,
+                                   hipStream_t st) {
+    if (count <= 0) return GRP_OK;
+    auto in = rocprim::make_transform_iterator(words, PopcountOf());
+    size_t need = 0;
+    GRP_HIP(rocprim::exclusive_scan(nullptr, need, in, out, (int32_t)0, (size_t)count, rocprim::plus<int32_t>(), st));
+    if (need > temp_bytes) return fail(GRP_EWORKSPACE, "scan temp %zu < %zu", temp_bytes, need);
+    GRP_HIP(rocprim::exclusive_scan(temp, need, in, out, (int32_t)0, (size_t)count, rocprim::plus<int32_t>(), st));
+    return GRP_OK;
+}
+
 // Same result as csr_from_keys_kernel for matrices with many empty rows (a sampled block has more
 // rows than most of them have entries): every row pointer is found by binary search instead of by
 // the thread at the end of the previous row walking over the gap.
@@ -1179,19 +1201,17 @@ grp_status launch_csr_from_sorted_keys(const uint64_t* keys, int64_t nnz, int64_
 }
 
 // ---- split schedule of the long rows, built on the device (no host pass, no synchronisation).
-// pack[r] = (1 << 32 | chunks of row r) for a long row, 0 otherwise; its exclusive prefix sum gives every
+// The exclusive prefix sum of (1 << 32 | chunks of row r) for a long row, 0 otherwise, gives every
 // long row its slot (high half) and first chunk (low half), in ascending row order.
-__global__ __launch_bounds__(256) void long_rows_pack_kernel(const int64_t* __restrict__ ptr, int64_t n,
-                                                             int64_t* __restrict__ pack /*[n+1]*/) {
-    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (r > n) return;
-    int64_t v = 0;
-    if (r < n) {
+struct LongRowPack {
+    const int64_t* ptr;
+    int64_t n;
+    __host__ __device__ int64_t operator()(int64_t r) const {
+        if (r >= n) return 0;
         const int64_t len = ptr[r + 1] - ptr[r];
-        if (len > SPMM_LONG_ROW) v = ((int64_t)1 << 32) | ((len + SPMM_CHUNK - 1) / SPMM_CHUNK);
+        return len > SPMM_LONG_ROW ? (((int64_t)1 << 32) | ((len + SPMM_CHUNK - 1) / SPMM_CHUNK)) : 0;
     }
-    pack[r] = v;
-}
+};
 
 // Slots past the real counts are made harmless: row -1 (skipped by the combine pass), empty chunks.
 __global__ __launch_bounds__(256) void long_rows_emit_kernel(const int64_t* __restrict__ ptr, int64_t n,
@@ -1226,10 +1246,14 @@ __global__ __launch_bounds__(256) void long_rows_emit_kernel(const int64_t* __re
 }
 
 grp_status build_long_rows_device(const int64_t* ptr_dev, int64_t n, LongRows* out, int64_t cap_long, int64_t cap_chunks,
-                                  int64_t* pack, int64_t* scanned, void* scan_tmp, size_t scan_bytes, hipStream_t st) {
-    hipLaunchKernelGGL(long_rows_pack_kernel, dim3((unsigned)cdiv(n + 1, 256)), dim3(256), 0, st, ptr_dev, n, pack);
-    GRP_LAUNCH_CHECK();
-    GRP_TRY(exclusive_scan_i64(scan_tmp, scan_bytes, pack, scanned, n + 1, st));
+                                  int64_t* scanned, void* scan_tmp, size_t scan_bytes, hipStream_t st) {
+    {
+        auto in = rocprim::make_transform_iterator(rocprim::make_counting_iterator<int64_t>(0), LongRowPack{ptr_dev, n});
+        size_t need = 0;
+        GRP_HIP(rocprim::exclusive_scan(nullptr, need, in, scanned, (int64_t)0, (size_t)(n + 1), rocprim::plus<int64_t>(), st));
+        if (need > scan_bytes) return fail(GRP_EWORKSPACE, "scan temp %zu < %zu", scan_bytes, need);
+        GRP_HIP(rocprim::exclusive_scan(scan_tmp, need, in, scanned, (int64_t)0, (size_t)(n + 1), rocprim::plus<int64_t>(), st));
+    }
     int64_t work = n;
     if (cap_long + 1 > work) work = cap_long + 1;
     if (cap_chunks > work) work = cap_chunks;

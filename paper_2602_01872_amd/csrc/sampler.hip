@@ -31,18 +31,29 @@ __host__ __device__ __forceinline__ uint64_t mixM(uint64_t x) {
     return z ^ (z >> 31);
 }
 
+// Per destination row: the number of edges it keeps and 1 / max(that, 1); above the input layer also
+// the row's place in the block's source list (destinations come first, in order) and in the node -> block
+// index map.  Element n_dst of `cnt` closes the prefix sum.
 __global__ __launch_bounds__(256) void sample_count_kernel(const int64_t* __restrict__ rowptr,
                                                            const int32_t* __restrict__ dst_nodes, int64_t n_dst,
                                                            int fanout, int64_t* __restrict__ cnt /*[n_dst+1]*/,
-                                                           int32_t* __restrict__ cnt32 /*[n_dst] or null*/) {
+                                                           int32_t* __restrict__ cnt32 /*[n_dst] or null*/,
+                                                           float* __restrict__ inv /*[n_dst]*/,
+                                                           int32_t* __restrict__ mark /*[n] or null*/,
+                                                           int32_t* __restrict__ src_nodes /*[>= n_dst] or null*/) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i > n_dst) return;
     if (i == n_dst) { cnt[i] = 0; return; }
-    const int64_t v = dst_nodes[i];
+    const int32_t v = dst_nodes[i];
     const int64_t d = rowptr[v + 1] - rowptr[v];
     const int64_t c = d < fanout ? d : fanout;
     cnt[i] = c;
     if (cnt32) cnt32[i] = (int32_t)c;
+    inv[i] = 1.0f / (float)(c > 1 ? c : 1);
+    if (mark) {
+        mark[v] = (int32_t)i + 1;
+        src_nodes[i] = v;
+    }
 }
 
 // One wavefront per destination row.  Lane t computes draw t; the subset is grown in `fanout`
@@ -83,14 +94,6 @@ __global__ __launch_bounds__(64 * SAMPLE_ROWS_PER_WG) void sample_select_kernel(
     if (lane < fanout) out_idx[o + rank] = col[b + mine];
 }
 
-__global__ __launch_bounds__(256) void mark_dst_kernel(const int32_t* __restrict__ dst_nodes, int64_t n_dst,
-                                                       int32_t* __restrict__ mark, int32_t* __restrict__ src_nodes) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n_dst) return;
-    mark[dst_nodes[i]] = (int32_t)i + 1;
-    src_nodes[i] = dst_nodes[i];
-}
-
 // New source nodes are collected in a bitmap over the partition's nodes (one bit each): the words'
 // population counts are prefix-summed and every non-empty word then numbers its own nodes, which
 // yields them in ascending local id while touching n / 8 bytes instead of per-node flag arrays.
@@ -102,13 +105,6 @@ __global__ __launch_bounds__(256) void flag_new_kernel(const int32_t* __restrict
         const int32_t u = idx_local[e];
         if (mark[u] == 0) atomicOr(&bits[u >> 5], 1u << (u & 31));
     }
-}
-
-__global__ __launch_bounds__(256) void word_count_kernel(const uint32_t* __restrict__ bits, int64_t n_words,
-                                                         int32_t* __restrict__ wcount /*[n_words+1]*/) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i > n_words) return;
-    wcount[i] = i < n_words ? __popc(bits[i]) : 0;
 }
 
 // Also clears the bitmap for the next layer.
@@ -156,14 +152,6 @@ __global__ __launch_bounds__(256) void clear_marks_kernel(const int32_t* __restr
     mark[src_nodes[i]] = 0;
 }
 
-__global__ __launch_bounds__(256) void inv_count_kernel(const int64_t* __restrict__ ptr, int64_t n_dst,
-                                                        float* __restrict__ inv) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n_dst) return;
-    const int64_t c = ptr[i + 1] - ptr[i];
-    inv[i] = 1.0f / (float)(c > 1 ? c : 1);
-}
-
 void sampler_bounds(int64_t n, int64_t n_seeds, const int32_t* fanouts, int k, SamplerBounds* out) {
     int64_t nd = n_seeds;
     for (int l = k - 1; l >= 0; --l) {
@@ -189,15 +177,15 @@ struct SamplerLayerBufs {
     float* inv_in;       // [dst]
     int32_t *lr_row, *lr_first;    // long rows of the transposed block
     int64_t *lr_cb, *lr_ce;
-    int64_t *lr_pack, *lr_scan;    // [src+1] scratch of the schedule's construction
+    int64_t* lr_scan;              // [src+1] scratch of the schedule's construction
     int64_t lr_cap_long, lr_cap_chunks;
 };
 
 struct SamplerBufs {
     SamplerLayerBufs L[GRP_MAX_LAYERS];
     int32_t* mark;                      // [n] block-local index + 1 of the current layer's nodes, else 0
-    uint32_t* bits;                     // [n_words] bitmap of newly reached nodes
-    int32_t *wcount, *wpos;             // [n_words + 1] set bits per word and their prefix sum
+    uint32_t* bits;                     // [n_words + 1] bitmap of newly reached nodes (the last word stays 0)
+    int32_t* wpos;                      // [n_words + 1] set bits in the words before each word
     int64_t n_words;
     void *scan_tmp, *sort_tmp;
     size_t scan_bytes, sort_bytes;
@@ -229,20 +217,18 @@ static SamplerBufs carve_sampler(int64_t n, const SamplerBounds& b, int k, void*
             L.lr_first = bump.take<int32_t>((size_t)L.lr_cap_long + 1);
             L.lr_cb = bump.take<int64_t>((size_t)L.lr_cap_chunks);
             L.lr_ce = bump.take<int64_t>((size_t)L.lr_cap_chunks);
-            L.lr_pack = bump.take<int64_t>((size_t)b.src[l] + 1);
             L.lr_scan = bump.take<int64_t>((size_t)b.src[l] + 1);
             if (b.nnz[l] > max_nnz) max_nnz = b.nnz[l];
         } else {
             L.idx_blk = nullptr; L.src_nodes = nullptr; L.keys = L.keys_sorted = nullptr;
             L.ptrT = nullptr; L.idxT = nullptr; L.lr_row = L.lr_first = nullptr; L.lr_cb = L.lr_ce = nullptr;
-            L.lr_pack = L.lr_scan = nullptr;
+            L.lr_scan = nullptr;
             L.lr_cap_long = L.lr_cap_chunks = 0;
         }
     }
     s.mark = bump.take<int32_t>((size_t)n);
     s.n_words = cdiv(n, 32);
-    s.bits = bump.take<uint32_t>((size_t)s.n_words);
-    s.wcount = bump.take<int32_t>((size_t)s.n_words + 1);
+    s.bits = bump.take<uint32_t>((size_t)s.n_words + 1);
     s.wpos = bump.take<int32_t>((size_t)s.n_words + 1);
     s.scan_bytes = scan_temp_bytes(s.n_words + 1 > max_dst + 1 ? s.n_words + 1 : max_dst + 1);
     s.scan_tmp = bump.take<char>(s.scan_bytes);
@@ -270,9 +256,10 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
     SamplerBufs s = carve_sampler(n, bd, k, ws, ws_bytes);
     if (s.total > ws_bytes) return fail(GRP_EWORKSPACE, "mini-batch: sampler workspace %zu < %zu", ws_bytes, s.total);
 
-    if (k > 1) {                                         // the flag arrays start at zero
-        GRP_TRY(launch_fill_zero(s.mark, (size_t)n * sizeof(int32_t), st));
-        GRP_TRY(launch_fill_zero(s.bits, (size_t)s.n_words * sizeof(uint32_t), st));
+    if (k > 1) {        // the node map and the bitmap start at zero (carved back to back: one fill covers both)
+        char* const lo = (char*)s.mark;
+        char* const hi = (char*)(s.bits + s.n_words + 1);
+        GRP_TRY(launch_fill_zero(lo, (size_t)(hi - lo), st));
     }
     int64_t* const mailbox = k > 1 ? host_mailbox() : nullptr;
     if (k > 1 && !mailbox) return fail(GRP_EHIP, "mini-batch: no pinned host memory for the block sizes");
@@ -283,7 +270,7 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
         SamplerLayerBufs& L = s.L[l];
         const int f = o->fanouts[l];
         hipLaunchKernelGGL(sample_count_kernel, dim3(blocks_for(n_dst + 1)), dim3(256), 0, st, part->rowptr, dst_nodes, n_dst,
-                           f, L.cnt, L.cnt32);
+                           f, L.cnt, L.cnt32, L.inv_in, l > 0 ? s.mark : nullptr, l > 0 ? L.src_nodes : nullptr);
         GRP_LAUNCH_CHECK();
         GRP_TRY(exclusive_scan_i64(s.scan_tmp, s.scan_bytes, L.cnt, L.ptr, n_dst + 1, st));
         {
@@ -293,8 +280,6 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
                                (const int64_t*)L.ptr, L.idx_local);
             GRP_LAUNCH_CHECK();
         }
-        hipLaunchKernelGGL(inv_count_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, st, (const int64_t*)L.ptr, n_dst, L.inv_in);
-        GRP_LAUNCH_CHECK();
 
         Block& B = blocks[l];
         B.n_dst = n_dst;
@@ -313,15 +298,10 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
             break;
         }
         // new source nodes in ascending local id, block-local relabelling, transposed block
-        hipLaunchKernelGGL(mark_dst_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, st, dst_nodes, n_dst, s.mark, L.src_nodes);
-        GRP_LAUNCH_CHECK();
         hipLaunchKernelGGL(flag_new_kernel, dim3(blocks_for(bd.nnz[l])), dim3(256), 0, st, (const int32_t*)L.idx_local,
                            (const int64_t*)(L.ptr + n_dst), (const int32_t*)s.mark, s.bits);
         GRP_LAUNCH_CHECK();
-        hipLaunchKernelGGL(word_count_kernel, dim3(blocks_for(s.n_words + 1)), dim3(256), 0, st, (const uint32_t*)s.bits,
-                           s.n_words, s.wcount);
-        GRP_LAUNCH_CHECK();
-        GRP_TRY(exclusive_scan_i32(s.scan_tmp, s.scan_bytes, s.wcount, s.wpos, s.n_words + 1, st));
+        GRP_TRY(exclusive_scan_popcount(s.scan_tmp, s.scan_bytes, s.bits, s.wpos, s.n_words + 1, st));
         hipLaunchKernelGGL(assign_new_kernel, dim3(blocks_for(s.n_words)), dim3(256), 0, st, s.n_words, s.bits,
                            (const int32_t*)s.wpos, n_dst, s.mark, L.src_nodes);
         GRP_LAUNCH_CHECK();
@@ -347,7 +327,7 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
         lr.long_row = L.lr_row; lr.long_first = L.lr_first; lr.chunk_begin = L.lr_cb; lr.chunk_end = L.lr_ce;
         const int64_t cap_long = host_nnz / SPMM_LONG_ROW + 1;
         const int64_t cap_chunks = host_nnz / SPMM_CHUNK + cap_long + 1;      // within L.lr_cap_*: host_nnz <= bd.nnz[l]
-        GRP_TRY(build_long_rows_device(L.ptrT, n_src, &lr, cap_long, cap_chunks, L.lr_pack, L.lr_scan, s.scan_tmp, s.scan_bytes, st));
+        GRP_TRY(build_long_rows_device(L.ptrT, n_src, &lr, cap_long, cap_chunks, L.lr_scan, s.scan_tmp, s.scan_bytes, st));
         B.idx = L.idx_blk;
         B.n_in = n_src;
         B.nnz = host_nnz;
