@@ -176,23 +176,45 @@ def run_evidence_workload(args, g, synth, torch, dev):
                                  stats[p * g.STATS_BYTES:(p + 1) * g.STATS_BYTES])
             g.grp_aggregate(grads, ld, stats, K, P, g.EST_SHRINKAGE, upd)
             g.grp_optimizer_step(opt, P, 1, theta, upd)
+        lanes = [torch.cuda.Stream() for _ in range(K)]       # default priority
+
+        def fn_lanes():            # the partitions of a phase are independent: one stream each, joined before the reduction
+            main = torch.cuda.current_stream()
+            ready = main.record_event()
+            for p in range(K):
+                lanes[p].wait_event(ready)
+                g.grp_train_step(parts[p], model, opts, xs[p], ys[p], None, theta, wss[p], grads[p],
+                                 stats[p * g.STATS_BYTES:(p + 1) * g.STATS_BYTES], stream=lanes[p])
+            for p in range(K):
+                main.wait_stream(lanes[p])
+            g.grp_aggregate(grads, ld, stats, K, P, g.EST_SHRINKAGE, upd)
+            g.grp_optimizer_step(opt, P, 1, theta, upd)
+
+        def captured(f):
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                f()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                f()
+            return graph
         dt = _time_steps(torch, fn, args.warmup, args.steps)
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            fn()
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            fn()
+        dt_lanes = _time_steps(torch, fn_lanes, args.warmup, args.steps)
+        graph, graph_lanes = captured(fn), captured(fn_lanes)
         dt_graph = _time_steps(torch, graph.replay, args.warmup, args.steps)
+        dt_graph_lanes = _time_steps(torch, graph_lanes.replay, args.warmup, args.steps)
         kernels = _kernel_table(g, torch, fn, args.steps)
         nnz = sum(p.nnz for p in parts)
+        best = min(dt, dt_lanes, dt_graph, dt_graph_lanes)
         out.update(metric="train-step edges/s over the 4 partitions (fwd+bwd), one iteration = 4 steps + aggregate + optimizer",
-                   unit="edges/s", value=nnz / dt_graph, ms_per_step=dt_graph * 1e3, dtype="f32",
+                   unit="edges/s", value=nnz / best, ms_per_step=best * 1e3, dtype="f32",
                    config={"workload": f"c1-step: GCN-2 {dims}, {N} nodes / {E} uniform edges, K={K}, local edges {nnz}",
-                           "ms_per_iteration_eager": dt * 1e3, "ms_per_iteration_hip_graph": dt_graph * 1e3, "params": P},
+                           "ms_per_iteration_eager": dt * 1e3, "ms_per_iteration_hip_graph": dt_graph * 1e3,
+                           "ms_per_iteration_eager_4_streams": dt_lanes * 1e3,
+                           "ms_per_iteration_hip_graph_4_streams": dt_graph_lanes * 1e3, "params": P},
                    roofline=_roofline(kernels, {}), kernels=kernels)
         print(json.dumps(out), flush=True)
         return

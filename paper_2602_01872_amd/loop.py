@@ -1,8 +1,9 @@
 """Phase-parallel epoch loop over the C ABI (the paper's phase-parallel algorithm, one GPU).
 
 Sequencing only: every partition step, the scale-and-reduce and the optimizer step are
-library calls; partitions of a phase are processed in turn on the one GPU and their
-gradients kept resident for the reduction.
+library calls; the partitions of a phase are independent of each other, so they are processed
+in turn on the one GPU or, with ``streams`` > 1, side by side on that many HIP streams (small
+partitions leave most of the chip idle); their gradients are kept resident for the reduction.
 """
 from __future__ import annotations
 
@@ -20,10 +21,12 @@ class PhaseParallelTrainer:
     number of partitions per phase.  Full-graph mode (one iteration per phase and epoch).
     ``dropout_rate`` / ``dropout_seed``: hidden-layer dropout; the masks of a phase are drawn with
     batch_id = the number of optimizer steps taken so far.
+    ``streams``: number of streams (default priority) the steps of a phase are spread over, each with a
+    workspace of its own; 1 = everything on the current stream.  The result does not depend on it.
     """
 
     def __init__(self, parts, model, xs, ys, masks, theta0, estimator, max_active, optimizer=None,
-                 dropout_rate=0.0, dropout_seed=0):
+                 dropout_rate=0.0, dropout_seed=0, streams=1):
         self.parts, self.model, self.xs, self.ys, self.masks = parts, model, xs, ys, masks
         self.estimator, self.max_active = estimator, max_active
         self.opt = optimizer if optimizer is not None else g.optimizer_desc()
@@ -39,7 +42,9 @@ class PhaseParallelTrainer:
         self.grads = torch.zeros(max_active, self.ld, device=dev)
         self.stats = g.new_stats(max_active, device=dev)
         ws_bytes = max(g.grp_step_workspace_bytes(p, model, self.opts) for p in parts)
-        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        n_lanes = max(1, min(int(streams), max_active))
+        self.ws = [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in range(n_lanes)]
+        self.side = [torch.cuda.Stream(device=dev) for _ in range(n_lanes)] if n_lanes > 1 else []
         self.step_count = 0
         self.history = []          # per optimizer step: device tensor views are copied lazily
 
@@ -49,10 +54,19 @@ class PhaseParallelTrainer:
 
     def run_phase(self, active):
         self.opts.batch_id = self.step_count
+        main = torch.cuda.current_stream()
+        if self.side:                 # the side streams start once theta (and everything before) is ready
+            ready = main.record_event()
+            for st in self.side:
+                st.wait_event(ready)
         for slot, p in enumerate(active):
+            lane = slot % len(self.ws)
             g.grp_train_step(self.parts[p], self.model, self.opts, self.xs[p], self.ys[p], self.masks[p],
-                             self.theta, self.ws, self.grads[slot],
-                             self.stats[slot * g.STATS_BYTES:(slot + 1) * g.STATS_BYTES])
+                             self.theta, self.ws[lane], self.grads[slot],
+                             self.stats[slot * g.STATS_BYTES:(slot + 1) * g.STATS_BYTES],
+                             stream=self.side[lane] if self.side else None)
+        for st in self.side:          # the reduction waits for every step
+            main.wait_stream(st)
         g.grp_aggregate(self.grads, self.ld, self.stats, len(active), self.P, self.estimator, self.update)
         self.step_count += 1
         g.grp_optimizer_step(self.opt, self.P, self.step_count, self.theta, self.update, self.m, self.v)

@@ -637,6 +637,38 @@ def test_phase_parallel_loop_matches_oracle(g, M, kind):
         p.destroy()
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("arch", ["sage", "gat"])
+def test_phase_steps_on_several_streams_give_the_same_bits(g, arch):
+    """The partitions of a phase are independent: spread over three streams (with M = 4, so one stream
+    takes two steps in a row on its workspace) the loop must reproduce the one-stream run bit for bit."""
+    _note(f"phase-parallel loop on several streams {arch}")
+    N, E, K, M = 3000, 40000, 4, 4
+    s, d = synth.rmat_graph(12, E, seed=91, n_nodes=N)
+    dims = [24, 32, 6]
+    x = synth.normal_matrix(N, dims[0], 92)
+    y = synth.planted_labels(x, dims[-1], 93)
+    theta0 = synth.model_weights(arch, dims, 94)
+    parts = [g.grp_partition(s.to(DEV), d.to(DEV), N, K, 1, p) for p in range(K)]
+    l2gs = [torch.from_numpy(p.array("l2g")).to(DEV) for p in parts]
+    xs = [x.to(DEV)[i].contiguous() for i in l2gs]
+    ys = [y.to(DEV)[i].contiguous() for i in l2gs]
+    model = g.model_desc(g.ARCH_SAGE_MEAN if arch == "sage" else g.ARCH_GAT, dims)
+    runs = []
+    for streams in (1, 3):
+        tr = g.PhaseParallelTrainer(parts, model, xs, ys, [None] * K, theta0.to(DEV), g.EST_SHRINKAGE, M,
+                                    g.optimizer_desc(g.OPT_ADAM, lr=0.003), dropout_rate=0.25, dropout_seed=5,
+                                    streams=streams)
+        for _ in range(3):
+            tr.run_epoch()
+        torch.cuda.synchronize()
+        runs.append((tr.theta.clone(), tr.losses()))
+    assert torch.equal(runs[0][0], runs[1][0])
+    assert runs[0][1] == runs[1][1]
+    for p in parts:
+        p.destroy()
+
+
 # ------------------------------------------------------------------ chunks and sweeping partitions
 @pytest.mark.gpu
 @pytest.mark.parametrize("kind,N,E,c", [("uniform", 3000, 40000, 4), ("rmat", 1 << 12, 150000, 3), ("uniform", 500, 0, 2),
