@@ -11,7 +11,7 @@ from oracle import gnn as ognn
 from oracle import graph as ograph
 from oracle import sampling as osampling
 from oracle import step as ostep
-from tests._cases import TOL_BF16, TOL_FP32, assert_grads_close, assert_step_grads_close, make_inputs, rel_err
+from tests._cases import TOL_BF16, TOL_FP32, assert_grads_close, assert_step_grads_close, make_inputs, rel_err, split_flat
 
 pytestmark = pytest.mark.gpu
 
@@ -487,6 +487,38 @@ def test_minibatch_block_with_a_source_shared_by_thousands_of_seeds(g):
     st = g.read_stats(stats)[0]
     assert int(st["nnz_used"]) == ost["nnz_used"]
     assert abs(float(st["R"]) - ost["R"]) <= 1e-9 * max(1.0, ost["R"])
+
+
+def test_minibatch_of_isolated_seeds_has_empty_blocks(g):
+    """Seeds without local in-edges: every block is empty (no sampled edge, no new source node) and
+    only the self path carries gradient."""
+    _note("minibatch isolated seeds")
+    N, E, K = 600, 250, 2
+    s, d = synth.uniform_graph(N, E, seed=2602018741)
+    part = g.grp_partition(s.to(DEV), d.to(DEV), N, K, 1, 1)
+    op = ograph.partition(s.numpy(), d.numpy(), N, K, 1, 1)
+    seeds = np.flatnonzero(op["d_local_in"] == 0)[:37].astype(np.int32)
+    assert seeds.size == 37
+    dims, fanouts = [9, 12, 12, 4], (3, 2, 5)
+    x, y, theta = make_inputs(part.n, dims, "sage", 29)
+    model = g.model_desc(g.ARCH_SAGE_MEAN, dims)
+    opts = g.step_opts(estimator=2, full_graph=False, seeds=torch.from_numpy(seeds).to(DEV), fanouts=fanouts,
+                       sampler_seed=3, batch_id=0)
+    ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+    grad = torch.full((g.grp_param_count(model),), float("nan"), device=DEV)
+    stats = g.new_stats(1)
+    g.grp_train_step(part, model, opts, x.to(DEV), y.to(DEV), None, theta.to(DEV), ws, grad, stats)
+    torch.cuda.synchronize()
+    mb = dict(seeds=seeds, fanouts=fanouts, sampler_seed=3, batch_id=0)
+
+    def oracle_fn(relu_flip=None, near_kink=None):
+        return ostep.train_step(op, "sage", dims, theta.double().numpy(), x.double().numpy(), y.numpy(),
+                                estimator=2, minibatch=mb, relu_flip=relu_flip, near_kink=near_kink)
+    og, ost = assert_step_grads_close(grad.cpu().numpy(), oracle_fn, "sage", dims, TOL_FP32)
+    st = g.read_stats(stats)[0]
+    assert int(st["nnz_used"]) == ost["nnz_used"] == 0 and int(st["S"]) == 37
+    wn = split_flat(grad.cpu().numpy(), "sage", dims)
+    assert all(np.all(wn[f"Wn{l}"] == 0.0) for l in range(3))           # no neighbour ever contributes
 
 
 def test_minibatch_is_bit_reproducible_and_batch_dependent(g):
