@@ -298,7 +298,7 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
             break;
         }
         // new source nodes in ascending local id, block-local relabelling, transposed block
-        hipLaunchKernelGGL(flag_new_kernel, dim3(blocks_for(bd.nnz[l])), dim3(256), 0, st, (const int32_t*)L.idx_local,
+        hipLaunchKernelGGL(flag_new_kernel, dim3(blocks_for(n_dst * f)), dim3(256), 0, st, (const int32_t*)L.idx_local,
                            (const int64_t*)(L.ptr + n_dst), (const int32_t*)s.mark, s.bits);
         GRP_LAUNCH_CHECK();
         GRP_TRY(exclusive_scan_popcount(s.scan_tmp, s.scan_bytes, s.bits, s.wpos, s.n_words + 1, st));
