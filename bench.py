@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path on one MI355X.
 
-Workload (benchmark configs[1]): 3-layer GraphSAGE-mean (100 -> 256 -> 256 -> 47) on one
+Workload (the headline configuration, the second of the five): 3-layer GraphSAGE-mean (100 -> 256 -> 256 -> 47) on one
 of 8 hash partitions of a seeded R-MAT graph with 2.4 M nodes / 62 M edges (a stand-in for
 the paper's OGBN-Products-sized input; ~300 k local nodes, ~0.97 M local edges once cut
 edges are dropped), fp32 features ~N(0,1), uniform labels, full-graph mode.
