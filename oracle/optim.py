@@ -12,7 +12,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import chunks, coverage, step
+from . import chunks, coverage, sampling, step
 
 SGD, ADAM = 0, 1
 
@@ -78,6 +78,50 @@ def train_epochs(parts, arch, dims, theta0, xs, ys, masks, n_epochs, max_active,
             else:
                 theta = sgd_step(theta, G, lr)
             history.append(float(np.mean([s["loss"] for s in stats])))
+    return theta, history
+
+
+def train_epochs_minibatch(parts, arch, dims, theta0, xs, ys, masks, n_epochs, max_active, estimator, batch_size,
+                           fanouts, sampler_seed, optimizer=ADAM, lr=0.003):
+    """The phase-parallel algorithm in mini-batch mode.
+
+    Every epoch each partition visits its training nodes once, in the order ``sampling.epoch_seed_order``
+    gives, ``batch_size`` seeds per iteration; an epoch has as many iterations as the partition with the
+    most training nodes needs, and a partition whose nodes are used up takes part with an empty batch (a
+    zero gradient that still counts in the average, as for a partition without loss nodes).  Iteration i
+    of epoch e samples with batch_id = e * iterations_per_epoch + i in every partition.  Within an
+    iteration the phases run as in ``train_epochs``: the active partitions step at the current theta,
+    their gradients are scaled and averaged, one optimizer step follows.  Returns (theta, history).
+    """
+    theta = np.asarray(theta0, dtype=np.float64).copy()
+    m = np.zeros_like(theta)
+    v = np.zeros_like(theta)
+    t = 0
+    history = []
+    n_train = [parts[p]["n"] if masks[p] is None else int(np.count_nonzero(masks[p])) for p in range(len(parts))]
+    iters = max(1, max(-(-c // batch_size) for c in n_train))
+    for epoch in range(n_epochs):
+        order = [sampling.epoch_seed_order(parts[p], masks[p], sampler_seed, epoch) for p in range(len(parts))]
+        for it in range(iters):
+            for active in phase_schedule(len(parts), max_active):
+                grads, stats = [], []
+                for p in active:
+                    seeds = order[p][it * batch_size:(it + 1) * batch_size]
+                    if seeds.size == 0:
+                        grads.append(np.zeros_like(theta))
+                        stats.append(dict(S=0, sum_ratio=0.0, R=0.0, loss=0.0, nnz_used=0))
+                        continue
+                    mb = dict(seeds=seeds, fanouts=fanouts, sampler_seed=sampler_seed, batch_id=epoch * iters + it)
+                    g, st = step.train_step(parts[p], arch, dims, theta, xs[p], ys[p], estimator=estimator, minibatch=mb)
+                    grads.append(g)
+                    stats.append(st)
+                G, _ = coverage.aggregate(grads, stats, estimator)
+                t += 1
+                if optimizer == ADAM:
+                    theta, m, v = adam_step(theta, G, m, v, t, lr)
+                else:
+                    theta = sgd_step(theta, G, lr)
+                history.append(float(np.mean([s["loss"] for s in stats])))
     return theta, history
 
 

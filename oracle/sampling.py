@@ -19,6 +19,11 @@ but fixes neither the sampler nor its random numbers.  Reading taken here:
     reached nodes in ascending local id; a block's edges are ordered by destination and,
     inside a destination, by ascending position.
 
+  * the seeds of an epoch (the paper lets every worker iterate over all of its training nodes once
+    per epoch, in no stated order): the partition's training nodes sorted by the 64-bit key
+    M(M(M(sampler_seed) ^ epoch) ^ global_id(v)), ties by local id; batch b of the epoch is the slice
+    [b * B, (b + 1) * B) of that order, the last one possibly shorter.
+
 Because the draws depend only on (seed, batch, layer, node, t) the result is independent of
 evaluation order.
 """
@@ -112,3 +117,13 @@ def sample_blocks(part: dict, seeds, fanouts, sampler_seed: int, batch_id: int):
                              esrc=lookup[esrc_local], edst=edst, src_nodes=src_nodes)
         dst_nodes = src_nodes
     return blocks, dst_nodes
+
+
+def epoch_seed_order(part: dict, train_mask, sampler_seed: int, epoch: int) -> np.ndarray:
+    """Local ids of the partition's training nodes (``train_mask`` non-zero; None = all) in the order an
+    epoch visits them: ascending key M(M(M(sampler_seed) ^ epoch) ^ global_id), ties by local id."""
+    n = part["n"]
+    ids = np.arange(n, dtype=np.int64) if train_mask is None else np.flatnonzero(np.asarray(train_mask) != 0).astype(np.int64)
+    h = _M(_M(np.uint64(sampler_seed & 0xFFFFFFFFFFFFFFFF)) ^ np.uint64(epoch))
+    keys = _M(h ^ np.asarray(part["l2g"], dtype=np.uint64)[ids])
+    return ids[np.lexsort((ids, keys))]

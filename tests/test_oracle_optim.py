@@ -148,3 +148,42 @@ def test_sweeping_switches_and_learns():
     assert sw == [9, 19, 29]                       # ceil(30 / 3) = 10 epochs per super-epoch
     assert len(hist) == 30 * 2
     assert np.mean(hist[-4:]) < 0.8 * np.mean(hist[:4])
+
+
+# ------------------------------------------------------------------ mini-batch epochs
+@pytest.mark.parametrize("M", [1, 3])
+def test_minibatch_epochs_with_one_full_batch_are_the_full_graph_epochs(M):
+    # one batch holding every training node, fanouts covering every row: each iteration is the
+    # full-graph step restricted to the training nodes, so the two loops must agree
+    parts, xs, ys = _problem(N=200, E=1200, K=3)
+    masks = [(np.arange(p["n"]) % 4 != 1).astype(np.uint8) for p in parts]
+    dims = [6, 8, 8, 3]
+    theta0 = synth.model_weights("sage", dims, 4).double().numpy()
+    big = int(max(p["d_local_in"].max() for p in parts)) + 1
+    for opt in (optim.SGD, optim.ADAM):
+        want, hw = optim.train_epochs(parts, "sage", dims, theta0, xs, ys, masks, 3, M, cov.BATCH_MIN_DIST,
+                                      optimizer=opt, lr=0.02)
+        got, hg = optim.train_epochs_minibatch(parts, "sage", dims, theta0, xs, ys, masks, 3, M, cov.BATCH_MIN_DIST,
+                                               batch_size=10 ** 6, fanouts=(big, big, big), sampler_seed=5,
+                                               optimizer=opt, lr=0.02)
+        np.testing.assert_allclose(got, want, rtol=1e-9, atol=1e-12)
+        np.testing.assert_allclose(hg, hw, rtol=1e-10)
+
+
+def test_minibatch_epochs_visit_every_training_node_once_and_learn():
+    parts, xs, ys = _problem(N=500, E=5000, K=3)
+    masks = [None, (np.arange(parts[1]["n"]) % 2 == 0).astype(np.uint8), None]
+    dims = [6, 16, 3]
+    theta0 = synth.model_weights("sage", dims, 4).double().numpy()
+    B = 32
+    n_train = [parts[0]["n"], int(masks[1].sum()), parts[2]["n"]]
+    iters = max(-(-c // B) for c in n_train)
+    th, hist = optim.train_epochs_minibatch(parts, "sage", dims, theta0, xs, ys, masks, 6, 2, cov.SHRINKAGE, B,
+                                            (5, 5), 9, optimizer=optim.ADAM, lr=0.01)
+    assert len(hist) == 6 * iters * 2                       # two phases (2 + 1 partitions) per iteration
+    assert np.isfinite(th).all()
+    assert np.mean(hist[-2 * iters:]) < 0.9 * np.mean(hist[:2 * iters])
+    # the shorter partition runs out of seeds first and then contributes empty batches
+    from oracle import sampling
+    order = sampling.epoch_seed_order(parts[1], masks[1], 9, 0)
+    assert order.size == n_train[1] < max(n_train)

@@ -184,3 +184,38 @@ def test_minibatch_shrinkage_uses_sampled_counts():
     assert abs(st["R"] - lit) < 1e-9
     blocks, _ = sampling.sample_blocks(part, seeds, (5, 3), 2, 5)
     assert st["nnz_used"] == blocks[0]["esrc"].size + blocks[1]["esrc"].size
+
+
+def test_epoch_seed_order_is_a_fresh_permutation_of_the_training_nodes():
+    part = _part(scale=9, E=9000)
+    n = part["n"]
+    mask = (np.arange(n) % 3 != 0).astype(np.uint8)
+    a = sampling.epoch_seed_order(part, mask, 11, 0)
+    assert sorted(a.tolist()) == np.flatnonzero(mask).tolist()          # each training node exactly once
+    assert a.tolist() == sampling.epoch_seed_order(part, mask, 11, 0).tolist()
+    b = sampling.epoch_seed_order(part, mask, 11, 1)
+    assert sorted(b.tolist()) == sorted(a.tolist()) and a.tolist() != b.tolist()
+    assert sampling.epoch_seed_order(part, mask, 12, 0).tolist() != a.tolist()
+    full = sampling.epoch_seed_order(part, None, 11, 0)
+    assert sorted(full.tolist()) == list(range(n))
+    assert sampling.epoch_seed_order(part, np.zeros(n, dtype=np.uint8), 11, 0).size == 0
+    # the key is a function of the global id: a node keeps its rank relative to another whatever else is masked
+    both = [v for v in full.tolist() if mask[v]]
+    assert both == a.tolist()
+    # and the key itself, redone with Python integers
+    h = _mix_int(_mix_int(11) ^ 0)
+    keys = [_mix_int(h ^ int(part["l2g"][v])) for v in a.tolist()]
+    assert keys == sorted(keys)
+
+
+def test_epoch_positions_are_spread_evenly():
+    # over many epochs every node's position in the order is uniform: mean (n-1)/2, no node favoured
+    part = graph.local_graph_from_edges(np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64), 50)
+    pos = np.zeros(50)
+    E = 600
+    for e in range(E):
+        order = sampling.epoch_seed_order(part, None, 5, e)
+        pos[order] += np.arange(50)
+    mean = pos / E
+    sigma = ((50 ** 2 - 1) / 12.0 / E) ** 0.5
+    assert np.abs(mean - 24.5).max() < 5 * sigma
