@@ -299,6 +299,17 @@ grp_status grp_train_step(const grp_partition_t* part, const grp_model_desc* mod
                           const float* weights, void* workspace, size_t workspace_bytes,
                           void* stream, float* grad_out, grp_step_stats* stats_out);
 
+/* Seed order of an epoch in mini-batch mode (the per-worker loop over batches of the phase-parallel
+ * algorithm; the paper lets every worker visit all of its training nodes once per epoch and fixes no
+ * order): the partition's training nodes (train_mask[v] != 0; NULL = every node; DEV uint8[n]) sorted
+ * ascending by key(v) = M(M(M(sampler_seed) ^ epoch) ^ global_id(v)), M as in grp_train_step's sampling
+ * rule, ties by local id.  seeds_out: DEV int32[n]; its first *n_seeds_out entries (HOST int64) are the
+ * local ids in visiting order; batch b of size B is the slice [b*B, min((b+1)*B, *n_seeds_out)), to be
+ * passed as opts->seeds / n_seeds.  Synchronous (the count is needed on the host); allocates and frees
+ * O(n) temporary device memory.  Errors: GRP_EINVAL, GRP_ENOMEM, GRP_EHIP.                           */
+grp_status grp_epoch_seeds(const grp_partition_t* part, const uint8_t* train_mask, uint64_t sampler_seed,
+                           uint64_t epoch, void* stream, int32_t* seeds_out, int64_t* n_seeds_out /*HOST*/);
+
 /* Inspection: where grp_train_step left the activation of layer `layer` inside the workspace it was
  * given (same partition, model and options).  *act_out is a borrowed DEV pointer into the workspace
  * to a [rows x *ld_out] row-major matrix (rows = n in full-graph mode; in mini-batch mode the layer's

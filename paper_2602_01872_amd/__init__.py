@@ -7,4 +7,4 @@ There is no CPU fallback: importing ``binding`` without the built library raises
 """
 from .binding import *  # noqa: F401,F403
 from .controller import Controller, sweep_pairs  # noqa: F401
-from .loop import PhaseParallelTrainer, SweepingTrainer  # noqa: F401
+from .loop import MiniBatchTrainer, PhaseParallelTrainer, SweepingTrainer  # noqa: F401

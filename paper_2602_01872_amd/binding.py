@@ -72,6 +72,7 @@ def load() -> C.CDLL:
     sigs = {
         "grp_partition": [vp, vp, i64, i64, i32, u64, i32, vp, C.POINTER(vp)],
         "grp_node_owners": [i64, i32, u64, vp, vp, vp],
+        "grp_epoch_seeds": [vp, vp, u64, u64, vp, vp, C.POINTER(i64)],
         "grp_partition_weighted": [vp, vp, vp, i64, i64, i32, u64, i32, vp, C.POINTER(vp)],
         "grp_partition_weights": [vp, C.POINTER(PartitionWeights)],
         "grp_partition_from_local_coo": [vp, vp, i64, i64, vp, vp, vp, C.POINTER(vp)],
@@ -248,6 +249,15 @@ def grp_node_owners(N: int, K: int, seed: int, owner_out, count_out=None, stream
     _check(load().grp_node_owners(N, K, seed, _ptr(owner_out), _ptr(count_out), _stream(stream)))
 
 
+def grp_epoch_seeds(part: Partition, train_mask, sampler_seed: int, epoch: int, seeds_out, stream=None) -> int:
+    """Fills ``seeds_out`` (int32 device tensor [n]) with the partition's training nodes in the order the
+    epoch visits them and returns their number."""
+    count = C.c_int64(0)
+    _check(load().grp_epoch_seeds(part.handle, _ptr(train_mask), sampler_seed, epoch, _stream(stream), _ptr(seeds_out),
+                                  C.byref(count)))
+    return int(count.value)
+
+
 def grp_partition_weighted(src, dst, w, N: int, K: int, seed: int, part_id: int, stream=None) -> Partition:
     """``w``: float32 device tensor, one positive weight per edge."""
     out = C.c_void_p()
@@ -414,7 +424,7 @@ def read_stats(stats: torch.Tensor) -> np.ndarray:
 
 
 def exported_symbols():
-    return ["grp_last_error", "grp_partition", "grp_node_owners", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_view",
+    return ["grp_last_error", "grp_partition", "grp_node_owners", "grp_epoch_seeds", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_view",
             "grp_partition_destroy", "grp_chunks_build", "grp_chunks_build_assigned", "grp_chunks_destroy", "grp_partition_from_chunks",
             "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_step_activation", "grp_train_step",
             "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",

@@ -332,6 +332,14 @@ grp_status launch_csr_from_sorted_keys(const uint64_t* keys, int64_t nnz, int64_
 grp_status build_long_rows_device(const int64_t* ptr_dev, int64_t n, LongRows* out, int64_t cap_long, int64_t cap_chunks,
                                   int64_t* scanned, void* scan_tmp, size_t scan_bytes, hipStream_t st);
 
+// M(x): the SplitMix64 finaliser of x + 0x9E3779B97F4A7C15 (the sampler's and the seed order's hash step)
+__host__ __device__ __forceinline__ uint64_t mixM(uint64_t x) {
+    uint64_t z = x + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
 // 64 bytes of pinned host memory the device can write, one per host thread, kept until the process
 // ends (sizes a kernel reports to the host; read after synchronising the stream).  Null on failure.
 int64_t* host_mailbox();

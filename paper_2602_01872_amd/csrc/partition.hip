@@ -999,6 +999,64 @@ extern "C" grp_status grp_node_owners(int64_t N, int32_t K, uint64_t seed, int32
     return GRP_OK;
 }
 
+namespace grp {
+// ---- seed order of an epoch: the training nodes sorted by M(M(M(seed) ^ epoch) ^ global id), ties by local id
+__global__ __launch_bounds__(256) void train_flag_kernel(const uint8_t* __restrict__ mask, int64_t n,
+                                                         int32_t* __restrict__ flag /*[n+1]*/) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v > n) return;
+    flag[v] = v < n && (!mask || mask[v] != 0) ? 1 : 0;
+}
+
+__global__ __launch_bounds__(256) void seed_keys_kernel(const int32_t* __restrict__ flag, const int32_t* __restrict__ pos,
+                                                        const int64_t* __restrict__ l2g, int64_t n, uint64_t h,
+                                                        uint64_t* __restrict__ keys, int32_t* __restrict__ ids) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v >= n || !flag[v]) return;
+    keys[pos[v]] = mixM(h ^ (uint64_t)l2g[v]);           // slots ascend with the local id: the stable sort keeps ties in that order
+    ids[pos[v]] = (int32_t)v;
+}
+}  // namespace grp
+
+extern "C" grp_status grp_epoch_seeds(const grp_partition_t* part, const uint8_t* train_mask, uint64_t sampler_seed,
+                                      uint64_t epoch, void* stream, int32_t* seeds_out, int64_t* n_seeds_out) {
+    using namespace grp;
+    if (!part || !n_seeds_out) return fail(GRP_EINVAL, "grp_epoch_seeds: null argument");
+    *n_seeds_out = 0;
+    const int64_t n = part->n;
+    if (n == 0) return GRP_OK;
+    if (!seeds_out) return fail(GRP_EINVAL, "grp_epoch_seeds: null output");
+    hipStream_t st = (hipStream_t)stream;
+    DevBuf flag, pos, keys, keys_alt, ids, tmp;
+    GRP_TRY(flag.alloc(((size_t)n + 1) * sizeof(int32_t)));
+    GRP_TRY(pos.alloc(((size_t)n + 1) * sizeof(int32_t)));
+    GRP_TRY(keys.alloc((size_t)n * sizeof(uint64_t)));
+    GRP_TRY(keys_alt.alloc((size_t)n * sizeof(uint64_t)));
+    GRP_TRY(ids.alloc((size_t)n * sizeof(int32_t)));
+    size_t sort_bytes = 0;
+    GRP_HIP(rocprim::radix_sort_pairs(nullptr, sort_bytes, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), ids.as<int32_t>(),
+                                      seeds_out, (size_t)n, 0u, 64u, st));
+    const size_t scan_bytes = scan_temp_bytes(n + 1);
+    GRP_TRY(tmp.alloc(sort_bytes > scan_bytes ? sort_bytes : scan_bytes));
+    hipLaunchKernelGGL(train_flag_kernel, dim3((unsigned)cdiv(n + 1, 256)), dim3(256), 0, st, train_mask, n, flag.as<int32_t>());
+    GRP_LAUNCH_CHECK();
+    GRP_TRY(exclusive_scan_i32(tmp.p, scan_bytes, flag.as<int32_t>(), pos.as<int32_t>(), n + 1, st));
+    hipLaunchKernelGGL(seed_keys_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, (const int32_t*)flag.as<int32_t>(),
+                       (const int32_t*)pos.as<int32_t>(), part->l2g, n, mixM(mixM(sampler_seed) ^ epoch), keys.as<uint64_t>(),
+                       ids.as<int32_t>());
+    GRP_LAUNCH_CHECK();
+    int32_t total = 0;
+    GRP_HIP(hipMemcpyAsync(&total, pos.as<int32_t>() + n, sizeof total, hipMemcpyDeviceToHost, st));
+    GRP_HIP(hipStreamSynchronize(st));
+    if (total > 0) {
+        GRP_HIP(rocprim::radix_sort_pairs(tmp.p, sort_bytes, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), ids.as<int32_t>(),
+                                          seeds_out, (size_t)total, 0u, 64u, st));
+        GRP_HIP(hipStreamSynchronize(st));               // the temporaries are released on return
+    }
+    *n_seeds_out = total;
+    return GRP_OK;
+}
+
 extern "C" grp_status grp_partition_weighted(const int64_t* src, const int64_t* dst, const float* w, int64_t E, int64_t N,
                                              int32_t K, uint64_t seed, int32_t part_id, void* stream,
                                              grp_partition_t** out) {

@@ -24,13 +24,6 @@ namespace grp {
 
 constexpr int SAMPLE_MAX_FANOUT = 64;         // one lane of a wavefront per chosen edge
 
-__host__ __device__ __forceinline__ uint64_t mixM(uint64_t x) {
-    uint64_t z = x + 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-
 // Per destination row: the number of edges it keeps and 1 / max(that, 1); above the input layer also
 // the row's place in the block's source list (destinations come first, in order) and in the node -> block
 // index map.  Element n_dst of `cnt` closes the prefix sum.

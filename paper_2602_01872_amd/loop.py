@@ -81,6 +81,77 @@ class PhaseParallelTrainer:
         return [float(g.read_stats(h)["loss"].mean()) for h in self.history]
 
 
+class MiniBatchTrainer:
+    """The phase-parallel loop in mini-batch mode (GraphSAGE): every epoch each partition visits its
+    training nodes once in the order ``grp_epoch_seeds`` gives, ``batch_size`` seeds per iteration; an epoch
+    has as many iterations as the partition with the most training nodes needs, and a partition whose
+    nodes are used up takes part with a zero gradient that still counts in the average.  Iteration i of
+    epoch e samples with batch_id = e * iterations_per_epoch + i.  Within an iteration the phases run as
+    in ``PhaseParallelTrainer``.  Sequencing only: the seed order, sampling, steps, reduction and update
+    are library calls.
+    """
+
+    def __init__(self, parts, model, xs, ys, masks, theta0, estimator, max_active, batch_size, fanouts,
+                 sampler_seed, optimizer=None):
+        self.parts, self.model, self.xs, self.ys, self.masks = parts, model, xs, ys, masks
+        self.estimator, self.max_active = estimator, max_active
+        self.batch_size, self.fanouts, self.sampler_seed = int(batch_size), tuple(fanouts), sampler_seed
+        self.opt = optimizer if optimizer is not None else g.optimizer_desc()
+        dev = theta0.device
+        self.P = g.grp_param_count(model)
+        self.ld = (self.P + 3) // 4 * 4
+        self.theta = theta0.detach().clone().to(torch.float32).contiguous()
+        self.m = torch.zeros(self.P, device=dev)
+        self.v = torch.zeros(self.P, device=dev)
+        self.update = torch.zeros(self.P, device=dev)
+        self.grads = torch.zeros(max_active, self.ld, device=dev)
+        self.stats = g.new_stats(max_active, device=dev)
+        self.seeds = [torch.zeros(max(p.n, 1), dtype=torch.int32, device=dev) for p in parts]
+        self.n_train = [p.n if mk is None else int(torch.count_nonzero(mk)) for p, mk in zip(parts, masks)]
+        self.iters = max(1, max(-(-c // self.batch_size) for c in self.n_train))
+        probe = g.step_opts(estimator=estimator, full_graph=False, seeds=self.seeds[0][:1], fanouts=self.fanouts)
+        ws_bytes = 0
+        for p, sd, c in zip(parts, self.seeds, self.n_train):       # the workspace is sized from the seed count alone
+            probe.n_seeds = max(1, min(self.batch_size, c))
+            ws_bytes = max(ws_bytes, g.grp_step_workspace_bytes(p, model, probe))
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.step_count = 0
+        self.epoch = 0
+        self.history = []
+
+    def phases(self):
+        K, M = len(self.parts), self.max_active
+        return [list(range(lo, min(K, lo + M))) for lo in range(0, K, M)]
+
+    def run_epoch(self):
+        B = self.batch_size
+        counts = [g.grp_epoch_seeds(p, mk, self.sampler_seed, self.epoch, sd)
+                  for p, mk, sd in zip(self.parts, self.masks, self.seeds)]
+        assert counts == self.n_train
+        for it in range(self.iters):
+            for active in self.phases():
+                for slot, p in enumerate(active):
+                    lo, hi = it * B, min((it + 1) * B, counts[p])
+                    st = self.stats[slot * g.STATS_BYTES:(slot + 1) * g.STATS_BYTES]
+                    if hi <= lo:                       # no seeds left: a zero gradient and an empty record
+                        self.grads[slot].zero_()
+                        st.zero_()
+                        continue
+                    opts = g.step_opts(estimator=self.estimator, full_graph=False, seeds=self.seeds[p][lo:hi],
+                                       fanouts=self.fanouts, sampler_seed=self.sampler_seed,
+                                       batch_id=self.epoch * self.iters + it)
+                    g.grp_train_step(self.parts[p], self.model, opts, self.xs[p], self.ys[p], None, self.theta,
+                                     self.ws, self.grads[slot], st)
+                g.grp_aggregate(self.grads, self.ld, self.stats, len(active), self.P, self.estimator, self.update)
+                self.step_count += 1
+                g.grp_optimizer_step(self.opt, self.P, self.step_count, self.theta, self.update, self.m, self.v)
+                self.history.append(self.stats[:len(active) * g.STATS_BYTES].clone())
+        self.epoch += 1
+
+    def losses(self):
+        return [float(g.read_stats(h)["loss"].mean()) for h in self.history]
+
+
 class SweepingTrainer:
     """Phase-parallel training over sweeping partitions: the graph is split once into chunks
     (``grp_chunks_build``); every super-epoch each worker's partition base + swept chunk is

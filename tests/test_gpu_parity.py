@@ -701,6 +701,65 @@ def test_phase_steps_on_several_streams_give_the_same_bits(g, arch):
         p.destroy()
 
 
+@pytest.mark.gpu
+def test_epoch_seed_order_bit_exact(g):
+    _note("epoch seed order")
+    N, E, K = 5000, 30000, 3
+    s, d = synth.uniform_graph(N, E, seed=61)
+    part = g.grp_partition(s.to(DEV), d.to(DEV), N, K, 1, 2)
+    op = ograph.partition(s.numpy(), d.numpy(), N, K, 1, 2)
+    n = part.n
+    third = (synth.stream_bits(3, 1, torch.arange(n)).numpy() % 3 == 0).astype(np.uint8)
+    out = torch.full((n,), -1, dtype=torch.int32, device=DEV)
+    for mask in (None, third, np.zeros(n, dtype=np.uint8), np.ones(n, dtype=np.uint8)):
+        for seed, epoch in ((7, 0), (7, 1), (2 ** 63 + 5, 12345678901)):
+            out.fill_(-1)
+            md = None if mask is None else torch.from_numpy(mask).to(DEV)
+            cnt = g.grp_epoch_seeds(part, md, seed, epoch, out)
+            want = osampling.epoch_seed_order(op, mask, seed, epoch)
+            assert cnt == want.size
+            assert np.array_equal(out[:cnt].cpu().numpy(), want.astype(np.int32))
+            assert bool((out[cnt:] == -1).all())                   # nothing is written past the count
+    part.destroy()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("M", [1, 2])
+def test_minibatch_phase_parallel_loop_matches_oracle(g, M):
+    """Two epochs of the mini-batch loop (K = 3 partitions of unequal training sets, so one runs out of
+    seeds before the others and takes part with empty batches): theta and the loss history."""
+    from oracle import optim as ooptim
+    _note(f"mini-batch loop M={M}")
+    N, E, K = 1500, 18000, 3
+    s, d = synth.rmat_graph(11, E, seed=71, n_nodes=N)
+    dims = [12, 24, 4]
+    x = synth.normal_matrix(N, dims[0], 72)
+    y = synth.planted_labels(x, dims[-1], 73)
+    theta0 = synth.model_weights("sage", dims, 74)
+    oparts = [ograph.partition(s.numpy(), d.numpy(), N, K, 1, p) for p in range(K)]
+    masks = [None, (np.arange(oparts[1]["n"]) % 3 == 0).astype(np.uint8), None]
+    oxs = [x.double().numpy()[p["l2g"]] for p in oparts]
+    oys = [y.numpy()[p["l2g"]] for p in oparts]
+    parts = [g.grp_partition(s.to(DEV), d.to(DEV), N, K, 1, p) for p in range(K)]
+    xs = [x.to(DEV)[torch.from_numpy(p["l2g"]).to(DEV)].contiguous() for p in oparts]
+    ys = [y.to(DEV)[torch.from_numpy(p["l2g"]).to(DEV)].contiguous() for p in oparts]
+    dmasks = [None if mk is None else torch.from_numpy(mk).to(DEV) for mk in masks]
+    model = g.model_desc(g.ARCH_SAGE_MEAN, dims)
+    B, fan, lr, n_epochs = 128, (4, 3), 0.05, 2
+    tr = g.MiniBatchTrainer(parts, model, xs, ys, dmasks, theta0.to(DEV), g.EST_SHRINKAGE, M, B, fan, 9,
+                            g.optimizer_desc(g.OPT_SGD, lr=lr))
+    for _ in range(n_epochs):
+        tr.run_epoch()
+    want, hist = ooptim.train_epochs_minibatch(oparts, "sage", dims, theta0.double().numpy(), oxs, oys, masks, n_epochs, M,
+                                               ocov.SHRINKAGE, B, fan, 9, optimizer=ooptim.SGD, lr=lr)
+    iters = max(-(-(p["n"] if mk is None else int(mk.sum())) // B) for p, mk in zip(oparts, masks))
+    assert tr.iters == iters and tr.step_count == len(hist) == n_epochs * iters * -(-K // M)
+    np.testing.assert_allclose(tr.losses(), hist, rtol=2e-4)
+    assert rel_err(tr.theta.cpu().double().numpy(), want) < TOL_FP32
+    for p in parts:
+        p.destroy()
+
+
 # ------------------------------------------------------------------ chunks and sweeping partitions
 @pytest.mark.gpu
 @pytest.mark.parametrize("kind,N,E,c", [("uniform", 3000, 40000, 4), ("rmat", 1 << 12, 150000, 3), ("uniform", 500, 0, 2),
