@@ -81,6 +81,46 @@ def train_epochs(parts, arch, dims, theta0, xs, ys, masks, n_epochs, max_active,
     return theta, history
 
 
+def _apply(optimizer, theta, G, m, v, t, lr):
+    if optimizer == ADAM:
+        return adam_step(theta, G, m, v, t, lr)
+    return sgd_step(theta, G, lr), m, v
+
+
+def minibatch_epoch(parts, arch, dims, state, xs, ys, masks, epoch, max_active, estimator, batch_size, fanouts,
+                    sampler_seed, optimizer, lr, on_step=None):
+    """One epoch of the mini-batch loop.  ``state`` = dict(theta, m, v, t, iteration) is updated in place:
+    ``t`` counts optimizer steps, ``iteration`` counts iterations (it is the sampler's batch_id, the same in
+    every partition of an iteration).  Returns the mean active loss of every optimizer step;
+    ``on_step(stats)`` is called after each one."""
+    n_train = [parts[p]["n"] if masks[p] is None else int(np.count_nonzero(masks[p])) for p in range(len(parts))]
+    iters = max(1, max(-(-c // batch_size) for c in n_train))
+    order = [sampling.epoch_seed_order(parts[p], masks[p], sampler_seed, epoch) for p in range(len(parts))]
+    history = []
+    for it in range(iters):
+        for active in phase_schedule(len(parts), max_active):
+            grads, stats = [], []
+            for p in active:
+                seeds = order[p][it * batch_size:(it + 1) * batch_size]
+                if seeds.size == 0:
+                    grads.append(np.zeros_like(state["theta"]))
+                    stats.append(dict(S=0, sum_ratio=0.0, R=0.0, loss=0.0, nnz_used=0))
+                    continue
+                mb = dict(seeds=seeds, fanouts=fanouts, sampler_seed=sampler_seed, batch_id=state["iteration"])
+                g, st = step.train_step(parts[p], arch, dims, state["theta"], xs[p], ys[p], estimator=estimator, minibatch=mb)
+                grads.append(g)
+                stats.append(st)
+            G, _ = coverage.aggregate(grads, stats, estimator)
+            state["t"] += 1
+            state["theta"], state["m"], state["v"] = _apply(optimizer, state["theta"], G, state["m"], state["v"],
+                                                            state["t"], lr)
+            history.append(float(np.mean([s["loss"] for s in stats])))
+            if on_step is not None:
+                on_step(stats)
+        state["iteration"] += 1
+    return history
+
+
 def train_epochs_minibatch(parts, arch, dims, theta0, xs, ys, masks, n_epochs, max_active, estimator, batch_size,
                            fanouts, sampler_seed, optimizer=ADAM, lr=0.003):
     """The phase-parallel algorithm in mini-batch mode.
@@ -88,45 +128,23 @@ def train_epochs_minibatch(parts, arch, dims, theta0, xs, ys, masks, n_epochs, m
     Every epoch each partition visits its training nodes once, in the order ``sampling.epoch_seed_order``
     gives, ``batch_size`` seeds per iteration; an epoch has as many iterations as the partition with the
     most training nodes needs, and a partition whose nodes are used up takes part with an empty batch (a
-    zero gradient that still counts in the average, as for a partition without loss nodes).  Iteration i
-    of epoch e samples with batch_id = e * iterations_per_epoch + i in every partition.  Within an
+    zero gradient that still counts in the average, as for a partition without loss nodes).  The sampler's
+    batch_id is the number of iterations done so far, the same in every partition.  Within an
     iteration the phases run as in ``train_epochs``: the active partitions step at the current theta,
     their gradients are scaled and averaged, one optimizer step follows.  Returns (theta, history).
     """
     theta = np.asarray(theta0, dtype=np.float64).copy()
-    m = np.zeros_like(theta)
-    v = np.zeros_like(theta)
-    t = 0
+    state = dict(theta=theta, m=np.zeros_like(theta), v=np.zeros_like(theta), t=0, iteration=0)
     history = []
-    n_train = [parts[p]["n"] if masks[p] is None else int(np.count_nonzero(masks[p])) for p in range(len(parts))]
-    iters = max(1, max(-(-c // batch_size) for c in n_train))
     for epoch in range(n_epochs):
-        order = [sampling.epoch_seed_order(parts[p], masks[p], sampler_seed, epoch) for p in range(len(parts))]
-        for it in range(iters):
-            for active in phase_schedule(len(parts), max_active):
-                grads, stats = [], []
-                for p in active:
-                    seeds = order[p][it * batch_size:(it + 1) * batch_size]
-                    if seeds.size == 0:
-                        grads.append(np.zeros_like(theta))
-                        stats.append(dict(S=0, sum_ratio=0.0, R=0.0, loss=0.0, nnz_used=0))
-                        continue
-                    mb = dict(seeds=seeds, fanouts=fanouts, sampler_seed=sampler_seed, batch_id=epoch * iters + it)
-                    g, st = step.train_step(parts[p], arch, dims, theta, xs[p], ys[p], estimator=estimator, minibatch=mb)
-                    grads.append(g)
-                    stats.append(st)
-                G, _ = coverage.aggregate(grads, stats, estimator)
-                t += 1
-                if optimizer == ADAM:
-                    theta, m, v = adam_step(theta, G, m, v, t, lr)
-                else:
-                    theta = sgd_step(theta, G, lr)
-                history.append(float(np.mean([s["loss"] for s in stats])))
-    return theta, history
+        history += minibatch_epoch(parts, arch, dims, state, xs, ys, masks, epoch, max_active, estimator, batch_size,
+                                   fanouts, sampler_seed, optimizer, lr)
+    return state["theta"], history
 
 
 def train_sweeping(src, dst, n_nodes, n_chunks, chunk_seed, arch, dims, theta0, x, y, train_mask, total_epochs,
-                   max_active, estimator, optimizer=ADAM, lr=0.003, controller=None, gcn_self_loops=True, dropout=None):
+                   max_active, estimator, optimizer=ADAM, lr=0.003, controller=None, gcn_self_loops=True, dropout=None,
+                   minibatch=None):
     """The phase-parallel algorithm over sweeping partitions (chunks + controller).
 
     The graph (global edge list ``src -> dst``, features ``x[n_nodes, F]``, labels ``y``, optional
@@ -137,6 +155,9 @@ def train_sweeping(src, dst, n_nodes, n_chunks, chunk_seed, arch, dims, theta0, 
     (theta, history, switches) with history the mean active loss per optimizer step and
     switches the list of epochs (0-based) after which the partitions were switched.
     ``dropout`` as in ``train_epochs`` (batch_id = optimizer steps taken so far, across super-epochs).
+    ``minibatch = dict(batch_size=, fanouts=, sampler_seed=)``: every epoch is a mini-batch epoch
+    (``minibatch_epoch``) over the current partitions, the seed order keyed by the global epoch number and
+    the iteration count running on across super-epochs.
     """
     ctl = controller if controller is not None else chunks.Controller(total_epochs, n_chunks)
     x = np.asarray(x, dtype=np.float64)
@@ -146,6 +167,7 @@ def train_sweeping(src, dst, n_nodes, n_chunks, chunk_seed, arch, dims, theta0, 
     m = np.zeros_like(theta)
     v = np.zeros_like(theta)
     t = 0
+    iteration = 0
     history, switches = [], []
     parts = None
     for epoch in range(total_epochs):
@@ -154,7 +176,15 @@ def train_sweeping(src, dst, n_nodes, n_chunks, chunk_seed, arch, dims, theta0, 
             xs = [x[p["l2g"]] for p in parts]
             ys = [y[p["l2g"]] for p in parts]
             masks = [p["base_mask"] & tm[p["l2g"]] for p in parts]
-        for active in phase_schedule(len(parts), max_active):
+        if minibatch is not None:
+            state = dict(theta=theta, m=m, v=v, t=t, iteration=iteration)
+            history += minibatch_epoch(parts, arch, dims, state, xs, ys, masks, epoch, max_active, estimator,
+                                       minibatch["batch_size"], minibatch["fanouts"], minibatch["sampler_seed"],
+                                       optimizer, lr,
+                                       on_step=lambda stats: ctl.observe_step([coverage.factor(s, coverage.BATCH_MIN_DIST)
+                                                                               for s in stats]))
+            theta, m, v, t, iteration = state["theta"], state["m"], state["v"], state["t"], state["iteration"]
+        for active in (phase_schedule(len(parts), max_active) if minibatch is None else []):
             grads, stats = [], []
             for p in active:
                 g, st = step.train_step(parts[p], arch, dims, theta, xs[p], ys[p], masks[p], estimator=estimator,

@@ -85,8 +85,8 @@ class MiniBatchTrainer:
     """The phase-parallel loop in mini-batch mode (GraphSAGE): every epoch each partition visits its
     training nodes once in the order ``grp_epoch_seeds`` gives, ``batch_size`` seeds per iteration; an epoch
     has as many iterations as the partition with the most training nodes needs, and a partition whose
-    nodes are used up takes part with a zero gradient that still counts in the average.  Iteration i of
-    epoch e samples with batch_id = e * iterations_per_epoch + i.  Within an iteration the phases run as
+    nodes are used up takes part with a zero gradient that still counts in the average.  The sampler's
+    batch_id is the number of iterations done so far (``iteration``).  Within an iteration the phases run as
     in ``PhaseParallelTrainer``.  Sequencing only: the seed order, sampling, steps, reduction and update
     are library calls.
     """
@@ -117,6 +117,7 @@ class MiniBatchTrainer:
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         self.step_count = 0
         self.epoch = 0
+        self.iteration = 0
         self.history = []
 
     def phases(self):
@@ -138,14 +139,14 @@ class MiniBatchTrainer:
                         st.zero_()
                         continue
                     opts = g.step_opts(estimator=self.estimator, full_graph=False, seeds=self.seeds[p][lo:hi],
-                                       fanouts=self.fanouts, sampler_seed=self.sampler_seed,
-                                       batch_id=self.epoch * self.iters + it)
+                                       fanouts=self.fanouts, sampler_seed=self.sampler_seed, batch_id=self.iteration)
                     g.grp_train_step(self.parts[p], self.model, opts, self.xs[p], self.ys[p], None, self.theta,
                                      self.ws, self.grads[slot], st)
                 g.grp_aggregate(self.grads, self.ld, self.stats, len(active), self.P, self.estimator, self.update)
                 self.step_count += 1
                 g.grp_optimizer_step(self.opt, self.P, self.step_count, self.theta, self.update, self.m, self.v)
                 self.history.append(self.stats[:len(active) * g.STATS_BYTES].clone())
+            self.iteration += 1
         self.epoch += 1
 
     def losses(self):
@@ -158,10 +159,16 @@ class SweepingTrainer:
     rebuilt on the GPU (``grp_partition_from_chunks``) and its rows of the global feature /
     label / mask tensors are gathered by ``l2g``; the controller decides after each epoch
     whether to switch.  theta and the optimizer state persist across super-epochs.
+    ``minibatch = dict(batch_size=, fanouts=, sampler_seed=)``: every epoch is a mini-batch epoch
+    (``MiniBatchTrainer``) over the current partitions; the epoch number and the iteration count run on
+    across super-epochs.
     """
 
     def __init__(self, src, dst, n_nodes, n_chunks, chunk_seed, model, x, y, train_mask, theta0, estimator,
-                 max_active, total_epochs, optimizer=None, controller=None, dropout_rate=0.0, dropout_seed=0):
+                 max_active, total_epochs, optimizer=None, controller=None, dropout_rate=0.0, dropout_seed=0,
+                 minibatch=None):
+        self.minibatch = minibatch
+        self.iteration = 0
         self.chunks = g.grp_chunks_build(src, dst, n_nodes, n_chunks, chunk_seed)
         self.dropout_rate, self.dropout_seed = dropout_rate, dropout_seed
         self.model, self.x, self.y, self.train_mask = model, x, y, train_mask
@@ -190,8 +197,14 @@ class SweepingTrainer:
             xs.append(self.x[l2g].contiguous())
             ys.append(self.y[l2g].contiguous())
             masks.append(mask.contiguous())
-        tr = PhaseParallelTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active, self.opt,
-                                  dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed)
+        if self.minibatch is not None:
+            mb = self.minibatch
+            tr = MiniBatchTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active,
+                                  mb["batch_size"], mb["fanouts"], mb["sampler_seed"], self.opt)
+            tr.epoch, tr.iteration = self.epoch, self.iteration
+        else:
+            tr = PhaseParallelTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active, self.opt,
+                                      dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed)
         tr.theta, tr.m, tr.v, tr.step_count = self.theta, self.m, self.v, self.step_count   # carried state
         return tr
 
@@ -201,6 +214,8 @@ class SweepingTrainer:
         first = len(self.inner.history)
         self.inner.run_epoch()
         self.step_count = self.inner.step_count
+        if self.minibatch is not None:
+            self.iteration = self.inner.iteration
         for h in self.inner.history[first:]:
             rec = g.read_stats(h)
             self._losses.append(float(rec["loss"].mean()))

@@ -39,3 +39,35 @@ def test_sweeping_loop_matches_oracle(c, M, masked, drop):
     assert tr.step_count == len(hist)
     np.testing.assert_allclose(tr.losses(), hist, rtol=2e-4)
     assert rel_err(tr.theta.cpu().double().numpy(), want) < TOL_FP32
+
+
+@pytest.mark.parametrize("c,M,masked", [(3, 2, True), (2, 2, False)])
+def test_sweeping_minibatch_loop_matches_oracle(c, M, masked):
+    """The loop as the paper runs it: sweeping partitions, mini-batches over every worker's training nodes,
+    the shrinkage factor per batch; partitions are rebuilt at the switches and the epoch / iteration counts
+    that key the seed order and the sampler run on across them."""
+    import paper_2602_01872_amd as g
+    g.load()
+    print(f"[case] sweeping mini-batch loop c={c} M={M} masked={masked}", flush=True)
+    N, E = 1800, 20000
+    s, d = synth.rmat_graph(11, E, seed=96, n_nodes=N)
+    dims = [10, 20, 4]
+    x = synth.normal_matrix(N, dims[0], 97)
+    y = synth.planted_labels(x, dims[-1], 98)
+    tm = synth.train_mask(N, 0.5, 99) if masked else None
+    theta0 = synth.model_weights("sage", dims, 100)
+    total_epochs = 2 * max(1, c - 1) if c > 2 else 3
+    lr = 0.05
+    mb = dict(batch_size=96, fanouts=(5, 4), sampler_seed=13)
+    tr = g.SweepingTrainer(s.to(DEV), d.to(DEV), N, c, 17, g.model_desc(g.ARCH_SAGE_MEAN, dims), x.to(DEV), y.to(DEV),
+                           None if tm is None else tm.to(DEV), theta0.to(DEV), g.EST_SHRINKAGE, M, total_epochs,
+                           g.optimizer_desc(g.OPT_SGD, lr=lr), minibatch=mb)
+    for _ in range(total_epochs):
+        tr.run_epoch()
+    want, hist, switches = ooptim.train_sweeping(s.numpy(), d.numpy(), N, c, 17, "sage", dims, theta0.double().numpy(),
+                                                 x.double().numpy(), y.numpy(), None if tm is None else tm.numpy(),
+                                                 total_epochs, M, ocov.SHRINKAGE, optimizer=ooptim.SGD, lr=lr, minibatch=mb)
+    assert tr.switches == switches
+    assert tr.step_count == len(hist) and tr.step_count > 3 * total_epochs
+    np.testing.assert_allclose(tr.losses(), hist, rtol=2e-4)
+    assert rel_err(tr.theta.cpu().double().numpy(), want) < TOL_FP32

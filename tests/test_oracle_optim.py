@@ -187,3 +187,24 @@ def test_minibatch_epochs_visit_every_training_node_once_and_learn():
     from oracle import sampling
     order = sampling.epoch_seed_order(parts[1], masks[1], 9, 0)
     assert order.size == n_train[1] < max(n_train)
+
+
+def test_sweeping_minibatch_with_one_full_batch_is_sweeping_full_graph():
+    # same reduction as above through the chunk / controller loop: identical theta, losses and switches
+    N = 300
+    s, d = synth.uniform_graph(N, 2400, seed=8)
+    s, d = s.numpy(), d.numpy()
+    dims = [6, 10, 3]
+    x = synth.normal_matrix(N, 6, 21)
+    y = synth.planted_labels(x, 3, 22).numpy()
+    tm = (np.arange(N) % 5 != 0).astype(np.uint8)
+    theta0 = synth.model_weights("sage", dims, 23).double().numpy()
+    big = int(np.bincount(d, minlength=N).max()) + 1
+    want = optim.train_sweeping(s, d, N, 3, 4, "sage", dims, theta0, x.double().numpy(), y, tm, 8, 2,
+                                cov.BATCH_MIN_DIST, optimizer=optim.ADAM, lr=0.01)
+    got = optim.train_sweeping(s, d, N, 3, 4, "sage", dims, theta0, x.double().numpy(), y, tm, 8, 2,
+                               cov.BATCH_MIN_DIST, optimizer=optim.ADAM, lr=0.01,
+                               minibatch=dict(batch_size=10 ** 6, fanouts=(big, big), sampler_seed=3))
+    np.testing.assert_allclose(got[0], want[0], rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(got[1], want[1], rtol=1e-10)
+    assert got[2] == want[2] and len(want[2]) >= 2
