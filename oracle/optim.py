@@ -88,10 +88,11 @@ def _apply(optimizer, theta, G, m, v, t, lr):
 
 
 def minibatch_epoch(parts, arch, dims, state, xs, ys, masks, epoch, max_active, estimator, batch_size, fanouts,
-                    sampler_seed, optimizer, lr, on_step=None):
+                    sampler_seed, optimizer, lr, on_step=None, dropout=None):
     """One epoch of the mini-batch loop.  ``state`` = dict(theta, m, v, t, iteration) is updated in place:
     ``t`` counts optimizer steps, ``iteration`` counts iterations (it is the sampler's batch_id, the same in
-    every partition of an iteration).  Returns the mean active loss of every optimizer step;
+    every partition of an iteration, and also the batch_id of the dropout masks when
+    ``dropout = dict(rate=, seed=)`` is given).  Returns the mean active loss of every optimizer step;
     ``on_step(stats)`` is called after each one."""
     n_train = [parts[p]["n"] if masks[p] is None else int(np.count_nonzero(masks[p])) for p in range(len(parts))]
     iters = max(1, max(-(-c // batch_size) for c in n_train))
@@ -107,7 +108,8 @@ def minibatch_epoch(parts, arch, dims, state, xs, ys, masks, epoch, max_active, 
                     stats.append(dict(S=0, sum_ratio=0.0, R=0.0, loss=0.0, nnz_used=0))
                     continue
                 mb = dict(seeds=seeds, fanouts=fanouts, sampler_seed=sampler_seed, batch_id=state["iteration"])
-                g, st = step.train_step(parts[p], arch, dims, state["theta"], xs[p], ys[p], estimator=estimator, minibatch=mb)
+                g, st = step.train_step(parts[p], arch, dims, state["theta"], xs[p], ys[p], estimator=estimator, minibatch=mb,
+                                        dropout=dropout)
                 grads.append(g)
                 stats.append(st)
             G, _ = coverage.aggregate(grads, stats, estimator)
@@ -122,7 +124,7 @@ def minibatch_epoch(parts, arch, dims, state, xs, ys, masks, epoch, max_active, 
 
 
 def train_epochs_minibatch(parts, arch, dims, theta0, xs, ys, masks, n_epochs, max_active, estimator, batch_size,
-                           fanouts, sampler_seed, optimizer=ADAM, lr=0.003):
+                           fanouts, sampler_seed, optimizer=ADAM, lr=0.003, dropout=None):
     """The phase-parallel algorithm in mini-batch mode.
 
     Every epoch each partition visits its training nodes once, in the order ``sampling.epoch_seed_order``
@@ -138,7 +140,7 @@ def train_epochs_minibatch(parts, arch, dims, theta0, xs, ys, masks, n_epochs, m
     history = []
     for epoch in range(n_epochs):
         history += minibatch_epoch(parts, arch, dims, state, xs, ys, masks, epoch, max_active, estimator, batch_size,
-                                   fanouts, sampler_seed, optimizer, lr)
+                                   fanouts, sampler_seed, optimizer, lr, dropout=dropout)
     return state["theta"], history
 
 
@@ -182,7 +184,8 @@ def train_sweeping(src, dst, n_nodes, n_chunks, chunk_seed, arch, dims, theta0, 
                                        minibatch["batch_size"], minibatch["fanouts"], minibatch["sampler_seed"],
                                        optimizer, lr,
                                        on_step=lambda stats: ctl.observe_step([coverage.factor(s, coverage.BATCH_MIN_DIST)
-                                                                               for s in stats]))
+                                                                               for s in stats]),
+                                       dropout=dropout)
             theta, m, v, t, iteration = state["theta"], state["m"], state["v"], state["t"], state["iteration"]
         for active in (phase_schedule(len(parts), max_active) if minibatch is None else []):
             grads, stats = [], []

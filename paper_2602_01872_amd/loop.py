@@ -92,7 +92,8 @@ class MiniBatchTrainer:
     """
 
     def __init__(self, parts, model, xs, ys, masks, theta0, estimator, max_active, batch_size, fanouts,
-                 sampler_seed, optimizer=None):
+                 sampler_seed, optimizer=None, dropout_rate=0.0, dropout_seed=0):
+        self.dropout_rate, self.dropout_seed = dropout_rate, dropout_seed
         self.parts, self.model, self.xs, self.ys, self.masks = parts, model, xs, ys, masks
         self.estimator, self.max_active = estimator, max_active
         self.batch_size, self.fanouts, self.sampler_seed = int(batch_size), tuple(fanouts), sampler_seed
@@ -139,7 +140,8 @@ class MiniBatchTrainer:
                         st.zero_()
                         continue
                     opts = g.step_opts(estimator=self.estimator, full_graph=False, seeds=self.seeds[p][lo:hi],
-                                       fanouts=self.fanouts, sampler_seed=self.sampler_seed, batch_id=self.iteration)
+                                       fanouts=self.fanouts, sampler_seed=self.sampler_seed, batch_id=self.iteration,
+                                       dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed)
                     g.grp_train_step(self.parts[p], self.model, opts, self.xs[p], self.ys[p], None, self.theta,
                                      self.ws, self.grads[slot], st)
                 g.grp_aggregate(self.grads, self.ld, self.stats, len(active), self.P, self.estimator, self.update)
@@ -200,7 +202,8 @@ class SweepingTrainer:
         if self.minibatch is not None:
             mb = self.minibatch
             tr = MiniBatchTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active,
-                                  mb["batch_size"], mb["fanouts"], mb["sampler_seed"], self.opt)
+                                  mb["batch_size"], mb["fanouts"], mb["sampler_seed"], self.opt,
+                                  dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed)
             tr.epoch, tr.iteration = self.epoch, self.iteration
         else:
             tr = PhaseParallelTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active, self.opt,

@@ -41,14 +41,14 @@ def test_sweeping_loop_matches_oracle(c, M, masked, drop):
     assert rel_err(tr.theta.cpu().double().numpy(), want) < TOL_FP32
 
 
-@pytest.mark.parametrize("c,M,masked", [(3, 2, True), (2, 2, False)])
-def test_sweeping_minibatch_loop_matches_oracle(c, M, masked):
+@pytest.mark.parametrize("c,M,masked,drop", [(3, 2, True, 0.0), (2, 2, False, 0.0), (3, 3, False, 0.5)])
+def test_sweeping_minibatch_loop_matches_oracle(c, M, masked, drop):
     """The loop as the paper runs it: sweeping partitions, mini-batches over every worker's training nodes,
     the shrinkage factor per batch; partitions are rebuilt at the switches and the epoch / iteration counts
     that key the seed order and the sampler run on across them."""
     import paper_2602_01872_amd as g
     g.load()
-    print(f"[case] sweeping mini-batch loop c={c} M={M} masked={masked}", flush=True)
+    print(f"[case] sweeping mini-batch loop c={c} M={M} masked={masked} dropout={drop}", flush=True)
     N, E = 1800, 20000
     s, d = synth.rmat_graph(11, E, seed=96, n_nodes=N)
     dims = [10, 20, 4]
@@ -61,12 +61,13 @@ def test_sweeping_minibatch_loop_matches_oracle(c, M, masked):
     mb = dict(batch_size=96, fanouts=(5, 4), sampler_seed=13)
     tr = g.SweepingTrainer(s.to(DEV), d.to(DEV), N, c, 17, g.model_desc(g.ARCH_SAGE_MEAN, dims), x.to(DEV), y.to(DEV),
                            None if tm is None else tm.to(DEV), theta0.to(DEV), g.EST_SHRINKAGE, M, total_epochs,
-                           g.optimizer_desc(g.OPT_SGD, lr=lr), minibatch=mb)
+                           g.optimizer_desc(g.OPT_SGD, lr=lr), minibatch=mb, dropout_rate=drop, dropout_seed=43)
     for _ in range(total_epochs):
         tr.run_epoch()
     want, hist, switches = ooptim.train_sweeping(s.numpy(), d.numpy(), N, c, 17, "sage", dims, theta0.double().numpy(),
                                                  x.double().numpy(), y.numpy(), None if tm is None else tm.numpy(),
-                                                 total_epochs, M, ocov.SHRINKAGE, optimizer=ooptim.SGD, lr=lr, minibatch=mb)
+                                                 total_epochs, M, ocov.SHRINKAGE, optimizer=ooptim.SGD, lr=lr, minibatch=mb,
+                                                 dropout=dict(rate=drop, seed=43) if drop > 0 else None)
     assert tr.switches == switches
     assert tr.step_count == len(hist) and tr.step_count > 3 * total_epochs
     np.testing.assert_allclose(tr.losses(), hist, rtol=2e-4)
