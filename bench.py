@@ -219,6 +219,49 @@ def run_evidence_workload(args, g, synth, torch, dev):
         print(json.dumps(out), flush=True)
         return
 
+    if wl == "c2-minibatch-epoch":
+        # the loop as the paper's experiments run it, on the headline graph: 8 hash partitions trained in turn on
+        # the one GPU (phase-parallel, M = 1 worker's worth of memory at a time is not needed: all 8 are resident),
+        # mini-batches of 1024 seeds with fanouts (15, 10, 5) over every partition's training nodes (8 % of the
+        # nodes, the share of the products-sized dataset), shrinkage factor per batch, Adam, dropout 0.5.
+        src, dst = synth.rmat_graph(RMAT_SCALE, N_EDGES, seed=GRAPH_SEED, n_nodes=N_NODES, device=dev)
+        parts = [g.grp_partition(src, dst, N_NODES, K_PARTS, PART_SEED, p) for p in range(K_PARTS)]
+        del src, dst
+        dims = [100, 256, 256, 47]
+        model = g.model_desc(g.ARCH_SAGE_MEAN, dims)
+        xg = synth.normal_matrix(N_NODES, dims[0], GRAPH_SEED, device=dev)
+        yg = synth.labels(N_NODES, dims[-1], GRAPH_SEED, device=dev)
+        tmg = synth.train_mask(N_NODES, 0.08, GRAPH_SEED, device=dev)
+        l2gs = [torch.from_numpy(p.array("l2g")).to(dev) for p in parts]
+        xs = [xg[i].contiguous() for i in l2gs]
+        ys = [yg[i].contiguous() for i in l2gs]
+        masks = [tmg[i].contiguous() for i in l2gs]
+        del xg, yg, tmg
+        theta = synth.model_weights("sage", dims, GRAPH_SEED, device=dev)
+        tr = g.MiniBatchTrainer(parts, model, xs, ys, masks, theta, g.EST_SHRINKAGE, K_PARTS, 1024, (15, 10, 5), 7,
+                                g.optimizer_desc(g.OPT_ADAM, lr=0.003), dropout_rate=0.5, dropout_seed=1)
+        for _ in range(max(1, args.warmup // 3)):
+            tr.run_epoch()
+        torch.cuda.synchronize()
+        first = len(tr.history)
+        epochs = max(1, args.steps // 10)
+        t0 = time.perf_counter()
+        for _ in range(epochs):
+            tr.run_epoch()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / epochs
+        used = sum(int(g.read_stats(h)["nnz_used"].sum()) for h in tr.history[first:]) / epochs
+        out.update(metric="sampled edges/s over one mini-batch epoch of all 8 partitions (fwd+bwd, aggregate, Adam)",
+                   unit="edges/s", value=used / dt, ms_per_step=dt * 1e3, dtype="f32", steps=epochs,
+                   config={"workload": f"c2-minibatch-epoch: SAGE-mean-3 {dims}, fanouts (15,10,5), 1024 seeds per batch, "
+                                       f"8 partitions of the R-MAT 2.4M-node / 62M-edge graph, {sum(tr.n_train)} training nodes",
+                           "ms_per_epoch": dt * 1e3, "iterations_per_epoch": tr.iters,
+                           "train_steps_per_epoch": tr.iters * K_PARTS, "sampled_edges_per_epoch": used,
+                           "losses_first_last": [tr.losses()[0], tr.losses()[-1]]},
+                   roofline=None)
+        print(json.dumps(out), flush=True)
+        return
+
     if wl in ("c2-gat-step", "c2-dropout-step", "c2-weighted-step"):
         # the headline workload's partition with the attention model in place of GraphSAGE, with
         # GraphSAGE and dropout 0.5 on the hidden layers, or with weighted edges (weighted-mean GraphSAGE)
@@ -358,7 +401,7 @@ def main():
     ap.add_argument("--small", action="store_true", help="scaled-down graph (debugging only; not a valid result)")
     ap.add_argument("--shapes", action="store_true", help="per-launch-shape kernel table on stderr (debugging)")
     ap.add_argument("--workload", default="c2-step",
-                    choices=["c2-step", "c1-step", "c2-gat-step", "c2-dropout-step", "c2-weighted-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "c5-step", "aggregate-stress"],
+                    choices=["c2-step", "c1-step", "c2-minibatch-epoch", "c2-gat-step", "c2-dropout-step", "c2-weighted-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "c5-step", "aggregate-stress"],
                     help="c2-step (default) is the headline workload; the others are evidence runs for the other "
                          "configurations (each prints one JSON line of the same form)")
     ap.add_argument("--copy-calibration", action="store_true",
