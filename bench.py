@@ -219,6 +219,58 @@ def run_evidence_workload(args, g, synth, torch, dev):
         print(json.dumps(out), flush=True)
         return
 
+    if wl == "c2-partition-build":
+        # the partition builders on the headline graph (what a super-epoch switch costs): one partition of 8 by
+        # hash from the whole edge list, the one-off split into 8 chunks, base + swept chunk from the chunks,
+        # the 1-hop halo variant and the weighted variant.  One "step" = one grp_partition call.
+        src, dst = synth.rmat_graph(RMAT_SCALE, N_EDGES, seed=GRAPH_SEED, n_nodes=N_NODES, device=dev)
+        ew = synth.edge_weights(N_EDGES, GRAPH_SEED, device=dev)
+        torch.cuda.synchronize()
+
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / reps
+
+        def build(make):
+            def fn():
+                p = make()
+                fn.nnz = p.nnz
+                p.destroy()
+            return fn
+        reps = max(3, args.steps // 5)
+        full = build(lambda: g.grp_partition(src, dst, N_NODES, K_PARTS, PART_SEED, PART_ID))
+        dt_full = timed(full, reps)
+        t0 = time.perf_counter()
+        ck = g.grp_chunks_build(src, dst, N_NODES, K_PARTS, PART_SEED)
+        torch.cuda.synchronize()
+        dt_chunks = time.perf_counter() - t0
+        alone = build(lambda: g.grp_partition_from_chunks(ck, 0, 0))
+        pair = build(lambda: g.grp_partition_from_chunks(ck, 0, 3))
+        halo = build(lambda: g.grp_partition_halo(src, dst, N_NODES, K_PARTS, PART_SEED, PART_ID, 1))
+        wgt = build(lambda: g.grp_partition_weighted(src, dst, ew, N_NODES, K_PARTS, PART_SEED, PART_ID))
+        times = {"grp_partition_ms": dt_full * 1e3, "grp_chunks_build_once_ms": dt_chunks * 1e3,
+                 "from_chunks_base_alone_ms": timed(alone, reps) * 1e3, "from_chunks_base_plus_swept_ms": timed(pair, reps) * 1e3,
+                 "grp_partition_halo_1hop_ms": timed(halo, 3) * 1e3, "grp_partition_weighted_ms": timed(wgt, 3) * 1e3,
+                 "local_edges": {"hash": full.nnz, "base_alone": alone.nnz, "base_plus_swept": pair.nnz, "halo": halo.nnz}}
+        ck.destroy()
+        kernels = _kernel_table(g, torch, full, reps)        # the two passes over the edge list
+        dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+        out.update(metric="edges/s scanned by grp_partition (one partition of 8 from the whole edge list)", unit="edges/s",
+                   value=N_EDGES / dt_full, ms_per_step=dt_full * 1e3, dtype="int64", steps=reps,
+                   config={"workload": "c2-partition-build: the partition builders on the R-MAT 2.4M-node / 62M-edge graph, K = c = 8",
+                           **times},
+                   roofline={"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["gbs"], "peak": PEAK_HBM_GBS,
+                             "unit": "GB/s", "frac": kernels[dom]["gbs"] / PEAK_HBM_GBS, "traffic": None,
+                             "avg_launch_us": kernels[dom]["avg_us"],
+                             "whole_call_GBs": 16.0 * N_EDGES / dt_full / 1e9}, kernels=kernels)
+        print(json.dumps(out), flush=True)
+        return
+
     if wl == "c2-minibatch-epoch":
         # the loop as the paper's experiments run it, on the headline graph: 8 hash partitions trained in turn on
         # the one GPU (phase-parallel, M = 1 worker's worth of memory at a time is not needed: all 8 are resident),
@@ -401,7 +453,7 @@ def main():
     ap.add_argument("--small", action="store_true", help="scaled-down graph (debugging only; not a valid result)")
     ap.add_argument("--shapes", action="store_true", help="per-launch-shape kernel table on stderr (debugging)")
     ap.add_argument("--workload", default="c2-step",
-                    choices=["c2-step", "c1-step", "c2-minibatch-epoch", "c2-gat-step", "c2-dropout-step", "c2-weighted-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "c5-step", "aggregate-stress"],
+                    choices=["c2-step", "c1-step", "c2-partition-build", "c2-minibatch-epoch", "c2-gat-step", "c2-dropout-step", "c2-weighted-step", "c3-step", "c4-step", "c4-spmm", "c5-spmm", "c5-step", "aggregate-stress"],
                     help="c2-step (default) is the headline workload; the others are evidence runs for the other "
                          "configurations (each prints one JSON line of the same form)")
     ap.add_argument("--copy-calibration", action="store_true",

@@ -97,6 +97,8 @@ struct grp_partition_s {
     double* w_local_in = nullptr;
     double* w_global_in = nullptr;
     uint8_t* base_mask = nullptr;    // partitions built from chunks: 1 for the base chunk's nodes
+    void* slab = nullptr;            // one allocation that holds the CSR / CSC arrays and the long-row schedules
+    size_t slab_bytes = 0;
     int device = 0;
 };
 

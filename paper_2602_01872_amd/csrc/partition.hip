@@ -61,21 +61,103 @@ __global__ __launch_bounds__(256) void scatter_l2g_kernel(int64_t N, const int32
     if (v < N && flag[v]) l2g[pos[v]] = v;
 }
 
+// Edges e and e + 1 (e even) of an id array with one 16-byte load when the array allows it; `fill` past the end.
+typedef int64_t i64x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void load_edge_pair(const int64_t* __restrict__ p, int64_t e, int64_t E, bool vec, int64_t fill,
+                                               int64_t& a, int64_t& b) {
+    if (vec && e + 1 < E) {
+        const i64x2 t = *reinterpret_cast<const i64x2*>(p + e);
+        a = t.x;
+        b = t.y;
+    } else {
+        a = e < E ? p[e] : fill;
+        b = e + 1 < E ? p[e + 1] : fill;
+    }
+}
+
+// A node set as a bitmap plus the number of members before each 32-node word: membership and the
+// member's rank (its local id) from two small arrays that stay in the L2 caches (N / 4 bytes in all),
+// where per-node flag and position arrays (12 bytes per node) cost a cache line from HBM per lookup.
+struct NodeSet {
+    const uint32_t* bits;
+    const int32_t* before;
+};
+__device__ __forceinline__ bool set_has(const NodeSet& s, int64_t v) { return (s.bits[v >> 5] >> (v & 31)) & 1u; }
+__device__ __forceinline__ int32_t set_rank(const NodeSet& s, int64_t v) {
+    return s.before[v >> 5] + __popc(s.bits[v >> 5] & ((1u << (v & 31)) - 1u));
+}
+
+// bits[w] = flags of nodes 32w .. 32w+31; the grid covers n_words * 32 nodes
+__global__ __launch_bounds__(256) void pack_bits_kernel(const int32_t* __restrict__ flag, int64_t N, int64_t n_words,
+                                                        uint32_t* __restrict__ bits) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const unsigned long long m = __ballot(v < N && flag[v] != 0);
+    const int64_t w = v >> 5;
+    if ((threadIdx.x & 63) == 0 && w < n_words) {
+        bits[w] = (uint32_t)m;
+        if (w + 1 < n_words) bits[w + 1] = (uint32_t)(m >> 32);
+    }
+}
+
 // Pass 1 over the edges: id range check, global in-degree of owned destinations, count of kept edges.
+// The in-degree counts go through a table in LDS first (open addressing on the local id, a few probes,
+// LDS atomics) and reach memory once per workgroup and node: a hub of a skewed graph receives 10^5..10^6
+// edges, and that many atomics on one address serialise in the L2 (they set the time of this pass before).
+// An edge that finds no slot adds to memory directly.
+constexpr int DG_SLOTS = 4096;
+constexpr int DG_PROBES = 4;
+constexpr int EDGE_SCAN_GRID = 4096;      // fat workgroups: more edges of a hub meet in one table
+
 __global__ __launch_bounds__(256) void edge_scan_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
-                                                        int64_t E, int64_t N, const int32_t* __restrict__ flag,
-                                                        const int64_t* __restrict__ pos,
+                                                        int64_t E, int64_t N, NodeSet own,
                                                         unsigned long long* __restrict__ dg,
                                                         unsigned long long* __restrict__ counters /*[0]=kept,[1]=bad*/) {
+    const bool vec = (((uintptr_t)src | (uintptr_t)dst) & 15) == 0;
+    __shared__ int32_t slot_key[DG_SLOTS];
+    __shared__ uint32_t slot_count[DG_SLOTS];
+    for (int i = threadIdx.x; i < DG_SLOTS; i += 256) { slot_key[i] = -1; slot_count[i] = 0u; }
+    __syncthreads();
     unsigned long long kept = 0, bad = 0;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
-        const int64_t u = src[e], v = dst[e];
-        if (u < 0 || v < 0 || u >= N || v >= N) { bad++; continue; }
-        if (flag[v]) {
-            atomicAdd(&dg[pos[v]], 1ull);
-            if (flag[u]) kept++;
+    constexpr int PER = 8;                               // edges per thread and tile: their loads are in flight together
+    const int64_t n_tiles = (E + 256 * PER - 1) / (256 * PER);
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t e0 = tile * (256 * PER) + 2 * threadIdx.x;
+        int64_t us[PER], vs[PER];
+#pragma unroll
+        for (int i = 0; i < PER; i += 2) {               // a thread takes pairs of consecutive edges
+            const int64_t e = e0 + (int64_t)i * 256;
+            load_edge_pair(src, e, E, vec, 0, us[i], us[i + 1]);
+            load_edge_pair(dst, e, E, vec, -2, vs[i], vs[i + 1]);     // -2: past the end, neither counted nor an error
+        }
+        bool mine[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int64_t u = us[i], v = vs[i];
+            mine[i] = false;
+            if (v == -2) continue;
+            if (u < 0 || v < 0 || u >= N || v >= N) { bad++; continue; }
+            mine[i] = set_has(own, v);
+        }
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            if (!mine[i]) continue;
+            const int32_t r = set_rank(own, vs[i]);
+            uint32_t h = (uint32_t)r * 2654435761u >> 20;            // top 12 bits of a multiplicative hash
+            bool placed = false;
+            for (int probe = 0; probe < DG_PROBES && !placed; ++probe, h = (h + 1) & (DG_SLOTS - 1)) {
+                const int32_t seen = atomicCAS(&slot_key[h], -1, r);
+                if (seen == -1 || seen == r) {
+                    atomicAdd(&slot_count[h], 1u);
+                    placed = true;
+                }
+            }
+            if (!placed) atomicAdd(&dg[r], 1ull);
+            if (set_has(own, us[i])) kept++;
         }
     }
+    __syncthreads();
+    for (int i = threadIdx.x; i < DG_SLOTS; i += 256)
+        if (slot_key[i] >= 0) atomicAdd(&dg[slot_key[i]], (unsigned long long)slot_count[i]);
     for (int o = 32; o > 0; o >>= 1) {
         kept += __shfl_down(kept, o, 64);
         bad += __shfl_down(bad, o, 64);
@@ -86,33 +168,57 @@ __global__ __launch_bounds__(256) void edge_scan_kernel(const int64_t* __restric
     }
 }
 
-// Pass 2: write the key (dst_local << 32 | src_local) of every kept edge.  The slot order is
+// Which edges a partition keeps and their key (dst_local << 32 | src_local).
+struct SetSelect {                        // both endpoints in the node set
+    NodeSet own;
+    __device__ __forceinline__ bool operator()(int64_t u, int64_t v, uint64_t& key) const {
+        if (!set_has(own, v) || !set_has(own, u)) return false;
+        key = ((uint64_t)(uint32_t)set_rank(own, v) << 32) | (uint64_t)(uint32_t)set_rank(own, u);
+        return true;
+    }
+};
+struct ArraySelect {                      // per-node flag and position arrays
+    const int32_t* flag;
+    const int64_t* pos;
+    int dst_only;                         // keep every edge whose destination is flagged (halo partitions), whatever its source
+    __device__ __forceinline__ bool operator()(int64_t u, int64_t v, uint64_t& key) const {
+        if (!flag[v] || !(dst_only || flag[u])) return false;
+        key = ((uint64_t)pos[v] << 32) | (uint64_t)pos[u];
+        return true;
+    }
+};
+
+// Pass 2: write the key of every kept edge.  The slot order is
 // arbitrary; the sort that follows makes the result canonical.  A workgroup takes tiles of
 // 256 x 8 edges, counts its kept edges through LDS and reserves their slots with one atomic
 // per tile (one atomic per kept edge on a single address would serialise the whole pass).
+template <typename Select>
 __global__ __launch_bounds__(256) void edge_keys_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
-                                                        int64_t E, const int32_t* __restrict__ flag,
-                                                        const int64_t* __restrict__ pos,
+                                                        int64_t E, Select select,
                                                         unsigned long long* __restrict__ cursor,
-                                                        uint64_t* __restrict__ keys, int dst_only) {
-    // dst_only: keep every edge whose destination is flagged (halo partitions), whatever its source
+                                                        uint64_t* __restrict__ keys) {
     constexpr int PER = 8;
+    const bool vec = (((uintptr_t)src | (uintptr_t)dst) & 15) == 0;
     __shared__ int wave_count[4];
     __shared__ unsigned long long tile_base;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t n_tiles = (E + 256 * PER - 1) / (256 * PER);
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int64_t e0 = tile * (256 * PER);
+        const int64_t e0 = tile * (256 * PER) + 2 * tid;
+        int64_t us[PER], vs[PER];
+#pragma unroll
+        for (int i = 0; i < PER; i += 2) {               // a thread takes pairs of consecutive edges
+            const int64_t e = e0 + (int64_t)i * 256;
+            load_edge_pair(src, e, E, vec, 0, us[i], us[i + 1]);
+            load_edge_pair(dst, e, E, vec, -1, vs[i], vs[i + 1]);     // -1: past the end
+        }
         uint64_t key[PER];
         int mine = 0;
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
-            const int64_t e = e0 + (int64_t)i * 256 + tid;
             key[i] = ~0ull;
-            if (e < E) {
-                const int64_t u = src[e], v = dst[e];
-                if (flag[v] && (dst_only || flag[u])) { key[i] = ((uint64_t)pos[v] << 32) | (uint64_t)pos[u]; ++mine; }
-            }
+            uint64_t k;
+            if (vs[i] >= 0 && select(us[i], vs[i], k)) { key[i] = k; ++mine; }
         }
         // exclusive prefix of `mine` over the workgroup: inside the wavefront by shuffles, across the four by LDS
         int incl = mine;
@@ -250,14 +356,21 @@ struct DevBuf {
     template <typename T> T* as() { return (T*)p; }
 };
 
+struct DevView {                          // a typed look at part of an allocation (same accessors as DevBuf)
+    void* p;
+    template <typename T> T* as() { return (T*)p; }
+};
+
 static void free_partition(grp_partition_t* h) {
     if (!h) return;
     void* ptrs[] = {h->l2g, h->rowptr, h->col, h->colptr, h->row, h->d_local_in, h->d_local_out, h->d_global_in,
                     h->csr_long.long_row, h->csr_long.long_first, h->csr_long.chunk_begin, h->csr_long.chunk_end,
                     h->csc_long.long_row, h->csc_long.long_first, h->csc_long.chunk_begin, h->csc_long.chunk_end,
                     h->spmm_scratch, h->base_mask, h->csr_w, h->csc_w, h->w_local_in, h->w_global_in};
+    const char* lo = (const char*)h->slab;
     for (void* q : ptrs)
-        if (q) (void)hipFree(q);
+        if (q && !(lo && (const char*)q >= lo && (const char*)q < lo + h->slab_bytes)) (void)hipFree(q);
+    if (h->slab) (void)hipFree(h->slab);
     delete h;
 }
 
@@ -280,38 +393,44 @@ static int bits_for(int64_t n) {
 }
 
 // Split schedule of the rows longer than SPMM_LONG_ROW edges (a function of the pointer
-// array only).  One-off host pass over a copy of the pointers; the result lives on the device.
-static grp_status build_long_rows(const int64_t* ptr_dev, int64_t n, LongRows* out, hipStream_t st) {
-    std::vector<int64_t> ptr((size_t)n + 1);
-    GRP_HIP(hipMemcpyAsync(ptr.data(), ptr_dev, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+// array only), built on the device into arrays sized for the worst case (out->long_row .. chunk_end,
+// cap_long / cap_chunks entries); the two counts come back to the host (the launches that use the
+// schedule are sized by them).  scanned: [n + 1] int64 scratch.
+static grp_status build_long_rows(const int64_t* ptr_dev, int64_t n, LongRows* out, int64_t cap_long, int64_t cap_chunks,
+                                  int64_t* scanned, void* tmp, size_t tmp_bytes, hipStream_t st) {
+    out->n_long = out->n_chunks = 0;
+    if (n == 0 || cap_long == 0) return GRP_OK;          // no row can be long
+    GRP_TRY(build_long_rows_device(ptr_dev, n, out, cap_long, cap_chunks, scanned, tmp, tmp_bytes, st));
+    int64_t total = 0;
+    GRP_HIP(hipMemcpyAsync(&total, scanned + n, sizeof total, hipMemcpyDeviceToHost, st));
     GRP_HIP(hipStreamSynchronize(st));
-    std::vector<int32_t> rows, first;
-    std::vector<int64_t> cb, ce;
-    for (int64_t v = 0; v < n; ++v) {
-        const int64_t b = ptr[v], e = ptr[v + 1];
-        if (e - b <= SPMM_LONG_ROW) continue;
-        if (cb.size() + (size_t)cdiv(e - b, SPMM_CHUNK) >= ((size_t)1 << 31))
-            return fail(GRP_ERANGE, "more than 2^31 row chunks");
-        rows.push_back((int32_t)v);
-        first.push_back((int32_t)cb.size());
-        for (int64_t c = b; c < e; c += SPMM_CHUNK) {
-            cb.push_back(c);
-            ce.push_back(c + SPMM_CHUNK < e ? c + SPMM_CHUNK : e);
-        }
-    }
-    first.push_back((int32_t)cb.size());
-    out->n_long = (int32_t)rows.size();
-    out->n_chunks = (int32_t)cb.size();
-    if (out->n_long == 0) return GRP_OK;
-    GRP_TRY(halloc(&out->long_row, out->n_long));
-    GRP_TRY(halloc(&out->long_first, out->n_long + 1));
-    GRP_TRY(halloc(&out->chunk_begin, out->n_chunks));
-    GRP_TRY(halloc(&out->chunk_end, out->n_chunks));
-    GRP_HIP(hipMemcpy(out->long_row, rows.data(), rows.size() * sizeof(int32_t), hipMemcpyHostToDevice));
-    GRP_HIP(hipMemcpy(out->long_first, first.data(), first.size() * sizeof(int32_t), hipMemcpyHostToDevice));
-    GRP_HIP(hipMemcpy(out->chunk_begin, cb.data(), cb.size() * sizeof(int64_t), hipMemcpyHostToDevice));
-    GRP_HIP(hipMemcpy(out->chunk_end, ce.data(), ce.size() * sizeof(int64_t), hipMemcpyHostToDevice));
+    out->n_long = (int32_t)(total >> 32);
+    out->n_chunks = (int32_t)(total & 0xFFFFFFFFll);
     return GRP_OK;
+}
+
+// The arrays build_csr_csc fills, carved from one allocation (base null: only measures).
+static size_t carve_csr_csc(grp_partition_t* h, bool weighted, int64_t cap_long, int64_t cap_chunks, void* base, size_t cap) {
+    Bump b(base, cap);
+    const size_t n1 = (size_t)(h->n > 0 ? h->n : 1), z1 = (size_t)(h->nnz > 0 ? h->nnz : 1);
+    if (weighted) {
+        h->csr_w = b.take<float>(z1);
+        h->csc_w = b.take<float>(z1);
+    }
+    h->rowptr = b.take<int64_t>(n1 + 1);
+    h->colptr = b.take<int64_t>(n1 + 1);
+    h->col = b.take<int32_t>(z1);
+    h->row = b.take<int32_t>(z1);
+    h->d_local_in = b.take<int32_t>(n1);
+    h->d_local_out = b.take<int32_t>(n1);
+    for (LongRows* lr : {&h->csr_long, &h->csc_long}) {
+        if (cap_long == 0) continue;
+        lr->long_row = b.take<int32_t>((size_t)cap_long);
+        lr->long_first = b.take<int32_t>((size_t)cap_long + 1);
+        lr->chunk_begin = b.take<int64_t>((size_t)cap_chunks);
+        lr->chunk_end = b.take<int64_t>((size_t)cap_chunks);
+    }
+    return b.total();
 }
 
 // keys (unsorted, nnz of them; clobbered) -> h->rowptr/col/d_local_in and h->colptr/row/d_local_out.
@@ -320,27 +439,32 @@ static grp_status build_long_rows(const int64_t* ptr_dev, int64_t n, LongRows* o
 static grp_status build_csr_csc(grp_partition_t* h, uint64_t* keys, uint64_t* keys_alt, hipStream_t st,
                                 float* vals = nullptr, float* vals_alt = nullptr) {
     const int64_t n = h->n, nnz = h->nnz;
-    if (vals) {
-        GRP_TRY(halloc(&h->csr_w, nnz));
-        GRP_TRY(halloc(&h->csc_w, nnz));
+    const int64_t cap_long = nnz > SPMM_LONG_ROW ? nnz / SPMM_LONG_ROW + 1 : 0;
+    const int64_t cap_chunks = cap_long ? nnz / SPMM_CHUNK + cap_long + 1 : 0;
+    if (cap_chunks >= ((int64_t)1 << 31)) return fail(GRP_ERANGE, "more than 2^31 row chunks");
+    h->slab_bytes = carve_csr_csc(h, vals != nullptr, cap_long, cap_chunks, nullptr, 0);
+    if (hipMalloc(&h->slab, h->slab_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        h->slab = nullptr;
+        return fail(GRP_ENOMEM, "device allocation of %zu bytes failed", h->slab_bytes);
     }
-    GRP_TRY(halloc(&h->rowptr, n + 1));
-    GRP_TRY(halloc(&h->colptr, n + 1));
-    GRP_TRY(halloc(&h->col, nnz));
-    GRP_TRY(halloc(&h->row, nnz));
-    GRP_TRY(halloc(&h->d_local_in, n));
-    GRP_TRY(halloc(&h->d_local_out, n));
+    (void)carve_csr_csc(h, vals != nullptr, cap_long, cap_chunks, h->slab, h->slab_bytes);
     const unsigned end_bit = 32 + bits_for(n > 1 ? n : 2);
-    size_t tmp_bytes = 0;
+    // one scratch allocation: the sorts' temporary storage, later the long-row pass's prefix sums
+    size_t sort_bytes = 0;
+    if (nnz > 0 && !vals)
+        GRP_HIP(rocprim::radix_sort_keys(nullptr, sort_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
+    else if (nnz > 0)
+        GRP_HIP(rocprim::radix_sort_pairs(nullptr, sort_bytes, keys, keys_alt, vals, vals_alt, (size_t)nnz, 0u, end_bit, st));
+    const size_t scan_bytes = cap_long ? scan_temp_bytes(n + 1) : 0;
+    const size_t scanned_bytes = cap_long ? (((size_t)n + 1) * sizeof(int64_t) + 255) & ~(size_t)255 : 0;
+    size_t tmp_bytes = sort_bytes > scanned_bytes + scan_bytes ? sort_bytes : scanned_bytes + scan_bytes;
     DevBuf tmp;
+    GRP_TRY(tmp.alloc(tmp_bytes));
     if (nnz > 0 && !vals) {
-        GRP_HIP(rocprim::radix_sort_keys(nullptr, tmp_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
-        GRP_TRY(tmp.alloc(tmp_bytes));
-        GRP_HIP(rocprim::radix_sort_keys(tmp.p, tmp_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
+        GRP_HIP(rocprim::radix_sort_keys(tmp.p, sort_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
     } else if (nnz > 0) {
-        GRP_HIP(rocprim::radix_sort_pairs(nullptr, tmp_bytes, keys, keys_alt, vals, vals_alt, (size_t)nnz, 0u, end_bit, st));
-        GRP_TRY(tmp.alloc(tmp_bytes));
-        GRP_HIP(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, keys, keys_alt, vals, vals_alt, (size_t)nnz, 0u, end_bit, st));
+        GRP_HIP(rocprim::radix_sort_pairs(tmp.p, sort_bytes, keys, keys_alt, vals, vals_alt, (size_t)nnz, 0u, end_bit, st));
         GRP_HIP(hipMemcpyAsync(h->csr_w, vals_alt, (size_t)nnz * sizeof(float), hipMemcpyDeviceToDevice, st));
     }
     hipLaunchKernelGGL(csr_from_keys_kernel, dim3(grid_for(nnz + 1)), dim3(256), 0, st, keys_alt, nnz, n, h->rowptr, h->col);
@@ -349,9 +473,9 @@ static grp_status build_csr_csc(grp_partition_t* h, uint64_t* keys, uint64_t* ke
         hipLaunchKernelGGL(swap_halves_kernel, dim3(grid_for(nnz)), dim3(256), 0, st, keys_alt, nnz, keys);
         GRP_LAUNCH_CHECK();
         if (!vals) {
-            GRP_HIP(rocprim::radix_sort_keys(tmp.p, tmp_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
+            GRP_HIP(rocprim::radix_sort_keys(tmp.p, sort_bytes, keys, keys_alt, (size_t)nnz, 0u, end_bit, st));
         } else {      // from CSR order (vals_alt) to CSC order (vals)
-            GRP_HIP(rocprim::radix_sort_pairs(tmp.p, tmp_bytes, keys, keys_alt, vals_alt, vals, (size_t)nnz, 0u, end_bit, st));
+            GRP_HIP(rocprim::radix_sort_pairs(tmp.p, sort_bytes, keys, keys_alt, vals_alt, vals, (size_t)nnz, 0u, end_bit, st));
             GRP_HIP(hipMemcpyAsync(h->csc_w, vals, (size_t)nnz * sizeof(float), hipMemcpyDeviceToDevice, st));
         }
     }
@@ -363,9 +487,11 @@ static grp_status build_csr_csc(grp_partition_t* h, uint64_t* keys, uint64_t* ke
         hipLaunchKernelGGL(degree_from_ptr_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, h->colptr, n, h->d_local_out);
         GRP_LAUNCH_CHECK();
     }
+    int64_t* const scanned = (int64_t*)tmp.p;            // the sorts are done (stream order): their scratch is free
+    void* const scan_tmp = (char*)tmp.p + scanned_bytes;
+    GRP_TRY(build_long_rows(h->rowptr, n, &h->csr_long, cap_long, cap_chunks, scanned, scan_tmp, scan_bytes, st));
+    GRP_TRY(build_long_rows(h->colptr, n, &h->csc_long, cap_long, cap_chunks, scanned, scan_tmp, scan_bytes, st));
     GRP_HIP(hipStreamSynchronize(st));
-    GRP_TRY(build_long_rows(h->rowptr, n, &h->csr_long, st));
-    GRP_TRY(build_long_rows(h->colptr, n, &h->csc_long, st));
     return GRP_OK;
 }
 
@@ -375,10 +501,27 @@ static grp_status weighted_build(const int64_t* src, const int64_t* dst, const f
 static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t E, int64_t N, int32_t K, uint64_t seed,
                                  int32_t part_id, hipStream_t st, grp_partition_t* h, const float* w = nullptr,
                                  bool weighted = false) {
-    DevBuf flag, pos, counters, scan_tmp;
-    GRP_TRY(flag.alloc((size_t)N * sizeof(int32_t)));
-    GRP_TRY(pos.alloc((size_t)N * sizeof(int64_t)));
-    GRP_TRY(counters.alloc(3 * sizeof(unsigned long long)));
+    // every N-sized temporary from one allocation: flags, positions, the node set, counters, scan scratch
+    const int64_t n_words = cdiv(N > 0 ? N : 1, 32);
+    size_t pos_scan_bytes = 0;
+    if (N > 0)
+        GRP_HIP(rocprim::exclusive_scan(nullptr, pos_scan_bytes, (const int32_t*)nullptr, (int64_t*)nullptr, (int64_t)0, (size_t)N,
+                                        rocprim::plus<int64_t>(), st));
+    const size_t set_scan_bytes = scan_temp_bytes(n_words + 1);
+    const size_t scratch_bytes = pos_scan_bytes > set_scan_bytes ? pos_scan_bytes : set_scan_bytes;
+    DevBuf slab;
+    struct { int32_t* flag; int64_t* pos; unsigned long long* counters; uint32_t* bits; int32_t* before; char* scratch; } t{};
+    for (int pass = 0; pass < 2; ++pass) {
+        Bump b(slab.p, 0);
+        t.counters = b.take<unsigned long long>(4);
+        t.flag = b.take<int32_t>((size_t)(N > 0 ? N : 1));
+        t.pos = b.take<int64_t>((size_t)(N > 0 ? N : 1));
+        t.bits = b.take<uint32_t>((size_t)n_words + 1);
+        t.before = b.take<int32_t>((size_t)n_words + 1);
+        t.scratch = b.take<char>(scratch_bytes);
+        if (pass == 0) GRP_TRY(slab.alloc(b.total()));
+    }
+    DevView flag{t.flag}, pos{t.pos}, counters{t.counters};
     GRP_HIP(hipMemsetAsync(counters.p, 0, 3 * sizeof(unsigned long long), st));
 
     int64_t n = 0;
@@ -386,11 +529,7 @@ static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t
         hipLaunchKernelGGL(owner_flag_kernel, dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st, N, (uint32_t)K, seed,
                            (uint32_t)part_id, flag.as<int32_t>());
         GRP_LAUNCH_CHECK();
-        size_t bytes = 0;
-        GRP_HIP(rocprim::exclusive_scan(nullptr, bytes, flag.as<int32_t>(), pos.as<int64_t>(), (int64_t)0, (size_t)N,
-                                        rocprim::plus<int64_t>(), st));
-        GRP_TRY(scan_tmp.alloc(bytes));
-        GRP_HIP(rocprim::exclusive_scan(scan_tmp.p, bytes, flag.as<int32_t>(), pos.as<int64_t>(), (int64_t)0, (size_t)N,
+        GRP_HIP(rocprim::exclusive_scan(t.scratch, pos_scan_bytes, flag.as<int32_t>(), pos.as<int64_t>(), (int64_t)0, (size_t)N,
                                         rocprim::plus<int64_t>(), st));
         int64_t last_pos = 0;
         int32_t last_flag = 0;
@@ -410,10 +549,23 @@ static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t
         GRP_LAUNCH_CHECK();
     }
     unsigned long long host_counters[3] = {0, 0, 0};
-    if (E > 0) {
-        hipLaunchKernelGGL(edge_scan_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, N, flag.as<int32_t>(),
-                           pos.as<int64_t>(), (unsigned long long*)h->d_global_in, counters.as<unsigned long long>());
+    NodeSet own{nullptr, nullptr};
+    if (E > 0 && N > 0) {
+        hipLaunchKernelGGL(pack_bits_kernel, dim3((unsigned)cdiv(n_words * 32, 256)), dim3(256), 0, st,
+                           (const int32_t*)flag.as<int32_t>(), N, n_words, t.bits);
         GRP_LAUNCH_CHECK();
+        GRP_HIP(hipMemsetAsync(t.bits + n_words, 0, sizeof(uint32_t), st));
+        GRP_TRY(exclusive_scan_popcount(t.scratch, set_scan_bytes, t.bits, t.before, n_words + 1, st));
+        own = NodeSet{t.bits, t.before};
+    }
+    if (E > 0) {
+        const unsigned scan_grid = grid_for(E) < (unsigned)EDGE_SCAN_GRID ? grid_for(E) : (unsigned)EDGE_SCAN_GRID;
+        {
+            ProfScope ps("partition_edge_scan", st, 0.0, 16.0 * (double)E);
+            hipLaunchKernelGGL(edge_scan_kernel, dim3(scan_grid), dim3(256), 0, st, src, dst, E, N, own,
+                               (unsigned long long*)h->d_global_in, counters.as<unsigned long long>());
+            GRP_LAUNCH_CHECK();
+        }
         GRP_HIP(hipMemcpyAsync(host_counters, counters.p, sizeof host_counters, hipMemcpyDeviceToHost, st));
         GRP_HIP(hipStreamSynchronize(st));
     }
@@ -422,15 +574,18 @@ static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t
     const int64_t nnz = (int64_t)host_counters[0];
     h->nnz = nnz;
     if (weighted) return weighted_build(src, dst, w, E, flag.as<int32_t>(), pos.as<int64_t>(), st, h);
-    DevBuf keys, keys_alt;
-    GRP_TRY(keys.alloc((size_t)nnz * sizeof(uint64_t)));
-    GRP_TRY(keys_alt.alloc((size_t)nnz * sizeof(uint64_t)));
+    DevBuf keybuf;                                       // both key arrays
+    const size_t key_pitch = (((size_t)(nnz > 0 ? nnz : 1) * sizeof(uint64_t)) + 255) & ~(size_t)255;
+    GRP_TRY(keybuf.alloc(2 * key_pitch));
+    uint64_t* const keys = keybuf.as<uint64_t>();
+    uint64_t* const keys_alt = (uint64_t*)((char*)keybuf.p + key_pitch);
     if (nnz > 0) {
-        hipLaunchKernelGGL(edge_keys_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, flag.as<int32_t>(),
-                           pos.as<int64_t>(), counters.as<unsigned long long>() + 2, keys.as<uint64_t>(), 0);
+        ProfScope ps("partition_edge_keys", st, 0.0, 16.0 * (double)E + 8.0 * (double)nnz);
+        hipLaunchKernelGGL(edge_keys_kernel<SetSelect>, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, SetSelect{own},
+                           counters.as<unsigned long long>() + 2, keys);
         GRP_LAUNCH_CHECK();
     }
-    return build_csr_csc(h, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), st);
+    return build_csr_csc(h, keys, keys_alt, st);
 }
 
 // ------------------------------------------------------------------ halo partitions
@@ -629,8 +784,9 @@ static grp_status halo_partition_impl(const int64_t* src, const int64_t* dst, in
     GRP_TRY(keys.alloc((size_t)nnz * sizeof(uint64_t)));
     GRP_TRY(keys_alt.alloc((size_t)nnz * sizeof(uint64_t)));
     if (nnz > 0) {
-        hipLaunchKernelGGL(edge_keys_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, inner.as<int32_t>(),
-                           pos.as<int64_t>(), counters.as<unsigned long long>() + 2, keys.as<uint64_t>(), 1);
+        hipLaunchKernelGGL(edge_keys_kernel<ArraySelect>, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E,
+                           ArraySelect{inner.as<int32_t>(), pos.as<int64_t>(), 1}, counters.as<unsigned long long>() + 2,
+                           keys.as<uint64_t>());
         GRP_LAUNCH_CHECK();
     }
     return build_csr_csc(h, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), st);
