@@ -7,6 +7,8 @@ partitions leave most of the chip idle); their gradients are kept resident for t
 """
 from __future__ import annotations
 
+from concurrent.futures import ThreadPoolExecutor
+
 import torch
 
 from . import binding as g
@@ -89,10 +91,14 @@ class MiniBatchTrainer:
     batch_id is the number of iterations done so far (``iteration``).  Within an iteration the phases run as
     in ``PhaseParallelTrainer``.  Sequencing only: the seed order, sampling, steps, reduction and update
     are library calls.
+    ``lanes``: the steps of a phase are independent, and a mini-batch step waits for the GPU once per
+    sampled layer; with ``lanes`` > 1 that many host threads each drive their share of the phase's steps on
+    a stream (default priority) and a workspace of their own, so one step's sampling overlaps another's
+    layers.  The result does not depend on it.
     """
 
     def __init__(self, parts, model, xs, ys, masks, theta0, estimator, max_active, batch_size, fanouts,
-                 sampler_seed, optimizer=None, dropout_rate=0.0, dropout_seed=0):
+                 sampler_seed, optimizer=None, dropout_rate=0.0, dropout_seed=0, lanes=1):
         self.dropout_rate, self.dropout_seed = dropout_rate, dropout_seed
         self.parts, self.model, self.xs, self.ys, self.masks = parts, model, xs, ys, masks
         self.estimator, self.max_active = estimator, max_active
@@ -115,7 +121,10 @@ class MiniBatchTrainer:
         for p, sd, c in zip(parts, self.seeds, self.n_train):       # the workspace is sized from the seed count alone
             probe.n_seeds = max(1, min(self.batch_size, c))
             ws_bytes = max(ws_bytes, g.grp_step_workspace_bytes(p, model, probe))
-        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        n_lanes = max(1, min(int(lanes), max_active))
+        self.ws = [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in range(n_lanes)]
+        self.side = [torch.cuda.Stream(device=dev) for _ in range(n_lanes)] if n_lanes > 1 else []
+        self.pool = ThreadPoolExecutor(max_workers=n_lanes) if n_lanes > 1 else None
         self.step_count = 0
         self.epoch = 0
         self.iteration = 0
@@ -130,20 +139,39 @@ class MiniBatchTrainer:
         counts = [g.grp_epoch_seeds(p, mk, self.sampler_seed, self.epoch, sd)
                   for p, mk, sd in zip(self.parts, self.masks, self.seeds)]
         assert counts == self.n_train
+        def one_step(slot, p, it, lane, stream):
+            lo, hi = it * B, min((it + 1) * B, counts[p])
+            st = self.stats[slot * g.STATS_BYTES:(slot + 1) * g.STATS_BYTES]
+            if hi <= lo:                               # no seeds left: a zero gradient and an empty record
+                self.grads[slot].zero_()
+                st.zero_()
+                return
+            opts = g.step_opts(estimator=self.estimator, full_graph=False, seeds=self.seeds[p][lo:hi],
+                               fanouts=self.fanouts, sampler_seed=self.sampler_seed, batch_id=self.iteration,
+                               dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed)
+            g.grp_train_step(self.parts[p], self.model, opts, self.xs[p], self.ys[p], None, self.theta,
+                             self.ws[lane], self.grads[slot], st, stream=stream)
+
+        def lane_job(lane, active, it):                # one host thread: its share of the phase, in order
+            with torch.cuda.stream(self.side[lane]):
+                for slot, p in enumerate(active):
+                    if slot % len(self.side) == lane:
+                        one_step(slot, p, it, lane, self.side[lane])
+
         for it in range(self.iters):
             for active in self.phases():
-                for slot, p in enumerate(active):
-                    lo, hi = it * B, min((it + 1) * B, counts[p])
-                    st = self.stats[slot * g.STATS_BYTES:(slot + 1) * g.STATS_BYTES]
-                    if hi <= lo:                       # no seeds left: a zero gradient and an empty record
-                        self.grads[slot].zero_()
-                        st.zero_()
-                        continue
-                    opts = g.step_opts(estimator=self.estimator, full_graph=False, seeds=self.seeds[p][lo:hi],
-                                       fanouts=self.fanouts, sampler_seed=self.sampler_seed, batch_id=self.iteration,
-                                       dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed)
-                    g.grp_train_step(self.parts[p], self.model, opts, self.xs[p], self.ys[p], None, self.theta,
-                                     self.ws, self.grads[slot], st)
+                if self.pool is None:
+                    for slot, p in enumerate(active):
+                        one_step(slot, p, it, 0, None)
+                else:
+                    main = torch.cuda.current_stream()
+                    ready = main.record_event()        # theta and everything before
+                    for sd in self.side:
+                        sd.wait_event(ready)
+                    for job in [self.pool.submit(lane_job, lane, active, it) for lane in range(len(self.side))]:
+                        job.result()
+                    for sd in self.side:               # the reduction waits for every step
+                        main.wait_stream(sd)
                 g.grp_aggregate(self.grads, self.ld, self.stats, len(active), self.P, self.estimator, self.update)
                 self.step_count += 1
                 g.grp_optimizer_step(self.opt, self.P, self.step_count, self.theta, self.update, self.m, self.v)

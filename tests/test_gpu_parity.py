@@ -760,6 +760,37 @@ def test_minibatch_phase_parallel_loop_matches_oracle(g, M):
         p.destroy()
 
 
+@pytest.mark.gpu
+def test_minibatch_steps_driven_by_several_host_threads_give_the_same_bits(g):
+    """The steps of a phase on three host threads, each with its stream and workspace (one thread takes two
+    of the four steps): same theta and losses as the one-thread loop, bit for bit."""
+    _note("mini-batch loop on several host threads")
+    N, E, K, M = 2000, 24000, 4, 4
+    s, d = synth.rmat_graph(11, E, seed=81, n_nodes=N)
+    dims = [12, 24, 24, 4]
+    x = synth.normal_matrix(N, dims[0], 82)
+    y = synth.planted_labels(x, dims[-1], 83)
+    theta0 = synth.model_weights("sage", dims, 84)
+    parts = [g.grp_partition(s.to(DEV), d.to(DEV), N, K, 1, p) for p in range(K)]
+    l2gs = [torch.from_numpy(p.array("l2g")).to(DEV) for p in parts]
+    xs = [x.to(DEV)[i].contiguous() for i in l2gs]
+    ys = [y.to(DEV)[i].contiguous() for i in l2gs]
+    masks = [None, (torch.arange(parts[1].n, device=DEV) % 2 == 0).to(torch.uint8), None, None]
+    model = g.model_desc(g.ARCH_SAGE_MEAN, dims)
+    runs = []
+    for lanes in (1, 3):
+        tr = g.MiniBatchTrainer(parts, model, xs, ys, masks, theta0.to(DEV), g.EST_SHRINKAGE, M, 100, (4, 3, 5), 21,
+                                g.optimizer_desc(g.OPT_ADAM, lr=0.003), dropout_rate=0.3, dropout_seed=2, lanes=lanes)
+        for _ in range(2):
+            tr.run_epoch()
+        torch.cuda.synchronize()
+        runs.append((tr.theta.clone(), tr.losses()))
+    assert torch.equal(runs[0][0], runs[1][0])
+    assert runs[0][1] == runs[1][1] and len(runs[0][1]) > 8
+    for p in parts:
+        p.destroy()
+
+
 # ------------------------------------------------------------------ chunks and sweeping partitions
 @pytest.mark.gpu
 @pytest.mark.parametrize("kind,N,E,c", [("uniform", 3000, 40000, 4), ("rmat", 1 << 12, 150000, 3), ("uniform", 500, 0, 2),
