@@ -189,7 +189,7 @@ class SweepingTrainer:
     rebuilt on the GPU (``grp_partition_from_chunks``) and its rows of the global feature /
     label / mask tensors are gathered by ``l2g``; the controller decides after each epoch
     whether to switch.  theta and the optimizer state persist across super-epochs.
-    ``minibatch = dict(batch_size=, fanouts=, sampler_seed=)``: every epoch is a mini-batch epoch
+    ``minibatch = dict(batch_size=, fanouts=, sampler_seed=[, lanes=])``: every epoch is a mini-batch epoch
     (``MiniBatchTrainer``) over the current partitions; the epoch number and the iteration count run on
     across super-epochs.
     """
@@ -231,7 +231,7 @@ class SweepingTrainer:
             mb = self.minibatch
             tr = MiniBatchTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active,
                                   mb["batch_size"], mb["fanouts"], mb["sampler_seed"], self.opt,
-                                  dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed)
+                                  dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed, lanes=mb.get("lanes", 1))
             tr.epoch, tr.iteration = self.epoch, self.iteration
         else:
             tr = PhaseParallelTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active, self.opt,

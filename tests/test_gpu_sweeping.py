@@ -58,7 +58,7 @@ def test_sweeping_minibatch_loop_matches_oracle(c, M, masked, drop):
     theta0 = synth.model_weights("sage", dims, 100)
     total_epochs = 2 * max(1, c - 1) if c > 2 else 3
     lr = 0.05
-    mb = dict(batch_size=96, fanouts=(5, 4), sampler_seed=13)
+    mb = dict(batch_size=96, fanouts=(5, 4), sampler_seed=13, lanes=2 if drop > 0 else 1)   # lanes: host threads, same bits
     tr = g.SweepingTrainer(s.to(DEV), d.to(DEV), N, c, 17, g.model_desc(g.ARCH_SAGE_MEAN, dims), x.to(DEV), y.to(DEV),
                            None if tm is None else tm.to(DEV), theta0.to(DEV), g.EST_SHRINKAGE, M, total_epochs,
                            g.optimizer_desc(g.OPT_SGD, lr=lr), minibatch=mb, dropout_rate=drop, dropout_seed=43)
