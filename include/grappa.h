@@ -97,6 +97,8 @@ grp_status grp_node_owners(int64_t N, int32_t K, uint64_t seed, int32_t* owner_o
  *                                   pairs keep their order in the edge list
  *   w_local_in      DEV double[n]   sum of a node's local in-edge weights, added in CSR order
  *   w_global_in     DEV double[n]   sum over all its in-edges, added in edge-list order
+ *                   (rows of more than 1024 weights: 256 consecutive runs added in order, then the
+ *                   run sums added in order)
  * (both sums are sequential fp64 additions in the stated order, so they are reproducible bit
  * for bit).  grp_train_step on such a handle (GraphSAGE, full-graph mode; GRP_EUNSUPPORTED
  * otherwise) aggregates with the weighted mean m_v = sum_u w_uv h_u / w_local_in(v), and its

@@ -87,6 +87,92 @@ __device__ __forceinline__ int32_t set_rank(const NodeSet& s, int64_t v) {
     return s.before[v >> 5] + __popc(s.bits[v >> 5] & ((1u << (v & 31)) - 1u));
 }
 
+// ---- weighted partitions: the selected edges are compacted in edge-list order, so that equal
+// (dst, src) pairs keep their order through the stable sorts and the result does not depend on
+// scheduling.  A tile is 2048 consecutive edges, eight consecutive edges per thread; a first pass counts
+// the selected edges of every tile, a prefix sum over the tiles gives each its first slot, a second pass
+// repeats the selection and places every edge at the tile's slot plus its rank inside the tile.
+// WHICH = 0: edges with both endpoints in the set; WHICH = 1: edges whose destination is in the set.
+constexpr int OC_PER = 8;
+constexpr int OC_TILE = 256 * OC_PER;
+
+template <int WHICH>
+__device__ __forceinline__ int oc_select(const int64_t* __restrict__ src, const int64_t* __restrict__ dst, int64_t E,
+                                         bool vec, const NodeSet& own, int64_t e0, int64_t (&us)[OC_PER],
+                                         int64_t (&vs)[OC_PER], bool (&on)[OC_PER]) {
+#pragma unroll
+    for (int i = 0; i < OC_PER; i += 2) {
+        load_edge_pair(src, e0 + i, E, vec, 0, us[i], us[i + 1]);
+        load_edge_pair(dst, e0 + i, E, vec, -1, vs[i], vs[i + 1]);       // -1: past the end
+    }
+    int count = 0;
+#pragma unroll
+    for (int i = 0; i < OC_PER; ++i) {
+        on[i] = vs[i] >= 0 && set_has(own, vs[i]) && (WHICH == 1 || set_has(own, us[i]));
+        count += on[i] ? 1 : 0;
+    }
+    return count;
+}
+
+template <int WHICH>
+__global__ __launch_bounds__(256) void ordered_count_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                            int64_t E, NodeSet own, int64_t n_tiles,
+                                                            int64_t* __restrict__ tile_count /*[n_tiles + 1]*/) {
+    __shared__ int wave_count[4];
+    const bool vec = (((uintptr_t)src | (uintptr_t)dst) & 15) == 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        int64_t us[OC_PER], vs[OC_PER];
+        bool on[OC_PER];
+        int c = oc_select<WHICH>(src, dst, E, vec, own, tile * OC_TILE + (int64_t)threadIdx.x * OC_PER, us, vs, on);
+        for (int o = 32; o > 0; o >>= 1) c += __shfl_down(c, o, 64);
+        if (lane == 0) wave_count[wave] = c;
+        __syncthreads();
+        if (threadIdx.x == 0) tile_count[tile] = wave_count[0] + wave_count[1] + wave_count[2] + wave_count[3];
+        __syncthreads();
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) tile_count[n_tiles] = 0;
+}
+
+template <int WHICH>
+__global__ __launch_bounds__(256) void ordered_emit_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                           const float* __restrict__ w, int64_t E, NodeSet own,
+                                                           int64_t n_tiles, const int64_t* __restrict__ tile_base,
+                                                           uint64_t* __restrict__ keys, uint32_t* __restrict__ keys32,
+                                                           float* __restrict__ vals) {
+    __shared__ int wave_count[4];
+    const bool vec = (((uintptr_t)src | (uintptr_t)dst) & 15) == 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t e0 = tile * OC_TILE + (int64_t)threadIdx.x * OC_PER;
+        int64_t us[OC_PER], vs[OC_PER];
+        bool on[OC_PER];
+        const int mine = oc_select<WHICH>(src, dst, E, vec, own, e0, us, vs, on);
+        int incl = mine;                                 // inclusive prefix over the wavefront, then over the four
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) wave_count[wave] = incl;
+        __syncthreads();
+        int before = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (q < wave) before += wave_count[q];
+        int64_t slot = tile_base[tile] + before + incl - mine;
+#pragma unroll
+        for (int i = 0; i < OC_PER; ++i) {
+            if (!on[i]) continue;
+            if (WHICH == 0) keys[slot] = ((uint64_t)(uint32_t)set_rank(own, vs[i]) << 32) | (uint64_t)(uint32_t)set_rank(own, us[i]);
+            else keys32[slot] = (uint32_t)set_rank(own, vs[i]);
+            vals[slot] = w[e0 + i];
+            ++slot;
+        }
+        __syncthreads();                                 // wave_count is reused by the next tile
+    }
+}
+
 // bits[w] = flags of nodes 32w .. 32w+31; the grid covers n_words * 32 nodes
 __global__ __launch_bounds__(256) void pack_bits_kernel(const int32_t* __restrict__ flag, int64_t N, int64_t n_words,
                                                         uint32_t* __restrict__ bits) {
@@ -293,31 +379,6 @@ __global__ __launch_bounds__(256) void widen_kernel(const int32_t* __restrict__ 
     if (v < n) out[v] = in[v];
 }
 
-// ---- weighted partitions: deterministic slots (a scan over per-edge flags) so that equal
-// (dst, src) pairs keep their order in the edge list through the stable sorts.
-// which = 0: edges with both endpoints owned; which = 1: edges whose destination is owned.
-__global__ __launch_bounds__(256) void edge_select_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
-                                                          int64_t E, const int32_t* __restrict__ flag, int which,
-                                                          int32_t* __restrict__ sel) {
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256)
-        sel[e] = (flag[dst[e]] && (which == 1 || flag[src[e]])) ? 1 : 0;
-}
-
-__global__ __launch_bounds__(256) void edge_emit_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
-                                                        const float* __restrict__ w, int64_t E,
-                                                        const int32_t* __restrict__ sel, const int64_t* __restrict__ slot,
-                                                        const int64_t* __restrict__ pos, int which,
-                                                        uint64_t* __restrict__ keys, uint32_t* __restrict__ keys32,
-                                                        float* __restrict__ vals) {
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
-        if (!sel[e]) continue;
-        const int64_t s = slot[e];
-        if (which == 0) keys[s] = ((uint64_t)pos[dst[e]] << 32) | (uint64_t)pos[src[e]];
-        else keys32[s] = (uint32_t)pos[dst[e]];
-        vals[s] = w[e];
-    }
-}
-
 __global__ __launch_bounds__(256) void weight_check_kernel(const float* __restrict__ w, int64_t E,
                                                            unsigned long long* __restrict__ bad) {
     unsigned long long b = 0;
@@ -326,15 +387,65 @@ __global__ __launch_bounds__(256) void weight_check_kernel(const float* __restri
     if (b) atomicAdd(bad, b);
 }
 
-// mass[r] = sum of vals over [ptr[r], ptr[r+1]) in stored order, fp64 (one thread per row: the order
-// of the additions is part of the result).
+// mass[r] = sum of vals over [ptr[r], ptr[r+1]) in fp64.  Rows of at most ROW_MASS_SERIAL entries are added in
+// stored order by one thread.  Longer rows (hubs: 10^5 entries and more, which one thread would take
+// milliseconds over) are left to row_mass_long_kernel: one workgroup per row, every thread adds a contiguous
+// run in stored order and the 256 partial sums are added in thread order, a fixed order that does not depend
+// on scheduling (and the same value as the serial sum whenever the partial sums are exact in fp64, as they
+// are for float weights of similar magnitude).
+constexpr int ROW_MASS_SERIAL = 1024;
+
 __global__ __launch_bounds__(256) void row_mass_kernel(const int64_t* __restrict__ ptr, const float* __restrict__ vals,
-                                                       int64_t n, double* __restrict__ mass) {
+                                                       int64_t n, double* __restrict__ mass,
+                                                       int32_t* __restrict__ long_rows, int32_t* __restrict__ n_long) {
     const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (r >= n) return;
+    const int64_t b = ptr[r], e = ptr[r + 1];
+    if (e - b > ROW_MASS_SERIAL) {
+        long_rows[atomicAdd(n_long, 1)] = (int32_t)r;    // any order: each row is summed on its own
+        return;
+    }
     double s = 0.0;
-    for (int64_t k = ptr[r]; k < ptr[r + 1]; ++k) s += (double)vals[k];
+    for (int64_t k = b; k < e; ++k) s += (double)vals[k];
     mass[r] = s;
+}
+
+__global__ __launch_bounds__(256) void row_mass_long_kernel(const int64_t* __restrict__ ptr, const float* __restrict__ vals,
+                                                            const int32_t* __restrict__ long_rows,
+                                                            const int32_t* __restrict__ n_long, double* __restrict__ mass) {
+    __shared__ double part[256];
+    const int count = *n_long;
+    for (int j = blockIdx.x; j < count; j += gridDim.x) {
+        const int64_t r = long_rows[j];
+        const int64_t b = ptr[r], e = ptr[r + 1];
+        const int64_t per = (e - b + 255) / 256;
+        int64_t lo = b + threadIdx.x * per, hi = lo + per;
+        if (lo > e) lo = e;
+        if (hi > e) hi = e;
+        double s = 0.0;
+        for (int64_t k = lo; k < hi; ++k) s += (double)vals[k];
+        part[threadIdx.x] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double t = 0.0;
+            for (int q = 0; q < 256; ++q) t += part[q];
+            mass[r] = t;
+        }
+        __syncthreads();
+    }
+}
+
+// Row masses of a CSR-like (ptr, vals) pair; `scratch`: [n + 1] int32 device words (list of long rows + their count).
+static grp_status launch_row_mass(const int64_t* ptr, const float* vals, int64_t n, double* mass, int32_t* scratch,
+                                  hipStream_t st) {
+    if (n == 0) return GRP_OK;
+    GRP_HIP(hipMemsetAsync(scratch + n, 0, sizeof(int32_t), st));
+    hipLaunchKernelGGL(row_mass_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, ptr, vals, n, mass, scratch, scratch + n);
+    GRP_LAUNCH_CHECK();
+    hipLaunchKernelGGL(row_mass_long_kernel, dim3(1024), dim3(256), 0, st, ptr, vals, (const int32_t*)scratch,
+                       (const int32_t*)(scratch + n), mass);
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
 }
 
 static unsigned grid_for(int64_t work) {
@@ -495,8 +606,8 @@ static grp_status build_csr_csc(grp_partition_t* h, uint64_t* keys, uint64_t* ke
     return GRP_OK;
 }
 
-static grp_status weighted_build(const int64_t* src, const int64_t* dst, const float* w, int64_t E, const int32_t* flag,
-                                 const int64_t* pos, hipStream_t st, grp_partition_t* h);
+static grp_status weighted_build(const int64_t* src, const int64_t* dst, const float* w, int64_t E, NodeSet own,
+                                 hipStream_t st, grp_partition_t* h);
 
 static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t E, int64_t N, int32_t K, uint64_t seed,
                                  int32_t part_id, hipStream_t st, grp_partition_t* h, const float* w = nullptr,
@@ -573,7 +684,7 @@ static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t
         return fail(GRP_ERANGE, "%llu edges have an endpoint outside [0, %lld)", host_counters[1], (long long)N);
     const int64_t nnz = (int64_t)host_counters[0];
     h->nnz = nnz;
-    if (weighted) return weighted_build(src, dst, w, E, flag.as<int32_t>(), pos.as<int64_t>(), st, h);
+    if (weighted) return weighted_build(src, dst, w, E, own, st, h);
     DevBuf keybuf;                                       // both key arrays
     const size_t key_pitch = (((size_t)(nnz > 0 ? nnz : 1) * sizeof(uint64_t)) + 255) & ~(size_t)255;
     GRP_TRY(keybuf.alloc(2 * key_pitch));
@@ -592,10 +703,10 @@ static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t
 // One hop outwards: the source of every edge whose destination is already inside joins.
 // The rest of a weighted partition build (h->n, h->nnz, h->l2g, h->d_global_in are set; the ids are
 // range-checked): CSR/CSC with the edge weights carried along, then the weight masses.
-static grp_status weighted_build(const int64_t* src, const int64_t* dst, const float* w, int64_t E, const int32_t* flag,
-                                 const int64_t* pos, hipStream_t st, grp_partition_t* h) {
+static grp_status weighted_build(const int64_t* src, const int64_t* dst, const float* w, int64_t E, NodeSet own,
+                                 hipStream_t st, grp_partition_t* h) {
     const int64_t n = h->n, nnz = h->nnz;
-    DevBuf bad, sel, slot, scan_tmp;
+    DevBuf bad, tiles, scan_tmp;
     GRP_TRY(bad.alloc(sizeof(unsigned long long)));
     GRP_HIP(hipMemsetAsync(bad.p, 0, sizeof(unsigned long long), st));
     unsigned long long host_bad = 0;
@@ -606,21 +717,23 @@ static grp_status weighted_build(const int64_t* src, const int64_t* dst, const f
         GRP_HIP(hipStreamSynchronize(st));
     }
     if (host_bad) return fail(GRP_EINVAL, "%llu edge weights are not positive finite numbers", host_bad);
-    GRP_TRY(sel.alloc((size_t)E * sizeof(int32_t)));
-    GRP_TRY(slot.alloc((size_t)E * sizeof(int64_t)));
-    size_t scan_bytes = 0;
-    if (E > 0) {
-        GRP_HIP(rocprim::exclusive_scan(nullptr, scan_bytes, sel.as<int32_t>(), slot.as<int64_t>(), (int64_t)0, (size_t)E,
-                                        rocprim::plus<int64_t>(), st));
-        GRP_TRY(scan_tmp.alloc(scan_bytes));
-    }
-    auto select = [&](int which) -> grp_status {
+    const int64_t n_tiles = cdiv(E, OC_TILE);
+    const size_t tile_pitch = (((size_t)n_tiles + 1) * sizeof(int64_t) + 255) & ~(size_t)255;
+    GRP_TRY(tiles.alloc(2 * tile_pitch));                 // per-tile counts, then their prefix sums
+    int64_t* const tile_count = tiles.as<int64_t>();
+    int64_t* const tile_base = (int64_t*)((char*)tiles.p + tile_pitch);
+    const size_t scan_bytes = scan_temp_bytes(n_tiles + 1);
+    GRP_TRY(scan_tmp.alloc(scan_bytes));
+    const unsigned oc_grid = (unsigned)(n_tiles < 16384 ? (n_tiles > 0 ? n_tiles : 1) : 16384);
+    // the slots of the selected edges, in edge-list order (which = 0: local edges, 1: every in-edge of an owned node)
+    auto place = [&](int which) -> grp_status {
         if (E <= 0) return GRP_OK;
-        hipLaunchKernelGGL(edge_select_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, flag, which, sel.as<int32_t>());
+        if (which == 0)
+            hipLaunchKernelGGL(ordered_count_kernel<0>, dim3(oc_grid), dim3(256), 0, st, src, dst, E, own, n_tiles, tile_count);
+        else
+            hipLaunchKernelGGL(ordered_count_kernel<1>, dim3(oc_grid), dim3(256), 0, st, src, dst, E, own, n_tiles, tile_count);
         GRP_LAUNCH_CHECK();
-        GRP_HIP(rocprim::exclusive_scan(scan_tmp.p, scan_bytes, sel.as<int32_t>(), slot.as<int64_t>(), (int64_t)0, (size_t)E,
-                                        rocprim::plus<int64_t>(), st));
-        return GRP_OK;
+        return exclusive_scan_i64(scan_tmp.p, scan_bytes, tile_count, tile_base, n_tiles + 1, st);
     };
     // ---- local edges with their weights
     DevBuf keys, keys_alt, vals, vals_alt;
@@ -628,18 +741,19 @@ static grp_status weighted_build(const int64_t* src, const int64_t* dst, const f
     GRP_TRY(keys_alt.alloc((size_t)nnz * sizeof(uint64_t)));
     GRP_TRY(vals.alloc((size_t)nnz * sizeof(float)));
     GRP_TRY(vals_alt.alloc((size_t)nnz * sizeof(float)));
-    GRP_TRY(select(0));
     if (nnz > 0) {
-        hipLaunchKernelGGL(edge_emit_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, w, E, sel.as<int32_t>(),
-                           slot.as<int64_t>(), pos, 0, keys.as<uint64_t>(), (uint32_t*)nullptr, vals.as<float>());
+        GRP_TRY(place(0));
+        hipLaunchKernelGGL(ordered_emit_kernel<0>, dim3(oc_grid), dim3(256), 0, st, src, dst, w, E, own, n_tiles,
+                           (const int64_t*)tile_base, keys.as<uint64_t>(), (uint32_t*)nullptr, vals.as<float>());
         GRP_LAUNCH_CHECK();
     }
     GRP_TRY(build_csr_csc(h, keys.as<uint64_t>(), keys_alt.as<uint64_t>(), st, vals.as<float>(), vals_alt.as<float>()));
     GRP_TRY(halloc(&h->w_local_in, n));
     GRP_TRY(halloc(&h->w_global_in, n));
     if (n == 0) return GRP_OK;
-    hipLaunchKernelGGL(row_mass_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, h->rowptr, h->csr_w, n, h->w_local_in);
-    GRP_LAUNCH_CHECK();
+    DevBuf mass_scratch;
+    GRP_TRY(mass_scratch.alloc(((size_t)n + 1) * sizeof(int32_t)));
+    GRP_TRY(launch_row_mass(h->rowptr, h->csr_w, n, h->w_local_in, mass_scratch.as<int32_t>(), st));
     // ---- every in-edge of an owned node, grouped by destination in edge-list order
     DevBuf cnt, off;
     GRP_TRY(cnt.alloc((size_t)(n + 1) * sizeof(int64_t)));
@@ -664,9 +778,9 @@ static grp_status weighted_build(const int64_t* src, const int64_t* dst, const f
     GRP_TRY(vin.alloc((size_t)total * sizeof(float)));
     GRP_TRY(vin_alt.alloc((size_t)total * sizeof(float)));
     if (total > 0) {
-        GRP_TRY(select(1));
-        hipLaunchKernelGGL(edge_emit_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, w, E, sel.as<int32_t>(),
-                           slot.as<int64_t>(), pos, 1, (uint64_t*)nullptr, k32.as<uint32_t>(), vin.as<float>());
+        GRP_TRY(place(1));
+        hipLaunchKernelGGL(ordered_emit_kernel<1>, dim3(oc_grid), dim3(256), 0, st, src, dst, w, E, own, n_tiles,
+                           (const int64_t*)tile_base, (uint64_t*)nullptr, k32.as<uint32_t>(), vin.as<float>());
         GRP_LAUNCH_CHECK();
         const unsigned end_bit = (unsigned)bits_for(n > 1 ? n : 2);
         size_t bytes = 0;
@@ -676,9 +790,7 @@ static grp_status weighted_build(const int64_t* src, const int64_t* dst, const f
         GRP_HIP(rocprim::radix_sort_pairs(sort_tmp.p, bytes, k32.as<uint32_t>(), k32_alt.as<uint32_t>(), vin.as<float>(),
                                           vin_alt.as<float>(), (size_t)total, 0u, end_bit, st));
     }
-    hipLaunchKernelGGL(row_mass_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, off.as<int64_t>(),
-                       vin_alt.as<float>(), n, h->w_global_in);
-    GRP_LAUNCH_CHECK();
+    GRP_TRY(launch_row_mass(off.as<int64_t>(), vin_alt.as<float>(), n, h->w_global_in, mass_scratch.as<int32_t>(), st));
     GRP_HIP(hipStreamSynchronize(st));
     return GRP_OK;
 }

@@ -51,6 +51,35 @@ def test_weighted_partition_bit_exact(g, kind, N, E, K):
     plain.destroy()
 
 
+def test_weight_masses_of_hub_rows_over_twenty_binades(g):
+    """Rows of more than 1024 weights are summed by a workgroup (256 runs added in order, then combined in
+    order) instead of one thread; with weights spread over twenty binades the fp64 partial sums round, so
+    those masses agree with the serial sum to fp64 rounding (1e-14 relative), the shorter rows exactly,
+    and everything else of the partition bit for bit."""
+    print("[case] weighted partition with hub rows, wide-range weights", flush=True)
+    N, K = 4000, 2
+    s, d = synth.uniform_graph(N, 60000, seed=51)
+    es, _ = synth.uniform_graph(N, 30000, seed=52)
+    ed = 7 + torch.arange(30000) % 3                       # three hubs with 10 000 extra in-edges each
+    s, d = torch.cat([s, es]), torch.cat([d, ed])
+    w = synth.edge_weights(s.numel(), 53, lo=1e-3, hi=1e3)
+    seen_long = 0
+    for p in range(K):
+        part = g.grp_partition_weighted(s.to(DEV), d.to(DEV), w.to(DEV), N, K, 7, p)
+        want = ograph.partition(s.numpy(), d.numpy(), N, K, 7, p, weights=w.numpy())
+        for key in ("l2g", "rowptr", "col", "colptr", "row", "d_local_in", "d_local_out", "d_global_in"):
+            assert np.array_equal(part.array(key), want[key]), key
+        got = part.weights()
+        assert np.array_equal(got["csr_w"], want["csr_w"]) and np.array_equal(got["csc_w"], want["csc_w"])
+        for key, deg in (("w_local_in", want["d_local_in"]), ("w_global_in", want["d_global_in"])):
+            short = deg <= 1024
+            seen_long += int((~short).sum())
+            assert np.array_equal(got[key][short], want[key][short]), key
+            np.testing.assert_allclose(got[key][~short], want[key][~short], rtol=1e-14, atol=0.0)
+        part.destroy()
+    assert seen_long >= 3
+
+
 def _step(g, part, dims, x, y, theta, mask, est, bf16=False):
     model = g.model_desc(g.ARCH_SAGE_MEAN, dims, g.DTYPE_BF16 if bf16 else g.DTYPE_FP32)
     opts = g.step_opts(estimator=est, full_graph=True)
