@@ -370,6 +370,18 @@ typedef struct grp_optimizer_desc {
 grp_status grp_optimizer_step(const grp_optimizer_desc* opt, int64_t P, int64_t step, float* theta,
                               const float* update, float* m, float* v, void* stream);
 
+/* The rows of a partition out of a tensor indexed by global node id (the feature movement the paper
+ * defers to repartitioning boundaries: when the partitions of a super-epoch are built, every worker
+ * takes its nodes' rows of the feature / label / mask tensors): out[r, :] = src[idx[r], :] for r in
+ * [0, n), rows of row_bytes bytes, both tensors dense row-major.
+ *   src   DEV [n_src x row_bytes]      idx  DEV int64[n] (a partition's l2g)      out  DEV [n x row_bytes]
+ *   keep  DEV uint8[n] or NULL: rows with keep[r] == 0 are zero-filled instead (e.g. the loss mask of a
+ *         sweeping partition: the training mask of its base chunk's nodes only)
+ * A row whose index is outside [0, n_src) is zero-filled.  16-byte moves when row_bytes and both
+ * pointers allow it.  Asynchronous on the stream.  Errors: GRP_EINVAL, GRP_EHIP.                    */
+grp_status grp_gather_rows(const void* src, int64_t n_src, int64_t row_bytes, const int64_t* idx, int64_t n,
+                           const uint8_t* keep, void* out, void* stream);
+
 /* ------------------------------------------------------------------ building blocks */
 
 /* Neighbour aggregation on a partition (the message-passing step of every layer):

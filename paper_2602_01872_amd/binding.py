@@ -73,6 +73,7 @@ def load() -> C.CDLL:
         "grp_partition": [vp, vp, i64, i64, i32, u64, i32, vp, C.POINTER(vp)],
         "grp_node_owners": [i64, i32, u64, vp, vp, vp],
         "grp_epoch_seeds": [vp, vp, u64, u64, vp, vp, C.POINTER(i64)],
+        "grp_gather_rows": [vp, i64, i64, vp, i64, vp, vp, vp],
         "grp_partition_weighted": [vp, vp, vp, i64, i64, i32, u64, i32, vp, C.POINTER(vp)],
         "grp_partition_weights": [vp, C.POINTER(PartitionWeights)],
         "grp_partition_from_local_coo": [vp, vp, i64, i64, vp, vp, vp, C.POINTER(vp)],
@@ -258,6 +259,17 @@ def grp_epoch_seeds(part: Partition, train_mask, sampler_seed: int, epoch: int, 
     return int(count.value)
 
 
+def grp_gather_rows(src, idx, keep=None, stream=None):
+    """Rows ``idx`` (int64 device tensor) of the dense tensor ``src`` ([n_src] or [n_src, F]) as a new tensor;
+    rows whose ``keep`` byte (uint8 device tensor [n]) is 0 are zero-filled."""
+    src = src.contiguous()
+    n = int(idx.numel())
+    out = torch.empty((n,) + tuple(src.shape[1:]), dtype=src.dtype, device=src.device)
+    row_bytes = src.element_size() * (int(src[0].numel()) if src.dim() > 1 else 1) if src.shape[0] > 0 else src.element_size()
+    _check(load().grp_gather_rows(_ptr(src), int(src.shape[0]), row_bytes, _ptr(idx), n, _ptr(keep), _ptr(out), _stream(stream)))
+    return out
+
+
 def grp_partition_weighted(src, dst, w, N: int, K: int, seed: int, part_id: int, stream=None) -> Partition:
     """``w``: float32 device tensor, one positive weight per edge."""
     out = C.c_void_p()
@@ -424,7 +436,7 @@ def read_stats(stats: torch.Tensor) -> np.ndarray:
 
 
 def exported_symbols():
-    return ["grp_last_error", "grp_partition", "grp_node_owners", "grp_epoch_seeds", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_view",
+    return ["grp_last_error", "grp_partition", "grp_node_owners", "grp_epoch_seeds", "grp_gather_rows", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_view",
             "grp_partition_destroy", "grp_chunks_build", "grp_chunks_build_assigned", "grp_chunks_destroy", "grp_partition_from_chunks",
             "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_step_activation", "grp_train_step",
             "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",

@@ -732,6 +732,52 @@ __global__ __launch_bounds__(256) void optimizer_kernel(int64_t P, float* __rest
 
 }  // namespace grp
 
+namespace grp {
+// out[r, :] = src[idx[r], :] for rows of `units` elements of type U; a row whose index is outside
+// [0, n_src) or whose keep byte is 0 is zero-filled.
+template <typename U>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const U* __restrict__ src, int64_t n_src, int64_t units,
+                                                          const int64_t* __restrict__ idx, int64_t n,
+                                                          const uint8_t* __restrict__ keep, U* __restrict__ out) {
+    const int64_t total = n * units;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t r = i / units, c = i - r * units;
+        const int64_t from = idx[r];
+        U v{};
+        if (from >= 0 && from < n_src && (!keep || keep[r])) v = src[from * units + c];
+        out[i] = v;
+    }
+}
+}  // namespace grp
+
+extern "C" grp_status grp_gather_rows(const void* src, int64_t n_src, int64_t row_bytes, const int64_t* idx, int64_t n,
+                                      const uint8_t* keep, void* out, void* stream) {
+    using namespace grp;
+    if (n < 0 || n_src < 0 || row_bytes < 1) return fail(GRP_EINVAL, "grp_gather_rows: n = %lld, n_src = %lld, row_bytes = %lld",
+                                                         (long long)n, (long long)n_src, (long long)row_bytes);
+    if (n == 0) return GRP_OK;
+    if (!src || !idx || !out) return fail(GRP_EINVAL, "grp_gather_rows: null pointer");
+    hipStream_t st = (hipStream_t)stream;
+    const uintptr_t both = (uintptr_t)src | (uintptr_t)out;
+    const double bytes = 2.0 * (double)n * (double)row_bytes + 8.0 * (double)n;
+    ProfScope ps("gather_rows", st, 0.0, bytes);
+    auto blocks = [](int64_t work) { int64_t b = (work + 255) / 256; return (unsigned)(b > 65536 ? 65536 : (b > 0 ? b : 1)); };
+    if (row_bytes % 16 == 0 && both % 16 == 0) {
+        const int64_t units = row_bytes / 16;
+        hipLaunchKernelGGL(gather_rows_kernel<uint4>, dim3(blocks(n * units)), dim3(256), 0, st, (const uint4*)src, n_src, units,
+                           idx, n, keep, (uint4*)out);
+    } else if (row_bytes % 4 == 0 && both % 4 == 0) {
+        const int64_t units = row_bytes / 4;
+        hipLaunchKernelGGL(gather_rows_kernel<uint32_t>, dim3(blocks(n * units)), dim3(256), 0, st, (const uint32_t*)src, n_src,
+                           units, idx, n, keep, (uint32_t*)out);
+    } else {
+        hipLaunchKernelGGL(gather_rows_kernel<uint8_t>, dim3(blocks(n * row_bytes)), dim3(256), 0, st, (const uint8_t*)src, n_src,
+                           row_bytes, idx, n, keep, (uint8_t*)out);
+    }
+    GRP_LAUNCH_CHECK();
+    return GRP_OK;
+}
+
 extern "C" grp_status grp_optimizer_step(const grp_optimizer_desc* opt, int64_t P, int64_t step, float* theta,
                                          const float* update, float* m, float* v, void* stream) {
     using namespace grp;

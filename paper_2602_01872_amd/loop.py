@@ -114,7 +114,7 @@ class MiniBatchTrainer:
         self.grads = torch.zeros(max_active, self.ld, device=dev)
         self.stats = g.new_stats(max_active, device=dev)
         self.seeds = [torch.zeros(max(p.n, 1), dtype=torch.int32, device=dev) for p in parts]
-        self.n_train = [p.n if mk is None else int(torch.count_nonzero(mk)) for p, mk in zip(parts, masks)]
+        self.n_train = [g.grp_epoch_seeds(p, mk, sampler_seed, 0, sd) for p, mk, sd in zip(parts, masks, self.seeds)]
         self.iters = max(1, max(-(-c // self.batch_size) for c in self.n_train))
         probe = g.step_opts(estimator=estimator, full_graph=False, seeds=self.seeds[0][:1], fanouts=self.fanouts)
         ws_bytes = 0
@@ -221,12 +221,12 @@ class SweepingTrainer:
             part = g.grp_partition_from_chunks(self.chunks, base, swept)
             l2g = torch.from_numpy(part.array("l2g")).to(self.x.device)
             mask = torch.from_numpy(part.base_mask()).to(self.x.device)
-            if self.train_mask is not None:
-                mask = mask & self.train_mask[l2g]
+            if self.train_mask is not None:            # the training nodes among the base chunk's nodes
+                mask = g.grp_gather_rows(self.train_mask, l2g, keep=mask)
             parts.append(part)
-            xs.append(self.x[l2g].contiguous())
-            ys.append(self.y[l2g].contiguous())
-            masks.append(mask.contiguous())
+            xs.append(g.grp_gather_rows(self.x, l2g))  # this worker's rows of the global tensors
+            ys.append(g.grp_gather_rows(self.y, l2g))
+            masks.append(mask)
         if self.minibatch is not None:
             mb = self.minibatch
             tr = MiniBatchTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active,

@@ -702,6 +702,36 @@ def test_phase_steps_on_several_streams_give_the_same_bits(g, arch):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("dtype,cols", [(torch.float32, 100), (torch.float32, 13), (torch.bfloat16, 128), (torch.bfloat16, 7),
+                                        (torch.int32, 0), (torch.uint8, 0), (torch.uint8, 5)])
+def test_gather_rows_bit_exact(g, dtype, cols):
+    """Rows of a global tensor by a partition's node list (16-, 4- and 1-byte moves; with and without the
+    keep mask; out-of-range indices zero-filled)."""
+    _note(f"gather rows {dtype} cols={cols}")
+    n_src, n = 5000, 1777
+    base = synth.stream_bits(9, 3, torch.arange(n_src * max(cols, 1)))
+    if dtype in (torch.float32, torch.bfloat16):
+        src = ((base % 2001).to(torch.float32) / 7.0 - 100.0).to(dtype)
+    else:
+        src = (base % 251).to(dtype)
+    src = src.reshape(n_src, cols) if cols else src.reshape(n_src)
+    idx = (synth.stream_bits(9, 4, torch.arange(n)) % n_src).abs()
+    idx[5], idx[6] = -1, n_src                                 # outside: zero rows
+    keep = (synth.stream_bits(9, 5, torch.arange(n)) % 3 != 0).to(torch.uint8)
+    for kp in (None, keep):
+        got = g.grp_gather_rows(src.to(DEV), idx.to(DEV), None if kp is None else kp.to(DEV)).cpu()
+        want = src[idx.clamp(0, n_src - 1)].clone()
+        dead = (idx < 0) | (idx >= n_src)
+        if kp is not None:
+            dead = dead | (kp == 0)
+        want[dead] = 0
+        assert got.dtype == src.dtype and got.shape == want.shape
+        assert torch.equal(got.view(torch.uint8) if dtype == torch.bfloat16 else got,
+                           want.view(torch.uint8) if dtype == torch.bfloat16 else want)
+    assert g.grp_gather_rows(src.to(DEV), idx[:0].to(DEV)).shape[0] == 0
+
+
+@pytest.mark.gpu
 def test_epoch_seed_order_bit_exact(g):
     _note("epoch seed order")
     N, E, K = 5000, 30000, 3
