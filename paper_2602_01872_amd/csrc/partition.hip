@@ -194,6 +194,19 @@ constexpr int DG_SLOTS = 4096;
 constexpr int DG_PROBES = 4;
 constexpr int EDGE_SCAN_GRID = 4096;      // fat workgroups: more edges of a hub meet in one table
 
+__device__ __forceinline__ void dg_table_add(int32_t* slot_key, uint32_t* slot_count, unsigned long long* __restrict__ dg,
+                                             int32_t r) {
+    uint32_t h = (uint32_t)r * 2654435761u >> 20;        // top 12 bits of a multiplicative hash
+    for (int probe = 0; probe < DG_PROBES; ++probe, h = (h + 1) & (DG_SLOTS - 1)) {
+        const int32_t seen = atomicCAS(&slot_key[h], -1, r);
+        if (seen == -1 || seen == r) {
+            atomicAdd(&slot_count[h], 1u);
+            return;
+        }
+    }
+    atomicAdd(&dg[r], 1ull);
+}
+
 __global__ __launch_bounds__(256) void edge_scan_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
                                                         int64_t E, int64_t N, NodeSet own,
                                                         unsigned long long* __restrict__ dg,
@@ -227,17 +240,7 @@ __global__ __launch_bounds__(256) void edge_scan_kernel(const int64_t* __restric
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             if (!mine[i]) continue;
-            const int32_t r = set_rank(own, vs[i]);
-            uint32_t h = (uint32_t)r * 2654435761u >> 20;            // top 12 bits of a multiplicative hash
-            bool placed = false;
-            for (int probe = 0; probe < DG_PROBES && !placed; ++probe, h = (h + 1) & (DG_SLOTS - 1)) {
-                const int32_t seen = atomicCAS(&slot_key[h], -1, r);
-                if (seen == -1 || seen == r) {
-                    atomicAdd(&slot_count[h], 1u);
-                    placed = true;
-                }
-            }
-            if (!placed) atomicAdd(&dg[r], 1ull);
+            dg_table_add(slot_key, slot_count, dg, set_rank(own, vs[i]));
             if (set_has(own, us[i])) kept++;
         }
     }
@@ -811,12 +814,19 @@ __global__ __launch_bounds__(256) void halo_scan_kernel(const int64_t* __restric
                                                         const int32_t* __restrict__ inner, const int64_t* __restrict__ pos,
                                                         unsigned long long* __restrict__ dg,
                                                         unsigned long long* __restrict__ kept_out) {
+    __shared__ int32_t slot_key[DG_SLOTS];               // in-degree counts go through an LDS table (see edge_scan_kernel)
+    __shared__ uint32_t slot_count[DG_SLOTS];
+    for (int i = threadIdx.x; i < DG_SLOTS; i += 256) { slot_key[i] = -1; slot_count[i] = 0u; }
+    __syncthreads();
     unsigned long long kept = 0;
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < E; e += (int64_t)gridDim.x * 256) {
         const int64_t v = dst[e];
-        if (member[v]) atomicAdd(&dg[pos[v]], 1ull);
+        if (member[v]) dg_table_add(slot_key, slot_count, dg, (int32_t)pos[v]);
         if (inner[v]) kept++;
     }
+    __syncthreads();
+    for (int i = threadIdx.x; i < DG_SLOTS; i += 256)
+        if (slot_key[i] >= 0) atomicAdd(&dg[slot_key[i]], (unsigned long long)slot_count[i]);
     for (int o = 32; o > 0; o >>= 1) kept += __shfl_down(kept, o, 64);
     if ((threadIdx.x & 63) == 0 && kept) atomicAdd(kept_out, kept);
 }
@@ -883,7 +893,8 @@ static grp_status halo_partition_impl(const int64_t* src, const int64_t* dst, in
         GRP_LAUNCH_CHECK();
     }
     if (E > 0) {
-        hipLaunchKernelGGL(halo_scan_kernel, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, member.as<int32_t>(),
+        const unsigned scan_grid = grid_for(E) < (unsigned)EDGE_SCAN_GRID ? grid_for(E) : (unsigned)EDGE_SCAN_GRID;
+        hipLaunchKernelGGL(halo_scan_kernel, dim3(scan_grid), dim3(256), 0, st, src, dst, E, member.as<int32_t>(),
                            inner.as<int32_t>(), pos.as<int64_t>(), (unsigned long long*)h->d_global_in,
                            counters.as<unsigned long long>());
         GRP_LAUNCH_CHECK();
