@@ -334,6 +334,82 @@ __global__ __launch_bounds__(256) void edge_keys_kernel(const int64_t* __restric
     }
 }
 
+// Both passes in one (unweighted builds): range check, global in-degrees of owned destinations and the keys of
+// the kept edges, written into a buffer of `cap` keys.  counters: [1] += bad ids, [2] += kept edges (the
+// slot cursor).  If the cursor ends above cap the keys are incomplete and the caller runs edge_keys_kernel
+// with a buffer of the exact size (the in-degrees and the count are complete either way).
+__global__ __launch_bounds__(256) void edge_scan_keys_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
+                                                             int64_t E, int64_t N, NodeSet own,
+                                                             unsigned long long* __restrict__ dg,
+                                                             unsigned long long* __restrict__ counters,
+                                                             uint64_t* __restrict__ keys, unsigned long long cap) {
+    constexpr int PER = 8;
+    const bool vec = (((uintptr_t)src | (uintptr_t)dst) & 15) == 0;
+    __shared__ int32_t slot_key[DG_SLOTS];
+    __shared__ uint32_t slot_count[DG_SLOTS];
+    __shared__ int wave_count[4];
+    __shared__ unsigned long long tile_base;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < DG_SLOTS; i += 256) { slot_key[i] = -1; slot_count[i] = 0u; }
+    __syncthreads();
+    unsigned long long bad = 0;
+    const int64_t n_tiles = (E + 256 * PER - 1) / (256 * PER);
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t e0 = tile * (256 * PER) + 2 * tid;
+        int64_t us[PER], vs[PER];
+#pragma unroll
+        for (int i = 0; i < PER; i += 2) {
+            const int64_t e = e0 + (int64_t)i * 256;
+            load_edge_pair(src, e, E, vec, 0, us[i], us[i + 1]);
+            load_edge_pair(dst, e, E, vec, -2, vs[i], vs[i + 1]);     // -2: past the end, neither counted nor an error
+        }
+        uint64_t key[PER];
+        int mine = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int64_t u = us[i], v = vs[i];
+            key[i] = ~0ull;
+            if (v == -2) continue;
+            if (u < 0 || v < 0 || u >= N || v >= N) { bad++; continue; }
+            if (!set_has(own, v)) continue;
+            const int32_t rv = set_rank(own, v);
+            dg_table_add(slot_key, slot_count, dg, rv);
+            if (set_has(own, u)) {
+                key[i] = ((uint64_t)(uint32_t)rv << 32) | (uint64_t)(uint32_t)set_rank(own, u);
+                ++mine;
+            }
+        }
+        int incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) wave_count[wave] = incl;
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) before += wave_count[w];
+            total += wave_count[w];
+        }
+        if (tid == 0) tile_base = total ? atomicAdd(&counters[2], (unsigned long long)total) : 0ull;
+        __syncthreads();
+        unsigned long long slot = tile_base + (unsigned long long)(before + incl - mine);
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (key[i] != ~0ull) {
+                if (slot < cap) keys[slot] = key[i];
+                ++slot;
+            }
+        __syncthreads();                                 // wave_count / tile_base are reused by the next tile
+    }
+    for (int i = tid; i < DG_SLOTS; i += 256)
+        if (slot_key[i] >= 0) atomicAdd(&dg[slot_key[i]], (unsigned long long)slot_count[i]);
+    for (int o = 32; o > 0; o >>= 1) bad += __shfl_down(bad, o, 64);
+    if (lane == 0 && bad) atomicAdd(&counters[1], bad);
+}
+
 // Local edge list: range check + keys in place order.
 __global__ __launch_bounds__(256) void local_keys_kernel(const int64_t* __restrict__ src, const int64_t* __restrict__ dst,
                                                          int64_t E, int64_t n, uint64_t* __restrict__ keys,
@@ -672,12 +748,24 @@ static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t
         GRP_TRY(exclusive_scan_popcount(t.scratch, set_scan_bytes, t.bits, t.before, n_words + 1, st));
         own = NodeSet{t.bits, t.before};
     }
+    const unsigned scan_grid = grid_for(E) < (unsigned)EDGE_SCAN_GRID ? grid_for(E) : (unsigned)EDGE_SCAN_GRID;
+    // unweighted: one pass writes the keys too, into a buffer sized for twice the expected E / K^2 kept edges
+    int64_t cap = weighted ? 0 : 2 * (E / K / K) + (1 << 20);
+    if (cap > E) cap = E;
+    DevBuf keybuf;                                       // both key arrays
+    size_t key_pitch = (((size_t)(cap > 0 ? cap : 1) * sizeof(uint64_t)) + 255) & ~(size_t)255;
+    if (!weighted) GRP_TRY(keybuf.alloc(2 * key_pitch));
     if (E > 0) {
-        const unsigned scan_grid = grid_for(E) < (unsigned)EDGE_SCAN_GRID ? grid_for(E) : (unsigned)EDGE_SCAN_GRID;
-        {
+        if (weighted) {
             ProfScope ps("partition_edge_scan", st, 0.0, 16.0 * (double)E);
             hipLaunchKernelGGL(edge_scan_kernel, dim3(scan_grid), dim3(256), 0, st, src, dst, E, N, own,
                                (unsigned long long*)h->d_global_in, counters.as<unsigned long long>());
+            GRP_LAUNCH_CHECK();
+        } else {
+            ProfScope ps("partition_edge_scan_keys", st, 0.0, 16.0 * (double)E);
+            hipLaunchKernelGGL(edge_scan_keys_kernel, dim3(scan_grid), dim3(256), 0, st, src, dst, E, N, own,
+                               (unsigned long long*)h->d_global_in, counters.as<unsigned long long>(), keybuf.as<uint64_t>(),
+                               (unsigned long long)cap);
             GRP_LAUNCH_CHECK();
         }
         GRP_HIP(hipMemcpyAsync(host_counters, counters.p, sizeof host_counters, hipMemcpyDeviceToHost, st));
@@ -685,20 +773,22 @@ static grp_status partition_impl(const int64_t* src, const int64_t* dst, int64_t
     }
     if (host_counters[1] != 0)
         return fail(GRP_ERANGE, "%llu edges have an endpoint outside [0, %lld)", host_counters[1], (long long)N);
-    const int64_t nnz = (int64_t)host_counters[0];
+    const int64_t nnz = (int64_t)(weighted ? host_counters[0] : host_counters[2]);
     h->nnz = nnz;
     if (weighted) return weighted_build(src, dst, w, E, own, st, h);
-    DevBuf keybuf;                                       // both key arrays
-    const size_t key_pitch = (((size_t)(nnz > 0 ? nnz : 1) * sizeof(uint64_t)) + 255) & ~(size_t)255;
-    GRP_TRY(keybuf.alloc(2 * key_pitch));
-    uint64_t* const keys = keybuf.as<uint64_t>();
-    uint64_t* const keys_alt = (uint64_t*)((char*)keybuf.p + key_pitch);
-    if (nnz > 0) {
+    DevBuf exact;                                        // only if the first buffer was too small
+    uint64_t* keys = keybuf.as<uint64_t>();
+    if (nnz > cap) {
+        key_pitch = (((size_t)nnz * sizeof(uint64_t)) + 255) & ~(size_t)255;
+        GRP_TRY(exact.alloc(2 * key_pitch));
+        keys = exact.as<uint64_t>();
+        GRP_HIP(hipMemsetAsync(counters.as<unsigned long long>() + 2, 0, sizeof(unsigned long long), st));
         ProfScope ps("partition_edge_keys", st, 0.0, 16.0 * (double)E + 8.0 * (double)nnz);
         hipLaunchKernelGGL(edge_keys_kernel<SetSelect>, dim3(grid_for(E)), dim3(256), 0, st, src, dst, E, SetSelect{own},
                            counters.as<unsigned long long>() + 2, keys);
         GRP_LAUNCH_CHECK();
     }
+    uint64_t* const keys_alt = (uint64_t*)((char*)keys + key_pitch);
     return build_csr_csc(h, keys, keys_alt, st);
 }
 

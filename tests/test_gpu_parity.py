@@ -390,6 +390,28 @@ def test_aggregate_invariants(g):
         assert rel_err(upd.cpu().numpy(), G) <= TOL_FP32
 
 
+@pytest.mark.gpu
+def test_partition_that_keeps_far_more_edges_than_a_random_one(g):
+    """Every edge lies inside partition 0 (a graph drawn on its nodes only), so the one-pass build's key
+    buffer, sized for about E / K^2 kept edges, overflows and the keys are written by the second pass."""
+    _note("partition with all edges kept")
+    N, K, E = 6000, 4, 1_600_000
+    owner = torch.empty(N, dtype=torch.int32, device=DEV)
+    g.grp_node_owners(N, K, 5, owner)
+    mine = torch.nonzero(owner == 0).flatten().cpu()
+    a, b = synth.uniform_graph(int(mine.numel()), E, seed=97)
+    s, d = mine[a], mine[b]
+    assert E > 2 * (E // K // K) + (1 << 20)                   # beyond the first buffer
+    part = g.grp_partition(s.to(DEV), d.to(DEV), N, K, 5, 0)
+    want = ograph.partition(s.numpy(), d.numpy(), N, K, 5, 0)
+    assert want["nnz"] == E
+    _assert_partition_equal(part, want)
+    part.destroy()
+    other = g.grp_partition(s.to(DEV), d.to(DEV), N, K, 5, 1)     # and a partition that keeps none of them
+    assert other.nnz == 0 and int(other.array("d_global_in").sum()) == 0
+    other.destroy()
+
+
 # ----------------------------------------------------------------------------- mini-batch + residual GCN
 @pytest.mark.parametrize("dims,fanouts,bf16,n_seeds", [
     ([32, 48, 6], (4, 3), False, 200),
