@@ -258,7 +258,16 @@ def run_evidence_workload(args, g, synth, torch, dev):
                  "grp_partition_halo_1hop_ms": timed(halo, 3) * 1e3, "grp_partition_weighted_ms": timed(wgt, 3) * 1e3,
                  "local_edges": {"hash": full.nnz, "base_alone": alone.nnz, "base_plus_swept": pair.nnz, "halo": halo.nnz}}
         ck.destroy()
-        kernels = _kernel_table(g, torch, full, reps)        # the two passes over the edge list
+        # the feature movement of a switch: this partition's rows of the global feature matrix
+        part0 = g.grp_partition(src, dst, N_NODES, K_PARTS, PART_SEED, PART_ID)
+        l2g0 = torch.from_numpy(part0.array("l2g")).to(dev)
+        xg = synth.normal_matrix(N_NODES, DIMS[0], GRAPH_SEED, device=dev)
+        dt_gather = timed(lambda: g.grp_gather_rows(xg, l2g0), reps)
+        times["gather_feature_rows_ms"] = dt_gather * 1e3
+        times["gather_feature_rows_GBs"] = (2.0 * part0.n * DIMS[0] * 4 + 8.0 * part0.n) / dt_gather / 1e9
+        part0.destroy()
+        del xg, l2g0
+        kernels = _kernel_table(g, torch, full, reps)        # the pass over the edge list
         dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
         out.update(metric="edges/s scanned by grp_partition (one partition of 8 from the whole edge list)", unit="edges/s",
                    value=N_EDGES / dt_full, ms_per_step=dt_full * 1e3, dtype="int64", steps=reps,
