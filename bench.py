@@ -139,7 +139,7 @@ def run_evidence_workload(args, g, synth, torch, dev):
         upd = torch.empty(P, device=dev)
         fn = lambda: g.grp_aggregate(grads, P, stats, K, P, g.EST_NONE, upd)
         dt = _time_steps(torch, fn, args.warmup, args.steps)
-        kernels = _kernel_table(g, torch, fn, args.steps)
+        kernels = _kernel_table(g, torch, fn, args.steps, detail=args.shapes)
         out.update(metric="aggregated gradient bytes/s (K=64, P=2^26; non-config stress shape)", unit="GB/s",
                    value=4.0 * P * (K + 1) / dt / 1e9, ms_per_step=dt * 1e3, dtype="f32",
                    config={"workload": "aggregate-stress: K=64 partition gradients of P=2^26 floats"},
@@ -206,7 +206,7 @@ def run_evidence_workload(args, g, synth, torch, dev):
         graph, graph_lanes = captured(fn), captured(fn_lanes)
         dt_graph = _time_steps(torch, graph.replay, args.warmup, args.steps)
         dt_graph_lanes = _time_steps(torch, graph_lanes.replay, args.warmup, args.steps)
-        kernels = _kernel_table(g, torch, fn, args.steps)
+        kernels = _kernel_table(g, torch, fn, args.steps, detail=args.shapes)
         nnz = sum(p.nnz for p in parts)
         best = min(dt, dt_lanes, dt_graph, dt_graph_lanes)
         out.update(metric="train-step edges/s over the 4 partitions (fwd+bwd), one iteration = 4 steps + aggregate + optimizer",
@@ -358,7 +358,7 @@ def run_evidence_workload(args, g, synth, torch, dev):
         ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=dev)
         fn = lambda: g.grp_train_step(part, model, opts, x, y, None, theta, ws, grad, stats)
         dt = _time_steps(torch, fn, args.warmup, args.steps)
-        kernels = _kernel_table(g, torch, fn, args.steps)
+        kernels = _kernel_table(g, torch, fn, args.steps, detail=args.shapes)
         out.update(metric="per-partition train-step edges/s (fwd+bwd)", unit="edges/s", value=part.nnz / dt,
                    ms_per_step=dt * 1e3, dtype="f32",
                    config={"workload": (f"c2-gat-step: GAT-3 (one head) {dims}" if gat else
@@ -404,7 +404,7 @@ def run_evidence_workload(args, g, synth, torch, dev):
             g.grp_spmm(part, False, g.SCALE_MEAN, False, F, x, F, dt_code, y, F)      # forward (CSR)
             g.grp_spmm(part, True, g.SCALE_MEAN, False, F, x, F, dt_code, y, F)       # transposed (CSC)
         dt = _time_steps(torch, fn, args.warmup, args.steps)
-        kernels = _kernel_table(g, torch, fn, args.steps)
+        kernels = _kernel_table(g, torch, fn, args.steps, detail=args.shapes)
         el = 2 if bf16 else 4
         b_min = 4 * nnz + 8 * (n + 1) + el * F * n + 4 * F * n
         out.update(metric="SpMM edges/s (one forward + one transposed aggregation)", unit="edges/s",
@@ -447,7 +447,7 @@ def run_evidence_workload(args, g, synth, torch, dev):
     log(f"{wl}: workspace {ws.numel() / 1e9:.2f} GB, P={P}")
     fn = lambda: g.grp_train_step(part, model, opts, x, y, None, theta, ws, grad, stats)
     dt = _time_steps(torch, fn, args.warmup, args.steps)
-    kernels = _kernel_table(g, torch, fn, args.steps)
+    kernels = _kernel_table(g, torch, fn, args.steps, detail=args.shapes)
     used = int(g.read_stats(stats)[0]["nnz_used"])
     out.update(metric="per-partition train-step edges/s (fwd+bwd)", unit="edges/s", value=used / dt, ms_per_step=dt * 1e3,
                dtype="bf16-stored features, f32 arithmetic" if wl in ("c3-step", "c5-step") else "f32",
