@@ -92,3 +92,21 @@ def test_header_is_plain_c_and_its_struct_layouts_are_the_bindings(tmp_path):
             continue
         assert size == C.sizeof(ctype), name
         assert offs == [getattr(ctype, m).offset for m in members], name
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_binding_fails_loudly_without_the_built_library(monkeypatch):
+    # no fallback path: a missing library is an ImportError at the first call, not a silent CPU route
+    from paper_2602_01872_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", os.path.join(os.path.dirname(binding.LIB_PATH), "no_such_library.so"))
+    with pytest.raises(ImportError):
+        binding.load()
