@@ -1358,7 +1358,7 @@ extern "C" grp_status grp_node_owners(int64_t N, int32_t K, uint64_t seed, int32
     if (N < 0 || K < 1) return fail(GRP_EINVAL, "grp_node_owners: N = %lld, K = %d", (long long)N, K);
     if (N > 0 && !owner_out) return fail(GRP_EINVAL, "grp_node_owners: null output");
     hipStream_t st = (hipStream_t)stream;
-    if (count_out) GRP_HIP(hipMemsetAsync(count_out, 0, (size_t)K * sizeof(int64_t), st));
+    if (count_out) GRP_TRY(launch_fill_zero(count_out, (size_t)K * sizeof(int64_t), st));    // a kernel: the call can be captured in a graph
     if (N == 0) return GRP_OK;
     int64_t blocks = cdiv(N, 256 * 8);
     if (blocks > 4096) blocks = 4096;
