@@ -178,6 +178,26 @@ grp_status grp_partition_from_local_coo(const int64_t* src_local, const int64_t*
                                         int64_t E, int64_t n, const int64_t* d_global_in,
                                         const int64_t* l2g, void* stream, grp_partition_t** out);
 
+/* Adopt a partition's share that already exists as rows of in-edges ("Isolated Training": a worker
+ * holds exclusively its local nodes and edges; at the paper's largest scale, a trillion-edge graph
+ * trained one partition at a time, a share has 2^32 edges, and an edge list of it plus the buffers of
+ * a sort would not leave room for the step).
+ *   rowptr  DEV int64[n+1]  0 = rowptr[0] <= ... <= rowptr[n] = nnz
+ *   col     DEV int32[nnz]  local source ids in [0, n), ascending inside every row (duplicates kept)
+ * The handle BORROWS both arrays: they are not copied, must stay valid and unchanged until
+ * grp_partition_destroy, and are returned as they are by grp_partition_view.  The call builds the
+ * transposed structure (colptr / row, destinations ascending), the degree arrays and the schedules of
+ * the long rows; d_global_in / l2g as in grp_partition_from_local_coo (copied).
+ *   slice_edges  upper bound on the edges transposed at a time (0 = 2^28): temporary device memory is
+ *                about 24 bytes per edge of a slice; a slice holds whole runs of n/4096 consecutive
+ *                sources, so the bound is raised to the largest such run if that is larger.
+ * Synchronous.  Errors: GRP_EINVAL (null, negative sizes, row pointers that are not a non-decreasing
+ * sequence from 0 to nnz, a row whose sources are not ascending), GRP_ERANGE (a source outside [0, n),
+ * n >= 2^31), GRP_ENOMEM, GRP_EHIP.  On error *out is NULL.                                           */
+grp_status grp_partition_from_csr(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t nnz,
+                                  const int64_t* d_global_in, const int64_t* l2g, int64_t slice_edges,
+                                  void* stream, grp_partition_t** out);
+
 grp_status grp_partition_view(const grp_partition_t* part, grp_partition_view_t* view /*HOST*/);
 grp_status grp_partition_destroy(grp_partition_t* part);   /* NULL is a no-op */
 

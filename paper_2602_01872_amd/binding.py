@@ -77,6 +77,7 @@ def load() -> C.CDLL:
         "grp_partition_weighted": [vp, vp, vp, i64, i64, i32, u64, i32, vp, C.POINTER(vp)],
         "grp_partition_weights": [vp, C.POINTER(PartitionWeights)],
         "grp_partition_from_local_coo": [vp, vp, i64, i64, vp, vp, vp, C.POINTER(vp)],
+        "grp_partition_from_csr": [vp, vp, i64, i64, vp, vp, i64, vp, C.POINTER(vp)],
         "grp_partition_halo": [vp, vp, i64, i64, i32, u64, i32, i32, vp, C.POINTER(vp)],
         "grp_partition_view": [vp, C.POINTER(PartitionView)],
         "grp_chunks_build": [vp, vp, i64, i64, i32, u64, vp, C.POINTER(vp)],
@@ -287,6 +288,18 @@ def grp_partition_from_local_coo(src_local, dst_local, n: int, d_global_in=None,
     return Partition(out.value)
 
 
+def grp_partition_from_csr(rowptr, col, n: int, d_global_in=None, l2g=None, slice_edges: int = 0, stream=None) -> Partition:
+    """``rowptr`` int64 [n+1], ``col`` int32 [nnz] device tensors; the handle borrows them (kept alive by the
+    returned object)."""
+    out = C.c_void_p()
+    nnz = 0 if col is None else int(col.numel())
+    _check(load().grp_partition_from_csr(_ptr(rowptr), _ptr(col), n, nnz, _ptr(d_global_in), _ptr(l2g), slice_edges,
+                                         _stream(stream), C.byref(out)))
+    part = Partition(out.value)
+    part._borrowed = (rowptr, col)
+    return part
+
+
 class Chunks:
     """Owns a grp_chunks_t handle (the graph split once into chunks)."""
 
@@ -436,7 +449,7 @@ def read_stats(stats: torch.Tensor) -> np.ndarray:
 
 
 def exported_symbols():
-    return ["grp_last_error", "grp_partition", "grp_node_owners", "grp_epoch_seeds", "grp_gather_rows", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_view",
+    return ["grp_last_error", "grp_partition", "grp_node_owners", "grp_epoch_seeds", "grp_gather_rows", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_from_csr", "grp_partition_view",
             "grp_partition_destroy", "grp_chunks_build", "grp_chunks_build_assigned", "grp_chunks_destroy", "grp_partition_from_chunks",
             "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_step_activation", "grp_train_step",
             "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",

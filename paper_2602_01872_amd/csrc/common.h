@@ -99,6 +99,7 @@ struct grp_partition_s {
     uint8_t* base_mask = nullptr;    // partitions built from chunks: 1 for the base chunk's nodes
     void* slab = nullptr;            // one allocation that holds the CSR / CSC arrays and the long-row schedules
     size_t slab_bytes = 0;
+    bool borrowed_csr = false;       // rowptr / col belong to the caller (grp_partition_from_csr): never freed here
     int device = 0;
 };
 

@@ -553,6 +553,7 @@ struct DevView {                          // a typed look at part of an allocati
 
 static void free_partition(grp_partition_t* h) {
     if (!h) return;
+    if (h->borrowed_csr) { h->rowptr = nullptr; h->col = nullptr; }
     void* ptrs[] = {h->l2g, h->rowptr, h->col, h->colptr, h->row, h->d_local_in, h->d_local_out, h->d_global_in,
                     h->csr_long.long_row, h->csr_long.long_first, h->csr_long.chunk_begin, h->csr_long.chunk_end,
                     h->csc_long.long_row, h->csc_long.long_first, h->csc_long.chunk_begin, h->csc_long.chunk_end,

@@ -66,6 +66,30 @@ def uniform_graph(n_nodes: int, n_edges: int, seed: int, device="cpu"):
     return src, dst
 
 
+def _rmat_range(scale: int, lo: int, hi: int, seed: int, n_nodes: int, a: float = 0.57, b: float = 0.19,
+                c: float = 0.19, device="cpu"):
+    """Edges number lo .. hi-1 of the R-MAT stream (see rmat_graph)."""
+    ta = int(a * 65536)
+    tb = int((a + b) * 65536)
+    tc = int((a + b + c) * 65536)
+    e = torch.arange(lo, hi, dtype=torch.int64, device=device)
+    s = torch.zeros_like(e)
+    d = torch.zeros_like(e)
+    bits = None
+    for lvl in range(scale):
+        if lvl % 4 == 0:
+            bits = stream_bits(seed, 16 + lvl // 4, e)
+        r = _lsr(bits, 16 * (lvl % 4)) & 0xFFFF
+        sbit = (r >= tb).to(torch.int64)                  # quadrants c, d: src bit set
+        dbit = ((r >= ta) & (r < tb) | (r >= tc)).to(torch.int64)  # quadrants b, d
+        s = (s << 1) | sbit
+        d = (d << 1) | dbit
+    scr = _wrap64(seed * _G2 + 99)
+    s = _lsr(_fmix(s ^ scr), 1) % n_nodes
+    d = _lsr(_fmix(d ^ scr), 1) % n_nodes
+    return s, d
+
+
 def rmat_graph(scale: int, n_edges: int, seed: int, n_nodes: int | None = None,
                a: float = 0.57, b: float = 0.19, c: float = 0.19, device="cpu",
                chunk: int = 1 << 26, progress=None):
@@ -79,27 +103,10 @@ def rmat_graph(scale: int, n_edges: int, seed: int, n_nodes: int | None = None,
     """
     if n_nodes is None:
         n_nodes = 1 << scale
-    ta = int(a * 65536)
-    tb = int((a + b) * 65536)
-    tc = int((a + b + c) * 65536)
     src_parts, dst_parts = [], []
     for lo in range(0, n_edges, chunk):
         hi = min(n_edges, lo + chunk)
-        e = torch.arange(lo, hi, dtype=torch.int64, device=device)
-        s = torch.zeros_like(e)
-        d = torch.zeros_like(e)
-        bits = None
-        for lvl in range(scale):
-            if lvl % 4 == 0:
-                bits = stream_bits(seed, 16 + lvl // 4, e)
-            r = _lsr(bits, 16 * (lvl % 4)) & 0xFFFF
-            sbit = (r >= tb).to(torch.int64)                  # quadrants c, d: src bit set
-            dbit = ((r >= ta) & (r < tb) | (r >= tc)).to(torch.int64)  # quadrants b, d
-            s = (s << 1) | sbit
-            d = (d << 1) | dbit
-        scr = _wrap64(seed * _G2 + 99)
-        s = _lsr(_fmix(s ^ scr), 1) % n_nodes
-        d = _lsr(_fmix(d ^ scr), 1) % n_nodes
+        s, d = _rmat_range(scale, lo, hi, seed, n_nodes, a, b, c, device)
         src_parts.append(s)
         dst_parts.append(d)
         if progress is not None:
@@ -107,6 +114,51 @@ def rmat_graph(scale: int, n_edges: int, seed: int, n_nodes: int | None = None,
     if len(src_parts) == 1:
         return src_parts[0], dst_parts[0]
     return torch.cat(src_parts), torch.cat(dst_parts)
+
+
+def rmat_local_csr(scale: int, n_edges: int, seed: int, n_nodes: int | None = None, device="cpu",
+                   chunk: int = 1 << 28, slice_edges: int = 1 << 28, progress=None, **rmat):
+    """The edges of ``rmat_graph`` (same arguments, same multiset) as rows of in-edges: ``rowptr`` int64
+    [n_nodes + 1] and ``col`` int32 [n_edges], row v listing the sources of the edges into v in ascending
+    order, duplicates kept.  For shares too large to hold as an edge list next to a sort of it (2**32 edges):
+    the edges are generated ``chunk`` at a time and kept only as sorted 64-bit keys (dst << 32 | src), then
+    merged one range of destinations of about ``slice_edges`` edges at a time."""
+    if n_nodes is None:
+        n_nodes = 1 << scale
+    sorted_chunks = []
+    for lo in range(0, n_edges, chunk):
+        hi = min(n_edges, lo + chunk)
+        s, d = _rmat_range(scale, lo, hi, seed, n_nodes, device=device, **rmat)
+        key = (d << 32) | s
+        del s, d
+        sorted_chunks.append(torch.sort(key)[0])
+        del key
+        if progress is not None:
+            progress(hi, n_edges)
+    col = torch.empty(n_edges, dtype=torch.int32, device=device)
+    deg = torch.zeros(n_nodes, dtype=torch.int64, device=device)
+    n_slices = max(1, -(-n_edges // slice_edges))
+    bounds = [n_nodes * i // n_slices for i in range(n_slices + 1)]
+    at = 0
+    for i in range(n_slices):
+        d0, d1 = bounds[i], bounds[i + 1]
+        lim = torch.tensor([d0 << 32, d1 << 32], dtype=torch.int64, device=device)
+        pieces = []
+        for c in sorted_chunks:
+            a, b = torch.searchsorted(c, lim).tolist()
+            pieces.append(c[a:b])
+        keys = torch.sort(torch.cat(pieces))[0] if len(pieces) > 1 else pieces[0]
+        del pieces
+        cnt = int(keys.numel())
+        col[at:at + cnt] = (keys & 0xFFFFFFFF).to(torch.int32)
+        if cnt:
+            deg[d0:d1] = torch.bincount((keys >> 32) - d0, minlength=d1 - d0)
+        at += cnt
+        del keys
+    assert at == n_edges
+    rowptr = torch.zeros(n_nodes + 1, dtype=torch.int64, device=device)
+    torch.cumsum(deg, 0, out=rowptr[1:])
+    return rowptr, col
 
 
 def normal_matrix(rows: int, cols: int, seed: int, stream: int = 3, std: float = 1.0,
