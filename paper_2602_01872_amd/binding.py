@@ -179,6 +179,19 @@ class Partition:
             _hip_memcpy_d2h(out, getattr(self.view, name))
         return out
 
+    def device_array(self, name: str) -> torch.Tensor:
+        """Device copy of one of the handle's arrays as a torch tensor (for checks at sizes where a host
+        copy is too slow)."""
+        dt, count = {"l2g": (torch.int64, self.n), "rowptr": (torch.int64, self.n + 1), "col": (torch.int32, self.nnz),
+                     "colptr": (torch.int64, self.n + 1), "row": (torch.int32, self.nnz), "d_local_in": (torch.int32, self.n),
+                     "d_local_out": (torch.int32, self.n), "d_global_in": (torch.int64, self.n)}[name]
+        out = torch.empty(count, dtype=dt, device="cuda")
+        if count:
+            torch.cuda.synchronize()
+            _hip_memcpy(out.data_ptr(), getattr(self.view, name), out.numel() * out.element_size(), 3)
+            torch.cuda.synchronize()
+        return out
+
     def weights(self):
         """Host copies of a weighted partition's arrays as a dict (None for an unweighted one)."""
         w = PartitionWeights()
@@ -227,16 +240,20 @@ class Partition:
 _hip = None
 
 
-def _hip_memcpy_d2h(dst: np.ndarray, src_ptr: int):
+def _hip_memcpy(dst_ptr: int, src_ptr: int, nbytes: int, kind: int):
     global _hip
     if _hip is None:
         # the SONAME resolves to the HIP runtime torch already loaded (never a second copy)
         _hip = C.CDLL("libamdhip64.so.7")
         _hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
         _hip.hipMemcpy.restype = C.c_int
-    rc = _hip.hipMemcpy(dst.ctypes.data, src_ptr, dst.nbytes, 2)
+    rc = _hip.hipMemcpy(dst_ptr, src_ptr, nbytes, kind)
     if rc != 0:
-        raise RuntimeError(f"hipMemcpy D2H failed: {rc}")
+        raise RuntimeError(f"hipMemcpy (kind {kind}) failed: {rc}")
+
+
+def _hip_memcpy_d2h(dst: np.ndarray, src_ptr: int):
+    _hip_memcpy(dst.ctypes.data, src_ptr, dst.nbytes, 2)
 
 
 def grp_partition(src, dst, N: int, K: int, seed: int, part_id: int, stream=None) -> Partition:
