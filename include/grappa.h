@@ -310,7 +310,7 @@ grp_status grp_step_workspace_bytes(const grp_partition_t* part, const grp_model
  * the chosen edges keep their row order; layers are built from the seeds inwards (the seeds draw
  * fanouts[k-1]); the mean
  * of a layer divides by the number of sampled neighbours.  Fanouts must lie in [1, 64]; seeds
- * must be distinct.  This mode synchronises the stream once per layer above the input layer
+ * must be distinct (not checked) and lie in [0, n) (checked: GRP_ERANGE).  This mode synchronises the stream once per layer above the input layer
  * (the sampled block sizes are needed on the host); the workspace is sized from the seeds and
  * fanouts alone.
  * Errors: GRP_EINVAL, GRP_EWORKSPACE, GRP_EUNSUPPORTED (mini-batch with a GCN arch; a
@@ -345,6 +345,28 @@ grp_status grp_epoch_seeds(const grp_partition_t* part, const uint8_t* train_mas
 grp_status grp_step_activation(const grp_partition_t* part, const grp_model_desc* model,
                                const grp_step_opts* opts, void* workspace, size_t workspace_bytes,
                                int32_t layer, const float** act_out /*HOST*/, int64_t* ld_out /*HOST*/);
+
+/* Inspection: the bipartite block that the isolated sampler of grp_train_step (mini-batch mode) built for
+ * layer `layer` and left inside the workspace it was given (same partition, model and options;
+ * "Isolated Training": k-hop subgraphs are sampled from the local partition only).  Borrowed DEV
+ * pointers into the workspace, valid until it is reused:
+ *   rowptr     int64[n_dst+1]  edges of destination row i: [rowptr[i], rowptr[i+1]), in ascending position
+ *                              of the partition's CSR row
+ *   col        int32[nnz]      layers >= 1: index into the block's source list; layer 0: partition-local id
+ *   dst_nodes  int32[n_dst]    partition-local id of destination row i (the seeds for the last layer)
+ *   src_nodes  int32[n_src]    layers >= 1: the block's source list = its destinations, then the newly
+ *                              reached nodes in ascending local id; NULL for layer 0 (sources = all nodes)
+ * Reads the block sizes back from the device: synchronises the device.
+ * Errors: GRP_EINVAL (full-graph options, layer out of range), GRP_EWORKSPACE, GRP_EHIP.             */
+typedef struct {
+    int64_t        n_dst, n_src, nnz;
+    const int64_t* rowptr;
+    const int32_t* col;
+    const int32_t* dst_nodes;
+    const int32_t* src_nodes;
+} grp_block_view_t;
+grp_status grp_step_block(const grp_partition_t* part, const grp_model_desc* model, const grp_step_opts* opts,
+                          void* workspace, size_t workspace_bytes, int32_t layer, grp_block_view_t* view /*HOST*/);
 
 /* ------------------------------------------------------------------ aggregation */
 
@@ -404,17 +426,22 @@ grp_status grp_gather_rows(const void* src, int64_t n_src, int64_t row_bytes, co
 
 /* ------------------------------------------------------------------ building blocks */
 
+#define GRP_SCALE_NONE  0
+#define GRP_SCALE_MEAN  1
+#define GRP_SCALE_RSQRT 2
 /* Neighbour aggregation on a partition (the message-passing step of every layer):
  *   transposed = 0:  Y[v,:] = a_v (sum_{u->v} X[u,:] + self*X[v,:])     rows of the CSR
  *   transposed = 1:  Y[u,:] = a_u (sum_{u->v} X[v,:] + self*X[u,:])     rows of the CSC
  * a = 1 (scale GRP_SCALE_NONE), 1/max(deg,1) (MEAN) or 1/sqrt(deg+self) clamped at
- * deg>=1 (RSQRT), deg = the row's length.  X: DEV [n x F] fp32/bf16, Y: DEV [n x F] fp32. */
-#define GRP_SCALE_NONE  0
-#define GRP_SCALE_MEAN  1
-#define GRP_SCALE_RSQRT 2
+ * deg>=1 (RSQRT), deg = the row's length.  X: DEV [n x F] fp32/bf16, Y: DEV [n x F] fp32.
+ * Scratch for the partial sums of the rows the partition splits (rows of more than 512 edges):
+ * grp_spmm_workspace_bytes gives the size for this direction and F (0 when no row is split); `workspace`
+ * is DEV, 16-byte aligned, contents undefined afterwards.  The call allocates nothing and is asynchronous
+ * on the stream.  Errors: GRP_EINVAL, GRP_EWORKSPACE, GRP_EUNSUPPORTED (F > 1024).                    */
+grp_status grp_spmm_workspace_bytes(const grp_partition_t* part, int32_t transposed, int32_t F, size_t* bytes /*HOST*/);
 grp_status grp_spmm(const grp_partition_t* part, int32_t transposed, int32_t scale,
                     int32_t self_term, int32_t F, const void* X, int64_t ldx, int32_t x_dtype,
-                    float* Y, int64_t ldy, void* stream);
+                    float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Dense transforms on the matrix cores (fp32 MFMA, fp32 accumulate):
  *   grp_gemm_nn:  C[M x N] = A[M x K] B[K x N]            (X W, dY W^T with B given transposed)

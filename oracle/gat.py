@@ -87,7 +87,7 @@ def _layer_backward(h, esrc, edst, n, w, a_s, a_d, saved, dout, need_dh):
 
 
 def forward_backward(dims, theta, x, blk, labels, node_w, loss_nodes, return_logits=False,
-                     relu_flip=None, near_kink=None, drop=None, relu_set=None):
+                     relu_flip=None, near_kink=None, drop=None, relu_set=None, keep_z=None):
     """Loss and flat gradient of a k-layer GAT on the full local graph ``blk`` (n_src = n_dst).
 
     ``relu_flip`` / ``near_kink`` / ``drop`` as in ``gnn.forward_backward`` (dropout acts on the
@@ -110,6 +110,8 @@ def forward_backward(dims, theta, x, blk, labels, node_w, loss_nodes, return_log
         if drop and l < k - 1:
             h = h * drop[l]
     logits = h
+    if keep_z is not None:          # for checkers that look at individual pre-activations
+        keep_z.extend(zs)
     loss, dz = softmax_xent(logits, labels, node_w, loss_nodes)
     grads = [None] * k
     dh_next = None

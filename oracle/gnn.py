@@ -194,7 +194,8 @@ def _gcn_backward(h, blk, w, saved, dz, need_dh, self_loops):
 
 
 def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
-                     gcn_self_loops=True, return_logits=False, relu_flip=None, near_kink=None, drop=None, relu_set=None):
+                     gcn_self_loops=True, return_logits=False, relu_flip=None, near_kink=None, drop=None, relu_set=None,
+                     keep_z=None):
     """Loss and flat parameter gradient of a k-layer model.
 
     ``blocks`` has one block per layer (input side first); pass the same block k times for
@@ -206,6 +207,8 @@ def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
     ``relu_set``: {(layer, row, col): bool} fixes the ReLU derivative decision of the listed elements
     (a checker passes the decisions another implementation took for the ``near_kink`` elements).
     ``drop``: per hidden layer the factor array keep / (1 - rate) of its output ([] or None: no dropout).
+    ``keep_z``: a list that receives the pre-activation array of every layer (for checkers that look at
+    individual elements).
     """
     if arch not in ARCHS:
         raise ValueError("unknown arch")
@@ -235,6 +238,8 @@ def forward_backward(arch, dims, theta, x, blocks, labels, node_w, loss_nodes,
                 a = h[:blk["n_dst"]] + a
             h = a
     logits = h
+    if keep_z is not None:
+        keep_z.extend(zs)
     loss, dz = softmax_xent(logits, labels, node_w, loss_nodes)
 
     grads = [None] * k

@@ -14,7 +14,7 @@ from . import coverage, dropout as dropout_mod, gat, gnn, sampling
 def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
                estimator: int = coverage.NONE, gcn_self_loops: bool = True,
                minibatch: dict | None = None, relu_flip=None, near_kink=None,
-               dropout: dict | None = None, relu_set=None):
+               dropout: dict | None = None, relu_set=None, keep_z=None):
     """Returns (grad[P] float64, stats dict) for one partition.
 
     full-graph mode (``minibatch is None``): every local node is an input, the loss runs
@@ -22,8 +22,8 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
     mini-batch mode: ``minibatch = dict(seeds=int array of local ids, fanouts=(f_0..f_{k-1}),
     sampler_seed=int, batch_id=int)``; fanouts[l] belongs to layer l, layer 0 being the input
     side, so the seeds draw fanouts[k-1] neighbours.
-    ``relu_flip`` / ``near_kink`` / ``relu_set`` are passed to ``gnn.forward_backward``; with ``near_kink`` the
-    stats dict gains the key "near_kink".
+    ``relu_flip`` / ``near_kink`` / ``relu_set`` / ``keep_z`` are passed to ``gnn.forward_backward``; with
+    ``near_kink`` the stats dict gains the key "near_kink".
     A partition built with edge weights (``graph.partition(..., weights=)``) trains the weighted-mean
     GraphSAGE aggregator and reports the coverage statistics of the weight masses (full-graph mode).
     ``dropout = dict(rate=, seed=, batch_id=)`` drops hidden activations as ``dropout.py`` describes,
@@ -54,10 +54,11 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
             loss_nodes = np.flatnonzero(np.asarray(train_mask) != 0).astype(np.int64)
         if arch == "gat":
             res = gat.forward_backward(dims, theta, x, blk, labels, w_all, loss_nodes,
-                                       relu_flip=relu_flip, near_kink=near_kink, drop=drop, relu_set=relu_set)
+                                       relu_flip=relu_flip, near_kink=near_kink, drop=drop, relu_set=relu_set, keep_z=keep_z)
         else:
             res = gnn.forward_backward(arch, dims, theta, x, [blk] * k, labels, w_all, loss_nodes,
-                                       gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink, drop=drop, relu_set=relu_set)
+                                       gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink, drop=drop, relu_set=relu_set,
+                                       keep_z=keep_z)
         loss, grad = res[0], res[1]
         if weighted:
             st = coverage.coverage_stats_weighted(part["w_local_in"], part["w_global_in"], dl, dg, loss_nodes)
@@ -88,7 +89,8 @@ def train_step(part: dict, arch: str, dims, theta, x, labels, train_mask=None,
             drop.append(keep.astype(np.float64) * sc)
     res = gnn.forward_backward(arch, dims, theta, xin, blocks, np.asarray(labels)[seeds],
                                w_all[seeds], np.arange(nseed, dtype=np.int64),
-                               gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink, relu_set=relu_set, drop=drop)
+                               gcn_self_loops, relu_flip=relu_flip, near_kink=near_kink, relu_set=relu_set, drop=drop,
+                               keep_z=keep_z)
     loss, grad = res[0], res[1]
     last = blocks[-1]
     sampled = np.bincount(last["edst"], minlength=nseed)

@@ -45,6 +45,11 @@ class PartitionWeights(C.Structure):
     _fields_ = [("csr_w", C.c_void_p), ("csc_w", C.c_void_p), ("w_local_in", C.c_void_p), ("w_global_in", C.c_void_p)]
 
 
+class BlockView(C.Structure):
+    _fields_ = [("n_dst", C.c_int64), ("n_src", C.c_int64), ("nnz", C.c_int64), ("rowptr", C.c_void_p), ("col", C.c_void_p),
+                ("dst_nodes", C.c_void_p), ("src_nodes", C.c_void_p)]
+
+
 class StepOpts(C.Structure):
     _fields_ = [("estimator", C.c_int32), ("full_graph", C.c_int32), ("n_seeds", C.c_int32),
                 ("reserved", C.c_int32), ("seeds", C.c_void_p), ("fanouts", C.c_int32 * GRP_MAX_LAYERS),
@@ -88,10 +93,12 @@ def load() -> C.CDLL:
         "grp_partition_destroy": [vp],
         "grp_step_workspace_bytes": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), C.POINTER(sz)],
         "grp_step_activation": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), vp, sz, i32, C.POINTER(vp), C.POINTER(i64)],
+        "grp_step_block": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), vp, sz, i32, C.POINTER(BlockView)],
         "grp_train_step": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), vp, vp, vp, vp, vp, sz, vp, vp, vp],
         "grp_aggregate": [vp, i64, vp, i32, i64, i32, vp, vp, vp],
         "grp_optimizer_step": [C.POINTER(OptimizerDesc), i64, i64, vp, vp, vp, vp, vp],
-        "grp_spmm": [vp, i32, i32, i32, i32, vp, i64, i32, vp, i64, vp],
+        "grp_spmm_workspace_bytes": [vp, i32, i32, C.POINTER(sz)],
+        "grp_spmm": [vp, i32, i32, i32, i32, vp, i64, i32, vp, i64, vp, sz, vp],
         "grp_gemm_nn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
         "grp_gemm_nt": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
         "grp_gemm_tn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp, sz, vp],
@@ -383,6 +390,30 @@ def grp_step_activation(part: Partition, model: ModelDesc, opts: StepOpts, works
     return ptr.value, int(ld.value)
 
 
+def grp_step_block(part: Partition, model: ModelDesc, opts: StepOpts, workspace, layer: int) -> BlockView:
+    v = BlockView()
+    _check(load().grp_step_block(part.handle, C.byref(model), C.byref(opts), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), layer, C.byref(v)))
+    return v
+
+
+def read_block(part: Partition, model: ModelDesc, opts: StepOpts, workspace, layer: int) -> dict:
+    """Host copies of a sampled block's arrays (n_dst, n_src, nnz, rowptr, col, dst_nodes, src_nodes or None)."""
+    v = grp_step_block(part, model, opts, workspace, layer)
+    out = dict(n_dst=int(v.n_dst), n_src=int(v.n_src), nnz=int(v.nnz))
+    for name, dt, count in (("rowptr", np.int64, out["n_dst"] + 1), ("col", np.int32, out["nnz"]),
+                            ("dst_nodes", np.int32, out["n_dst"]), ("src_nodes", np.int32, out["n_src"])):
+        ptr = getattr(v, name)
+        if not ptr:
+            out[name] = None
+            continue
+        a = np.empty(count, dtype=dt)
+        if count:
+            _hip_memcpy_d2h(a, ptr)
+        out[name] = a
+    return out
+
+
 def read_activation(part: Partition, model: ModelDesc, opts: StepOpts, workspace, layer: int, rows, cols):
     """Host values of the stored activation at the (row, col) pairs given as equal-length int arrays."""
     ptr, ld = grp_step_activation(part, model, opts, workspace, layer)
@@ -417,10 +448,25 @@ def grp_optimizer_step(opt: OptimizerDesc, P: int, step: int, theta, update, m=N
     _check(load().grp_optimizer_step(C.byref(opt), P, step, _ptr(theta), _ptr(update), _ptr(m), _ptr(v), _stream(stream)))
 
 
+def grp_spmm_workspace_bytes(part: Partition, transposed: bool, F: int) -> int:
+    b = C.c_size_t()
+    _check(load().grp_spmm_workspace_bytes(part.handle, int(transposed), F, C.byref(b)))
+    return int(b.value)
+
+
 def grp_spmm(part: Partition, transposed: bool, scale: int, self_term: bool, F: int, X, ldx: int, x_dtype: int, Y,
-             ldy: int, stream=None):
+             ldy: int, workspace=None, stream=None):
+    """``workspace``: uint8 device tensor of at least grp_spmm_workspace_bytes; None: one is allocated here (torch) and
+    kept with the Partition object for later calls."""
+    if workspace is None:
+        need = grp_spmm_workspace_bytes(part, transposed, F)
+        workspace = getattr(part, "_spmm_ws", None)
+        if need and (workspace is None or workspace.numel() < need):
+            workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+            part._spmm_ws = workspace
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().grp_spmm(part.handle, int(transposed), scale, int(self_term), F, _ptr(X), ldx, x_dtype, _ptr(Y), ldy,
-                           _stream(stream)))
+                           _ptr(workspace), wb, _stream(stream)))
 
 
 def grp_gemm_nn(M, N, K, A, lda, a_dtype, B, ldb, Cm, ldc, stream=None):
@@ -468,6 +514,6 @@ def read_stats(stats: torch.Tensor) -> np.ndarray:
 def exported_symbols():
     return ["grp_last_error", "grp_partition", "grp_node_owners", "grp_epoch_seeds", "grp_gather_rows", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_from_csr", "grp_partition_view",
             "grp_partition_destroy", "grp_chunks_build", "grp_chunks_build_assigned", "grp_chunks_destroy", "grp_partition_from_chunks",
-            "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_step_activation", "grp_train_step",
-            "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
+            "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_step_activation", "grp_step_block", "grp_train_step",
+            "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_spmm_workspace_bytes", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
             "grp_profile_enable", "grp_profile_report"]

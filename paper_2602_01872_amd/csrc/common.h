@@ -79,8 +79,6 @@ struct LongRows {
 
 struct grp_partition_s {
     grp::LongRows csr_long, csc_long;
-    float* spmm_scratch = nullptr;   // partial sums of the standalone grp_spmm call
-    size_t spmm_scratch_bytes = 0;
     int64_t n = 0, nnz = 0;
     int64_t* l2g = nullptr;
     int64_t* rowptr = nullptr;
@@ -379,6 +377,8 @@ size_t sampler_workspace_bytes(int64_t n, const SamplerBounds& b, int k);
 grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* opts, int k, void* ws, size_t ws_bytes,
                          Block* blocks, LongRows* long_bwd_store, const int64_t** nnz_parts_dev,
                          const int32_t** seed_counts_dev, hipStream_t st);
+grp_status sampler_block_view(const grp_partition_t* part, const grp_step_opts* o, int k, void* ws, size_t ws_bytes, int layer,
+                              grp_block_view_t* out);
 }  // namespace grp
 
 namespace grp {

@@ -557,7 +557,7 @@ static void free_partition(grp_partition_t* h) {
     void* ptrs[] = {h->l2g, h->rowptr, h->col, h->colptr, h->row, h->d_local_in, h->d_local_out, h->d_global_in,
                     h->csr_long.long_row, h->csr_long.long_first, h->csr_long.chunk_begin, h->csr_long.chunk_end,
                     h->csc_long.long_row, h->csc_long.long_first, h->csc_long.chunk_begin, h->csc_long.chunk_end,
-                    h->spmm_scratch, h->base_mask, h->csr_w, h->csc_w, h->w_local_in, h->w_global_in};
+                    h->base_mask, h->csr_w, h->csc_w, h->w_local_in, h->w_global_in};
     const char* lo = (const char*)h->slab;
     for (void* q : ptrs)
         if (q && !(lo && (const char*)q >= lo && (const char*)q < lo + h->slab_bytes)) (void)hipFree(q);

@@ -49,6 +49,18 @@ __global__ __launch_bounds__(256) void sample_count_kernel(const int64_t* __rest
     }
 }
 
+// Seeds outside [0, n) are counted (pinned host memory, read by the host at its next synchronisation) and
+// replaced by node 0 in the copy the sampler works on, so that no kernel reads outside the partition.
+__global__ __launch_bounds__(256) void check_seeds_kernel(const int32_t* __restrict__ seeds, int64_t n_seeds, int64_t n,
+                                                          int32_t* __restrict__ safe, int64_t* __restrict__ bad /*pinned*/) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_seeds) return;
+    const int32_t v = seeds[i];
+    const bool ok = v >= 0 && (int64_t)v < n;
+    safe[i] = ok ? v : 0;
+    if (!ok) atomicAdd((unsigned long long*)bad, 1ull);
+}
+
 // One wavefront per destination row.  Lane t computes draw t; the subset is grown in `fanout`
 // wave-uniform steps with lane t keeping the t-th element; each lane then finds the rank of its
 // element (they are distinct) and writes the edge to that output slot.
@@ -123,10 +135,11 @@ __global__ __launch_bounds__(256) void relabel_kernel(const int64_t* __restrict_
                                                       const int32_t* __restrict__ idx_local,
                                                       const int32_t* __restrict__ mark, int32_t* __restrict__ idx_blk,
                                                       uint64_t* __restrict__ keyT, const int32_t* __restrict__ n_new,
-                                                      int64_t* __restrict__ mailbox /*pinned host memory*/) {
+                                                      int64_t* __restrict__ mailbox /*pinned host memory*/,
+                                                      int64_t* __restrict__ sizes /*device copy, for later inspection*/) {
     if (blockIdx.x == 0 && threadIdx.x == 0) {           // the block's sizes, for the host
-        mailbox[0] = ptr[n_dst];
-        mailbox[1] = *n_new;
+        mailbox[0] = sizes[0] = ptr[n_dst];
+        mailbox[1] = sizes[1] = *n_new;
     }
     const int64_t i = (int64_t)blockIdx.x * 4 + threadIdx.x / 64;
     if (i >= n_dst) return;
@@ -176,6 +189,8 @@ struct SamplerLayerBufs {
 
 struct SamplerBufs {
     SamplerLayerBufs L[GRP_MAX_LAYERS];
+    int32_t* seeds;                     // [n_seeds] the caller's seeds, range-checked
+    int64_t* sizes;                     // [2 * GRP_MAX_LAYERS] per layer >= 1: edges of the block, newly reached nodes
     int32_t* mark;                      // [n] block-local index + 1 of the current layer's nodes, else 0
     uint32_t* bits;                     // [n_words + 1] bitmap of newly reached nodes (the last word stays 0)
     int32_t* wpos;                      // [n_words + 1] set bits in the words before each word
@@ -189,6 +204,8 @@ static SamplerBufs carve_sampler(int64_t n, const SamplerBounds& b, int k, void*
     SamplerBufs s;
     Bump bump(ws, ws_bytes);
     int64_t max_nnz = 1, max_dst = 1;
+    s.sizes = bump.take<int64_t>(2 * GRP_MAX_LAYERS);
+    s.seeds = bump.take<int32_t>((size_t)b.dst[k - 1]);
     for (int l = 0; l < k; ++l) {
         SamplerLayerBufs& L = s.L[l];
         L.cnt = bump.take<int64_t>((size_t)b.dst[l] + 1);
@@ -254,10 +271,19 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
         char* const hi = (char*)(s.bits + s.n_words + 1);
         GRP_TRY(launch_fill_zero(lo, (size_t)(hi - lo), st));
     }
-    int64_t* const mailbox = k > 1 ? host_mailbox() : nullptr;
-    if (k > 1 && !mailbox) return fail(GRP_EHIP, "mini-batch: no pinned host memory for the block sizes");
+    int64_t* const mailbox = host_mailbox();
+    if (!mailbox) return fail(GRP_EHIP, "mini-batch: no pinned host memory for the block sizes");
+    if (n == 0) return fail(GRP_ERANGE, "mini-batch: seeds given for a partition without nodes");
+    mailbox[2] = 0;
+    hipLaunchKernelGGL(check_seeds_kernel, dim3(blocks_for(o->n_seeds)), dim3(256), 0, st, o->seeds, (int64_t)o->n_seeds, n,
+                       s.seeds, mailbox + 2);
+    GRP_LAUNCH_CHECK();
+    if (k == 1) {                                        // no later round trip would report the count
+        GRP_HIP(hipStreamSynchronize(st));
+        if (mailbox[2]) return fail(GRP_ERANGE, "mini-batch: %lld seeds outside [0, %lld)", (long long)mailbox[2], (long long)n);
+    }
     const uint64_t h1 = mixM(mixM(o->sampler_seed) ^ o->batch_id);
-    const int32_t* dst_nodes = o->seeds;
+    const int32_t* dst_nodes = s.seeds;
     int64_t n_dst = o->n_seeds;
     for (int l = k - 1; l >= 0; --l) {
         SamplerLayerBufs& L = s.L[l];
@@ -301,9 +327,10 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
         mailbox[0] = mailbox[1] = -1;
         hipLaunchKernelGGL(relabel_kernel, dim3((unsigned)cdiv(n_dst, 4)), dim3(256), 0, st, (const int64_t*)L.ptr, n_dst,
                            (const int32_t*)L.idx_local, (const int32_t*)s.mark, L.idx_blk, L.keys,
-                           (const int32_t*)(s.wpos + s.n_words), mailbox);
+                           (const int32_t*)(s.wpos + s.n_words), mailbox, s.sizes + 2 * l);
         GRP_LAUNCH_CHECK();
         GRP_HIP(hipStreamSynchronize(st));               // the one host round trip of the layer
+        if (mailbox[2]) return fail(GRP_ERANGE, "mini-batch: %lld seeds outside [0, %lld)", (long long)mailbox[2], (long long)n);
         const int64_t host_nnz = mailbox[0];
         const int64_t host_new = mailbox[1];
         const int64_t n_src = n_dst + host_new;
@@ -330,6 +357,41 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
         B.long_bwd = &lr;
         dst_nodes = L.src_nodes;
         n_dst = n_src;
+    }
+    return GRP_OK;
+}
+
+// Where a finished step left block `layer` inside its sampler workspace (same partition size, seeds count,
+// fanouts and depth).  Copies the block sizes from the device: synchronises the device.
+grp_status sampler_block_view(const grp_partition_t* part, const grp_step_opts* o, int k, void* ws, size_t ws_bytes, int layer,
+                              grp_block_view_t* out) {
+    SamplerBounds bd;
+    sampler_bounds(part->n, o->n_seeds, o->fanouts, k, &bd);
+    const SamplerBufs s = carve_sampler(part->n, bd, k, ws, ws_bytes);
+    if (s.total > ws_bytes) return fail(GRP_EWORKSPACE, "grp_step_block: sampler workspace %zu < %zu", ws_bytes, s.total);
+    int64_t sizes[2 * GRP_MAX_LAYERS] = {0};
+    GRP_HIP(hipDeviceSynchronize());
+    if (k > 1) GRP_HIP(hipMemcpy(sizes, s.sizes, sizeof sizes, hipMemcpyDeviceToHost));
+    int64_t n_dst = o->n_seeds;
+    const int32_t* dst_nodes = s.seeds;
+    for (int l = k - 1; l > layer; --l) {                // walk down from the seed side
+        n_dst += sizes[2 * l + 1];
+        dst_nodes = s.L[l].src_nodes;
+    }
+    const SamplerLayerBufs& L = s.L[layer];
+    out->n_dst = n_dst;
+    out->rowptr = L.ptr;
+    out->dst_nodes = dst_nodes;
+    if (layer == 0) {
+        GRP_HIP(hipMemcpy(&out->nnz, L.ptr + n_dst, sizeof(int64_t), hipMemcpyDeviceToHost));
+        out->n_src = part->n;
+        out->col = L.idx_local;
+        out->src_nodes = nullptr;
+    } else {
+        out->nnz = sizes[2 * layer];
+        out->n_src = n_dst + sizes[2 * layer + 1];
+        out->col = L.idx_blk;
+        out->src_nodes = L.src_nodes;
     }
     return GRP_OK;
 }

@@ -380,14 +380,16 @@ grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
 
 }  // namespace grp
 
-extern "C" grp_status grp_spmm(const grp_partition_t* part, int32_t transposed, int32_t scale,
-                               int32_t self_term, int32_t F, const void* X, int64_t ldx, int32_t x_dtype,
-                               float* Y, int64_t ldy, void* stream) {
-    if (!part || !X || !Y) return grp::fail(GRP_EINVAL, "grp_spmm: null argument");
-    if (F <= 0 || F > 1024 || ldx < F || ldy < F) return grp::fail(GRP_EINVAL, "grp_spmm: bad F / pitch");
-    if (scale < GRP_SCALE_NONE || scale > GRP_SCALE_RSQRT) return grp::fail(GRP_EINVAL, "grp_spmm: bad scale");
-    if (x_dtype != GRP_DTYPE_FP32 && x_dtype != GRP_DTYPE_BF16) return grp::fail(GRP_EINVAL, "grp_spmm: bad dtype");
-    grp::SpmmArgs a;
+namespace grp {
+
+static grp_status spmm_args_from_call(const grp_partition_t* part, int32_t transposed, int32_t scale, int32_t self_term, int32_t F,
+                                      const void* X, int64_t ldx, int32_t x_dtype, float* Y, int64_t ldy, const char* who,
+                                      SpmmArgs* out) {
+    if (!part || !X || !Y) return fail(GRP_EINVAL, "%s: null argument", who);
+    if (F <= 0 || F > 1024 || ldx < F || ldy < F) return fail(GRP_EINVAL, "%s: bad F / pitch", who);
+    if (scale < GRP_SCALE_NONE || scale > GRP_SCALE_RSQRT) return fail(GRP_EINVAL, "%s: bad scale", who);
+    if (x_dtype != GRP_DTYPE_FP32 && x_dtype != GRP_DTYPE_BF16) return fail(GRP_EINVAL, "%s: bad dtype", who);
+    SpmmArgs a;
     a.ptr = transposed ? part->colptr : part->rowptr;
     a.idx = transposed ? part->row : part->col;
     a.long_rows = transposed ? &part->csc_long : &part->csr_long;
@@ -401,19 +403,28 @@ extern "C" grp_status grp_spmm(const grp_partition_t* part, int32_t transposed, 
     a.self_term = self_term ? 1 : 0;
     a.Y = Y;
     a.ldy = ldy;
-    // the standalone call keeps its partial-sum scratch in the handle (grown on demand)
+    *out = a;
+    return GRP_OK;
+}
+
+}  // namespace grp
+
+extern "C" grp_status grp_spmm_workspace_bytes(const grp_partition_t* part, int32_t transposed, int32_t F, size_t* bytes) {
+    if (!part || !bytes) return grp::fail(GRP_EINVAL, "grp_spmm_workspace_bytes: null argument");
+    if (F <= 0 || F > 1024) return grp::fail(GRP_EINVAL, "grp_spmm_workspace_bytes: bad F");
+    *bytes = grp::spmm_partials_bytes(transposed ? &part->csc_long : &part->csr_long, F);
+    return GRP_OK;
+}
+
+extern "C" grp_status grp_spmm(const grp_partition_t* part, int32_t transposed, int32_t scale,
+                               int32_t self_term, int32_t F, const void* X, int64_t ldx, int32_t x_dtype,
+                               float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    grp::SpmmArgs a;
+    GRP_TRY(grp::spmm_args_from_call(part, transposed, scale, self_term, F, X, ldx, x_dtype, Y, ldy, "grp_spmm", &a));
     const size_t need = grp::spmm_partials_bytes(a.long_rows, F);
-    if (need > part->spmm_scratch_bytes) {
-        grp_partition_t* mut = const_cast<grp_partition_t*>(part);
-        if (mut->spmm_scratch) (void)hipFree(mut->spmm_scratch);
-        mut->spmm_scratch = nullptr;
-        mut->spmm_scratch_bytes = 0;
-        if (hipMalloc((void**)&mut->spmm_scratch, need) != hipSuccess) {
-            (void)hipGetLastError();
-            return grp::fail(GRP_ENOMEM, "grp_spmm: scratch allocation of %zu bytes failed", need);
-        }
-        mut->spmm_scratch_bytes = need;
-    }
-    a.partials = part->spmm_scratch;
+    if (need > 0 && (!workspace || workspace_bytes < need))
+        return grp::fail(GRP_EWORKSPACE, "grp_spmm: workspace of %zu bytes, %zu needed", workspace_bytes, need);
+    if (need > 0 && ((uintptr_t)workspace % 16) != 0) return grp::fail(GRP_EINVAL, "grp_spmm: workspace must be 16-byte aligned");
+    a.partials = need ? (float*)workspace : nullptr;
     return grp::launch_spmm(a, (hipStream_t)stream);
 }

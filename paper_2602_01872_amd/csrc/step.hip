@@ -489,6 +489,20 @@ extern "C" grp_status grp_step_activation(const grp_partition_t* part, const grp
     return GRP_OK;
 }
 
+extern "C" grp_status grp_step_block(const grp_partition_t* part, const grp_model_desc* model, const grp_step_opts* opts,
+                                     void* workspace, size_t workspace_bytes, int32_t layer, grp_block_view_t* view) {
+    using namespace grp;
+    if (!view) return fail(GRP_EINVAL, "grp_step_block: null output");
+    memset(view, 0, sizeof *view);
+    GRP_TRY(check_step_args(part, model, opts));
+    if (opts->full_graph || model->arch != GRP_ARCH_SAGE_MEAN) return fail(GRP_EINVAL, "grp_step_block: not a mini-batch step");
+    if (layer < 0 || layer >= model->n_layers) return fail(GRP_EINVAL, "grp_step_block: layer %d", layer);
+    if (!workspace || (uintptr_t)workspace % 256 != 0) return fail(GRP_EINVAL, "grp_step_block: bad workspace");
+    const StepPlan p = make_plan(part, model, opts, workspace, workspace_bytes);
+    if (workspace_bytes < p.total) return fail(GRP_EWORKSPACE, "grp_step_block: workspace too small");
+    return sampler_block_view(part, opts, model->n_layers, p.sampler_ws, p.sampler_bytes, layer, view);
+}
+
 extern "C" grp_status grp_train_step(const grp_partition_t* part, const grp_model_desc* model, const grp_step_opts* opts,
                                      const void* features, const int32_t* labels, const uint8_t* train_mask,
                                      const float* weights, void* workspace, size_t workspace_bytes, void* stream,

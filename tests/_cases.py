@@ -103,3 +103,61 @@ def make_inputs(n, dims, arch, seed, bf16=False, n_classes=None):
     y = synth.labels(n, dims[-1], seed)
     theta = synth.model_weights(arch if arch in ("sage", "gat") else "gcn", dims, seed)
     return x, y, theta
+
+
+def assert_blocks_equal(g, part, model, opts, ws, oracle_part, seeds, fanouts, sampler_seed, batch_id):
+    """The sampled blocks the step left in its workspace against the oracle's, bit for bit: per layer the
+    row pointer, the source index of every edge, the destination nodes and the source list."""
+    from oracle import sampling as osampling
+    blocks, input_nodes = osampling.sample_blocks(oracle_part, np.asarray(seeds, dtype=np.int64), fanouts, sampler_seed, batch_id)
+    k = len(fanouts)
+    dst_nodes = np.asarray(seeds, dtype=np.int64)
+    for l in range(k - 1, -1, -1):
+        got, want = g.read_block(part, model, opts, ws, l), blocks[l]
+        assert got["n_dst"] == want["n_dst"] and got["nnz"] == want["edst"].size, (l, got["n_dst"], got["nnz"])
+        ptr = np.zeros(want["n_dst"] + 1, dtype=np.int64)
+        np.cumsum(np.bincount(want["edst"], minlength=want["n_dst"]), out=ptr[1:])
+        assert np.array_equal(got["rowptr"], ptr), f"layer {l}: row pointer"
+        assert np.array_equal(got["dst_nodes"].astype(np.int64), dst_nodes), f"layer {l}: destination nodes"
+        if l == 0:          # the input layer keeps partition-local ids and has no source list of its own
+            assert got["src_nodes"] is None and got["n_src"] == oracle_part["n"]
+            assert np.array_equal(got["col"].astype(np.int64), want["src_nodes"][want["esrc"]]), "layer 0: sources"
+        else:
+            assert got["n_src"] == want["n_src"]
+            assert np.array_equal(got["col"].astype(np.int64), want["esrc"]), f"layer {l}: sources"
+            assert np.array_equal(got["src_nodes"].astype(np.int64), want["src_nodes"]), f"layer {l}: source list"
+        dst_nodes = want["src_nodes"]
+    return blocks
+
+
+def library_relu_decisions(g, part, model, opts, ws, dims, near, zs, factors=None, n_sample=100_000, seed=11):
+    """The ReLU-derivative decisions the library took at the oracle's near-kink elements, read from its stored
+    activations - after proving that they are legitimate: at every near-kink element the library's stored value
+    must lie within KINK_GUARD * rms of the oracle's max(z, 0) (so either decision is within rounding), and on a
+    seeded sample of other elements the sign of the stored value must be the oracle's.  ``zs``: the oracle's
+    pre-activations per layer; ``factors``: per hidden layer the dropout factor array (stored value =
+    max(z, 0) * factor), or None.  Elements dropped by dropout are stored as 0 and need no decision."""
+    decisions = {}
+    for l in range(len(dims) - 2):
+        z = zs[l]
+        rms = float(np.sqrt(np.mean(z ** 2)))
+        fac = factors[l] if factors else None
+        el = [e for e in near if e[0] == l]
+        if el:
+            rr, cc = np.array([e[1] for e in el]), np.array([e[2] for e in el])
+            vals = g.read_activation(part, model, opts, ws, l, rr, cc).astype(np.float64)
+            f = fac[rr, cc] if fac is not None else np.ones(len(el))
+            want = np.maximum(z[rr, cc], 0.0) * f
+            assert np.all(np.abs(vals - want) <= KINK_GUARD * rms * np.maximum(f, 1.0)), \
+                f"layer {l}: a stored activation at a near-kink element is not within rounding of the oracle's"
+            decisions.update({e: bool(v > 0) for e, v, kept in zip(el, vals, f > 0) if kept})
+        idx = torch.arange(n_sample, dtype=torch.int64)
+        rr = ((synth.stream_bits(seed, 50 + l, idx) >> 1) % z.shape[0]).numpy()
+        cc = ((synth.stream_bits(seed, 60 + l, idx) >> 1) % z.shape[1]).numpy()
+        vals = g.read_activation(part, model, opts, ws, l, rr, cc)
+        zz = z[rr, cc]
+        far = np.abs(zz) > KINK_GUARD * rms
+        if fac is not None:
+            far &= fac[rr, cc] > 0
+        assert np.array_equal(vals[far] > 0, zz[far] > 0), f"layer {l}: a ReLU decision away from the kink differs"
+    return decisions

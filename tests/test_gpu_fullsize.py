@@ -15,7 +15,7 @@ import synth
 from oracle import dropout as odropout
 from oracle import graph as ograph
 from oracle import step as ostep
-from tests._cases import KINK_GUARD, TOL_FP32, grad_errors
+from tests._cases import KINK_GUARD, TOL_FP32, assert_blocks_equal, grad_errors, library_relu_decisions
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -46,8 +46,9 @@ def test_workload2_partition0_full_size():
     stats = g.new_stats(1)
     g.grp_train_step(part, model, opts, x, y, None, theta, ws, grad, stats)
     torch.cuda.synchronize()
+    zs = []
     og, ost = ostep.train_step(op, "sage", dims, theta.cpu().double().numpy(), x.cpu().double().numpy(),
-                               y.cpu().numpy(), near_kink=KINK_GUARD)
+                               y.cpu().numpy(), near_kink=KINK_GUARD, keep_z=zs)
     st = g.read_stats(stats)[0]
     assert int(st["S"]) == ost["S"] and int(st["nnz_used"]) == ost["nnz_used"] and float(st["R"]) == ost["R"]
     assert abs(float(st["sum_ratio"]) - ost["sum_ratio"]) <= 1e-9 * ost["sum_ratio"]
@@ -62,12 +63,8 @@ def test_workload2_partition0_full_size():
     # ReLU-derivative decision; the oracle is rerun with the decisions the library took there (read
     # from its stored activations) and with its own decisions everywhere else.
     assert len(near) < 5000
-    decisions = {}
-    for l in range(len(dims) - 2):
-        el = [e for e in near if e[0] == l]
-        if el:
-            vals = g.read_activation(part, model, opts, ws, l, [e[1] for e in el], [e[2] for e in el])
-            decisions.update({e: bool(v > 0) for e, v in zip(el, vals)})
+    decisions = library_relu_decisions(g, part, model, opts, ws, dims, near, zs)
+    del zs
     og2, _ = ostep.train_step(op, "sage", dims, theta.cpu().double().numpy(), x.cpu().double().numpy(),
                               y.cpu().numpy(), relu_set=decisions)
     errs2 = grad_errors(grad.cpu().numpy(), og2, "sage", dims)
@@ -87,8 +84,8 @@ def test_workload2_partition0_full_size_gat():
     seed = 2602018722
     s, d = synth.rmat_graph(22, E, seed=seed, n_nodes=N, device=DEV)
     part = g.grp_partition(s, d, N, K, 1, 0)
-    op = {k: part.array(k) for k in ("l2g", "rowptr", "col", "colptr", "row", "d_local_in", "d_local_out", "d_global_in")}
-    op.update(n=part.n, nnz=part.nnz)          # bit-exactness of these arrays is the previous test's subject
+    op = ograph.partition(s.cpu().numpy(), d.cpu().numpy(), N, K, 1, 0)      # the oracle's own arrays
+    assert part.n == op["n"] and part.nnz == op["nnz"]
     del s, d
     l2g = torch.from_numpy(op["l2g"]).to(DEV)
     x = synth.normal_matrix(N, dims[0], seed, device=DEV)[l2g].contiguous()
@@ -104,7 +101,8 @@ def test_workload2_partition0_full_size_gat():
     torch.cuda.synchronize()
     th, xh, yh = theta.cpu().double().numpy(), x.cpu().double().numpy(), y.cpu().numpy()
     print("[case] oracle pass 1 (lists the near-kink elements)", flush=True)
-    og, ost = ostep.train_step(op, "gat", dims, th, xh, yh, near_kink=KINK_GUARD)
+    zs = []
+    og, ost = ostep.train_step(op, "gat", dims, th, xh, yh, near_kink=KINK_GUARD, keep_z=zs)
     st = g.read_stats(stats)[0]
     assert int(st["S"]) == ost["S"] and float(st["R"]) == ost["R"]
     assert abs(float(st["loss"]) - ost["loss"]) <= TOL_FP32 * abs(ost["loss"])
@@ -113,12 +111,8 @@ def test_workload2_partition0_full_size_gat():
     print("[case] per-tensor errors before the kink decisions are matched", {k: f"{v:.2e}" for k, v in errs.items()},
           "near-kink", len(near), flush=True)
     assert len(near) < 5000
-    decisions = {}
-    for l in range(len(dims) - 2):
-        el = [e for e in near if e[0] == l]
-        if el:
-            vals = g.read_activation(part, model, opts, ws, l, [e[1] for e in el], [e[2] for e in el])
-            decisions.update({e: bool(v > 0) for e, v in zip(el, vals)})
+    decisions = library_relu_decisions(g, part, model, opts, ws, dims, near, zs)
+    del zs
     print("[case] oracle pass 2 (the library's decisions at those elements)", flush=True)
     og2, _ = ostep.train_step(op, "gat", dims, th, xh, yh, relu_set=decisions)
     errs2 = grad_errors(grad.cpu().numpy(), og2, "gat", dims)
@@ -162,7 +156,8 @@ def test_workload2_partition0_full_size_weighted_with_dropout():
     th, xh, yh = theta.cpu().double().numpy(), x.cpu().double().numpy(), y.cpu().numpy()
     dr = dict(rate=0.5, seed=99, batch_id=5)
     print("[case] oracle pass 1 (lists the near-kink elements)", flush=True)
-    og, ost = ostep.train_step(op, "sage", dims, th, xh, yh, estimator=1, near_kink=KINK_GUARD, dropout=dr)
+    zs = []
+    og, ost = ostep.train_step(op, "sage", dims, th, xh, yh, estimator=1, near_kink=KINK_GUARD, dropout=dr, keep_z=zs)
     st = g.read_stats(stats)[0]
     assert int(st["S"]) == ost["S"]
     assert abs(float(st["R"]) - ost["R"]) <= 1e-9 * ost["R"]
@@ -170,13 +165,9 @@ def test_workload2_partition0_full_size_weighted_with_dropout():
     assert abs(float(st["loss"]) - ost["loss"]) <= TOL_FP32 * abs(ost["loss"])
     # a dropped element is stored as 0 by the library and needs no decision; the others are matched
     near = ost["near_kink"]
-    decisions = {}
-    for l in range(len(dims) - 2):
-        el = [e for e in near if e[0] == l]
-        if el:
-            vals = g.read_activation(part, model, opts, ws, l, [e[1] for e in el], [e[2] for e in el])
-            keep = odropout.keep_mask(99, 5, l, op["l2g"][[e[1] for e in el]], dims[l + 1], 0.5)[np.arange(len(el)), [e[2] for e in el]]
-            decisions.update({e: bool(v > 0) for e, v, kp in zip(el, vals, keep) if kp})
+    factors = odropout.layer_factors(99, 5, op["l2g"], dims, 0.5)
+    decisions = library_relu_decisions(g, part, model, opts, ws, dims, near, zs, factors=factors)
+    del zs, factors
     print(f"[case] near-kink {len(near)}, kept by dropout {len(decisions)}; oracle pass 2", flush=True)
     og2, _ = ostep.train_step(op, "sage", dims, th, xh, yh, estimator=1, relu_set=decisions, dropout=dr)
     errs2 = grad_errors(grad.cpu().numpy(), og2, "sage", dims)
@@ -189,8 +180,9 @@ def test_workload2_partition0_full_size_weighted_with_dropout():
 def test_workload3_minibatch_full_size():
     """Workload 3 at full size (`bench.py --workload c3-step`): a 7 M-node / 100 M-edge store with hub
     rows of 10^5 in-edges, isolated 3-hop sampling with fanouts (15, 10, 5) from 1024 seeds, bf16
-    features.  The store's CSR comes from the library (checked here against the edge list by its
-    degrees and a sample of rows); the oracle samples and trains on it."""
+    features.  The library builds its store from the edge list; the oracle samples and trains on the
+    same edges generated independently as sorted rows (the two stores must agree bit for bit), and the
+    sampled blocks are compared bit for bit before the gradients."""
     import paper_2602_01872_amd as g
     g.load()
     print("[case] workload 3 full size, mini-batch", flush=True)
@@ -200,17 +192,12 @@ def test_workload3_minibatch_full_size():
     d_global = synth.stand_in_global_degree(d_local, torch.arange(n, device=DEV), seed, 15)
     part = g.grp_partition_from_local_coo(src, dst, n, d_global_in=d_global)
     assert part.n == n and part.nnz == E
-    rowptr = torch.from_numpy(part.array("rowptr")).to(DEV)
-    col = torch.from_numpy(part.array("col")).to(DEV)
+    del src, dst
+    # the oracle's store is built without the library: the same edges generated as sorted rows
+    rowptr, col = synth.rmat_local_csr(scale, E, seed=seed, n_nodes=n, device=DEV, chunk=1 << 26, slice_edges=1 << 26)
     assert torch.equal(rowptr[1:] - rowptr[:-1], d_local) and int(rowptr[-1]) == E
     assert int(d_local.max()) > 50_000                        # hub rows: the sampler's whole-workgroup scan
-    pick = torch.unique((synth.stream_bits(seed, 21, torch.arange(2000, dtype=torch.int64)) >> 1) % n).to(DEV)
-    pick = torch.cat([pick, d_local.argmax().reshape(1)])
-    for v in pick.tolist()[-40:]:                             # rows against the edge list, as sorted multisets
-        want = torch.sort(src[dst == v]).values
-        got = col[int(rowptr[v]):int(rowptr[v + 1])].to(torch.int64)
-        assert torch.equal(got, want), v
-    del src, dst
+    assert torch.equal(part.device_array("rowptr"), rowptr) and torch.equal(part.device_array("col"), col)
     op = dict(n=n, nnz=E, l2g=np.arange(n, dtype=np.int64), rowptr=rowptr.cpu().numpy(), col=col.cpu().numpy(),
               d_local_in=d_local.cpu().numpy().astype(np.int32), d_global_in=d_global.cpu().numpy())
     del rowptr, col
@@ -232,7 +219,9 @@ def test_workload3_minibatch_full_size():
     xh = x.cpu().to(torch.float32).numpy()                    # the oracle widens the rows it gathers
     mb = dict(seeds=seeds.cpu().numpy(), fanouts=fanouts, sampler_seed=7, batch_id=0)
     print("[case] oracle pass 1 (sampling, lists the near-kink elements)", flush=True)
-    og, ost = ostep.train_step(op, "sage", dims, th, xh, yh, estimator=2, minibatch=mb, near_kink=KINK_GUARD)
+    assert_blocks_equal(g, part, model, opts, ws, op, mb["seeds"], fanouts, 7, 0)
+    zs = []
+    og, ost = ostep.train_step(op, "sage", dims, th, xh, yh, estimator=2, minibatch=mb, near_kink=KINK_GUARD, keep_z=zs)
     st = g.read_stats(stats)[0]
     assert int(st["S"]) == ost["S"] == 1024
     assert int(st["nnz_used"]) == ost["nnz_used"]             # the sampled edge multiset has the same size
@@ -240,12 +229,8 @@ def test_workload3_minibatch_full_size():
     assert abs(float(st["sum_ratio"]) - ost["sum_ratio"]) <= 1e-9 * ost["sum_ratio"]
     assert abs(float(st["loss"]) - ost["loss"]) <= TOL_FP32 * abs(ost["loss"])
     near = ost["near_kink"]
-    decisions = {}
-    for l in range(len(dims) - 2):
-        el = [e for e in near if e[0] == l]
-        if el:
-            vals = g.read_activation(part, model, opts, ws, l, [e[1] for e in el], [e[2] for e in el])
-            decisions.update({e: bool(v > 0) for e, v in zip(el, vals)})
+    decisions = library_relu_decisions(g, part, model, opts, ws, dims, near, zs, n_sample=20_000)
+    del zs
     print(f"[case] edges used {ost['nnz_used']}, near-kink {len(near)}; oracle pass 2", flush=True)
     og2, _ = ostep.train_step(op, "sage", dims, th, xh, yh, estimator=2, minibatch=mb, relu_set=decisions)
     errs2 = grad_errors(grad.cpu().numpy(), og2, "sage", dims)

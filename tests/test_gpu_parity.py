@@ -11,7 +11,7 @@ from oracle import gnn as ognn
 from oracle import graph as ograph
 from oracle import sampling as osampling
 from oracle import step as ostep
-from tests._cases import TOL_BF16, TOL_FP32, assert_grads_close, assert_step_grads_close, make_inputs, rel_err, split_flat
+from tests._cases import TOL_BF16, TOL_FP32, assert_blocks_equal, assert_grads_close, assert_step_grads_close, make_inputs, rel_err, split_flat
 
 pytestmark = pytest.mark.gpu
 
@@ -138,7 +138,8 @@ def test_spmm_matches_oracle(g, F, ld, bf16):
     part = g.grp_partition(s, d, N, K, 5, 1)
     op = ograph.partition(s.cpu().numpy(), d.cpu().numpy(), N, K, 5, 1)
     n = part.n
-    assert int(op["d_local_in"].max()) > 300          # a hub row spanning several index tiles
+    assert int(op["d_local_in"].max()) > 2 * 512      # a hub row that is split into chunks (rows over 512 edges are)
+    assert int(op["d_local_out"].max()) > 2 * 512
     assert (op["d_local_in"] == 0).any()
     xf = synth.normal_matrix(n, ld, 3)
     xf[:, F:] = 0
@@ -456,6 +457,7 @@ def test_minibatch_train_step_matches_oracle(g, dims, fanouts, bf16, n_seeds):
         g.grp_train_step(part, model, opts, x.to(DEV), y.to(DEV), None, theta.to(DEV), ws, grad, stats)
         torch.cuda.synchronize()
         mb = dict(seeds=seeds, fanouts=fanouts, sampler_seed=7, batch_id=batch)
+        assert_blocks_equal(g, part, model, opts, ws, op, seeds, fanouts, 7, batch)      # the sampled structure, bit for bit
 
         def oracle_fn(relu_flip=None, near_kink=None, est=est, mb=mb):
             return ostep.train_step(op, "sage", dims, theta.double().numpy(), x.double().numpy(), y.numpy(),
@@ -467,6 +469,34 @@ def test_minibatch_train_step_matches_oracle(g, dims, fanouts, bf16, n_seeds):
         assert abs(float(st["R"]) - ost["R"]) <= 1e-9 * max(1.0, ost["R"])
         assert abs(float(st["sum_ratio"]) - ost["sum_ratio"]) <= 1e-9 * max(1.0, ost["sum_ratio"])
         assert abs(float(st["loss"]) - ost["loss"]) <= TOL_FP32 * abs(ost["loss"])
+
+
+def test_minibatch_rejects_seeds_outside_the_partition(g):
+    _note("minibatch bad seeds")
+    n, dims = 500, [8, 8, 3]
+    s, d = synth.uniform_graph(n, 4000, seed=3, device=DEV)
+    part = g.grp_partition_from_local_coo(s, d, n)
+    x, y, theta = make_inputs(n, dims, "sage", 2)
+    model = g.model_desc(g.ARCH_SAGE_MEAN, dims)
+    P = g.grp_param_count(model)
+    for fanouts in ((3, 3), (3,)):
+        m = g.model_desc(g.ARCH_SAGE_MEAN, dims[:len(fanouts)] + [dims[-1]])
+        th = synth.model_weights("sage", dims[:len(fanouts)] + [dims[-1]], 2).to(DEV)
+        for bad in (n, -1, 2**31 - 1):
+            seeds = torch.tensor([1, 2, bad, 7], dtype=torch.int32, device=DEV)
+            opts = g.step_opts(full_graph=False, seeds=seeds, fanouts=fanouts, sampler_seed=1)
+            ws = torch.empty(g.grp_step_workspace_bytes(part, m, opts), dtype=torch.uint8, device=DEV)
+            grad = torch.zeros(g.grp_param_count(m), device=DEV)
+            with pytest.raises(g.GrappaError) as ei:
+                g.grp_train_step(part, m, opts, x.to(DEV), y.to(DEV), None, th, ws, grad, g.new_stats(1))
+            assert ei.value.status == g.ERANGE, (fanouts, bad, ei.value)
+            torch.cuda.synchronize()
+    # and the same call with valid seeds still works afterwards
+    seeds = torch.tensor([1, 2, 3, 7], dtype=torch.int32, device=DEV)
+    opts = g.step_opts(full_graph=False, seeds=seeds, fanouts=(3, 3), sampler_seed=1)
+    ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+    g.grp_train_step(part, model, opts, x.to(DEV), y.to(DEV), None, theta.to(DEV), ws, torch.zeros(P, device=DEV), g.new_stats(1))
+    torch.cuda.synchronize()
 
 
 def test_minibatch_block_with_a_source_shared_by_thousands_of_seeds(g):
