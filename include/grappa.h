@@ -443,6 +443,18 @@ grp_status grp_spmm(const grp_partition_t* part, int32_t transposed, int32_t sca
                     int32_t self_term, int32_t F, const void* X, int64_t ldx, int32_t x_dtype,
                     float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
+/* grp_spmm for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the partial sums of the split rows live
+ * in a scratch array built into the library, 32 MiB per GPU, reserved when the library is loaded and kept
+ * until the process ends.  Same arguments, kernels and results (bit for bit) as grp_spmm.  A partition
+ * whose split rows need more than 32 MiB at this F (more than 32 MiB / (4 * round_up(F, 4)) chunks of 512
+ * edges) is refused with GRP_EWORKSPACE; nothing is allocated or freed.  All calls on one GPU share that
+ * GPU's array: calls that may overlap in time on one GPU (different streams or threads) race on it and
+ * must be serialised by the caller; calls on one stream are safe.                                      */
+grp_status grp_spmm_static(const grp_partition_t* part, int32_t transposed, int32_t scale,
+                           int32_t self_term, int32_t F, const void* X, int64_t ldx, int32_t x_dtype,
+                           float* Y, int64_t ldy, void* stream);
+
 /* Dense transforms on the matrix cores (fp32 MFMA, fp32 accumulate):
  *   grp_gemm_nn:  C[M x N] = A[M x K] B[K x N]            (X W, dY W^T with B given transposed)
  *   grp_gemm_tn:  C[K x N] = A[M x K]^T B[M x N]          (X^T dY), reduction over M in a

@@ -99,6 +99,7 @@ def load() -> C.CDLL:
         "grp_optimizer_step": [C.POINTER(OptimizerDesc), i64, i64, vp, vp, vp, vp, vp],
         "grp_spmm_workspace_bytes": [vp, i32, i32, C.POINTER(sz)],
         "grp_spmm": [vp, i32, i32, i32, i32, vp, i64, i32, vp, i64, vp, sz, vp],
+        "grp_spmm_static": [vp, i32, i32, i32, i32, vp, i64, i32, vp, i64, vp],
         "grp_gemm_nn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
         "grp_gemm_nt": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
         "grp_gemm_tn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp, sz, vp],
@@ -469,6 +470,12 @@ def grp_spmm(part: Partition, transposed: bool, scale: int, self_term: bool, F: 
                            _ptr(workspace), wb, _stream(stream)))
 
 
+def grp_spmm_static(part: Partition, transposed: bool, scale: int, self_term: bool, F: int, X, ldx: int, x_dtype: int, Y,
+                    ldy: int, stream=None):
+    _check(load().grp_spmm_static(part.handle, int(transposed), scale, int(self_term), F, _ptr(X), ldx, x_dtype, _ptr(Y), ldy,
+                                  _stream(stream)))
+
+
 def grp_gemm_nn(M, N, K, A, lda, a_dtype, B, ldb, Cm, ldc, stream=None):
     _check(load().grp_gemm_nn(M, N, K, _ptr(A), lda, a_dtype, _ptr(B), ldb, _ptr(Cm), ldc, _stream(stream)))
 
@@ -515,5 +522,5 @@ def exported_symbols():
     return ["grp_last_error", "grp_partition", "grp_node_owners", "grp_epoch_seeds", "grp_gather_rows", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_from_csr", "grp_partition_view",
             "grp_partition_destroy", "grp_chunks_build", "grp_chunks_build_assigned", "grp_chunks_destroy", "grp_partition_from_chunks",
             "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_step_activation", "grp_step_block", "grp_train_step",
-            "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_spmm_workspace_bytes", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
+            "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_spmm_workspace_bytes", "grp_spmm_static", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
             "grp_profile_enable", "grp_profile_report"]

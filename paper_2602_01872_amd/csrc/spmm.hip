@@ -21,6 +21,8 @@
 // depends only on the graph, so results do not depend on scheduling.
 #include "common.h"
 
+#include <mutex>
+
 namespace grp {
 
 template <typename T> struct Vec4Load;
@@ -407,6 +409,29 @@ static grp_status spmm_args_from_call(const grp_partition_t* part, int32_t trans
     return GRP_OK;
 }
 
+// The partial sums of split rows for callers that cannot allocate: one array per GPU, reserved when the
+// library is loaded and kept until the process ends.  The array's name is only a host-side stand-in;
+// its device address is looked up once per device and cached.
+constexpr size_t SPMM_STATIC_SCRATCH_BYTES = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char g_spmm_scratch[SPMM_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_spmm_scratch_ptr[MAX_DEVICES] = {nullptr};
+static std::mutex g_spmm_scratch_mu;
+
+static grp_status spmm_static_scratch(void** out) {
+    int dev = 0;
+    GRP_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(GRP_EUNSUPPORTED, "device index %d is outside [0, %d)", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lk(g_spmm_scratch_mu);
+    if (!g_spmm_scratch_ptr[dev]) {
+        void* p = nullptr;
+        GRP_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(g_spmm_scratch)));      // the copy of the array on the current device
+        g_spmm_scratch_ptr[dev] = p;
+    }
+    *out = g_spmm_scratch_ptr[dev];
+    return GRP_OK;
+}
+
 }  // namespace grp
 
 extern "C" grp_status grp_spmm_workspace_bytes(const grp_partition_t* part, int32_t transposed, int32_t F, size_t* bytes) {
@@ -426,5 +451,20 @@ extern "C" grp_status grp_spmm(const grp_partition_t* part, int32_t transposed, 
         return grp::fail(GRP_EWORKSPACE, "grp_spmm: workspace of %zu bytes, %zu needed", workspace_bytes, need);
     if (need > 0 && ((uintptr_t)workspace % 16) != 0) return grp::fail(GRP_EINVAL, "grp_spmm: workspace must be 16-byte aligned");
     a.partials = need ? (float*)workspace : nullptr;
+    return grp::launch_spmm(a, (hipStream_t)stream);
+}
+
+extern "C" grp_status grp_spmm_static(const grp_partition_t* part, int32_t transposed, int32_t scale,
+                                      int32_t self_term, int32_t F, const void* X, int64_t ldx, int32_t x_dtype,
+                                      float* Y, int64_t ldy, void* stream) {
+    grp::SpmmArgs a;
+    GRP_TRY(grp::spmm_args_from_call(part, transposed, scale, self_term, F, X, ldx, x_dtype, Y, ldy, "grp_spmm_static", &a));
+    const size_t need = grp::spmm_partials_bytes(a.long_rows, F);
+    if (need > grp::SPMM_STATIC_SCRATCH_BYTES)
+        return grp::fail(GRP_EWORKSPACE, "grp_spmm_static: the split rows of this partition need %zu bytes of partial sums at F = %d, "
+                         "the built-in scratch holds %zu; use grp_spmm with a workspace", need, F, grp::SPMM_STATIC_SCRATCH_BYTES);
+    void* scratch = nullptr;
+    if (need > 0) GRP_TRY(grp::spmm_static_scratch(&scratch));
+    a.partials = (float*)scratch;
     return grp::launch_spmm(a, (hipStream_t)stream);
 }
