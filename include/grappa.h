@@ -472,6 +472,16 @@ grp_status grp_gemm_tn(int64_t M, int32_t K, int32_t N, const void* A, int64_t l
                        int32_t a_dtype, const float* B, int64_t ldb, float* C, int64_t ldc,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------ tuning */
+
+/* Partitions with at least this many nodes (default 2^17) also get the source-sliced schedule of their long
+ * rows when they are built: rows of more than 512 edges are cut where their sorted sources pass from one of 64
+ * equal ranges of node ids into the next, and the aggregation then processes the pieces range by range, so
+ * that the rows gathered at any one time come from one 64th of the nodes and stay in the L2 cache.  Results
+ * differ from the unsliced schedule only by the order of fp32 additions (both orders are fixed by the graph).
+ * Applies to partitions built afterwards; process-wide.  n >= 1.                                        */
+grp_status grp_set_slice_min_nodes(int64_t n);
+
 /* ------------------------------------------------------------------ profiling */
 
 /* Per-kernel timing with HIP events on the launch stream.  While enabled, every kernel

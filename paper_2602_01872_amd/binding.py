@@ -103,6 +103,7 @@ def load() -> C.CDLL:
         "grp_gemm_nn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
         "grp_gemm_nt": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
         "grp_gemm_tn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp, sz, vp],
+        "grp_set_slice_min_nodes": [i64],
         "grp_profile_enable": [i32],
         "grp_profile_report": [C.c_char_p, sz],
     }
@@ -494,6 +495,10 @@ def grp_gemm_tn(M, K, N, A, lda, a_dtype, B, ldb, Cm, ldc, workspace, stream=Non
                               _stream(stream)))
 
 
+def grp_set_slice_min_nodes(n: int):
+    _check(load().grp_set_slice_min_nodes(n))
+
+
 def grp_profile_enable(on):
     _check(load().grp_profile_enable(int(on)))
 
@@ -523,4 +528,4 @@ def exported_symbols():
             "grp_partition_destroy", "grp_chunks_build", "grp_chunks_build_assigned", "grp_chunks_destroy", "grp_partition_from_chunks",
             "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_step_activation", "grp_step_block", "grp_train_step",
             "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_spmm_workspace_bytes", "grp_spmm_static", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
-            "grp_profile_enable", "grp_profile_report"]
+            "grp_set_slice_min_nodes", "grp_profile_enable", "grp_profile_report"]

@@ -347,6 +347,8 @@ static grp_status adopt_impl(grp_partition_t* h, const int64_t* rowptr, const in
         GRP_TRY(long_rows_of(h->colptr, n, &h->csc_long, cap_long, cap_chunks, scanned, scan_tmp, scan_bytes, st));
     }
     GRP_HIP(hipStreamSynchronize(st));
+    GRP_TRY(build_slice_tasks(h->rowptr, h->col, n, &h->csr_long, st));
+    GRP_TRY(build_slice_tasks(h->colptr, h->row, n, &h->csc_long, st));
     return GRP_OK;
 }
 

@@ -68,13 +68,31 @@ namespace grp {
 // (device arrays, built once with the partition; see spmm.hip).
 constexpr int SPMM_LONG_ROW = 512;
 constexpr int SPMM_CHUNK = 512;
+// Source-sliced schedule of the long rows of a large structure (slices.hip): a long row is cut where its
+// sorted sources cross from one of SLICES equal ranges of node ids into the next, and each segment into tasks
+// of at most SLICE_PIECE edges; the tasks are processed slice by slice.
+constexpr int SLICES = 64;
+constexpr int SLICE_PIECE = 128;
+constexpr int SLICE_MIN_PIECE = 32;  // a row is not cut at a slice boundary before its current piece has this many edges
+struct SliceTask {
+    int64_t begin;                   // first edge of the task
+    uint32_t id;                     // its number in row-major order: where its partial row goes
+    uint32_t len;                    // 1 .. SLICE_PIECE edges
+};
 struct LongRows {
     int32_t n_long = 0, n_chunks = 0;
     int32_t* long_row = nullptr;     // [n_long]    row index
     int32_t* long_first = nullptr;   // [n_long+1]  first chunk of each long row
     int64_t* chunk_begin = nullptr;  // [n_chunks]  edge range of the chunk
     int64_t* chunk_end = nullptr;    // [n_chunks]
+    // the sliced schedule of the same rows (n_tasks = 0: not built; the aggregation then walks the chunks)
+    int64_t n_tasks = 0;
+    SliceTask* tasks = nullptr;      // [n_tasks] in processing order (slice-major, rows ascending inside a slice)
+    int64_t* row_task = nullptr;     // [n_long+1] first task id of each long row
 };
+// Structures with fewer rows than this keep the chunk schedule (their gathered rows fit the caches anyway).
+int64_t slice_min_nodes();
+grp_status build_slice_tasks(const int64_t* ptr, const int32_t* idx, int64_t n, LongRows* lr, hipStream_t st);
 }  // namespace grp
 
 struct grp_partition_s {

@@ -557,7 +557,7 @@ static void free_partition(grp_partition_t* h) {
     void* ptrs[] = {h->l2g, h->rowptr, h->col, h->colptr, h->row, h->d_local_in, h->d_local_out, h->d_global_in,
                     h->csr_long.long_row, h->csr_long.long_first, h->csr_long.chunk_begin, h->csr_long.chunk_end,
                     h->csc_long.long_row, h->csc_long.long_first, h->csc_long.chunk_begin, h->csc_long.chunk_end,
-                    h->base_mask, h->csr_w, h->csc_w, h->w_local_in, h->w_global_in};
+                    h->base_mask, h->csr_long.tasks, h->csr_long.row_task, h->csc_long.tasks, h->csc_long.row_task, h->csr_w, h->csc_w, h->w_local_in, h->w_global_in};
     const char* lo = (const char*)h->slab;
     for (void* q : ptrs)
         if (q && !(lo && (const char*)q >= lo && (const char*)q < lo + h->slab_bytes)) (void)hipFree(q);
@@ -683,6 +683,10 @@ static grp_status build_csr_csc(grp_partition_t* h, uint64_t* keys, uint64_t* ke
     GRP_TRY(build_long_rows(h->rowptr, n, &h->csr_long, cap_long, cap_chunks, scanned, scan_tmp, scan_bytes, st));
     GRP_TRY(build_long_rows(h->colptr, n, &h->csc_long, cap_long, cap_chunks, scanned, scan_tmp, scan_bytes, st));
     GRP_HIP(hipStreamSynchronize(st));
+    if (!vals) {                                          // weighted partitions keep the chunk schedule
+        GRP_TRY(build_slice_tasks(h->rowptr, h->col, n, &h->csr_long, st));
+        GRP_TRY(build_slice_tasks(h->colptr, h->row, n, &h->csc_long, st));
+    }
     return GRP_OK;
 }
 

@@ -1,0 +1,168 @@
+// Source-sliced schedule of the long rows of a CSR-like structure (built once with the partition).
+//
+// Why: a gather-bound aggregation over a graph without locality misses the L2 on almost every neighbour
+// row (measured on a 2^24-node, 2^32-edge share: 0.82 line fills per edge), because the rows gathered
+// at any one time are spread over all n sources.  The rows that hold most of the edges are long
+// (90 % of that share's edges sit in the 8 % of rows longer than 512 edges), and a row's sources are
+// sorted, so a long row can be cut where its sources cross from one range of node ids into the next: the
+// node ids are divided into SLICES = 64 equal ranges, every long row is cut at the boundaries between them
+// (where the piece so far is long enough to be worth a task), and every piece into tasks of at most SLICE_PIECE edges.  The tasks are then processed slice by slice: at any one
+// time the whole chip gathers from one 64th of the nodes, whose frequently used rows stay in the L2
+// (measured with the sources restricted to one 64th: 0.14 fills per edge).  A task's result is a partial
+// row; a long row's partial rows are added in task order (ascending source, the row's own edge order) by the
+// combine pass, so the result does not depend on scheduling.
+//
+// Layout: tasks are numbered row-major (a long row's tasks are consecutive: row_task[j] .. row_task[j+1]),
+// and the records are stored in processing order (a stable sort by slice, so that inside a slice they keep
+// row order and neighbouring workgroups read neighbouring pieces of the index array).
+#include "common.h"
+
+#include <atomic>
+
+#include <rocprim/rocprim.hpp>
+
+namespace grp {
+
+static std::atomic<int64_t> g_slice_min_nodes{(int64_t)1 << 17};
+int64_t slice_min_nodes() { return g_slice_min_nodes.load(); }
+
+static __device__ __forceinline__ int64_t lower_bound_idx(const int32_t* __restrict__ idx, int64_t b, int64_t e, int64_t want) {
+    while (b < e) {
+        const int64_t mid = (b + e) >> 1;
+        if ((int64_t)idx[mid] < want) b = mid + 1; else e = mid;
+    }
+    return b;
+}
+
+// One wavefront per long row.  Lane s finds where the row's sources enter slice s; the row is then cut at such a
+// boundary wherever the piece before it has reached SLICE_MIN_PIECE edges (a row of 600 edges is not worth 64
+// pieces of 9: a piece costs a partial row and ~200 instructions), and every piece into tasks of at most
+// SLICE_PIECE edges.  A task's key is the slice of its first edge.  EMIT = false: the row's number of tasks.
+// EMIT = true: its task records (row-major numbering from row_task[j]) and their keys.
+template <bool EMIT>
+__global__ __launch_bounds__(256) void slice_rows_kernel(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx,
+                                                         const int32_t* __restrict__ long_row, int64_t n_long, int shift,
+                                                         int64_t* __restrict__ row_tasks, SliceTask* __restrict__ recs,
+                                                         uint8_t* __restrict__ keys) {
+    __shared__ int64_t cut_s[4][SLICES + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t j = (int64_t)blockIdx.x * 4 + wave;
+    if (j >= n_long) return;                                   // uniform over the wavefront
+    const int64_t r = long_row[j];
+    if (r < 0) {                                               // an unused slot of a schedule built to its capacity
+        if (!EMIT && lane == 0) row_tasks[j] = 0;
+        return;
+    }
+    const int64_t b = ptr[r], e = ptr[r + 1];
+    cut_s[wave][lane] = lane == 0 ? b : lower_bound_idx(idx, b, e, (int64_t)lane << shift);
+    if (lane == 0) cut_s[wave][SLICES] = e;
+    __builtin_amdgcn_wave_barrier();                           // the wavefront's own LDS writes, read back below
+    int64_t t = EMIT ? row_tasks[j] : 0;                       // (row_tasks holds the exclusive prefix sum when emitting)
+    int64_t count = 0;
+    int64_t from = b;                                          // start of the current piece
+    int from_slice = 0;
+    for (int s = 1; s <= SLICES; ++s) {                        // the same walk in every lane
+        const int64_t at = cut_s[wave][s];
+        const bool close = s == SLICES || at - from >= SLICE_MIN_PIECE;
+        if (!close) continue;
+        const int64_t nt = (at - from + SLICE_PIECE - 1) / SLICE_PIECE;
+        if (EMIT) {
+            for (int64_t i = lane; i < nt; i += 64) {
+                SliceTask rec;
+                rec.begin = from + i * SLICE_PIECE;
+                rec.id = (uint32_t)(t + i);
+                rec.len = (uint32_t)(at - rec.begin < SLICE_PIECE ? at - rec.begin : SLICE_PIECE);
+                recs[t + i] = rec;
+                keys[t + i] = (uint8_t)from_slice;
+            }
+        }
+        t += nt;
+        count += nt;
+        from = at;
+        from_slice = s;
+    }
+    if (!EMIT && lane == 0) row_tasks[j] = count;
+}
+
+// Builds lr->tasks / lr->row_task for the long rows already listed in lr (allocations owned by the caller's
+// handle through these pointers).  Leaves lr untouched (n_tasks = 0) when the structure is too small to gain.
+grp_status build_slice_tasks(const int64_t* ptr, const int32_t* idx, int64_t n, LongRows* lr, hipStream_t st) {
+    lr->n_tasks = 0;
+    lr->tasks = nullptr;
+    lr->row_task = nullptr;
+    if (n < slice_min_nodes() || lr->n_long <= 0) return GRP_OK;
+    int shift = 0;
+    while (((n - 1) >> shift) >= SLICES) ++shift;
+    const int64_t n_long = lr->n_long;
+    int64_t* row_task = nullptr;
+    GRP_HIP(hipMalloc((void**)&row_task, (size_t)(n_long + 1) * sizeof(int64_t)));
+    auto fail_free = [&](grp_status s) { (void)hipFree(row_task); return s; };
+    GRP_HIP(hipMemsetAsync(row_task + n_long, 0, sizeof(int64_t), st));
+    const unsigned grid = (unsigned)cdiv(n_long, 4);
+    hipLaunchKernelGGL(slice_rows_kernel<false>, dim3(grid), dim3(256), 0, st, ptr, idx, lr->long_row, n_long, shift, row_task,
+                       (SliceTask*)nullptr, (uint8_t*)nullptr);
+    {
+        size_t need = 0;
+        if (rocprim::exclusive_scan(nullptr, need, row_task, row_task, (int64_t)0, (size_t)(n_long + 1), rocprim::plus<int64_t>(), st) != hipSuccess)
+            return fail_free(fail(GRP_EHIP, "slice schedule: scan size query failed"));
+        void* tmp = nullptr;
+        if (hipMalloc(&tmp, need ? need : 4) != hipSuccess) { (void)hipGetLastError(); return fail_free(fail(GRP_ENOMEM, "slice schedule: scan scratch")); }
+        const hipError_t e = rocprim::exclusive_scan(tmp, need, row_task, row_task, (int64_t)0, (size_t)(n_long + 1), rocprim::plus<int64_t>(), st);
+        (void)hipStreamSynchronize(st);
+        (void)hipFree(tmp);
+        if (e != hipSuccess) return fail_free(fail(GRP_EHIP, "slice schedule: scan failed"));
+    }
+    int64_t n_tasks = 0;
+    if (hipMemcpy(&n_tasks, row_task + n_long, sizeof n_tasks, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail_free(fail(GRP_EHIP, "slice schedule: task count did not reach the host"));
+    if (n_tasks <= 0 || n_tasks >= ((int64_t)1 << 32)) {       // nothing to do, or more tasks than a 32-bit id holds
+        (void)hipFree(row_task);
+        return GRP_OK;
+    }
+    SliceTask *recs = nullptr, *sorted = nullptr;
+    uint8_t *keys = nullptr, *keys_out = nullptr;
+    void* tmp = nullptr;
+    auto cleanup = [&]() { (void)hipFree(recs); (void)hipFree(keys); (void)hipFree(keys_out); (void)hipFree(tmp); };
+    grp_status status = GRP_OK;
+    do {
+        if (hipMalloc((void**)&recs, (size_t)n_tasks * sizeof(SliceTask)) != hipSuccess ||
+            hipMalloc((void**)&sorted, (size_t)n_tasks * sizeof(SliceTask)) != hipSuccess ||
+            hipMalloc((void**)&keys, (size_t)n_tasks) != hipSuccess || hipMalloc((void**)&keys_out, (size_t)n_tasks) != hipSuccess) {
+            (void)hipGetLastError();
+            status = fail(GRP_ENOMEM, "slice schedule: %lld task records", (long long)n_tasks);
+            break;
+        }
+        hipLaunchKernelGGL(slice_rows_kernel<true>, dim3(grid), dim3(256), 0, st, ptr, idx, lr->long_row, n_long, shift, row_task,
+                           recs, keys);
+        size_t need = 0;
+        if (rocprim::radix_sort_pairs(nullptr, need, keys, keys_out, recs, sorted, (size_t)n_tasks, 0u, 6u, st) != hipSuccess ||
+            hipMalloc(&tmp, need ? need : 4) != hipSuccess) {
+            (void)hipGetLastError();
+            status = fail(GRP_ENOMEM, "slice schedule: sort scratch");
+            break;
+        }
+        if (rocprim::radix_sort_pairs(tmp, need, keys, keys_out, recs, sorted, (size_t)n_tasks, 0u, 6u, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess) {
+            status = fail(GRP_EHIP, "slice schedule: sort failed");
+            break;
+        }
+    } while (false);
+    cleanup();
+    if (status != GRP_OK) {
+        (void)hipFree(sorted);
+        (void)hipFree(row_task);
+        return status;
+    }
+    lr->n_tasks = n_tasks;
+    lr->tasks = sorted;
+    lr->row_task = row_task;
+    return GRP_OK;
+}
+
+}  // namespace grp
+
+extern "C" grp_status grp_set_slice_min_nodes(int64_t n) {
+    if (n < 1) return grp::fail(GRP_EINVAL, "grp_set_slice_min_nodes: %lld", (long long)n);
+    grp::g_slice_min_nodes.store(n);
+    return GRP_OK;
+}

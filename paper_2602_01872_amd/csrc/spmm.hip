@@ -262,6 +262,161 @@ __global__ __launch_bounds__(256) void spmm_combine_kernel(const int32_t* __rest
     }
 }
 
+// ---- the source-sliced schedule of the long rows (slices.hip): one wavefront per task.
+// A task is at most SLICE_PIECE = 128 consecutive edges of one long row whose sources lie in one slice of the
+// node ids.  The wavefront reads the task's indices with one coalesced load (two per lane), its 64 / G groups
+// take consecutive runs of them (handed round with shuffles, up to four gathers in flight per group), the
+// groups' sums are added across the wavefront in a fixed butterfly, and the first group writes the partial row.
+template <typename XT, int G, int NJ, bool EV, bool CS>
+__global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __restrict__ tasks, int64_t n_tasks, int64_t per_wave,
+                                                         const int32_t* __restrict__ idx, const float* __restrict__ val, int F,
+                                                         const XT* __restrict__ X, int64_t ldx,
+                                                         const float* __restrict__ colscale, float* __restrict__ partials,
+                                                         int64_t ld_part) {
+    static_assert(SLICE_PIECE == 128, "two indices per lane");
+    constexpr int NG = 64 / G;
+    constexpr int U = (G >= 16 && NJ == 1) ? 8 : 4;       // gathers in flight per group (measured: 8 loses for narrower rows)
+    const int lane = threadIdx.x & 63;
+    const int t = lane % G, gi = lane / G;
+    // wavefront w takes the tasks [w * per_wave, (w + 1) * per_wave): consecutive wavefronts walk the processing
+    // order front to back (a launch holds at most 2^32 work-items, so one task per wavefront does not scale).
+    // The loop is software-pipelined: while the gathers of task p are in flight, the indices of task p + 1 and the
+    // record of task p + 2 are requested, so a task costs one memory round trip instead of three.
+    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t p0 = w * per_wave;
+    const int64_t p_end = p0 + per_wave < n_tasks ? p0 + per_wave : n_tasks;
+    if (p0 >= p_end) return;                               // uniform over the wavefront
+    // Every load below is unconditional (an index past a task's end is clamped to its last edge and the gathered
+    // row then dropped by a select): a conditional load becomes a branch with a wait behind it, and the gathers
+    // of a task would no longer overlap.
+    auto load_indices = [&](const SliceTask& tk, int32_t& a, int32_t& b, float& wa, float& wb) {
+        const int last = (int)tk.len > 0 ? (int)tk.len - 1 : 0;
+        const int64_t ea = tk.begin + (lane < last ? lane : last), eb = tk.begin + (64 + lane < last ? 64 + lane : last);
+        a = idx[ea];
+        b = idx[eb];
+        if (EV) { wa = val[ea]; wb = val[eb]; }
+    };
+    SliceTask cur = tasks[p0];
+    SliceTask nxt = tasks[p0 + 1 < p_end ? p0 + 1 : p0];
+    int32_t i0, i1;
+    float w0 = 1.f, w1 = 1.f;
+    load_indices(cur, i0, i1, w0, w1);
+    bool live[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) live[j] = 4 * (t + G * j) < F;
+    for (int64_t p = p0; p < p_end; ++p) {
+        const int len = (int)cur.len;                      // >= 1
+        const int per = (len + NG - 1) / NG;               // the same in every lane
+        const int first = gi * per;
+        float4 acc[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        SliceTask nn = nxt;
+        int32_t n0 = 0, n1 = 0;
+        float nw0 = 1.f, nw1 = 1.f;
+        for (int k0 = 0; k0 < per; k0 += U) {
+            int64_t c[U];
+            float sc[U];
+            bool on[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int pos = first + k0 + u;
+                on[u] = k0 + u < per && pos < len;
+                const int src = pos & 63;
+                const int32_t a = __shfl(i0, src, 64), b = __shfl(i1, src, 64);
+                c[u] = (pos & 64) ? b : a;                 // a valid index of this task even where `on` is false
+                sc[u] = 1.f;
+                if (EV) {
+                    const float wa = __shfl(w0, src, 64), wb = __shfl(w1, src, 64);
+                    sc[u] = (pos & 64) ? wb : wa;
+                }
+                if (CS) sc[u] *= colscale[c[u]];
+            }
+            float4 v[NJ][U];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    v[j][u] = Vec4Load<XT>::ld(X + c[u] * ldx + 4 * ((live[j] ? t : 0) + (live[j] ? G * j : 0)));
+            if (k0 == 0) {                                 // behind the first gathers: what the next two tasks need
+                __builtin_amdgcn_sched_barrier(0);
+                load_indices(nxt, n0, n1, nw0, nw1);
+                nn = tasks[p + 2 < p_end ? p + 2 : p];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    float4 x = v[j][u];
+                    if (EV || CS) { x.x *= sc[u]; x.y *= sc[u]; x.z *= sc[u]; x.w *= sc[u]; }
+                    acc[j].x += on[u] ? x.x : 0.f;
+                    acc[j].y += on[u] ? x.y : 0.f;
+                    acc[j].z += on[u] ? x.z : 0.f;
+                    acc[j].w += on[u] ? x.w : 0.f;
+                }
+        }
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+            for (int o = G; o < 64; o <<= 1) {
+                acc[j].x += __shfl_xor(acc[j].x, o, 64);
+                acc[j].y += __shfl_xor(acc[j].y, o, 64);
+                acc[j].z += __shfl_xor(acc[j].z, o, 64);
+                acc[j].w += __shfl_xor(acc[j].w, o, 64);
+            }
+            if (gi == 0 && live[j]) *reinterpret_cast<float4*>(partials + (int64_t)cur.id * ld_part + 4 * (t + G * j)) = acc[j];
+        }
+        cur = nxt; nxt = nn;
+        i0 = n0; i1 = n1;
+        if (EV) { w0 = nw0; w1 = nw1; }
+    }
+}
+
+// One wavefront per long row: group g adds the row's partial rows g, g + 64/G, ... in ascending order, the groups'
+// sums are added in a fixed butterfly, then the epilogue.
+template <typename XT, int G, int NJ>
+__global__ __launch_bounds__(256) void spmm_combine_tasks_kernel(const int32_t* __restrict__ long_row,
+                                                                 const int64_t* __restrict__ row_task, int n_long,
+                                                                 const int64_t* __restrict__ ptr,
+                                                                 const float* __restrict__ partials, int64_t ld_part,
+                                                                 const XT* __restrict__ X, int64_t ldx, SpmmEpilogue ep) {
+    constexpr int NG = 64 / G;
+    const int lane = threadIdx.x & 63;
+    const int j0 = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j0 >= n_long) return;
+    const int64_t i = long_row[j0];
+    if (i < 0) return;
+    const int t = lane % G, gi = lane / G;
+    const int64_t t0 = row_task[j0], t1 = row_task[j0 + 1];
+    const int64_t deg = ptr[i + 1] - ptr[i];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int col = 4 * (t + G * j);
+        const bool live = col < ep.F;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (live) {
+            int64_t c = t0 + gi;
+            for (; c + 3 * NG < t1; c += 4 * NG) {          // four loads in flight, added in ascending order
+                const float4 a0 = *reinterpret_cast<const float4*>(partials + c * ld_part + col);
+                const float4 a1 = *reinterpret_cast<const float4*>(partials + (c + NG) * ld_part + col);
+                const float4 a2 = *reinterpret_cast<const float4*>(partials + (c + 2 * NG) * ld_part + col);
+                const float4 a3 = *reinterpret_cast<const float4*>(partials + (c + 3 * NG) * ld_part + col);
+                add4(acc, a0); add4(acc, a1); add4(acc, a2); add4(acc, a3);
+            }
+            for (; c < t1; c += NG) add4(acc, *reinterpret_cast<const float4*>(partials + c * ld_part + col));
+        }
+#pragma unroll
+        for (int o = G; o < 64; o <<= 1) {
+            acc.x += __shfl_xor(acc.x, o, 64);
+            acc.y += __shfl_xor(acc.y, o, 64);
+            acc.z += __shfl_xor(acc.z, o, 64);
+            acc.w += __shfl_xor(acc.w, o, 64);
+        }
+        if (gi == 0 && live) finish_row<XT>(ep, i, deg, col, acc, X, ldx);
+    }
+}
+
 // Fallback for pitches or pointers that are not 16-byte friendly: one wavefront per row,
 // one lane per column (handles rows of any length itself).
 template <typename XT>
@@ -293,19 +448,36 @@ static void launch_one(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_t st
     constexpr int ROWS = 256 / G;
     const LongRows* lr = a.long_rows;
     const bool split = lr && lr->n_long > 0;
+    const bool sliced = split && lr->n_tasks > 0;
     const int64_t thr = split ? (int64_t)SPMM_LONG_ROW : INT64_MAX;
-    const int n_chunks = split ? lr->n_chunks : 0;
+    const int n_chunks = split && !sliced ? lr->n_chunks : 0;
     const int64_t ld_part = round_up(a.F, 4);
+    if (sliced) {                                          // the long rows' tasks, slice by slice
+        const int64_t per_wave = cdiv(lr->n_tasks, (int64_t)4 << 21);      // at most 2^21 workgroups of four wavefronts
+        const dim3 tgrid((unsigned)cdiv(lr->n_tasks, 4 * per_wave));
+        auto go = [&](auto kernel) {
+            hipLaunchKernelGGL(kernel, tgrid, dim3(256), 0, st, (const SliceTask*)lr->tasks, lr->n_tasks, per_wave, a.idx, a.val, a.F,
+                               (const XT*)a.X, a.ldx, a.colscale, a.partials, ld_part);
+        };
+        if (a.val && a.colscale) go(spmm_tasks_kernel<XT, G, NJ, true, true>);
+        else if (a.val) go(spmm_tasks_kernel<XT, G, NJ, true, false>);
+        else if (a.colscale) go(spmm_tasks_kernel<XT, G, NJ, false, true>);
+        else go(spmm_tasks_kernel<XT, G, NJ, false, false>);
+    }
     const dim3 grid((unsigned)(n_chunks + cdiv(a.n_rows, ROWS)));
     if (a.val)
         hipLaunchKernelGGL((spmm_rows_kernel<XT, G, NJ, true>), grid, dim3(256), 0, st, a.ptr, a.idx, a.val, a.n_rows, thr,
-                           (const XT*)a.X, a.ldx, a.colscale, ep, n_chunks, split ? lr->chunk_begin : nullptr,
-                           split ? lr->chunk_end : nullptr, a.partials, ld_part);
+                           (const XT*)a.X, a.ldx, a.colscale, ep, n_chunks, n_chunks ? lr->chunk_begin : nullptr,
+                           n_chunks ? lr->chunk_end : nullptr, a.partials, ld_part);
     else
         hipLaunchKernelGGL((spmm_rows_kernel<XT, G, NJ, false>), grid, dim3(256), 0, st, a.ptr, a.idx, a.val, a.n_rows, thr,
-                           (const XT*)a.X, a.ldx, a.colscale, ep, n_chunks, split ? lr->chunk_begin : nullptr,
-                           split ? lr->chunk_end : nullptr, a.partials, ld_part);
-    if (split) {
+                           (const XT*)a.X, a.ldx, a.colscale, ep, n_chunks, n_chunks ? lr->chunk_begin : nullptr,
+                           n_chunks ? lr->chunk_end : nullptr, a.partials, ld_part);
+    if (sliced) {
+        hipLaunchKernelGGL((spmm_combine_tasks_kernel<XT, G, NJ>), dim3((unsigned)cdiv(lr->n_long, 4)), dim3(256), 0, st,
+                           lr->long_row, (const int64_t*)lr->row_task, lr->n_long, a.ptr, (const float*)a.partials, ld_part,
+                           (const XT*)a.X, a.ldx, ep);
+    } else if (split) {
         hipLaunchKernelGGL((spmm_combine_kernel<XT, G, NJ>), dim3((unsigned)cdiv(lr->n_long, ROWS)), dim3(256), 0, st,
                            lr->long_row, lr->long_first, lr->n_long, a.ptr, (const float*)a.partials, ld_part,
                            (const XT*)a.X, a.ldx, ep);
@@ -315,6 +487,14 @@ static void launch_one(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_t st
 template <typename XT>
 static grp_status dispatch(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_t st) {
     const int f4 = (a.F + 3) / 4;
+    {       // a launch holds fewer than 2^32 work-items: a row per group of f4 lanes (rounded up to a power of two)
+        int g = 1;
+        while (g < f4 && g < 64) g <<= 1;
+        const LongRows* lr = a.long_rows;
+        const int64_t chunks = lr && lr->n_long > 0 && lr->n_tasks == 0 ? lr->n_chunks : 0;
+        if ((chunks + cdiv(a.n_rows, 256 / g)) * 256 >= ((int64_t)1 << 32))
+            return fail(GRP_EUNSUPPORTED, "spmm: %lld rows of %d columns exceed one launch", (long long)a.n_rows, a.F);
+    }
     if (f4 <= 1) launch_one<XT, 1, 1>(a, ep, st);
     else if (f4 <= 2) launch_one<XT, 2, 1>(a, ep, st);
     else if (f4 <= 4) launch_one<XT, 4, 1>(a, ep, st);
@@ -330,7 +510,8 @@ static grp_status dispatch(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_
 
 size_t spmm_partials_bytes(const LongRows* lr, int32_t F) {
     if (!lr || lr->n_long == 0) return 0;
-    return (size_t)lr->n_chunks * round_up(F, 4) * sizeof(float);
+    const int64_t slots = lr->n_tasks > 0 ? lr->n_tasks : (int64_t)lr->n_chunks;      // one partial row per task or chunk
+    return (size_t)slots * round_up(F, 4) * sizeof(float);
 }
 
 grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {

@@ -76,7 +76,9 @@ static StepPlan make_plan(const grp_partition_t* part, const grp_model_desc* m, 
     const bool sage = m->arch == GRP_ARCH_SAGE_MEAN;
     const bool mb = !o->full_graph;
     SamplerBounds bd;
-    int64_t chunks_cap = part->csr_long.n_chunks > part->csc_long.n_chunks ? part->csr_long.n_chunks : part->csc_long.n_chunks;
+    // partial rows of the split long rows: one per task of the sliced schedule, else one per chunk
+    auto slots = [](const LongRows& lr) { return lr.n_tasks > 0 ? lr.n_tasks : (int64_t)lr.n_chunks; };
+    int64_t chunks_cap = slots(part->csr_long) > slots(part->csc_long) ? slots(part->csr_long) : slots(part->csc_long);
     if (mb) {
         sampler_bounds(n, o->n_seeds, o->fanouts, k, &bd);
         p.sampler_bytes = sampler_workspace_bytes(n, bd, k);
@@ -148,9 +150,12 @@ static StepPlan make_plan(const grp_partition_t* part, const grp_model_desc* m, 
     p.colsum_ws = b.take<char>(cs_bytes);
     p.stats_ws = b.take<char>(stats_workspace_bytes(n));
     {
-        int64_t fsp = 0;
-        for (int l = 0; l <= k; ++l)
-            if (ldp(m->dims[l]) > fsp) fsp = ldp(m->dims[l]);
+        int64_t fsp = 0;                                   // the widest aggregation of the step
+        for (int l = 0; l < k; ++l) {
+            const int64_t w = sage ? (p.L[l].agg_first ? ldp(m->dims[l]) : ldp(m->dims[l + 1]))
+                                   : (ldp(m->dims[l]) > ldp(m->dims[l + 1]) ? ldp(m->dims[l]) : ldp(m->dims[l + 1]));
+            if (w > fsp) fsp = w;
+        }
         p.partials = b.take<float>((size_t)chunks_cap * fsp);
     }
     p.total = b.total();

@@ -172,8 +172,10 @@ def _run(SCALE, N, E, CH):
         want = _oracle_rows(rows, lists, x)
         got = y[rows].cpu().double().numpy()
         err = np.abs(got - want).max() / max(np.abs(want).max(), 1e-30)
+        worst = int(np.abs(got - want).max(axis=1).argmax())
         _note(f"transposed={transposed}: {rows.numel()} sampled rows (longest {max(len(a) for a in lists)}, "
-              f"{sum(len(a) == 0 for a in lists)} empty) rel err {err:.2e}")
+              f"{sum(len(a) == 0 for a in lists)} empty) rel err {err:.2e} (largest at row {int(rows[worst])} "
+              f"of {len(lists[worst])} edges)")
         assert err <= TOL_FP32
         lhs = y.sum(dim=0, dtype=torch.float64)
         w = w_bwd if transposed else w_fwd

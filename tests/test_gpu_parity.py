@@ -156,6 +156,50 @@ def test_spmm_matches_oracle(g, F, ld, bf16):
             assert rel_err(got, want) <= tol, (transposed, scale, self_term, rel_err(got, want))
 
 
+@pytest.mark.parametrize("F,bf16", [(16, False), (64, True), (47, False), (256, False), (300, False)])
+def test_spmm_with_the_sliced_schedule_matches_oracle(g, F, bf16):
+    """The source-sliced schedule of the long rows (built for large partitions) forced on a small one: rows cut
+    into 64 source ranges and pieces of at most 128 edges, partial rows combined per row."""
+    _note(f"spmm sliced schedule F={F} bf16={bf16}")
+    n, E = 5000, 700000
+    s, d = synth.rmat_graph(13, E, seed=78, n_nodes=n, device=DEV)
+    g.grp_set_slice_min_nodes(1)
+    try:
+        part = g.grp_partition_from_local_coo(s, d, n)
+    finally:
+        g.grp_set_slice_min_nodes(1 << 17)
+    op = ograph.local_graph_from_edges(s.cpu().numpy(), d.cpu().numpy(), n)
+    assert int(op["d_local_in"].max()) > 15000 and int((op["d_local_in"] > 512).sum()) > 100      # hub rows of many pieces per range
+    assert g.grp_spmm_workspace_bytes(part, False, F) > 0
+    ld = (F + 3) // 4 * 4
+    xf = synth.normal_matrix(n, ld, 3)
+    xf[:, F:] = 0
+    x = (synth.to_bf16_rne(xf) if bf16 else xf).to(DEV)
+    x64 = x.cpu().double().numpy()[:, :F]
+    for transposed in (False, True):
+        for scale, self_term in ((g.SCALE_MEAN, False), (g.SCALE_RSQRT, True)):
+            y = torch.full((n, ld), float("nan"), device=DEV)
+            g.grp_spmm(part, transposed, scale, self_term, F, x, ld, g.DTYPE_BF16 if bf16 else g.DTYPE_FP32, y, ld)
+            torch.cuda.synchronize()
+            want = _oracle_spmm(op, transposed, scale, self_term, x64)
+            assert rel_err(y.cpu().numpy()[:, :F], want) <= TOL_FP32, (transposed, scale, rel_err(y.cpu().numpy()[:, :F], want))
+    # a train step on the same handle (every aggregation of the step takes the sliced path), GCN for the per-source scale
+    for arch, name, dims in ((g.ARCH_SAGE_MEAN, "sage", [24, 40, 6]), (g.ARCH_GCN, "gcn", [24, 16, 6])):
+        xs, ys, theta = make_inputs(n, dims, name, 9)
+        model = g.model_desc(arch, dims)
+        opts = g.step_opts(estimator=g.EST_SHRINKAGE)
+        P = g.grp_param_count(model)
+        ws = torch.empty(g.grp_step_workspace_bytes(part, model, opts), dtype=torch.uint8, device=DEV)
+        grad = torch.full((P,), float("nan"), device=DEV)
+        stats = g.new_stats(1)
+        g.grp_train_step(part, model, opts, xs.to(DEV), ys.to(DEV), None, theta.to(DEV), ws, grad, stats)
+        torch.cuda.synchronize()
+        fn = lambda relu_flip=None, near_kink=None: ostep.train_step(op, name, dims, theta.double().numpy(), xs.double().numpy(),
+                                                                      ys.numpy(), estimator=3, relu_flip=relu_flip, near_kink=near_kink)
+        assert_step_grads_close(grad.cpu().numpy(), fn, name, dims, TOL_FP32)
+    part.destroy()
+
+
 # ----------------------------------------------------------------------------- GEMMs
 @pytest.mark.parametrize("M,N,K,bf16", [(1000, 256, 256, False), (777, 47, 100, False), (129, 8, 64, False),
                                         (5000, 172, 128, True), (333, 130, 33, False), (64, 64, 256, False)])
