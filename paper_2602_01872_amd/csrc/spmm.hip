@@ -22,6 +22,7 @@
 #include "common.h"
 
 #include <mutex>
+#include <type_traits>
 
 namespace grp {
 
@@ -267,7 +268,34 @@ __global__ __launch_bounds__(256) void spmm_combine_kernel(const int32_t* __rest
 // node ids.  The wavefront reads the task's indices with one coalesced load (two per lane), its 64 / G groups
 // take consecutive runs of them (handed round with shuffles, up to four gathers in flight per group), the
 // groups' sums are added across the wavefront in a fixed butterfly, and the first group writes the partial row.
-template <typename XT, int G, int NJ, bool EV, bool CS>
+// VW consecutive elements of a row as floats: the unit a lane owns (16 bytes of fp32, 8 or 16 bytes of bf16).
+template <typename XT, int VW> struct LaneVec;
+template <> struct LaneVec<float, 4> {
+    static __device__ __forceinline__ void ld(const float* p, float (&f)[4]) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+};
+template <> struct LaneVec<__hip_bfloat16, 4> {
+    static __device__ __forceinline__ void ld(const __hip_bfloat16* p, float (&f)[4]) {
+        const uint2 r = *reinterpret_cast<const uint2*>(p);
+        f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xFFFF0000u);
+        f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xFFFF0000u);
+    }
+};
+template <> struct LaneVec<__hip_bfloat16, 8> {
+    static __device__ __forceinline__ void ld(const __hip_bfloat16* p, float (&f)[8]) {
+        const uint4 r = *reinterpret_cast<const uint4*>(p);
+        f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xFFFF0000u);
+        f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xFFFF0000u);
+        f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xFFFF0000u);
+        f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xFFFF0000u);
+    }
+};
+
+// G lanes own a row, VW elements each (VW = 8 for bf16 rows that allow 16-byte loads: half the lanes per row,
+// so twice the rows in flight per wavefront for the same registers), NJ slabs of G * VW columns.
+template <typename XT, int G, int NJ, int VW, bool EV, bool CS>
 __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __restrict__ tasks, int64_t n_tasks, int64_t per_wave,
                                                          const int32_t* __restrict__ idx, const float* __restrict__ val, int F,
                                                          const XT* __restrict__ X, int64_t ldx,
@@ -275,7 +303,7 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
                                                          int64_t ld_part) {
     static_assert(SLICE_PIECE == 128, "two indices per lane");
     constexpr int NG = 64 / G;
-    constexpr int U = (G >= 16 && NJ == 1) ? 8 : 4;       // gathers in flight per group (measured: 8 loses for narrower rows)
+    constexpr int U = (G * VW >= 64 && NJ == 1) ? 8 : 4;   // gathers in flight per group (measured: 8 loses for narrower rows)
     const int lane = threadIdx.x & 63;
     const int t = lane % G, gi = lane / G;
     // wavefront w takes the tasks [w * per_wave, (w + 1) * per_wave): consecutive wavefronts walk the processing
@@ -301,16 +329,22 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
     int32_t i0, i1;
     float w0 = 1.f, w1 = 1.f;
     load_indices(cur, i0, i1, w0, w1);
+    int col[NJ];                                           // first column of the lane's unit in slab j (a dead unit reads column 0)
     bool live[NJ];
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) live[j] = 4 * (t + G * j) < F;
+    for (int j = 0; j < NJ; ++j) {
+        live[j] = VW * (t + G * j) < F;
+        col[j] = live[j] ? VW * (t + G * j) : 0;
+    }
     for (int64_t p = p0; p < p_end; ++p) {
         const int len = (int)cur.len;                      // >= 1
         const int per = (len + NG - 1) / NG;               // the same in every lane
         const int first = gi * per;
-        float4 acc[NJ];
+        float acc[NJ][VW];
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int q = 0; q < VW; ++q) acc[j][q] = 0.f;
         SliceTask nn = nxt;
         int32_t n0 = 0, n1 = 0;
         float nw0 = 1.f, nw1 = 1.f;
@@ -332,12 +366,11 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
                 }
                 if (CS) sc[u] *= colscale[c[u]];
             }
-            float4 v[NJ][U];
+            float v[NJ][U][VW];
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    v[j][u] = Vec4Load<XT>::ld(X + c[u] * ldx + 4 * ((live[j] ? t : 0) + (live[j] ? G * j : 0)));
+                for (int u = 0; u < U; ++u) LaneVec<XT, VW>::ld(X + c[u] * ldx + col[j], v[j][u]);
             if (k0 == 0) {                                 // behind the first gathers: what the next two tasks need
                 __builtin_amdgcn_sched_barrier(0);
                 load_indices(nxt, n0, n1, nw0, nw1);
@@ -347,25 +380,26 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    float4 x = v[j][u];
-                    if (EV || CS) { x.x *= sc[u]; x.y *= sc[u]; x.z *= sc[u]; x.w *= sc[u]; }
-                    acc[j].x += on[u] ? x.x : 0.f;
-                    acc[j].y += on[u] ? x.y : 0.f;
-                    acc[j].z += on[u] ? x.z : 0.f;
-                    acc[j].w += on[u] ? x.w : 0.f;
-                }
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int q = 0; q < VW; ++q) {
+                        float x = v[j][u][q];
+                        if (EV || CS) x *= sc[u];
+                        acc[j][q] += on[u] ? x : 0.f;
+                    }
         }
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
 #pragma unroll
-            for (int o = G; o < 64; o <<= 1) {
-                acc[j].x += __shfl_xor(acc[j].x, o, 64);
-                acc[j].y += __shfl_xor(acc[j].y, o, 64);
-                acc[j].z += __shfl_xor(acc[j].z, o, 64);
-                acc[j].w += __shfl_xor(acc[j].w, o, 64);
+            for (int o = G; o < 64; o <<= 1)
+#pragma unroll
+                for (int q = 0; q < VW; ++q) acc[j][q] += __shfl_xor(acc[j][q], o, 64);
+            if (gi == 0 && live[j]) {
+                float* out = partials + (int64_t)cur.id * ld_part + col[j];
+#pragma unroll
+                for (int q = 0; q < VW; q += 4)
+                    *reinterpret_cast<float4*>(out + q) = make_float4(acc[j][q], acc[j][q + 1], acc[j][q + 2], acc[j][q + 3]);
             }
-            if (gi == 0 && live[j]) *reinterpret_cast<float4*>(partials + (int64_t)cur.id * ld_part + 4 * (t + G * j)) = acc[j];
         }
         cur = nxt; nxt = nn;
         i0 = n0; i1 = n1;
@@ -459,10 +493,23 @@ static void launch_one(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_t st
             hipLaunchKernelGGL(kernel, tgrid, dim3(256), 0, st, (const SliceTask*)lr->tasks, lr->n_tasks, per_wave, a.idx, a.val, a.F,
                                (const XT*)a.X, a.ldx, a.colscale, a.partials, ld_part);
         };
-        if (a.val && a.colscale) go(spmm_tasks_kernel<XT, G, NJ, true, true>);
-        else if (a.val) go(spmm_tasks_kernel<XT, G, NJ, true, false>);
-        else if (a.colscale) go(spmm_tasks_kernel<XT, G, NJ, false, true>);
-        else go(spmm_tasks_kernel<XT, G, NJ, false, false>);
+        // bf16 rows of whole 16-byte units: eight elements per lane, half the lanes per row
+        constexpr bool bf16 = std::is_same<XT, __hip_bfloat16>::value;
+        const bool wide = bf16 && G >= 2 && NJ == 1 && a.F % 8 == 0 && a.ldx % 8 == 0 && ((uintptr_t)a.X % 16) == 0;
+        if constexpr (bf16 && G >= 2 && NJ == 1) {
+            if (wide) {
+                if (a.val && a.colscale) go(spmm_tasks_kernel<XT, G / 2, 1, 8, true, true>);
+                else if (a.val) go(spmm_tasks_kernel<XT, G / 2, 1, 8, true, false>);
+                else if (a.colscale) go(spmm_tasks_kernel<XT, G / 2, 1, 8, false, true>);
+                else go(spmm_tasks_kernel<XT, G / 2, 1, 8, false, false>);
+            }
+        }
+        if (!wide) {
+            if (a.val && a.colscale) go(spmm_tasks_kernel<XT, G, NJ, 4, true, true>);
+            else if (a.val) go(spmm_tasks_kernel<XT, G, NJ, 4, true, false>);
+            else if (a.colscale) go(spmm_tasks_kernel<XT, G, NJ, 4, false, true>);
+            else go(spmm_tasks_kernel<XT, G, NJ, 4, false, false>);
+        }
     }
     const dim3 grid((unsigned)(n_chunks + cdiv(a.n_rows, ROWS)));
     if (a.val)
