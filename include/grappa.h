@@ -382,6 +382,41 @@ grp_status grp_step_block(const grp_partition_t* part, const grp_model_desc* mod
 grp_status grp_aggregate(const float* grads, int64_t ld_grads, const grp_step_stats* stats,
                          int32_t K, int64_t P, int32_t variant, void* stream,
                          float* update, float* c_out);
+/* The same reduction over K separately owned gradient buffers (the buffers a framework's backward pass fills,
+ * as the paper's gradient hook sees them): grads is a DEV array of K DEV pointers, each to P floats.
+ * aligned16 != 0 promises that every buffer is 16-byte aligned (16-byte loads); results are the same bits either
+ * way, and the same as grp_aggregate's on the same values.                                                  */
+grp_status grp_aggregate_ptrs(const float* const* grads, int32_t aligned16, const grp_step_stats* stats,
+                              int32_t K, int64_t P, int32_t variant, void* stream,
+                              float* update, float* c_out);
+
+/* ------------------------------------------------------------------ training controller (host arithmetic) */
+
+/* The chunk worker `worker` (base chunk = worker) sweeps in super-epoch t: (worker + 1 + (t mod (c-1))) mod c for
+ * c = n_chunks > 1, 0 for c = 1 (coverage guarantee paragraph: after c - 1 super-epochs every pair of chunks
+ * has shared a partition; then the cycle repeats).  -1 for arguments out of range.                         */
+int32_t grp_sweep_chunk(int32_t worker, int64_t super_epoch, int32_t n_chunks);
+/* Epochs per super-epoch: ceil(e / (c - 1)) for e epochs in all ("Training Controller and Partitions Switching":
+ * the e epochs are spread over the c - 1 super-epochs of a cycle), at least 1; -1 for arguments out of range. */
+int64_t grp_super_epoch_epochs(int64_t total_epochs, int32_t n_chunks);
+
+/* The controller (same subsection): it lets a super-epoch run its epochs and switches partitions earlier once
+ * the coverage deficit of a step, 1 - mean over the step's active partitions of the minimum-distance factor
+ * c_hat_p = sum_ratio_p / S_p (1 if S_p = 0), has exceeded `threshold` on `patience` consecutive steps (the paper
+ * monitors the deficit and gives neither number: both are the caller's).  Host object; not thread-safe.   */
+typedef struct grp_controller_s grp_controller_t;
+grp_status grp_controller_create(int64_t total_epochs, int32_t n_chunks, double threshold, int64_t patience,
+                                 grp_controller_t** out);
+/* One training step: c_hat HOST float[m] (e.g. c_out of grp_aggregate with GRP_EST_BATCH_MIN_DIST), or the step's
+ * statistics records themselves, HOST grp_step_stats[m] (a copy of what grp_train_step wrote), m >= 1.        */
+grp_status grp_controller_observe(grp_controller_t* ctl, const float* c_hat, int32_t m);
+grp_status grp_controller_observe_stats(grp_controller_t* ctl, const grp_step_stats* stats, int32_t m);
+/* End of an epoch: *switched = 1 if the partitions must be rebuilt for the next super-epoch (its number is
+ * then one higher and the step streak starts again).                                                        */
+grp_status grp_controller_end_epoch(grp_controller_t* ctl, int32_t* switched /*HOST*/);
+grp_status grp_controller_state(const grp_controller_t* ctl, int64_t* super_epoch /*HOST or NULL*/,
+                                int64_t* epochs_per_super_epoch /*HOST or NULL*/);
+grp_status grp_controller_destroy(grp_controller_t* ctl);   /* NULL is a no-op */
 
 /* ------------------------------------------------------------------ optimizer */
 

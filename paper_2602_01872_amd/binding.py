@@ -96,6 +96,7 @@ def load() -> C.CDLL:
         "grp_step_block": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), vp, sz, i32, C.POINTER(BlockView)],
         "grp_train_step": [vp, C.POINTER(ModelDesc), C.POINTER(StepOpts), vp, vp, vp, vp, vp, sz, vp, vp, vp],
         "grp_aggregate": [vp, i64, vp, i32, i64, i32, vp, vp, vp],
+        "grp_aggregate_ptrs": [vp, i32, vp, i32, i64, i32, vp, vp, vp],
         "grp_optimizer_step": [C.POINTER(OptimizerDesc), i64, i64, vp, vp, vp, vp, vp],
         "grp_spmm_workspace_bytes": [vp, i32, i32, C.POINTER(sz)],
         "grp_spmm": [vp, i32, i32, i32, i32, vp, i64, i32, vp, i64, vp, sz, vp],
@@ -104,6 +105,12 @@ def load() -> C.CDLL:
         "grp_gemm_nt": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
         "grp_gemm_tn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp, sz, vp],
         "grp_set_slice_min_nodes": [i64],
+        "grp_controller_create": [i64, i32, C.c_double, i64, C.POINTER(vp)],
+        "grp_controller_observe": [vp, vp, i32],
+        "grp_controller_observe_stats": [vp, vp, i32],
+        "grp_controller_end_epoch": [vp, C.POINTER(i32)],
+        "grp_controller_state": [vp, C.POINTER(i64), C.POINTER(i64)],
+        "grp_controller_destroy": [vp],
         "grp_profile_enable": [i32],
         "grp_profile_report": [C.c_char_p, sz],
     }
@@ -113,6 +120,10 @@ def load() -> C.CDLL:
         fn.restype = i32
     lib.grp_param_count.argtypes = [C.POINTER(ModelDesc)]
     lib.grp_param_count.restype = i64
+    lib.grp_sweep_chunk.argtypes = [i32, i64, i32]
+    lib.grp_sweep_chunk.restype = i32
+    lib.grp_super_epoch_epochs.argtypes = [i64, i32]
+    lib.grp_super_epoch_epochs.restype = i64
     lib.grp_gemm_tn_workspace_bytes.argtypes = [i64, i32, i32]
     lib.grp_gemm_tn_workspace_bytes.restype = sz
     _lib = lib
@@ -439,6 +450,15 @@ def grp_aggregate(grads, ld_grads: int, stats, K: int, P: int, variant: int, upd
                                 _ptr(c_out)))
 
 
+def grp_aggregate_ptrs(grad_tensors, stats, P: int, variant: int, update, c_out=None, stream=None):
+    """``grad_tensors``: a list of K device tensors of at least P floats each (separately owned buffers)."""
+    ptrs = torch.tensor([t.data_ptr() for t in grad_tensors], dtype=torch.int64, device=update.device)
+    aligned = all(t.data_ptr() % 16 == 0 for t in grad_tensors)
+    _check(load().grp_aggregate_ptrs(_ptr(ptrs), int(aligned), _ptr(stats), len(grad_tensors), P, variant, _stream(stream),
+                                     _ptr(update), _ptr(c_out)))
+    return ptrs          # keep alive until the stream has run the launch
+
+
 def optimizer_desc(kind: int = OPT_ADAM, lr: float = 0.003, beta1: float = 0.9, beta2: float = 0.999,
                    eps: float = 1e-8) -> OptimizerDesc:
     o = OptimizerDesc()
@@ -527,5 +547,5 @@ def exported_symbols():
     return ["grp_last_error", "grp_partition", "grp_node_owners", "grp_epoch_seeds", "grp_gather_rows", "grp_partition_weighted", "grp_partition_weights", "grp_partition_from_local_coo", "grp_partition_from_csr", "grp_partition_view",
             "grp_partition_destroy", "grp_chunks_build", "grp_chunks_build_assigned", "grp_chunks_destroy", "grp_partition_from_chunks",
             "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_step_activation", "grp_step_block", "grp_train_step",
-            "grp_aggregate", "grp_optimizer_step", "grp_spmm", "grp_spmm_workspace_bytes", "grp_spmm_static", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
-            "grp_set_slice_min_nodes", "grp_profile_enable", "grp_profile_report"]
+            "grp_aggregate", "grp_aggregate_ptrs", "grp_optimizer_step", "grp_spmm", "grp_spmm_workspace_bytes", "grp_spmm_static", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
+            "grp_set_slice_min_nodes", "grp_sweep_chunk", "grp_super_epoch_epochs", "grp_controller_create", "grp_controller_observe", "grp_controller_observe_stats", "grp_controller_end_epoch", "grp_controller_state", "grp_controller_destroy", "grp_profile_enable", "grp_profile_report"]

@@ -250,7 +250,7 @@ class SweepingTrainer:
         for h in self.inner.history[first:]:
             rec = g.read_stats(h)
             self._losses.append(float(rec["loss"].mean()))
-            self.ctl.observe_step([float(r["sum_ratio"]) / int(r["S"]) if int(r["S"]) > 0 else 1.0 for r in rec])
+            self.ctl.observe_stats(rec)                   # the deficit is derived from the records inside the library
         if self.ctl.end_epoch():
             self.switches.append(self.epoch)
             for p in self.inner.parts:

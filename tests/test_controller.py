@@ -1,5 +1,5 @@
-"""Host logic of the product's training controller against the oracle's (written separately)
-and against the schedule's defining properties."""
+"""The library's host-side controller calls against the oracle's controller (written separately) and against the
+schedule's defining properties."""
 import numpy as np
 import pytest
 
@@ -7,14 +7,9 @@ from oracle import chunks as ochunks
 
 
 def _product():
-    # the controller module has no dependency on the HIP library
-    import importlib.util
-    import os
-    path = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2602_01872_amd", "controller.py")
-    spec = importlib.util.spec_from_file_location("grp_controller", path)
-    mod = importlib.util.module_from_spec(spec)
-    spec.loader.exec_module(mod)
-    return mod
+    # the controller calls are host arithmetic: they need the built library but no GPU
+    from paper_2602_01872_amd import controller
+    return controller
 
 
 @pytest.mark.parametrize("c", [1, 2, 3, 5, 8])
@@ -40,3 +35,28 @@ def test_controller_decisions_match_the_oracle(total, c, thr, pat):
         assert a.end_epoch() == b.end_epoch()
         assert a.super_epoch == b.super_epoch
         assert a.pairs() == b.pairs()
+
+
+def test_observe_stats_derives_the_factor_from_the_records():
+    mod = _product()
+    from paper_2602_01872_amd import binding
+    a = mod.Controller(10, 3, 0.4, 2)
+    b = ochunks.Controller(10, 3, 0.4, 2)
+    rng = np.random.default_rng(5)
+    for epoch in range(12):
+        for _ in range(3):
+            rec = np.zeros(2, dtype=binding.STATS_DTYPE)
+            rec["S"] = rng.integers(0, 50, size=2)
+            rec["sum_ratio"] = rng.uniform(0.0, 1.0, size=2) * rec["S"]
+            a.observe_stats(rec)
+            b.observe_step([float(r["sum_ratio"]) / int(r["S"]) if int(r["S"]) > 0 else 1.0 for r in rec])
+        assert a.end_epoch() == b.end_epoch()
+        assert a.super_epoch == b.super_epoch
+
+
+def test_sweep_chunk_and_super_epoch_length_reject_bad_arguments():
+    from paper_2602_01872_amd import binding
+    lib = binding.load()
+    assert lib.grp_sweep_chunk(0, 0, 0) == -1 and lib.grp_sweep_chunk(3, 0, 3) == -1 and lib.grp_sweep_chunk(0, -1, 3) == -1
+    assert lib.grp_super_epoch_epochs(-1, 3) == -1 and lib.grp_super_epoch_epochs(5, 0) == -1
+    assert lib.grp_super_epoch_epochs(10, 4) == 4 and lib.grp_super_epoch_epochs(0, 4) == 1 and lib.grp_super_epoch_epochs(7, 1) == 7

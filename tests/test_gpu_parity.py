@@ -435,6 +435,43 @@ def test_aggregate_invariants(g):
         assert rel_err(upd.cpu().numpy(), G) <= TOL_FP32
 
 
+@pytest.mark.parametrize("K,P", [(4, 4680), (13, 1001), (256, 20624), (9, 3)])
+def test_aggregate_over_separately_owned_buffers(g, K, P):
+    """grp_aggregate_ptrs: K gradient buffers of their own (some deliberately misaligned) against the oracle, and
+    bit for bit against the slab form on the same values."""
+    _note(f"aggregate_ptrs K={K} P={P}")
+    vals = synth.normal_matrix(K, P, 12)
+    aligned = [vals[p].clone().to(DEV) for p in range(K)]
+    odd = []
+    for p in range(K):                                      # every other buffer starts 4 bytes off a 16-byte boundary
+        buf = torch.zeros(P + 4, device=DEV)
+        view = buf[1:P + 1] if p % 2 else buf[:P]
+        view.copy_(vals[p])
+        odd.append(view)
+    recs = np.zeros(K, dtype=g.STATS_DTYPE)
+    recs["S"] = 100 + np.arange(K)
+    recs["sum_ratio"] = np.linspace(3.0, 90.0, K)
+    recs["R"] = np.arange(K) * 3.0
+    stats = torch.from_numpy(recs.view(np.uint8)).to(DEV)
+    ost = [dict(S=int(r["S"]), sum_ratio=float(r["sum_ratio"]), R=float(r["R"])) for r in recs]
+    og = [vals[p].double().numpy() for p in range(K)]
+    ld = (P + 3) // 4 * 4
+    slab = torch.zeros(K, ld, device=DEV)
+    slab[:, :P] = vals.to(DEV)
+    for variant in (0, 2, 3):
+        want = torch.zeros(P, device=DEV)
+        g.grp_aggregate(slab, ld, stats, K, P, variant, want)
+        G, oc = ocov.aggregate(og, ost, variant)
+        for bufs in (aligned, odd):
+            upd = torch.full((P,), float("nan"), device=DEV)
+            c = torch.zeros(K, device=DEV)
+            keep = g.grp_aggregate_ptrs(bufs, stats, P, variant, upd, c)
+            torch.cuda.synchronize()
+            assert rel_err(upd.cpu().numpy(), G) <= TOL_FP32 and rel_err(c.cpu().numpy(), oc) <= TOL_FP32
+            assert torch.equal(upd, want)
+            del keep
+
+
 @pytest.mark.gpu
 def test_partition_that_keeps_far_more_edges_than_a_random_one(g):
     """Every edge lies inside partition 0 (a graph drawn on its nodes only), so the one-pass build's key

@@ -101,6 +101,39 @@ def test_controller_schedule():
     assert ctl.super_epoch == 1 and ctl.pairs() == chunks.sweep_schedule(3)[1]
 
 
+@pytest.mark.parametrize("c", [2, 3, 4, 7, 12])
+def test_every_pair_of_chunks_shares_a_partition_within_a_cycle(c):
+    """The coverage guarantee, by brute force over the controller's own schedule: walking the controller through
+    c - 1 super-epochs (one epoch each), every unordered pair of distinct chunks must have been base + swept of
+    some worker, and no worker ever sweeps its own base chunk."""
+    ctl = chunks.Controller(total_epochs=c - 1, n_chunks=c)
+    assert ctl.epochs_per_super_epoch == 1
+    seen = set()
+    for t in range(c - 1):
+        pairs = ctl.pairs()
+        assert [b for b, _ in pairs] == list(range(c))
+        assert all(b != s for b, s in pairs)
+        seen |= {frozenset(p) for p in pairs}
+        assert ctl.end_epoch() and ctl.super_epoch == t + 1
+    assert seen == {frozenset((a, b)) for a in range(c) for b in range(a + 1, c)}
+
+
+def test_controller_switch_points_worked_by_hand():
+    """10 epochs over 4 chunks: ceil(10 / 3) = 4 epochs per super-epoch, so the switches fall after epochs 4 and 8
+    (1-based); 7 epochs over 3 chunks: ceil(7 / 2) = 4: after epoch 4; a single chunk never divides by zero and
+    switches every total_epochs epochs.  With patience 2 and threshold 0.25, deficits 0.3, 0.3 switch at the end
+    of that epoch, 0.3, 0.2, 0.3 do not."""
+    ctl = chunks.Controller(total_epochs=10, n_chunks=4)
+    assert [e + 1 for e in range(10) if ctl.end_epoch()] == [4, 8]
+    ctl = chunks.Controller(total_epochs=7, n_chunks=3)
+    assert [e + 1 for e in range(7) if ctl.end_epoch()] == [4]
+    ctl = chunks.Controller(total_epochs=5, n_chunks=1)
+    assert ctl.epochs_per_super_epoch == 5 and ctl.pairs() == [(0, 0)]
+    ctl = chunks.Controller(total_epochs=100, n_chunks=5, threshold=0.25, patience=2)
+    ctl.observe_step([0.7]); ctl.observe_step([0.6, 0.8]); assert ctl.end_epoch()          # deficits 0.3, 0.3
+    ctl.observe_step([0.7]); ctl.observe_step([0.8]); ctl.observe_step([0.7]); assert not ctl.end_epoch()   # 0.3, 0.2, 0.3
+
+
 def test_assigned_chunks_generalise_the_random_split():
     """A caller-supplied assignment equal to the random split gives the same partitions; a contiguous
     range assignment (what a locality-preserving partitioner returns) is checked by brute force."""
