@@ -545,7 +545,7 @@ def run_evidence_workload(args, g, synth, torch, dev):
                dtype="f32 (input features stored in bf16)" if wl in ("c3-step", "c5-step") else "f32",
                config={"workload": f"{wl}: dims {dims}, R-MAT scale {scale}, n={n}, nnz={nnz}, edges used per step {used}"
                                    + (f", + shrinkage aggregation of {K_agg} gradients" if K_agg > 1 else ""),
-                       "params": P, "small": bool(args.small)},
+                       "params": P, "small": bool(args.small), "sliced_schedule": not args.no_slices},
                edge_traversals_per_s=used / dt * (2 * k_layers - 1),
                roofline=_roofline(kernels, traffic), spmm=_spmm_table(kernels, traffic), kernels=kernels)
     if wl == "c5-step" and not args.no_cpu_baseline:
@@ -605,6 +605,9 @@ def main():
                     help="c5-step (default) is the headline workload, the largest configuration at its stated size; "
                          "c2-step is the second configuration, the others are evidence runs (each prints one JSON "
                          "line of the same form)")
+    ap.add_argument("--no-slices", action="store_true",
+                    help="build the partitions without the source-sliced schedule of their long rows (the aggregation then "
+                         "walks them in 512-edge chunks, row by row): the reference point of the schedule's effect")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for hardware byte counters)")
     args = ap.parse_args()
@@ -622,6 +625,8 @@ def main():
     g.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.no_slices:
+        g.grp_set_slice_min_nodes(1 << 62)
     if args.workload != "c2-step":
         run_evidence_workload(args, g, synth, torch, dev)
         return
