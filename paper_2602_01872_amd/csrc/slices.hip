@@ -36,14 +36,14 @@ static __device__ __forceinline__ int64_t lower_bound_idx(const int32_t* __restr
 
 // One wavefront per long row.  Lane s finds where the row's sources enter slice s; the row is then cut at such a
 // boundary wherever the piece before it has reached SLICE_MIN_PIECE edges (a row of 600 edges is not worth 64
-// pieces of 9: a piece costs a partial row and ~200 instructions), and every piece into tasks of at most
+// pieces of 9: a piece costs a partial row and ~200 instructions; see the measurements beside the constant), and every piece into tasks of at most
 // SLICE_PIECE edges.  A task's key is the slice of its first edge.  EMIT = false: the row's number of tasks.
 // EMIT = true: its task records (row-major numbering from row_task[j]) and their keys.
 template <bool EMIT>
 __global__ __launch_bounds__(256) void slice_rows_kernel(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx,
                                                          const int32_t* __restrict__ long_row, int64_t n_long, int shift,
-                                                         int64_t* __restrict__ row_tasks, SliceTask* __restrict__ recs,
-                                                         uint8_t* __restrict__ keys) {
+                                                         int min_piece, int64_t* __restrict__ row_tasks,
+                                                         SliceTask* __restrict__ recs, uint8_t* __restrict__ keys) {
     __shared__ int64_t cut_s[4][SLICES + 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t j = (int64_t)blockIdx.x * 4 + wave;
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void slice_rows_kernel(const int64_t* __restri
     int from_slice = 0;
     for (int s = 1; s <= SLICES; ++s) {                        // the same walk in every lane
         const int64_t at = cut_s[wave][s];
-        const bool close = s == SLICES || at - from >= SLICE_MIN_PIECE;
+        const bool close = s == SLICES || at - from >= min_piece;
         if (!close) continue;
         const int64_t nt = (at - from + SLICE_PIECE - 1) / SLICE_PIECE;
         if (EMIT) {
@@ -94,13 +94,14 @@ grp_status build_slice_tasks(const int64_t* ptr, const int32_t* idx, int64_t n, 
     int shift = 0;
     while (((n - 1) >> shift) >= SLICES) ++shift;
     const int64_t n_long = lr->n_long;
+    const int min_piece = SLICE_MIN_PIECE;
     int64_t* row_task = nullptr;
     GRP_HIP(hipMalloc((void**)&row_task, (size_t)(n_long + 1) * sizeof(int64_t)));
     auto fail_free = [&](grp_status s) { (void)hipFree(row_task); return s; };
     GRP_HIP(hipMemsetAsync(row_task + n_long, 0, sizeof(int64_t), st));
     const unsigned grid = (unsigned)cdiv(n_long, 4);
-    hipLaunchKernelGGL(slice_rows_kernel<false>, dim3(grid), dim3(256), 0, st, ptr, idx, lr->long_row, n_long, shift, row_task,
-                       (SliceTask*)nullptr, (uint8_t*)nullptr);
+    hipLaunchKernelGGL(slice_rows_kernel<false>, dim3(grid), dim3(256), 0, st, ptr, idx, lr->long_row, n_long, shift, min_piece,
+                       row_task, (SliceTask*)nullptr, (uint8_t*)nullptr);
     {
         size_t need = 0;
         if (rocprim::exclusive_scan(nullptr, need, row_task, row_task, (int64_t)0, (size_t)(n_long + 1), rocprim::plus<int64_t>(), st) != hipSuccess)
@@ -132,8 +133,8 @@ grp_status build_slice_tasks(const int64_t* ptr, const int32_t* idx, int64_t n, 
             status = fail(GRP_ENOMEM, "slice schedule: %lld task records", (long long)n_tasks);
             break;
         }
-        hipLaunchKernelGGL(slice_rows_kernel<true>, dim3(grid), dim3(256), 0, st, ptr, idx, lr->long_row, n_long, shift, row_task,
-                           recs, keys);
+        hipLaunchKernelGGL(slice_rows_kernel<true>, dim3(grid), dim3(256), 0, st, ptr, idx, lr->long_row, n_long, shift, min_piece,
+                           row_task, recs, keys);
         size_t need = 0;
         if (rocprim::radix_sort_pairs(nullptr, need, keys, keys_out, recs, sorted, (size_t)n_tasks, 0u, 6u, st) != hipSuccess ||
             hipMalloc(&tmp, need ? need : 4) != hipSuccess) {

@@ -264,8 +264,8 @@ __global__ __launch_bounds__(256) void spmm_combine_kernel(const int32_t* __rest
 }
 
 // ---- the source-sliced schedule of the long rows (slices.hip): one wavefront per task.
-// A task is at most SLICE_PIECE = 128 consecutive edges of one long row whose sources lie in one slice of the
-// node ids.  The wavefront reads the task's indices with one coalesced load (two per lane), its 64 / G groups
+// A task is at most SLICE_PIECE consecutive edges of one long row whose sources lie in one slice of the
+// node ids.  The wavefront reads the task's indices with coalesced loads (SLICE_PIECE / 64 per lane), its 64 / G groups
 // take consecutive runs of them (handed round with shuffles, up to four gathers in flight per group), the
 // groups' sums are added across the wavefront in a fixed butterfly, and the first group writes the partial row.
 // VW consecutive elements of a row as floats: the unit a lane owns (16 bytes of fp32, 8 or 16 bytes of bf16).
@@ -301,7 +301,8 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
                                                          const XT* __restrict__ X, int64_t ldx,
                                                          const float* __restrict__ colscale, float* __restrict__ partials,
                                                          int64_t ld_part) {
-    static_assert(SLICE_PIECE == 128, "two indices per lane");
+    constexpr int IPL = SLICE_PIECE / 64;                 // indices of a task per lane
+    static_assert(IPL * 64 == SLICE_PIECE && (IPL & (IPL - 1)) == 0, "a task's indices fill whole registers");
     constexpr int NG = 64 / G;
     constexpr int U = (G * VW >= 64 && NJ == 1) ? 8 : 4;   // gathers in flight per group (measured: 8 loses for narrower rows)
     const int lane = threadIdx.x & 63;
@@ -317,18 +318,22 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
     // Every load below is unconditional (an index past a task's end is clamped to its last edge and the gathered
     // row then dropped by a select): a conditional load becomes a branch with a wait behind it, and the gathers
     // of a task would no longer overlap.
-    auto load_indices = [&](const SliceTask& tk, int32_t& a, int32_t& b, float& wa, float& wb) {
+    auto load_indices = [&](const SliceTask& tk, int32_t (&ix)[IPL], float (&wx)[IPL]) {
         const int last = (int)tk.len > 0 ? (int)tk.len - 1 : 0;
-        const int64_t ea = tk.begin + (lane < last ? lane : last), eb = tk.begin + (64 + lane < last ? 64 + lane : last);
-        a = idx[ea];
-        b = idx[eb];
-        if (EV) { wa = val[ea]; wb = val[eb]; }
+#pragma unroll
+        for (int q = 0; q < IPL; ++q) {
+            const int64_t e = tk.begin + (64 * q + lane < last ? 64 * q + lane : last);
+            ix[q] = idx[e];
+            if (EV) wx[q] = val[e];
+        }
     };
     SliceTask cur = tasks[p0];
     SliceTask nxt = tasks[p0 + 1 < p_end ? p0 + 1 : p0];
-    int32_t i0, i1;
-    float w0 = 1.f, w1 = 1.f;
-    load_indices(cur, i0, i1, w0, w1);
+    int32_t ix[IPL];
+    float wx[IPL];
+#pragma unroll
+    for (int q = 0; q < IPL; ++q) wx[q] = 1.f;
+    load_indices(cur, ix, wx);
     int col[NJ];                                           // first column of the lane's unit in slab j (a dead unit reads column 0)
     bool live[NJ];
 #pragma unroll
@@ -346,8 +351,10 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
 #pragma unroll
             for (int q = 0; q < VW; ++q) acc[j][q] = 0.f;
         SliceTask nn = nxt;
-        int32_t n0 = 0, n1 = 0;
-        float nw0 = 1.f, nw1 = 1.f;
+        int32_t nix[IPL];
+        float nwx[IPL];
+#pragma unroll
+        for (int q = 0; q < IPL; ++q) { nix[q] = 0; nwx[q] = 1.f; }
         for (int k0 = 0; k0 < per; k0 += U) {
             int64_t c[U];
             float sc[U];
@@ -357,12 +364,22 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
                 const int pos = first + k0 + u;
                 on[u] = k0 + u < per && pos < len;
                 const int src = pos & 63;
-                const int32_t a = __shfl(i0, src, 64), b = __shfl(i1, src, 64);
-                c[u] = (pos & 64) ? b : a;                 // a valid index of this task even where `on` is false
+                int32_t ci = __shfl(ix[0], src, 64);
+#pragma unroll
+                for (int q = 1; q < IPL; ++q) {
+                    const int32_t o = __shfl(ix[q], src, 64);
+                    ci = (pos >> 6) == q ? o : ci;
+                }
+                c[u] = ci;                                 // a valid index of this task even where `on` is false
                 sc[u] = 1.f;
                 if (EV) {
-                    const float wa = __shfl(w0, src, 64), wb = __shfl(w1, src, 64);
-                    sc[u] = (pos & 64) ? wb : wa;
+                    float wi = __shfl(wx[0], src, 64);
+#pragma unroll
+                    for (int q = 1; q < IPL; ++q) {
+                        const float o = __shfl(wx[q], src, 64);
+                        wi = (pos >> 6) == q ? o : wi;
+                    }
+                    sc[u] = wi;
                 }
                 if (CS) sc[u] *= colscale[c[u]];
             }
@@ -373,7 +390,7 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
                 for (int u = 0; u < U; ++u) LaneVec<XT, VW>::ld(X + c[u] * ldx + col[j], v[j][u]);
             if (k0 == 0) {                                 // behind the first gathers: what the next two tasks need
                 __builtin_amdgcn_sched_barrier(0);
-                load_indices(nxt, n0, n1, nw0, nw1);
+                load_indices(nxt, nix, nwx);
                 nn = tasks[p + 2 < p_end ? p + 2 : p];
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -402,8 +419,8 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
             }
         }
         cur = nxt; nxt = nn;
-        i0 = n0; i1 = n1;
-        if (EV) { w0 = nw0; w1 = nw1; }
+#pragma unroll
+        for (int q = 0; q < IPL; ++q) { ix[q] = nix[q]; if (EV) wx[q] = nwx[q]; }
     }
 }
 
