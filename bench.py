@@ -354,9 +354,10 @@ def run_evidence_workload(args, g, synth, torch, dev):
         theta = synth.model_weights("sage", dims, GRAPH_SEED, device=dev)
         epochs = max(1, args.steps // 10)
 
-        def timed_epochs(lanes):
+        def timed_epochs(lanes, graphs=False):
             tr = g.MiniBatchTrainer(parts, model, xs, ys, masks, theta, g.EST_SHRINKAGE, K_PARTS, 1024, (15, 10, 5), 7,
-                                    g.optimizer_desc(g.OPT_ADAM, lr=0.003), dropout_rate=0.5, dropout_seed=1, lanes=lanes)
+                                    g.optimizer_desc(g.OPT_ADAM, lr=0.003), dropout_rate=0.5, dropout_seed=1, lanes=lanes,
+                                    graphs=graphs)
             for _ in range(max(1, args.warmup // 3)):
                 tr.run_epoch()
             torch.cuda.synchronize()
@@ -367,13 +368,18 @@ def run_evidence_workload(args, g, synth, torch, dev):
             torch.cuda.synchronize()
             return tr, first, (time.perf_counter() - t0) / epochs
         tr, first, dt_one = timed_epochs(1)
-        tr, first, dt = timed_epochs(4)                      # four host threads, each with its stream and workspace
+        tr, first, dt_threads = timed_epochs(4)              # four host threads, each with its stream and workspace
+        losses_eager = tr.losses()
+        tr, first, dt = timed_epochs(8, graphs=True)         # one host thread replaying captured steps on eight streams
+        assert tr.losses() == losses_eager, "the captured steps must reproduce the uncaptured ones bit for bit"
         used = sum(int(g.read_stats(h)["nnz_used"].sum()) for h in tr.history[first:]) / epochs
         out.update(metric="sampled edges/s over one mini-batch epoch of all 8 partitions (fwd+bwd, aggregate, Adam)",
                    unit="edges/s", value=used / dt, ms_per_step=dt * 1e3, dtype="f32", steps=epochs,
                    config={"workload": f"c2-minibatch-epoch: SAGE-mean-3 {dims}, fanouts (15,10,5), 1024 seeds per batch, "
                                        f"8 partitions of the R-MAT 2.4M-node / 62M-edge graph, {sum(tr.n_train)} training nodes",
-                           "ms_per_epoch": dt * 1e3, "ms_per_epoch_one_host_thread": dt_one * 1e3, "host_threads": 4,
+                           "ms_per_epoch": dt * 1e3, "launch": "captured steps (HIP graphs) replayed on 8 streams by one host thread",
+                           "ms_per_epoch_uncaptured_one_host_thread": dt_one * 1e3,
+                           "ms_per_epoch_uncaptured_four_host_threads": dt_threads * 1e3,
                            "iterations_per_epoch": tr.iters,
                            "train_steps_per_epoch": tr.iters * K_PARTS, "sampled_edges_per_epoch": used,
                            "losses_first_last": [tr.losses()[0], tr.losses()[-1]]},
@@ -537,6 +543,25 @@ def run_evidence_workload(args, g, synth, torch, dev):
             rec[p]["R"] = float(int(rec[0]["R"] * (0.75 + 0.0005 * int(spread[p]))))
         stats.copy_(torch.from_numpy(rec.view(np.uint8).copy()).to(dev))
     dt, dt_med = _timed_steps(torch, fn, args.warmup, args.steps)
+    dt_eager = dt
+    if wl == "c3-step":
+        # a chain of ~65 small launches: the host's launch cost bounds the uncaptured step, so the step is also
+        # captured once in a HIP graph and the replays are timed (the same work: nothing in the graph depends on
+        # the captured batch; a trainer rewrites the seed buffer and the device-resident batch id between replays)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        want = grads[0].clone()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fn()
+        dt_graph, dt_graph_med = _timed_steps(torch, graph.replay, args.warmup, args.steps)
+        assert torch.equal(grads[0], want), "the replayed step must reproduce the uncaptured one bit for bit"
+        if dt_graph < dt:
+            dt, dt_med = dt_graph, dt_graph_med
     kernels = _kernel_table(g, torch, fn, args.steps, detail=args.shapes)
     used = int(g.read_stats(stats)[0]["nnz_used"])
     k_layers = len(dims) - 1
@@ -545,7 +570,9 @@ def run_evidence_workload(args, g, synth, torch, dev):
                dtype="f32 (input features stored in bf16)" if wl in ("c3-step", "c5-step") else "f32",
                config={"workload": f"{wl}: dims {dims}, R-MAT scale {scale}, n={n}, nnz={nnz}, edges used per step {used}"
                                    + (f", + shrinkage aggregation of {K_agg} gradients" if K_agg > 1 else ""),
-                       "params": P, "small": bool(args.small), "sliced_schedule": not args.no_slices},
+                       "params": P, "small": bool(args.small), "sliced_schedule": not args.no_slices,
+                       **({"launch": "HIP graph replay" if dt < dt_eager else "uncaptured",
+                           "ms_per_step_uncaptured": dt_eager * 1e3} if wl == "c3-step" else {})},
                edge_traversals_per_s=used / dt * (2 * k_layers - 1),
                roofline=_roofline(kernels, traffic), spmm=_spmm_table(kernels, traffic), kernels=kernels)
     if wl == "c5-step" and not args.no_cpu_baseline:

@@ -257,6 +257,11 @@ typedef struct {
     float          dropout_rate;  /* in [0, 1); 0 = off (see below)                            */
     int32_t        reserved2;
     uint64_t       dropout_seed;
+    const uint64_t* batch_id_dev; /* DEV or NULL.  When set, batch_id above is ignored and the batch
+                                     id (of the sampler and of dropout) is read from this address
+                                     when the step's kernels run: a step captured in a HIP graph can
+                                     then be replayed as the next batch by writing the new id (and the
+                                     new seeds) into the same device buffers.                     */
 } grp_step_opts;
 
 /* Written to DEV memory by grp_train_step (one record per partition). */
@@ -266,7 +271,9 @@ typedef struct {
     double  R;           /* sum_{v in S} (d_global - d_local)|S_v|/d_local; full-graph:
                             sum (d_global - d_local), the number of dropped in-edges of S     */
     int64_t S;           /* nodes carrying loss                                               */
-    int64_t nnz_used;    /* edges processed (local edges, or edges of the sampled blocks)     */
+    int64_t nnz_used;    /* edges processed (local edges, or edges of the sampled blocks);
+                            negative: minus the number of seeds outside the partition, the
+                            record and the gradient of that step are invalid                  */
 } grp_step_stats;
 
 /* Bytes of caller-provided DEV workspace grp_train_step needs for this partition, model
@@ -310,9 +317,14 @@ grp_status grp_step_workspace_bytes(const grp_partition_t* part, const grp_model
  * the chosen edges keep their row order; layers are built from the seeds inwards (the seeds draw
  * fanouts[k-1]); the mean
  * of a layer divides by the number of sampled neighbours.  Fanouts must lie in [1, 64]; seeds
- * must be distinct (not checked) and lie in [0, n) (checked: GRP_ERANGE).  This mode synchronises the stream once per layer above the input layer
- * (the sampled block sizes are needed on the host); the workspace is sized from the seeds and
- * fanouts alone.
+ * must be distinct (not checked) and lie in [0, n).  This mode is as asynchronous as the full-graph
+ * one: the sizes of the sampled blocks stay on the device, every launch is sized by the upper bounds
+ * that follow from the seeds and fanouts (as is the workspace) and reads the real sizes from device
+ * memory, so a step may be queued behind earlier work or captured in a HIP graph (no memset nodes are
+ * recorded; a replay draws the same blocks unless the caller changes the seeds' contents, which are read
+ * on the device).  The price is that an invalid seed list cannot fail the call: a seed outside [0, n)
+ * is replaced by node 0 (no memory outside the partition is touched), and stats_out->nnz_used is set to
+ * minus the number of such seeds; the other results of that step are then meaningless.
  * Errors: GRP_EINVAL, GRP_EWORKSPACE, GRP_EUNSUPPORTED (mini-batch with a GCN arch; a
  * residual first layer on bf16 features), GRP_EHIP.                                    */
 grp_status grp_train_step(const grp_partition_t* part, const grp_model_desc* model,

@@ -173,6 +173,11 @@ struct SpmmArgs {
     int64_t ldy2 = 0;
     const float* val = nullptr;           // [nnz] per-edge multiplier of the gathered row, or null
     const float* rowscale = nullptr;      // [n_rows] a_i given explicitly (replaces `scale`), or null
+    // Sizes known on the device only (blocks sampled without a host round trip).  When set, n_rows and
+    // addend_rows above are upper bounds that size the launch (ptr must be valid, with empty rows, up to
+    // n_rows) and the kernels stop at the values stored here.
+    const int64_t* n_rows_dev = nullptr;
+    const int64_t* addend_rows_dev = nullptr;
 };
 grp_status launch_spmm(const SpmmArgs& a, hipStream_t st);
 size_t spmm_partials_bytes(const LongRows* lr, int32_t F);
@@ -213,6 +218,10 @@ struct GemmNNArgs {
     int64_t ldbt = 0;
     const float* Bt2 = nullptr;     // same for the second product
     int64_t ldbt2 = 0;
+    // Row counts known on the device only: when set, M (and a_valid_rows) above are upper bounds that
+    // size the launch, and the kernels read the real values here.
+    const int64_t* M_dev = nullptr;
+    const int64_t* a_valid_rows_dev = nullptr;
 };
 grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st);
 
@@ -239,6 +248,7 @@ struct GemmTNArgs {
     const float* B2 = nullptr;       // C2[K x N] = A^T B2[M x N]
     int64_t ldb2 = 0;
     float* C2 = nullptr;             // pitch ldc
+    const int64_t* M_dev = nullptr;  // when set: the real number of rows (on the device); M above is an upper bound
 };
 grp_status launch_gemm_tn(const GemmTNArgs& a, hipStream_t st);
 
@@ -280,15 +290,17 @@ struct DropoutPlan {
     uint32_t thresh = 0;
     float scale = 1.f;
     uint64_t seed = 0, batch_id = 0;
+    const uint64_t* batch_id_dev = nullptr;   // when set: the batch id is read on the device instead
 };
 DropoutPlan dropout_plan(const grp_step_opts* o);
 uint64_t dropout_layer_key(const DropoutPlan& d, int layer);
 grp_status launch_dropout(const DropoutPlan& d, int layer, const int64_t* l2g, int64_t n, int32_t F, float* H, int64_t ldh,
                           float* act, int64_t ld_act, const float* res, int64_t ld_res, hipStream_t st,
-                          const int32_t* node_of_row = nullptr /*row i is local node node_of_row[i] (null: i)*/);
+                          const int32_t* node_of_row = nullptr /*row i is local node node_of_row[i] (null: i)*/,
+                          const int64_t* n_dev = nullptr /*when set: the real row count (on the device), n an upper bound*/);
 // Y[i, :F] = rowscale[i] * X[i, :F] (whole 16-byte column groups)
 grp_status launch_scale_rows(const float* X, int64_t ldx, const float* rowscale, int64_t n, int32_t F, float* Y, int64_t ldy,
-                             hipStream_t st);
+                             hipStream_t st, const int64_t* n_dev = nullptr /*as for launch_dropout*/);
 // Y[i, :] = [X[i, :F] | 0 ...] up to the pitch ldy
 grp_status launch_pad_rows(const float* X, int64_t ldx, int64_t n, int32_t F, float* Y, int64_t ldy, hipStream_t st);
 // out[i] = in[i] * s
@@ -306,13 +318,15 @@ grp_status gat_step(const grp_partition_t* g, const grp_model_desc* m, const grp
 
 // Coverage statistics over the loss nodes and the weighted softmax cross-entropy.
 size_t stats_workspace_bytes(int64_t n);
-// nnz_used = nnz_const + the sum of the n_parts device counters nnz_parts[i][0].
+// nnz_used = nnz_const + the sum of the n_parts device counters nnz_parts[i][0]; or, when the device counter
+// *bad_seeds is set and positive, minus that count (the record of a step whose seed list was invalid).
 grp_status launch_stats(int64_t n_loss, const int32_t* loss_nodes /*null = 0..n-1 by mask*/,
                         const uint8_t* mask, const int32_t* d_local, const int64_t* d_global,
                         const int32_t* sampled_count /*null = full graph*/, int64_t nnz_const,
                         const int64_t* const* nnz_parts /*HOST array of device pointers*/, int n_parts,
                         void* scratch, grp_step_stats* out, hipStream_t st,
-                        const double* w_local = nullptr, const double* w_global = nullptr /*weight masses: full graph*/);
+                        const double* w_local = nullptr, const double* w_global = nullptr /*weight masses: full graph*/,
+                        const int64_t* bad_seeds = nullptr);
 grp_status launch_softmax_xent(int64_t n_rows, int32_t C, const float* Z, int64_t ldz,
                                const int32_t* labels, const int32_t* node_of_row /*null = row*/,
                                const uint8_t* mask, int32_t node_level,
@@ -361,10 +375,6 @@ __host__ __device__ __forceinline__ uint64_t mixM(uint64_t x) {
     return z ^ (z >> 31);
 }
 
-// 64 bytes of pinned host memory the device can write, one per host thread, kept until the process
-// ends (sizes a kernel reports to the host; read after synchronising the stream).  Null on failure.
-int64_t* host_mailbox();
-
 // ---------------------------------------------------------------- blocks and sampling (sampler.hip)
 // One bipartite message-passing layer.  Rows of `ptr/idx` are the layer's outputs
 // (destinations); `idx` indexes rows of the layer's input matrix.  The outputs are the first
@@ -382,6 +392,12 @@ struct Block {
     const int32_t* dst_nodes = nullptr;  // mini-batch: partition-local id of every destination row (null: row i is node i)
     const float* val = nullptr;          // weighted partitions: edge weights in ptr/idx order
     const float* valT = nullptr;         //                      and in ptrT/idxT order
+    // Sampled blocks: n_dst, n_in and nnz above are upper bounds (from the seeds and fanouts) that size the
+    // launches, and the real sizes live on the device (ptr and ptrT are valid up to the bounds: the rows
+    // past the real ones are empty).  Null for a block whose sizes the host knows (n_in_dev is also null for
+    // the input-side block, whose inputs are the partition's n nodes).
+    const int64_t* n_dst_dev = nullptr;
+    const int64_t* n_in_dev = nullptr;
 };
 
 struct SamplerBounds {                   // upper bounds per layer, from seeds and fanouts alone
@@ -393,10 +409,12 @@ size_t sampler_workspace_bytes(int64_t n, const SamplerBounds& b, int k);
 // Layer 0's idx holds partition-local node ids (rows of the feature matrix) and its self_rows
 // the destinations' ids; deeper layers are relabelled to block-local indices.  seeds_out
 // receives the device pointer of the seed list; nnz_parts_dev[k] the per-layer edge counts
-// (device).  Synchronises the stream once per layer above the input layer.
+// (device); *bad_seeds_dev the number of seeds outside [0, n) (device; such a seed is replaced by node 0).
+// Nothing here waits for the device: every launch is sized by the bounds and reads the real sizes from
+// device memory, so the whole step can be queued (or captured in a graph) at once.
 grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* opts, int k, void* ws, size_t ws_bytes,
                          Block* blocks, LongRows* long_bwd_store, const int64_t** nnz_parts_dev,
-                         const int32_t** seed_counts_dev, hipStream_t st);
+                         const int32_t** seed_counts_dev, const int64_t** bad_seeds_dev, hipStream_t st);
 grp_status sampler_block_view(const grp_partition_t* part, const grp_step_opts* o, int k, void* ws, size_t ws_bytes, int layer,
                               grp_block_view_t* out);
 }  // namespace grp

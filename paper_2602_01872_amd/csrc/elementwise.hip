@@ -86,6 +86,7 @@ DropoutPlan dropout_plan(const grp_step_opts* o) {
         d.scale = 1.0f / (1.0f - o->dropout_rate);
         d.seed = o->dropout_seed;
         d.batch_id = o->batch_id;
+        d.batch_id_dev = o->batch_id_dev;
     }
     return d;
 }
@@ -101,9 +102,14 @@ __global__ __launch_bounds__(256) void dropout_kernel(const int64_t* __restrict_
                                                       uint32_t thresh, float scale, float* __restrict__ H, int64_t ldh,
                                                       float* __restrict__ act, int64_t ld_act,
                                                       const float* __restrict__ res, int64_t ld_res,
-                                                      const int32_t* __restrict__ node_of_row) {
+                                                      const int32_t* __restrict__ node_of_row,
+                                                      const int64_t* __restrict__ n_dev, uint64_t seed, int layer,
+                                                      const uint64_t* __restrict__ batch_id_dev) {
+    if (batch_id_dev)                 // the layer's key from a batch id that lives on the device
+        key = sm64_mix(seed + (*batch_id_dev * (uint64_t)GRP_MAX_LAYERS + (uint64_t)layer + 1ull) * SM64_GAMMA);
     const int C4 = (F + 3) / 4;
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n_dev) n = *n_dev;            // the launch was sized by an upper bound
     if (e >= n * C4) return;
     const int64_t v = e / C4;
     const int f0 = 4 * (int)(e % C4);
@@ -136,7 +142,7 @@ __global__ __launch_bounds__(256) void dropout_kernel(const int64_t* __restrict_
 
 grp_status launch_dropout(const DropoutPlan& d, int layer, const int64_t* l2g, int64_t n, int32_t F, float* H, int64_t ldh,
                           float* act, int64_t ld_act, const float* res, int64_t ld_res, hipStream_t st,
-                          const int32_t* node_of_row) {
+                          const int32_t* node_of_row, const int64_t* n_dev) {
     if (!d.on || n <= 0) return GRP_OK;
     if (!l2g || !H || (act && !res)) return fail(GRP_EINVAL, "dropout: null argument");
     ProfScope ps("dropout", st, 0.0, 8.0 * n * F * (act ? 2 : 1));
@@ -147,10 +153,10 @@ grp_status launch_dropout(const DropoutPlan& d, int layer, const int64_t* l2g, i
     const uint64_t key = dropout_layer_key(d, layer);
     if (vec)
         hipLaunchKernelGGL(dropout_kernel<true>, dim3((unsigned)cdiv(work, 256)), dim3(256), 0, st, l2g, n, (int)F, key,
-                           d.thresh, d.scale, H, ldh, act, ld_act, res, ld_res, node_of_row);
+                           d.thresh, d.scale, H, ldh, act, ld_act, res, ld_res, node_of_row, n_dev, d.seed, layer, d.batch_id_dev);
     else
         hipLaunchKernelGGL(dropout_kernel<false>, dim3((unsigned)cdiv(work, 256)), dim3(256), 0, st, l2g, n, (int)F, key,
-                           d.thresh, d.scale, H, ldh, act, ld_act, res, ld_res, node_of_row);
+                           d.thresh, d.scale, H, ldh, act, ld_act, res, ld_res, node_of_row, n_dev, d.seed, layer, d.batch_id_dev);
     GRP_LAUNCH_CHECK();
     return GRP_OK;
 }
@@ -164,8 +170,10 @@ __global__ __launch_bounds__(256) void scale_copy_kernel(const float* __restrict
 // Y[i, :] = rowscale[i] * X[i, :] over c4 float4 columns (pitches multiples of 4, 16-byte aligned bases).
 __global__ __launch_bounds__(256) void scale_rows_kernel(const float* __restrict__ X, int64_t ldx,
                                                          const float* __restrict__ rowscale, int64_t n, int c4,
-                                                         float* __restrict__ Y, int64_t ldy) {
+                                                         float* __restrict__ Y, int64_t ldy,
+                                                         const int64_t* __restrict__ n_dev) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n_dev) n = *n_dev;            // the launch was sized by an upper bound
     if (e >= n * c4) return;
     const int64_t i = e / c4;
     const int c = 4 * (int)(e % c4);
@@ -176,13 +184,13 @@ __global__ __launch_bounds__(256) void scale_rows_kernel(const float* __restrict
 }
 
 grp_status launch_scale_rows(const float* X, int64_t ldx, const float* rowscale, int64_t n, int32_t F, float* Y, int64_t ldy,
-                             hipStream_t st) {
+                             hipStream_t st, const int64_t* n_dev) {
     if (n <= 0) return GRP_OK;
     const int c4 = (F + 3) / 4;
     if (ldx % 4 || ldy % 4 || ldx < 4 * c4 || ldy < 4 * c4 || (uintptr_t)X % 16 || (uintptr_t)Y % 16)
         return fail(GRP_EINVAL, "scale_rows: operands must be 16-byte friendly");
     ProfScope ps("scale_rows", st, 0.0, 8.0 * n * F);
-    hipLaunchKernelGGL(scale_rows_kernel, dim3((unsigned)cdiv(n * c4, 256)), dim3(256), 0, st, X, ldx, rowscale, n, c4, Y, ldy);
+    hipLaunchKernelGGL(scale_rows_kernel, dim3((unsigned)cdiv(n * c4, 256)), dim3(256), 0, st, X, ldx, rowscale, n, c4, Y, ldy, n_dev);
     GRP_LAUNCH_CHECK();
     return GRP_OK;
 }
@@ -419,6 +427,7 @@ __global__ __launch_bounds__(256) void stats_partial_kernel(int64_t n_rows, cons
 struct NnzParts {
     const int64_t* p[GRP_MAX_LAYERS];
     int n;
+    const int64_t* bad_seeds;      // null, or the number of seeds that were outside the partition
 };
 
 __global__ __launch_bounds__(256) void stats_final_kernel(const StatsPartial* __restrict__ part, int blocks,
@@ -442,6 +451,7 @@ __global__ __launch_bounds__(256) void stats_final_kernel(const StatsPartial* __
         out->S = s;
         int64_t nnz_used = nnz_const;
         for (int i = 0; i < np.n; ++i) nnz_used += np.p[i][0];
+        if (np.bad_seeds && *np.bad_seeds > 0) nnz_used = -*np.bad_seeds;
         out->nnz_used = nnz_used;
     }
 }
@@ -449,9 +459,10 @@ __global__ __launch_bounds__(256) void stats_final_kernel(const StatsPartial* __
 grp_status launch_stats(int64_t n_rows, const int32_t* nodes, const uint8_t* mask, const int32_t* d_local,
                         const int64_t* d_global, const int32_t* sampled_count, int64_t nnz_const,
                         const int64_t* const* nnz_parts, int n_parts, void* scratch, grp_step_stats* out, hipStream_t st,
-                        const double* w_local, const double* w_global) {
+                        const double* w_local, const double* w_global, const int64_t* bad_seeds) {
     NnzParts np;
     np.n = n_parts;
+    np.bad_seeds = bad_seeds;
     for (int i = 0; i < GRP_MAX_LAYERS; ++i) np.p[i] = i < n_parts ? nnz_parts[i] : nullptr;
     ProfScope ps("coverage_stats", st);
     StatsPartial* part = (StatsPartial*)scratch;

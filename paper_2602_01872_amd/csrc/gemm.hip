@@ -241,6 +241,10 @@ __device__ __forceinline__ void nn_epilogue(const GemmNNArgs& g, floatx16 (&acc)
 // ------------------------------------------------------------------------------- NN
 template <typename AT, bool VEC, int WM, int WN, int TM, int TN, int BK, int NBUF>
 __global__ __launch_bounds__(256) void gemm_nn_kernel(GemmNNArgs g) {
+    if (g.M_dev) {                                    // the launch was sized by upper bounds
+        g.M = *g.M_dev;
+        if (g.a_valid_rows_dev) g.a_valid_rows = *g.a_valid_rows_dev;
+    }
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int PA = BM + 2, PB = BN + 4;          // PA = 2 mod 8 spreads the transposing writes
     constexpr int A_REPS = BM * BK / 4 / 256;        // 4-element loads per thread for the A tile
@@ -477,6 +481,10 @@ __device__ __forceinline__ void nn_epilogue_interior(const GemmNNArgs& g, floatx
 // IRREG selects the variant with gathered (a_rows) or limited (a_valid_rows) A rows.
 template <typename AT, int WM, int WN, int TM, int TN, bool IRREG, int BKT, int NBUF>
 __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNNArgs g) {
+    if (g.M_dev) {                                    // the launch was sized by upper bounds
+        g.M = *g.M_dev;
+        if (g.a_valid_rows_dev) g.a_valid_rows = *g.a_valid_rows_dev;
+    }
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int PK = BKT + 4;
     constexpr int KQ = BKT / 4;                       // 16-byte slots per tile row
@@ -733,7 +741,7 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
             GRP_LAUNCH_CHECK();
             return GRP_OK;
         }
-        const bool rowlimit = a.a_rows != nullptr || (a.a_valid_rows > 0 && a.a_valid_rows < a.M);
+        const bool rowlimit = a.a_rows != nullptr || a.a_valid_rows_dev != nullptr || (a.a_valid_rows > 0 && a.a_valid_rows < a.M);
         int tile_n = n_eff > 96 ? 128 : n_eff > 64 ? 96 : 64;
         // A product whose 128-row tiles would leave half the chip idle (mini-batch blocks) is cut into
         // 64 x 64 tiles instead: four times the workgroups, each a quarter of the work.
@@ -829,6 +837,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
                                                       float* __restrict__ out, float* __restrict__ out2, int64_t out_ld,
                                                       int64_t out_split_stride, float* __restrict__ cs_out,
                                                       int64_t cs_split_stride) {
+    if (g.M_dev) g.M = *g.M_dev;                           // the launch (and `chunk`) were sized by an upper bound
     constexpr int BKA = WM * TM * 32, BN = WN * TN * 32;   // output tile: BKA (rows of C) x BN
     constexpr int PA = BKA + 4, PB = BN + 4;
     constexpr int QA = BKA / 4, QB = BN / 4;               // 16-byte slots per tile row

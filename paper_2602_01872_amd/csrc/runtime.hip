@@ -66,16 +66,6 @@ void prof_end(hipStream_t st) {
     g_open_end = nullptr;
 }
 
-int64_t* host_mailbox() {
-    static thread_local int64_t* box = nullptr;
-    if (!box) {
-        void* p = nullptr;
-        if (hipHostMalloc(&p, 64, hipHostMallocDefault) != hipSuccess) return nullptr;
-        box = (int64_t*)p;
-    }
-    return box;
-}
-
 }  // namespace grp
 
 extern "C" const char* grp_last_error(void) { return grp::g_err.c_str(); }

@@ -16,6 +16,12 @@
 // relabelled to block-local indices and the block is also stored transposed (by radix
 // sort) for the backward pass.  The input layer keeps partition-local ids: they index the
 // feature matrix directly, so no feature rows are copied.
+//
+// The host never learns a block's sizes.  They depend on the draws, so they exist on the device only
+// (`sizes`, four numbers per layer); every launch is sized by the upper bounds that follow from the seeds
+// and fanouts, reads the real sizes from device memory and leaves the slots between the two in a state
+// that is harmless to read (empty rows, sentinel keys).  A step is therefore queued without waiting for
+// the device, and can be captured in a graph.
 #include "common.h"
 
 #include <vector>
@@ -23,20 +29,24 @@
 namespace grp {
 
 constexpr int SAMPLE_MAX_FANOUT = 64;         // one lane of a wavefront per chosen edge
+// A layer's sizes on the device: destinations, sources (destinations first, then the newly reached nodes),
+// edges, newly reached nodes.
+enum { SZ_DST = 0, SZ_SRC = 1, SZ_NNZ = 2, SZ_NEW = 3, SZ_PER_LAYER = 4 };
 
 // Per destination row: the number of edges it keeps and 1 / max(that, 1); above the input layer also
 // the row's place in the block's source list (destinations come first, in order) and in the node -> block
-// index map.  Element n_dst of `cnt` closes the prefix sum.
+// index map.  The elements of `cnt` from n_dst to the bound are zero and close the prefix sum.
 __global__ __launch_bounds__(256) void sample_count_kernel(const int64_t* __restrict__ rowptr,
-                                                           const int32_t* __restrict__ dst_nodes, int64_t n_dst,
-                                                           int fanout, int64_t* __restrict__ cnt /*[n_dst+1]*/,
+                                                           const int32_t* __restrict__ dst_nodes,
+                                                           const int64_t* __restrict__ n_dst_dev, int64_t bound,
+                                                           int fanout, int64_t* __restrict__ cnt /*[bound+1]*/,
                                                            int32_t* __restrict__ cnt32 /*[n_dst] or null*/,
                                                            float* __restrict__ inv /*[n_dst]*/,
                                                            int32_t* __restrict__ mark /*[n] or null*/,
                                                            int32_t* __restrict__ src_nodes /*[>= n_dst] or null*/) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i > n_dst) return;
-    if (i == n_dst) { cnt[i] = 0; return; }
+    if (i > bound) return;
+    if (i >= *n_dst_dev) { cnt[i] = 0; return; }          // rows between the real count and the bound are empty
     const int32_t v = dst_nodes[i];
     const int64_t d = rowptr[v + 1] - rowptr[v];
     const int64_t c = d < fanout ? d : fanout;
@@ -49,11 +59,14 @@ __global__ __launch_bounds__(256) void sample_count_kernel(const int64_t* __rest
     }
 }
 
-// Seeds outside [0, n) are counted (pinned host memory, read by the host at its next synchronisation) and
-// replaced by node 0 in the copy the sampler works on, so that no kernel reads outside the partition.
+// Seeds outside [0, n) are counted (`bad`, zero on entry; the step's statistics report it) and replaced by
+// node 0 in the copy the sampler works on, so that no kernel reads outside the partition.  Also states the
+// seed-side block's number of destinations.
 __global__ __launch_bounds__(256) void check_seeds_kernel(const int32_t* __restrict__ seeds, int64_t n_seeds, int64_t n,
-                                                          int32_t* __restrict__ safe, int64_t* __restrict__ bad /*pinned*/) {
+                                                          int32_t* __restrict__ safe, int64_t* __restrict__ bad,
+                                                          int64_t* __restrict__ n_dst_out) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i == 0) *n_dst_out = n_seeds;
     if (i >= n_seeds) return;
     const int32_t v = seeds[i];
     const bool ok = v >= 0 && (int64_t)v < n;
@@ -70,11 +83,17 @@ __global__ __launch_bounds__(64 * SAMPLE_ROWS_PER_WG) void sample_select_kernel(
                                                                                 const int32_t* __restrict__ col,
                                                                                 const int64_t* __restrict__ l2g,
                                                                                 const int32_t* __restrict__ dst_nodes,
-                                                                                int64_t n_dst, int fanout, uint64_t h2,
+                                                                                int64_t* __restrict__ sizes /*of this layer*/,
+                                                                                int fanout, uint64_t h0 /*M(sampler_seed)*/,
+                                                                                uint64_t batch_id,
+                                                                                const uint64_t* __restrict__ batch_id_dev,
+                                                                                int layer,
                                                                                 const int64_t* __restrict__ out_ptr,
                                                                                 int32_t* __restrict__ out_idx) {
     const int lane = threadIdx.x & 63;
     const int64_t i = (int64_t)blockIdx.x * SAMPLE_ROWS_PER_WG + (threadIdx.x >> 6);
+    const int64_t n_dst = sizes[SZ_DST];
+    if (blockIdx.x == 0 && threadIdx.x == 0) sizes[SZ_NNZ] = out_ptr[n_dst];      // the block's number of edges
     if (i >= n_dst) return;                              // uniform over the wavefront
     const int64_t v = dst_nodes[i];
     const int64_t b = rowptr[v];
@@ -84,6 +103,7 @@ __global__ __launch_bounds__(64 * SAMPLE_ROWS_PER_WG) void sample_select_kernel(
         for (int64_t j = lane; j < d; j += 64) out_idx[o + j] = col[b + j];
         return;
     }
+    const uint64_t h2 = mixM(mixM(h0 ^ (batch_id_dev ? *batch_id_dev : batch_id)) ^ (uint64_t)layer);
     const uint64_t h3 = mixM(h2 ^ (uint64_t)l2g[v]);
     const uint64_t my_bits = mixM(h3 ^ (uint64_t)lane);
     int64_t mine = -1;                                   // lane t < fanout: the t-th element of the subset
@@ -114,14 +134,15 @@ __global__ __launch_bounds__(256) void flag_new_kernel(const int32_t* __restrict
 
 // Also clears the bitmap for the next layer.
 __global__ __launch_bounds__(256) void assign_new_kernel(int64_t n_words, uint32_t* __restrict__ bits,
-                                                         const int32_t* __restrict__ wpos, int64_t n_dst,
+                                                         const int32_t* __restrict__ wpos,
+                                                         const int64_t* __restrict__ n_dst_dev,
                                                          int32_t* __restrict__ mark, int32_t* __restrict__ src_nodes) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n_words) return;
     uint32_t w = bits[i];
     if (!w) return;
     bits[i] = 0;
-    int32_t p = (int32_t)n_dst + wpos[i];
+    int32_t p = (int32_t)*n_dst_dev + wpos[i];
     while (w) {
         const int32_t u = (int32_t)(i * 32) + (__ffs(w) - 1);
         src_nodes[p] = u;
@@ -130,17 +151,24 @@ __global__ __launch_bounds__(256) void assign_new_kernel(int64_t n_words, uint32
     }
 }
 
-// idx_blk[e] = block-local index of the source; keyT[e] = (source index << 32) | destination index
-__global__ __launch_bounds__(256) void relabel_kernel(const int64_t* __restrict__ ptr, int64_t n_dst,
-                                                      const int32_t* __restrict__ idx_local,
+// idx_blk[e] = block-local index of the source; keyT[e] = (source index << 32) | destination index.  The key
+// slots from the real number of edges to the bound receive `sentinel` (a source index above every real
+// one), so that the sort of the whole bound leaves them at the end.  Also completes the layer's sizes and
+// states the next layer's number of destinations (this layer's sources).
+__global__ __launch_bounds__(256) void relabel_kernel(const int64_t* __restrict__ ptr, int64_t* __restrict__ sizes,
+                                                      int64_t* __restrict__ next_n_dst, const int32_t* __restrict__ idx_local,
                                                       const int32_t* __restrict__ mark, int32_t* __restrict__ idx_blk,
-                                                      uint64_t* __restrict__ keyT, const int32_t* __restrict__ n_new,
-                                                      int64_t* __restrict__ mailbox /*pinned host memory*/,
-                                                      int64_t* __restrict__ sizes /*device copy, for later inspection*/) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) {           // the block's sizes, for the host
-        mailbox[0] = sizes[0] = ptr[n_dst];
-        mailbox[1] = sizes[1] = *n_new;
+                                                      uint64_t* __restrict__ keyT, int64_t nnz_bound, uint64_t sentinel,
+                                                      const int32_t* __restrict__ n_new) {
+    const int64_t n_dst = sizes[SZ_DST];
+    const int64_t nnz = sizes[SZ_NNZ];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        sizes[SZ_NEW] = *n_new;
+        sizes[SZ_SRC] = n_dst + *n_new;
+        *next_n_dst = n_dst + *n_new;
     }
+    for (int64_t e = nnz + (int64_t)blockIdx.x * 256 + threadIdx.x; e < nnz_bound; e += (int64_t)gridDim.x * 256)
+        keyT[e] = sentinel;
     const int64_t i = (int64_t)blockIdx.x * 4 + threadIdx.x / 64;
     if (i >= n_dst) return;
     const int lane = threadIdx.x & 63;
@@ -151,10 +179,10 @@ __global__ __launch_bounds__(256) void relabel_kernel(const int64_t* __restrict_
     }
 }
 
-__global__ __launch_bounds__(256) void clear_marks_kernel(const int32_t* __restrict__ src_nodes, int64_t n_src,
-                                                          int32_t* __restrict__ mark) {
+__global__ __launch_bounds__(256) void clear_marks_kernel(const int32_t* __restrict__ src_nodes,
+                                                          const int64_t* __restrict__ n_src_dev, int32_t* __restrict__ mark) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n_src) return;
+    if (i >= *n_src_dev) return;
     mark[src_nodes[i]] = 0;
 }
 
@@ -190,7 +218,8 @@ struct SamplerLayerBufs {
 struct SamplerBufs {
     SamplerLayerBufs L[GRP_MAX_LAYERS];
     int32_t* seeds;                     // [n_seeds] the caller's seeds, range-checked
-    int64_t* sizes;                     // [2 * GRP_MAX_LAYERS] per layer >= 1: edges of the block, newly reached nodes
+    int64_t* sizes;                     // [SZ_PER_LAYER * GRP_MAX_LAYERS] the blocks' real sizes (see the enum)
+    int64_t* bad;                       // [2] seeds outside the partition (carved just before `mark`: one fill clears all)
     int32_t* mark;                      // [n] block-local index + 1 of the current layer's nodes, else 0
     uint32_t* bits;                     // [n_words + 1] bitmap of newly reached nodes (the last word stays 0)
     int32_t* wpos;                      // [n_words + 1] set bits in the words before each word
@@ -204,7 +233,7 @@ static SamplerBufs carve_sampler(int64_t n, const SamplerBounds& b, int k, void*
     SamplerBufs s;
     Bump bump(ws, ws_bytes);
     int64_t max_nnz = 1, max_dst = 1;
-    s.sizes = bump.take<int64_t>(2 * GRP_MAX_LAYERS);
+    s.sizes = bump.take<int64_t>(SZ_PER_LAYER * GRP_MAX_LAYERS);
     s.seeds = bump.take<int32_t>((size_t)b.dst[k - 1]);
     for (int l = 0; l < k; ++l) {
         SamplerLayerBufs& L = s.L[l];
@@ -236,6 +265,7 @@ static SamplerBufs carve_sampler(int64_t n, const SamplerBounds& b, int k, void*
             L.lr_cap_long = L.lr_cap_chunks = 0;
         }
     }
+    s.bad = bump.take<int64_t>(2);
     s.mark = bump.take<int32_t>((size_t)n);
     s.n_words = cdiv(n, 32);
     s.bits = bump.take<uint32_t>((size_t)s.n_words + 1);
@@ -255,9 +285,10 @@ static unsigned blocks_for(int64_t work) { return (unsigned)cdiv(work > 0 ? work
 
 grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, int k, void* ws, size_t ws_bytes,
                          Block* blocks, LongRows* long_bwd_store, const int64_t** nnz_parts_dev,
-                         const int32_t** seed_counts_dev, hipStream_t st) {
+                         const int32_t** seed_counts_dev, const int64_t** bad_seeds_dev, hipStream_t st) {
     const int64_t n = part->n;
     if (o->n_seeds < 1 || !o->seeds) return fail(GRP_EINVAL, "mini-batch: need at least one seed node");
+    if (n == 0) return fail(GRP_ERANGE, "mini-batch: seeds given for a partition without nodes");
     for (int l = 0; l < k; ++l)
         if (o->fanouts[l] < 1 || o->fanouts[l] > SAMPLE_MAX_FANOUT)
             return fail(GRP_EINVAL, "mini-batch: fanout %d outside [1, %d]", o->fanouts[l], SAMPLE_MAX_FANOUT);
@@ -266,97 +297,90 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
     SamplerBufs s = carve_sampler(n, bd, k, ws, ws_bytes);
     if (s.total > ws_bytes) return fail(GRP_EWORKSPACE, "mini-batch: sampler workspace %zu < %zu", ws_bytes, s.total);
 
-    if (k > 1) {        // the node map and the bitmap start at zero (carved back to back: one fill covers both)
-        char* const lo = (char*)s.mark;
-        char* const hi = (char*)(s.bits + s.n_words + 1);
+    {   // the bad-seed counter and, with more than one layer, the node map and the bitmap start at zero
+        // (carved back to back: one fill covers them)
+        char* const lo = (char*)s.bad;
+        char* const hi = k > 1 ? (char*)(s.bits + s.n_words + 1) : (char*)(s.bad + 2);
         GRP_TRY(launch_fill_zero(lo, (size_t)(hi - lo), st));
     }
-    int64_t* const mailbox = host_mailbox();
-    if (!mailbox) return fail(GRP_EHIP, "mini-batch: no pinned host memory for the block sizes");
-    if (n == 0) return fail(GRP_ERANGE, "mini-batch: seeds given for a partition without nodes");
-    mailbox[2] = 0;
     hipLaunchKernelGGL(check_seeds_kernel, dim3(blocks_for(o->n_seeds)), dim3(256), 0, st, o->seeds, (int64_t)o->n_seeds, n,
-                       s.seeds, mailbox + 2);
+                       s.seeds, s.bad, s.sizes + SZ_PER_LAYER * (k - 1) + SZ_DST);
     GRP_LAUNCH_CHECK();
-    if (k == 1) {                                        // no later round trip would report the count
-        GRP_HIP(hipStreamSynchronize(st));
-        if (mailbox[2]) return fail(GRP_ERANGE, "mini-batch: %lld seeds outside [0, %lld)", (long long)mailbox[2], (long long)n);
-    }
-    const uint64_t h1 = mixM(mixM(o->sampler_seed) ^ o->batch_id);
+    *bad_seeds_dev = s.bad;
+    const uint64_t h0 = mixM(o->sampler_seed);
     const int32_t* dst_nodes = s.seeds;
-    int64_t n_dst = o->n_seeds;
     for (int l = k - 1; l >= 0; --l) {
         SamplerLayerBufs& L = s.L[l];
+        int64_t* const D = s.sizes + SZ_PER_LAYER * l;   // this layer's sizes; D[SZ_DST] is already there
+        const int64_t dst_bound = bd.dst[l];
         const int f = o->fanouts[l];
-        hipLaunchKernelGGL(sample_count_kernel, dim3(blocks_for(n_dst + 1)), dim3(256), 0, st, part->rowptr, dst_nodes, n_dst,
-                           f, L.cnt, L.cnt32, L.inv_in, l > 0 ? s.mark : nullptr, l > 0 ? L.src_nodes : nullptr);
+        hipLaunchKernelGGL(sample_count_kernel, dim3(blocks_for(dst_bound + 1)), dim3(256), 0, st, part->rowptr, dst_nodes,
+                           (const int64_t*)(D + SZ_DST), dst_bound, f, L.cnt, L.cnt32, L.inv_in, l > 0 ? s.mark : nullptr,
+                           l > 0 ? L.src_nodes : nullptr);
         GRP_LAUNCH_CHECK();
-        GRP_TRY(exclusive_scan_i64(s.scan_tmp, s.scan_bytes, L.cnt, L.ptr, n_dst + 1, st));
+        GRP_TRY(exclusive_scan_i64(s.scan_tmp, s.scan_bytes, L.cnt, L.ptr, dst_bound + 1, st));
         {
             ProfScope ps("sample_select", st);
-            hipLaunchKernelGGL(sample_select_kernel, dim3((unsigned)cdiv(n_dst, SAMPLE_ROWS_PER_WG)), dim3(64 * SAMPLE_ROWS_PER_WG),
-                               0, st, part->rowptr, part->col, part->l2g, dst_nodes, n_dst, f, mixM(h1 ^ (uint64_t)l),
-                               (const int64_t*)L.ptr, L.idx_local);
+            hipLaunchKernelGGL(sample_select_kernel, dim3((unsigned)cdiv(dst_bound, SAMPLE_ROWS_PER_WG)),
+                               dim3(64 * SAMPLE_ROWS_PER_WG), 0, st, part->rowptr, part->col, part->l2g, dst_nodes, D, f,
+                               h0, (uint64_t)o->batch_id, o->batch_id_dev, l, (const int64_t*)L.ptr, L.idx_local);
             GRP_LAUNCH_CHECK();
         }
 
         Block& B = blocks[l];
-        B.n_dst = n_dst;
+        B.n_dst = dst_bound;
+        B.n_dst_dev = D + SZ_DST;
+        B.nnz = bd.nnz[l];
         B.dst_nodes = dst_nodes;
         B.ptr = L.ptr;
         B.inv_in = L.inv_in;
         B.long_fwd = nullptr;                            // rows hold at most `fanout` edges
-        nnz_parts_dev[l] = L.ptr + n_dst;
+        nnz_parts_dev[l] = D + SZ_NNZ;
         if (l == k - 1) *seed_counts_dev = L.cnt32;
         if (l == 0) {
             B.idx = L.idx_local;
             B.n_in = n;
+            B.n_in_dev = nullptr;                        // the inputs are the partition's nodes
             B.self_rows = dst_nodes;
             B.ptrT = nullptr; B.idxT = nullptr; B.long_bwd = nullptr;
-            B.nnz = bd.nnz[0];                           // upper bound; only the profiler reads it
             break;
         }
         // new source nodes in ascending local id, block-local relabelling, transposed block
-        hipLaunchKernelGGL(flag_new_kernel, dim3(blocks_for(n_dst * f)), dim3(256), 0, st, (const int32_t*)L.idx_local,
-                           (const int64_t*)(L.ptr + n_dst), (const int32_t*)s.mark, s.bits);
+        const int64_t src_bound = bd.src[l], nnz_bound = bd.nnz[l];
+        hipLaunchKernelGGL(flag_new_kernel, dim3(blocks_for(nnz_bound)), dim3(256), 0, st, (const int32_t*)L.idx_local,
+                           (const int64_t*)(D + SZ_NNZ), (const int32_t*)s.mark, s.bits);
         GRP_LAUNCH_CHECK();
         GRP_TRY(exclusive_scan_popcount(s.scan_tmp, s.scan_bytes, s.bits, s.wpos, s.n_words + 1, st));
         hipLaunchKernelGGL(assign_new_kernel, dim3(blocks_for(s.n_words)), dim3(256), 0, st, s.n_words, s.bits,
-                           (const int32_t*)s.wpos, n_dst, s.mark, L.src_nodes);
+                           (const int32_t*)s.wpos, (const int64_t*)(D + SZ_DST), s.mark, L.src_nodes);
         GRP_LAUNCH_CHECK();
-        mailbox[0] = mailbox[1] = -1;
-        hipLaunchKernelGGL(relabel_kernel, dim3((unsigned)cdiv(n_dst, 4)), dim3(256), 0, st, (const int64_t*)L.ptr, n_dst,
-                           (const int32_t*)L.idx_local, (const int32_t*)s.mark, L.idx_blk, L.keys,
-                           (const int32_t*)(s.wpos + s.n_words), mailbox, s.sizes + 2 * l);
-        GRP_LAUNCH_CHECK();
-        GRP_HIP(hipStreamSynchronize(st));               // the one host round trip of the layer
-        if (mailbox[2]) return fail(GRP_ERANGE, "mini-batch: %lld seeds outside [0, %lld)", (long long)mailbox[2], (long long)n);
-        const int64_t host_nnz = mailbox[0];
-        const int64_t host_new = mailbox[1];
-        const int64_t n_src = n_dst + host_new;
-        if (host_nnz < 0 || host_new < 0) return fail(GRP_EHIP, "mini-batch: the block sizes did not reach the host");
-        if (host_nnz > bd.nnz[l] || n_src > bd.src[l]) return fail(GRP_EHIP, "mini-batch: sampled block exceeds its bounds");
-        hipLaunchKernelGGL(clear_marks_kernel, dim3(blocks_for(n_src)), dim3(256), 0, st, (const int32_t*)L.src_nodes, n_src,
-                           s.mark);
-        GRP_LAUNCH_CHECK();
+        // Keys are (source << 32 | destination); the unused slots up to the bound get the source index
+        // src_bound, which no real source reaches, and the sort covers the bits of that value.
         int bits = 1;
-        while (bits < 32 && ((int64_t)1 << bits) < n_src) ++bits;
-        GRP_TRY(sort_keys_u64(s.sort_tmp, s.sort_bytes, L.keys, L.keys_sorted, host_nnz, 32u + (unsigned)bits, st));
-        GRP_TRY(launch_csr_from_sorted_keys(L.keys_sorted, host_nnz, n_src, L.ptrT, L.idxT, st));
+        while (bits < 32 && ((int64_t)1 << bits) <= src_bound) ++bits;
+        hipLaunchKernelGGL(relabel_kernel, dim3((unsigned)cdiv(dst_bound, 4)), dim3(256), 0, st, (const int64_t*)L.ptr, D,
+                           s.sizes + SZ_PER_LAYER * (l - 1) + SZ_DST, (const int32_t*)L.idx_local, (const int32_t*)s.mark,
+                           L.idx_blk, L.keys, nnz_bound, (uint64_t)src_bound << 32, (const int32_t*)(s.wpos + s.n_words));
+        GRP_LAUNCH_CHECK();
+        hipLaunchKernelGGL(clear_marks_kernel, dim3(blocks_for(src_bound)), dim3(256), 0, st, (const int32_t*)L.src_nodes,
+                           (const int64_t*)(D + SZ_SRC), s.mark);
+        GRP_LAUNCH_CHECK();
+        GRP_TRY(sort_keys_u64(s.sort_tmp, s.sort_bytes, L.keys, L.keys_sorted, nnz_bound, 32u + (unsigned)bits, st));
+        // Over src_bound rows: those past the real sources come out empty (their pointer is the real number
+        // of edges, where the sentinels begin), and the entries of idxT past that number are never read.
+        GRP_TRY(launch_csr_from_sorted_keys(L.keys_sorted, nnz_bound, src_bound, L.ptrT, L.idxT, st));
         LongRows& lr = long_bwd_store[l];
         lr.long_row = L.lr_row; lr.long_first = L.lr_first; lr.chunk_begin = L.lr_cb; lr.chunk_end = L.lr_ce;
-        const int64_t cap_long = host_nnz / SPMM_LONG_ROW + 1;
-        const int64_t cap_chunks = host_nnz / SPMM_CHUNK + cap_long + 1;      // within L.lr_cap_*: host_nnz <= bd.nnz[l]
-        GRP_TRY(build_long_rows_device(L.ptrT, n_src, &lr, cap_long, cap_chunks, L.lr_scan, s.scan_tmp, s.scan_bytes, st));
+        GRP_TRY(build_long_rows_device(L.ptrT, src_bound, &lr, L.lr_cap_long, L.lr_cap_chunks, L.lr_scan, s.scan_tmp,
+                                       s.scan_bytes, st));
         B.idx = L.idx_blk;
-        B.n_in = n_src;
-        B.nnz = host_nnz;
+        B.n_in = src_bound;
+        B.n_in_dev = D + SZ_SRC;
         B.self_rows = nullptr;
         B.ptrT = L.ptrT;
         B.idxT = L.idxT;
         B.long_bwd = &lr;
         dst_nodes = L.src_nodes;
-        n_dst = n_src;
     }
     return GRP_OK;
 }
@@ -369,27 +393,25 @@ grp_status sampler_block_view(const grp_partition_t* part, const grp_step_opts* 
     sampler_bounds(part->n, o->n_seeds, o->fanouts, k, &bd);
     const SamplerBufs s = carve_sampler(part->n, bd, k, ws, ws_bytes);
     if (s.total > ws_bytes) return fail(GRP_EWORKSPACE, "grp_step_block: sampler workspace %zu < %zu", ws_bytes, s.total);
-    int64_t sizes[2 * GRP_MAX_LAYERS] = {0};
+    int64_t sizes[SZ_PER_LAYER * GRP_MAX_LAYERS] = {0};
     GRP_HIP(hipDeviceSynchronize());
-    if (k > 1) GRP_HIP(hipMemcpy(sizes, s.sizes, sizeof sizes, hipMemcpyDeviceToHost));
-    int64_t n_dst = o->n_seeds;
-    const int32_t* dst_nodes = s.seeds;
-    for (int l = k - 1; l > layer; --l) {                // walk down from the seed side
-        n_dst += sizes[2 * l + 1];
-        dst_nodes = s.L[l].src_nodes;
-    }
+    GRP_HIP(hipMemcpy(sizes, s.sizes, sizeof sizes, hipMemcpyDeviceToHost));
+    const int64_t* const D = sizes + SZ_PER_LAYER * layer;
     const SamplerLayerBufs& L = s.L[layer];
-    out->n_dst = n_dst;
+    if (D[SZ_DST] < 0 || D[SZ_DST] > bd.dst[layer] || D[SZ_NNZ] < 0 || D[SZ_NNZ] > bd.nnz[layer])
+        return fail(GRP_EINVAL, "grp_step_block: the workspace does not hold a step of this shape");
+    out->n_dst = D[SZ_DST];
+    out->nnz = D[SZ_NNZ];
     out->rowptr = L.ptr;
-    out->dst_nodes = dst_nodes;
+    out->dst_nodes = layer == k - 1 ? s.seeds : s.L[layer + 1].src_nodes;
     if (layer == 0) {
-        GRP_HIP(hipMemcpy(&out->nnz, L.ptr + n_dst, sizeof(int64_t), hipMemcpyDeviceToHost));
         out->n_src = part->n;
         out->col = L.idx_local;
         out->src_nodes = nullptr;
     } else {
-        out->nnz = sizes[2 * layer];
-        out->n_src = n_dst + sizes[2 * layer + 1];
+        if (D[SZ_SRC] < D[SZ_DST] || D[SZ_SRC] > bd.src[layer])
+            return fail(GRP_EINVAL, "grp_step_block: the workspace does not hold a step of this shape");
+        out->n_src = D[SZ_SRC];
         out->col = L.idx_blk;
         out->src_nodes = L.src_nodes;
     }

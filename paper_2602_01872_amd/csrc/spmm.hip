@@ -131,6 +131,8 @@ struct SpmmEpilogue {
     const float* mask;        // keep where mask > 0 (after the ReLU); null otherwise
     int64_t ld_mask;
     const float* rowscale;    // a_i given explicitly; null: from `scale` and the row length
+    const int64_t* n_rows_dev;       // when set: the real row count and the real addend_rows (device values;
+    const int64_t* addend_rows_dev;  //           the launch and addend_rows above are upper bounds)
 };
 
 template <typename XT>
@@ -139,7 +141,7 @@ __device__ __forceinline__ void finish_row(const SpmmEpilogue& ep, int64_t i, in
     const float a = ep.rowscale ? ep.rowscale[i] : row_scale(ep.scale, deg, ep.self_term);
     if (ep.self_term) add4(r, Vec4Load<XT>::ld(X + i * ldx + col));
     r.x *= a; r.y *= a; r.z *= a; r.w *= a;
-    if (ep.addend && i < ep.addend_rows) add4(r, *reinterpret_cast<const float4*>(ep.addend + i * ep.ld_add + col));
+    if (ep.addend && i < (ep.addend_rows_dev ? *ep.addend_rows_dev : ep.addend_rows)) add4(r, *reinterpret_cast<const float4*>(ep.addend + i * ep.ld_add + col));
     float o[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -222,7 +224,7 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(const int64_t* __restric
     }
     const int t = threadIdx.x % G;
     const int64_t i = (int64_t)(blockIdx.x - n_chunks) * ROWS + threadIdx.x / G;
-    if (i >= n_rows) return;          // whole groups leave together (G divides 64)
+    if (i >= (ep.n_rows_dev ? *ep.n_rows_dev : n_rows)) return;          // whole groups leave together (G divides 64)
     const int64_t b = ptr[i], e = ptr[i + 1];
     if (e - b > long_thr) return;     // its chunks are reduced above, the row is finished by the combine kernel
     float4 acc[NJ];
@@ -475,9 +477,10 @@ __global__ __launch_bounds__(256) void spmm_rows_scalar_kernel(
     const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx, int64_t n_rows, int F,
     const XT* __restrict__ X, int64_t ldx, int scale, int self_term, const float* __restrict__ colscale,
     const float* addend, int64_t ld_add, const float* __restrict__ bias, int relu,
-    float* Y, int64_t ldy, const float* __restrict__ val, const float* __restrict__ rowscale) {
+    float* Y, int64_t ldy, const float* __restrict__ val, const float* __restrict__ rowscale,
+    const int64_t* __restrict__ n_rows_dev /*when set: the real row count; n_rows sized the launch*/) {
     const int64_t i = (int64_t)blockIdx.x * 4 + threadIdx.x / 64;
-    if (i >= n_rows) return;
+    if (i >= (n_rows_dev ? *n_rows_dev : n_rows)) return;
     const int t = threadIdx.x % 64;
     const int64_t b = ptr[i], e = ptr[i + 1];
     const float a = rowscale ? rowscale[i] : row_scale(scale, e - b, self_term);
@@ -606,20 +609,20 @@ grp_status launch_spmm(const SpmmArgs& a, hipStream_t st) {
             return fail(GRP_EINVAL, "spmm: mask must be 16-byte aligned with a pitch multiple of 4");
         SpmmEpilogue ep{a.scale, a.self_term, a.relu, a.F, a.addend, a.ld_add, a.bias, a.Y, a.ldy,
                         a.residual, a.ld_res, a.Y2, a.ldy2, a.addend_rows > 0 ? a.addend_rows : a.n_rows, a.mask, a.ld_mask,
-                        a.rowscale};
+                        a.rowscale, a.n_rows_dev, a.addend_rows_dev};
         GRP_TRY(a.x_bf16 ? dispatch<__hip_bfloat16>(a, ep, st) : dispatch<float>(a, ep, st));
     } else {
-        if (a.residual || a.Y2 || a.mask || a.addend_rows > 0)
+        if (a.residual || a.Y2 || a.mask || a.addend_rows > 0 || a.addend_rows_dev)
             return fail(GRP_EUNSUPPORTED, "spmm: this epilogue needs 16-byte friendly operands");
         const int64_t blocks = cdiv(a.n_rows, 4);
         if (a.x_bf16)
             hipLaunchKernelGGL((spmm_rows_scalar_kernel<__hip_bfloat16>), dim3((unsigned)blocks), dim3(256), 0, st,
                                a.ptr, a.idx, a.n_rows, a.F, (const __hip_bfloat16*)a.X, a.ldx, a.scale,
-                               a.self_term, a.colscale, a.addend, a.ld_add, a.bias, a.relu, a.Y, a.ldy, a.val, a.rowscale);
+                               a.self_term, a.colscale, a.addend, a.ld_add, a.bias, a.relu, a.Y, a.ldy, a.val, a.rowscale, a.n_rows_dev);
         else
             hipLaunchKernelGGL((spmm_rows_scalar_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, st, a.ptr,
                                a.idx, a.n_rows, a.F, (const float*)a.X, a.ldx, a.scale, a.self_term, a.colscale, a.addend,
-                               a.ld_add, a.bias, a.relu, a.Y, a.ldy, a.val, a.rowscale);
+                               a.ld_add, a.bias, a.relu, a.Y, a.ldy, a.val, a.rowscale, a.n_rows_dev);
     }
     GRP_LAUNCH_CHECK();
     return GRP_OK;

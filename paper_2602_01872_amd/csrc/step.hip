@@ -190,6 +190,7 @@ static void fill_spmm(SpmmArgs& s, const Block& B, bool transposed, float* parti
     s.idx = transposed ? B.idxT : B.idx;
     s.nnz = B.nnz;
     s.n_rows = transposed ? B.n_in : B.n_dst;
+    s.n_rows_dev = transposed ? B.n_in_dev : B.n_dst_dev;
     s.n_src = transposed ? B.n_dst : B.n_in;
     s.long_rows = transposed ? B.long_bwd : B.long_fwd;
     s.partials = partials;
@@ -246,12 +247,12 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             s.F = fin; s.X = H; s.ldx = ldh; s.x_bf16 = h_bf16; set_mean(s, B); s.Y = L.M; s.ldy = ldp(fin);
             GRP_TRY(launch_spmm(s, st));
             GemmNNArgs a;
-            a.M = B.n_dst; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.a_rows = B.self_rows;
-            a.Bt = L.Wt_s; a.ldbt = L.ldwt;
+            a.M = B.n_dst; a.M_dev = B.n_dst_dev; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16;
+            a.a_rows = B.self_rows; a.Bt = L.Wt_s; a.ldbt = L.ldwt;
             a.K2 = fin; a.A2 = L.M; a.lda2 = ldp(fin); a.Bt2 = L.Wt_n; a.ldbt2 = L.ldwt;
             a.bias = theta + L.off_b; a.relu = relu; a.C = L.H_out; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
             GRP_TRY(launch_gemm_nn(a, st));
-        } else if (B.n_in == B.n_dst && !B.self_rows) {
+        } else if (B.n_in == B.n_dst && !B.self_rows && !B.n_dst_dev) {
             // [T | Z0] = H [Wn | Ws] (+ b on the second half) in one pass over H, then
             // H' = ReLU(mean-aggregate(T) + Z0)
             const int64_t w2 = 2 * ldp(fout);
@@ -267,10 +268,11 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             GRP_TRY(launch_spmm(s, st));
         } else {
             GemmNNArgs a;      // T = H Wn over every input row, Z0 = H_self Ws + b
-            a.M = B.n_in; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16; a.Bt = L.Wt_n; a.ldbt = L.ldwt;
+            a.M = B.n_in; a.M_dev = B.n_in_dev; a.N = fout; a.K = fin; a.A = H; a.lda = ldh; a.a_bf16 = h_bf16;
+            a.Bt = L.Wt_n; a.ldbt = L.ldwt;
             a.C = p.tmpA; a.ldc = ldp(fout); a.zero_pad_to = (int)ldp(fout);
             GRP_TRY(launch_gemm_nn(a, st));
-            a.M = B.n_dst; a.a_rows = B.self_rows; a.Bt = L.Wt_s; a.bias = theta + L.off_b; a.C = L.H_out;
+            a.M = B.n_dst; a.M_dev = B.n_dst_dev; a.a_rows = B.self_rows; a.Bt = L.Wt_s; a.bias = theta + L.off_b; a.C = L.H_out;
             GRP_TRY(launch_gemm_nn(a, st));
             SpmmArgs s;
             fill_spmm(s, B, false, p.partials);
@@ -278,7 +280,8 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             s.addend = L.H_out; s.ld_add = ldp(fout); s.relu = relu; s.Y = L.H_out; s.ldy = ldp(fout);
             GRP_TRY(launch_spmm(s, st));
         }
-        if (relu) GRP_TRY(launch_dropout(drop, l, g->l2g, B.n_dst, fout, L.H_out, ldp(fout), nullptr, 0, nullptr, 0, st, B.dst_nodes));
+        if (relu) GRP_TRY(launch_dropout(drop, l, g->l2g, B.n_dst, fout, L.H_out, ldp(fout), nullptr, 0, nullptr, 0, st, B.dst_nodes,
+                                          B.n_dst_dev));
         H = L.H_out; ldh = ldp(fout); h_bf16 = 0;
     }
 
@@ -300,11 +303,11 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
         const int64_t ldin = l == 0 ? m->dims[0] : ldp(fin);
         const int in_bf16 = l == 0 && m->feat_dtype == GRP_DTYPE_BF16;
         GemmTNArgs t;      // dW_self = H_self^T dZ, and db = 1^T dZ from the same pass over dZ
-        t.M = B.n_dst; t.K = fin; t.N = fout; t.A = Hin; t.lda = ldin; t.a_bf16 = in_bf16; t.a_rows = B.self_rows;
+        t.M = B.n_dst; t.M_dev = B.n_dst_dev; t.K = fin; t.N = fout; t.A = Hin; t.lda = ldin; t.a_bf16 = in_bf16; t.a_rows = B.self_rows;
         t.B = dZ; t.ldb = ldp(fout); t.C = grad + L.off_ws; t.ldc = fout; t.workspace = p.tn_ws; t.workspace_bytes = p.tn_ws_bytes;
         t.colsum_out = grad + L.off_b;
         // the same rows of the input feed both weight gradients of a transform-first layer
-        const bool shared_rows = !L.agg_first && B.n_in == B.n_dst && !B.self_rows;
+        const bool shared_rows = !L.agg_first && B.n_in == B.n_dst && !B.self_rows && !B.n_dst_dev;
         if (L.agg_first) {
             t.A2 = L.M; t.lda2 = ldp(fin); t.C2 = grad + L.off_wn;       // dW_neigh = M^T dZ in the same launch
             GRP_TRY(launch_gemm_tn(t, st));
@@ -318,7 +321,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
                 const int64_t w2 = 2 * ldp(fin);
                 if (B.n_dst > 0) {
                     GemmNNArgs a;
-                    a.M = B.n_dst; a.N = (int)(ldp(fin) + fin); a.K = fout; a.A = dZ; a.lda = ldp(fout);
+                    a.M = B.n_dst; a.M_dev = B.n_dst_dev; a.N = (int)(ldp(fin) + fin); a.K = fout; a.A = dZ; a.lda = ldp(fout);
                     a.Bt = L.Wp_n; a.ldbt = L.ldwp; a.rowscale = B.inv_in; a.rowscale_cols = (int)ldp(fin);
                     a.C = p.tmpA; a.ldc = w2; a.zero_pad_to = (int)w2;
                     GRP_TRY(launch_gemm_nn(a, st));
@@ -326,7 +329,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
                 SpmmArgs s;
                 fill_spmm(s, B, true, p.partials);
                 s.F = fin; s.X = p.tmpA; s.ldx = w2; s.addend = p.tmpA + ldp(fin); s.ld_add = w2;
-                s.addend_rows = B.n_dst; s.mask = p.L[l - 1].H_out; s.ld_mask = ldp(fin);
+                s.addend_rows = B.n_dst; s.addend_rows_dev = B.n_dst_dev; s.mask = p.L[l - 1].H_out; s.ld_mask = ldp(fin);
                 s.Y = dZ_other; s.ldy = ldp(fin);
                 GRP_TRY(launch_spmm(s, st));
             }
@@ -337,7 +340,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
             // The per-edge gather of 1/|N_v| costs a cache line per edge once that array outgrows the L2:
             // where a row has more edges than an eighth of its width it is cheaper to scale dZ's rows once.
             if (B.nnz > (int64_t)B.n_dst * fout / 8) {
-                GRP_TRY(launch_scale_rows(dZ, ldp(fout), B.inv_in, B.n_dst, fout, p.tmpB, ldp(fout), st));
+                GRP_TRY(launch_scale_rows(dZ, ldp(fout), B.inv_in, B.n_dst, fout, p.tmpB, ldp(fout), st, B.n_dst_dev));
                 s.X = p.tmpB;
                 s.colscale = nullptr;
             }
@@ -346,12 +349,13 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
                 t.B2 = p.tmpA; t.ldb2 = ldp(fout); t.C2 = grad + L.off_wn;
             } else {
                 t.colsum_out = nullptr;
-                t.M = B.n_in; t.a_rows = nullptr; t.B = p.tmpA; t.C = grad + L.off_wn;
+                t.M = B.n_in; t.M_dev = B.n_in_dev; t.a_rows = nullptr; t.B = p.tmpA; t.C = grad + L.off_wn;
             }
             GRP_TRY(launch_gemm_tn(t, st));
             if (l > 0 && B.n_in > 0) {
                 GemmNNArgs c;      // dZ_prev = mask * ([dZ Ws^T ; 0] + dT Wn^T)
-                c.M = B.n_in; c.N = fin; c.K = fout; c.A = dZ; c.lda = ldp(fout); c.a_valid_rows = B.n_dst;
+                c.M = B.n_in; c.M_dev = B.n_in_dev; c.N = fin; c.K = fout; c.A = dZ; c.lda = ldp(fout);
+                c.a_valid_rows = B.n_dst; c.a_valid_rows_dev = B.n_dst_dev;
                 c.Bt = L.Wp_s; c.ldbt = L.ldwp;
                 c.K2 = fout; c.A2 = p.tmpA; c.lda2 = ldp(fout); c.Bt2 = L.Wp_n; c.ldbt2 = L.ldwp;
                 c.mask = p.L[l - 1].H_out; c.ld_mask = ldp(fin);
@@ -559,8 +563,11 @@ extern "C" grp_status grp_train_step(const grp_partition_t* part, const grp_mode
     LongRows long_bwd[GRP_MAX_LAYERS];
     const int64_t* nnz_parts[GRP_MAX_LAYERS];
     const int32_t* seed_counts = nullptr;
-    GRP_TRY(sample_blocks(part, opts, k, p.sampler_ws, p.sampler_bytes, blocks, long_bwd, nnz_parts, &seed_counts, st));
-    GRP_TRY(launch_stats(opts->n_seeds, opts->seeds, nullptr, part->d_local_in, part->d_global_in, seed_counts, 0, nnz_parts,
-                         k, p.stats_ws, stats_out, st));
-    return sage_step(part, model, opts, blocks, features, labels, nullptr, opts->seeds, weights, p, st, grad_out, stats_out);
+    const int64_t* bad_seeds = nullptr;
+    GRP_TRY(sample_blocks(part, opts, k, p.sampler_ws, p.sampler_bytes, blocks, long_bwd, nnz_parts, &seed_counts, &bad_seeds,
+                          st));
+    const int32_t* const seeds = blocks[k - 1].dst_nodes;     // the range-checked copy of the caller's list
+    GRP_TRY(launch_stats(opts->n_seeds, seeds, nullptr, part->d_local_in, part->d_global_in, seed_counts, 0, nnz_parts, k,
+                         p.stats_ws, stats_out, st, nullptr, nullptr, bad_seeds));
+    return sage_step(part, model, opts, blocks, features, labels, nullptr, seeds, weights, p, st, grad_out, stats_out);
 }

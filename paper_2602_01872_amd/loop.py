@@ -91,14 +91,18 @@ class MiniBatchTrainer:
     batch_id is the number of iterations done so far (``iteration``).  Within an iteration the phases run as
     in ``PhaseParallelTrainer``.  Sequencing only: the seed order, sampling, steps, reduction and update
     are library calls.
-    ``lanes``: the steps of a phase are independent, and a mini-batch step waits for the GPU once per
-    sampled layer; with ``lanes`` > 1 that many host threads each drive their share of the phase's steps on
-    a stream (default priority) and a workspace of their own, so one step's sampling overlaps another's
-    layers.  The result does not depend on it.
+    ``lanes``: the steps of a phase are independent, and a mini-batch step is a chain of ~60 small launches
+    that leaves most of the chip idle; with ``lanes`` > 1 that many host threads each queue their share of
+    the phase's steps on a stream (default priority) with a workspace of their own, so the steps overlap
+    on the GPU.  The result does not depend on it.
+    ``graphs``: the step of every partition is captured once in a HIP graph (a full batch; the seeds and the
+    batch id are read from device buffers that are rewritten before each replay), so an iteration costs the
+    host three launches per partition instead of ~60: one thread then keeps ``lanes`` streams busy.  Batches
+    shorter than ``batch_size`` (the last of an epoch) run uncaptured.  Same bits as without.
     """
 
     def __init__(self, parts, model, xs, ys, masks, theta0, estimator, max_active, batch_size, fanouts,
-                 sampler_seed, optimizer=None, dropout_rate=0.0, dropout_seed=0, lanes=1):
+                 sampler_seed, optimizer=None, dropout_rate=0.0, dropout_seed=0, lanes=1, graphs=False):
         self.dropout_rate, self.dropout_seed = dropout_rate, dropout_seed
         self.parts, self.model, self.xs, self.ys, self.masks = parts, model, xs, ys, masks
         self.estimator, self.max_active = estimator, max_active
@@ -123,8 +127,12 @@ class MiniBatchTrainer:
             ws_bytes = max(ws_bytes, g.grp_step_workspace_bytes(p, model, probe))
         n_lanes = max(1, min(int(lanes), max_active))
         self.ws = [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in range(n_lanes)]
-        self.side = [torch.cuda.Stream(device=dev) for _ in range(n_lanes)] if n_lanes > 1 else []
-        self.pool = ThreadPoolExecutor(max_workers=n_lanes) if n_lanes > 1 else None
+        self.graphs = bool(graphs)
+        self.side = [torch.cuda.Stream(device=dev) for _ in range(n_lanes)] if (n_lanes > 1 or self.graphs) else []
+        self.pool = ThreadPoolExecutor(max_workers=n_lanes) if (n_lanes > 1 and not self.graphs) else None
+        self.bid_dev = torch.zeros(1, dtype=torch.int64, device=dev)          # the batch id of the captured steps
+        self.batch_seeds = [torch.zeros(self.batch_size, dtype=torch.int32, device=dev) for _ in parts] if self.graphs else []
+        self.captured = {}                                                     # partition -> its step's graph
         self.step_count = 0
         self.epoch = 0
         self.iteration = 0
@@ -158,9 +166,46 @@ class MiniBatchTrainer:
                     if slot % len(self.side) == lane:
                         one_step(slot, p, it, lane, self.side[lane])
 
+        def graph_step(slot, p, it):                    # replay (capturing at first use) the partition's full-batch step
+            lane = slot % len(self.side)
+            lo = it * B
+            with torch.cuda.stream(self.side[lane]):
+                self.batch_seeds[p].copy_(self.seeds[p][lo:lo + B])
+                if p not in self.captured:
+                    st = self.stats[slot * g.STATS_BYTES:(slot + 1) * g.STATS_BYTES]
+                    opts = g.step_opts(estimator=self.estimator, full_graph=False, seeds=self.batch_seeds[p],
+                                       fanouts=self.fanouts, sampler_seed=self.sampler_seed, batch_id_dev=self.bid_dev,
+                                       dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed)
+                    # once uncaptured on this stream first: nothing lazy (a kernel's first load) is left for the capture
+                    g.grp_train_step(self.parts[p], self.model, opts, self.xs[p], self.ys[p], None, self.theta,
+                                     self.ws[lane], self.grads[slot], st)
+                    graph = torch.cuda.CUDAGraph()
+                    torch.cuda.synchronize()
+                    with torch.cuda.graph(graph, stream=self.side[lane]):
+                        g.grp_train_step(self.parts[p], self.model, opts, self.xs[p], self.ys[p], None, self.theta,
+                                         self.ws[lane], self.grads[slot], st)
+                    self.captured[p] = (graph, opts)
+                self.captured[p][0].replay()
+
         for it in range(self.iters):
+            if self.graphs:
+                self.bid_dev.fill_(self.iteration)
             for active in self.phases():
-                if self.pool is None:
+                if self.graphs:
+                    main = torch.cuda.current_stream()
+                    ready = main.record_event()
+                    for sd in self.side:
+                        sd.wait_event(ready)
+                    for slot, p in enumerate(active):
+                        if min((it + 1) * B, counts[p]) - it * B == B:
+                            graph_step(slot, p, it)
+                        else:
+                            lane = slot % len(self.side)
+                            with torch.cuda.stream(self.side[lane]):
+                                one_step(slot, p, it, lane, self.side[lane])
+                    for sd in self.side:
+                        main.wait_stream(sd)
+                elif self.pool is None:
                     for slot, p in enumerate(active):
                         one_step(slot, p, it, 0, None)
                 else:
@@ -189,7 +234,7 @@ class SweepingTrainer:
     rebuilt on the GPU (``grp_partition_from_chunks``) and its rows of the global feature /
     label / mask tensors are gathered by ``l2g``; the controller decides after each epoch
     whether to switch.  theta and the optimizer state persist across super-epochs.
-    ``minibatch = dict(batch_size=, fanouts=, sampler_seed=[, lanes=])``: every epoch is a mini-batch epoch
+    ``minibatch = dict(batch_size=, fanouts=, sampler_seed=[, lanes=, graphs=])``: every epoch is a mini-batch epoch
     (``MiniBatchTrainer``) over the current partitions; the epoch number and the iteration count run on
     across super-epochs.
     """
@@ -231,7 +276,8 @@ class SweepingTrainer:
             mb = self.minibatch
             tr = MiniBatchTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active,
                                   mb["batch_size"], mb["fanouts"], mb["sampler_seed"], self.opt,
-                                  dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed, lanes=mb.get("lanes", 1))
+                                  dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed, lanes=mb.get("lanes", 1),
+                                  graphs=mb.get("graphs", False))
             tr.epoch, tr.iteration = self.epoch, self.iteration
         else:
             tr = PhaseParallelTrainer(parts, self.model, xs, ys, masks, self.theta, self.estimator, self.max_active, self.opt,

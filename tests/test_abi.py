@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_header():
     import paper_2602_01872_amd as g
     assert C.sizeof(g.ModelDesc) == 4 * (2 + 17 + 2)
-    assert C.sizeof(g.StepOpts) == 16 + 8 + 4 * 16 + 16 + 16
+    assert C.sizeof(g.StepOpts) == 16 + 8 + 4 * 16 + 16 + 16 + 8
     assert g.STATS_BYTES == 40
     assert C.sizeof(g.PartitionView) == 8 * 10
     assert C.sizeof(g.OptimizerDesc) == 24
@@ -68,7 +68,7 @@ def test_header_is_plain_c_and_its_struct_layouts_are_the_bindings(tmp_path):
         "grp_partition_weights_t": (g.PartitionWeights, ["csr_w", "csc_w", "w_local_in", "w_global_in"]),
         "grp_model_desc": (g.ModelDesc, ["arch", "n_layers", "dims", "feat_dtype", "gcn_self_loops"]),
         "grp_step_opts": (g.StepOpts, ["estimator", "full_graph", "n_seeds", "seeds", "fanouts", "sampler_seed", "batch_id",
-                                       "dropout_rate", "dropout_seed"]),
+                                       "dropout_rate", "dropout_seed", "batch_id_dev"]),
         "grp_step_stats": (None, ["loss", "sum_ratio", "R", "S", "nnz_used"]),
         "grp_optimizer_desc": (g.OptimizerDesc, ["kind", "lr", "beta1", "beta2", "eps"]),
     }
