@@ -556,7 +556,7 @@ def run_evidence_workload(args, g, synth, torch, dev):
         torch.cuda.synchronize()
         want = grads[0].clone()
         graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
+        with torch.cuda.graph(graph, stream=side):         # the stream of the warm-up: its helper stream exists
             fn()
         dt_graph, dt_graph_med = _timed_steps(torch, graph.replay, args.warmup, args.steps)
         assert torch.equal(grads[0], want), "the replayed step must reproduce the uncaptured one bit for bit"

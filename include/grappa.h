@@ -255,7 +255,7 @@ typedef struct {
     uint64_t       sampler_seed;
     uint64_t       batch_id;
     float          dropout_rate;  /* in [0, 1); 0 = off (see below)                            */
-    int32_t        reserved2;
+    int32_t        flags;         /* GRP_STEP_* bits, 0 = defaults                              */
     uint64_t       dropout_seed;
     const uint64_t* batch_id_dev; /* DEV or NULL.  When set, batch_id above is ignored and the batch
                                      id (of the sampler and of dropout) is read from this address
@@ -263,6 +263,13 @@ typedef struct {
                                      then be replayed as the next batch by writing the new id (and the
                                      new seeds) into the same device buffers.                     */
 } grp_step_opts;
+
+/* grp_step_opts.flags.  A mini-batch step builds the transposed blocks (read by the backward pass only) on a
+ * helper stream of the library's (default priority; one per caller stream, created at the first uncaptured
+ * mini-batch step on that stream and kept) beside the next layers' sampling and the forward pass, and joins
+ * it before the backward pass: shorter steps.  A caller that already runs several steps side by side on
+ * streams of its own gains nothing from it and can keep every step on its one stream with this bit.     */
+#define GRP_STEP_ONE_STREAM 1
 
 /* Written to DEV memory by grp_train_step (one record per partition). */
 typedef struct {

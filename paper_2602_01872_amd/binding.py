@@ -54,9 +54,10 @@ class StepOpts(C.Structure):
     _fields_ = [("estimator", C.c_int32), ("full_graph", C.c_int32), ("n_seeds", C.c_int32),
                 ("reserved", C.c_int32), ("seeds", C.c_void_p), ("fanouts", C.c_int32 * GRP_MAX_LAYERS),
                 ("sampler_seed", C.c_uint64), ("batch_id", C.c_uint64), ("dropout_rate", C.c_float),
-                ("reserved2", C.c_int32), ("dropout_seed", C.c_uint64), ("batch_id_dev", C.c_void_p)]
+                ("flags", C.c_int32), ("dropout_seed", C.c_uint64), ("batch_id_dev", C.c_void_p)]
 
 
+STEP_ONE_STREAM = 1
 STATS_DTYPE = np.dtype([("loss", "<f8"), ("sum_ratio", "<f8"), ("R", "<f8"), ("S", "<i8"), ("nnz_used", "<i8")])
 STATS_BYTES = STATS_DTYPE.itemsize
 
@@ -161,7 +162,8 @@ def model_desc(arch: int, dims, feat_dtype: int = DTYPE_FP32, gcn_self_loops: bo
 
 
 def step_opts(estimator: int = EST_NONE, full_graph: bool = True, seeds=None, fanouts=(), sampler_seed: int = 0,
-              batch_id: int = 0, dropout_rate: float = 0.0, dropout_seed: int = 0, batch_id_dev=None) -> StepOpts:
+              batch_id: int = 0, dropout_rate: float = 0.0, dropout_seed: int = 0, batch_id_dev=None,
+              flags: int = 0) -> StepOpts:
     """``batch_id_dev``: a one-element int64 device tensor holding the batch id (read when the step runs, see grappa.h)."""
     o = StepOpts()
     o.estimator = estimator
@@ -174,6 +176,7 @@ def step_opts(estimator: int = EST_NONE, full_graph: bool = True, seeds=None, fa
     o.batch_id = batch_id
     o.dropout_rate = dropout_rate
     o.dropout_seed = dropout_seed
+    o.flags = flags
     if batch_id_dev is not None:
         assert batch_id_dev.is_cuda and batch_id_dev.dtype == torch.int64 and batch_id_dev.numel() == 1
     o.batch_id_dev = _ptr(batch_id_dev)

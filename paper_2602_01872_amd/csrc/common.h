@@ -375,6 +375,19 @@ __host__ __device__ __forceinline__ uint64_t mixM(uint64_t x) {
     return z ^ (z >> 31);
 }
 
+// A helper stream beside a caller's stream, for work of a step that is off its critical path: the caller's
+// stream records fork[i], the helper waits for it, works, records `join`, and the caller's stream waits for
+// `join` before it needs the result (a fork and join that a graph capture of the caller's stream follows).
+// Null when none can be had (creation failed, or the first request for this stream came while it was being
+// captured): the work then stays on the caller's stream.  Calls that use the same caller stream from
+// several host threads at once would mix up the events; the steps of one stream come from one thread.
+struct SideLane {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork[GRP_MAX_LAYERS] = {};
+    hipEvent_t join = nullptr;
+};
+SideLane* side_lane(hipStream_t main);
+
 // ---------------------------------------------------------------- blocks and sampling (sampler.hip)
 // One bipartite message-passing layer.  Rows of `ptr/idx` are the layer's outputs
 // (destinations); `idx` indexes rows of the layer's input matrix.  The outputs are the first
@@ -414,7 +427,11 @@ size_t sampler_workspace_bytes(int64_t n, const SamplerBounds& b, int k);
 // device memory, so the whole step can be queued (or captured in a graph) at once.
 grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* opts, int k, void* ws, size_t ws_bytes,
                          Block* blocks, LongRows* long_bwd_store, const int64_t** nnz_parts_dev,
-                         const int32_t** seed_counts_dev, const int64_t** bad_seeds_dev, hipStream_t st);
+                         const int32_t** seed_counts_dev, const int64_t** bad_seeds_dev, hipStream_t st,
+                         hipEvent_t* transposed_ready);
+// *transposed_ready: null, or the event the caller's stream has to wait for before it reads a block's
+// transposed structure (ptrT, idxT, long_bwd): those are built on a helper stream beside the sampling of the
+// next layers, since only the backward pass reads them.
 grp_status sampler_block_view(const grp_partition_t* part, const grp_step_opts* o, int k, void* ws, size_t ws_bytes, int layer,
                               grp_block_view_t* out);
 }  // namespace grp

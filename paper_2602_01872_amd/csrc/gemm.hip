@@ -731,7 +731,7 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
         // one profiling name per kernel variant, so that the names line up with a kernel trace
         char pname[64];
         snprintf(pname, sizeof pname, "gemm_%s_%s_%s%s", ok ? "nt" : "nn", a.a_bf16 ? "bf16a" : "f32",
-                 ok ? (a.M > 0 && n_eff > 32 && cdiv(a.M, 128) * cdiv(n_eff, n_eff > 96 ? 128 : n_eff > 64 ? 96 : 64) < 384
+                 ok ? (a.M > 0 && n_eff > 32 && cdiv(a.M_dev ? (a.M + 1) / 2 : a.M, 128) * cdiv(n_eff, n_eff > 96 ? 128 : n_eff > 64 ? 96 : 64) < 384
                            ? "64x64" : n_eff > 96 ? "128x128" : n_eff > 64 ? "128x96" : "128x64")
                     : (n_eff > 64 ? "128x128" : n_eff > 32 ? "128x64" : "128x32"),
                  short_k ? "_k16" : "_k32");
@@ -745,7 +745,9 @@ grp_status launch_gemm_nn(const GemmNNArgs& a, hipStream_t st) {
         int tile_n = n_eff > 96 ? 128 : n_eff > 64 ? 96 : 64;
         // A product whose 128-row tiles would leave half the chip idle (mini-batch blocks) is cut into
         // 64 x 64 tiles instead: four times the workgroups, each a quarter of the work.
-        const bool small_tiles = n_eff > 32 && cdiv(a.M, 128) * cdiv(n_eff, tile_n) < 384;
+        // (an upper bound of M that the device will cut down counts half: sampled blocks fill about that much)
+        const int64_t m_plan = a.M_dev ? (a.M + 1) / 2 : a.M;
+        const bool small_tiles = n_eff > 32 && cdiv(m_plan, 128) * cdiv(n_eff, tile_n) < 384;
         if (small_tiles) tile_n = 64;
         const int64_t slabs = round_up(cdiv(a.M, small_tiles ? 64 : 128), NXCD);
         const unsigned blocks = (unsigned)(slabs * cdiv(n_eff, tile_n));
@@ -837,7 +839,12 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTNArgs g, int tiles_k,
                                                       float* __restrict__ out, float* __restrict__ out2, int64_t out_ld,
                                                       int64_t out_split_stride, float* __restrict__ cs_out,
                                                       int64_t cs_split_stride) {
-    if (g.M_dev) g.M = *g.M_dev;                           // the launch (and `chunk`) were sized by an upper bound
+    if (g.M_dev) {                                         // the launch was sized by an upper bound of M:
+        g.M = *g.M_dev;                                    // the real rows are dealt evenly to its slices
+        chunk = (g.M + splits - 1) / splits;
+        chunk = (chunk + BK - 1) / BK * BK;
+        if (chunk < BK) chunk = BK;
+    }
     constexpr int BKA = WM * TM * 32, BN = WN * TN * 32;   // output tile: BKA (rows of C) x BN
     constexpr int PA = BKA + 4, PB = BN + 4;
     constexpr int QA = BKA / 4, QB = BN / 4;               // 16-byte slots per tile row

@@ -66,6 +66,36 @@ void prof_end(hipStream_t st) {
     g_open_end = nullptr;
 }
 
+// One helper stream (default priority, not synchronising with the legacy stream) and its events per caller
+// stream and device, created at the first request and kept until the process ends.
+SideLane* side_lane(hipStream_t main) {
+    static std::mutex mu;
+    static std::map<std::pair<int, hipStream_t>, SideLane*> lanes;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    std::lock_guard<std::mutex> lk(mu);
+    auto it = lanes.find({dev, main});
+    if (it != lanes.end()) return it->second;
+    if (main) {            // nothing is created while the caller's stream is being captured
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(main, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+    }
+    SideLane* lane = new SideLane();
+    bool ok = hipStreamCreateWithFlags(&lane->stream, hipStreamNonBlocking) == hipSuccess;
+    for (int l = 0; ok && l < GRP_MAX_LAYERS; ++l)
+        ok = hipEventCreateWithFlags(&lane->fork[l], hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&lane->join, hipEventDisableTiming) == hipSuccess;
+    if (!ok) {             // the step then runs on the caller's stream alone; what was created stays allocated
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    lanes[{dev, main}] = lane;
+    return lane;
+}
+
 }  // namespace grp
 
 extern "C" const char* grp_last_error(void) { return grp::g_err.c_str(); }

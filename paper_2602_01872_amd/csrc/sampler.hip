@@ -225,6 +225,7 @@ struct SamplerBufs {
     int32_t* wpos;                      // [n_words + 1] set bits in the words before each word
     int64_t n_words;
     void *scan_tmp, *sort_tmp;
+    void* scan_tmp_side;                // the prefix sums of the transposed blocks (built on a helper stream)
     size_t scan_bytes, sort_bytes;
     size_t total;
 };
@@ -272,6 +273,7 @@ static SamplerBufs carve_sampler(int64_t n, const SamplerBounds& b, int k, void*
     s.wpos = bump.take<int32_t>((size_t)s.n_words + 1);
     s.scan_bytes = scan_temp_bytes(s.n_words + 1 > max_dst + 1 ? s.n_words + 1 : max_dst + 1);
     s.scan_tmp = bump.take<char>(s.scan_bytes);
+    s.scan_tmp_side = k > 1 ? bump.take<char>(s.scan_bytes) : nullptr;
     s.sort_bytes = k > 1 ? sort_keys_temp_bytes(max_nnz) : 0;
     s.sort_tmp = bump.take<char>(s.sort_bytes);
     s.total = bump.total();
@@ -285,8 +287,10 @@ static unsigned blocks_for(int64_t work) { return (unsigned)cdiv(work > 0 ? work
 
 grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, int k, void* ws, size_t ws_bytes,
                          Block* blocks, LongRows* long_bwd_store, const int64_t** nnz_parts_dev,
-                         const int32_t** seed_counts_dev, const int64_t** bad_seeds_dev, hipStream_t st) {
+                         const int32_t** seed_counts_dev, const int64_t** bad_seeds_dev, hipStream_t st,
+                         hipEvent_t* transposed_ready) {
     const int64_t n = part->n;
+    *transposed_ready = nullptr;
     if (o->n_seeds < 1 || !o->seeds) return fail(GRP_EINVAL, "mini-batch: need at least one seed node");
     if (n == 0) return fail(GRP_ERANGE, "mini-batch: seeds given for a partition without nodes");
     for (int l = 0; l < k; ++l)
@@ -307,6 +311,7 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
                        s.seeds, s.bad, s.sizes + SZ_PER_LAYER * (k - 1) + SZ_DST);
     GRP_LAUNCH_CHECK();
     *bad_seeds_dev = s.bad;
+    SideLane* const lane = (k > 1 && !(o->flags & GRP_STEP_ONE_STREAM)) ? side_lane(st) : nullptr;
     const uint64_t h0 = mixM(o->sampler_seed);
     const int32_t* dst_nodes = s.seeds;
     for (int l = k - 1; l >= 0; --l) {
@@ -362,17 +367,27 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
                            s.sizes + SZ_PER_LAYER * (l - 1) + SZ_DST, (const int32_t*)L.idx_local, (const int32_t*)s.mark,
                            L.idx_blk, L.keys, nnz_bound, (uint64_t)src_bound << 32, (const int32_t*)(s.wpos + s.n_words));
         GRP_LAUNCH_CHECK();
+        // The transposed block is read by the backward pass only: it is built on the helper stream, beside the
+        // sampling of the next layers and the forward pass.
+        hipStream_t bst = st;
+        void* scan_tmp_t = s.scan_tmp;
+        if (lane) {
+            GRP_HIP(hipEventRecord(lane->fork[l], st));
+            GRP_HIP(hipStreamWaitEvent(lane->stream, lane->fork[l], 0));
+            bst = lane->stream;
+            scan_tmp_t = s.scan_tmp_side;
+        }
         hipLaunchKernelGGL(clear_marks_kernel, dim3(blocks_for(src_bound)), dim3(256), 0, st, (const int32_t*)L.src_nodes,
                            (const int64_t*)(D + SZ_SRC), s.mark);
         GRP_LAUNCH_CHECK();
-        GRP_TRY(sort_keys_u64(s.sort_tmp, s.sort_bytes, L.keys, L.keys_sorted, nnz_bound, 32u + (unsigned)bits, st));
+        GRP_TRY(sort_keys_u64(s.sort_tmp, s.sort_bytes, L.keys, L.keys_sorted, nnz_bound, 32u + (unsigned)bits, bst));
         // Over src_bound rows: those past the real sources come out empty (their pointer is the real number
         // of edges, where the sentinels begin), and the entries of idxT past that number are never read.
-        GRP_TRY(launch_csr_from_sorted_keys(L.keys_sorted, nnz_bound, src_bound, L.ptrT, L.idxT, st));
+        GRP_TRY(launch_csr_from_sorted_keys(L.keys_sorted, nnz_bound, src_bound, L.ptrT, L.idxT, bst));
         LongRows& lr = long_bwd_store[l];
         lr.long_row = L.lr_row; lr.long_first = L.lr_first; lr.chunk_begin = L.lr_cb; lr.chunk_end = L.lr_ce;
-        GRP_TRY(build_long_rows_device(L.ptrT, src_bound, &lr, L.lr_cap_long, L.lr_cap_chunks, L.lr_scan, s.scan_tmp,
-                                       s.scan_bytes, st));
+        GRP_TRY(build_long_rows_device(L.ptrT, src_bound, &lr, L.lr_cap_long, L.lr_cap_chunks, L.lr_scan, scan_tmp_t,
+                                       s.scan_bytes, bst));
         B.idx = L.idx_blk;
         B.n_in = src_bound;
         B.n_in_dev = D + SZ_SRC;
@@ -381,6 +396,10 @@ grp_status sample_blocks(const grp_partition_t* part, const grp_step_opts* o, in
         B.idxT = L.idxT;
         B.long_bwd = &lr;
         dst_nodes = L.src_nodes;
+    }
+    if (lane) {
+        GRP_HIP(hipEventRecord(lane->join, lane->stream));
+        *transposed_ready = lane->join;
     }
     return GRP_OK;
 }

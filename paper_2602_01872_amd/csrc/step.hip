@@ -226,7 +226,8 @@ static grp_status prep_weights(const grp_model_desc* m, const float* theta, Step
 
 static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, const grp_step_opts* o, const Block* blk,
                             const void* X, const int32_t* labels, const uint8_t* mask, const int32_t* loss_nodes,
-                            const float* theta, StepPlan& p, hipStream_t st, float* grad, grp_step_stats* stats) {
+                            const float* theta, StepPlan& p, hipStream_t st, float* grad, grp_step_stats* stats,
+                            hipEvent_t transposed_ready = nullptr) {
     const int k = m->n_layers;
     const DropoutPlan drop = dropout_plan(o);
     GRP_TRY(prep_weights(m, theta, p, drop.scale, st));
@@ -295,6 +296,7 @@ static grp_status sage_step(const grp_partition_t* g, const grp_model_desc* m, c
                                 p.stats_ws, stats, st, g->w_local_in, g->w_global_in));
 
     // ---------------- backward
+    if (transposed_ready) GRP_HIP(hipStreamWaitEvent(st, transposed_ready, 0));   // the blocks' transposed structures
     for (int l = k - 1; l >= 0; --l) {
         const LayerBufs& L = p.L[l];
         const Block& B = blk[l];
@@ -564,10 +566,12 @@ extern "C" grp_status grp_train_step(const grp_partition_t* part, const grp_mode
     const int64_t* nnz_parts[GRP_MAX_LAYERS];
     const int32_t* seed_counts = nullptr;
     const int64_t* bad_seeds = nullptr;
+    hipEvent_t transposed_ready = nullptr;
     GRP_TRY(sample_blocks(part, opts, k, p.sampler_ws, p.sampler_bytes, blocks, long_bwd, nnz_parts, &seed_counts, &bad_seeds,
-                          st));
+                          st, &transposed_ready));
     const int32_t* const seeds = blocks[k - 1].dst_nodes;     // the range-checked copy of the caller's list
     GRP_TRY(launch_stats(opts->n_seeds, seeds, nullptr, part->d_local_in, part->d_global_in, seed_counts, 0, nnz_parts, k,
                          p.stats_ws, stats_out, st, nullptr, nullptr, bad_seeds));
-    return sage_step(part, model, opts, blocks, features, labels, nullptr, seeds, weights, p, st, grad_out, stats_out);
+    return sage_step(part, model, opts, blocks, features, labels, nullptr, seeds, weights, p, st, grad_out, stats_out,
+                     transposed_ready);
 }

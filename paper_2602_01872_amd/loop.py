@@ -175,7 +175,8 @@ class MiniBatchTrainer:
                     st = self.stats[slot * g.STATS_BYTES:(slot + 1) * g.STATS_BYTES]
                     opts = g.step_opts(estimator=self.estimator, full_graph=False, seeds=self.batch_seeds[p],
                                        fanouts=self.fanouts, sampler_seed=self.sampler_seed, batch_id_dev=self.bid_dev,
-                                       dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed)
+                                       dropout_rate=self.dropout_rate, dropout_seed=self.dropout_seed,
+                                       flags=g.STEP_ONE_STREAM if len(self.side) > 1 else 0)   # the lanes fill the GPU
                     # once uncaptured on this stream first: nothing lazy (a kernel's first load) is left for the capture
                     g.grp_train_step(self.parts[p], self.model, opts, self.xs[p], self.ys[p], None, self.theta,
                                      self.ws[lane], self.grads[slot], st)

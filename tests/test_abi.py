@@ -68,7 +68,7 @@ def test_header_is_plain_c_and_its_struct_layouts_are_the_bindings(tmp_path):
         "grp_partition_weights_t": (g.PartitionWeights, ["csr_w", "csc_w", "w_local_in", "w_global_in"]),
         "grp_model_desc": (g.ModelDesc, ["arch", "n_layers", "dims", "feat_dtype", "gcn_self_loops"]),
         "grp_step_opts": (g.StepOpts, ["estimator", "full_graph", "n_seeds", "seeds", "fanouts", "sampler_seed", "batch_id",
-                                       "dropout_rate", "dropout_seed", "batch_id_dev"]),
+                                       "dropout_rate", "flags", "dropout_seed", "batch_id_dev"]),
         "grp_step_stats": (None, ["loss", "sum_ratio", "R", "S", "nnz_used"]),
         "grp_optimizer_desc": (g.OptimizerDesc, ["kind", "lr", "beta1", "beta2", "eps"]),
     }

@@ -67,7 +67,8 @@ def test_captured_step_replays_match_eager(arch, dims):
     part.destroy()
 
 
-def test_captured_minibatch_step_replays_match_eager():
+@pytest.mark.parametrize("capture_on_warm_stream", [False, True])
+def test_captured_minibatch_step_replays_match_eager(capture_on_warm_stream):
     """A mini-batch step (isolated sampling, the sampled blocks' layers, reduction, update) waits for the device
     nowhere: the block sizes stay in device memory.  Captured once, it is replayed with new seeds written
     and a new batch id written into the same device buffers; every replay must equal the eager step with those
@@ -75,7 +76,7 @@ def test_captured_minibatch_step_replays_match_eager():
     replay to replay (the graph holds no sizes of the captured batch)."""
     import paper_2602_01872_amd as g
     g.load()
-    print("[case] graph capture of a mini-batch step", flush=True)
+    print(f"[case] graph capture of a mini-batch step, on the warm stream: {capture_on_warm_stream}", flush=True)
     N, E, dims, fanouts, B = 6000, 90000, [48, 64, 32, 7], (6, 4, 3), 96
     s, d = synth.rmat_graph(13, E, seed=11, n_nodes=N)
     part = g.grp_partition(s.to(DEV), d.to(DEV), N, 1, 1, 0)
@@ -125,7 +126,7 @@ def test_captured_minibatch_step_replays_match_eager():
     torch.cuda.synchronize()
     cap["theta"].copy_(theta0.to(DEV))
     graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
+    with torch.cuda.graph(graph, stream=side if capture_on_warm_stream else None):
         one_iteration(cap)
     for i, b in enumerate(batches):
         cap["seeds"].copy_(b)
