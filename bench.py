@@ -653,7 +653,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     if args.no_slices:
-        g.grp_set_slice_min_nodes(1 << 62)
+        g.grp_set_slice_policy(1 << 62, 100)
     if args.workload != "c2-step":
         run_evidence_workload(args, g, synth, torch, dev)
         return

@@ -528,13 +528,15 @@ grp_status grp_gemm_tn(int64_t M, int32_t K, int32_t N, const void* A, int64_t l
 
 /* ------------------------------------------------------------------ tuning */
 
-/* Partitions with at least this many nodes (default 2^17) also get the source-sliced schedule of their long
- * rows when they are built: rows of more than 512 edges are cut where their sorted sources pass from one of 64
- * equal ranges of node ids into the next, and the aggregation then processes the pieces range by range, so
- * that the rows gathered at any one time come from one 64th of the nodes and stay in the L2 cache.  Results
- * differ from the unsliced schedule only by the order of fp32 additions (both orders are fixed by the graph).
- * Applies to partitions built afterwards; process-wide.  n >= 1.                                        */
-grp_status grp_set_slice_min_nodes(int64_t n);
+/* Which partitions also get the source-sliced schedule of their long rows when they are built: those with at
+ * least min_nodes nodes (default 2^17) whose rows of more than 512 edges hold at least min_long_edge_percent
+ * of the edges of that direction (default 25; on a share whose few hubs hold a tenth of the edges the partial
+ * rows cost more than the cache hits save: measured 5 % slower).  Such rows are cut where their sorted sources
+ * pass from one of 64 equal ranges of node ids into the next, and the aggregation then processes the pieces
+ * range by range, so that the rows gathered at any one time come from one 64th of the nodes and stay in the L2
+ * cache.  Results differ from the unsliced schedule only by the order of fp32 additions (both orders are fixed
+ * by the graph).  Applies to partitions built afterwards; process-wide.  min_nodes >= 1, percent in [0, 100]. */
+grp_status grp_set_slice_policy(int64_t min_nodes, int32_t min_long_edge_percent);
 
 /* ------------------------------------------------------------------ profiling */
 

@@ -105,7 +105,7 @@ def load() -> C.CDLL:
         "grp_gemm_nn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
         "grp_gemm_nt": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp],
         "grp_gemm_tn": [i64, i32, i32, vp, i64, i32, vp, i64, vp, i64, vp, sz, vp],
-        "grp_set_slice_min_nodes": [i64],
+        "grp_set_slice_policy": [i64, C.c_int32],
         "grp_controller_create": [i64, i32, C.c_double, i64, C.POINTER(vp)],
         "grp_controller_observe": [vp, vp, i32],
         "grp_controller_observe_stats": [vp, vp, i32],
@@ -522,8 +522,8 @@ def grp_gemm_tn(M, K, N, A, lda, a_dtype, B, ldb, Cm, ldc, workspace, stream=Non
                               _stream(stream)))
 
 
-def grp_set_slice_min_nodes(n: int):
-    _check(load().grp_set_slice_min_nodes(n))
+def grp_set_slice_policy(min_nodes: int = 1 << 17, min_long_edge_percent: int = 25):
+    _check(load().grp_set_slice_policy(min_nodes, min_long_edge_percent))
 
 
 def grp_profile_enable(on):
@@ -555,4 +555,4 @@ def exported_symbols():
             "grp_partition_destroy", "grp_chunks_build", "grp_chunks_build_assigned", "grp_chunks_destroy", "grp_partition_from_chunks",
             "grp_partition_base_mask", "grp_partition_halo", "grp_param_count", "grp_step_workspace_bytes", "grp_step_activation", "grp_step_block", "grp_train_step",
             "grp_aggregate", "grp_aggregate_ptrs", "grp_optimizer_step", "grp_spmm", "grp_spmm_workspace_bytes", "grp_spmm_static", "grp_gemm_nn", "grp_gemm_nt", "grp_gemm_tn_workspace_bytes", "grp_gemm_tn",
-            "grp_set_slice_min_nodes", "grp_sweep_chunk", "grp_super_epoch_epochs", "grp_controller_create", "grp_controller_observe", "grp_controller_observe_stats", "grp_controller_end_epoch", "grp_controller_state", "grp_controller_destroy", "grp_profile_enable", "grp_profile_report"]
+            "grp_set_slice_policy", "grp_sweep_chunk", "grp_super_epoch_epochs", "grp_controller_create", "grp_controller_observe", "grp_controller_observe_stats", "grp_controller_end_epoch", "grp_controller_state", "grp_controller_destroy", "grp_profile_enable", "grp_profile_report"]

@@ -93,8 +93,7 @@ struct LongRows {
     int64_t* row_task = nullptr;     // [n_long+1] first task id of each long row
 };
 // Structures with fewer rows than this keep the chunk schedule (their gathered rows fit the caches anyway).
-int64_t slice_min_nodes();
-grp_status build_slice_tasks(const int64_t* ptr, const int32_t* idx, int64_t n, LongRows* lr, hipStream_t st);
+grp_status build_slice_tasks(const int64_t* ptr, const int32_t* idx, int64_t n, int64_t nnz, LongRows* lr, hipStream_t st);
 }  // namespace grp
 
 struct grp_partition_s {

@@ -684,8 +684,8 @@ static grp_status build_csr_csc(grp_partition_t* h, uint64_t* keys, uint64_t* ke
     GRP_TRY(build_long_rows(h->colptr, n, &h->csc_long, cap_long, cap_chunks, scanned, scan_tmp, scan_bytes, st));
     GRP_HIP(hipStreamSynchronize(st));
     if (!vals) {                                          // weighted partitions keep the chunk schedule
-        GRP_TRY(build_slice_tasks(h->rowptr, h->col, n, &h->csr_long, st));
-        GRP_TRY(build_slice_tasks(h->colptr, h->row, n, &h->csc_long, st));
+        GRP_TRY(build_slice_tasks(h->rowptr, h->col, n, h->nnz, &h->csr_long, st));
+        GRP_TRY(build_slice_tasks(h->colptr, h->row, n, h->nnz, &h->csc_long, st));
     }
     return GRP_OK;
 }

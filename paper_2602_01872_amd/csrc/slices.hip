@@ -24,7 +24,7 @@
 namespace grp {
 
 static std::atomic<int64_t> g_slice_min_nodes{(int64_t)1 << 17};
-int64_t slice_min_nodes() { return g_slice_min_nodes.load(); }
+static std::atomic<int32_t> g_slice_min_percent{25};
 
 static __device__ __forceinline__ int64_t lower_bound_idx(const int32_t* __restrict__ idx, int64_t b, int64_t e, int64_t want) {
     while (b < e) {
@@ -84,13 +84,26 @@ __global__ __launch_bounds__(256) void slice_rows_kernel(const int64_t* __restri
     if (!EMIT && lane == 0) row_tasks[j] = count;
 }
 
+// *total += the edges of the listed rows (one atomic per wavefront)
+__global__ __launch_bounds__(256) void long_edges_kernel(const int64_t* __restrict__ ptr, const int32_t* __restrict__ long_row,
+                                                         int64_t n_long, unsigned long long* __restrict__ total) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int64_t len = 0;
+    if (j < n_long) {
+        const int64_t r = long_row[j];
+        if (r >= 0) len = ptr[r + 1] - ptr[r];
+    }
+    for (int o = 32; o > 0; o >>= 1) len += __shfl_down(len, o, 64);
+    if ((threadIdx.x & 63) == 0 && len > 0) atomicAdd(total, (unsigned long long)len);
+}
+
 // Builds lr->tasks / lr->row_task for the long rows already listed in lr (allocations owned by the caller's
 // handle through these pointers).  Leaves lr untouched (n_tasks = 0) when the structure is too small to gain.
-grp_status build_slice_tasks(const int64_t* ptr, const int32_t* idx, int64_t n, LongRows* lr, hipStream_t st) {
+grp_status build_slice_tasks(const int64_t* ptr, const int32_t* idx, int64_t n, int64_t nnz, LongRows* lr, hipStream_t st) {
     lr->n_tasks = 0;
     lr->tasks = nullptr;
     lr->row_task = nullptr;
-    if (n < slice_min_nodes() || lr->n_long <= 0) return GRP_OK;
+    if (n < g_slice_min_nodes.load() || lr->n_long <= 0) return GRP_OK;
     int shift = 0;
     while (((n - 1) >> shift) >= SLICES) ++shift;
     const int64_t n_long = lr->n_long;
@@ -99,6 +112,20 @@ grp_status build_slice_tasks(const int64_t* ptr, const int32_t* idx, int64_t n, 
     GRP_HIP(hipMalloc((void**)&row_task, (size_t)(n_long + 1) * sizeof(int64_t)));
     auto fail_free = [&](grp_status s) { (void)hipFree(row_task); return s; };
     GRP_HIP(hipMemsetAsync(row_task + n_long, 0, sizeof(int64_t), st));
+    {   // the long rows' share of the edges decides whether the schedule pays
+        hipLaunchKernelGGL(long_edges_kernel, dim3((unsigned)cdiv(n_long, 256)), dim3(256), 0, st, ptr, lr->long_row, n_long,
+                           (unsigned long long*)(row_task + n_long));
+        int64_t long_edges = 0;
+        if (hipMemcpyAsync(&long_edges, row_task + n_long, sizeof long_edges, hipMemcpyDeviceToHost, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess)
+            return fail_free(fail(GRP_EHIP, "slice schedule: the long rows' edge count did not reach the host"));
+        if (long_edges * 100 < nnz * (int64_t)g_slice_min_percent.load()) {
+            (void)hipFree(row_task);
+            return GRP_OK;
+        }
+        if (hipMemsetAsync(row_task + n_long, 0, sizeof(int64_t), st) != hipSuccess)
+            return fail_free(fail(GRP_EHIP, "slice schedule: clearing the task total failed"));
+    }
     const unsigned grid = (unsigned)cdiv(n_long, 4);
     hipLaunchKernelGGL(slice_rows_kernel<false>, dim3(grid), dim3(256), 0, st, ptr, idx, lr->long_row, n_long, shift, min_piece,
                        row_task, (SliceTask*)nullptr, (uint8_t*)nullptr);
@@ -162,8 +189,10 @@ grp_status build_slice_tasks(const int64_t* ptr, const int32_t* idx, int64_t n, 
 
 }  // namespace grp
 
-extern "C" grp_status grp_set_slice_min_nodes(int64_t n) {
-    if (n < 1) return grp::fail(GRP_EINVAL, "grp_set_slice_min_nodes: %lld", (long long)n);
-    grp::g_slice_min_nodes.store(n);
+extern "C" grp_status grp_set_slice_policy(int64_t min_nodes, int32_t min_long_edge_percent) {
+    if (min_nodes < 1 || min_long_edge_percent < 0 || min_long_edge_percent > 100)
+        return grp::fail(GRP_EINVAL, "grp_set_slice_policy: %lld nodes, %d %%", (long long)min_nodes, min_long_edge_percent);
+    grp::g_slice_min_nodes.store(min_nodes);
+    grp::g_slice_min_percent.store(min_long_edge_percent);
     return GRP_OK;
 }

@@ -163,11 +163,15 @@ def test_spmm_with_the_sliced_schedule_matches_oracle(g, F, bf16):
     _note(f"spmm sliced schedule F={F} bf16={bf16}")
     n, E = 5000, 700000
     s, d = synth.rmat_graph(13, E, seed=78, n_nodes=n, device=DEV)
-    g.grp_set_slice_min_nodes(1)
+    plain = g.grp_partition_from_local_coo(s, d, n)        # 5000 nodes: below the default policy's size
+    g.grp_set_slice_policy(1, 0)
     try:
         part = g.grp_partition_from_local_coo(s, d, n)
     finally:
-        g.grp_set_slice_min_nodes(1 << 17)
+        g.grp_set_slice_policy(1 << 17, 25)
+    # the sliced handle keeps a partial row per piece of at most 128 edges, the plain one per chunk of 512
+    assert g.grp_spmm_workspace_bytes(part, False, F) > 2 * g.grp_spmm_workspace_bytes(plain, False, F) > 0
+    plain.destroy()
     op = ograph.local_graph_from_edges(s.cpu().numpy(), d.cpu().numpy(), n)
     assert int(op["d_local_in"].max()) > 15000 and int((op["d_local_in"] > 512).sum()) > 100      # hub rows of many pieces per range
     assert g.grp_spmm_workspace_bytes(part, False, F) > 0
