@@ -488,7 +488,7 @@ grp_status grp_gather_rows(const void* src, int64_t n_src, int64_t row_bytes, co
  *   transposed = 1:  Y[u,:] = a_u (sum_{u->v} X[v,:] + self*X[u,:])     rows of the CSC
  * a = 1 (scale GRP_SCALE_NONE), 1/max(deg,1) (MEAN) or 1/sqrt(deg+self) clamped at
  * deg>=1 (RSQRT), deg = the row's length.  X: DEV [n x F] fp32/bf16, Y: DEV [n x F] fp32.
- * Scratch for the partial sums of the rows the partition splits (rows of more than 512 edges):
+ * Scratch for the partial sums of the rows the partition splits (rows of more than 128 edges):
  * grp_spmm_workspace_bytes gives the size for this direction and F (0 when no row is split); `workspace`
  * is DEV, 16-byte aligned, contents undefined afterwards.  The call allocates nothing and is asynchronous
  * on the stream.  Errors: GRP_EINVAL, GRP_EWORKSPACE, GRP_EUNSUPPORTED (F > 1024).                    */
@@ -529,9 +529,9 @@ grp_status grp_gemm_tn(int64_t M, int32_t K, int32_t N, const void* A, int64_t l
 /* ------------------------------------------------------------------ tuning */
 
 /* Which partitions also get the source-sliced schedule of their long rows when they are built: those with at
- * least min_nodes nodes (default 2^17) whose rows of more than 512 edges hold at least min_long_edge_percent
- * of the edges of that direction (default 25; on a share whose few hubs hold a tenth of the edges the partial
- * rows cost more than the cache hits save: measured 5 % slower).  Such rows are cut where their sorted sources
+ * least min_nodes nodes (default 2^19) whose rows of more than 128 edges hold at least min_long_edge_percent
+ * of the edges of that direction (default 25).  Below either bound the partial rows cost more than the cache hits save (a 3·10^5-node share whose
+ * feature matrix about fits the last-level cache: 5 % slower aggregation with the schedule).  Such rows are cut where their sorted sources
  * pass from one of 64 equal ranges of node ids into the next, and the aggregation then processes the pieces
  * range by range, so that the rows gathered at any one time come from one 64th of the nodes and stay in the L2
  * cache.  Results differ from the unsliced schedule only by the order of fp32 additions (both orders are fixed

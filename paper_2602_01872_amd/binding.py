@@ -522,7 +522,7 @@ def grp_gemm_tn(M, K, N, A, lda, a_dtype, B, ldb, Cm, ldc, workspace, stream=Non
                               _stream(stream)))
 
 
-def grp_set_slice_policy(min_nodes: int = 1 << 17, min_long_edge_percent: int = 25):
+def grp_set_slice_policy(min_nodes: int = 1 << 19, min_long_edge_percent: int = 25):
     _check(load().grp_set_slice_policy(min_nodes, min_long_edge_percent))
 
 

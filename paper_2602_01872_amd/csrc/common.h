@@ -66,7 +66,7 @@ struct ProfScope {
 namespace grp {
 // Rows longer than SPMM_LONG_ROW edges are cut into chunks of at most SPMM_CHUNK edges
 // (device arrays, built once with the partition; see spmm.hip).
-constexpr int SPMM_LONG_ROW = 512;
+constexpr int SPMM_LONG_ROW = 128;
 constexpr int SPMM_CHUNK = 512;
 // Source-sliced schedule of the long rows of a large structure (slices.hip): a long row is cut where its
 // sorted sources cross from one of SLICES equal ranges of node ids into the next, and each segment into tasks

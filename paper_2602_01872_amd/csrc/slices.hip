@@ -3,7 +3,7 @@
 // Why: a gather-bound aggregation over a graph without locality misses the L2 on almost every neighbour
 // row (measured on a 2^24-node, 2^32-edge share: 0.82 line fills per edge), because the rows gathered
 // at any one time are spread over all n sources.  The rows that hold most of the edges are long
-// (90 % of that share's edges sit in the 8 % of rows longer than 512 edges), and a row's sources are
+// (96 % of the edges of a share with that mean degree sit in the fifth of the rows that are longer than 128 edges), and a row's sources are
 // sorted, so a long row can be cut where its sources cross from one range of node ids into the next: the
 // node ids are divided into SLICES = 64 equal ranges, every long row is cut at the boundaries between them
 // (where the piece so far is long enough to be worth a task), and every piece into tasks of at most SLICE_PIECE edges.  The tasks are then processed slice by slice: at any one
@@ -23,7 +23,9 @@
 
 namespace grp {
 
-static std::atomic<int64_t> g_slice_min_nodes{(int64_t)1 << 17};
+constexpr unsigned SLICE_KEY_BITS = SLICES <= 64 ? 6u : SLICES <= 128 ? 7u : 8u;
+static_assert(SLICES <= 256 && (SLICES & (SLICES - 1)) == 0, "a slice key is one byte; the ranges are a power of two");
+static std::atomic<int64_t> g_slice_min_nodes{(int64_t)1 << 19};
 static std::atomic<int32_t> g_slice_min_percent{25};
 
 static __device__ __forceinline__ int64_t lower_bound_idx(const int32_t* __restrict__ idx, int64_t b, int64_t e, int64_t want) {
@@ -54,7 +56,7 @@ __global__ __launch_bounds__(256) void slice_rows_kernel(const int64_t* __restri
         return;
     }
     const int64_t b = ptr[r], e = ptr[r + 1];
-    cut_s[wave][lane] = lane == 0 ? b : lower_bound_idx(idx, b, e, (int64_t)lane << shift);
+    for (int sl = lane; sl < SLICES; sl += 64) cut_s[wave][sl] = sl == 0 ? b : lower_bound_idx(idx, b, e, (int64_t)sl << shift);
     if (lane == 0) cut_s[wave][SLICES] = e;
     __builtin_amdgcn_wave_barrier();                           // the wavefront's own LDS writes, read back below
     int64_t t = EMIT ? row_tasks[j] : 0;                       // (row_tasks holds the exclusive prefix sum when emitting)
@@ -163,13 +165,13 @@ grp_status build_slice_tasks(const int64_t* ptr, const int32_t* idx, int64_t n, 
         hipLaunchKernelGGL(slice_rows_kernel<true>, dim3(grid), dim3(256), 0, st, ptr, idx, lr->long_row, n_long, shift, min_piece,
                            row_task, recs, keys);
         size_t need = 0;
-        if (rocprim::radix_sort_pairs(nullptr, need, keys, keys_out, recs, sorted, (size_t)n_tasks, 0u, 6u, st) != hipSuccess ||
+        if (rocprim::radix_sort_pairs(nullptr, need, keys, keys_out, recs, sorted, (size_t)n_tasks, 0u, SLICE_KEY_BITS, st) != hipSuccess ||
             hipMalloc(&tmp, need ? need : 4) != hipSuccess) {
             (void)hipGetLastError();
             status = fail(GRP_ENOMEM, "slice schedule: sort scratch");
             break;
         }
-        if (rocprim::radix_sort_pairs(tmp, need, keys, keys_out, recs, sorted, (size_t)n_tasks, 0u, 6u, st) != hipSuccess ||
+        if (rocprim::radix_sort_pairs(tmp, need, keys, keys_out, recs, sorted, (size_t)n_tasks, 0u, SLICE_KEY_BITS, st) != hipSuccess ||
             hipStreamSynchronize(st) != hipSuccess) {
             status = fail(GRP_EHIP, "slice schedule: sort failed");
             break;

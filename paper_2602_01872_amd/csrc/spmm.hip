@@ -297,12 +297,17 @@ template <> struct LaneVec<__hip_bfloat16, 8> {
 
 // G lanes own a row, VW elements each (VW = 8 for bf16 rows that allow 16-byte loads: half the lanes per row,
 // so twice the rows in flight per wavefront for the same registers), NJ slabs of G * VW columns.
-template <typename XT, int G, int NJ, int VW, bool EV, bool CS>
+// SHIFT32 (plain sums only: no edge values, no per-source scale): the rows of X start at multiples of 2^row_shift
+// bytes and X is smaller than 4 GiB, so a row's address is a 32-bit shift and add beside the base (the generic
+// 64-bit index x pitch product costs three quarter-rate multiplies per gather: a third of the loop's issue cycles),
+// and a gathered row is added with one multiply-add per element (times 1, or 0 past the task's end).
+template <typename XT, int G, int NJ, int VW, bool EV, bool CS, bool SHIFT32 = false>
 __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __restrict__ tasks, int64_t n_tasks, int64_t per_wave,
                                                          const int32_t* __restrict__ idx, const float* __restrict__ val, int F,
                                                          const XT* __restrict__ X, int64_t ldx,
                                                          const float* __restrict__ colscale, float* __restrict__ partials,
-                                                         int64_t ld_part) {
+                                                         int64_t ld_part, int row_shift) {
+    static_assert(!SHIFT32 || (!EV && !CS), "the 32-bit addressing variant is built for plain sums");
     constexpr int IPL = SLICE_PIECE / 64;                 // indices of a task per lane
     static_assert(IPL * 64 == SLICE_PIECE && (IPL & (IPL - 1)) == 0, "a task's indices fill whole registers");
     constexpr int NG = 64 / G;
@@ -389,7 +394,15 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                for (int u = 0; u < U; ++u) LaneVec<XT, VW>::ld(X + c[u] * ldx + col[j], v[j][u]);
+                for (int u = 0; u < U; ++u) {
+                    if constexpr (SHIFT32) {
+                        const uint32_t off = ((uint32_t)c[u] << row_shift) + (uint32_t)(col[j] * (int)sizeof(XT));
+                        const XT* const src = reinterpret_cast<const XT*>(reinterpret_cast<const char*>(X) + off);
+                        LaneVec<XT, VW>::ld(src, v[j][u]);
+                    } else {
+                        LaneVec<XT, VW>::ld(X + c[u] * ldx + col[j], v[j][u]);
+                    }
+                }
             if (k0 == 0) {                                 // behind the first gathers: what the next two tasks need
                 __builtin_amdgcn_sched_barrier(0);
                 load_indices(nxt, nix, nwx);
@@ -403,8 +416,12 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
 #pragma unroll
                     for (int q = 0; q < VW; ++q) {
                         float x = v[j][u][q];
-                        if (EV || CS) x *= sc[u];
-                        acc[j][q] += on[u] ? x : 0.f;
+                        if constexpr (SHIFT32) {
+                            acc[j][q] = fmaf(x, on[u] ? 1.f : 0.f, acc[j][q]);     // x * 1 + acc rounds once, as x + acc does
+                        } else {
+                            if (EV || CS) x *= sc[u];
+                            acc[j][q] += on[u] ? x : 0.f;
+                        }
                     }
         }
 #pragma unroll
@@ -509,9 +526,20 @@ static void launch_one(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_t st
     if (sliced) {                                          // the long rows' tasks, slice by slice
         const int64_t per_wave = cdiv(lr->n_tasks, (int64_t)4 << 21);      // at most 2^21 workgroups of four wavefronts
         const dim3 tgrid((unsigned)cdiv(lr->n_tasks, 4 * per_wave));
+        // plain sums over rows that start at multiples of a power of two inside less than 4 GiB: 32-bit addressing
+        int row_shift = -1;
+        {
+            const int64_t pitch_bytes = a.ldx * (int64_t)sizeof(XT);
+            const int64_t x_rows = a.n_src > 0 ? a.n_src : a.n_rows;
+            if (!a.val && !a.colscale && pitch_bytes > 0 && (pitch_bytes & (pitch_bytes - 1)) == 0 &&
+                x_rows * pitch_bytes <= ((int64_t)1 << 32)) {
+                row_shift = 0;
+                while (((int64_t)1 << row_shift) < pitch_bytes) ++row_shift;
+            }
+        }
         auto go = [&](auto kernel) {
             hipLaunchKernelGGL(kernel, tgrid, dim3(256), 0, st, (const SliceTask*)lr->tasks, lr->n_tasks, per_wave, a.idx, a.val, a.F,
-                               (const XT*)a.X, a.ldx, a.colscale, a.partials, ld_part);
+                               (const XT*)a.X, a.ldx, a.colscale, a.partials, ld_part, row_shift);
         };
         // bf16 rows of whole 16-byte units: eight elements per lane, half the lanes per row
         constexpr bool bf16 = std::is_same<XT, __hip_bfloat16>::value;
@@ -521,6 +549,7 @@ static void launch_one(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_t st
                 if (a.val && a.colscale) go(spmm_tasks_kernel<XT, G / 2, 1, 8, true, true>);
                 else if (a.val) go(spmm_tasks_kernel<XT, G / 2, 1, 8, true, false>);
                 else if (a.colscale) go(spmm_tasks_kernel<XT, G / 2, 1, 8, false, true>);
+                else if (row_shift >= 0) go(spmm_tasks_kernel<XT, G / 2, 1, 8, false, false, true>);
                 else go(spmm_tasks_kernel<XT, G / 2, 1, 8, false, false>);
             }
         }
@@ -528,6 +557,7 @@ static void launch_one(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_t st
             if (a.val && a.colscale) go(spmm_tasks_kernel<XT, G, NJ, 4, true, true>);
             else if (a.val) go(spmm_tasks_kernel<XT, G, NJ, 4, true, false>);
             else if (a.colscale) go(spmm_tasks_kernel<XT, G, NJ, 4, false, true>);
+            else if (row_shift >= 0) go(spmm_tasks_kernel<XT, G, NJ, 4, false, false, true>);
             else go(spmm_tasks_kernel<XT, G, NJ, 4, false, false>);
         }
     }

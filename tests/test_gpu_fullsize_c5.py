@@ -73,7 +73,11 @@ def _run(SCALE, N, E, CH):
     deg_in = rowptr[1:] - rowptr[:-1]
     d_global = synth.stand_in_global_degree(deg_in, torch.arange(N, device=DEV), SEED, 255)
     _note("adopting the share")
-    part = g.grp_partition_from_csr(rowptr, col, N, d_global_in=d_global, slice_edges=CH)
+    g.grp_set_slice_policy(1, 25)          # the reduced-size run takes the sliced schedule too (default: 2^19 nodes and more)
+    try:
+        part = g.grp_partition_from_csr(rowptr, col, N, d_global_in=d_global, slice_edges=CH)
+    finally:
+        g.grp_set_slice_policy()
     _note("adopted")
     assert part.n == N and part.nnz == E
     assert part.view.rowptr == rowptr.data_ptr() and part.view.col == col.data_ptr()

@@ -168,7 +168,7 @@ def test_spmm_with_the_sliced_schedule_matches_oracle(g, F, bf16):
     try:
         part = g.grp_partition_from_local_coo(s, d, n)
     finally:
-        g.grp_set_slice_policy(1 << 17, 25)
+        g.grp_set_slice_policy()
     # the sliced handle keeps a partial row per piece of at most 128 edges, the plain one per chunk of 512
     assert g.grp_spmm_workspace_bytes(part, False, F) > 2 * g.grp_spmm_workspace_bytes(plain, False, F) > 0
     plain.destroy()
