@@ -70,16 +70,18 @@ constexpr int SPMM_LONG_ROW = 128;
 constexpr int SPMM_CHUNK = 512;
 // Source-sliced schedule of the long rows of a large structure (slices.hip): a long row is cut where its
 // sorted sources cross from one of SLICES equal ranges of node ids into the next, and each segment into tasks
-// of at most SLICE_PIECE edges; the tasks are processed slice by slice.
+// of at most SLICE_TASK_MAX edges; the tasks are processed slice by slice.
 constexpr int SLICES = 64;
-constexpr int SLICE_PIECE = 128;
+constexpr int SLICE_PIECE = 128;       // edges a wavefront takes in one pass (two indices per lane)
+constexpr int SLICE_TASK_MAX = 1024;   // edges of a task: up to this many consecutive edges of one piece share a partial row
+                                       // (128, i.e. a partial row per pass: 40 % more partial rows, step 142.3 against 139.0 ms; 4096: 139.7)
 constexpr int SLICE_MIN_PIECE = 96;  // a row is not cut at a slice boundary before its current piece has this many edges
                                      // (measured on the 2^32-edge share, ms per call at F = 16 fp32 / F = 64 bf16: 1: 43.0 / 82.4,
                                      //  32: 38.4 / 60.2, 96: 37.3 / 54.7, 128: 37.7 / 56.4; pieces of up to 256 edges: no better)
 struct SliceTask {
     int64_t begin;                   // first edge of the task
     uint32_t id;                     // its number in row-major order: where its partial row goes
-    uint32_t len;                    // 1 .. SLICE_PIECE edges
+    uint32_t len;                    // 1 .. SLICE_TASK_MAX edges
 };
 struct LongRows {
     int32_t n_long = 0, n_chunks = 0;

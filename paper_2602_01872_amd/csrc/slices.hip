@@ -6,7 +6,8 @@
 // (96 % of the edges of a share with that mean degree sit in the fifth of the rows that are longer than 128 edges), and a row's sources are
 // sorted, so a long row can be cut where its sources cross from one range of node ids into the next: the
 // node ids are divided into SLICES = 64 equal ranges, every long row is cut at the boundaries between them
-// (where the piece so far is long enough to be worth a task), and every piece into tasks of at most SLICE_PIECE edges.  The tasks are then processed slice by slice: at any one
+// (where the piece so far is long enough to be worth a task), and every piece into tasks of at most SLICE_TASK_MAX edges
+// (a wavefront walks a task in passes of SLICE_PIECE edges).  The tasks are then processed slice by slice: at any one
 // time the whole chip gathers from one 64th of the nodes, whose frequently used rows stay in the L2
 // (measured with the sources restricted to one 64th: 0.14 fills per edge).  A task's result is a partial
 // row; a long row's partial rows are added in task order (ascending source, the row's own edge order) by the
@@ -39,7 +40,7 @@ static __device__ __forceinline__ int64_t lower_bound_idx(const int32_t* __restr
 // One wavefront per long row.  Lane s finds where the row's sources enter slice s; the row is then cut at such a
 // boundary wherever the piece before it has reached SLICE_MIN_PIECE edges (a row of 600 edges is not worth 64
 // pieces of 9: a piece costs a partial row and ~200 instructions; see the measurements beside the constant), and every piece into tasks of at most
-// SLICE_PIECE edges.  A task's key is the slice of its first edge.  EMIT = false: the row's number of tasks.
+// SLICE_TASK_MAX edges.  A task's key is the slice of its first edge.  EMIT = false: the row's number of tasks.
 // EMIT = true: its task records (row-major numbering from row_task[j]) and their keys.
 template <bool EMIT>
 __global__ __launch_bounds__(256) void slice_rows_kernel(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx,
@@ -67,13 +68,13 @@ __global__ __launch_bounds__(256) void slice_rows_kernel(const int64_t* __restri
         const int64_t at = cut_s[wave][s];
         const bool close = s == SLICES || at - from >= min_piece;
         if (!close) continue;
-        const int64_t nt = (at - from + SLICE_PIECE - 1) / SLICE_PIECE;
+        const int64_t nt = (at - from + SLICE_TASK_MAX - 1) / SLICE_TASK_MAX;
         if (EMIT) {
             for (int64_t i = lane; i < nt; i += 64) {
                 SliceTask rec;
-                rec.begin = from + i * SLICE_PIECE;
+                rec.begin = from + i * SLICE_TASK_MAX;
                 rec.id = (uint32_t)(t + i);
-                rec.len = (uint32_t)(at - rec.begin < SLICE_PIECE ? at - rec.begin : SLICE_PIECE);
+                rec.len = (uint32_t)(at - rec.begin < SLICE_TASK_MAX ? at - rec.begin : SLICE_TASK_MAX);
                 recs[t + i] = rec;
                 keys[t + i] = (uint8_t)from_slice;
             }

@@ -266,7 +266,7 @@ __global__ __launch_bounds__(256) void spmm_combine_kernel(const int32_t* __rest
 }
 
 // ---- the source-sliced schedule of the long rows (slices.hip): one wavefront per task.
-// A task is at most SLICE_PIECE consecutive edges of one long row whose sources lie in one slice of the
+// A task is at most SLICE_TASK_MAX consecutive edges of one long row whose sources lie in one slice of the
 // node ids.  The wavefront reads the task's indices with coalesced loads (SLICE_PIECE / 64 per lane), its 64 / G groups
 // take consecutive runs of them (handed round with shuffles, up to four gathers in flight per group), the
 // groups' sums are added across the wavefront in a fixed butterfly, and the first group writes the partial row.
@@ -325,22 +325,24 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
     // Every load below is unconditional (an index past a task's end is clamped to its last edge and the gathered
     // row then dropped by a select): a conditional load becomes a branch with a wait behind it, and the gathers
     // of a task would no longer overlap.
-    auto load_indices = [&](const SliceTask& tk, int32_t (&ix)[IPL], float (&wx)[IPL]) {
-        const int last = (int)tk.len > 0 ? (int)tk.len - 1 : 0;
+    // A task is walked in passes of up to SLICE_PIECE edges; (begin, len) name a pass.
+    auto load_indices = [&](int64_t begin, int len, int32_t (&ix)[IPL], float (&wx)[IPL]) {
+        const int last = len > 0 ? len - 1 : 0;
 #pragma unroll
         for (int q = 0; q < IPL; ++q) {
-            const int64_t e = tk.begin + (64 * q + lane < last ? 64 * q + lane : last);
+            const int64_t e = begin + (64 * q + lane < last ? 64 * q + lane : last);
             ix[q] = idx[e];
             if (EV) wx[q] = val[e];
         }
     };
+    auto pass_len = [](const SliceTask& tk, int off) { return (int)tk.len - off < SLICE_PIECE ? (int)tk.len - off : SLICE_PIECE; };
     SliceTask cur = tasks[p0];
     SliceTask nxt = tasks[p0 + 1 < p_end ? p0 + 1 : p0];
     int32_t ix[IPL];
     float wx[IPL];
 #pragma unroll
     for (int q = 0; q < IPL; ++q) wx[q] = 1.f;
-    load_indices(cur, ix, wx);
+    load_indices(cur.begin, pass_len(cur, 0), ix, wx);
     int col[NJ];                                           // first column of the lane's unit in slab j (a dead unit reads column 0)
     bool live[NJ];
 #pragma unroll
@@ -348,15 +350,17 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
         live[j] = VW * (t + G * j) < F;
         col[j] = live[j] ? VW * (t + G * j) : 0;
     }
-    for (int64_t p = p0; p < p_end; ++p) {
-        const int len = (int)cur.len;                      // >= 1
+    float acc[NJ][VW];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int q = 0; q < VW; ++q) acc[j][q] = 0.f;
+    int off = 0;                                           // edges of the current task already added
+    for (int64_t p = p0; p < p_end;) {
+        const int len = pass_len(cur, off);                // >= 1: this pass
+        const bool last_pass = off + len == (int)cur.len;
         const int per = (len + NG - 1) / NG;               // the same in every lane
         const int first = gi * per;
-        float acc[NJ][VW];
-#pragma unroll
-        for (int j = 0; j < NJ; ++j)
-#pragma unroll
-            for (int q = 0; q < VW; ++q) acc[j][q] = 0.f;
         SliceTask nn = nxt;
         int32_t nix[IPL];
         float nwx[IPL];
@@ -403,10 +407,14 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
                         LaneVec<XT, VW>::ld(X + c[u] * ldx + col[j], v[j][u]);
                     }
                 }
-            if (k0 == 0) {                                 // behind the first gathers: what the next two tasks need
+            if (k0 == 0) {                                 // behind the first gathers: what the next pass and the task after next need
                 __builtin_amdgcn_sched_barrier(0);
-                load_indices(nxt, nix, nwx);
-                nn = tasks[p + 2 < p_end ? p + 2 : p];
+                if (last_pass) {
+                    load_indices(nxt.begin, pass_len(nxt, 0), nix, nwx);
+                    nn = tasks[p + 2 < p_end ? p + 2 : p];
+                } else {
+                    load_indices(cur.begin + off + len, pass_len(cur, off + len), nix, nwx);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
@@ -424,20 +432,28 @@ __global__ __launch_bounds__(256) void spmm_tasks_kernel(const SliceTask* __rest
                         }
                     }
         }
+        if (last_pass) {                                   // uniform: the task's partial row
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
+            for (int j = 0; j < NJ; ++j) {
 #pragma unroll
-            for (int o = G; o < 64; o <<= 1)
+                for (int o = G; o < 64; o <<= 1)
 #pragma unroll
-                for (int q = 0; q < VW; ++q) acc[j][q] += __shfl_xor(acc[j][q], o, 64);
-            if (gi == 0 && live[j]) {
-                float* out = partials + (int64_t)cur.id * ld_part + col[j];
+                    for (int q = 0; q < VW; ++q) acc[j][q] += __shfl_xor(acc[j][q], o, 64);
+                if (gi == 0 && live[j]) {
+                    float* out = partials + (int64_t)cur.id * ld_part + col[j];
 #pragma unroll
-                for (int q = 0; q < VW; q += 4)
-                    *reinterpret_cast<float4*>(out + q) = make_float4(acc[j][q], acc[j][q + 1], acc[j][q + 2], acc[j][q + 3]);
+                    for (int q = 0; q < VW; q += 4)
+                        *reinterpret_cast<float4*>(out + q) = make_float4(acc[j][q], acc[j][q + 1], acc[j][q + 2], acc[j][q + 3]);
+                }
+#pragma unroll
+                for (int q = 0; q < VW; ++q) acc[j][q] = 0.f;
             }
+            cur = nxt; nxt = nn;
+            off = 0;
+            ++p;
+        } else {
+            off += len;
         }
-        cur = nxt; nxt = nn;
 #pragma unroll
         for (int q = 0; q < IPL; ++q) { ix[q] = nix[q]; if (EV) wx[q] = nwx[q]; }
     }
