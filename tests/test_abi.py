@@ -110,3 +110,15 @@ def test_binding_fails_loudly_without_the_built_library(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", os.path.join(os.path.dirname(binding.LIB_PATH), "no_such_library.so"))
     with pytest.raises(ImportError):
         binding.load()
+
+
+def test_slice_policy_rejects_bad_arguments():
+    # host-side setting: needs the built library but no GPU
+    import paper_2602_01872_amd as g
+    if not os.path.exists(g.LIB_PATH):
+        pytest.skip("library not built")
+    for bad in ((0, 25), (-5, 25), (1 << 19, -1), (1 << 19, 101)):
+        with pytest.raises(g.GrappaError) as ei:
+            g.grp_set_slice_policy(*bad)
+        assert ei.value.status == g.EINVAL
+    g.grp_set_slice_policy()            # the defaults again
