@@ -14,7 +14,7 @@ Metric: per-partition train-step edges/s = nnz_used / t_step.
 
 Prints ONE JSON line with `roofline` (dominant kernel, timed with HIP events on the launch stream in a
 second, separately profiled pass over the same steps) and `cpu_baseline` (the fp64 numpy oracle timed on
-the host on the same model at R-MAT scale 13 with the same edge factor, with one BLAS thread and with all).
+the host on the same model at R-MAT scale 14 with the same edge factor, with one BLAS thread and with all).
 `--workload c2-step` is the second configuration (MFMA-bound), the other names are evidence runs.
 """
 from __future__ import annotations
@@ -580,9 +580,9 @@ def run_evidence_workload(args, g, synth, torch, dev):
     print(json.dumps(out), flush=True)
 
 
-def _c5_cpu_baseline(synth, torch, seed, dims, scale=13, edge_factor=256):
-    """The oracle's train step + shrinkage aggregation on the same model and graph family at R-MAT scale 13 with
-    the same edge factor (1/2048 of the configuration's nodes and edges: the oracle needs ~5 us per edge), timed
+def _c5_cpu_baseline(synth, torch, seed, dims, scale=14, edge_factor=256):
+    """The oracle's train step + shrinkage aggregation on the same model and graph family at R-MAT scale 14 with
+    the same edge factor (1/1024 of the configuration's nodes and edges: the oracle needs ~1.6 us per edge, about 13 s for the two timings), timed
     with one BLAS thread and with the default thread count.  A reported baseline, never tuned."""
     import numpy as np
     from oracle import coverage as ocov
