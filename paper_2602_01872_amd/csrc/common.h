@@ -75,9 +75,10 @@ constexpr int SLICES = 64;
 constexpr int SLICE_PIECE = 128;       // edges a wavefront takes in one pass (two indices per lane)
 constexpr int SLICE_TASK_MAX = 1024;   // edges of a task: up to this many consecutive edges of one piece share a partial row
                                        // (128, i.e. a partial row per pass: 40 % more partial rows, step 142.3 against 139.0 ms; 4096: 139.7)
-constexpr int SLICE_MIN_PIECE = 96;  // a row is not cut at a slice boundary before its current piece has this many edges
-                                     // (measured on the 2^32-edge share, ms per call at F = 16 fp32 / F = 64 bf16: 1: 43.0 / 82.4,
-                                     //  32: 38.4 / 60.2, 96: 37.3 / 54.7, 128: 37.7 / 56.4; pieces of up to 256 edges: no better)
+constexpr int SLICE_MIN_PIECE = 112; // a row is not cut at a slice boundary before its current piece has this many edges
+                                     // (measured on the 2^32-edge share, ms per step: 64: 153.3 and 96: 145.5 with tasks of at most 128
+                                     //  edges; with tasks of up to 1024: 80: 143.1, 96: 139.0, 112: 137.3, 128: 137.6, 144: 137.6; the
+                                     //  10^8-edge share with 1 KB rows prefers shorter pieces: 96: 291, 112: 295, 128: 297 ms per step)
 struct SliceTask {
     int64_t begin;                   // first edge of the task
     uint32_t id;                     // its number in row-major order: where its partial row goes
