@@ -65,7 +65,16 @@ __device__ __forceinline__ void add4(float4& acc, const float4& v) {
 // EV: every edge carries a value val[e] that multiplies its gathered row.
 // U neighbour rows are requested before any is accumulated: 4, or 8 for groups of 16 lanes (measured:
 // +4 % at F = 47; no gain for wider rows, and narrower groups fetch fewer than 8 indices per batch).
-template <typename XT, int G, int NJ, bool EV>
+// WIDE (bf16 rows of whole 16-byte units, NJ = 2): a lane owns eight consecutive columns, fetched with one 16-byte load
+// and kept as two adjacent 4-column slabs, so a row takes half the lanes and a wavefront gathers twice the rows.
+template <int G, bool WIDE> __device__ __forceinline__ int slab_col(int t, int j) { return WIDE ? 8 * t + 4 * j : 4 * (t + G * j); }
+__device__ __forceinline__ void bf16x8_to_float4s(const uint4& r, float4& lo, float4& hi) {
+    lo = make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u), __uint_as_float(r.y << 16),
+                     __uint_as_float(r.y & 0xFFFF0000u));
+    hi = make_float4(__uint_as_float(r.z << 16), __uint_as_float(r.z & 0xFFFF0000u), __uint_as_float(r.w << 16),
+                     __uint_as_float(r.w & 0xFFFF0000u));
+}
+template <typename XT, int G, int NJ, bool EV, bool WIDE = false>
 __device__ __forceinline__ void gather_rows(const int32_t* __restrict__ idx, const float* __restrict__ val, int64_t b,
                                             int64_t e, const XT* __restrict__ X, int64_t ldx,
                                             const float* __restrict__ colscale, int t, const bool (&live)[NJ],
@@ -86,6 +95,21 @@ __device__ __forceinline__ void gather_rows(const int32_t* __restrict__ idx, con
                 sc[u] = colscale ? colscale[c[u]] : 1.f;
                 if (EV) sc[u] *= __shfl(minew, k + u, G);
             }
+            if constexpr (WIDE) {
+                static_assert(!WIDE || (NJ == 2 && sizeof(XT) == 2), "eight bf16 columns per lane");
+                if (live[0]) {                             // F is a multiple of 8: both slabs are live or neither
+                    uint4 r[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) r[u] = *reinterpret_cast<const uint4*>(X + c[u] * ldx + 8 * t);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        float4 lo, hi;
+                        bf16x8_to_float4s(r[u], lo, hi);
+                        if (EV || colscale) { axpy4(acc[0], sc[u], lo); axpy4(acc[1], sc[u], hi); }
+                        else { add4(acc[0], lo); add4(acc[1], hi); }
+                    }
+                }
+            } else
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
                 if (!live[j]) continue;
@@ -106,6 +130,13 @@ __device__ __forceinline__ void gather_rows(const int32_t* __restrict__ idx, con
             const int64_t c0 = __shfl(mine, k, G);
             float s0 = colscale ? colscale[c0] : 1.f;
             if (EV) s0 *= __shfl(minew, k, G);
+            if constexpr (WIDE) {
+                if (live[0]) {
+                    float4 lo, hi;
+                    bf16x8_to_float4s(*reinterpret_cast<const uint4*>(X + c0 * ldx + 8 * t), lo, hi);
+                    axpy4(acc[0], s0, lo); axpy4(acc[1], s0, hi);
+                }
+            } else
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
                 if (!live[j]) continue;
@@ -169,7 +200,7 @@ __device__ __forceinline__ void finish_row(const SpmmEpilogue& ep, int64_t i, in
 }
 
 // One workgroup per chunk of a long row -> one partial row.
-template <typename XT, int G, int NJ, bool EV>
+template <typename XT, int G, int NJ, bool EV, bool WIDE = false>
 __device__ __forceinline__ void chunk_body(int64_t cb, int64_t ce, const int32_t* __restrict__ idx,
                                            const float* __restrict__ val, int F,
                                            const XT* __restrict__ X, int64_t ldx, const float* __restrict__ colscale,
@@ -186,12 +217,12 @@ __device__ __forceinline__ void chunk_body(int64_t cb, int64_t ce, const int32_t
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
         acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        live[j] = 4 * (t + G * j) < F;
+        live[j] = slab_col<G, WIDE>(t, j) < F;
     }
-    gather_rows<XT, G, NJ, EV>(idx, val, b, e, X, ldx, colscale, t, live, acc);
+    gather_rows<XT, G, NJ, EV, WIDE>(idx, val, b, e, X, ldx, colscale, t, live, acc);
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
-        *reinterpret_cast<float4*>(&red[gi * W + 4 * (t + G * j)]) = acc[j];
+        *reinterpret_cast<float4*>(&red[gi * W + slab_col<G, WIDE>(t, j)]) = acc[j];
     __syncthreads();
     const int fpad = (F + 3) & ~3;
     for (int c = threadIdx.x; c < fpad; c += 256) {
@@ -206,7 +237,7 @@ __device__ __forceinline__ void chunk_body(int64_t cb, int64_t ce, const int32_t
 // are the heavy ones, so they start first); the others take the rows of at most `long_thr`
 // edges, one group per row.  One launch instead of two keeps the few chunk workgroups from
 // running on an otherwise idle chip.
-template <typename XT, int G, int NJ, bool EV>
+template <typename XT, int G, int NJ, bool EV, bool WIDE = false>
 __global__ __launch_bounds__(256) void spmm_rows_kernel(const int64_t* __restrict__ ptr, const int32_t* __restrict__ idx,
                                                         const float* __restrict__ val, int64_t n_rows, int64_t long_thr,
                                                         const XT* __restrict__ X,
@@ -218,7 +249,7 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(const int64_t* __restric
     constexpr int ROWS = 256 / G;
     __shared__ __attribute__((aligned(16))) float red[ROWS * 4 * G * NJ];
     if ((int)blockIdx.x < n_chunks) {              // uniform per workgroup
-        chunk_body<XT, G, NJ, EV>(chunk_begin[blockIdx.x], chunk_end[blockIdx.x], idx, val, ep.F, X, ldx, colscale,
+        chunk_body<XT, G, NJ, EV, WIDE>(chunk_begin[blockIdx.x], chunk_end[blockIdx.x], idx, val, ep.F, X, ldx, colscale,
                               partials + (int64_t)blockIdx.x * ld_part, red);
         return;
     }
@@ -232,12 +263,12 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(const int64_t* __restric
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
         acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        live[j] = 4 * (t + G * j) < ep.F;
+        live[j] = slab_col<G, WIDE>(t, j) < ep.F;
     }
-    gather_rows<XT, G, NJ, EV>(idx, val, b, e, X, ldx, colscale, t, live, acc);
+    gather_rows<XT, G, NJ, EV, WIDE>(idx, val, b, e, X, ldx, colscale, t, live, acc);
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
-        if (live[j]) finish_row<XT>(ep, i, e - b, 4 * (t + G * j), acc[j], X, ldx);
+        if (live[j]) finish_row<XT>(ep, i, e - b, slab_col<G, WIDE>(t, j), acc[j], X, ldx);
 }
 
 // One group per long row: partial rows added in chunk order, then the epilogue.
@@ -580,8 +611,26 @@ static void launch_one(const SpmmArgs& a, const SpmmEpilogue& ep, hipStream_t st
             else go(spmm_tasks_kernel<XT, G, NJ, 4, false, false>);
         }
     }
+    bool rows_done = false;
+    if constexpr (std::is_same<XT, __hip_bfloat16>::value && G >= 2 && NJ == 1) {
+        // bf16 rows of whole 16-byte units: eight columns per lane, half the lanes per row (twice the rows per wavefront)
+        if (a.F % 8 == 0 && a.ldx % 8 == 0 && ((uintptr_t)a.X % 16) == 0 && !a.self_term) {
+            constexpr int GW = G / 2;
+            const dim3 wgrid((unsigned)(n_chunks + cdiv(a.n_rows, 256 / GW)));
+            if (a.val)
+                hipLaunchKernelGGL((spmm_rows_kernel<XT, GW, 2, true, true>), wgrid, dim3(256), 0, st, a.ptr, a.idx, a.val, a.n_rows,
+                                   thr, (const XT*)a.X, a.ldx, a.colscale, ep, n_chunks, n_chunks ? lr->chunk_begin : nullptr,
+                                   n_chunks ? lr->chunk_end : nullptr, a.partials, ld_part);
+            else
+                hipLaunchKernelGGL((spmm_rows_kernel<XT, GW, 2, false, true>), wgrid, dim3(256), 0, st, a.ptr, a.idx, a.val, a.n_rows,
+                                   thr, (const XT*)a.X, a.ldx, a.colscale, ep, n_chunks, n_chunks ? lr->chunk_begin : nullptr,
+                                   n_chunks ? lr->chunk_end : nullptr, a.partials, ld_part);
+            rows_done = true;
+        }
+    }
     const dim3 grid((unsigned)(n_chunks + cdiv(a.n_rows, ROWS)));
-    if (a.val)
+    if (rows_done) {
+    } else if (a.val)
         hipLaunchKernelGGL((spmm_rows_kernel<XT, G, NJ, true>), grid, dim3(256), 0, st, a.ptr, a.idx, a.val, a.n_rows, thr,
                            (const XT*)a.X, a.ldx, a.colscale, ep, n_chunks, n_chunks ? lr->chunk_begin : nullptr,
                            n_chunks ? lr->chunk_end : nullptr, a.partials, ld_part);
