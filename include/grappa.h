@@ -17,11 +17,13 @@
  *     returns and frees them in *_destroy.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous on that stream and do not synchronise it unless stated otherwise
- *     (grp_partition*, and grp_train_step in mini-batch mode, do).
+ *     (the builders grp_partition*, grp_chunks_build*, grp_epoch_seeds and the inspection calls do;
+ *     grp_train_step does not, in either mode).
  *   - Every function returns GRP_OK (0) or a negative status; it never throws or aborts.
  *     grp_last_error() gives a thread-local, library-owned description of the last
  *     failure on the calling thread.
- *   - Matrices are dense row-major; `ld*` is the row pitch in elements.
+ *   - Matrices are dense row-major; `ld*` is the row pitch in elements.  Values are expected to be finite: an
+ *     infinity in a gathered feature row may come out as NaN (some kernels drop a row with a multiplication by 0).
  *   - Local node ids are int32, edge offsets int64 (a partition may hold 2^32 edges).
  */
 #ifndef GRAPPA_H_
